@@ -1,0 +1,122 @@
+"""Element splits of an FP32 value into low-precision parts, in numpy.
+
+TEST INFRASTRUCTURE ONLY.  Written from the paper's equations; shares nothing with the
+HIP split kernel, for which `split_fp16` and `split_bf16x3` are the bit-exact reference.
+
+halfhalf (Eqs. corr-elm-1 and corr-elm-2-1024):
+    v16  = toFP16(v32)
+    dv16 = toFP16((v32 - toFP32(v16)) * 2^11)          v32 ~ v16 + dv16 * 2^-11
+Markidis' halfhalf (Eqs. corr-elm-1 and corr-elm-2): the same without the 2^11.
+toFP16 rounds to nearest, ties to even (the paper's choice for FP16); an RZ variant
+exists only because the paper's worked bit example and its underflow analysis assume
+truncation.
+
+Three-term BF16 split (stands where the paper uses TF32 for the full exponent range):
+    b0 = toBF16(v); b1 = toBF16(v - b0); b2 = toBF16(v - b0 - b1),    v = b0 + b1 + b2
+with round to nearest even; 8 + 8 + 8 significand bits cover FP32's 24.
+
+Readings where the paper is silent (the HIP kernel follows the same ones):
+  * saturation: a finite input never produces an infinite part.  toFP16 / toBF16 results
+    that would round to +-Inf are replaced by the largest finite value of the format
+    (65504 for FP16); the residual then carries the remainder.
+  * Inf input: the high part is +-Inf and every lower part is 0.  NaN: all parts NaN.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+FP16_MAX = np.float32(65504.0)
+RESIDUAL_SCALE = np.float32(2048.0)  # 2^(l_F16 + 1) = 2^11
+
+
+def to_fp16_rn(x: np.ndarray) -> np.ndarray:
+    """FP32 -> FP16, round to nearest even, finite inputs saturate at +-65504."""
+    x = np.asarray(x, dtype=np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        h = x.astype(np.float16)
+    overflowed = np.isinf(h) & np.isfinite(x)
+    if np.any(overflowed):
+        h = np.where(overflowed, np.copysign(np.float16(65504.0), h), h)
+    return h
+
+
+def to_fp16_rz(x: np.ndarray) -> np.ndarray:
+    """FP32 -> FP16, round toward zero (truncate), subnormals included.  Finite |x| only."""
+    x = np.asarray(x, dtype=np.float32)
+    with np.errstate(over="ignore"):
+        near = x.astype(np.float16)
+    # stepping one FP16 toward zero whenever rounding to nearest went away from zero
+    too_big = np.abs(near.astype(np.float32)) > np.abs(x)
+    toward_zero = np.nextafter(near, np.float16(0.0))
+    out = np.where(too_big, toward_zero, near)
+    return np.where(np.isinf(out), np.copysign(np.float16(65504.0), out), out).astype(np.float16)
+
+
+def split_fp16(x: np.ndarray, scaled: bool = True, rounding: str = "rn"):
+    """halfhalf split.  Returns (v16, dv16) as float16 arrays.
+
+    scaled=True  : the paper's halfhalf, residual multiplied by 2^11 before conversion
+    scaled=False : Markidis' halfhalf
+    rounding     : "rn" (method) or "rz" (only for the paper's RZ analysis)
+    """
+    x = np.asarray(x, dtype=np.float32)
+    conv = {"rn": to_fp16_rn, "rz": to_fp16_rz}[rounding]
+    v16 = conv(x)
+    with np.errstate(invalid="ignore", over="ignore"):
+        residual = x - v16.astype(np.float32)
+        if scaled:
+            residual = residual * RESIDUAL_SCALE
+        dv16 = conv(residual)
+    dv16 = np.where(np.isinf(v16), np.float16(0.0), dv16).astype(np.float16)
+    return v16, dv16
+
+
+def fp16_pair_value(v16: np.ndarray, dv16: np.ndarray, scaled: bool = True) -> np.ndarray:
+    """What the pair stands for, in FP64: v16 + dv16 * 2^-11 (or v16 + dv16)."""
+    s = 2.0 ** -11 if scaled else 1.0
+    return v16.astype(np.float64) + dv16.astype(np.float64) * s
+
+
+BF16_MAX_BITS = np.uint32(0x7F7F)
+
+
+def to_bf16_rn_bits(x: np.ndarray) -> np.ndarray:
+    """FP32 -> BF16 bit pattern (uint16), round to nearest even, finite inputs saturate."""
+    x = np.asarray(x, dtype=np.float32)
+    u = x.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    with np.errstate(over="ignore"):
+        rounded = (u + np.uint32(0x7FFF) + lsb) >> np.uint32(16)
+    sign = (u >> np.uint32(16)) & np.uint32(0x8000)
+    exp_all_ones = (rounded & np.uint32(0x7F80)) == np.uint32(0x7F80)
+    finite_in = np.isfinite(x)
+    rounded = np.where(exp_all_ones & finite_in, sign | BF16_MAX_BITS, rounded)
+    rounded = np.where(np.isnan(x), sign | np.uint32(0x7FC0), rounded)
+    rounded = np.where(np.isinf(x), sign | np.uint32(0x7F80), rounded)
+    return rounded.astype(np.uint16)
+
+
+def bf16_bits_to_fp32(b: np.ndarray) -> np.ndarray:
+    return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def split_bf16x3(x: np.ndarray):
+    """Three-term BF16 split.  Returns (b0, b1, b2) as uint16 BF16 bit patterns."""
+    x = np.asarray(x, dtype=np.float32)
+    b0 = to_bf16_rn_bits(x)
+    with np.errstate(invalid="ignore", over="ignore"):
+        r1 = x - bf16_bits_to_fp32(b0)
+        b1 = to_bf16_rn_bits(r1)
+        r2 = r1 - bf16_bits_to_fp32(b1)
+        b2 = to_bf16_rn_bits(r2)
+    is_inf = np.isinf(x)
+    if np.any(is_inf):
+        b1 = np.where(is_inf, np.uint16(0), b1).astype(np.uint16)
+        b2 = np.where(is_inf, np.uint16(0), b2).astype(np.uint16)
+    return b0, b1, b2
+
+
+def bf16_triple_value(b0, b1, b2) -> np.ndarray:
+    """b0 + b1 + b2 in FP64."""
+    return (bf16_bits_to_fp32(b0).astype(np.float64) + bf16_bits_to_fp32(b1).astype(np.float64)
+            + bf16_bits_to_fp32(b2).astype(np.float64))

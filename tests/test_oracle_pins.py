@@ -1,0 +1,394 @@
+"""Pins for the CPU oracle: it is checked against what the paper prints and what the
+mathematics fixes, never against itself and never against the GPU path.
+
+Each test names the plausible oracle mistake it would catch.
+"""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+from oracle import gemm, model, split
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _golden(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        return json.load(f)
+
+
+def _binade(exponent: int, mantissas: np.ndarray) -> np.ndarray:
+    """float32 values 1.m * 2^exponent for the given 23-bit mantissa integers."""
+    bits = (np.uint32(exponent + 127) << np.uint32(23)) | mantissas.astype(np.uint32)
+    return bits.view(np.float32)
+
+
+ALL_MANTISSAS = np.arange(1 << 23, dtype=np.uint32)
+
+
+# --------------------------------------------------------------------------- splits
+
+def _kept_length(x: np.ndarray, reconstructed: np.ndarray) -> np.ndarray:
+    """Mantissa bits kept (out of 23): 23 minus the bit length of the error in ulps of x."""
+    ulp = np.spacing(np.abs(x)).astype(np.float64)
+    err_ulps = np.rint(np.abs(x.astype(np.float64) - reconstructed) / ulp).astype(np.int64)
+    lost = np.zeros_like(err_ulps)
+    nz = err_ulps > 0
+    lost[nz] = np.floor(np.log2(err_ulps[nz])).astype(np.int64) + 1
+    return 23 - lost
+
+
+@pytest.mark.parametrize("rounding", ["rn", "rz"])
+def test_halfhalf_mantissa_length_table(rounding):
+    """Exhaustive over one binade: the (len, prob) columns of the two mantissa tables and
+    the expectations 22.75 / 22.25.  Catches a wrong rounding mode, a wrong scale and a
+    residual taken against the wrong high part."""
+    table = _golden("mantissa_length_tables.json")[rounding]
+    x = _binade(0, ALL_MANTISSAS)
+    v16, dv16 = split.split_fp16(x, scaled=True, rounding=rounding)
+    kept = _kept_length(x, split.fp16_pair_value(v16, dv16))
+    n = x.size
+    for length in (21, 22, 23):
+        expected = Fraction(table.get(str(length), 0.0))
+        assert Fraction(int(np.sum(kept == length)), n) == expected, (rounding, length)
+    assert kept.min() >= 21
+    assert float(np.mean(kept)) == table["expectation"]
+
+
+def test_lsb_truncation_length():
+    """Dropping the last FP32 mantissa bit keeps 22.5 bits on average (the comparison the
+    paper draws against the 22.75 of the split).  Pins _kept_length itself."""
+    table = _golden("mantissa_length_tables.json")["lsb_truncation"]
+    x = _binade(3, ALL_MANTISSAS)
+    truncated = (x.view(np.uint32) & np.uint32(0xFFFFFFFE)).view(np.float32)
+    kept = _kept_length(x, truncated.astype(np.float64))
+    assert float(np.mean(kept)) == table["expectation"]
+    assert Fraction(int(np.sum(kept == 23)), x.size) == Fraction(table["23"])
+
+
+def test_halfhalf_worked_example():
+    """The 24-bit significand 10000000000'10000000000'11 of Eq. mantissa-example."""
+    g = _golden("mantissa_split_example.json")
+    I = int(g["I_FP32_bits"], 2)
+    x = np.array([I * 2.0 ** -23], dtype=np.float32)
+    assert float(x[0]) * 2 ** 23 == I
+    # RZ: hi = 10000000000, lo = +10000000000 two places up, trailing "11" lost
+    v16, dv16 = split.split_fp16(x, rounding="rz")
+    hi_units = float(v16[0]) * 2 ** 23
+    lo_units = float(dv16[0]) * 2.0 ** -11 * 2 ** 23
+    assert hi_units == int(g["rz"]["hi_bits"], 2) * 2 ** 13
+    assert lo_units == g["rz"]["lo_sign"] * int(g["rz"]["lo_bits_at_2"], 2) * 2 ** 2
+    assert I - hi_units - lo_units == g["rz"]["loss_units"] == 0b11
+    # RN: hi rounds up to 10000000001, lo is negative, one bit lost
+    v16, dv16 = split.split_fp16(x, rounding="rn")
+    hi_units = float(v16[0]) * 2 ** 23
+    lo_units = float(dv16[0]) * 2.0 ** -11 * 2 ** 23
+    assert hi_units == int(g["rn"]["hi_bits"], 2) * 2 ** 13
+    assert lo_units == g["rn"]["lo_sign"] * int(g["rn"]["lo_bits_at_1"], 2) * 2 ** 1
+    assert abs(I - hi_units - lo_units) == g["rn"]["loss_units"]
+
+
+def test_halfhalf_residual_is_exact_and_one_ulp():
+    """v - toFP32(v16) and the 2^11 scaling are exact, so the pair is off by at most one
+    FP32 ulp wherever the scaled residual stays a normal FP16 number (2^-13 <= |v| < 2^15);
+    one binade lower the residual goes subnormal and the error may reach two ulps."""
+    x = si.exp_rand(1 << 20, 1, -13, 14, seed=3, matrix_id=0)[:, 0]
+    v16, dv16 = split.split_fp16(x)
+    r64 = x.astype(np.float64) - v16.astype(np.float64)
+    r32 = x - v16.astype(np.float32)
+    assert np.array_equal(r32.astype(np.float64), r64)
+    assert np.array_equal((r32 * np.float32(2048)).astype(np.float64), r64 * 2048)
+    err = np.abs(split.fp16_pair_value(v16, dv16) - x)
+    assert np.all(err <= np.spacing(np.abs(x)).astype(np.float64))
+    wide = np.abs(x) >= 2.0 ** -12                   # residual never subnormal here: the table's 3/4 holds
+    frac_exact = np.mean(err[wide] == 0)
+    assert abs(frac_exact - 0.75) < 3 * np.sqrt(0.75 * 0.25 / wide.sum())
+    low = si.exp_rand(1 << 18, 1, -14, -14, seed=3, matrix_id=1)[:, 0]
+    err_low = np.abs(split.fp16_pair_value(*split.split_fp16(low)) - low)
+    assert 1.0 < np.max(err_low / np.spacing(np.abs(low))) <= 2.0
+
+
+def _p_l0(n, l32=23, l16=10):
+    if n < 0:
+        return Fraction(0)
+    if n < l32 - l16:
+        return Fraction(1, 2 ** (n + 1))
+    if n == l32 - l16:
+        return Fraction(1, 2 ** (l32 - l16))
+    return Fraction(0)
+
+
+@pytest.mark.parametrize("scaled", [False, True])
+def test_underflow_probabilities(scaled):
+    """Eqs. up, prob_g_u and prob_u: probability that the residual of the (RZ) split lands in
+    FP16's subnormal range or vanishes, per exponent e_v.  The residual only depends on the
+    low 13 mantissa bits, so enumerating those gives the probabilities exactly.  With the
+    2^11 scaling both curves move by 11 exponents.  Catches a wrong scale constant and an
+    unscaled/scaled mix-up."""
+    g = _golden("underflow_model.json")
+    b16, l16, l32 = g["b_F16"], g["l_F16"], g["l_F32"]
+    shift = g["scale_log2"] if scaled else 0
+    low = np.arange(1 << (l32 - l16), dtype=np.uint32)
+    high = np.uint32(0b1011001110) << np.uint32(l32 - l16)
+    min_normal = 2.0 ** (-b16 + 1)
+    for e_v in range(-14, 16):
+        x = _binade(e_v, high | low)
+        _, dv16 = split.split_fp16(x, scaled=scaled, rounding="rz")
+        mag = np.abs(dv16.astype(np.float64))
+        e_eff = e_v + shift
+        first_gu = (e_eff - l16 + b16 - 2) + 1
+        first_u = (e_eff + b16 - 2) + 1
+        p_gu = sum(_p_l0(l) for l in range(max(first_gu, 0), l32 - l16 + 1))
+        p_u = sum(_p_l0(l) for l in range(max(first_u, 0), l32 - l16 + 1))
+        zero_residual = low == 0                     # the l0 = 13 case of Eq. up
+        counts_zero_gu = first_gu <= l32 - l16
+        counts_zero_u = first_u <= l32 - l16
+        ev_gu = (mag < min_normal) & (~zero_residual | counts_zero_gu)
+        ev_u = (mag == 0) & (~zero_residual | counts_zero_u)
+        assert Fraction(int(ev_gu.sum()), low.size) == p_gu, (e_v, scaled)
+        assert Fraction(int(ev_u.sum()), low.size) == p_u, (e_v, scaled)
+    if scaled:
+        # with the scaling no residual of a normal-range FP16 value is lost to zero
+        assert p_u == 0
+
+
+def test_bf16_triple_is_exact():
+    """8 + 8 + 8 significand bits: b0 + b1 + b2 == v for every mantissa, at the centre and
+    near both ends of the exponent range the full-range mode has to cover."""
+    for e in (0, -100, 100, 127 - 1, -126 + 24):
+        x = _binade(e, ALL_MANTISSAS[:: 7] if e not in (0,) else ALL_MANTISSAS)
+        for sign in (1.0, -1.0):
+            xs = (x * np.float32(sign)).astype(np.float32)
+            assert np.array_equal(split.bf16_triple_value(*split.split_bf16x3(xs)), xs.astype(np.float64))
+    x = si.exp_rand(1 << 20, 1, -100, 100, seed=5, matrix_id=0)[:, 0]
+    b0, b1, b2 = split.split_bf16x3(x)
+    assert np.array_equal(split.bf16_triple_value(b0, b1, b2), x.astype(np.float64))
+    # the parts are ordered by magnitude: each at most half an ulp (2^-8) of the previous one
+    f = [np.abs(split.bf16_bits_to_fp32(b).astype(np.float64)) for b in (b0, b1, b2)]
+    assert np.all(f[1] <= f[0] * 2.0 ** -8) and np.all(f[2] <= f[0] * 2.0 ** -16)
+
+
+def test_bf16_rounding_is_nearest_even():
+    """toBF16 against hand-worked patterns: below half, tie to even (down and up), above half."""
+    cases = {0x3F800000: 0x3F80, 0x3F807FFF: 0x3F80, 0x3F808000: 0x3F80, 0x3F808001: 0x3F81,
+             0x3F818000: 0x3F82, 0x3F81FFFF: 0x3F82, 0xBF808001: 0xBF81, 0x7F7FFFFF: 0x7F7F,
+             0x00000000: 0x0000, 0x80000000: 0x8000, 0x7F800000: 0x7F80, 0x00010000: 0x0001}
+    x = np.array(list(cases.keys()), dtype=np.uint32).view(np.float32)
+    assert split.to_bf16_rn_bits(x).tolist() == list(cases.values())
+    assert np.all(np.isnan(split.bf16_bits_to_fp32(split.to_bf16_rn_bits(np.array([np.nan], np.float32)))))
+
+
+def test_split_edge_values():
+    """Saturation reading: a finite input never yields an infinite part, and the pair still
+    reconstructs values up to 2^16 to better than 2^-22; Inf keeps only its high part."""
+    x = np.array([65504.0, 65519.996, 65520.0, 65535.996, -65535.996, 0.0, -0.0, 2.0 ** -24, 2.0 ** -35,
+                  1e-45], dtype=np.float32)
+    v16, dv16 = split.split_fp16(x)
+    assert np.all(np.isfinite(v16)) and np.all(np.isfinite(dv16))
+    assert v16[3] == np.float16(65504) and v16[4] == np.float16(-65504)
+    rec = split.fp16_pair_value(v16, dv16)
+    assert np.all(np.abs(rec[:5] - x[:5]) <= np.abs(x[:5]) * 2.0 ** -22)
+    assert rec[7] == x[7] and rec[8] == x[8]          # down to 2^-35 through the scaled residual
+    assert rec[9] == 0.0                              # below that the pair holds nothing
+    inf = np.array([np.inf, -np.inf], dtype=np.float32)
+    v16, dv16 = split.split_fp16(inf)
+    assert np.all(np.isinf(v16)) and np.all(dv16 == 0)
+    b0, b1, b2 = split.split_bf16x3(inf)
+    assert b0.tolist() == [0x7F80, 0xFF80] and not b1.any() and not b2.any()
+    big = np.array([np.finfo(np.float32).max, -np.finfo(np.float32).max], dtype=np.float32)
+    parts = split.split_bf16x3(big)
+    assert np.all(np.isfinite(split.bf16_triple_value(*parts)))
+    assert np.all(np.abs(split.bf16_triple_value(*parts) - big) <= np.abs(big) * 2.0 ** -22)
+
+
+# ----------------------------------------------------------------------------- GEMMs
+
+def _python_gemm_exact(opA, opB, alpha, beta, Cin):
+    """alpha * op(A) op(B) + beta * C in exact rational arithmetic (tiny sizes only)."""
+    M, K = opA.shape
+    N = opB.shape[1]
+    out = [[Fraction(0)] * N for _ in range(M)]
+    for i in range(M):
+        for j in range(N):
+            s = Fraction(0)
+            for k in range(K):
+                s += Fraction(float(opA[i, k])) * Fraction(float(opB[k, j]))
+            out[i][j] = Fraction(float(alpha)) * s + (Fraction(float(beta)) * Fraction(float(Cin[i, j])) if beta else 0)
+    return out
+
+
+def _python_gemm_fp32(opA, opB, alpha, beta, Cin):
+    """The naive FP32 product in pure Python, np.float32 scalars, i-j-k loop order."""
+    M, K = opA.shape
+    N = opB.shape[1]
+    out = np.zeros((M, N), dtype=np.float32)
+    f = np.float32
+    for i in range(M):
+        for j in range(N):
+            acc = f(0)
+            for k in range(K):
+                acc = f(acc + f(opA[i, k] * opB[k, j]))
+            val = f(f(alpha) * acc)
+            if beta != 0:
+                val = f(val + f(f(beta) * Cin[i, j]))
+            out[i, j] = val
+    return out
+
+
+TINY = [(1, 1, 1), (2, 3, 5), (5, 2, 3), (3, 5, 2), (8, 8, 8), (17, 5, 8), (4, 17, 9)]
+
+
+@pytest.mark.parametrize("transA", ["N", "T"])
+@pytest.mark.parametrize("transB", ["N", "T"])
+def test_gemm_brute_force_tiny(transA, transB):
+    """All transposes, padded leading dimensions, several alpha/beta: the FP64 reference
+    against exact rational arithmetic, the naive FP32 product bit-for-bit against a pure
+    Python loop.  Catches transposed operands, swapped M/N/K, wrong ld handling, a reading
+    of C when beta == 0, fused multiply-adds."""
+    for idx, (M, N, K) in enumerate(TINY):
+        for alpha, beta in [(1.0, 0.0), (1.5, 0.5), (-1.0, 1.0), (0.0, 2.0), (1.0, -1.0)]:
+            ar, ac = (M, K) if transA == "N" else (K, M)
+            br, bc = (K, N) if transB == "N" else (N, K)
+            A = si.urand(ar, ac, seed=idx, matrix_id=si.ID_A, ld=ar + 3)
+            B = si.exp_rand(br, bc, -4, 4, seed=idx, matrix_id=si.ID_B, ld=br + 1)
+            C = si.urand(M, N, seed=idx, matrix_id=si.ID_C, ld=M + 2)
+            if beta == 0.0:
+                C[:] = np.nan                       # must not be read
+            opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)
+            c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C)
+            c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C)
+            exact = _python_gemm_exact(opA, opB, alpha, beta, C[:M, :N])
+            mag = np.abs(alpha) * (np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64))
+            if beta != 0:
+                mag = mag + np.abs(beta * C[:M, :N].astype(np.float64))
+            for i in range(M):
+                for j in range(N):
+                    assert abs(Fraction(float(c64[i, j])) - exact[i][j]) <= (K + 3) * 2.0 ** -53 * mag[i, j] + 1e-300
+                    assert abs(Fraction(float(c32[i, j])) - exact[i][j]) <= (K + 3) * 2.0 ** -24 * mag[i, j] + 1e-40
+            ref32 = _python_gemm_fp32(opA, opB, alpha, beta, C[:M, :N])
+            assert np.array_equal(c32.view(np.uint32), ref32.view(np.uint32)), (M, N, K, alpha, beta)
+
+
+def test_gemm_row_subset_matches_full():
+    M, N, K = 37, 29, 53
+    A = si.urand(K, M, 1, si.ID_A)
+    B = si.urand(K, N, 1, si.ID_B)
+    C = si.urand(M, N, 1, si.ID_C)
+    rows = si.sample_indices(M, 9, seed=4)
+    assert len(set(rows.tolist())) == 9
+    for fn in (gemm.sgemm_fp32_naive, gemm.sgemm_fp64_ref):
+        full = fn("T", "N", M, N, K, 1.5, A, B, 0.5, C)
+        part = fn("T", "N", M, N, K, 1.5, A, B, 0.5, C, rows=rows)
+        assert np.array_equal(full[rows], part)
+
+
+def test_small_integers_are_exact():
+    """Integer entries small enough that every partial sum is below 2^24: FP32, FP64 and the
+    method models must all equal the integer product, whatever the summation order."""
+    M, N, K = 24, 40, 512
+    A = si.randint(M, K, -15, 15, seed=0, matrix_id=si.ID_A)
+    B = si.randint(K, N, -15, 15, seed=0, matrix_id=si.ID_B)
+    exact = A.astype(np.int64) @ B.astype(np.int64)
+    assert np.abs(exact).max() < 2 ** 24
+    assert np.array_equal(gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.0, A, B).astype(np.int64), exact)
+    assert np.array_equal(gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.0, A, B).astype(np.int64), exact)
+    assert np.array_equal(model.gemm_fp16_mode(A, B), exact.astype(np.float64))
+    assert np.array_equal(model.gemm_bf16_mode(A, B), exact.astype(np.float64))
+    # integers that need the low parts: up to 2^20 in A (FP16 residual / second BF16 term)
+    A2 = si.randint(8, 64, -(2 ** 20), 2 ** 20, seed=1, matrix_id=si.ID_A)
+    B2 = si.randint(64, 8, -7, 7, seed=1, matrix_id=si.ID_B)
+    exact2 = A2.astype(np.int64) @ B2.astype(np.int64)
+    assert np.array_equal(gemm.sgemm_fp64_ref("N", "N", 8, 8, 64, 1.0, A2, B2).astype(np.int64), exact2)
+    assert np.array_equal(model.gemm_bf16_mode(A2, B2), exact2.astype(np.float64))
+
+
+def test_fp64_reference_against_library_dgemm():
+    M, N, K = 96, 80, 700
+    A = si.exp_rand(M, K, -15, 14, 2, si.ID_A)
+    B = si.exp_rand(N, K, -15, 14, 2, si.ID_B)
+    c64 = gemm.sgemm_fp64_ref("N", "T", M, N, K, 1.0, A, B)
+    lib = A.astype(np.float64) @ B.astype(np.float64).T
+    bound = (np.abs(A).astype(np.float64) @ np.abs(B).astype(np.float64).T) * K * 2.0 ** -52
+    assert np.all(np.abs(c64 - lib) <= bound)
+
+
+def test_metric_definitions():
+    """Eq. eval-matmul on a case worked by hand: C64 = [[3, 4]], target = [[3, 4.5]]."""
+    c64 = np.array([[3.0, 4.0]])
+    tgt = np.array([[3.0, 4.5]], dtype=np.float32)
+    assert gemm.relative_residual(c64, tgt) == 0.5 / 5.0
+    assert gemm.max_deviation(c64, tgt) == 0.5
+    assert gemm.relative_residual(c64, c64) == 0.0
+
+
+def test_fp32_error_grows_like_sqrt_k():
+    """The experiment of the paper's first figure (A 16 x k, B k x 16, uniform(-1, 1)):
+    the naive FP32 product's relative residual grows about as sqrt(k) * 2^-24, far below
+    the worst-case bound k * 2^-24; the exact-accumulation models of both modes stay flat
+    and below it.  Catches an oracle that accumulates in higher precision (too small an
+    error) or fuses/reorders (wrong growth)."""
+    ks = [2 ** p for p in range(4, 17, 2)]
+    errs, floor16, floor_bf = [], [], []
+    for k in ks:
+        e, f16, fbf = [], [], []
+        for seed in range(4):
+            A = si.urand(16, k, seed, si.ID_A)
+            B = si.urand(k, 16, seed, si.ID_B)
+            c64 = gemm.sgemm_fp64_ref("N", "N", 16, 16, k, 1.0, A, B)
+            e.append(gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", 16, 16, k, 1.0, A, B)))
+            f16.append(gemm.relative_residual(c64, model.gemm_fp16_mode(A, B)))
+            fbf.append(gemm.relative_residual(c64, model.gemm_bf16_mode(A, B)))
+        errs.append(np.mean(e)); floor16.append(np.mean(f16)); floor_bf.append(np.mean(fbf))
+    u = 2.0 ** -24
+    for k, e in zip(ks, errs):
+        assert 0.02 * np.sqrt(k) * u <= e <= 1.0 * np.sqrt(k) * u, (k, e)
+    slope = np.polyfit(np.log2(ks), np.log2(errs), 1)[0]
+    assert 0.35 <= slope <= 0.65, slope
+    assert max(floor16) < 2.0 * u and max(floor_bf) < 0.2 * u
+    assert all(f < e for f, e in zip(floor16, errs))
+
+
+def test_dropped_terms_are_negligible():
+    """dA16 dB16 / 2^22 is at least 2^22 times smaller than A16 B16 in norm, and leaving it
+    out does not move the relative residual; likewise the three BF16 products left out."""
+    n = 256
+    A = si.urand(n, n, 0, si.ID_A)
+    B = si.urand(n, n, 0, si.ID_B)
+    main, _, corr2 = model.fp16_terms(A, B)
+    assert np.linalg.norm(corr2 * 2.0 ** -22) <= np.linalg.norm(main) * 2.0 ** -22
+    c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+    r3 = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 3))
+    r4 = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 4))
+    r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
+    # the fourth product moves the result by less than a quarter ulp: far inside FP32's own error
+    assert abs(r3 - r4) <= 2.0 ** -26 and abs(r3 - r4) <= 0.05 * r32 and r3 < r32
+    r6 = gemm.relative_residual(c64, model.gemm_bf16_mode(A, B, 6))
+    r9 = gemm.relative_residual(c64, model.gemm_bf16_mode(A, B, 9))
+    assert r9 < 1e-12 and r6 < 2.0 ** -26
+
+
+def test_models_reach_fp32_accuracy_in_their_exponent_ranges():
+    """The paper's accuracy claims, checked on the exact-accumulation models: halfhalf matches
+    FP32 for exp_rand(-15, 14) inputs and degrades for exp_rand(-35, -15); the full-range
+    split (TF32 in the paper, three BF16 terms here) holds for exp_rand(-100, -35) x
+    exp_rand(-15, 14), where halfhalf cannot work at all."""
+    n = 192
+
+    def run(a_rng, b_rng):
+        A = si.exp_rand(n, n, *a_rng, 0, si.ID_A)
+        B = si.exp_rand(n, n, *b_rng, 0, si.ID_B)
+        c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+        r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
+        return r32, gemm.relative_residual(c64, model.gemm_fp16_mode(A, B)), \
+            gemm.relative_residual(c64, model.gemm_bf16_mode(A, B))
+
+    r32, r16, rbf = run((-15, 14), (-15, 14))          # Type 1
+    assert r16 <= r32 and rbf <= r32
+    r32, r16, rbf = run((-35, -15), (-35, -15))        # Type 3
+    assert r16 > 3 * r32 and rbf <= r32
+    r32, r16, rbf = run((-100, -35), (-15, 14))        # Type 2 / 4
+    assert r16 > 0.1 and rbf <= r32          # above the 0.1 "broken kernel" threshold of the tuning section
