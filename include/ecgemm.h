@@ -1,0 +1,139 @@
+/*
+ * ecgemm: error-corrected single-precision GEMM for AMD MI355X (gfx950).
+ *
+ * C-ABI of the split-and-correct SGEMM of Ootomo & Yokota, "Recovering single precision
+ * accuracy from Tensor Cores while surpassing the FP32 theoretical peak performance".
+ * Every FP32 input is split into low-precision parts, the product is formed from the
+ * leading product plus the first-order correction products on the matrix units, the
+ * corrections are summed in an accumulator of their own and merged once at the end.
+ *
+ * All matrix pointers are DEVICE pointers owned by the caller.  The library only reads A
+ * and B, writes C, keeps no pointer after a call returns, and never frees caller memory.
+ * All work is enqueued on the handle's stream and the calls return without waiting for it.
+ * Every function returns an ecgemm_status_t and never throws or aborts; on any status other
+ * than ECGEMM_OK no work has been enqueued by that call.  A handle may be used by one host
+ * thread at a time.  Results are bitwise reproducible for equal inputs and equal settings
+ * (no floating-point atomics; the split-K reduction has a fixed order).
+ */
+#ifndef ECGEMM_H
+#define ECGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ecgemm_context *ecgemm_handle_t;
+
+typedef enum { ECGEMM_OP_N = 0, ECGEMM_OP_T = 1 } ecgemm_op_t;
+
+typedef enum {
+    /* "halfhalf" (Eqs. corr-1-1024 .. corr-4-1024 and corr-5-1024-reduce): v ~ v16 + dv16 * 2^-11 with
+     * two FP16 parts, three matrix-unit products.  FP32 accuracy for inputs of magnitude 2^-14 .. 2^16;
+     * precision tapers below and nothing is left under 2^-35 (section "Effect of the exponent range"). */
+    ECGEMM_MODE_FP16_SPLIT = 0,
+    /* Full FP32 exponent range.  The paper uses TF32 pairs (section "Reducing the underflow ...", tf32tf32);
+     * gfx950 has no TF32 matrix instruction, so each value is split exactly into three BF16 terms and the
+     * six products of relative size >= 2^-16 are kept (same argument as section "Removing negligible
+     * error correction"). */
+    ECGEMM_MODE_BF16_FULL = 1
+} ecgemm_mode_t;
+
+typedef enum {
+    ECGEMM_OK = 0,
+    ECGEMM_ERR_INVALID_ARG = 1, /* bad enum, negative size, leading dimension too small, null pointer */
+    ECGEMM_ERR_ALLOC = 2,       /* device workspace could not be allocated, or the caller's is too small */
+    ECGEMM_ERR_HIP = 3,         /* a HIP runtime call failed; see ecgemm_last_error_string */
+    ECGEMM_ERR_UNSUPPORTED = 4  /* device is not gfx950 */
+} ecgemm_status_t;
+
+/* Creates a handle bound to the current HIP device.  Allocates no device memory.  The device must
+ * be a gfx950; otherwise ECGEMM_ERR_UNSUPPORTED.  `handle` is a host pointer. */
+ecgemm_status_t ecgemm_create(ecgemm_handle_t *handle);
+
+/* Frees the handle and the workspace it allocated itself (never a caller-provided one).  Work already
+ * enqueued must have finished: the caller synchronises the stream first. */
+ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle);
+
+/* Stream (a hipStream_t passed as void*) on which every later call enqueues its kernels.
+ * Default: the null stream. */
+ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
+
+/* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit
+ * fragment order, zero-padded to whole tiles, plus the partial sums when K is divided among blocks.
+ * `bytes` is a host pointer. */
+ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
+                                      ecgemm_mode_t mode, size_t *bytes);
+
+/* Hands the library a caller-owned device buffer (256-byte aligned) to use as workspace from now on;
+ * (NULL, 0) returns to the handle-owned workspace, which is allocated on first need and only ever
+ * grows.  With a caller buffer the library never allocates: a too small one makes ecgemm_sgemm return
+ * ECGEMM_ERR_ALLOC.  The workspace must not overlap A, B or C. */
+ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void *device_buffer, size_t bytes);
+
+/*
+ * C <- alpha * op(A) * op(B) + beta * C        (BLAS sgemm semantics, column-major)
+ *
+ *   op(A) is M x K, op(B) is K x N, C is M x N; op(X) = X or X^T per transA / transB.
+ *   A: device, FP32, column-major, leading dimension lda >= (transA == N ? M : K)
+ *   B: device, FP32, column-major, leading dimension ldb >= (transB == N ? K : N)
+ *   C: device, FP32, column-major, ldc >= M; read only when beta != 0 (so NaN/Inf already in C do
+ *      not propagate when beta == 0), written for all M x N elements.  C must not overlap A or B.
+ *   alpha, beta: host scalars.
+ *
+ * Steps (each a kernel on the handle's stream):
+ *   1. split: A and B are read once and written to the workspace as FP16 (v16, dv16 = (v - v16) * 2^11;
+ *      Eqs. corr-1-1024 .. corr-4-1024) or as three BF16 terms, round to nearest even, K-contiguous,
+ *      in the lane order the matrix instruction wants, zero-padded to tile multiples.  A finite input
+ *      never produces an infinite part: conversions saturate at the largest finite FP16 / BF16 value.
+ *   2. product: A16 B16 goes to one FP32 accumulator; the correction products (dA16 B16 + A16 dB16, or
+ *      the five lower BF16 products) go to a second FP32 accumulator that is never mixed with the first
+ *      inside the loop; dA16 dB16 and the BF16 products below 2^-16 are left out (Eq. corr-5-1024-reduce).
+ *   3. epilogue: c = main + correction * 2^-11 (FP16 mode) or main + correction (BF16 mode), then
+ *      C <- alpha * c + beta * C in FP32.
+ *
+ * M == 0 or N == 0: nothing is done.  K == 0 or alpha == 0: C <- beta * C (C <- 0 when beta == 0).
+ * Inf / NaN inputs give Inf / NaN outputs but not necessarily in IEEE-exact positions.
+ */
+ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                             int64_t M, int64_t N, int64_t K, float alpha,
+                             const float *A, int64_t lda, const float *B, int64_t ldb,
+                             float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
+
+/*
+ * Step 1 alone (Eqs. corr-1-1024 .. corr-4-1024 / the BF16 three-term split), for inspection and tests.
+ * Splits the `rows` x `depth` matrix X = op(src) into `packed`, a device buffer of
+ * ecgemm_split_size(rows, depth, mode) bytes, laid out as
+ *     packed[row_block][k_step][part][lane][8]   (16-bit elements)
+ * with row_block = r / 32, k_step = k / 16, lane = ((k % 16) / 8) * 32 + r % 32, element k % 8;
+ * part 0 is the high part.  Rows are padded to a multiple of 256 and depth to a multiple of 32, with
+ * zeros.  src: device, FP32, column-major with leading dimension ld; op == N means X(r, k) =
+ * src[r + k * ld] (ld >= rows), op == T means X(r, k) = src[k + r * ld] (ld >= depth).
+ */
+ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth,
+                             const float *src, int64_t ld, ecgemm_mode_t mode, void *packed);
+
+/* Bytes ecgemm_split writes for a rows x depth operand.  `bytes` is a host pointer. */
+ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mode, size_t *bytes);
+
+/* When enabled, every ecgemm_sgemm brackets its split kernels and its product kernel with HIP events on
+ * the handle's stream so that their device durations can be read back; off by default. */
+ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled);
+
+/* Synchronises with the events of the calls made since timing was enabled (or since the last call of
+ * this function) and returns the number of ecgemm_sgemm calls seen and the summed device milliseconds
+ * of their split kernels and of their product kernel.  All three outputs are host pointers. */
+ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int *calls, float *split_ms, float *product_ms);
+
+/* Human-readable text for the last failure on this handle (host string owned by the handle). */
+const char *ecgemm_last_error_string(ecgemm_handle_t handle);
+
+/* Static name of a status code. */
+const char *ecgemm_status_string(ecgemm_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECGEMM_H */

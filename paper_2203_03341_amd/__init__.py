@@ -1,0 +1,6 @@
+"""Error-corrected SGEMM for MI355X: thin Python face of the C-ABI library (see include/ecgemm.h)."""
+from .binding import (ERR_ALLOC, ERR_HIP, ERR_INVALID_ARG, ERR_UNSUPPORTED, MODE_BF16_FULL, MODE_FP16_SPLIT, OK, OP_N,
+                      OP_T, EcgemmError, Handle, split_size, status_string)
+
+__all__ = ["Handle", "EcgemmError", "split_size", "status_string", "OP_N", "OP_T", "MODE_FP16_SPLIT", "MODE_BF16_FULL",
+           "OK", "ERR_INVALID_ARG", "ERR_ALLOC", "ERR_HIP", "ERR_UNSUPPORTED"]

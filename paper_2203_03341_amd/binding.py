@@ -1,0 +1,135 @@
+"""ctypes binding of libecgemm.so: argument marshalling only, every step runs in the HIP kernels.
+
+The functions mirror include/ecgemm.h one to one.  Matrices are torch CUDA tensors used purely as
+device memory: a column-major (ld, cols) matrix is any float32 tensor whose storage holds it, and
+the binding passes `data_ptr()` straight through.  There is no CPU fallback: if the shared library
+is missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libecgemm.so")
+
+OP_N, OP_T = 0, 1
+MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
+OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
+
+EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
+           "ecgemm_sgemm", "ecgemm_split", "ecgemm_split_size", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_last_error_string", "ecgemm_status_string"]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, f32, vp, sz = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    lib.ecgemm_create.argtypes = [ctypes.POINTER(vp)]
+    lib.ecgemm_destroy.argtypes = [vp]
+    lib.ecgemm_set_stream.argtypes = [vp, vp]
+    lib.ecgemm_workspace_size.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
+    lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
+                                 ctypes.c_int]
+    lib.ecgemm_split.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
+    lib.ecgemm_split_size.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.ecgemm_set_timing.argtypes = [vp, ctypes.c_int]
+    lib.ecgemm_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f32), ctypes.POINTER(f32)]
+    lib.ecgemm_last_error_string.argtypes = [vp]
+    lib.ecgemm_last_error_string.restype = ctypes.c_char_p
+    lib.ecgemm_status_string.argtypes = [ctypes.c_int]
+    lib.ecgemm_status_string.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if getattr(lib, name).restype is not ctypes.c_char_p:
+            getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+_lib = _load()
+
+
+class EcgemmError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        self.status = status
+        super().__init__(f"{_lib.ecgemm_status_string(status).decode()}: {detail}")
+
+
+def _ptr(t) -> int:
+    """Device address of a torch tensor (or a raw integer address, or None)."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+class Handle:
+    """Owns one ecgemm_handle_t.  Methods have the names and argument order of the C functions."""
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        st = _lib.ecgemm_create(ctypes.byref(h))
+        if st != OK:
+            raise EcgemmError(st, "ecgemm_create")
+        self._h = h
+
+    def _check(self, st: int):
+        if st != OK:
+            raise EcgemmError(st, _lib.ecgemm_last_error_string(self._h).decode())
+
+    def destroy(self):
+        if self._h:
+            st = _lib.ecgemm_destroy(self._h)
+            self._h = None
+            if st != OK:
+                raise EcgemmError(st, "ecgemm_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def set_stream(self, stream_ptr: int):
+        self._check(_lib.ecgemm_set_stream(self._h, stream_ptr))
+
+    def workspace_size(self, M: int, N: int, K: int, mode: int) -> int:
+        out = ctypes.c_size_t()
+        self._check(_lib.ecgemm_workspace_size(self._h, M, N, K, mode, ctypes.byref(out)))
+        return out.value
+
+    def set_workspace(self, buffer, nbytes: int):
+        self._check(_lib.ecgemm_set_workspace(self._h, _ptr(buffer), nbytes))
+
+    def sgemm(self, transA: int, transB: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int,
+              beta: float, C, ldc: int, mode: int):
+        self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                      _ptr(C), ldc, mode))
+
+    def split(self, op: int, rows: int, depth: int, src, ld: int, mode: int, packed):
+        self._check(_lib.ecgemm_split(self._h, op, rows, depth, _ptr(src), ld, mode, _ptr(packed)))
+
+    def set_timing(self, enabled: bool):
+        self._check(_lib.ecgemm_set_timing(self._h, int(enabled)))
+
+    def get_timing(self):
+        """(calls, split_ms, product_ms) summed over the calls since timing was enabled / last read."""
+        calls, a, b = ctypes.c_int(), ctypes.c_float(), ctypes.c_float()
+        self._check(_lib.ecgemm_get_timing(self._h, ctypes.byref(calls), ctypes.byref(a), ctypes.byref(b)))
+        return calls.value, a.value, b.value
+
+
+def split_size(rows: int, depth: int, mode: int) -> int:
+    out = ctypes.c_size_t()
+    st = _lib.ecgemm_split_size(rows, depth, mode, ctypes.byref(out))
+    if st != OK:
+        raise EcgemmError(st, "ecgemm_split_size")
+    return out.value
+
+
+def status_string(status: int) -> str:
+    return _lib.ecgemm_status_string(status).decode()

@@ -1,0 +1,360 @@
+// Host side of the ecgemm C-ABI (see include/ecgemm.h): argument checks, workspace, kernel launches.
+#include "../../include/ecgemm.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "product_kernel.hpp"
+#include "split_kernels.hpp"
+
+using namespace ecgemm;
+
+struct TimedCall {
+  hipEvent_t start, split_done, product_done;
+};
+
+struct ecgemm_context {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  void* own_workspace = nullptr;
+  size_t own_bytes = 0;
+  void* user_workspace = nullptr;
+  size_t user_bytes = 0;
+  bool timing = false;
+  std::vector<TimedCall> timed;
+  std::vector<hipEvent_t> free_events;
+  std::string last_error;
+};
+
+namespace {
+
+typedef ProductConfig<false, 256, 128, 128, 64> Fp16Config;
+typedef ProductConfig<true, 256, 128, 128, 64> Bf16Config;
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int parts_of(ecgemm_mode_t mode) { return mode == ECGEMM_MODE_BF16_FULL ? 3 : 2; }
+inline bool valid_mode(int mode) { return mode == ECGEMM_MODE_FP16_SPLIT || mode == ECGEMM_MODE_BF16_FULL; }
+inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
+
+size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
+  return (size_t)round_up(rows, kRowPad) * (size_t)round_up(depth, kDepthPad) * 2 * parts_of(mode);
+}
+
+struct Plan {
+  int64_t Mp, Np, Kp;
+  int tiles_m, tiles_n, k_tiles, k_splits;
+  size_t a_bytes, b_bytes, partial_bytes, total_bytes;
+};
+
+// One tile shape per mode (256 x 128 x 32, 4 waves).  K is divided among blocks only when the output
+// tiles alone cannot occupy the 256 CUs and K is deep enough to leave every block a long loop.
+Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
+  Plan pl;
+  pl.Mp = round_up(M, kRowPad);
+  pl.Np = round_up(N, kRowPad);
+  pl.Kp = round_up(K, kDepthPad);
+  pl.tiles_m = (int)((M + Fp16Config::BM - 1) / Fp16Config::BM);
+  pl.tiles_n = (int)((N + Fp16Config::BN - 1) / Fp16Config::BN);
+  pl.k_tiles = (int)(pl.Kp / Fp16Config::BK);
+  const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+  int splits = 1;
+  if (tiles < 192) {
+    splits = (int)((512 + tiles - 1) / tiles);
+    const int max_by_depth = pl.k_tiles / 16;  // at least 16 k tiles (512 k) per block
+    if (splits > max_by_depth) splits = max_by_depth;
+    if (splits > 64) splits = 64;
+    if (splits < 1) splits = 1;
+  }
+  pl.k_splits = splits;
+  pl.a_bytes = align256(packed_bytes(M, K, mode));
+  pl.b_bytes = align256(packed_bytes(N, K, mode));
+  pl.partial_bytes = splits > 1 ? align256((size_t)splits * pl.Mp * pl.Np * sizeof(float)) : 0;
+  pl.total_bytes = pl.a_bytes + pl.b_bytes + pl.partial_bytes;
+  return pl;
+}
+
+ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {
+  if (h) h->last_error = what;
+  return st;
+}
+
+ecgemm_status_t hip_fail(ecgemm_handle_t h, hipError_t e, const char* where) {
+  return fail(h, ECGEMM_ERR_HIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+
+#define ECGEMM_HIP(h, call)                                   \
+  do {                                                        \
+    hipError_t e_ = (call);                                   \
+    if (e_ != hipSuccess) return hip_fail((h), e_, #call);    \
+  } while (0)
+
+// X = op(src) is rows x depth.  op == N: X(r, k) = src[r + k * ld]; op == T: X(r, k) = src[k + r * ld].
+ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
+                             int64_t ld, ecgemm_mode_t mode, void* packed) {
+  const int64_t Rp = round_up(rows, kRowPad), Kp = round_up(depth, kDepthPad);
+  const int64_t k_steps = Kp / 16;
+  if (Rp / 64 > 65535) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 4193280 rows");
+  const dim3 grid((unsigned)(Kp / 32), (unsigned)(Rp / 64)), block(256);
+  unsigned short* out = static_cast<unsigned short*>(packed);
+  const bool bf16 = mode == ECGEMM_MODE_BF16_FULL;
+  if (op == ECGEMM_OP_T) {
+    const bool vec = (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
+    if (bf16) {
+      if (vec) hipLaunchKernelGGL((split_k_contiguous<true, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+      else hipLaunchKernelGGL((split_k_contiguous<true, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+    } else {
+      if (vec) hipLaunchKernelGGL((split_k_contiguous<false, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+      else hipLaunchKernelGGL((split_k_contiguous<false, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+    }
+  } else {
+    if (bf16) hipLaunchKernelGGL((split_r_contiguous<true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+    else hipLaunchKernelGGL((split_r_contiguous<false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+  }
+  ECGEMM_HIP(h, hipGetLastError());
+  return ECGEMM_OK;
+}
+
+hipEvent_t take_event(ecgemm_handle_t h) {
+  if (!h->free_events.empty()) {
+    hipEvent_t e = h->free_events.back();
+    h->free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ecgemm_status_string(ecgemm_status_t status) {
+  switch (status) {
+    case ECGEMM_OK: return "ECGEMM_OK";
+    case ECGEMM_ERR_INVALID_ARG: return "ECGEMM_ERR_INVALID_ARG";
+    case ECGEMM_ERR_ALLOC: return "ECGEMM_ERR_ALLOC";
+    case ECGEMM_ERR_HIP: return "ECGEMM_ERR_HIP";
+    case ECGEMM_ERR_UNSUPPORTED: return "ECGEMM_ERR_UNSUPPORTED";
+  }
+  return "ECGEMM_ERR_UNKNOWN";
+}
+
+const char* ecgemm_last_error_string(ecgemm_handle_t handle) {
+  return handle ? handle->last_error.c_str() : "null handle";
+}
+
+ecgemm_status_t ecgemm_create(ecgemm_handle_t* handle) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  *handle = nullptr;
+  int device = 0;
+  if (hipGetDevice(&device) != hipSuccess) return ECGEMM_ERR_HIP;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return ECGEMM_ERR_HIP;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return ECGEMM_ERR_UNSUPPORTED;
+  ecgemm_context* ctx = new (std::nothrow) ecgemm_context();
+  if (!ctx) return ECGEMM_ERR_ALLOC;
+  ctx->device = device;
+  *handle = ctx;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  ecgemm_status_t st = ECGEMM_OK;
+  if (handle->own_workspace && hipFree(handle->own_workspace) != hipSuccess) st = ECGEMM_ERR_HIP;
+  for (TimedCall& t : handle->timed) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.split_done);
+    (void)hipEventDestroy(t.product_done);
+  }
+  for (hipEvent_t e : handle->free_events) (void)hipEventDestroy(e);
+  delete handle;
+  return st;
+}
+
+ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void* hip_stream) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  handle->stream = static_cast<hipStream_t>(hip_stream);
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
+                                      ecgemm_mode_t mode, size_t* bytes) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!bytes || M < 0 || N < 0 || K < 0 || !valid_mode(mode))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_workspace_size: bad argument");
+  *bytes = (M == 0 || N == 0 || K == 0) ? 0 : make_plan(M, N, K, mode).total_bytes;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void* device_buffer, size_t bytes) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if ((device_buffer == nullptr) != (bytes == 0) || ((uintptr_t)device_buffer % 256) != 0)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_workspace: buffer must be 256-byte aligned, or (NULL, 0)");
+  handle->user_workspace = device_buffer;
+  handle->user_bytes = bytes;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mode, size_t* bytes) {
+  if (!bytes || rows < 0 || depth < 0 || !valid_mode(mode)) return ECGEMM_ERR_INVALID_ARG;
+  *bytes = packed_bytes(rows, depth, mode);
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth,
+                             const float* src, int64_t ld, ecgemm_mode_t mode, void* packed) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!valid_op(op) || !valid_mode(mode) || rows < 0 || depth < 0)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: bad enum or negative size");
+  if (rows == 0 || depth == 0) return ECGEMM_OK;
+  if (!src || !packed || ((uintptr_t)packed % 16) != 0)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: null or misaligned pointer");
+  if (ld < (op == ECGEMM_OP_N ? rows : depth))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: leading dimension too small");
+  return launch_split(handle, op, rows, depth, src, ld, mode, packed);
+}
+
+ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  handle->timing = enabled != 0;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int* calls, float* split_ms, float* product_ms) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!calls || !split_ms || !product_ms) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_get_timing: null output");
+  *calls = 0;
+  *split_ms = 0.0f;
+  *product_ms = 0.0f;
+  for (TimedCall& t : handle->timed) {
+    ECGEMM_HIP(handle, hipEventSynchronize(t.product_done));
+    float a = 0.0f, b = 0.0f;
+    ECGEMM_HIP(handle, hipEventElapsedTime(&a, t.start, t.split_done));
+    ECGEMM_HIP(handle, hipEventElapsedTime(&b, t.split_done, t.product_done));
+    *split_ms += a;
+    *product_ms += b;
+    *calls += 1;
+    handle->free_events.push_back(t.start);
+    handle->free_events.push_back(t.split_done);
+    handle->free_events.push_back(t.product_done);
+  }
+  handle->timed.clear();
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                             int64_t M, int64_t N, int64_t K, float alpha,
+                             const float* A, int64_t lda, const float* B, int64_t ldb,
+                             float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
+  ecgemm_handle_t h = handle;
+  if (!h) return ECGEMM_ERR_INVALID_ARG;
+  if (!valid_op(transA) || !valid_op(transB) || !valid_mode(mode))
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: bad transA / transB / mode");
+  if (M < 0 || N < 0 || K < 0) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: negative size");
+  if (M == 0 || N == 0) return ECGEMM_OK;
+  if (!C || ldc < M) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: C is null or ldc < M");
+  if (M > 0x7fffffffLL * 32 || N > 0x7fffffffLL * 32 || K > 0x7fffffffLL)
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: size too large");
+
+  const dim3 block256(256);
+  if (K == 0 || alpha == 0.0f) {
+    const dim3 grid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
+    hipLaunchKernelGGL(scale_c_kernel, grid, block256, 0, h->stream, M, N, beta, C, ldc);
+    ECGEMM_HIP(h, hipGetLastError());
+    return ECGEMM_OK;
+  }
+  if (!A || !B) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: A or B is null");
+  if (lda < (transA == ECGEMM_OP_N ? M : K)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: lda too small");
+  if (ldb < (transB == ECGEMM_OP_N ? K : N)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: ldb too small");
+
+  const Plan pl = make_plan(M, N, K, mode);
+  if ((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits > 0x7fffffffLL)
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: too many tiles");
+
+  char* ws = nullptr;
+  if (h->user_workspace) {
+    if (h->user_bytes < pl.total_bytes) return fail(h, ECGEMM_ERR_ALLOC, "ecgemm_sgemm: caller workspace too small");
+    ws = static_cast<char*>(h->user_workspace);
+  } else {
+    if (h->own_bytes < pl.total_bytes) {
+      // the old buffer may still be in use by earlier calls on the stream
+      ECGEMM_HIP(h, hipStreamSynchronize(h->stream));
+      if (h->own_workspace) ECGEMM_HIP(h, hipFree(h->own_workspace));
+      h->own_workspace = nullptr;
+      h->own_bytes = 0;
+      if (hipMalloc(&h->own_workspace, pl.total_bytes) != hipSuccess) {
+        h->own_workspace = nullptr;
+        (void)hipGetLastError();
+        return fail(h, ECGEMM_ERR_ALLOC, "ecgemm_sgemm: hipMalloc of the workspace failed");
+      }
+      h->own_bytes = pl.total_bytes;
+    }
+    ws = static_cast<char*>(h->own_workspace);
+  }
+  char* a_packed = ws;
+  char* b_packed = ws + pl.a_bytes;
+  float* partials = pl.k_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
+
+  TimedCall tc{};
+  if (h->timing) {
+    tc.start = take_event(h);
+    tc.split_done = take_event(h);
+    tc.product_done = take_event(h);
+    if (!tc.start || !tc.split_done || !tc.product_done) return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: hipEventCreate failed");
+    ECGEMM_HIP(h, hipEventRecord(tc.start, h->stream));
+  }
+
+  // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
+  // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
+  ecgemm_status_t st = launch_split(h, transA, M, K, A, lda, mode, a_packed);
+  if (st != ECGEMM_OK) return st;
+  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed);
+  if (st != ECGEMM_OK) return st;
+  if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
+
+  // steps 2 and 3
+  ProductParams pp;
+  pp.a_packed = a_packed;
+  pp.b_packed = b_packed;
+  pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
+  pp.k_tiles = pl.k_tiles;
+  pp.k_splits = pl.k_splits;
+  pp.tiles_m = pl.tiles_m;
+  pp.tiles_n = pl.tiles_n;
+  pp.M = M;
+  pp.N = N;
+  pp.ldc = ldc;
+  pp.alpha = alpha;
+  pp.beta = beta;
+  pp.C = C;
+  pp.partials = partials;
+  pp.Mp = pl.Mp;
+  pp.Np = pl.Np;
+  const dim3 grid((unsigned)((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits));
+  if (mode == ECGEMM_MODE_BF16_FULL)
+    hipLaunchKernelGGL(product_kernel<Bf16Config>, grid, dim3(Bf16Config::THREADS), 0, h->stream, pp);
+  else
+    hipLaunchKernelGGL(product_kernel<Fp16Config>, grid, dim3(Fp16Config::THREADS), 0, h->stream, pp);
+  ECGEMM_HIP(h, hipGetLastError());
+  if (pl.k_splits > 1) {
+    const dim3 rgrid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
+    hipLaunchKernelGGL(reduce_partials_kernel, rgrid, block256, 0, h->stream, partials, pl.k_splits, pl.Mp, pl.Np, M, N,
+                       alpha, beta, C, ldc);
+    ECGEMM_HIP(h, hipGetLastError());
+  }
+  if (h->timing) {
+    ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
+    h->timed.push_back(tc);
+  }
+  return ECGEMM_OK;
+}
+
+}  // extern "C"

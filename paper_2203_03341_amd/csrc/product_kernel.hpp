@@ -1,0 +1,280 @@
+// Steps 2 and 3 of the error-corrected SGEMM: the MFMA main loop and the merge epilogue.
+//
+// FP16 mode (Eq. corr-5-1024-reduce):   C = A16 B16 + (dA16 B16 + A16 dB16) / 2^11
+// BF16 mode (a = a0 + a1 + a2, b alike): C = a0 b0 + [a0 b1 + a1 b0 + a1 b1 + a0 b2 + a2 b0]
+//
+// The leading product has an FP32 accumulator of its own; every correction product goes to a
+// second FP32 accumulator (the frag_dc of the paper's listing) and the two meet once, after
+// the loop.  That matters on this hardware for the same reason it does in the paper: the
+// matrix unit aligns all addends of one instruction to the largest exponent among them and
+// drops what falls below about 2^-25 of it, so a correction term added into the big
+// accumulator would lose its low bits, while among terms of its own size it loses nothing.
+// The accumulate itself rounds to nearest even on gfx950 (measured), so the paper's
+// zero-accumulator trick against round-toward-zero is not needed here.
+//
+// Data flow per workgroup (one per CU, 4 waves, one per SIMD, up to 512 registers each):
+//   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS double buffer (no VGPR staging)
+//   LDS --ds_read_b128--> operand fragments, double buffered in registers
+//   v_mfma_f32_32x32x16_{f16,bf16} --> 2 x (TM x TN) accumulators of 16 floats per lane
+// Operands are stored in fragment order (see split_kernels.hpp), so both hops are linear
+// 1 KiB-per-wave copies: coalesced in global memory and bank-conflict free in LDS by construction.
+//
+// The matrix instruction is used "transposed": the B-side fragment is its first operand and
+// the A-side fragment its second, so a lane owns one row index m of C and a wave's store
+// instruction covers 32 consecutive m: 128-byte runs of column-major C.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "split_kernels.hpp"
+
+namespace ecgemm {
+
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+struct ProductParams {
+  const char* a_packed;     // [Mp/32][k_steps][NP][64][8] 16-bit
+  const char* b_packed;     // [Np/32][k_steps][NP][64][8] 16-bit
+  int64_t row_block_bytes;  // k_steps * NP * 1024
+  int k_tiles;              // depth_padded / 32
+  int k_splits;             // blocks along K per output tile
+  int tiles_m, tiles_n;
+  int64_t M, N, ldc;
+  float alpha, beta;
+  float* C;
+  float* partials;          // [k_splits][Np][Mp] when k_splits > 1
+  int64_t Mp, Np;
+};
+
+template <bool BF16>
+struct Mfma;
+template <>
+struct Mfma<false> {
+  typedef half8_t frag_t;
+  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, acc, 0, 0, 0);
+  }
+};
+template <>
+struct Mfma<true> {
+  typedef bf16x8_t frag_t;
+  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
+  }
+};
+
+template <bool BF16, int BM_, int BN_, int WM_, int WN_>
+struct ProductConfig {
+  static constexpr bool kBf16 = BF16;
+  static constexpr int NP = BF16 ? 3 : 2;
+  static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
+  static constexpr int BK = 32, K_STEPS = BK / 16;
+  static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, WAVES = WAVES_M * WAVES_N;
+  static constexpr int THREADS = WAVES * 64;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int ROW_CHUNKS = K_STEPS * NP;                 // 1 KiB chunks per 32 rows per k tile
+  static constexpr int A_CHUNKS = (BM / 32) * ROW_CHUNKS, B_CHUNKS = (BN / 32) * ROW_CHUNKS;
+  static constexpr int STAGE_BYTES = (A_CHUNKS + B_CHUNKS) * 1024;
+  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shapes");
+  static_assert(kRowPad % BM == 0 && kRowPad % BN == 0, "padded operands must hold whole tiles");
+};
+
+// Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one
+// contiguous range of the tile order, and walk tiles in column groups so that the ~32 tiles
+// an XCD works on at one time share a few A and B panels.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks) {
+  constexpr int kXcds = 8;
+  const int xcd = bid % kXcds, local = bid / kXcds;
+  const int base = nblocks / kXcds, rem = nblocks % kXcds;
+  const int start = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
+  return start + local;
+}
+
+template <class Cfg>
+__global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductParams p) {
+  constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN;
+  typedef typename Mfma<Cfg::kBf16>::frag_t frag_t;
+  __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wave_m = wave % Cfg::WAVES_M, wave_n = wave / Cfg::WAVES_M;
+
+  // ---- which tile, which K range
+  const int tiles = p.tiles_m * p.tiles_n;
+  int pid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int split = pid / tiles;
+  pid -= split * tiles;
+  constexpr int kGroupM = 4;
+  const int group_size = kGroupM * p.tiles_n;
+  const int group = pid / group_size;
+  const int first_m = group * kGroupM;
+  const int group_m = min(p.tiles_m - first_m, kGroupM);
+  const int tile_m = first_m + (pid % group_size) % group_m;
+  const int tile_n = (pid % group_size) / group_m;
+  const int kt_per_split = (p.k_tiles + p.k_splits - 1) / p.k_splits;
+  const int kt_begin = split * kt_per_split;
+  const int kt_count = max(0, min(p.k_tiles, kt_begin + kt_per_split) - kt_begin);
+
+  // ---- global -> LDS: wave w moves the 1 KiB chunks w, w + WAVES, ... of a stage; A_CHUNKS is a
+  // multiple of WAVES, so whether load i fetches from A or from B is known at compile time.  Source
+  // addresses are wave-uniform (scalar registers) plus 16 bytes per lane.
+  constexpr int kLoads = (Cfg::A_CHUNKS + Cfg::B_CHUNKS) / Cfg::WAVES, kALoads = Cfg::A_CHUNKS / Cfg::WAVES;
+  static_assert(Cfg::A_CHUNKS % Cfg::WAVES == 0 && Cfg::B_CHUNKS % Cfg::WAVES == 0, "chunks per wave");
+  const unsigned lane_bytes = lane * 16;
+  const char* src[kLoads];
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) {
+    const bool from_a = i < kALoads;
+    const int c = (from_a ? i : i - kALoads) * Cfg::WAVES + wave;
+    const int64_t first_row_block = from_a ? (int64_t)tile_m * (Cfg::BM / 32) : (int64_t)tile_n * (Cfg::BN / 32);
+    src[i] = (from_a ? p.a_packed : p.b_packed) + (first_row_block + c / Cfg::ROW_CHUNKS) * p.row_block_bytes +
+             (int64_t)kt_begin * (Cfg::ROW_CHUNKS * 1024) + (c % Cfg::ROW_CHUNKS) * 1024;
+  }
+  auto issue_stage = [&](int buf) {  // fetches the next tile not yet requested, then moves on by one tile
+    char* stage = lds + buf * Cfg::STAGE_BYTES + wave * 1024;
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + lane_bytes),
+                                       (void __attribute__((address_space(3)))*)(stage + i * Cfg::WAVES * 1024), 16, 0, 0);
+      src[i] += Cfg::ROW_CHUNKS * 1024;
+    }
+  };
+
+  // ---- LDS -> registers
+  frag_t fa[2][TM][NP], fb[2][TN][NP];
+  const int a_frag_off = wave_m * TM * Cfg::ROW_CHUNKS * 1024 + lane * 16;
+  const int b_frag_off = Cfg::A_CHUNKS * 1024 + wave_n * TN * Cfg::ROW_CHUNKS * 1024 + lane * 16;
+  auto read_frags = [&](int set, int buf, int ks) {
+    const char* stage = lds + buf * Cfg::STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < NP; ++q)
+        fa[set][i][q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + ((i * Cfg::K_STEPS + ks) * NP + q) * 1024);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < NP; ++q)
+        fb[set][j][q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + ((j * Cfg::K_STEPS + ks) * NP + q) * 1024);
+  };
+
+  float16_t acc_main[TM][TN], acc_corr[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        acc_main[i][j][v] = 0.0f;
+        acc_corr[i][j][v] = 0.0f;
+      }
+
+  // One product at a time over all TM x TN tiles: consecutive instructions never share an accumulator.
+  auto multiply = [&](int set) {
+#define ECGEMM_PRODUCT(ACC, QB, QA)                                                    \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
+      ACC[i][j] = Mfma<Cfg::kBf16>::run(fb[set][j][QB], fa[set][i][QA], ACC[i][j]);
+    ECGEMM_PRODUCT(acc_main, 0, 0)
+    if constexpr (!Cfg::kBf16) {
+      ECGEMM_PRODUCT(acc_corr, 1, 0)
+      ECGEMM_PRODUCT(acc_corr, 0, 1)
+    } else {
+      ECGEMM_PRODUCT(acc_corr, 2, 0)
+      ECGEMM_PRODUCT(acc_corr, 0, 2)
+      ECGEMM_PRODUCT(acc_corr, 1, 1)
+      ECGEMM_PRODUCT(acc_corr, 1, 0)
+      ECGEMM_PRODUCT(acc_corr, 0, 1)
+    }
+#undef ECGEMM_PRODUCT
+  };
+
+  // ---- main loop.  Tile kt lives in buffer kt & 1.  The barrier sits between the two k steps of a
+  // tile: by then every wave holds the last fragments of the current buffer in registers, so the buffer
+  // can be refilled (tile kt + 2) while the second k step computes, and the first fragments of tile
+  // kt + 1 are fetched under those same instructions.
+  if (kt_count > 0) {
+    issue_stage(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt_count > 1) issue_stage(1);
+    read_frags(0, 0, 0);
+    for (int t = 0; t < kt_count; ++t) {
+      const int buf = t & 1;
+      read_frags(1, buf, 1);
+      multiply(0);
+      // matrix instructions have no memory side effects, so without the fences the compiler hoists the
+      // barrier (and with it the wait for the fragment reads just issued) above them
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      if (t + 2 < kt_count) issue_stage(buf);
+      if (t + 1 < kt_count) read_frags(0, buf ^ 1, 0);
+      multiply(1);
+    }
+  }
+
+  // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
+  // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
+  const float corr_scale = Cfg::kBf16 ? 1.0f : 0x1p-11f;
+  const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane & 31);
+  const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane >> 5);
+  auto for_each_output = [&](auto&& store) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          store(m_base + i * 32, n_base + j * 32 + 8 * (v / 4) + (v % 4),
+                acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale);
+  };
+  const bool interior = (int64_t)(tile_m + 1) * Cfg::BM <= p.M && (int64_t)(tile_n + 1) * Cfg::BN <= p.N;
+  if (p.k_splits > 1) {
+    float* out = p.partials + (int64_t)split * p.Np * p.Mp;
+    for_each_output([&](int64_t m, int64_t n, float c) { out[n * p.Mp + m] = c; });
+  } else if (interior && p.beta == 0.0f) {
+    for_each_output([&](int64_t m, int64_t n, float c) { p.C[m + n * p.ldc] = p.alpha * c; });
+  } else if (interior) {
+    for_each_output([&](int64_t m, int64_t n, float c) {
+      float* dst = p.C + m + n * p.ldc;
+      *dst = p.alpha * c + p.beta * *dst;
+    });
+  } else {
+    for_each_output([&](int64_t m, int64_t n, float c) {
+      if (m < p.M && n < p.N) {
+        float* dst = p.C + m + n * p.ldc;
+        *dst = (p.beta == 0.0f) ? p.alpha * c : p.alpha * c + p.beta * *dst;
+      }
+    });
+  }
+}
+
+// Split-K tail: sums the k_splits partial tiles in a fixed order, then alpha / beta.
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partials, int k_splits,
+                                                              int64_t Mp, int64_t Np, int64_t M, int64_t N,
+                                                              float alpha, float beta, float* __restrict__ C, int64_t ldc) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  for (int64_t n = blockIdx.y; n < N; n += gridDim.y) {
+    float sum = 0.0f;
+    for (int s = 0; s < k_splits; ++s) sum += partials[((int64_t)s * Np + n) * Mp + m];
+    float* dst = C + m + n * ldc;
+    *dst = (beta == 0.0f) ? alpha * sum : alpha * sum + beta * *dst;
+  }
+}
+
+// K == 0 or alpha == 0: C <- beta * C, and C <- 0 without reading it when beta == 0.
+__global__ void __launch_bounds__(256) scale_c_kernel(int64_t M, int64_t N, float beta, float* __restrict__ C, int64_t ldc) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  for (int64_t n = blockIdx.y; n < N; n += gridDim.y) {
+    float* dst = C + m + n * ldc;
+    *dst = (beta == 0.0f) ? 0.0f : beta * *dst;
+  }
+}
+
+}  // namespace ecgemm

@@ -1,0 +1,140 @@
+// Step 1 of the error-corrected SGEMM: element split + repack, HBM-bandwidth bound.
+//
+// FP16 mode (Eqs. corr-1-1024 .. corr-4-1024):  v16 = toFP16(v),  dv16 = toFP16((v - toFP32(v16)) * 2^11)
+// BF16 mode (three exact terms, stands in for the paper's TF32 pair on hardware without a TF32
+// matrix instruction):  b0 = toBF16(v), b1 = toBF16(v - b0), b2 = toBF16(v - b0 - b1)
+// Conversions round to nearest even (the hardware converts) and saturate: a finite input never
+// yields an infinite part.  An infinite input keeps only its high part.
+//
+// Output layout ("fragment order"), 16-bit elements:
+//     packed[row_block][k_step][part][lane][8],  row_block = r / 32, k_step = k / 16,
+//     lane = ((k % 16) / 8) * 32 + r % 32, element = k % 8
+// so that one 1 KiB chunk is exactly what the 64 lanes of a wave feed to one
+// v_mfma_f32_32x32x16 operand, and a block tile is a run of whole chunks.  Rows are padded to
+// kRowPad and depth to kDepthPad with zeros, which makes every tile of the product kernel full.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ecgemm {
+
+constexpr int kRowPad = 256;
+constexpr int kDepthPad = 32;
+constexpr int kChunkElems = 512;  // 64 lanes x 8 elements
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef unsigned short ushort8_t __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ float saturate_finite(float v, float limit) {
+  // leaves Inf and NaN alone, clamps everything finite into [-limit, limit]
+  return (__builtin_fabsf(v) <= 3.402823466e+38f) ? __builtin_fminf(__builtin_fmaxf(v, -limit), limit) : v;
+}
+
+template <bool BF16>
+struct Splitter;
+
+template <>
+struct Splitter<false> {
+  static constexpr int kParts = 2;
+  __device__ static __forceinline__ void split(float v, unsigned short (&out)[2]) {
+    const _Float16 hi = (_Float16)saturate_finite(v, 65504.0f);
+    const float residual = (v - (float)hi) * 2048.0f;  // both operations exact
+    _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
+    if (__builtin_isinf((float)hi)) lo = (_Float16)0.0f;
+    out[0] = __builtin_bit_cast(unsigned short, hi);
+    out[1] = __builtin_bit_cast(unsigned short, lo);
+  }
+};
+
+template <>
+struct Splitter<true> {
+  static constexpr int kParts = 3;
+  static constexpr float kMax = 3.3895313892515355e+38f;  // largest finite BF16
+  __device__ static __forceinline__ void split(float v, unsigned short (&out)[3]) {
+    const __bf16 b0 = (__bf16)saturate_finite(v, kMax);
+    const float r1 = v - (float)b0;
+    __bf16 b1 = (__bf16)saturate_finite(r1, kMax);
+    const float r2 = r1 - (float)b1;
+    __bf16 b2 = (__bf16)saturate_finite(r2, kMax);
+    if (__builtin_isinf((float)b0)) {
+      b1 = (__bf16)0.0f;
+      b2 = (__bf16)0.0f;
+    }
+    out[0] = __builtin_bit_cast(unsigned short, b0);
+    out[1] = __builtin_bit_cast(unsigned short, b1);
+    out[2] = __builtin_bit_cast(unsigned short, b2);
+  }
+};
+
+// Writes the eight consecutive-k values `v` of row r (global indices) to their place in `packed`.
+template <bool BF16>
+__device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ packed, int64_t k_steps_total,
+                                                   int64_t r, int64_t k, const float (&v)[8]) {
+  constexpr int NP = Splitter<BF16>::kParts;
+  ushort8_t parts[NP];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    unsigned short s[NP];
+    Splitter<BF16>::split(v[e], s);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) parts[p][e] = s[p];
+  }
+  const int64_t row_block = r >> 5, k_step = k >> 4;
+  const int lane = (int)((k >> 3) & 1) * 32 + (int)(r & 31);
+  unsigned short* chunk = packed + ((row_block * k_steps_total + k_step) * NP) * kChunkElems + lane * 8;
+#pragma unroll
+  for (int p = 0; p < NP; ++p) *reinterpret_cast<ushort8_t*>(chunk + p * kChunkElems) = parts[p];
+}
+
+// Source with k contiguous: X(r, k) = src[k + r * ld].  One block: 64 rows x 32 k, 256 threads,
+// thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4).
+template <bool BF16, bool VEC>
+__global__ void __launch_bounds__(256) split_k_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
+                                                          int64_t depth, int64_t k_steps_total,
+                                                          unsigned short* __restrict__ packed) {
+  const int t = threadIdx.x;
+  const int64_t r = (int64_t)blockIdx.y * 64 + (t >> 2);
+  const int64_t k = (int64_t)blockIdx.x * 32 + (t & 3) * 8;
+  float v[8];
+  if (r < rows && k + 8 <= depth && VEC) {
+    const float4 lo = *reinterpret_cast<const float4*>(src + r * ld + k);
+    const float4 hi = *reinterpret_cast<const float4*>(src + r * ld + k + 4);
+    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+    v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r * ld + k + e] : 0.0f;
+  }
+  store_fragment_row<BF16>(packed, k_steps_total, r, k, v);
+}
+
+// Source with r contiguous: X(r, k) = src[r + k * ld].  One block: 64 rows x 32 k, transposed
+// through LDS so that both the global reads (along r) and the fragment writes are coalesced.
+template <bool BF16>
+__global__ void __launch_bounds__(256) split_r_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
+                                                          int64_t depth, int64_t k_steps_total,
+                                                          unsigned short* __restrict__ packed) {
+  constexpr int kStride = 66;  // floats per k line in LDS; 66 keeps the transposed reads conflict-free
+  __shared__ float tile[32 * kStride];
+  const int t = threadIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.y * 64, k0 = (int64_t)blockIdx.x * 32;
+  {
+    const int rr = t & 63;
+    const int64_t r = r0 + rr;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int kk = (t >> 6) + 4 * j;
+      const int64_t k = k0 + kk;
+      tile[kk * kStride + rr] = (r < rows && k < depth) ? src[r + k * ld] : 0.0f;
+    }
+  }
+  __syncthreads();
+  const int rr = t >> 2, kk = (t & 3) * 8;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = tile[(kk + e) * kStride + rr];
+  store_fragment_row<BF16>(packed, k_steps_total, r0 + rr, k0 + kk, v);
+}
+
+}  // namespace ecgemm

@@ -1,0 +1,45 @@
+"""The shared library loads and exports every symbol the header declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ecgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ecgemm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_north_star_entry_points():
+    names = _declared_functions()
+    for required in ("ecgemm_create", "ecgemm_sgemm", "ecgemm_destroy"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2203_03341_amd import binding
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == _declared_functions()
+
+
+def test_status_strings_and_sizes_need_no_gpu():
+    import paper_2203_03341_amd as ec
+    assert ec.status_string(ec.OK) == "ECGEMM_OK"
+    assert ec.status_string(ec.ERR_INVALID_ARG) == "ECGEMM_ERR_INVALID_ARG"
+    # rows pad to 256, depth to 32, two (FP16) or three (BF16) 16-bit parts
+    assert ec.split_size(1, 1, ec.MODE_FP16_SPLIT) == 256 * 32 * 2 * 2
+    assert ec.split_size(257, 33, ec.MODE_BF16_FULL) == 512 * 64 * 2 * 3
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The package must not import, load or mention the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2203_03341_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)

@@ -1,0 +1,273 @@
+"""Whole-path parity: ecgemm_sgemm through the C-ABI against the CPU oracle.
+
+Pass rule (the accuracy bar of the method): the relative residual of the GPU result against the FP64
+reference is at most 1.25 x that of the naive FP32 product on the same inputs.  The exact bits of an
+FP32 GEMM depend on the summation order, so bit parity with any CPU loop is not defined; what is
+unique is checked element by element instead:
+
+  * against the exact-accumulation model of the method (same split, FP64 sums) the GPU result may only
+    differ by its FP32 accumulation.  The matrix unit adds eight products to the accumulator per
+    rounding, each rounding is to nearest (relative 2^-24) after an alignment that drops less than
+    2^-24 of the largest addend, so |C_gpu - C_model| <= (K / 8 + 4) * 2^-23 * (|A| |B|) element-wise.
+  * integer inputs whose partial sums stay below 2^24 must come out exact, bit for bit.
+"""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+from oracle import gemm, model
+from gpu_util import empty_colmajor, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+RATIO = 1.25
+
+
+def _modes():
+    import paper_2203_03341_amd as ec
+    return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL}
+
+
+def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None):
+    import torch
+    import paper_2203_03341_amd as ec
+    h = handle or ec.Handle()
+    dA, dB = to_device(A), to_device(B)
+    ldc = ldc or (C.shape[0] if C is not None else M)
+    if C is not None:
+        dC = to_device(C)
+    else:
+        dC = empty_colmajor(ldc, N, fill=float("nan"))
+    ops = {"N": ec.OP_N, "T": ec.OP_T}
+    h.sgemm(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], beta, dC, ldc, _modes()[mode])
+    torch.cuda.synchronize()
+    out = to_host(dC, ldc, N)
+    if handle is None:
+        h.destroy()
+    return out
+
+
+def _inputs(M, N, K, transA, transB, dist, seed, pad=0):
+    ar, ac = (M, K) if transA == "N" else (K, M)
+    br, bc = (K, N) if transB == "N" else (N, K)
+    if dist == "urand":
+        A = si.urand(ar, ac, seed, si.ID_A, ld=ar + pad)
+        B = si.urand(br, bc, seed, si.ID_B, ld=br + pad)
+    else:
+        (a_lo, a_hi), (b_lo, b_hi) = dist
+        A = si.exp_rand(ar, ac, a_lo, a_hi, seed, si.ID_A, ld=ar + pad)
+        B = si.exp_rand(br, bc, b_lo, b_hi, seed, si.ID_B, ld=br + pad)
+    return A, B
+
+
+def _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=0, pad=0, rows=None, elementwise=True,
+           ratio_rule=True):
+    A, B = _inputs(M, N, K, transA, transB, dist, seed, pad)
+    C = si.urand(M, N, seed, si.ID_C, ld=M + pad) if beta != 0 else None
+    got_store = _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=M + pad)
+    got = got_store[:M, :N]
+    if pad and beta != 0:
+        # rows beyond M belong to the caller and must be left alone (they hold NaN from the generator)
+        assert np.all(np.isnan(got_store[M:, :]))
+    if rows is not None:
+        got = got[rows, :]
+    c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C, rows=rows)
+    c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C, rows=rows)
+    assert np.all(np.isfinite(got))
+    r_gpu = gemm.relative_residual(c64, got)
+    r_cpu = gemm.relative_residual(c64, c32)
+    if ratio_rule:
+        assert r_gpu <= RATIO * r_cpu, (mode, M, N, K, r_gpu, r_cpu, r_gpu / r_cpu)
+    else:
+        # a handful of products: the statistical rule means nothing (one FP32 product has a single 2^-24
+        # rounding, the FP16 pair may be off by an ulp, 2^-23, per input); bound every element instead
+        opA_, opB_ = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)
+        mag_ = np.abs(alpha) * (np.abs(opA_).astype(np.float64) @ np.abs(opB_).astype(np.float64))
+        assert np.all(np.abs(got - c64) <= (2.0 ** -22 + (K / 8 + 4) * 2.0 ** -23) * mag_ + 1e-300)
+    if elementwise:
+        opA = gemm.logical(transA, A, M, K)
+        opB = gemm.logical(transB, B, K, N)
+        if rows is not None:
+            opA = opA[rows, :]
+        mdl = model.gemm_fp16_mode(opA, opB) if mode == "fp16" else model.gemm_bf16_mode(opA, opB)
+        mag = np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64)
+        want = alpha * mdl
+        bound = (K / 8 + 4) * 2.0 ** -23 * abs(alpha) * mag
+        if beta != 0:
+            cin = C[:M, :N] if rows is None else C[:M, :N][rows, :]
+            want = want + beta * cin.astype(np.float64)
+            bound = bound + 2.0 ** -22 * (np.abs(want) + np.abs(beta * cin))
+        worst = np.max(np.abs(got - want) / (bound + 1e-300))
+        assert worst <= 1.0, (mode, M, N, K, worst)
+    return r_gpu, r_cpu
+
+
+# ----- config 1 of the baseline and friends: small, full oracle, several tiles plus a ragged tail
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_config1_256_cubed(mode):
+    _check("N", "N", 256, 256, 256, 1.0, 0.0, mode, "urand", seed=0)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+@pytest.mark.parametrize("transA", ["N", "T"])
+@pytest.mark.parametrize("transB", ["N", "T"])
+def test_transposes_ragged_and_alpha_beta(mode, transA, transB):
+    _check(transA, transB, 300, 200, 77, 1.5, 0.5, mode, "urand", seed=1, pad=3)
+    _check(transA, transB, 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_tiny_shapes(mode):
+    for (M, N, K) in [(1, 1, 1), (2, 3, 5), (17, 5, 8), (31, 33, 15), (64, 1, 100), (1, 257, 33)]:
+        _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=M + N + K, ratio_rule=False)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_small_integers_bit_exact(mode):
+    """Exact products of small integers: every summation order gives the same FP32 bits."""
+    M, N, K = 320, 192, 2048
+    A = si.randint(M, K, -15, 15, 0, si.ID_A)
+    B = si.randint(K, N, -15, 15, 0, si.ID_B)
+    exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float32)
+    got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)
+    assert np.array_equal(got[:M, :N].view(np.uint32), exact.view(np.uint32))
+    # integers that need the low parts (|a| up to 2^15: 16 significant bits), sums still below 2^24
+    A2 = si.randint(M, 16, -(2 ** 15), 2 ** 15, 1, si.ID_A)
+    B2 = si.randint(16, N, -3, 3, 1, si.ID_B)
+    exact2 = (A2.astype(np.int64) @ B2.astype(np.int64))
+    assert np.abs(exact2).max() < 2 ** 24
+    got2 = _gpu_sgemm("N", "N", M, N, 16, 1.0, A2, B2, 0.0, None, mode)[:M, :N]
+    assert np.array_equal(got2.astype(np.int64), exact2)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_degenerate_cases(mode):
+    import torch
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    m = _modes()[mode]
+    M, N, K = 70, 50, 40
+    A, B = _inputs(M, N, K, "N", "N", "urand", 3)
+    C = si.urand(M, N, 3, si.ID_C)
+    dA, dB = to_device(A), to_device(B)
+    # K == 0 and alpha == 0: C <- beta * C
+    for (kk, alpha) in [(0, 1.0), (K, 0.0)]:
+        dC = to_device(C)
+        h.sgemm(ec.OP_N, ec.OP_N, M, N, kk, alpha, dA, M, dB, max(K, 1), 0.5, dC, M, m)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(dC, M, N), (np.float32(0.5) * C).astype(np.float32))
+        dC = empty_colmajor(M, N, fill=float("nan"))
+        h.sgemm(ec.OP_N, ec.OP_N, M, N, kk, alpha, dA, M, dB, max(K, 1), 0.0, dC, M, m)
+        torch.cuda.synchronize()
+        assert np.all(to_host(dC, M, N) == 0.0)
+    # M == 0 / N == 0: nothing is touched, null pointers are fine
+    h.sgemm(ec.OP_N, ec.OP_N, 0, N, K, 1.0, None, 1, dB, K, 0.0, None, 1, m)
+    h.sgemm(ec.OP_N, ec.OP_N, M, 0, K, 1.0, dA, M, None, K, 0.0, None, M, m)
+    # beta == 0 must not read C: NaN already there does not propagate
+    dC = empty_colmajor(M, N, fill=float("nan"))
+    h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, m)
+    torch.cuda.synchronize()
+    assert np.all(np.isfinite(to_host(dC, M, N)))
+    h.destroy()
+
+
+def test_invalid_arguments_are_rejected():
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    M = N = K = 64
+    A, B = _inputs(M, N, K, "N", "N", "urand", 0)
+    dA, dB = to_device(A), to_device(B)
+    dC = empty_colmajor(M, N, fill=1.0)
+    bad_calls = [
+        dict(transA=7), dict(transB=-1), dict(mode=5), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
+        dict(ldc=M - 1), dict(A=None), dict(B=None), dict(C=None),
+    ]
+    base = dict(transA=ec.OP_N, transB=ec.OP_N, M=M, N=N, K=K, alpha=1.0, A=dA, lda=M, B=dB, ldb=K, beta=0.0, C=dC,
+                ldc=M, mode=ec.MODE_FP16_SPLIT)
+    for bad in bad_calls:
+        args = dict(base, **bad)
+        with pytest.raises(ec.EcgemmError) as ei:
+            h.sgemm(**args)
+        assert ei.value.status == ec.ERR_INVALID_ARG, bad
+    # a caller workspace that is too small is refused before anything is launched
+    import torch
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    h.set_workspace(ws, 1024)
+    with pytest.raises(ec.EcgemmError) as ei:
+        h.sgemm(**base)
+    assert ei.value.status == ec.ERR_ALLOC
+    need = h.workspace_size(M, N, K, ec.MODE_FP16_SPLIT)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h.set_workspace(ws, need)
+    h.sgemm(**base)
+    torch.cuda.synchronize()
+    assert np.all(to_host(dC, M, N) != 1.0)
+    h.set_workspace(None, 0)
+    h.destroy()
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_bitwise_reproducible_and_stream(mode):
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 512, 384, 4096          # K deep enough that the K range is divided among blocks
+    A, B = _inputs(M, N, K, "N", "T", "urand", 5)
+    h = ec.Handle()
+    stream = torch.cuda.Stream()
+    h.set_stream(stream.cuda_stream)
+    h.set_timing(True)
+    outs = []
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            outs.append(_gpu_sgemm("N", "T", M, N, K, 1.0, A, B, 0.0, None, mode, handle=h))
+    calls, split_ms, product_ms = h.get_timing()
+    assert calls == 3 and split_ms > 0 and product_ms > 0
+    h.destroy()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))
+
+
+# ----- the shape sweep of the baseline (config 5), reduced in size where the full oracle would take minutes
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_deep_k_uses_split_k(mode):
+    _check("N", "N", 256, 256, 16384, 1.0, 0.0, mode, "urand", seed=7)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_tall_skinny(mode):
+    rows = si.sample_indices(4096, 512, seed=1)
+    _check("N", "N", 4096, 4096, 256, 1.0, 0.0, mode, "urand", seed=8, rows=rows)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_odd_sizes_transA(mode):
+    M, N, K = 1023, 751, 1251          # config 5's 4095 x 3001 x 5003 at a quarter of the size, same raggedness
+    _check("T", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=9)
+
+
+# ----- exponent ranges (section "Effect of the exponent range of input matrices")
+
+def test_fp16_mode_limited_exponent_range():
+    """Type 1 inputs, widened to the baseline's [-15, 15]: the top binade saturates at 65504 in the split."""
+    _check("N", "N", 512, 512, 512, 1.0, 0.0, "fp16", ((-15, 15), (-15, 15)), seed=0)
+    _check("N", "N", 512, 512, 512, 1.0, 0.0, "fp16", ((-15, 14), (-15, 14)), seed=1)
+
+
+def test_bf16_mode_full_exponent_range():
+    """Wide-range A times Type-1 B (finite in FP32), and both wide but bounded so products stay finite."""
+    _check("N", "N", 512, 512, 512, 1.5, 0.5, "bf16", ((-100, 100), (-15, 14)), seed=0)
+    _check("N", "N", 512, 512, 512, 1.0, 0.0, "bf16", ((-50, 50), (-50, 50)), seed=1)
+    _check("N", "N", 384, 256, 640, 1.0, 0.0, "bf16", ((-100, -35), (-15, 14)), seed=2)
+
+
+def test_fp16_mode_fails_outside_its_range_like_the_paper_says():
+    """Type 4: inputs in exp_rand(-100, -35) are below anything halfhalf can hold; the result is (nearly)
+    all zeros and the error is of order one, while the BF16 mode still meets the bar."""
+    M = N = K = 256
+    A, B = _inputs(M, N, K, "N", "N", ((-100, -35), (-15, 14)), 0)
+    c64 = gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.0, A, B)
+    got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "fp16")[:M, :N]
+    assert gemm.relative_residual(c64, got) > 0.1
+    _check("N", "N", M, N, K, 1.0, 0.0, "bf16", ((-100, -35), (-15, 14)), seed=0)

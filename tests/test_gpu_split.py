@@ -1,0 +1,90 @@
+"""Step 1 parity: the HIP split kernel against the numpy split, bit for bit, through the C-ABI."""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+from oracle import split
+from gpu_util import pack_fragment_order, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def _expected(op, store, rows, depth, mode_bf16):
+    X = store[:rows, :depth] if op == "N" else store[:depth, :rows].T
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    if mode_bf16:
+        parts = list(split.split_bf16x3(X))
+    else:
+        parts = [p.view(np.uint16) for p in split.split_fp16(X)]
+    return pack_fragment_order(parts)
+
+
+def _run(op, store, rows, depth, mode_bf16, offset_elems=0):
+    import torch
+    import paper_2203_03341_amd as ec
+    mode = ec.MODE_BF16_FULL if mode_bf16 else ec.MODE_FP16_SPLIT
+    h = ec.Handle()
+    src = to_device(store)
+    nbytes = ec.split_size(rows, depth, mode)
+    packed = torch.full((nbytes // 2,), 0x7FFF, dtype=torch.int16, device="cuda")   # poison
+    ld = store.shape[0]
+    h.split(ec.OP_N if op == "N" else ec.OP_T, rows, depth, src, ld, mode, packed)
+    torch.cuda.synchronize()
+    got = packed.cpu().numpy().view(np.uint16)
+    h.destroy()
+    return got
+
+
+CASES = [
+    # (op, rows, depth, ld padding)
+    ("N", 256, 256, 0), ("T", 256, 256, 0),
+    ("N", 300, 77, 5), ("T", 300, 77, 3),
+    ("N", 1, 1, 0), ("T", 1, 1, 0),
+    ("N", 33, 1031, 1), ("T", 515, 40, 4), ("T", 70, 129, 1),
+]
+
+
+@pytest.mark.parametrize("mode_bf16", [False, True])
+@pytest.mark.parametrize("op,rows,depth,pad", CASES)
+def test_split_matches_oracle_bitwise(op, rows, depth, pad, mode_bf16):
+    sr, sc = (rows, depth) if op == "N" else (depth, rows)
+    for kind in ("urand", "exp15", "exp100"):
+        if kind == "urand":
+            store = si.urand(sr, sc, seed=1, matrix_id=si.ID_A, ld=sr + pad)
+        elif kind == "exp15":
+            store = si.exp_rand(sr, sc, -15, 15, seed=2, matrix_id=si.ID_A, ld=sr + pad)
+        else:
+            store = si.exp_rand(sr, sc, -100, 100, seed=3, matrix_id=si.ID_A, ld=sr + pad)
+        got = _run(op, store, rows, depth, mode_bf16)
+        want = _expected(op, store, rows, depth, mode_bf16)
+        assert got.shape == want.shape
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, (kind, bad[:8], got[bad[:8]], want[bad[:8]])
+
+
+@pytest.mark.parametrize("mode_bf16", [False, True])
+def test_split_edge_values(mode_bf16):
+    """Saturation, signed zeros, values that only the scaled residual can hold, FP32 subnormals, Inf, NaN."""
+    vals = [0.0, -0.0, 65504.0, 65519.996, 65520.0, 65535.996, -65535.996, 2.0 ** -24, 2.0 ** -25, 2.0 ** -35,
+            2.0 ** -36, 1.5 * 2.0 ** -36, 1e-45, -1e-40, 2.0 ** -126, 3.4028234e38, -3.4028234e38, 3.39e38,
+            np.inf, -np.inf, 1.0, -1.0, 0.1, 2.0 ** -14, 2.0 ** -15, 1.9999999 * 2.0 ** -15, 6.1e-5, 100000.0, 1e30]
+    vals = np.array(vals, dtype=np.float32)
+    rows, depth = 8, vals.size
+    store = np.asfortranarray(np.tile(vals, (rows, 1)) * np.array([[1], [-1], [1], [-1], [1], [-1], [1], [-1]], np.float32))
+    store = np.asfortranarray(store.astype(np.float32))
+    for op in ("N", "T"):
+        st = store if op == "N" else np.asfortranarray(store.T)
+        got = _run(op, st, rows, depth, mode_bf16)
+        want = _expected(op, st, rows, depth, mode_bf16)
+        assert np.array_equal(got, want), np.flatnonzero(got != want)[:10]
+    # NaN: every part is a NaN (payload bits are not compared)
+    nan_store = np.full((4, 4), np.nan, dtype=np.float32, order="F")
+    got = _run("N", nan_store, 4, 4, mode_bf16)
+    nparts = 3 if mode_bf16 else 2
+    first = got.reshape(-1, nparts, 64, 8)[0]
+    for p in range(nparts):
+        bits = first[p, 0, 0]
+        if mode_bf16:
+            assert (bits & 0x7F80) == 0x7F80 and (bits & 0x7F) != 0
+        else:
+            assert (bits & 0x7C00) == 0x7C00 and (bits & 0x3FF) != 0
