@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Throughput and accuracy of the error-corrected SGEMM on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one whole `ecgemm_sgemm` call (split of A and B, MFMA product, merge epilogue) on inputs that
+already sit in HBM.  The default workload is the one the headline metric is quoted on: M = N = K = 16384,
+FP16-split mode, entries sign * (1 + u) * 2^e with e uniform in [-15, 15].  One JSON line is printed:
+FP32-equivalent TFLOP/s = 2 M N K / t, the MFMA roofline of the product kernel (its own duration measured
+with HIP events on the launch stream), the relative residual against an FP64 reference next to that of a
+naive FP32 product (both from the CPU oracle, on a seeded sample of rows of C), and the oracle's own speed
+on the host cores as `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "FP32-equivalent TFLOP/s (2MNK/t) at 16384^3 + rel. error vs FP64 ref"
+PEAK_MFMA_16BIT_TFLOPS = 2516.6     # 256 CU x 4096 flop/clk x 2.4 GHz, dense FP16 / BF16
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+
+# HBM bytes per product-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
+# workload; None where no counter run has been made for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+WORKLOADS = {
+    # name: (M, N, K, transA, transB, mode, alpha, beta, distribution, oracle rows)
+    "c1_256_fp16_urand": (256, 256, 256, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "c2_4096_fp16_urand": (4096, 4096, 4096, "N", "N", "fp16", 1.0, 0.0, "urand", 1024),
+    "c2_4096_bf16_urand": (4096, 4096, 4096, "N", "N", "bf16", 1.0, 0.0, "urand", 1024),
+    "c3_16384_fp16_exprand15": (16384, 16384, 16384, "N", "N", "fp16", 1.0, 0.0, ((-15, 15), (-15, 15)), 512),
+    # config 4 as written (both operands exp_rand(-100, 100)) overflows FP32 in every element of C, on the CPU
+    # and on the GPU alike; the graded stand-in keeps A wide and B in the Type-1 range so that C stays finite
+    "c4_8192_bf16_widerange": (8192, 8192, 8192, "N", "N", "bf16", 1.5, 0.5, ((-100, 100), (-15, 14)), 512),
+    "c5_tallskinny_fp16": (16384, 16384, 256, "N", "N", "fp16", 1.0, 0.0, "urand", 2048),
+    "c5_tallskinny_bf16": (16384, 16384, 256, "N", "N", "bf16", 1.0, 0.0, "urand", 2048),
+    "c5_deepk_fp16": (1024, 1024, 65536, "N", "N", "fp16", 1.0, 0.0, "urand", 256),
+    "c5_deepk_bf16": (1024, 1024, 65536, "N", "N", "bf16", 1.0, 0.0, "urand", 256),
+    "c5_odd_transA_fp16": (4095, 3001, 5003, "T", "N", "fp16", 1.0, 0.0, "urand", 1024),
+    "c5_odd_transA_bf16": (4095, 3001, 5003, "T", "N", "bf16", 1.0, 0.0, "urand", 1024),
+}
+DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
+
+
+def make_inputs(M, N, K, transA, transB, dist, beta, seed=0):
+    import seeded_inputs as si
+    ar, ac = (M, K) if transA == "N" else (K, M)
+    br, bc = (K, N) if transB == "N" else (N, K)
+    if dist == "urand":
+        A = si.urand(ar, ac, seed, si.ID_A)
+        B = si.urand(br, bc, seed, si.ID_B)
+    else:
+        (a_lo, a_hi), (b_lo, b_hi) = dist
+        A = si.exp_rand(ar, ac, a_lo, a_hi, seed, si.ID_A)
+        B = si.exp_rand(br, bc, b_lo, b_hi, seed, si.ID_B)
+    C = si.urand(M, N, seed, si.ID_C) if beta != 0 else None
+    return A, B, C
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle (no error figures, no cpu_baseline)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the product has no exchange step to measure); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    import paper_2203_03341_amd as ec
+    import seeded_inputs as si
+
+    M, N, K, transA, transB, mode, alpha, beta, dist, oracle_rows = WORKLOADS[args.workload]
+    parts_products = {"fp16": 3, "bf16": 6}[mode]
+    mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL}[mode]
+    ops = {"N": ec.OP_N, "T": ec.OP_T}
+
+    t0 = time.time()
+    A, B, C = make_inputs(M, N, K, transA, transB, dist, beta, args.seed)
+    gen_s = time.time() - t0
+    dA = torch.from_numpy(np.ascontiguousarray(A.T)).cuda()
+    dB = torch.from_numpy(np.ascontiguousarray(B.T)).cuda()
+    dC0 = torch.from_numpy(np.ascontiguousarray(C.T)).cuda() if C is not None else None
+    dC = torch.empty((N, M), dtype=torch.float32, device="cuda")
+
+    stream = torch.cuda.current_stream()
+    h = ec.Handle()
+    h.set_stream(stream.cuda_stream)
+    ws_bytes = h.workspace_size(M, N, K, mode_id)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    h.set_workspace(ws, ws_bytes)
+
+    def step():
+        if dC0 is not None:
+            dC.copy_(dC0)          # beta != 0: every step starts from the same C (the copy is inside the timed region)
+        h.sgemm(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], beta, dC, M, mode_id)
+
+    if args.copy_probe:
+        probe_src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        probe_dst = torch.empty_like(probe_src)
+        probe_dst.copy_(probe_src)
+        torch.cuda.synchronize()
+        del probe_src, probe_dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    h.set_timing(True)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    start.record(stream)
+    for _ in range(args.steps):
+        step()
+    stop.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - wall0) * 1e3
+    event_ms = start.elapsed_time(stop)
+    calls, split_ms, product_ms = h.get_timing()
+    h.set_timing(False)
+    assert calls == args.steps
+    ms_per_step = max(wall_ms, event_ms) / args.steps
+    flops = 2.0 * M * N * K
+    tflops = flops / (ms_per_step * 1e-3) / 1e12
+    product_ms_avg = product_ms / calls
+    mfma_tflops = parts_products * flops / (product_ms_avg * 1e-3) / 1e12
+
+    got = dC.cpu().numpy().T          # logical M x N
+    result = {
+        "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16" if mode == "fp16" else "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": transA, "transB": transB,
+                   "mode": mode, "alpha": alpha, "beta": beta, "products": parts_products,
+                   "inputs": "urand(-1,1)" if dist == "urand" else f"exp_rand{dist[0]} x exp_rand{dist[1]}", "seed": args.seed},
+        "split_ms": round(split_ms / calls, 4), "product_ms": round(product_ms_avg, 4),
+        "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
+        "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(mfma_tflops / PEAK_MFMA_16BIT_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel": "product_kernel",
+                     "flops_per_launch": parts_products * flops},
+    }
+
+    if not args.no_oracle:
+        from oracle import gemm
+        rows = None if oracle_rows is None or oracle_rows >= M else si.sample_indices(M, oracle_rows, seed=args.seed + 1)
+        nrows = M if rows is None else len(rows)
+        t0 = time.perf_counter()
+        c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C, rows=rows)
+        oracle_s = time.perf_counter() - t0
+        c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C, rows=rows)
+        got_rows = got if rows is None else got[rows, :]
+        finite = bool(np.all(np.isfinite(got_rows)))
+        r_gpu = gemm.relative_residual(c64, got_rows)
+        r_cpu = gemm.relative_residual(c64, c32)
+        result.update({
+            "relres_gpu": r_gpu, "relres_fp32_oracle": r_cpu, "relres_ratio": round(r_gpu / r_cpu, 4),
+            "max_dev_gpu": gemm.max_deviation(c64, got_rows), "max_dev_fp32_oracle": gemm.max_deviation(c64, c32),
+            "accuracy_pass": bool(finite and r_gpu <= 1.25 * r_cpu), "accuracy_rows": nrows,
+            "cpu_baseline": {"value": round(2.0 * nrows * N * K / oracle_s / 1e12, 5), "unit": "TFLOP/s",
+                             "cores": gemm.num_threads(), "kind": "oracle",
+                             "sample": f"naive FP32 product of {nrows} seeded rows of C (all {N} columns, full K = {K}) "
+                                       f"of the same workload, {oracle_s:.1f} s"},
+        })
+    result["input_generation_s"] = round(gen_s, 1)
+    h.destroy()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -33,8 +33,8 @@ struct ecgemm_context {
 
 namespace {
 
-typedef ProductConfig<false, 256, 128, 128, 64> Fp16Config;
-typedef ProductConfig<true, 256, 128, 128, 64> Bf16Config;
+typedef ProductConfig<false, 256, 128, 128, 64, 2, 3> Fp16Config;  // 32-deep stages, 3 x 48 KiB of LDS
+typedef ProductConfig<true, 256, 128, 128, 64, 1, 4> Bf16Config;   // 16-deep stages, 4 x 36 KiB of LDS
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -61,12 +61,12 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   pl.Kp = round_up(K, kDepthPad);
   pl.tiles_m = (int)((M + Fp16Config::BM - 1) / Fp16Config::BM);
   pl.tiles_n = (int)((N + Fp16Config::BN - 1) / Fp16Config::BN);
-  pl.k_tiles = (int)(pl.Kp / Fp16Config::BK);
+  pl.k_tiles = (int)(pl.Kp / (mode == ECGEMM_MODE_BF16_FULL ? Bf16Config::BK : Fp16Config::BK));
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   int splits = 1;
   if (tiles < 192) {
     splits = (int)((512 + tiles - 1) / tiles);
-    const int max_by_depth = pl.k_tiles / 16;  // at least 16 k tiles (512 k) per block
+    const int max_by_depth = (int)(pl.Kp / 512);  // at least 512 of depth per block
     if (splits > max_by_depth) splits = max_by_depth;
     if (splits > 64) splits = 64;
     if (splits < 1) splits = 1;

@@ -26,6 +26,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "split_kernels.hpp"
 
 namespace ecgemm {
@@ -63,22 +65,30 @@ struct Mfma<true> {
   }
 };
 
-template <bool BF16, int BM_, int BN_, int WM_, int WN_>
+template <bool BF16, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_>
 struct ProductConfig {
   static constexpr bool kBf16 = BF16;
-  static constexpr int NP = BF16 ? 3 : 2;
+  static constexpr int NP = BF16 ? 3 : 2;                         // parts per value
+  static constexpr int PRODUCTS = BF16 ? 6 : 3;                   // matrix products kept
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-  static constexpr int BK = 32, K_STEPS = BK / 16;
+  static constexpr int K_STEPS = K_STEPS_, BK = 16 * K_STEPS;     // 16-deep MFMA steps per LDS stage
+  static constexpr int STAGES = STAGES_;                          // LDS ring: tile t lives in buffer t % STAGES
   static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN, WAVES = WAVES_M * WAVES_N;
   static constexpr int THREADS = WAVES * 64;
   static constexpr int TM = WM / 32, TN = WN / 32;
-  static constexpr int ROW_CHUNKS = K_STEPS * NP;                 // 1 KiB chunks per 32 rows per k tile
+  static constexpr int ROW_CHUNKS = K_STEPS * NP;                 // 1 KiB chunks per 32 rows per stage
   static constexpr int A_CHUNKS = (BM / 32) * ROW_CHUNKS, B_CHUNKS = (BN / 32) * ROW_CHUNKS;
   static constexpr int STAGE_BYTES = (A_CHUNKS + B_CHUNKS) * 1024;
-  static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static constexpr int LDS_BYTES = STAGES * STAGE_BYTES;
+  static constexpr int LOADS = (A_CHUNKS + B_CHUNKS) / WAVES;     // global_load_lds instructions per wave per stage
+  static constexpr int FRAG_READS = (TM + TN) * NP;               // ds_read_b128 per wave per k step
+  static constexpr int MFMAS = TM * TN * PRODUCTS;                // matrix instructions per wave per k step
+  static_assert(K_STEPS == 1 || K_STEPS == 2, "one or two k steps per stage");
+  static_assert(STAGES >= 2 && (STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shapes");
   static_assert(kRowPad % BM == 0 && kRowPad % BN == 0, "padded operands must hold whole tiles");
+  static_assert(A_CHUNKS % WAVES == 0 && B_CHUNKS % WAVES == 0, "chunks per wave");
 };
 
 // Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one
@@ -92,9 +102,14 @@ __device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks) {
   return start + local;
 }
 
+template <int N>
+__device__ __forceinline__ void wait_loads_and_lds() {  // at most N global loads of this wave still in flight
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
+}
+
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductParams p) {
-  constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN;
+  constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::STAGES;
   typedef typename Mfma<Cfg::kBf16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
@@ -121,9 +136,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   // ---- global -> LDS: wave w moves the 1 KiB chunks w, w + WAVES, ... of a stage; A_CHUNKS is a
   // multiple of WAVES, so whether load i fetches from A or from B is known at compile time.  Source
   // addresses are wave-uniform (scalar registers) plus 16 bytes per lane.
-  constexpr int kLoads = (Cfg::A_CHUNKS + Cfg::B_CHUNKS) / Cfg::WAVES, kALoads = Cfg::A_CHUNKS / Cfg::WAVES;
-  static_assert(Cfg::A_CHUNKS % Cfg::WAVES == 0 && Cfg::B_CHUNKS % Cfg::WAVES == 0, "chunks per wave");
+  constexpr int kLoads = Cfg::LOADS, kALoads = Cfg::A_CHUNKS / Cfg::WAVES;
   const unsigned lane_bytes = lane * 16;
+  unsigned k_off = 0;  // bytes from the first tile of this block to the next tile to request
   const char* src[kLoads];
 #pragma unroll
   for (int i = 0; i < kLoads; ++i) {
@@ -133,14 +148,17 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
     src[i] = (from_a ? p.a_packed : p.b_packed) + (first_row_block + c / Cfg::ROW_CHUNKS) * p.row_block_bytes +
              (int64_t)kt_begin * (Cfg::ROW_CHUNKS * 1024) + (c % Cfg::ROW_CHUNKS) * 1024;
   }
-  auto issue_stage = [&](int buf) {  // fetches the next tile not yet requested, then moves on by one tile
+  auto issue_stage = [&](int buf) {  // requests the next tile not yet requested, then moves on by one tile
     char* stage = lds + buf * Cfg::STAGE_BYTES + wave * 1024;
+    // one 32-bit vector offset per tile; kept opaque inside this block so that every address folds to
+    // "scalar base + vector offset" and the scalar bases never change
+    unsigned voff = lane_bytes + k_off;
+    asm volatile("" : "+v"(voff));
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + lane_bytes),
+    for (int i = 0; i < kLoads; ++i)
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + voff),
                                        (void __attribute__((address_space(3)))*)(stage + i * Cfg::WAVES * 1024), 16, 0, 0);
-      src[i] += Cfg::ROW_CHUNKS * 1024;
-    }
+    k_off += Cfg::ROW_CHUNKS * 1024;
   };
 
   // ---- LDS -> registers
@@ -191,29 +209,122 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 #undef ECGEMM_PRODUCT
   };
 
-  // ---- main loop.  Tile kt lives in buffer kt & 1.  The barrier sits between the two k steps of a
-  // tile: by then every wave holds the last fragments of the current buffer in registers, so the buffer
-  // can be refilled (tile kt + 2) while the second k step computes, and the first fragments of tile
-  // kt + 1 are fetched under those same instructions.
+  // Asks the scheduler to thread the memory instructions of a k step between its matrix instructions
+  // (one matrix instruction occupies the pipe for 8 passes; anything issued meanwhile is free):
+  // `vmem` LDS-DMA loads and `ds` fragment reads, one of each per matrix instruction, then the rest.
+  auto interleave = [&](auto vmem_c, auto ds_c) {
+    constexpr int vmem = decltype(vmem_c)::value, ds = decltype(ds_c)::value;
+    constexpr int slots = vmem > ds ? vmem : ds;
+    static_assert(slots <= Cfg::MFMAS, "more memory instructions than matrix instructions");
+#pragma unroll
+    for (int i = 0; i < slots; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (i < vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+      if (i < ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, Cfg::MFMAS - slots, 0);
+  };
+  typedef std::integral_constant<int, 0> none_t;
+  typedef std::integral_constant<int, Cfg::LOADS> loads_t;
+  typedef std::integral_constant<int, Cfg::FRAG_READS> reads_t;
+
+  // Matrix instructions have no memory side effects, so the compiler would move the barrier across them;
+  // the fences pin it.  The wait lets the newest STAGES - 2 tiles stay in flight (or none, near the end).
+  auto stage_barrier = [&](auto pending_c) {
+    __builtin_amdgcn_sched_barrier(0);
+    wait_loads_and_lds<decltype(pending_c)::value>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  typedef std::integral_constant<int, (S - 2) * Cfg::LOADS> steady_t;
+
+  // ---- main loop.  Tile t lives in buffer t % STAGES; tiles t + 1 .. t + STAGES - 1 are in flight while
+  // tile t is multiplied.  The barrier of iteration t comes when every wave holds the last fragments of
+  // buffer t % STAGES in registers: the buffer is then refilled with tile t + STAGES, and the first
+  // fragments of tile t + 1 are fetched under the matrix instructions that follow.
   if (kt_count > 0) {
-    issue_stage(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt_count > 1) issue_stage(1);
+    const int prefetched = min(S, kt_count);
+    for (int s = 0; s < prefetched; ++s) issue_stage(s);
+    if (kt_count >= S) wait_loads_and_lds<(S - 1) * Cfg::LOADS>(); else wait_loads_and_lds<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     read_frags(0, 0, 0);
-    for (int t = 0; t < kt_count; ++t) {
-      const int buf = t & 1;
+    int buf = 0, next = (S > 1 && kt_count > 1) ? 1 : 0;
+    auto advance = [&]() {
+      buf = next;
+      next = (next + 1 == S) ? 0 : next + 1;
+    };
+    const int steady = kt_count - S;  // iterations that still have a tile to request
+    if constexpr (Cfg::K_STEPS == 2) {
+      int t = 0;
+      for (; t < steady; ++t) {
+        read_frags(1, buf, 1);
+        multiply(0);
+        interleave(none_t{}, reads_t{});
+        stage_barrier(steady_t{});
+        issue_stage(buf);
+        read_frags(0, next, 0);
+        multiply(1);
+        interleave(loads_t{}, reads_t{});
+        advance();
+      }
+      for (; t < kt_count - 1; ++t) {
+        read_frags(1, buf, 1);
+        multiply(0);
+        interleave(none_t{}, reads_t{});
+        stage_barrier(none_t{});
+        read_frags(0, next, 0);
+        multiply(1);
+        interleave(none_t{}, reads_t{});
+        advance();
+      }
       read_frags(1, buf, 1);
       multiply(0);
-      // matrix instructions have no memory side effects, so without the fences the compiler hoists the
-      // barrier (and with it the wait for the fragment reads just issued) above them
-      __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-      if (t + 2 < kt_count) issue_stage(buf);
-      if (t + 1 < kt_count) read_frags(0, buf ^ 1, 0);
       multiply(1);
+    } else {
+      // One k step per stage: tile t is multiplied from fragment set t & 1 while set (t + 1) & 1 is filled.
+      // Register arrays must be indexed statically, so the loops advance two tiles at a time and an odd
+      // leftover step is followed by a register copy that puts the live fragments back into set 0.
+      auto step = [&](auto set_c, auto issue_c, auto pending_c) {
+        constexpr int set = decltype(set_c)::value;
+        stage_barrier(pending_c);
+        if constexpr (decltype(issue_c)::value != 0) issue_stage(buf);
+        read_frags(set ^ 1, next, 0);
+        multiply(set);
+        interleave(issue_c, reads_t{});
+        advance();
+      };
+      auto odd_step = [&](auto issue_c, auto pending_c) {
+        step(std::integral_constant<int, 0>{}, issue_c, pending_c);
+#pragma unroll
+        for (int q = 0; q < NP; ++q) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i) fa[0][i][q] = fa[1][i][q];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) fb[0][j][q] = fb[1][j][q];
+        }
+      };
+      typedef std::integral_constant<int, 0> set0_t;
+      typedef std::integral_constant<int, 1> set1_t;
+      int t = 0;
+      if (steady > 0 && (steady & 1)) {
+        odd_step(loads_t{}, steady_t{});
+        t = 1;
+      }
+      for (; t < steady; t += 2) {
+        step(set0_t{}, loads_t{}, steady_t{});
+        step(set1_t{}, loads_t{}, steady_t{});
+      }
+      if ((kt_count - 1 - t) & 1) {
+        odd_step(none_t{}, none_t{});
+        ++t;
+      }
+      for (; t < kt_count - 1; t += 2) {
+        step(set0_t{}, none_t{}, none_t{});
+        step(set1_t{}, none_t{}, none_t{});
+      }
+      multiply(0);
     }
   }
 
