@@ -30,7 +30,11 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 
 # HBM bytes per product-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
 # workload; None where no counter run has been made for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # FETCH_SIZE 1.719e7 KiB x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE 1.0486e6 KiB x 1.0
+    "c3_16384_fp16_exprand15": 3.63e10,      # profiles/product_kernel_fp16_16384cubed.md
+    "c4_8192_bf16_widerange": 7.01e9,        # profiles/product_kernel_bf16_8192cubed.md
+}
 
 WORKLOADS = {
     # name: (M, N, K, transA, transB, mode, alpha, beta, distribution, oracle rows)

@@ -11,7 +11,8 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libecgemm.so")
+# ECGEMM_LIB points the binding at another build of the same library (used to time tile-shape variants)
+LIB_PATH = os.environ.get("ECGEMM_LIB") or os.path.join(HERE, "libecgemm.so")
 
 OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1

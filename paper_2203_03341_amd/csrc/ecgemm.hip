@@ -33,8 +33,22 @@ struct ecgemm_context {
 
 namespace {
 
-typedef ProductConfig<false, 256, 128, 128, 64, 2, 3> Fp16Config;  // 32-deep stages, 3 x 48 KiB of LDS
-typedef ProductConfig<true, 256, 128, 128, 64, 1, 4> Bf16Config;   // 16-deep stages, 4 x 36 KiB of LDS
+// Tile shapes.  The macros exist so that other shapes can be built and timed side by side; the defaults are
+// the ones every figure in this repository was measured with.
+#ifndef ECGEMM_FP16_KSTEPS
+#define ECGEMM_FP16_KSTEPS 2
+#endif
+#ifndef ECGEMM_FP16_STAGES
+#define ECGEMM_FP16_STAGES 3
+#endif
+#ifndef ECGEMM_BF16_KSTEPS
+#define ECGEMM_BF16_KSTEPS 1
+#endif
+#ifndef ECGEMM_BF16_STAGES
+#define ECGEMM_BF16_STAGES 4
+#endif
+typedef ProductConfig<false, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> Fp16Config;  // 3 x 48 KiB of LDS
+typedef ProductConfig<true, 256, 128, 128, 64, ECGEMM_BF16_KSTEPS, ECGEMM_BF16_STAGES> Bf16Config;   // 4 x 36 KiB of LDS
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }

@@ -122,7 +122,10 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   int pid = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int split = pid / tiles;
   pid -= split * tiles;
-  constexpr int kGroupM = 4;
+#ifndef ECGEMM_GROUP_M
+#define ECGEMM_GROUP_M 4
+#endif
+  constexpr int kGroupM = ECGEMM_GROUP_M;
   const int group_size = kGroupM * p.tiles_n;
   const int group = pid / group_size;
   const int first_m = group * kGroupM;

@@ -271,3 +271,41 @@ def test_fp16_mode_fails_outside_its_range_like_the_paper_says():
     got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "fp16")[:M, :N]
     assert gemm.relative_residual(c64, got) > 0.1
     _check("N", "N", M, N, K, 1.0, 0.0, "bf16", ((-100, -35), (-15, 14)), seed=0)
+
+
+# ----- the baseline's own sizes, in the launch configuration bench.py times; oracle on seeded sample rows of C
+
+def _full_size(M, N, K, transA, transB, alpha, beta, mode, dist, nrows):
+    rows = si.sample_indices(M, nrows, seed=11)
+    return _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=0, rows=rows)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_config2_4096_cubed(mode):
+    _full_size(4096, 4096, 4096, "N", "N", 1.0, 0.0, mode, "urand", 256)
+
+
+def test_config3_16384_cubed_fp16_limited_exponent():
+    _full_size(16384, 16384, 16384, "N", "N", 1.0, 0.0, "fp16", ((-15, 15), (-15, 15)), 64)
+
+
+def test_config4_8192_cubed_bf16_wide_exponent():
+    # the literal config (both operands exp_rand(-100, 100)) overflows FP32 everywhere; graded stand-in as in bench.py
+    _full_size(8192, 8192, 8192, "N", "N", 1.5, 0.5, "bf16", ((-100, 100), (-15, 14)), 128)
+
+
+def test_config4_literal_is_non_finite_for_everyone():
+    """Both operands exp_rand(-100, 100): products reach 2^200, so the FP32 oracle and the GPU both overflow."""
+    M = N = 256
+    K = 8192
+    A, B = _inputs(M, N, K, "N", "N", ((-100, 100), (-100, 100)), 0)
+    c32 = gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.0, A, B)
+    got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "bf16")[:M, :N]
+    assert np.mean(~np.isfinite(c32)) > 0.99 and np.mean(~np.isfinite(got)) > 0.99
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_config5_full_shapes(mode):
+    _full_size(16384, 16384, 256, "N", "N", 1.0, 0.0, mode, "urand", 256)
+    _full_size(1024, 1024, 65536, "N", "N", 1.0, 0.0, mode, "urand", 64)
+    _full_size(4095, 3001, 5003, "T", "N", 1.0, 0.0, mode, "urand", 256)
