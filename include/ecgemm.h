@@ -38,7 +38,19 @@ typedef enum {
      * gfx950 has no TF32 matrix instruction, so each value is split exactly into three BF16 terms and the
      * six products of relative size >= 2^-16 are kept (same argument as section "Removing negligible
      * error correction"). */
-    ECGEMM_MODE_BF16_FULL = 1
+    ECGEMM_MODE_BF16_FULL = 1,
+    /* The remaining modes are the methods the paper compares against, run through the same kernels so that its
+     * error curves can be redrawn on this hardware.  They are not meant for production use. */
+    /* Markidis' method: unscaled residual dv16 = toFP16(v - v16) (Eqs. corr-1 .. corr-4), all four products
+     * dA dB + dA B + A dB + A B summed in one accumulator (Eq. corr-5, listing "Markidis' error correction method"). */
+    ECGEMM_MODE_FP16_MARKIDIS = 2,
+    /* The method's three products and separate correction accumulator, but on Markidis' unscaled residual: isolates
+     * what the 2^11 scaling of section "Reducing the underflow ..." buys. */
+    ECGEMM_MODE_FP16_UNSCALED = 3,
+    /* toFP16(A) toFP16(B), one product, no correction (listing "A simple matrix-matrix multiplication ..."). */
+    ECGEMM_MODE_FP16_PLAIN = 4,
+    /* toBF16(A) toBF16(B), one product, no correction. */
+    ECGEMM_MODE_BF16_PLAIN = 5
 } ecgemm_mode_t;
 
 typedef enum {
@@ -94,6 +106,7 @@ ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void *device_buffer
  *   3. epilogue: c = main + correction * 2^-11 (FP16 mode) or main + correction (BF16 mode), then
  *      C <- alpha * c + beta * C in FP32.
  *
+ * Sizes: a packed row block (K / 16 * parts KiB) must stay below 4 GiB, i.e. K < 2^25 for two parts, 2^24.4 for three.
  * M == 0 or N == 0: nothing is done.  K == 0 or alpha == 0: C <- beta * C (C <- 0 when beta == 0).
  * Inf / NaN inputs give Inf / NaN outputs but not necessarily in IEEE-exact positions.
  */
@@ -108,12 +121,24 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
  * ecgemm_split_size(rows, depth, mode) bytes, laid out as
  *     packed[row_block][k_step][part][lane][8]   (16-bit elements)
  * with row_block = r / 32, k_step = k / 16, lane = ((k % 16) / 8) * 32 + r % 32, element k % 8;
- * part 0 is the high part.  Rows are padded to a multiple of 256 and depth to a multiple of 32, with
- * zeros.  src: device, FP32, column-major with leading dimension ld; op == N means X(r, k) =
+ * part 0 is the high part; there are 2 parts in the FP16 pair modes, 3 in ECGEMM_MODE_BF16_FULL, 1 in the plain
+ * modes.  Rows are padded to a multiple of 256 and depth to a multiple of 32, with zeros.  src: device, FP32, column-major with leading dimension ld; op == N means X(r, k) =
  * src[r + k * ld] (ld >= rows), op == T means X(r, k) = src[k + r * ld] (ld >= depth).
  */
 ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth,
                              const float *src, int64_t ld, ecgemm_mode_t mode, void *packed);
+
+/*
+ * Steps 2 and 3 alone (Eq. corr-5-1024-reduce and the merge at the end of the paper's listing), for callers that keep
+ * an operand split across many products:  C <- alpha * op(A) op(B) + beta * C  with op(A) (M x K) and op(B)^T (N x K)
+ * given as the outputs of ecgemm_split(handle, ..., rows = M or N, depth = K, ..., mode, packed) for the SAME mode.
+ * For op(B) that means: ecgemm_split(op = T if B is stored K x N (transB == N), op = N if stored N x K).  packedA,
+ * packedB: device, read only.  C, ldc, alpha, beta as in ecgemm_sgemm.  Uses the workspace only for the partial sums
+ * of a divided K.  The result is bitwise what ecgemm_sgemm returns for the same operands.
+ */
+ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
+                               const void *packedA, const void *packedB, float beta, float *C, int64_t ldc,
+                               ecgemm_mode_t mode);
 
 /* Bytes ecgemm_split writes for a rows x depth operand.  `bytes` is a host pointer. */
 ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mode, size_t *bytes);

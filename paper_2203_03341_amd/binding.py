@@ -16,10 +16,11 @@ LIB_PATH = os.environ.get("ECGEMM_LIB") or os.path.join(HERE, "libecgemm.so")
 
 OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
+MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN = 2, 3, 4, 5   # comparison methods
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_split", "ecgemm_split_size", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -36,6 +37,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
+    lib.ecgemm_product.argtypes = [vp, i64, i64, i64, f32, vp, vp, f32, vp, i64, ctypes.c_int]
     lib.ecgemm_split.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_split_size.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
     lib.ecgemm_set_timing.argtypes = [vp, ctypes.c_int]
@@ -110,6 +112,9 @@ class Handle:
               beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
+
+    def product(self, M: int, N: int, K: int, alpha: float, packedA, packedB, beta: float, C, ldc: int, mode: int):
+        self._check(_lib.ecgemm_product(self._h, M, N, K, alpha, _ptr(packedA), _ptr(packedB), beta, _ptr(C), ldc, mode))
 
     def split(self, op: int, rows: int, depth: int, src, ld: int, mode: int, packed):
         self._check(_lib.ecgemm_split(self._h, op, rows, depth, _ptr(src), ld, mode, _ptr(packed)))

@@ -47,13 +47,27 @@ namespace {
 #ifndef ECGEMM_BF16_STAGES
 #define ECGEMM_BF16_STAGES 4
 #endif
-typedef ProductConfig<false, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> Fp16Config;  // 3 x 48 KiB of LDS
-typedef ProductConfig<true, 256, 128, 128, 64, ECGEMM_BF16_KSTEPS, ECGEMM_BF16_STAGES> Bf16Config;   // 4 x 36 KiB of LDS
+typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> Fp16Config;  // 3 x 48 KiB of LDS
+typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, ECGEMM_BF16_KSTEPS, ECGEMM_BF16_STAGES> Bf16Config;   // 4 x 36 KiB of LDS
+// comparison methods: same tile, same pipeline
+typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> MarkidisConfig;
+typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> UnscaledConfig;
+typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3> PlainFp16Config;
+typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3> PlainBf16Config;
+constexpr int kBM = 256, kBN = 128;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
-inline int parts_of(ecgemm_mode_t mode) { return mode == ECGEMM_MODE_BF16_FULL ? 3 : 2; }
-inline bool valid_mode(int mode) { return mode == ECGEMM_MODE_FP16_SPLIT || mode == ECGEMM_MODE_BF16_FULL; }
+// the ecgemm_mode_t values are the ProductMethod values
+inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
+inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_BF16_PLAIN; }
+inline int stage_depth_of(ecgemm_mode_t mode) { return mode == ECGEMM_MODE_BF16_FULL ? Bf16Config::BK : Fp16Config::BK; }
+static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
+              (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
+              (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
+              (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain,
+              "mode numbering");
+static_assert(PlainFp16Config::BK == Fp16Config::BK && MarkidisConfig::BK == Fp16Config::BK, "stage depths");
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
 
 size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
@@ -73,9 +87,9 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   pl.Mp = round_up(M, kRowPad);
   pl.Np = round_up(N, kRowPad);
   pl.Kp = round_up(K, kDepthPad);
-  pl.tiles_m = (int)((M + Fp16Config::BM - 1) / Fp16Config::BM);
-  pl.tiles_n = (int)((N + Fp16Config::BN - 1) / Fp16Config::BN);
-  pl.k_tiles = (int)(pl.Kp / (mode == ECGEMM_MODE_BF16_FULL ? Bf16Config::BK : Fp16Config::BK));
+  pl.tiles_m = (int)((M + kBM - 1) / kBM);
+  pl.tiles_n = (int)((N + kBN - 1) / kBN);
+  pl.k_tiles = (int)(pl.Kp / stage_depth_of(mode));
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   int splits = 1;
   if (tiles < 192) {
@@ -116,21 +130,100 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
   if (Rp / 64 > 65535) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 4193280 rows");
   const dim3 grid((unsigned)(Kp / 32), (unsigned)(Rp / 64)), block(256);
   unsigned short* out = static_cast<unsigned short*>(packed);
-  const bool bf16 = mode == ECGEMM_MODE_BF16_FULL;
-  if (op == ECGEMM_OP_T) {
-    const bool vec = (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
-    if (bf16) {
-      if (vec) hipLaunchKernelGGL((split_k_contiguous<true, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
-      else hipLaunchKernelGGL((split_k_contiguous<true, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
-    } else {
-      if (vec) hipLaunchKernelGGL((split_k_contiguous<false, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
-      else hipLaunchKernelGGL((split_k_contiguous<false, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
-    }
-  } else {
-    if (bf16) hipLaunchKernelGGL((split_r_contiguous<true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
-    else hipLaunchKernelGGL((split_r_contiguous<false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);
+  const bool k_contiguous = op == ECGEMM_OP_T;
+  const bool vec = k_contiguous && (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
+#define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                          \
+  do {                                                                                                                     \
+    if (!k_contiguous)                                                                                                     \
+      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);       \
+    else if (vec)                                                                                                          \
+      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out); \
+    else                                                                                                                   \
+      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);\
+  } while (0)
+  switch (split_kind_of((int)mode)) {
+    case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;
+    case kSplitBf16x3: ECGEMM_LAUNCH_SPLIT(kSplitBf16x3); break;
+    case kSplitFp16Unscaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Unscaled); break;
+    case kSplitFp16Plain: ECGEMM_LAUNCH_SPLIT(kSplitFp16Plain); break;
+    default: ECGEMM_LAUNCH_SPLIT(kSplitBf16Plain); break;
+  }
+#undef ECGEMM_LAUNCH_SPLIT
+  ECGEMM_HIP(h, hipGetLastError());
+  return ECGEMM_OK;
+}
+
+// Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
+ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
+                               const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials) {
+  ProductParams pp;
+  pp.a_packed = static_cast<const char*>(a_packed);
+  pp.b_packed = static_cast<const char*>(b_packed);
+  pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
+  pp.k_tiles = pl.k_tiles;
+  pp.k_splits = pl.k_splits;
+  pp.tiles_m = pl.tiles_m;
+  pp.tiles_n = pl.tiles_n;
+  pp.M = M;
+  pp.N = N;
+  pp.ldc = ldc;
+  pp.alpha = alpha;
+  pp.beta = beta;
+  pp.C = C;
+  pp.partials = partials;
+  pp.Mp = pl.Mp;
+  pp.Np = pl.Np;
+  const dim3 grid((unsigned)((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits));
+  switch (mode) {
+    case ECGEMM_MODE_FP16_SPLIT: hipLaunchKernelGGL(product_kernel<Fp16Config>, grid, dim3(Fp16Config::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_BF16_FULL: hipLaunchKernelGGL(product_kernel<Bf16Config>, grid, dim3(Bf16Config::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_FP16_MARKIDIS: hipLaunchKernelGGL(product_kernel<MarkidisConfig>, grid, dim3(MarkidisConfig::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_FP16_UNSCALED: hipLaunchKernelGGL(product_kernel<UnscaledConfig>, grid, dim3(UnscaledConfig::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_FP16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainFp16Config>, grid, dim3(PlainFp16Config::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_BF16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainBf16Config>, grid, dim3(PlainBf16Config::THREADS), 0, h->stream, pp); break;
   }
   ECGEMM_HIP(h, hipGetLastError());
+  if (pl.k_splits > 1) {
+    const dim3 rgrid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
+    hipLaunchKernelGGL(reduce_partials_kernel, rgrid, dim3(256), 0, h->stream, partials, pl.k_splits, pl.Mp, pl.Np, M, N, alpha,
+                       beta, C, ldc);
+    ECGEMM_HIP(h, hipGetLastError());
+  }
+  return ECGEMM_OK;
+}
+
+// Device memory for this call: the caller's workspace if one is set (never allocating), else the handle's own,
+// grown on demand.
+ecgemm_status_t acquire_workspace(ecgemm_handle_t h, size_t bytes, char** out) {
+  *out = nullptr;
+  if (bytes == 0) return ECGEMM_OK;
+  if (h->user_workspace) {
+    if (h->user_bytes < bytes) return fail(h, ECGEMM_ERR_ALLOC, "caller workspace too small");
+    *out = static_cast<char*>(h->user_workspace);
+    return ECGEMM_OK;
+  }
+  if (h->own_bytes < bytes) {
+    // the old buffer may still be in use by earlier calls on the stream
+    ECGEMM_HIP(h, hipStreamSynchronize(h->stream));
+    if (h->own_workspace) ECGEMM_HIP(h, hipFree(h->own_workspace));
+    h->own_workspace = nullptr;
+    h->own_bytes = 0;
+    if (hipMalloc(&h->own_workspace, bytes) != hipSuccess) {
+      h->own_workspace = nullptr;
+      (void)hipGetLastError();
+      return fail(h, ECGEMM_ERR_ALLOC, "hipMalloc of the workspace failed");
+    }
+    h->own_bytes = bytes;
+  }
+  *out = static_cast<char*>(h->own_workspace);
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t check_sizes(ecgemm_handle_t h, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
+  // tile indices are 32-bit and the byte offset along K inside a row block is a 32-bit vector offset
+  if (M > (int64_t)1 << 36 || N > (int64_t)1 << 36) return fail(h, ECGEMM_ERR_INVALID_ARG, "M or N too large");
+  if ((round_up(K, kDepthPad) / 16) * parts_of(mode) * 1024 >= ((int64_t)1 << 32))
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "K too large: a packed row block must stay below 4 GiB");
   return ECGEMM_OK;
 }
 
@@ -275,8 +368,6 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
   if (M < 0 || N < 0 || K < 0) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: negative size");
   if (M == 0 || N == 0) return ECGEMM_OK;
   if (!C || ldc < M) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: C is null or ldc < M");
-  if (M > 0x7fffffffLL * 32 || N > 0x7fffffffLL * 32 || K > 0x7fffffffLL)
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: size too large");
 
   const dim3 block256(256);
   if (K == 0 || alpha == 0.0f) {
@@ -289,30 +380,14 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
   if (lda < (transA == ECGEMM_OP_N ? M : K)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: lda too small");
   if (ldb < (transB == ECGEMM_OP_N ? K : N)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: ldb too small");
 
+  ecgemm_status_t st = check_sizes(h, M, N, K, mode);
+  if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode);
   if ((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits > 0x7fffffffLL)
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: too many tiles");
-
   char* ws = nullptr;
-  if (h->user_workspace) {
-    if (h->user_bytes < pl.total_bytes) return fail(h, ECGEMM_ERR_ALLOC, "ecgemm_sgemm: caller workspace too small");
-    ws = static_cast<char*>(h->user_workspace);
-  } else {
-    if (h->own_bytes < pl.total_bytes) {
-      // the old buffer may still be in use by earlier calls on the stream
-      ECGEMM_HIP(h, hipStreamSynchronize(h->stream));
-      if (h->own_workspace) ECGEMM_HIP(h, hipFree(h->own_workspace));
-      h->own_workspace = nullptr;
-      h->own_bytes = 0;
-      if (hipMalloc(&h->own_workspace, pl.total_bytes) != hipSuccess) {
-        h->own_workspace = nullptr;
-        (void)hipGetLastError();
-        return fail(h, ECGEMM_ERR_ALLOC, "ecgemm_sgemm: hipMalloc of the workspace failed");
-      }
-      h->own_bytes = pl.total_bytes;
-    }
-    ws = static_cast<char*>(h->own_workspace);
-  }
+  st = acquire_workspace(h, pl.total_bytes, &ws);
+  if (st != ECGEMM_OK) return st;
   char* a_packed = ws;
   char* b_packed = ws + pl.a_bytes;
   float* partials = pl.k_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
@@ -328,47 +403,48 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
 
   // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
   // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
-  ecgemm_status_t st = launch_split(h, transA, M, K, A, lda, mode, a_packed);
+  st = launch_split(h, transA, M, K, A, lda, mode, a_packed);
   if (st != ECGEMM_OK) return st;
   st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed);
   if (st != ECGEMM_OK) return st;
   if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
 
   // steps 2 and 3
-  ProductParams pp;
-  pp.a_packed = a_packed;
-  pp.b_packed = b_packed;
-  pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
-  pp.k_tiles = pl.k_tiles;
-  pp.k_splits = pl.k_splits;
-  pp.tiles_m = pl.tiles_m;
-  pp.tiles_n = pl.tiles_n;
-  pp.M = M;
-  pp.N = N;
-  pp.ldc = ldc;
-  pp.alpha = alpha;
-  pp.beta = beta;
-  pp.C = C;
-  pp.partials = partials;
-  pp.Mp = pl.Mp;
-  pp.Np = pl.Np;
-  const dim3 grid((unsigned)((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits));
-  if (mode == ECGEMM_MODE_BF16_FULL)
-    hipLaunchKernelGGL(product_kernel<Bf16Config>, grid, dim3(Bf16Config::THREADS), 0, h->stream, pp);
-  else
-    hipLaunchKernelGGL(product_kernel<Fp16Config>, grid, dim3(Fp16Config::THREADS), 0, h->stream, pp);
-  ECGEMM_HIP(h, hipGetLastError());
-  if (pl.k_splits > 1) {
-    const dim3 rgrid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
-    hipLaunchKernelGGL(reduce_partials_kernel, rgrid, block256, 0, h->stream, partials, pl.k_splits, pl.Mp, pl.Np, M, N,
-                       alpha, beta, C, ldc);
-    ECGEMM_HIP(h, hipGetLastError());
-  }
+  st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials);
+  if (st != ECGEMM_OK) return st;
   if (h->timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
     h->timed.push_back(tc);
   }
   return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
+                               const void* packedA, const void* packedB, float beta, float* C, int64_t ldc,
+                               ecgemm_mode_t mode) {
+  ecgemm_handle_t h = handle;
+  if (!h) return ECGEMM_ERR_INVALID_ARG;
+  if (!valid_mode(mode)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: bad mode");
+  if (M < 0 || N < 0 || K < 0) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: negative size");
+  if (M == 0 || N == 0) return ECGEMM_OK;
+  if (!C || ldc < M) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: C is null or ldc < M");
+  if (K == 0 || alpha == 0.0f) {
+    const dim3 grid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
+    hipLaunchKernelGGL(scale_c_kernel, grid, dim3(256), 0, h->stream, M, N, beta, C, ldc);
+    ECGEMM_HIP(h, hipGetLastError());
+    return ECGEMM_OK;
+  }
+  if (!packedA || !packedB || ((uintptr_t)packedA % 16) != 0 || ((uintptr_t)packedB % 16) != 0)
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: packed operand is null or not 16-byte aligned");
+  ecgemm_status_t st = check_sizes(h, M, N, K, mode);
+  if (st != ECGEMM_OK) return st;
+  const Plan pl = make_plan(M, N, K, mode);
+  if ((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits > 0x7fffffffLL)
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: too many tiles");
+  char* ws = nullptr;
+  st = acquire_workspace(h, pl.partial_bytes, &ws);
+  if (st != ECGEMM_OK) return st;
+  return launch_product(h, pl, M, N, alpha, packedA, packedB, beta, C, ldc, mode, reinterpret_cast<float*>(ws));
 }
 
 }  // extern "C"

@@ -19,6 +19,10 @@
 // Operands are stored in fragment order (see split_kernels.hpp), so both hops are linear
 // 1 KiB-per-wave copies: coalesced in global memory and bank-conflict free in LDS by construction.
 //
+// Besides the two modes of the method the kernel can run the paper's comparison methods (see ProductMethod):
+// Markidis' four products into one accumulator, the three products with an unscaled residual, and plain
+// one-product FP16 / BF16 GEMMs.  They share every line of the data path and differ only in the product list.
+//
 // The matrix instruction is used "transposed": the B-side fragment is its first operand and
 // the A-side fragment its second, so a lane owns one row index m of C and a wave's store
 // instruction covers 32 consecutive m: 128-byte runs of column-major C.
@@ -65,11 +69,33 @@ struct Mfma<true> {
   }
 };
 
-template <bool BF16, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_>
+// Which products are formed and where they are summed.
+enum ProductMethod {
+  kMethodFp16Split = 0,     // Eq. corr-5-1024-reduce: A16 B16 | dA16 B16 + A16 dB16 (scaled by 2^-11 at the end)
+  kMethodBf16Full = 1,      // a0 b0 | a0 b1 + a1 b0 + a1 b1 + a0 b2 + a2 b0
+  kMethodFp16Markidis = 2,  // Eq. corr-5 and listing "Markidis' error correction method": dA dB + dA B + A dB + A B, one accumulator
+  kMethodFp16Unscaled = 3,  // the method's three products and two accumulators on Markidis' unscaled residual
+  kMethodFp16Plain = 4,     // A16 B16 only (listing "A simple matrix-matrix multiplication ... on Tensor Cores")
+  kMethodBf16Plain = 5      // toBF16(A) toBF16(B) only
+};
+
+__host__ __device__ constexpr int split_kind_of(int method) {
+  return method == kMethodFp16Split ? kSplitFp16Scaled
+       : method == kMethodBf16Full ? kSplitBf16x3
+       : (method == kMethodFp16Markidis || method == kMethodFp16Unscaled) ? kSplitFp16Unscaled
+       : method == kMethodFp16Plain ? kSplitFp16Plain : kSplitBf16Plain;
+}
+__host__ __device__ constexpr int products_of(int method) {
+  return method == kMethodFp16Split || method == kMethodFp16Unscaled ? 3
+       : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : 1;
+}
+
+template <int METHOD, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_>
 struct ProductConfig {
-  static constexpr bool kBf16 = BF16;
-  static constexpr int NP = BF16 ? 3 : 2;                         // parts per value
-  static constexpr int PRODUCTS = BF16 ? 6 : 3;                   // matrix products kept
+  static constexpr int kMethod = METHOD;
+  static constexpr bool kBf16 = split_is_bf16(split_kind_of(METHOD));
+  static constexpr int NP = parts_of_split(split_kind_of(METHOD));  // parts per value
+  static constexpr int PRODUCTS = products_of(METHOD);              // matrix products formed
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
   static constexpr int K_STEPS = K_STEPS_, BK = 16 * K_STEPS;     // 16-deep MFMA steps per LDS stage
   static constexpr int STAGES = STAGES_;                          // LDS ring: tile t lives in buffer t % STAGES
@@ -198,16 +224,23 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 #define ECGEMM_PRODUCT(ACC, QB, QA)                                                    \
   _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
       ACC[i][j] = Mfma<Cfg::kBf16>::run(fb[set][j][QB], fa[set][i][QA], ACC[i][j]);
-    ECGEMM_PRODUCT(acc_main, 0, 0)
-    if constexpr (!Cfg::kBf16) {
-      ECGEMM_PRODUCT(acc_corr, 1, 0)
-      ECGEMM_PRODUCT(acc_corr, 0, 1)
+    if constexpr (Cfg::kMethod == kMethodFp16Markidis) {  // everything into one accumulator, smallest first
+      ECGEMM_PRODUCT(acc_main, 1, 1)
+      ECGEMM_PRODUCT(acc_main, 1, 0)
+      ECGEMM_PRODUCT(acc_main, 0, 1)
+      ECGEMM_PRODUCT(acc_main, 0, 0)
     } else {
-      ECGEMM_PRODUCT(acc_corr, 2, 0)
-      ECGEMM_PRODUCT(acc_corr, 0, 2)
-      ECGEMM_PRODUCT(acc_corr, 1, 1)
-      ECGEMM_PRODUCT(acc_corr, 1, 0)
-      ECGEMM_PRODUCT(acc_corr, 0, 1)
+      ECGEMM_PRODUCT(acc_main, 0, 0)
+      if constexpr (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Unscaled) {
+        ECGEMM_PRODUCT(acc_corr, 1, 0)
+        ECGEMM_PRODUCT(acc_corr, 0, 1)
+      } else if constexpr (Cfg::kMethod == kMethodBf16Full) {
+        ECGEMM_PRODUCT(acc_corr, 2, 0)
+        ECGEMM_PRODUCT(acc_corr, 0, 2)
+        ECGEMM_PRODUCT(acc_corr, 1, 1)
+        ECGEMM_PRODUCT(acc_corr, 1, 0)
+        ECGEMM_PRODUCT(acc_corr, 0, 1)
+      }
     }
 #undef ECGEMM_PRODUCT
   };
@@ -333,7 +366,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
-  const float corr_scale = Cfg::kBf16 ? 1.0f : 0x1p-11f;
+  const float corr_scale = Cfg::kMethod == kMethodFp16Split ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
   const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane >> 5);
   auto for_each_output = [&](auto&& store) {

@@ -31,52 +31,66 @@ __device__ __forceinline__ float saturate_finite(float v, float limit) {
   return (__builtin_fabsf(v) <= 3.402823466e+38f) ? __builtin_fminf(__builtin_fmaxf(v, -limit), limit) : v;
 }
 
-template <bool BF16>
-struct Splitter;
-
-template <>
-struct Splitter<false> {
-  static constexpr int kParts = 2;
-  __device__ static __forceinline__ void split(float v, unsigned short (&out)[2]) {
-    const _Float16 hi = (_Float16)saturate_finite(v, 65504.0f);
-    const float residual = (v - (float)hi) * 2048.0f;  // both operations exact
-    _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
-    if (__builtin_isinf((float)hi)) lo = (_Float16)0.0f;
-    out[0] = __builtin_bit_cast(unsigned short, hi);
-    out[1] = __builtin_bit_cast(unsigned short, lo);
-  }
+// What a value is split into.  The first two are the method; the others exist to reproduce the paper's
+// comparisons (Markidis' unscaled residual, and plain conversion with no residual at all).
+enum SplitKind {
+  kSplitFp16Scaled = 0,    // v16, (v - v16) * 2^11      Eqs. corr-elm-1, corr-elm-2-1024 ("halfhalf")
+  kSplitBf16x3 = 1,        // three exact BF16 terms
+  kSplitFp16Unscaled = 2,  // v16, v - v16               Eqs. corr-elm-1, corr-elm-2 ("Markidis' halfhalf")
+  kSplitFp16Plain = 3,     // v16 only
+  kSplitBf16Plain = 4      // toBF16(v) only
 };
 
-template <>
-struct Splitter<true> {
-  static constexpr int kParts = 3;
-  static constexpr float kMax = 3.3895313892515355e+38f;  // largest finite BF16
-  __device__ static __forceinline__ void split(float v, unsigned short (&out)[3]) {
-    const __bf16 b0 = (__bf16)saturate_finite(v, kMax);
-    const float r1 = v - (float)b0;
-    __bf16 b1 = (__bf16)saturate_finite(r1, kMax);
-    const float r2 = r1 - (float)b1;
-    __bf16 b2 = (__bf16)saturate_finite(r2, kMax);
-    if (__builtin_isinf((float)b0)) {
-      b1 = (__bf16)0.0f;
-      b2 = (__bf16)0.0f;
+__host__ __device__ constexpr int parts_of_split(int kind) {
+  return kind == kSplitBf16x3 ? 3 : (kind == kSplitFp16Plain || kind == kSplitBf16Plain) ? 1 : 2;
+}
+__host__ __device__ constexpr bool split_is_bf16(int kind) { return kind == kSplitBf16x3 || kind == kSplitBf16Plain; }
+
+constexpr float kBf16Max = 3.3895313892515355e+38f;  // largest finite BF16
+
+template <int KIND>
+struct Splitter {
+  static constexpr int kParts = parts_of_split(KIND);
+  __device__ static __forceinline__ void split(float v, unsigned short (&out)[kParts]) {
+    if constexpr (!split_is_bf16(KIND)) {
+      const _Float16 hi = (_Float16)saturate_finite(v, 65504.0f);
+      out[0] = __builtin_bit_cast(unsigned short, hi);
+      if constexpr (kParts == 2) {
+        float residual = v - (float)hi;                                  // exact
+        if constexpr (KIND == kSplitFp16Scaled) residual *= 2048.0f;     // exact
+        _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
+        if (__builtin_isinf((float)hi)) lo = (_Float16)0.0f;
+        out[1] = __builtin_bit_cast(unsigned short, lo);
+      }
+    } else {
+      const __bf16 b0 = (__bf16)saturate_finite(v, kBf16Max);
+      out[0] = __builtin_bit_cast(unsigned short, b0);
+      if constexpr (kParts == 3) {
+        const float r1 = v - (float)b0;
+        __bf16 b1 = (__bf16)saturate_finite(r1, kBf16Max);
+        const float r2 = r1 - (float)b1;
+        __bf16 b2 = (__bf16)saturate_finite(r2, kBf16Max);
+        if (__builtin_isinf((float)b0)) {
+          b1 = (__bf16)0.0f;
+          b2 = (__bf16)0.0f;
+        }
+        out[1] = __builtin_bit_cast(unsigned short, b1);
+        out[2] = __builtin_bit_cast(unsigned short, b2);
+      }
     }
-    out[0] = __builtin_bit_cast(unsigned short, b0);
-    out[1] = __builtin_bit_cast(unsigned short, b1);
-    out[2] = __builtin_bit_cast(unsigned short, b2);
   }
 };
 
 // Writes the eight consecutive-k values `v` of row r (global indices) to their place in `packed`.
-template <bool BF16>
+template <int KIND>
 __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ packed, int64_t k_steps_total,
                                                    int64_t r, int64_t k, const float (&v)[8]) {
-  constexpr int NP = Splitter<BF16>::kParts;
+  constexpr int NP = Splitter<KIND>::kParts;
   ushort8_t parts[NP];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     unsigned short s[NP];
-    Splitter<BF16>::split(v[e], s);
+    Splitter<KIND>::split(v[e], s);
 #pragma unroll
     for (int p = 0; p < NP; ++p) parts[p][e] = s[p];
   }
@@ -89,7 +103,7 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
 
 // Source with k contiguous: X(r, k) = src[k + r * ld].  One block: 64 rows x 32 k, 256 threads,
 // thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4).
-template <bool BF16, bool VEC>
+template <int KIND, bool VEC>
 __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
                                                           int64_t depth, int64_t k_steps_total,
                                                           unsigned short* __restrict__ packed) {
@@ -106,12 +120,12 @@ __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restric
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r * ld + k + e] : 0.0f;
   }
-  store_fragment_row<BF16>(packed, k_steps_total, r, k, v);
+  store_fragment_row<KIND>(packed, k_steps_total, r, k, v);
 }
 
 // Source with r contiguous: X(r, k) = src[r + k * ld].  One block: 64 rows x 32 k, transposed
 // through LDS so that both the global reads (along r) and the fragment writes are coalesced.
-template <bool BF16>
+template <int KIND>
 __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
                                                           int64_t depth, int64_t k_steps_total,
                                                           unsigned short* __restrict__ packed) {
@@ -134,7 +148,7 @@ __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restric
   float v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = tile[(kk + e) * kStride + rr];
-  store_fragment_row<BF16>(packed, k_steps_total, r0 + rr, k0 + kk, v);
+  store_fragment_row<KIND>(packed, k_steps_total, r0 + rr, k0 + kk, v);
 }
 
 }  // namespace ecgemm

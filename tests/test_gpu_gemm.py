@@ -25,7 +25,17 @@ RATIO = 1.25
 
 def _modes():
     import paper_2203_03341_amd as ec
-    return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL}
+    return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "markidis": ec.MODE_FP16_MARKIDIS,
+            "unscaled": ec.MODE_FP16_UNSCALED, "plain16": ec.MODE_FP16_PLAIN, "plainbf": ec.MODE_BF16_PLAIN}
+
+
+def _model(mode, opA, opB):
+    """Exact-accumulation model of a mode (FP64 sums of the same low-precision parts)."""
+    return {"fp16": lambda: model.gemm_fp16_mode(opA, opB), "bf16": lambda: model.gemm_bf16_mode(opA, opB),
+            "markidis": lambda: model.gemm_fp16_mode(opA, opB, products=4, scaled=False),
+            "unscaled": lambda: model.gemm_fp16_mode(opA, opB, products=3, scaled=False),
+            "plain16": lambda: model.gemm_plain(opA, opB, "fp16"),
+            "plainbf": lambda: model.gemm_plain(opA, opB, "bf16")}[mode]()
 
 
 def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None):
@@ -89,7 +99,7 @@ def _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=0, pad=0, rows
         opB = gemm.logical(transB, B, K, N)
         if rows is not None:
             opA = opA[rows, :]
-        mdl = model.gemm_fp16_mode(opA, opB) if mode == "fp16" else model.gemm_bf16_mode(opA, opB)
+        mdl = _model(mode, opA, opB)
         mag = np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64)
         want = alpha * mdl
         bound = (K / 8 + 4) * 2.0 ** -23 * abs(alpha) * mag
@@ -180,7 +190,7 @@ def test_invalid_arguments_are_rejected():
     dA, dB = to_device(A), to_device(B)
     dC = empty_colmajor(M, N, fill=1.0)
     bad_calls = [
-        dict(transA=7), dict(transB=-1), dict(mode=5), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
+        dict(transA=7), dict(transB=-1), dict(mode=6), dict(mode=-1), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
         dict(ldc=M - 1), dict(A=None), dict(B=None), dict(C=None),
     ]
     base = dict(transA=ec.OP_N, transB=ec.OP_N, M=M, N=N, K=K, alpha=1.0, A=dA, lda=M, B=dB, ldb=K, beta=0.0, C=dC,
@@ -309,3 +319,57 @@ def test_config5_full_shapes(mode):
     _full_size(16384, 16384, 256, "N", "N", 1.0, 0.0, mode, "urand", 256)
     _full_size(1024, 1024, 65536, "N", "N", 1.0, 0.0, mode, "urand", 64)
     _full_size(4095, 3001, 5003, "T", "N", 1.0, 0.0, mode, "urand", 256)
+
+
+# ----- the comparison methods of the paper, run through the same kernels
+
+@pytest.mark.parametrize("mode", ["markidis", "unscaled", "plain16", "plainbf"])
+def test_comparison_methods_match_their_models(mode):
+    """Element by element against the exact-accumulation model of each method (the pass rule does not apply:
+    these methods are less accurate than FP32 by design)."""
+    for (M, N, K, seed) in [(300, 200, 77, 1), (256, 256, 1024, 2)]:
+        A, B = _inputs(M, N, K, "N", "T", "urand", seed, pad=1)
+        got = _gpu_sgemm("N", "T", M, N, K, 1.0, A, B, 0.0, None, mode, ldc=M)[:M, :N]
+        opA, opB = gemm.logical("N", A, M, K), gemm.logical("T", B, K, N)
+        mag = np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64)
+        slack = 2.0 if mode == "markidis" else 1.0     # one accumulator: the small products are aligned to the big sum
+        assert np.all(np.abs(got - _model(mode, opA, opB)) <= slack * (K / 8 + 4) * 2.0 ** -23 * mag)
+
+
+def test_error_ordering_of_the_papers_first_figure():
+    """A 16 x k, B k x 16, uniform(-1, 1), k = 4096: plain FP16 is orders of magnitude worse than everything
+    else, Markidis' method sits in between, the method matches FP32."""
+    k = 4096
+    res = {m: [] for m in ("plain16", "markidis", "unscaled", "fp16", "bf16", "fp32")}
+    for seed in range(4):
+        A, B = _inputs(16, 16, k, "N", "N", "urand", seed)
+        c64 = gemm.sgemm_fp64_ref("N", "N", 16, 16, k, 1.0, A, B)
+        res["fp32"].append(gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", 16, 16, k, 1.0, A, B)))
+        for m in ("plain16", "markidis", "unscaled", "fp16", "bf16"):
+            res[m].append(gemm.relative_residual(c64, _gpu_sgemm("N", "N", 16, 16, k, 1.0, A, B, 0.0, None, m)[:16, :16]))
+    mean = {m: float(np.mean(v)) for m, v in res.items()}
+    assert mean["plain16"] > 100 * mean["fp32"]
+    assert mean["fp16"] <= 1.25 * mean["fp32"] and mean["bf16"] <= 1.25 * mean["fp32"]
+    assert mean["markidis"] >= mean["fp16"]
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16", "markidis"])
+def test_product_on_presplit_operands_equals_sgemm(mode):
+    """ecgemm_split + ecgemm_product is bitwise ecgemm_sgemm, for both storage orders of B and with split-K."""
+    import torch
+    import paper_2203_03341_amd as ec
+    m = _modes()[mode]
+    h = ec.Handle()
+    for (M, N, K, transA, transB) in [(300, 200, 77, "N", "N"), (513, 130, 4096, "T", "T")]:
+        A, B = _inputs(M, N, K, transA, transB, "urand", 3, pad=2)
+        C = si.urand(M, N, 3, si.ID_C)
+        want = _gpu_sgemm(transA, transB, M, N, K, 1.5, A, B, 0.5, C, mode, handle=h)
+        dA, dB, dC = to_device(A), to_device(B), to_device(C)
+        pa = torch.empty(ec.split_size(M, K, m), dtype=torch.uint8, device="cuda")
+        pb = torch.empty(ec.split_size(N, K, m), dtype=torch.uint8, device="cuda")
+        h.split(ec.OP_N if transA == "N" else ec.OP_T, M, K, dA, A.shape[0], m, pa)
+        h.split(ec.OP_T if transB == "N" else ec.OP_N, N, K, dB, B.shape[0], m, pb)
+        h.product(M, N, K, 1.5, pa, pb, 0.5, dC, M, m)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(dC, M, N).view(np.uint32), want.view(np.uint32))
+    h.destroy()

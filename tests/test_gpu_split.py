@@ -9,20 +9,34 @@ from gpu_util import pack_fragment_order, to_device
 pytestmark = pytest.mark.gpu
 
 
-def _expected(op, store, rows, depth, mode_bf16):
+def _mode_id(mode):
+    import paper_2203_03341_amd as ec
+    if isinstance(mode, bool):
+        return ec.MODE_BF16_FULL if mode else ec.MODE_FP16_SPLIT
+    return {"unscaled": ec.MODE_FP16_UNSCALED, "markidis": ec.MODE_FP16_MARKIDIS, "plain16": ec.MODE_FP16_PLAIN,
+            "plainbf": ec.MODE_BF16_PLAIN}[mode]
+
+
+def _expected(op, store, rows, depth, mode):
     X = store[:rows, :depth] if op == "N" else store[:depth, :rows].T
     X = np.ascontiguousarray(X, dtype=np.float32)
-    if mode_bf16:
+    if mode is True:
         parts = list(split.split_bf16x3(X))
-    else:
+    elif mode is False:
         parts = [p.view(np.uint16) for p in split.split_fp16(X)]
+    elif mode in ("unscaled", "markidis"):
+        parts = [p.view(np.uint16) for p in split.split_fp16(X, scaled=False)]
+    elif mode == "plain16":
+        parts = [split.to_fp16_rn(X).view(np.uint16)]
+    else:
+        parts = [split.to_bf16_rn_bits(X)]
     return pack_fragment_order(parts)
 
 
 def _run(op, store, rows, depth, mode_bf16, offset_elems=0):
     import torch
     import paper_2203_03341_amd as ec
-    mode = ec.MODE_BF16_FULL if mode_bf16 else ec.MODE_FP16_SPLIT
+    mode = _mode_id(mode_bf16)
     h = ec.Handle()
     src = to_device(store)
     nbytes = ec.split_size(rows, depth, mode)
@@ -88,3 +102,15 @@ def test_split_edge_values(mode_bf16):
             assert (bits & 0x7F80) == 0x7F80 and (bits & 0x7F) != 0
         else:
             assert (bits & 0x7C00) == 0x7C00 and (bits & 0x3FF) != 0
+
+
+@pytest.mark.parametrize("mode", ["unscaled", "markidis", "plain16", "plainbf"])
+@pytest.mark.parametrize("op", ["N", "T"])
+def test_split_of_comparison_methods(mode, op):
+    """Markidis' unscaled residual (Eqs. corr-elm-1, corr-elm-2) and the plain conversions, bit for bit."""
+    rows, depth = 300, 77
+    sr, sc = (rows, depth) if op == "N" else (depth, rows)
+    for store in (si.urand(sr, sc, 4, si.ID_A, ld=sr + 2), si.exp_rand(sr, sc, -20, 15, 5, si.ID_A, ld=sr + 1)):
+        got = _run(op, store, rows, depth, mode)
+        want = _expected(op, store, rows, depth, mode)
+        assert got.shape == want.shape and np.array_equal(got, want)

@@ -392,3 +392,32 @@ def test_models_reach_fp32_accuracy_in_their_exponent_ranges():
     assert r16 > 3 * r32 and rbf <= r32
     r32, r16, rbf = run((-100, -35), (-15, 14))        # Type 2 / 4
     assert r16 > 0.1 and rbf <= r32          # above the 0.1 "broken kernel" threshold of the tuning section
+
+
+def test_comparison_method_models():
+    """Models of the methods the paper compares against.  Plain conversion: the relative residual is the
+    conversion error: rounding to p fraction bits (10 for FP16, 7 for BF16) is off by a uniform +-2^-(p+1) of the
+    binade, so per operand the relative rms is 2^-(p+1) / sqrt(3) * sqrt(E[1/m^2]) with m uniform in [1, 2)
+    (E[1/m^2] = 1/2), and two operands give sqrt(2) times that: 2.8e-4 and 2.3e-3, independent of k.  Markidis' unscaled
+    residual equals the scaled one wherever nothing underflows (inputs of magnitude >= 1 here), and loses
+    accuracy on small inputs (exp_rand(-14, -8): the residual sits in FP16's subnormal range), where the scaled
+    split does not: this is what the 2^11 of Eq. corr-elm-2-1024 is for."""
+    n = 256
+    A = si.exp_rand(n, n, -3, 3, 0, si.ID_A)
+    B = si.exp_rand(n, n, -3, 3, 0, si.ID_B)
+    c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+    r16 = gemm.relative_residual(c64, model.gemm_plain(A, B, "fp16"))
+    rbf = gemm.relative_residual(c64, model.gemm_plain(A, B, "bf16"))
+    assert 2.3e-4 <= r16 <= 3.3e-4 and 1.8e-3 <= rbf <= 2.7e-3
+    big_a = si.exp_rand(n, n, 0, 3, 1, si.ID_A)
+    big_b = si.exp_rand(n, n, 0, 3, 1, si.ID_B)
+    for products in (3, 4):
+        assert np.array_equal(model.gemm_fp16_mode(big_a, big_b, products, scaled=True),
+                              model.gemm_fp16_mode(big_a, big_b, products, scaled=False))
+    A = si.exp_rand(n, n, -14, -8, 2, si.ID_A)
+    B = si.exp_rand(n, n, -14, -8, 2, si.ID_B)
+    c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+    r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
+    r_scaled = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 3, scaled=True))
+    r_unscaled = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 4, scaled=False))
+    assert r_scaled < r32 < 0.1 * r_unscaled
