@@ -143,6 +143,17 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
 /* Bytes ecgemm_split writes for a rows x depth operand.  `bytes` is a host pointer. */
 ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mode, size_t *bytes);
 
+/*
+ * Diagnostic: executes `count` independent v_mfma_f32_32x32x16_f16 (bf16 == 0) or _bf16 (bf16 != 0) instructions,
+ * D = A B + C with A 32 x 16, B 16 x 32, C and D 32 x 32, on registers given lane by lane, so that tests can state what
+ * the matrix unit does (the method's accumulation discipline, section "Avoiding RZ during Tensor Core accumulation",
+ * depends on it).  For problem p and lane l (0..63): a[(p*64 + l)*8 + e] = A(l % 32, 8*(l/32) + e),
+ * b[(p*64 + l)*8 + e] = B(8*(l/32) + e, l % 32), c and d [(p*64 + l)*16 + v] = element (8*(v/4) + 4*(l/32) + v%4, l % 32).
+ * a, b: device, 16-bit patterns, 16-byte aligned; c, d: device FP32, 64-byte aligned; d may equal c.
+ */
+ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void *a, const void *b,
+                                  const float *c, float *d);
+
 /* When enabled, every ecgemm_sgemm brackets its split kernels and its product kernel with HIP events on
  * the handle's stream so that their device durations can be read back; off by default. */
 ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled);

@@ -20,7 +20,7 @@ MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN = 2, 3,
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -40,6 +40,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_product.argtypes = [vp, i64, i64, i64, f32, vp, vp, f32, vp, i64, ctypes.c_int]
     lib.ecgemm_split.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_split_size.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.ecgemm_debug_mfma.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp, vp]
     lib.ecgemm_set_timing.argtypes = [vp, ctypes.c_int]
     lib.ecgemm_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f32), ctypes.POINTER(f32)]
     lib.ecgemm_last_error_string.argtypes = [vp]
@@ -118,6 +119,9 @@ class Handle:
 
     def split(self, op: int, rows: int, depth: int, src, ld: int, mode: int, packed):
         self._check(_lib.ecgemm_split(self._h, op, rows, depth, _ptr(src), ld, mode, _ptr(packed)))
+
+    def debug_mfma(self, bf16: bool, count: int, a, b, c, d):
+        self._check(_lib.ecgemm_debug_mfma(self._h, int(bf16), count, _ptr(a), _ptr(b), _ptr(c), _ptr(d)))
 
     def set_timing(self, enabled: bool):
         self._check(_lib.ecgemm_set_timing(self._h, int(enabled)))

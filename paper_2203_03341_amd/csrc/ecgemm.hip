@@ -329,6 +329,21 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
   return launch_split(handle, op, rows, depth, src, ld, mode, packed);
 }
 
+ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void* a, const void* b,
+                                  const float* c, float* d) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (count < 0 || count > 0x7fffffff) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma: bad count");
+  if (count == 0) return ECGEMM_OK;
+  if (!a || !b || !c || !d || ((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 64) || ((uintptr_t)d % 64))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma: null or misaligned pointer");
+  const unsigned short* ua = static_cast<const unsigned short*>(a);
+  const unsigned short* ub = static_cast<const unsigned short*>(b);
+  if (bf16) hipLaunchKernelGGL(single_mfma_kernel<true>, dim3((unsigned)count), dim3(64), 0, handle->stream, ua, ub, c, d);
+  else hipLaunchKernelGGL(single_mfma_kernel<false>, dim3((unsigned)count), dim3(64), 0, handle->stream, ua, ub, c, d);
+  ECGEMM_HIP(handle, hipGetLastError());
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
   handle->timing = enabled != 0;

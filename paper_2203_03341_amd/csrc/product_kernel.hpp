@@ -400,6 +400,21 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   }
 }
 
+// One v_mfma_f32_32x32x16 per wave on caller-supplied registers, for tests that pin down what the matrix unit does
+// (lane map, rounding, subnormals): lane l of problem p reads a[(p * 64 + l) * 8 .. +8], b likewise, c[(p * 64 + l) * 16
+// .. +16] and writes d at the same place.
+template <bool BF16>
+__global__ void __launch_bounds__(64) single_mfma_kernel(const unsigned short* __restrict__ a, const unsigned short* __restrict__ b,
+                                                         const float* __restrict__ c, float* __restrict__ d) {
+  typedef typename Mfma<BF16>::frag_t frag_t;
+  const int64_t slot = (int64_t)blockIdx.x * 64 + threadIdx.x;
+  const frag_t fa = *reinterpret_cast<const frag_t*>(a + slot * 8);
+  const frag_t fb = *reinterpret_cast<const frag_t*>(b + slot * 8);
+  float16_t acc = *reinterpret_cast<const float16_t*>(c + slot * 16);
+  acc = Mfma<BF16>::run(fa, fb, acc);
+  *reinterpret_cast<float16_t*>(d + slot * 16) = acc;
+}
+
 // Split-K tail: sums the k_splits partial tiles in a fixed order, then alpha / beta.
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partials, int k_splits,
                                                               int64_t Mp, int64_t Np, int64_t M, int64_t N,

@@ -421,3 +421,42 @@ def test_comparison_method_models():
     r_scaled = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 3, scaled=True))
     r_unscaled = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B, 4, scaled=False))
     assert r_scaled < r32 < 0.1 * r_unscaled
+
+
+def test_mma_emulators():
+    """The paper's mma_rn / mma_rz emulators.  Pinned by exact integer products, by hand-worked single additions
+    (1 + 0.75 ulp: RN gives 1 + ulp, RZ gives 1; 1 - 0.25 ulp(1-): RN gives 1, RZ gives the next value below 1) and
+    by the paper's emulator experiment: Markidis' method through mma_rn is as accurate as the naive FP32 product,
+    through mma_rz it is clearly worse."""
+    from oracle import mma_emulator as emu
+    rng = np.random.default_rng(0)
+    A = rng.integers(-7, 8, (8, 8)).astype(np.float32)
+    B = rng.integers(-7, 8, (8, 8)).astype(np.float32)
+    C = rng.integers(-100, 100, (8, 8)).astype(np.float32)
+    exact = (A.astype(np.int64) @ B.astype(np.int64) + C.astype(np.int64)).astype(np.float32)
+    assert np.array_equal(emu.mma_rn(A, B, C), exact) and np.array_equal(emu.mma_rz(A, B, C), exact)
+    ulp = 2.0 ** -23
+    one = np.ones((1, 1), dtype=np.float32)
+    a = np.array([[0.75 * 2.0 ** -10]], dtype=np.float32)
+    b = np.array([[2.0 ** -13]], dtype=np.float32)
+    assert emu.mma_rn(a, b, one)[0, 0] == np.float32(1 + ulp) and emu.mma_rz(a, b, one)[0, 0] == np.float32(1.0)
+    assert emu.mma_rn(-a / 6, b, one)[0, 0] == np.float32(1.0) and emu.mma_rz(-a / 6, b, one)[0, 0] == np.float32(1 - ulp / 2)
+    # Markidis' method (four products, one accumulator, unscaled residual) through both emulators
+    k = 1024
+    err = {"rn": [], "rz": [], "fp32": []}
+    for seed in range(3):
+        A32 = si.urand(16, k, seed, si.ID_A)
+        B32 = si.urand(k, 16, seed, si.ID_B)
+        a16, da16 = (p.astype(np.float32) for p in split.split_fp16(A32, scaled=False))
+        b16, db16 = (p.astype(np.float32) for p in split.split_fp16(B32, scaled=False))
+        c64 = gemm.sgemm_fp64_ref("N", "N", 16, 16, k, 1.0, A32, B32)
+        for name, fn in (("rn", emu.mma_rn), ("rz", emu.mma_rz)):
+            acc = np.zeros((16, 16), dtype=np.float32)
+            for k0 in range(0, k, 8):
+                s = slice(k0, k0 + 8)
+                for x, y in ((da16, db16), (da16, b16), (a16, db16), (a16, b16)):
+                    acc = fn(x[:, s], y[s, :], acc)
+            err[name].append(gemm.relative_residual(c64, acc))
+        err["fp32"].append(gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", 16, 16, k, 1.0, A32, B32)))
+    rn, rz, fp32 = (float(np.mean(err[n])) for n in ("rn", "rz", "fp32"))
+    assert rn <= 1.25 * fp32 and rz > 2 * rn
