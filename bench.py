@@ -78,6 +78,10 @@ def main():
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle (no error figures, no cpu_baseline)")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--power-seconds", type=float, default=2.5,
+                    help="after the timed steps, loop the same call for this long while sampling board power from sysfs "
+                         "every 20 ms (the paper samples NVML every 0.02 s over >= 2 s); 0 disables")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the matrix-instruction-only rate measurement")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -148,6 +152,58 @@ def main():
     product_ms_avg = product_ms / calls
     mfma_tflops = parts_products * flops / (product_ms_avg * 1e-3) / 1e12
 
+    # ---- what the matrix pipes sustain on this board with random operands and no memory traffic (same dtype)
+    ceiling = None
+    if not args.no_ceiling:
+        ops16 = (torch.rand(12 * 256 * 8, device="cuda") * 2 - 1).to(torch.bfloat16 if mode == "bf16" else torch.float16)
+        sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        h.debug_mfma_rate(mode == "bf16", ops16, sink, 256, 2000)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        probe_flops = h.debug_mfma_rate(mode == "bf16", ops16, sink, 256, 40000)     # ~15-20 ms
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ceiling = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+    # ---- board power while the same call runs back to back
+    power = None
+    if args.power_seconds > 0:
+        import glob
+        import threading
+        paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        if paths:
+            samples, stop_flag = [], threading.Event()
+
+            def sampler():
+                while not stop_flag.is_set():
+                    try:
+                        with open(paths[0]) as f:
+                            samples.append(int(f.read()) * 1e-6)
+                    except OSError:
+                        pass
+                    time.sleep(0.02)
+
+            th = threading.Thread(target=sampler)
+            t_begin = time.perf_counter()
+            calls_done = 0
+            th.start()
+            while time.perf_counter() - t_begin < args.power_seconds:
+                for _ in range(4):
+                    step()
+                torch.cuda.synchronize()
+                calls_done += 4
+            elapsed = time.perf_counter() - t_begin
+            stop_flag.set()
+            th.join()
+            steady = samples[len(samples) // 4:]        # drop the ramp-up quarter
+            if steady:
+                watts = float(np.mean(steady))
+                rate = flops * calls_done / elapsed
+                power = {"avg_w": round(watts, 1), "max_w": round(float(np.max(steady)), 1), "samples": len(steady),
+                         "interval_s": 0.02, "seconds": round(elapsed, 2), "source": paths[0],
+                         "tflops_during": round(rate / 1e12, 1), "gflops_per_w": round(rate / 1e9 / watts, 1)}
+
     got = dC.cpu().numpy().T          # logical M x N
     result = {
         "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -161,7 +217,11 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(mfma_tflops / PEAK_MFMA_16BIT_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "kernel": "product_kernel",
-                     "flops_per_launch": parts_products * flops},
+                     "flops_per_launch": parts_products * flops,
+                     # the same matrix instructions with random operands and nothing else running, this board, this run
+                     "mfma_only_random_operands_tflops": None if ceiling is None else round(ceiling, 1),
+                     "frac_of_mfma_only": None if ceiling is None else round(mfma_tflops / ceiling, 4)},
+        "power": power,
     }
 
     if not args.no_oracle:

@@ -116,6 +116,26 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
+ * Power-of-two pre-scaling (the "additional scaling before matrix-matrix multiplication" the paper asks for at the
+ * end of section "Effect of the exponent range of input matrices" when all elements are small).  From now on
+ * ecgemm_sgemm on this handle splits op(A) * 2^log2_scale_a and op(B) * 2^log2_scale_b and multiplies the product by
+ * 2^-(log2_scale_a + log2_scale_b) before alpha / beta.  Multiplying by a power of two is exact, so this only moves
+ * the inputs inside the exponent window of the FP16 pair (2^-14 .. 2^16); the caller must pick exponents that neither
+ * overflow nor underflow FP32.  Each exponent and their sum must lie in [-126, 126].  (0, 0) switches it off.
+ * ecgemm_split and ecgemm_product are not affected.
+ */
+ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int log2_scale_b);
+
+/*
+ * Helper for choosing a mode or a pre-scaling: binary exponents (floor(log2 |x|)) of the smallest and the largest
+ * non-zero finite element of a column-major rows x cols FP32 matrix (src: device, ld >= rows).  Subnormals count as
+ * -127; a matrix without such elements gives (INT_MAX, INT_MIN).  Unlike the other calls this one waits for the
+ * stream: the two results are host integers.
+ */
+ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int64_t cols, const float *src, int64_t ld,
+                                      int *min_exponent, int *max_exponent);
+
+/*
  * Step 1 alone (Eqs. corr-1-1024 .. corr-4-1024 / the BF16 three-term split), for inspection and tests.
  * Splits the `rows` x `depth` matrix X = op(src) into `packed`, a device buffer of
  * ecgemm_split_size(rows, depth, mode) bytes, laid out as
@@ -153,6 +173,17 @@ ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mod
  */
 ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void *a, const void *b,
                                   const float *c, float *d);
+
+/*
+ * Diagnostic: enqueues a kernel of `blocks` workgroups x 4 waves that does nothing but `iters` x 24 matrix
+ * instructions per wave (FP16 if bf16 == 0, else BF16) on operands read once from `operands` (device, 12 x 256 x 8
+ * 16-bit values = 48 KiB, 16-byte aligned).  `sink`: device, blocks x 256 floats, receives a checksum.  `flops`
+ * (host pointer) receives the floating-point operations the kernel performs; timing it (the caller brackets it with
+ * events on the handle's stream) gives the rate the matrix pipes sustain for that operand content on this device,
+ * against which the product kernel's rate can be read.
+ */
+ecgemm_status_t ecgemm_debug_mfma_rate(ecgemm_handle_t handle, int bf16, const void *operands, float *sink, int blocks,
+                                       int iters, double *flops);
 
 /* When enabled, every ecgemm_sgemm brackets its split kernels and its product kernel with HIP events on
  * the handle's stream so that their device durations can be read back; off by default. */

@@ -20,7 +20,7 @@ MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN = 2, 3,
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -37,10 +37,13 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
+    lib.ecgemm_set_scaling.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+    lib.ecgemm_exponent_range.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_product.argtypes = [vp, i64, i64, i64, f32, vp, vp, f32, vp, i64, ctypes.c_int]
     lib.ecgemm_split.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_split_size.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
     lib.ecgemm_debug_mfma.argtypes = [vp, ctypes.c_int, i64, vp, vp, vp, vp]
+    lib.ecgemm_debug_mfma_rate.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double)]
     lib.ecgemm_set_timing.argtypes = [vp, ctypes.c_int]
     lib.ecgemm_get_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f32), ctypes.POINTER(f32)]
     lib.ecgemm_last_error_string.argtypes = [vp]
@@ -114,6 +117,14 @@ class Handle:
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
 
+    def set_scaling(self, log2_scale_a: int, log2_scale_b: int):
+        self._check(_lib.ecgemm_set_scaling(self._h, log2_scale_a, log2_scale_b))
+
+    def exponent_range(self, rows: int, cols: int, src, ld: int):
+        lo, hi = ctypes.c_int(), ctypes.c_int()
+        self._check(_lib.ecgemm_exponent_range(self._h, rows, cols, _ptr(src), ld, ctypes.byref(lo), ctypes.byref(hi)))
+        return lo.value, hi.value
+
     def product(self, M: int, N: int, K: int, alpha: float, packedA, packedB, beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_product(self._h, M, N, K, alpha, _ptr(packedA), _ptr(packedB), beta, _ptr(C), ldc, mode))
 
@@ -122,6 +133,12 @@ class Handle:
 
     def debug_mfma(self, bf16: bool, count: int, a, b, c, d):
         self._check(_lib.ecgemm_debug_mfma(self._h, int(bf16), count, _ptr(a), _ptr(b), _ptr(c), _ptr(d)))
+
+    def debug_mfma_rate(self, bf16: bool, operands, sink, blocks: int, iters: int) -> float:
+        """Enqueues the matrix-instruction-only kernel; returns the flops it performs."""
+        flops = ctypes.c_double()
+        self._check(_lib.ecgemm_debug_mfma_rate(self._h, int(bf16), _ptr(operands), _ptr(sink), blocks, iters, ctypes.byref(flops)))
+        return flops.value
 
     def set_timing(self, enabled: bool):
         self._check(_lib.ecgemm_set_timing(self._h, int(enabled)))

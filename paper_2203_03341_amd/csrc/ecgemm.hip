@@ -3,6 +3,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -26,6 +28,8 @@ struct ecgemm_context {
   void* user_workspace = nullptr;
   size_t user_bytes = 0;
   bool timing = false;
+  int log2_scale_a = 0, log2_scale_b = 0;
+  int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
   std::vector<TimedCall> timed;
   std::vector<hipEvent_t> free_events;
   std::string last_error;
@@ -124,7 +128,8 @@ ecgemm_status_t hip_fail(ecgemm_handle_t h, hipError_t e, const char* where) {
 
 // X = op(src) is rows x depth.  op == N: X(r, k) = src[r + k * ld]; op == T: X(r, k) = src[k + r * ld].
 ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
-                             int64_t ld, ecgemm_mode_t mode, void* packed) {
+                             int64_t ld, ecgemm_mode_t mode, void* packed, int log2_prescale = 0) {
+  const float prescale = std::ldexp(1.0f, log2_prescale);
   const int64_t Rp = round_up(rows, kRowPad), Kp = round_up(depth, kDepthPad);
   const int64_t k_steps = Kp / 16;
   if (Rp / 64 > 65535) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 4193280 rows");
@@ -135,11 +140,11 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
 #define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                          \
   do {                                                                                                                     \
     if (!k_contiguous)                                                                                                     \
-      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);       \
+      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out); \
     else if (vec)                                                                                                          \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out); \
+      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out); \
     else                                                                                                                   \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, out);\
+      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out);\
   } while (0)
   switch (split_kind_of((int)mode)) {
     case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;
@@ -155,7 +160,8 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
 
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
-                               const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials) {
+                               const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials,
+                               int log2_out_scale = 0) {
   ProductParams pp;
   pp.a_packed = static_cast<const char*>(a_packed);
   pp.b_packed = static_cast<const char*>(b_packed);
@@ -169,6 +175,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.ldc = ldc;
   pp.alpha = alpha;
   pp.beta = beta;
+  pp.out_scale = std::ldexp(1.0f, log2_out_scale);
   pp.C = C;
   pp.partials = partials;
   pp.Mp = pl.Mp;
@@ -276,6 +283,7 @@ ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
   ecgemm_status_t st = ECGEMM_OK;
   if (handle->own_workspace && hipFree(handle->own_workspace) != hipSuccess) st = ECGEMM_ERR_HIP;
+  if (handle->range_buffer && hipFree(handle->range_buffer) != hipSuccess) st = ECGEMM_ERR_HIP;
   for (TimedCall& t : handle->timed) {
     (void)hipEventDestroy(t.start);
     (void)hipEventDestroy(t.split_done);
@@ -329,6 +337,41 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
   return launch_split(handle, op, rows, depth, src, ld, mode, packed);
 }
 
+ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int log2_scale_b) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (std::abs(log2_scale_a) > 126 || std::abs(log2_scale_b) > 126 || std::abs(log2_scale_a + log2_scale_b) > 126)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_scaling: exponents (and their sum) must stay within +-126");
+  handle->log2_scale_a = log2_scale_a;
+  handle->log2_scale_b = log2_scale_b;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int64_t cols, const float* src, int64_t ld,
+                                      int* min_exponent, int* max_exponent) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!min_exponent || !max_exponent || rows < 0 || cols < 0)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_exponent_range: bad argument");
+  int host[2] = {INT_MAX, INT_MIN};
+  if (rows > 0 && cols > 0) {
+    if (!src || ld < rows) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_exponent_range: null source or ld < rows");
+    if (!handle->range_buffer && hipMalloc(&handle->range_buffer, 2 * sizeof(int)) != hipSuccess) {
+      handle->range_buffer = nullptr;
+      (void)hipGetLastError();
+      return fail(handle, ECGEMM_ERR_ALLOC, "ecgemm_exponent_range: hipMalloc failed");
+    }
+    ECGEMM_HIP(handle, hipMemcpyAsync(handle->range_buffer, host, sizeof(host), hipMemcpyHostToDevice, handle->stream));
+    const int64_t row_blocks = (rows + 255) / 256;
+    const dim3 grid((unsigned)(row_blocks < 1024 ? row_blocks : 1024), (unsigned)(cols < 4096 ? cols : 4096));
+    hipLaunchKernelGGL(exponent_range_kernel, grid, dim3(256), 0, handle->stream, src, ld, rows, cols, handle->range_buffer);
+    ECGEMM_HIP(handle, hipGetLastError());
+    ECGEMM_HIP(handle, hipMemcpyAsync(host, handle->range_buffer, sizeof(host), hipMemcpyDeviceToHost, handle->stream));
+    ECGEMM_HIP(handle, hipStreamSynchronize(handle->stream));
+  }
+  *min_exponent = host[0];
+  *max_exponent = host[1];
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void* a, const void* b,
                                   const float* c, float* d) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
@@ -341,6 +384,19 @@ ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t coun
   if (bf16) hipLaunchKernelGGL(single_mfma_kernel<true>, dim3((unsigned)count), dim3(64), 0, handle->stream, ua, ub, c, d);
   else hipLaunchKernelGGL(single_mfma_kernel<false>, dim3((unsigned)count), dim3(64), 0, handle->stream, ua, ub, c, d);
   ECGEMM_HIP(handle, hipGetLastError());
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_debug_mfma_rate(ecgemm_handle_t handle, int bf16, const void* operands, float* sink, int blocks,
+                                       int iters, double* flops) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!operands || !sink || !flops || blocks <= 0 || iters <= 0 || ((uintptr_t)operands % 16))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma_rate: bad argument");
+  const unsigned short* ops = static_cast<const unsigned short*>(operands);
+  if (bf16) hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, handle->stream, ops, sink, iters);
+  else hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, handle->stream, ops, sink, iters);
+  ECGEMM_HIP(handle, hipGetLastError());
+  *flops = (double)blocks * 4.0 * iters * 24.0 * 2.0 * 32 * 32 * 16;
   return ECGEMM_OK;
 }
 
@@ -418,14 +474,15 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
 
   // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
   // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
-  st = launch_split(h, transA, M, K, A, lda, mode, a_packed);
+  st = launch_split(h, transA, M, K, A, lda, mode, a_packed, h->log2_scale_a);
   if (st != ECGEMM_OK) return st;
-  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed);
+  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed, h->log2_scale_b);
   if (st != ECGEMM_OK) return st;
   if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
 
   // steps 2 and 3
-  st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials);
+  st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials,
+                      -(h->log2_scale_a + h->log2_scale_b));
   if (st != ECGEMM_OK) return st;
   if (h->timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));

@@ -47,6 +47,7 @@ struct ProductParams {
   int tiles_m, tiles_n;
   int64_t M, N, ldc;
   float alpha, beta;
+  float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
   float* C;
   float* partials;          // [k_splits][Np][Mp] when k_splits > 1
   int64_t Mp, Np;
@@ -377,7 +378,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 #pragma unroll
         for (int v = 0; v < 16; ++v)
           store(m_base + i * 32, n_base + j * 32 + 8 * (v / 4) + (v % 4),
-                acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale);
+                (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
   };
   const bool interior = (int64_t)(tile_m + 1) * Cfg::BM <= p.M && (int64_t)(tile_n + 1) * Cfg::BN <= p.N;
   if (p.k_splits > 1) {
@@ -413,6 +414,39 @@ __global__ void __launch_bounds__(64) single_mfma_kernel(const unsigned short* _
   float16_t acc = *reinterpret_cast<const float16_t*>(c + slot * 16);
   acc = Mfma<BF16>::run(fa, fb, acc);
   *reinterpret_cast<float16_t*>(d + slot * 16) = acc;
+}
+
+// Matrix instructions only, no memory traffic in the loop: every wave of the grid issues `iters` x 24
+// v_mfma_f32_32x32x16 on operands it read once (12 fragments per lane from `operands`, 256 lanes x 16 bytes each).
+// Timed by the caller, this gives the rate the matrix pipes sustain for a given operand content; with random
+// operands it is well below the nominal peak because the clock drops under load.
+template <bool BF16>
+__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short* __restrict__ operands, float* __restrict__ sink,
+                                                           int iters) {
+  typedef typename Mfma<BF16>::frag_t frag_t;
+  frag_t fa[6], fb[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) {
+    fa[i] = *reinterpret_cast<const frag_t*>(operands + (i * 256 + threadIdx.x) * 8);
+    fb[i] = *reinterpret_cast<const frag_t*>(operands + ((6 + i) * 256 + threadIdx.x) * 8);
+  }
+  float16_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = Mfma<BF16>::run(fa[(i + 2 * r) % 6], fb[(i * 5 + r) % 6], acc[i]);
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s += acc[i][v];
+  sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
 // Split-K tail: sums the k_splits partial tiles in a fixed order, then alpha / beta.

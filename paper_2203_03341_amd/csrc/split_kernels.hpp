@@ -105,7 +105,7 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
 // thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4).
 template <int KIND, bool VEC>
 __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                          int64_t depth, int64_t k_steps_total,
+                                                          int64_t depth, int64_t k_steps_total, float prescale,
                                                           unsigned short* __restrict__ packed) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)blockIdx.y * 64 + (t >> 2);
@@ -120,6 +120,8 @@ __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restric
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r * ld + k + e] : 0.0f;
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] *= prescale;  // a power of two chosen by the caller (1 by default): exact
   store_fragment_row<KIND>(packed, k_steps_total, r, k, v);
 }
 
@@ -127,7 +129,7 @@ __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restric
 // through LDS so that both the global reads (along r) and the fragment writes are coalesced.
 template <int KIND>
 __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                          int64_t depth, int64_t k_steps_total,
+                                                          int64_t depth, int64_t k_steps_total, float prescale,
                                                           unsigned short* __restrict__ packed) {
   constexpr int kStride = 66;  // floats per k line in LDS; 66 keeps the transposed reads conflict-free
   __shared__ float tile[32 * kStride];
@@ -147,8 +149,28 @@ __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restric
   const int rr = t >> 2, kk = (t & 3) * 8;
   float v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = tile[(kk + e) * kStride + rr];
+  for (int e = 0; e < 8; ++e) v[e] = tile[(kk + e) * kStride + rr] * prescale;
   store_fragment_row<KIND>(packed, k_steps_total, r0 + rr, k0 + kk, v);
+}
+
+// Smallest and largest binary exponent among the non-zero finite elements of a column-major rows x cols matrix
+// (subnormals count as exponent -127).  range[0] must start at INT_MAX and range[1] at INT_MIN.
+__global__ void __launch_bounds__(256) exponent_range_kernel(const float* __restrict__ src, int64_t ld, int64_t rows,
+                                                             int64_t cols, int* __restrict__ range) {
+  int lo = 0x7fffffff, hi = -0x7fffffff - 1;
+  for (int64_t c = blockIdx.y; c < cols; c += gridDim.y)
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < rows; r += (int64_t)gridDim.x * 256) {
+      const unsigned bits = __builtin_bit_cast(unsigned, src[r + c * ld]) & 0x7fffffffu;
+      if (bits != 0 && bits < 0x7f800000u) {
+        const int e = (int)(bits >> 23) - 127;
+        lo = e < lo ? e : lo;
+        hi = e > hi ? e : hi;
+      }
+    }
+  if (lo <= hi) {
+    atomicMin(&range[0], lo);
+    atomicMax(&range[1], hi);
+  }
 }
 
 }  // namespace ecgemm

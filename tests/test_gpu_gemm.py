@@ -373,3 +373,34 @@ def test_product_on_presplit_operands_equals_sgemm(mode):
         torch.cuda.synchronize()
         assert np.array_equal(to_host(dC, M, N).view(np.uint32), want.view(np.uint32))
     h.destroy()
+
+
+def test_prescaling_brings_small_inputs_into_the_fp16_window():
+    """Type 3 of the paper (both inputs exp_rand(-35, -15)) loses accuracy in FP16 mode; the paper's remedy is a
+    scaling before the product.  With exact power-of-two factors chosen from the measured exponent range the FP16
+    mode meets the FP32 bar again, and the factors are undone exactly in the epilogue."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 384, 320, 512
+    A, B = _inputs(M, N, K, "N", "N", ((-35, -15), (-35, -15)), 0)
+    C = si.urand(M, N, 0, si.ID_C)
+    C *= np.float32(2.0 ** -40)                                  # same scale as the product, so beta matters
+    c64 = gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.5, A, B, 0.5, C)
+    r_cpu = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.5, A, B, 0.5, C))
+    h = ec.Handle()
+    dA, dB = to_device(A), to_device(B)
+    assert h.exponent_range(M, K, dA, M) == (-35, -15)
+    assert h.exponent_range(K, N, dB, K) == (-35, -15)
+    assert h.exponent_range(0, 0, None, 1) == (2 ** 31 - 1, -2 ** 31)
+    plain = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
+    assert gemm.relative_residual(c64, plain) > 2 * r_cpu         # degraded, as the paper reports
+    shift = 14 - (-15)                                            # top binade of the inputs lands on 2^14
+    h.set_scaling(shift, shift)
+    scaled = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
+    assert gemm.relative_residual(c64, scaled) <= RATIO * r_cpu
+    h.set_scaling(0, 0)
+    again = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
+    assert np.array_equal(again.view(np.uint32), plain.view(np.uint32))
+    with pytest.raises(ec.EcgemmError):
+        h.set_scaling(100, 100)
+    h.destroy()
