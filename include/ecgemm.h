@@ -50,7 +50,12 @@ typedef enum {
     /* toFP16(A) toFP16(B), one product, no correction (listing "A simple matrix-matrix multiplication ..."). */
     ECGEMM_MODE_FP16_PLAIN = 4,
     /* toBF16(A) toBF16(B), one product, no correction. */
-    ECGEMM_MODE_BF16_PLAIN = 5
+    ECGEMM_MODE_BF16_PLAIN = 5,
+    /* ECGEMM_MODE_FP16_SPLIT exactly as the paper's listing has it: A16 B16 is multiplied into a zeroed temporary and
+     * added to the running sum outside the matrix unit, every k step (section "Avoiding RZ during Tensor Core
+     * accumulation").  On this hardware the matrix unit already rounds to nearest, so this only costs time; it is kept
+     * to show that. */
+    ECGEMM_MODE_FP16_OUTSIDE_ACC = 6
 } ecgemm_mode_t;
 
 typedef enum {

@@ -58,18 +58,20 @@ typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS
 typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> UnscaledConfig;
 typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3> PlainFp16Config;
 typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3> PlainBf16Config;
+typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> OutsideConfig;
 constexpr int kBM = 256, kBN = 128;
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // the ecgemm_mode_t values are the ProductMethod values
 inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
-inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_BF16_PLAIN; }
+inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_FP16_OUTSIDE_ACC; }
 inline int stage_depth_of(ecgemm_mode_t mode) { return mode == ECGEMM_MODE_BF16_FULL ? Bf16Config::BK : Fp16Config::BK; }
 static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
               (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
               (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
-              (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain,
+              (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain &&
+              (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside,
               "mode numbering");
 static_assert(PlainFp16Config::BK == Fp16Config::BK && MarkidisConfig::BK == Fp16Config::BK, "stage depths");
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
@@ -188,6 +190,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
     case ECGEMM_MODE_FP16_UNSCALED: hipLaunchKernelGGL(product_kernel<UnscaledConfig>, grid, dim3(UnscaledConfig::THREADS), 0, h->stream, pp); break;
     case ECGEMM_MODE_FP16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainFp16Config>, grid, dim3(PlainFp16Config::THREADS), 0, h->stream, pp); break;
     case ECGEMM_MODE_BF16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainBf16Config>, grid, dim3(PlainBf16Config::THREADS), 0, h->stream, pp); break;
+    case ECGEMM_MODE_FP16_OUTSIDE_ACC: hipLaunchKernelGGL(product_kernel<OutsideConfig>, grid, dim3(OutsideConfig::THREADS), 0, h->stream, pp); break;
   }
   ECGEMM_HIP(h, hipGetLastError());
   if (pl.k_splits > 1) {

@@ -77,17 +77,19 @@ enum ProductMethod {
   kMethodFp16Markidis = 2,  // Eq. corr-5 and listing "Markidis' error correction method": dA dB + dA B + A dB + A B, one accumulator
   kMethodFp16Unscaled = 3,  // the method's three products and two accumulators on Markidis' unscaled residual
   kMethodFp16Plain = 4,     // A16 B16 only (listing "A simple matrix-matrix multiplication ... on Tensor Cores")
-  kMethodBf16Plain = 5      // toBF16(A) toBF16(B) only
+  kMethodBf16Plain = 5,     // toBF16(A) toBF16(B) only
+  kMethodFp16Outside = 6    // kMethodFp16Split with A16 B16 added to its accumulator outside the matrix unit, every k
+                            // step, through a zeroed temporary (frag_tmp of the paper's listing; its contribution 1)
 };
 
 __host__ __device__ constexpr int split_kind_of(int method) {
-  return method == kMethodFp16Split ? kSplitFp16Scaled
+  return (method == kMethodFp16Split || method == kMethodFp16Outside) ? kSplitFp16Scaled
        : method == kMethodBf16Full ? kSplitBf16x3
        : (method == kMethodFp16Markidis || method == kMethodFp16Unscaled) ? kSplitFp16Unscaled
        : method == kMethodFp16Plain ? kSplitFp16Plain : kSplitBf16Plain;
 }
 __host__ __device__ constexpr int products_of(int method) {
-  return method == kMethodFp16Split || method == kMethodFp16Unscaled ? 3
+  return method == kMethodFp16Split || method == kMethodFp16Unscaled || method == kMethodFp16Outside ? 3
        : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : 1;
 }
 
@@ -231,8 +233,24 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
       ECGEMM_PRODUCT(acc_main, 0, 1)
       ECGEMM_PRODUCT(acc_main, 0, 0)
     } else {
-      ECGEMM_PRODUCT(acc_main, 0, 0)
-      if constexpr (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Unscaled) {
+      if constexpr (Cfg::kMethod == kMethodFp16Outside) {
+        // the matrix unit only multiplies: its accumulator input is zero and the running sum is kept by FP32 vector adds
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            float16_t zero;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+            const float16_t tmp = Mfma<Cfg::kBf16>::run(fb[set][j][0], fa[set][i][0], zero);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_main[i][j][v] += tmp[v];
+          }
+      } else {
+        ECGEMM_PRODUCT(acc_main, 0, 0)
+      }
+      if constexpr (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Unscaled ||
+                    Cfg::kMethod == kMethodFp16Outside) {
         ECGEMM_PRODUCT(acc_corr, 1, 0)
         ECGEMM_PRODUCT(acc_corr, 0, 1)
       } else if constexpr (Cfg::kMethod == kMethodBf16Full) {
@@ -367,7 +385,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
-  const float corr_scale = Cfg::kMethod == kMethodFp16Split ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
+  const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
   const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane >> 5);
   auto for_each_output = [&](auto&& store) {

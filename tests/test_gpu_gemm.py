@@ -26,12 +26,14 @@ RATIO = 1.25
 def _modes():
     import paper_2203_03341_amd as ec
     return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "markidis": ec.MODE_FP16_MARKIDIS,
-            "unscaled": ec.MODE_FP16_UNSCALED, "plain16": ec.MODE_FP16_PLAIN, "plainbf": ec.MODE_BF16_PLAIN}
+            "unscaled": ec.MODE_FP16_UNSCALED, "plain16": ec.MODE_FP16_PLAIN, "plainbf": ec.MODE_BF16_PLAIN,
+            "outside": ec.MODE_FP16_OUTSIDE_ACC}
 
 
 def _model(mode, opA, opB):
     """Exact-accumulation model of a mode (FP64 sums of the same low-precision parts)."""
     return {"fp16": lambda: model.gemm_fp16_mode(opA, opB), "bf16": lambda: model.gemm_bf16_mode(opA, opB),
+            "outside": lambda: model.gemm_fp16_mode(opA, opB),
             "markidis": lambda: model.gemm_fp16_mode(opA, opB, products=4, scaled=False),
             "unscaled": lambda: model.gemm_fp16_mode(opA, opB, products=3, scaled=False),
             "plain16": lambda: model.gemm_plain(opA, opB, "fp16"),
@@ -190,7 +192,7 @@ def test_invalid_arguments_are_rejected():
     dA, dB = to_device(A), to_device(B)
     dC = empty_colmajor(M, N, fill=1.0)
     bad_calls = [
-        dict(transA=7), dict(transB=-1), dict(mode=6), dict(mode=-1), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
+        dict(transA=7), dict(transB=-1), dict(mode=99), dict(mode=-1), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
         dict(ldc=M - 1), dict(A=None), dict(B=None), dict(C=None),
     ]
     base = dict(transA=ec.OP_N, transB=ec.OP_N, M=M, N=N, K=K, alpha=1.0, A=dA, lda=M, B=dB, ldb=K, beta=0.0, C=dC,
@@ -404,3 +406,14 @@ def test_prescaling_brings_small_inputs_into_the_fp16_window():
     with pytest.raises(ec.EcgemmError):
         h.set_scaling(100, 100)
     h.destroy()
+
+
+def test_accumulating_outside_the_matrix_unit_as_the_paper_does():
+    """The paper's listing verbatim (zeroed temporary, FP32 vector adds every k step): meets the same bar as the
+    default FP16 mode; one FP32 rounding per 16 products instead of per 8, so the element-wise bound holds too."""
+    _check("N", "N", 300, 200, 77, 1.5, 0.5, "outside", "urand", seed=1, pad=3)
+    _check("T", "N", 512, 384, 4096, 1.0, 0.0, "outside", "urand", seed=2)
+    rows = si.sample_indices(4096, 128, seed=3)
+    r_out, r_cpu = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "outside", "urand", seed=0, rows=rows)
+    r_def, _ = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "fp16", "urand", seed=0, rows=rows)
+    assert r_out < r_cpu and r_def < r_cpu          # neither needs the detour to beat the FP32 sum here
