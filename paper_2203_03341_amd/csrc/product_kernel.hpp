@@ -148,7 +148,10 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
 
   // ---- which tile, which K range
   const int tiles = p.tiles_m * p.tiles_n;
-  int pid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+#ifndef ECGEMM_XCD_REMAP
+#define ECGEMM_XCD_REMAP 1
+#endif
+  int pid = ECGEMM_XCD_REMAP ? xcd_contiguous_id(blockIdx.x, gridDim.x) : (int)blockIdx.x;
   const int split = pid / tiles;
   pid -= split * tiles;
 #ifndef ECGEMM_GROUP_M
