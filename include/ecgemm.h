@@ -78,7 +78,7 @@ ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle);
  * Default: the null stream. */
 ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 
-/* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit
+/* Bytes of device workspace ecgemm_sgemm needs for this problem (the handle is not used and may be NULL): the split operands in matrix-unit
  * fragment order, zero-padded to whole tiles, plus the partial sums when K is divided among blocks.
  * `bytes` is a host pointer. */
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
@@ -139,6 +139,19 @@ ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int
  */
 ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int64_t cols, const float *src, int64_t ld,
                                       int *min_exponent, int *max_exponent);
+
+/*
+ * Picks settings for a product from the data (synchronous, reads A and B once): if the non-zero elements of each operand
+ * span at most 29 binades, ECGEMM_MODE_FP16_SPLIT with the pre-scaling exponents that put each operand's largest binade
+ * at 2^14 (every element then sits in the window where the FP16 pair is fully precise: the paper's Type 1 after its
+ * "additional scaling"); otherwise ECGEMM_MODE_BF16_FULL with no scaling (Types 2 to 4).  The caller passes the
+ * exponents to ecgemm_set_scaling and the mode to ecgemm_sgemm.  Conservative: inputs with a few tiny elements (such
+ * as uniform(-1, 1) draws) also do well in FP16 mode, because the residual of Eq. eval-matmul is dominated by the
+ * large ones.  A, B, lda, ldb, transA, transB, M, N, K as in ecgemm_sgemm; mode and the two exponents are host pointers.
+ */
+ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
+                                   int64_t K, const float *A, int64_t lda, const float *B, int64_t ldb,
+                                   ecgemm_mode_t *mode, int *log2_scale_a, int *log2_scale_b);
 
 /*
  * Step 1 alone (Eqs. corr-1-1024 .. corr-4-1024 / the BF16 three-term split), for inspection and tests.

@@ -20,7 +20,7 @@ MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_F
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -39,6 +39,8 @@ def _load() -> ctypes.CDLL:
                                  ctypes.c_int]
     lib.ecgemm_set_scaling.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.ecgemm_exponent_range.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+    lib.ecgemm_choose_mode.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64,
+                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_product.argtypes = [vp, i64, i64, i64, f32, vp, vp, f32, vp, i64, ctypes.c_int]
     lib.ecgemm_split.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_split_size.argtypes = [i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
@@ -125,6 +127,13 @@ class Handle:
         self._check(_lib.ecgemm_exponent_range(self._h, rows, cols, _ptr(src), ld, ctypes.byref(lo), ctypes.byref(hi)))
         return lo.value, hi.value
 
+    def choose_mode(self, transA: int, transB: int, M: int, N: int, K: int, A, lda: int, B, ldb: int):
+        """(mode, log2_scale_a, log2_scale_b) recommended for this product."""
+        mode, sa, sb = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        self._check(_lib.ecgemm_choose_mode(self._h, transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, ctypes.byref(mode),
+                                            ctypes.byref(sa), ctypes.byref(sb)))
+        return mode.value, sa.value, sb.value
+
     def product(self, M: int, N: int, K: int, alpha: float, packedA, packedB, beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_product(self._h, M, N, K, alpha, _ptr(packedA), _ptr(packedB), beta, _ptr(C), ldc, mode))
 
@@ -148,6 +157,15 @@ class Handle:
         calls, a, b = ctypes.c_int(), ctypes.c_float(), ctypes.c_float()
         self._check(_lib.ecgemm_get_timing(self._h, ctypes.byref(calls), ctypes.byref(a), ctypes.byref(b)))
         return calls.value, a.value, b.value
+
+
+def workspace_size(M: int, N: int, K: int, mode: int) -> int:
+    """ecgemm_workspace_size without a handle (none is needed)."""
+    out = ctypes.c_size_t()
+    st = _lib.ecgemm_workspace_size(None, M, N, K, mode, ctypes.byref(out))
+    if st != OK:
+        raise EcgemmError(st, "ecgemm_workspace_size")
+    return out.value
 
 
 def split_size(rows: int, depth: int, mode: int) -> int:

@@ -305,7 +305,6 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void* hip_stream) {
 
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
                                       ecgemm_mode_t mode, size_t* bytes) {
-  if (!handle) return ECGEMM_ERR_INVALID_ARG;
   if (!bytes || M < 0 || N < 0 || K < 0 || !valid_mode(mode))
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_workspace_size: bad argument");
   *bytes = (M == 0 || N == 0 || K == 0) ? 0 : make_plan(M, N, K, mode).total_bytes;
@@ -372,6 +371,34 @@ ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int6
   }
   *min_exponent = host[0];
   *max_exponent = host[1];
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
+                                   int64_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
+                                   ecgemm_mode_t* mode, int* log2_scale_a, int* log2_scale_b) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!mode || !log2_scale_a || !log2_scale_b || !valid_op(transA) || !valid_op(transB) || M < 0 || N < 0 || K < 0)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_choose_mode: bad argument");
+  int lo[2] = {0, 0}, hi[2] = {0, 0};
+  ecgemm_status_t st = ecgemm_exponent_range(handle, transA == ECGEMM_OP_N ? M : K, transA == ECGEMM_OP_N ? K : M, A, lda,
+                                             &lo[0], &hi[0]);
+  if (st != ECGEMM_OK) return st;
+  st = ecgemm_exponent_range(handle, transB == ECGEMM_OP_N ? K : N, transB == ECGEMM_OP_N ? N : K, B, ldb, &lo[1], &hi[1]);
+  if (st != ECGEMM_OK) return st;
+  // The FP16 pair is fully precise for magnitudes 2^-14 .. 2^15 (top binade kept one below the saturation point):
+  // an operand fits if its non-zero elements span at most 29 binades; its top binade is then moved to 2^14.
+  int scale[2] = {0, 0};
+  bool fits = true;
+  for (int i = 0; i < 2; ++i) {
+    if (lo[i] > hi[i]) continue;  // no non-zero finite element
+    if (hi[i] - lo[i] > 28) fits = false;
+    scale[i] = 14 - hi[i];
+  }
+  if (fits && (std::abs(scale[0]) > 126 || std::abs(scale[1]) > 126 || std::abs(scale[0] + scale[1]) > 126)) fits = false;
+  *mode = fits ? ECGEMM_MODE_FP16_SPLIT : ECGEMM_MODE_BF16_FULL;
+  *log2_scale_a = fits ? scale[0] : 0;
+  *log2_scale_b = fits ? scale[1] : 0;
   return ECGEMM_OK;
 }
 

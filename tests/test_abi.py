@@ -43,3 +43,25 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+
+
+def test_workspace_plan_needs_no_gpu():
+    """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and K divided
+    among blocks (with one partial C per slice) only when the tiles alone cannot fill the chip."""
+    import paper_2203_03341_amd as ec
+    n = 16384
+    assert ec.workspace_size(n, n, n, ec.MODE_FP16_SPLIT) == 2 * n * n * 4              # two packed operands, no split-K
+    assert ec.workspace_size(n, n, n, ec.MODE_BF16_FULL) == 2 * n * n * 6
+    assert ec.workspace_size(n, n, n, ec.MODE_FP16_PLAIN) == 2 * n * n * 2
+    assert ec.workspace_size(1, 1, 1, ec.MODE_FP16_SPLIT) == 2 * 256 * 32 * 4
+    assert ec.workspace_size(0, 5, 5, ec.MODE_FP16_SPLIT) == 0
+    deep = ec.workspace_size(1024, 1024, 65536, ec.MODE_FP16_SPLIT)
+    operands = 2 * 1024 * 65536 * 4
+    slices = (deep - operands) // (1024 * 1024 * 4)
+    assert deep > operands and (deep - operands) % (1024 * 1024 * 4) == 0 and 2 <= slices <= 64
+    assert ec.workspace_size(4095, 3001, 5003, ec.MODE_BF16_FULL) == (4096 + 3072) * 5024 * 6
+    import pytest
+    with pytest.raises(ec.EcgemmError):
+        ec.workspace_size(-1, 1, 1, ec.MODE_FP16_SPLIT)
+    with pytest.raises(ec.EcgemmError):
+        ec.workspace_size(1, 1, 1, 99)

@@ -417,3 +417,27 @@ def test_accumulating_outside_the_matrix_unit_as_the_paper_does():
     r_out, r_cpu = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "outside", "urand", seed=0, rows=rows)
     r_def, _ = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "fp16", "urand", seed=0, rows=rows)
     assert r_out < r_cpu and r_def < r_cpu          # neither needs the detour to beat the FP32 sum here
+
+
+def test_choose_mode_follows_the_papers_types():
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    n = 256
+
+    def choose(ra, rb):
+        A, B = _inputs(n, n, n, "N", "T", (ra, rb), 0)
+        return h.choose_mode(ec.OP_N, ec.OP_T, n, n, n, to_device(A), n, to_device(B), n)
+
+    assert choose((-15, 13), (-15, 13)) == (ec.MODE_FP16_SPLIT, 1, 1)            # Type 1: fits as it is
+    assert choose((-35, -15), (-35, -15)) == (ec.MODE_FP16_SPLIT, 29, 29)        # Type 3: fits after scaling
+    assert choose((-15, 14), (-100, -35))[0] == ec.MODE_BF16_FULL                 # Type 2: one operand spans 66 binades
+    assert choose((-100, 100), (-15, 14))[0] == ec.MODE_BF16_FULL
+    # the recommendation meets the bar when followed
+    A, B = _inputs(n, n, n, "N", "T", ((-60, -40), (5, 30)), 1)
+    mode, sa, sb = h.choose_mode(ec.OP_N, ec.OP_T, n, n, n, to_device(A), n, to_device(B), n)
+    assert (mode, sa, sb) == (ec.MODE_FP16_SPLIT, 54, -16)
+    h.set_scaling(sa, sb)
+    got = _gpu_sgemm("N", "T", n, n, n, 1.0, A, B, 0.0, None, "fp16", handle=h)[:n, :n]
+    c64 = gemm.sgemm_fp64_ref("N", "T", n, n, n, 1.0, A, B)
+    assert gemm.relative_residual(c64, got) <= RATIO * gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "T", n, n, n, 1.0, A, B))
+    h.destroy()
