@@ -441,3 +441,46 @@ def test_choose_mode_follows_the_papers_types():
     c64 = gemm.sgemm_fp64_ref("N", "T", n, n, n, 1.0, A, B)
     assert gemm.relative_residual(c64, got) <= RATIO * gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "T", n, n, n, 1.0, A, B))
     h.destroy()
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_operand_with_more_than_2_pow_31_elements(mode):
+    """A is 70000 x 32768 (2.3e9 elements, 8.5 GiB; its packed form crosses 4 GiB byte offsets as well): catches
+    32-bit index arithmetic anywhere on the path.  A is drawn on the device from torch's seeded generator (moving
+    8.5 GiB through numpy would take minutes); the oracle gets the sampled rows of that same A."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 70000, 192, 32768
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1234)
+    dA = torch.empty((K, M), dtype=torch.float32, device="cuda")          # column-major M x K, lda = M
+    dA.uniform_(-1.0, 1.0, generator=gen)
+    B = si.urand(K, N, 7, si.ID_B)
+    dB = to_device(B)
+    dC = empty_colmajor(M, N, fill=float("nan"))
+    h = ec.Handle()
+    h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, _modes()[mode])
+    torch.cuda.synchronize()
+    rows = np.concatenate([si.sample_indices(M, 40, seed=5), np.array([0, 65535, 65536, M - 1])])
+    A_rows = np.asfortranarray(dA[:, torch.from_numpy(rows).cuda()].T.contiguous().cpu().numpy())   # len(rows) x K
+    got = dC[:, torch.from_numpy(rows).cuda()].T.contiguous().cpu().numpy()                         # len(rows) x N
+    h.destroy()
+    del dA
+    torch.cuda.empty_cache()
+    c64 = gemm.sgemm_fp64_ref("N", "N", len(rows), N, K, 1.0, A_rows, B)
+    c32 = gemm.sgemm_fp32_naive("N", "N", len(rows), N, K, 1.0, A_rows, B)
+    assert np.all(np.isfinite(got))
+    assert gemm.relative_residual(c64, got) <= RATIO * gemm.relative_residual(c64, c32)
+    mdl = _model(mode, A_rows, gemm.logical("N", B, K, N))
+    mag = np.abs(A_rows).astype(np.float64) @ np.abs(B[:K, :N]).astype(np.float64)
+    assert np.all(np.abs(got - mdl) <= (K / 8 + 4) * 2.0 ** -23 * mag)
+
+
+def test_sizes_beyond_the_supported_depth_are_refused():
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    dummy = empty_colmajor(8, 8, fill=0.0)
+    with pytest.raises(ec.EcgemmError) as ei:       # nothing is read or allocated before the check
+        h.sgemm(ec.OP_T, ec.OP_N, 4, 4, 1 << 26, 1.0, dummy, 1 << 26, dummy, 1 << 26, 0.0, dummy, 4, ec.MODE_FP16_SPLIT)
+    assert ei.value.status == ec.ERR_INVALID_ARG
+    h.destroy()

@@ -114,3 +114,14 @@ def test_split_of_comparison_methods(mode, op):
         got = _run(op, store, rows, depth, mode)
         want = _expected(op, store, rows, depth, mode)
         assert got.shape == want.shape and np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("mode_bf16", [False, True])
+def test_split_of_a_large_operand(mode_bf16):
+    """2048 x 3000 in both orientations: every block position of a many-tile grid, bit for bit."""
+    for op in ("N", "T"):
+        rows, depth = 2048, 3000
+        sr, sc = (rows, depth) if op == "N" else (depth, rows)
+        store = si.exp_rand(sr, sc, -30, 20, 9, si.ID_B)
+        got = _run(op, store, rows, depth, mode_bf16)
+        assert np.array_equal(got, _expected(op, store, rows, depth, mode_bf16))
