@@ -31,9 +31,9 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 # HBM bytes per product-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
 # workload; None where no counter run has been made for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    # FETCH_SIZE 1.719e7 KiB x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE 1.0486e6 KiB x 1.0
-    "c3_16384_fp16_exprand15": 3.63e10,      # profiles/product_kernel_fp16_16384cubed.md
-    "c4_8192_bf16_widerange": 7.01e9,        # profiles/product_kernel_bf16_8192cubed.md
+    # FETCH_SIZE x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE x 1.0, in bytes
+    "c3_16384_fp16_exprand15": 3.66e10,      # profiles/product_kernel_fp16_16384cubed.md: 35.5 GB + 1.07 GB
+    "c4_8192_bf16_widerange": 7.0e9,         # profiles/product_kernel_bf16_8192cubed.md
 }
 
 WORKLOADS = {

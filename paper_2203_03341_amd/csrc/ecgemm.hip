@@ -493,7 +493,18 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
   char* b_packed = ws + pl.a_bytes;
   float* partials = pl.k_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
 
-  TimedCall tc{};
+  // Events for the optional timing go back to the handle's pool whenever the call does not complete.
+  struct EventLease {
+    ecgemm_handle_t h;
+    TimedCall tc{};
+    bool keep = false;
+    ~EventLease() {
+      if (keep) return;
+      for (hipEvent_t e : {tc.start, tc.split_done, tc.product_done})
+        if (e) h->free_events.push_back(e);
+    }
+  } lease{h};
+  TimedCall& tc = lease.tc;
   if (h->timing) {
     tc.start = take_event(h);
     tc.split_done = take_event(h);
@@ -517,6 +528,7 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
   if (h->timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
     h->timed.push_back(tc);
+    lease.keep = true;
   }
   return ECGEMM_OK;
 }
