@@ -22,6 +22,7 @@ struct TimedCall {
 
 struct ecgemm_context {
   int device = 0;
+  int compute_units = 256;
   hipStream_t stream = nullptr;
   void* own_workspace = nullptr;
   size_t own_bytes = 0;
@@ -59,7 +60,15 @@ typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS
 typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3> PlainFp16Config;
 typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3> PlainBf16Config;
 typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> OutsideConfig;
-constexpr int kBM = 256, kBN = 128;
+// 128 x 128 tiles, two workgroups per CU: twice the LDS and L2 traffic per flop, but one workgroup's epilogue and
+// pipeline fill hide behind the other's main loop.  Used for shallow K, where those fixed costs dominate.
+typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 2, 2, 2> SmallFp16Config;   // 2 x 32 KiB of LDS per workgroup
+typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> SmallBf16Config;    // 3 x 24 KiB of LDS per workgroup
+#ifndef ECGEMM_SMALL_TILE_MAX_K
+#define ECGEMM_SMALL_TILE_MAX_K 512
+#endif
+static_assert(SmallFp16Config::BK == Fp16Config::BK && SmallBf16Config::BK == Bf16Config::BK, "stage depths");
+
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -81,6 +90,8 @@ size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
 }
 
 struct Plan {
+  bool small_tiles;  // 128 x 128, two workgroups per CU
+  int bm, bn;
   int64_t Mp, Np, Kp;
   int tiles_m, tiles_n, k_tiles, k_splits;
   size_t a_bytes, b_bytes, partial_bytes, total_bytes;
@@ -93,8 +104,11 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   pl.Mp = round_up(M, kRowPad);
   pl.Np = round_up(N, kRowPad);
   pl.Kp = round_up(K, kDepthPad);
-  pl.tiles_m = (int)((M + kBM - 1) / kBM);
-  pl.tiles_n = (int)((N + kBN - 1) / kBN);
+  pl.small_tiles = (mode == ECGEMM_MODE_FP16_SPLIT || mode == ECGEMM_MODE_BF16_FULL) && pl.Kp <= ECGEMM_SMALL_TILE_MAX_K;
+  pl.bm = pl.small_tiles ? 128 : 256;
+  pl.bn = 128;
+  pl.tiles_m = (int)((M + pl.bm - 1) / pl.bm);
+  pl.tiles_n = (int)((N + pl.bn - 1) / pl.bn);
   pl.k_tiles = (int)(pl.Kp / stage_depth_of(mode));
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   int splits = 1;
@@ -182,7 +196,16 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.partials = partials;
   pp.Mp = pl.Mp;
   pp.Np = pl.Np;
-  const dim3 grid((unsigned)((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits));
+  // persistent grid: one block per CU at most, a multiple of the 8 XCDs
+  const int64_t items = (int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits;
+  const int64_t slots = (int64_t)h->compute_units * (pl.small_tiles ? 2 : 1);
+  const dim3 grid((unsigned)(items < slots ? round_up(items, 8) : slots));
+  if (pl.small_tiles) {
+    if (mode == ECGEMM_MODE_BF16_FULL)
+      hipLaunchKernelGGL(product_kernel<SmallBf16Config>, grid, dim3(SmallBf16Config::THREADS), 0, h->stream, pp);
+    else
+      hipLaunchKernelGGL(product_kernel<SmallFp16Config>, grid, dim3(SmallFp16Config::THREADS), 0, h->stream, pp);
+  } else
   switch (mode) {
     case ECGEMM_MODE_FP16_SPLIT: hipLaunchKernelGGL(product_kernel<Fp16Config>, grid, dim3(Fp16Config::THREADS), 0, h->stream, pp); break;
     case ECGEMM_MODE_BF16_FULL: hipLaunchKernelGGL(product_kernel<Bf16Config>, grid, dim3(Bf16Config::THREADS), 0, h->stream, pp); break;
@@ -278,6 +301,7 @@ ecgemm_status_t ecgemm_create(ecgemm_handle_t* handle) {
   ecgemm_context* ctx = new (std::nothrow) ecgemm_context();
   if (!ctx) return ECGEMM_ERR_ALLOC;
   ctx->device = device;
+  ctx->compute_units = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
   *handle = ctx;
   return ECGEMM_OK;
 }

@@ -12,7 +12,7 @@
 // The accumulate itself rounds to nearest even on gfx950 (measured), so the paper's
 // zero-accumulator trick against round-toward-zero is not needed here.
 //
-// Data flow per workgroup (one per CU, 4 waves, one per SIMD, up to 512 registers each):
+// Data flow per workgroup (persistent, one per CU, 4 waves, one per SIMD, up to 512 registers each):
 //   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS double buffer (no VGPR staging)
 //   LDS --ds_read_b128--> operand fragments, double buffered in registers
 //   v_mfma_f32_32x32x16_{f16,bf16} --> 2 x (TM x TN) accumulators of 16 floats per lane
@@ -93,8 +93,9 @@ __host__ __device__ constexpr int products_of(int method) {
        : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : 1;
 }
 
-template <int METHOD, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_>
+template <int METHOD, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_, int BLOCKS_PER_CU_ = 1>
 struct ProductConfig {
+  static constexpr int BLOCKS_PER_CU = BLOCKS_PER_CU_;            // resident workgroups per CU (registers and LDS permitting)
   static constexpr int kMethod = METHOD;
   static constexpr bool kBf16 = split_is_bf16(split_kind_of(METHOD));
   static constexpr int NP = parts_of_split(split_kind_of(METHOD));  // parts per value
@@ -114,22 +115,11 @@ struct ProductConfig {
   static constexpr int MFMAS = TM * TN * PRODUCTS;                // matrix instructions per wave per k step
   static_assert(K_STEPS == 1 || K_STEPS == 2, "one or two k steps per stage");
   static_assert(STAGES >= 2 && (STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
-  static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(LDS_BYTES * BLOCKS_PER_CU <= 160 * 1024, "LDS budget");
   static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shapes");
   static_assert(kRowPad % BM == 0 && kRowPad % BN == 0, "padded operands must hold whole tiles");
   static_assert(A_CHUNKS % WAVES == 0 && B_CHUNKS % WAVES == 0, "chunks per wave");
 };
-
-// Blocks are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD one
-// contiguous range of the tile order, and walk tiles in column groups so that the ~32 tiles
-// an XCD works on at one time share a few A and B panels.
-__device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks) {
-  constexpr int kXcds = 8;
-  const int xcd = bid % kXcds, local = bid / kXcds;
-  const int base = nblocks / kXcds, rem = nblocks % kXcds;
-  const int start = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
-  return start + local;
-}
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_lds() {  // at most N global loads of this wave still in flight
@@ -137,7 +127,7 @@ __device__ __forceinline__ void wait_loads_and_lds() {  // at most N global load
 }
 
 template <class Cfg>
-__global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductParams p) {
+__global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kernel(const ProductParams p) {
   constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::STAGES;
   typedef typename Mfma<Cfg::kBf16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
@@ -146,43 +136,71 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave_m = wave % Cfg::WAVES_M, wave_n = wave / Cfg::WAVES_M;
 
-  // ---- which tile, which K range
+  // ---- work items.  The grid is persistent: at most one block per CU, each walking through several items
+  // (an item = one output tile x one K slice).  Blocks are dealt round-robin to the 8 XCDs, so block b lives on
+  // XCD b % 8; that XCD owns one contiguous range of items and its blocks stride through it together, so the
+  // ~32 tiles an XCD works on at any time are neighbours that share A and B panels in its L2.
+  struct Work {
+    int tile_m, tile_n, split, kt_begin, kt_count;
+  };
   const int tiles = p.tiles_m * p.tiles_n;
 #ifndef ECGEMM_XCD_REMAP
 #define ECGEMM_XCD_REMAP 1
 #endif
-  int pid = ECGEMM_XCD_REMAP ? xcd_contiguous_id(blockIdx.x, gridDim.x) : (int)blockIdx.x;
-  const int split = pid / tiles;
-  pid -= split * tiles;
 #ifndef ECGEMM_GROUP_M
 #define ECGEMM_GROUP_M 4
 #endif
-  constexpr int kGroupM = ECGEMM_GROUP_M;
-  const int group_size = kGroupM * p.tiles_n;
-  const int group = pid / group_size;
-  const int first_m = group * kGroupM;
-  const int group_m = min(p.tiles_m - first_m, kGroupM);
-  const int tile_m = first_m + (pid % group_size) % group_m;
-  const int tile_n = (pid % group_size) / group_m;
-  const int kt_per_split = (p.k_tiles + p.k_splits - 1) / p.k_splits;
-  const int kt_begin = split * kt_per_split;
-  const int kt_count = max(0, min(p.k_tiles, kt_begin + kt_per_split) - kt_begin);
+  auto locate = [&](int item) {
+    Work w;
+    w.split = item / tiles;
+    const int pid = item - w.split * tiles;
+    constexpr int kGroupM = ECGEMM_GROUP_M;
+    const int group_size = kGroupM * p.tiles_n;
+    const int group = pid / group_size;
+    const int first_m = group * kGroupM;
+    const int group_m = min(p.tiles_m - first_m, kGroupM);
+    w.tile_m = first_m + (pid % group_size) % group_m;
+    w.tile_n = (pid % group_size) / group_m;
+    const int kt_per_split = (p.k_tiles + p.k_splits - 1) / p.k_splits;
+    w.kt_begin = w.split * kt_per_split;
+    w.kt_count = max(0, min(p.k_tiles, w.kt_begin + kt_per_split) - w.kt_begin);
+    return w;
+  };
+  const int items = tiles * p.k_splits;
+  int item, item_end, item_stride;
+  if (ECGEMM_XCD_REMAP) {
+    constexpr int kXcds = 8;  // gridDim.x is a multiple of 8
+    const int xcd = blockIdx.x % kXcds, base = items / kXcds, rem = items % kXcds;
+    const int start = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
+    item = start + blockIdx.x / kXcds;
+    item_end = start + base + (xcd < rem ? 1 : 0);
+    item_stride = gridDim.x / kXcds;
+  } else {
+    item = blockIdx.x;
+    item_end = items;
+    item_stride = gridDim.x;
+  }
+  if (item >= item_end) return;
+  Work work = locate(item);
 
   // ---- global -> LDS: wave w moves the 1 KiB chunks w, w + WAVES, ... of a stage; A_CHUNKS is a
   // multiple of WAVES, so whether load i fetches from A or from B is known at compile time.  Source
   // addresses are wave-uniform (scalar registers) plus 16 bytes per lane.
   constexpr int kLoads = Cfg::LOADS, kALoads = Cfg::A_CHUNKS / Cfg::WAVES;
   const unsigned lane_bytes = lane * 16;
-  unsigned k_off = 0;  // bytes from the first tile of this block to the next tile to request
+  unsigned k_off = 0;  // bytes from the first tile of the current item to the next tile to request
   const char* src[kLoads];
+  auto point_sources = [&](const Work& w) {
+    k_off = 0;
 #pragma unroll
-  for (int i = 0; i < kLoads; ++i) {
-    const bool from_a = i < kALoads;
-    const int c = (from_a ? i : i - kALoads) * Cfg::WAVES + wave;
-    const int64_t first_row_block = from_a ? (int64_t)tile_m * (Cfg::BM / 32) : (int64_t)tile_n * (Cfg::BN / 32);
-    src[i] = (from_a ? p.a_packed : p.b_packed) + (first_row_block + c / Cfg::ROW_CHUNKS) * p.row_block_bytes +
-             (int64_t)kt_begin * (Cfg::ROW_CHUNKS * 1024) + (c % Cfg::ROW_CHUNKS) * 1024;
-  }
+    for (int i = 0; i < kLoads; ++i) {
+      const bool from_a = i < kALoads;
+      const int c = (from_a ? i : i - kALoads) * Cfg::WAVES + wave;
+      const int64_t first_row_block = from_a ? (int64_t)w.tile_m * (Cfg::BM / 32) : (int64_t)w.tile_n * (Cfg::BN / 32);
+      src[i] = (from_a ? p.a_packed : p.b_packed) + (first_row_block + c / Cfg::ROW_CHUNKS) * p.row_block_bytes +
+               (int64_t)w.kt_begin * (Cfg::ROW_CHUNKS * 1024) + (c % Cfg::ROW_CHUNKS) * 1024;
+    }
+  };
   auto issue_stage = [&](int buf) {  // requests the next tile not yet requested, then moves on by one tile
     char* stage = lds + buf * Cfg::STAGE_BYTES + wave * 1024;
     // one 32-bit vector offset per tile; kept opaque inside this block so that every address folds to
@@ -215,15 +233,17 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   };
 
   float16_t acc_main[TM][TN], acc_corr[TM][TN];
+  auto clear_accumulators = [&]() {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        acc_main[i][j][v] = 0.0f;
-        acc_corr[i][j][v] = 0.0f;
-      }
+        for (int v = 0; v < 16; ++v) {
+          acc_main[i][j][v] = 0.0f;
+          acc_corr[i][j][v] = 0.0f;
+        }
+  };
 
   // One product at a time over all TM x TN tiles: consecutive instructions never share an accumulator.
   auto multiply = [&](int set) {
@@ -297,13 +317,22 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
   };
   typedef std::integral_constant<int, (S - 2) * Cfg::LOADS> steady_t;
 
-  // ---- main loop.  Tile t lives in buffer t % STAGES; tiles t + 1 .. t + STAGES - 1 are in flight while
-  // tile t is multiplied.  The barrier of iteration t comes when every wave holds the last fragments of
+  // ---- main loop of one item.  Tile t lives in buffer t % STAGES; tiles t + 1 .. t + STAGES - 1 are in flight
+  // while tile t is multiplied.  The barrier of iteration t comes when every wave holds the last fragments of
   // buffer t % STAGES in registers: the buffer is then refilled with tile t + STAGES, and the first
   // fragments of tile t + 1 are fetched under the matrix instructions that follow.
-  if (kt_count > 0) {
-    const int prefetched = min(S, kt_count);
+  auto request_first_stages = [&](const Work& w) {
+    point_sources(w);
+    const int prefetched = min(S, w.kt_count);
     for (int s = 0; s < prefetched; ++s) issue_stage(s);
+  };
+  request_first_stages(work);
+  while (true) {
+  const int kt_count = work.kt_count;
+  clear_accumulators();
+  if (kt_count > 0) {
+    // (stores of the previous item's epilogue may still be in flight behind the loads: waiting for "all but the
+    // newest n operations" then waits for more than needed, never for less)
     if (kt_count >= S) wait_loads_and_lds<(S - 1) * Cfg::LOADS>(); else wait_loads_and_lds<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -386,8 +415,20 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
     }
   }
 
+  // ---- next item: once every wave is done with the LDS ring, its first stages are requested, so that they travel
+  // while this item's results are written out.
+  const Work done = work;
+  const int next_item = item + item_stride;
+  const bool more = next_item < item_end;
+  if (more) {
+    stage_barrier(none_t{});
+    work = locate(next_item);
+    request_first_stages(work);
+  }
+
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
+  const int tile_m = done.tile_m, tile_n = done.tile_n, split = done.split;
   const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
   const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane >> 5);
@@ -420,6 +461,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, 1) product_kernel(const ProductP
       }
     });
   }
+  if (!more) break;
+  item = next_item;
+  }  // items
 }
 
 // One v_mfma_f32_32x32x16 per wave on caller-supplied registers, for tests that pin down what the matrix unit does
