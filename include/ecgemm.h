@@ -121,8 +121,8 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
- * Power-of-two pre-scaling (the "additional scaling before matrix-matrix multiplication" the paper asks for at the
- * end of section "Effect of the exponent range of input matrices" when all elements are small).  From now on
+ * Power-of-two pre-scaling: the remedy the paper names, at the end of section "Effect of the exponent range of input
+ * matrices", for inputs whose elements are all too small for the FP16 pair.  From now on
  * ecgemm_sgemm on this handle splits op(A) * 2^log2_scale_a and op(B) * 2^log2_scale_b and multiplies the product by
  * 2^-(log2_scale_a + log2_scale_b) before alpha / beta.  Multiplying by a power of two is exact, so this only moves
  * the inputs inside the exponent window of the FP16 pair (2^-14 .. 2^16); the caller must pick exponents that neither
@@ -143,8 +143,8 @@ ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int6
 /*
  * Picks settings for a product from the data (synchronous, reads A and B once): if the non-zero elements of each operand
  * span at most 29 binades, ECGEMM_MODE_FP16_SPLIT with the pre-scaling exponents that put each operand's largest binade
- * at 2^14 (every element then sits in the window where the FP16 pair is fully precise: the paper's Type 1 after its
- * "additional scaling"); otherwise ECGEMM_MODE_BF16_FULL with no scaling (Types 2 to 4).  The caller passes the
+ * at 2^14 (every element then sits in the window where the FP16 pair is fully precise, the paper's Type 1 situation);
+ * otherwise ECGEMM_MODE_BF16_FULL with no scaling (Types 2 to 4).  The caller passes the
  * exponents to ecgemm_set_scaling and the mode to ecgemm_sgemm.  Conservative: inputs with a few tiny elements (such
  * as uniform(-1, 1) draws) also do well in FP16 mode, because the residual of Eq. eval-matmul is dominated by the
  * large ones.  A, B, lda, ldb, transA, transB, M, N, K as in ecgemm_sgemm; mode and the two exponents are host pointers.

@@ -12,8 +12,9 @@
 // The accumulate itself rounds to nearest even on gfx950 (measured), so the paper's
 // zero-accumulator trick against round-toward-zero is not needed here.
 //
-// Data flow per workgroup (persistent, one per CU, 4 waves, one per SIMD, up to 512 registers each):
-//   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS double buffer (no VGPR staging)
+// Data flow per workgroup (persistent; one per CU, 4 waves, one per SIMD, up to 512 registers each, for the
+// 256 x 128 tile; two per CU for the 128 x 128 tile used when K is shallow):
+//   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS ring of 2 to 4 stages (no VGPR staging)
 //   LDS --ds_read_b128--> operand fragments, double buffered in registers
 //   v_mfma_f32_32x32x16_{f16,bf16} --> 2 x (TM x TN) accumulators of 16 floats per lane
 // Operands are stored in fragment order (see split_kernels.hpp), so both hops are linear
@@ -42,7 +43,7 @@ struct ProductParams {
   const char* a_packed;     // [Mp/32][k_steps][NP][64][8] 16-bit
   const char* b_packed;     // [Np/32][k_steps][NP][64][8] 16-bit
   int64_t row_block_bytes;  // k_steps * NP * 1024
-  int k_tiles;              // depth_padded / 32
+  int k_tiles;              // depth_padded / (16 * K_STEPS): LDS stages along K
   int k_splits;             // blocks along K per output tile
   int tiles_m, tiles_n;
   int64_t M, N, ldc;

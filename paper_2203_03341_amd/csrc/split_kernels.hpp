@@ -4,7 +4,8 @@
 // BF16 mode (three exact terms, stands in for the paper's TF32 pair on hardware without a TF32
 // matrix instruction):  b0 = toBF16(v), b1 = toBF16(v - b0), b2 = toBF16(v - b0 - b1)
 // Conversions round to nearest even (the hardware converts) and saturate: a finite input never
-// yields an infinite part.  An infinite input keeps only its high part.
+// yields an infinite part.  An infinite input keeps only its high part.  SplitKind lists the other
+// splits the kernels can produce for the paper's comparison methods.
 //
 // Output layout ("fragment order"), 16-bit elements:
 //     packed[row_block][k_step][part][lane][8],  row_block = r / 32, k_step = k / 16,
