@@ -32,8 +32,8 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 # workload; None where no counter run has been made for that workload.
 MEASURED_TRAFFIC_BYTES = {
     # FETCH_SIZE x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE x 1.0, in bytes
-    "c3_16384_fp16_exprand15": 3.66e10,      # profiles/product_kernel_fp16_16384cubed.md: 35.5 GB + 1.07 GB
-    "c4_8192_bf16_widerange": 7.0e9,         # profiles/product_kernel_bf16_8192cubed.md
+    "c3_16384_fp16_exprand15": 3.86e10,      # profiles/product_kernel_fp16_16384cubed.md: 37.5 GB + 1.11 GB
+    "c4_8192_bf16_widerange": 7.1e9,         # profiles/product_kernel_bf16_8192cubed.md: 6.8 GB + 0.29 GB
 }
 
 WORKLOADS = {

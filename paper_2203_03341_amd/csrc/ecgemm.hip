@@ -67,6 +67,11 @@ typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> SmallBf16Confi
 #ifndef ECGEMM_SMALL_TILE_MAX_K
 #define ECGEMM_SMALL_TILE_MAX_K 512
 #endif
+// Deepest K slice per work item for which the 256 x 128 product kernels run as a persistent grid (measured: 1-2 %
+// faster up to here, 1-2 % slower at 16384; the 128 x 128 kernels are never faster as a persistent grid).
+#ifndef ECGEMM_PERSISTENT_MAX_K
+#define ECGEMM_PERSISTENT_MAX_K 4096
+#endif
 static_assert(SmallFp16Config::BK == Fp16Config::BK && SmallBf16Config::BK == Bf16Config::BK, "stage depths");
 
 
@@ -196,10 +201,16 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.partials = partials;
   pp.Mp = pl.Mp;
   pp.Np = pl.Np;
-  // persistent grid: one block per CU at most, a multiple of the 8 XCDs
+  // Grid, always a multiple of the 8 XCDs.  Items of moderate depth on the 256 x 128 kernels: a persistent grid, one
+  // block per CU, each block walking through several items with the next item's loads in flight during its epilogue.
+  // Otherwise one block per item, handed out in order by the hardware as CUs free up, which keeps the tiles an XCD
+  // works on at any time next to each other: blocks of a persistent grid drift apart over long items and lose L2
+  // hits (72 % instead of 82 % at K = 16384), and two co-resident 128 x 128 blocks already cover each other's epilogue.
   const int64_t items = (int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits;
   const int64_t slots = (int64_t)h->compute_units * (pl.small_tiles ? 2 : 1);
-  const dim3 grid((unsigned)(items < slots ? round_up(items, 8) : slots));
+  const int64_t depth_per_item = (pl.Kp + pl.k_splits - 1) / pl.k_splits;
+  const bool persistent = !pl.small_tiles && depth_per_item <= ECGEMM_PERSISTENT_MAX_K;
+  const dim3 grid((unsigned)(items < slots || !persistent ? round_up(items, 8) : slots));
   if (pl.small_tiles) {
     if (mode == ECGEMM_MODE_BF16_FULL)
       hipLaunchKernelGGL(product_kernel<SmallBf16Config>, grid, dim3(SmallBf16Config::THREADS), 0, h->stream, pp);

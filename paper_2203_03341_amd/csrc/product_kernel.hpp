@@ -12,7 +12,7 @@
 // The accumulate itself rounds to nearest even on gfx950 (measured), so the paper's
 // zero-accumulator trick against round-toward-zero is not needed here.
 //
-// Data flow per workgroup (persistent; one per CU, 4 waves, one per SIMD, up to 512 registers each, for the
+// Data flow per workgroup (one per CU, 4 waves, one per SIMD, up to 512 registers each, for the
 // 256 x 128 tile; two per CU for the 128 x 128 tile used when K is shallow):
 //   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS ring of 2 to 4 stages (no VGPR staging)
 //   LDS --ds_read_b128--> operand fragments, double buffered in registers
@@ -137,10 +137,11 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wave_m = wave % Cfg::WAVES_M, wave_n = wave / Cfg::WAVES_M;
 
-  // ---- work items.  The grid is persistent: at most one block per CU, each walking through several items
-  // (an item = one output tile x one K slice).  Blocks are dealt round-robin to the 8 XCDs, so block b lives on
-  // XCD b % 8; that XCD owns one contiguous range of items and its blocks stride through it together, so the
-  // ~32 tiles an XCD works on at any time are neighbours that share A and B panels in its L2.
+  // ---- work items (an item = one output tile x one K slice).  The host launches either one block per item or
+  // a persistent grid of one block per CU whose blocks each walk through several items.  Blocks are dealt
+  // round-robin to the 8 XCDs, so block b lives on XCD b % 8; that XCD owns one contiguous range of items and its
+  // blocks stride through it together, so the ~32 tiles an XCD works on at any time are neighbours that share
+  // A and B panels in its L2.
   struct Work {
     int tile_m, tile_n, split, kt_begin, kt_count;
   };
