@@ -153,19 +153,27 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
   const float prescale = std::ldexp(1.0f, log2_prescale);
   const int64_t Rp = round_up(rows, kRowPad), Kp = round_up(depth, kDepthPad);
   const int64_t k_steps = Kp / 16;
-  if (Rp / 64 > 65535) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 4193280 rows");
-  const dim3 grid((unsigned)(Kp / 32), (unsigned)(Rp / 64)), block(256);
+  const int64_t blocks64 = (Kp / 32) * (Rp / 64);
+  if (blocks64 > 0x7fffffff) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 2^42 elements");
+  const dim3 block(256), grid64((unsigned)blocks64), grid256((unsigned)(blocks64 / 4));
+  const unsigned k_tiles = (unsigned)(Kp / 32);
   unsigned short* out = static_cast<unsigned short*>(packed);
   const bool k_contiguous = op == ECGEMM_OP_T;
-  const bool vec = k_contiguous && (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
+  const bool vec = (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
 #define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                          \
   do {                                                                                                                     \
-    if (!k_contiguous)                                                                                                     \
-      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out); \
+    if (!k_contiguous && vec)                                                                                              \
+      hipLaunchKernelGGL((split_r_contiguous_wide<KIND>), grid256, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
+                         prescale, out, (unsigned)(Rp / 256));                                                             \
+    else if (!k_contiguous)                                                                                                \
+      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, \
+                         out, (unsigned)(Rp / 64));                                                                        \
     else if (vec)                                                                                                          \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out); \
+      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
+                         prescale, out, k_tiles);                                                                          \
     else                                                                                                                   \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, out);\
+      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,    \
+                         prescale, out, k_tiles);                                                                          \
   } while (0)
   switch (split_kind_of((int)mode)) {
     case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;

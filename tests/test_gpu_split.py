@@ -55,6 +55,8 @@ CASES = [
     ("N", 300, 77, 5), ("T", 300, 77, 3),
     ("N", 1, 1, 0), ("T", 1, 1, 0),
     ("N", 33, 1031, 1), ("T", 515, 40, 4), ("T", 70, 129, 1),
+    # r-contiguous with a 16-byte aligned leading dimension (the 256-row kernel) and 1, 2, 3 rows past a multiple of 4
+    ("N", 301, 77, 3), ("N", 1022, 70, 2), ("N", 515, 40, 1), ("N", 260, 33, 0),
 ]
 
 
