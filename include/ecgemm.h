@@ -121,6 +121,26 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
+ * Kernel shape of the product (steps 2 to 5); a tuning and test knob.  The paper's counterpart are the block and warp
+ * tile sizes that it picks for each matrix size by grid search (section "Parameter tuning of CUTLASS").
+ * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for every later ecgemm_sgemm / ecgemm_product /
+ * ecgemm_workspace_size on the handle:
+ *   256x128_W4  block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
+ *   256x128_W8  block tile 256 x 128, 8 waves of 64 x 64, one block per compute unit (the two modes of the method);
+ *   128x128_X2  block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method).
+ * All shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
+ * the tail of the tile grid is sliced along K differently.  A call whose mode has no kernel of the forced shape
+ * returns ECGEMM_ERR_UNSUPPORTED.
+ */
+typedef enum {
+  ECGEMM_SHAPE_AUTO = 0,
+  ECGEMM_SHAPE_256x128_W4 = 1,
+  ECGEMM_SHAPE_256x128_W8 = 2,
+  ECGEMM_SHAPE_128x128_X2 = 3
+} ecgemm_shape_t;
+ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
+
+/*
  * Power-of-two pre-scaling: the remedy the paper names, at the end of section "Effect of the exponent range of input
  * matrices", for inputs whose elements are all too small for the FP16 pair.  From now on
  * ecgemm_sgemm on this handle splits op(A) * 2^log2_scale_a and op(B) * 2^log2_scale_b and multiplies the product by

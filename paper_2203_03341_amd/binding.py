@@ -18,9 +18,10 @@ OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
 MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_FP16_OUTSIDE_ACC = 2, 3, 4, 5, 6  # comparisons
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
+SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_256x128_W8, SHAPE_128x128_X2 = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -37,6 +38,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
+    lib.ecgemm_set_shape.argtypes = [vp, ctypes.c_int]
     lib.ecgemm_set_scaling.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.ecgemm_exponent_range.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_choose_mode.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64,
@@ -118,6 +120,9 @@ class Handle:
               beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
+
+    def set_shape(self, shape: int):
+        self._check(_lib.ecgemm_set_shape(self._h, shape))
 
     def set_scaling(self, log2_scale_a: int, log2_scale_b: int):
         self._check(_lib.ecgemm_set_scaling(self._h, log2_scale_a, log2_scale_b))

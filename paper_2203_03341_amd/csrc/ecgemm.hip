@@ -30,6 +30,7 @@ struct ecgemm_context {
   size_t user_bytes = 0;
   bool timing = false;
   int log2_scale_a = 0, log2_scale_b = 0;
+  ecgemm_shape_t shape = ECGEMM_SHAPE_AUTO;
   int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
   std::vector<TimedCall> timed;
   std::vector<hipEvent_t> free_events;
@@ -38,56 +39,68 @@ struct ecgemm_context {
 
 namespace {
 
-// Tile shapes.  The macros exist so that other shapes can be built and timed side by side; the defaults are
-// the ones every figure in this repository was measured with.
-#ifndef ECGEMM_FP16_KSTEPS
-#define ECGEMM_FP16_KSTEPS 2
-#endif
-#ifndef ECGEMM_FP16_STAGES
-#define ECGEMM_FP16_STAGES 3
-#endif
-#ifndef ECGEMM_BF16_KSTEPS
-#define ECGEMM_BF16_KSTEPS 1
-#endif
-#ifndef ECGEMM_BF16_STAGES
-#define ECGEMM_BF16_STAGES 4
-#endif
-typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> Fp16Config;  // 3 x 48 KiB of LDS
-typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, ECGEMM_BF16_KSTEPS, ECGEMM_BF16_STAGES> Bf16Config;   // 4 x 36 KiB of LDS
-// comparison methods: same tile, same pipeline
-typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> MarkidisConfig;
-typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> UnscaledConfig;
-typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3> PlainFp16Config;
-typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3> PlainBf16Config;
-typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, ECGEMM_FP16_KSTEPS, ECGEMM_FP16_STAGES> OutsideConfig;
-// 128 x 128 tiles, two workgroups per CU: twice the LDS and L2 traffic per flop, but one workgroup's epilogue and
-// pipeline fill hide behind the other's main loop.  Used for shallow K, where those fixed costs dominate.
-typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 2, 2, 2> SmallFp16Config;   // 2 x 32 KiB of LDS per workgroup
-typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> SmallBf16Config;    // 3 x 24 KiB of LDS per workgroup
-#ifndef ECGEMM_SMALL_TILE_MAX_K
-#define ECGEMM_SMALL_TILE_MAX_K 512
-#endif
-// Deepest K slice per work item for which the 256 x 128 product kernels run as a persistent grid (measured: 1-2 %
-// faster up to here, 1-2 % slower at 16384; the 128 x 128 kernels are never faster as a persistent grid).
-#ifndef ECGEMM_PERSISTENT_MAX_K
-#define ECGEMM_PERSISTENT_MAX_K 4096
-#endif
-static_assert(SmallFp16Config::BK == Fp16Config::BK && SmallBf16Config::BK == Bf16Config::BK, "stage depths");
+// Kernel shapes: block tile, waves per block, k steps per LDS stage, stages, resident blocks per CU.
+//   W4: 256 x 128, 4 waves (one per SIMD) of 128 x 64.  Least LDS and L2 traffic per flop.
+//   W8: 256 x 128, 8 waves (two per SIMD) of 64 x 64.  A third more LDS reads per flop, but a SIMD always has a second
+//       wave to issue from while the first waits.
+//   X2: 128 x 128, 4 waves of 64 x 64, two blocks per CU.  A third more LDS reads and L2 traffic per flop; one block's
+//       epilogue and pipeline fill hide behind the other's main loop.
+typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
+typedef ProductConfig<kMethodFp16Split, 256, 128, 64, 64, 2, 3, 1> Fp16W8;
+typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 2, 2, 2> Fp16X2;      // 2 x 32 KiB of LDS per block
+typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 1, 4, 1> Bf16W4;      // 4 x 36 KiB
+typedef ProductConfig<kMethodBf16Full, 256, 128, 64, 64, 2, 2, 1> Bf16W8;       // 2 x 72 KiB
+typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
+// comparison methods: the W4 shape only
+typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisConfig;
+typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, 2, 3, 1> UnscaledConfig;
+typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3, 1> PlainFp16Config;
+typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Config;
+typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
 
+typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
+struct Shape {
+  void (*product)(ProductParams);
+  reduce_fn_t reduce;
+  int bm, bn, bk, threads, blocks_per_cu;
+  // Deepest K for which the kernel runs as a persistent grid: one block per CU, each walking through several items
+  // with the next item's first loads in flight during its epilogue.  Beyond it, one block per item, handed out in
+  // order by the hardware as CUs free up, which keeps the tiles an XCD works on at any time next to each other: blocks
+  // of a persistent grid drift apart over long items and lose L2 hits (72 % instead of 82 % at 16384^3, W4).
+  // Measured at 16384 x 16384 x K, persistent against one block per item: K = 1024: -6 % (FP16 W4), -9 % (FP16 W8),
+  // -5 % (BF16 W8); K = 4096: -5 %, +3 %, -2 %; K = 8192: -1 %, +3 %, 0.  Two co-resident X2 blocks already cover each
+  // other's epilogue and never gain.
+  int persistent_max_k;
+};
+template <class Cfg>
+constexpr Shape shape_of(int persistent_max_k) {
+  return Shape{product_kernel<Cfg>, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::THREADS, Cfg::BLOCKS_PER_CU,
+               persistent_max_k};
+}
+constexpr Shape kNoShape{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+// [mode][ecgemm_shape_t - 1]
+const Shape kShapes[7][3] = {
+    {shape_of<Fp16W4>(4096), shape_of<Fp16W8>(2048), shape_of<Fp16X2>(0)},
+    {shape_of<Bf16W4>(4096), shape_of<Bf16W8>(4096), shape_of<Bf16X2>(0)},
+    {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
+    {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
+    {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
+    {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
+    {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
+};
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // the ecgemm_mode_t values are the ProductMethod values
 inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
 inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_FP16_OUTSIDE_ACC; }
-inline int stage_depth_of(ecgemm_mode_t mode) { return mode == ECGEMM_MODE_BF16_FULL ? Bf16Config::BK : Fp16Config::BK; }
 static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
               (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
               (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
               (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain &&
               (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside,
               "mode numbering");
-static_assert(PlainFp16Config::BK == Fp16Config::BK && MarkidisConfig::BK == Fp16Config::BK, "stage depths");
+inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_X2; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
 
 size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
@@ -95,41 +108,67 @@ size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
 }
 
 struct Plan {
-  bool small_tiles;  // 128 x 128, two workgroups per CU
-  int bm, bn;
-  int64_t Mp, Np, Kp;
-  int tiles_m, tiles_n, k_tiles, k_splits;
+  const Shape* shape;  // null: the requested shape does not exist for the mode
+  int64_t Kp;
+  int tiles_m, tiles_n, k_tiles;
+  int full_tiles, tail_tiles, tail_splits;  // see ProductParams
   size_t a_bytes, b_bytes, partial_bytes, total_bytes;
+  int64_t items() const { return (int64_t)full_tiles + (int64_t)tail_tiles * tail_splits; }
 };
 
-// One tile shape per mode (256 x 128 x 32, 4 waves).  K is divided among blocks only when the output
-// tiles alone cannot occupy the 256 CUs and K is deep enough to leave every block a long loop.
-Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
+// The plan is made for the 256 compute units of the MI355X whatever device the handle is on, so that the workspace
+// size is a function of the problem (and the shape, if the caller fixed one) alone.
+constexpr int kPlanComputeUnits = 256;
+
+// Tiles of one shape, and how they become work items.  As many tiles as fill every workgroup slot of the chip a whole
+// number of times are one item each.  The tiles left over would occupy only part of the chip for the time of a whole
+// tile; when K is deep enough each of them is cut into slices along K (at least 512 deep) so that the slices fill the
+// slots once more, and a second kernel adds the slices up in a fixed order.
+Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
   Plan pl;
-  pl.Mp = round_up(M, kRowPad);
-  pl.Np = round_up(N, kRowPad);
   pl.Kp = round_up(K, kDepthPad);
-  pl.small_tiles = (mode == ECGEMM_MODE_FP16_SPLIT || mode == ECGEMM_MODE_BF16_FULL) && pl.Kp <= ECGEMM_SMALL_TILE_MAX_K;
-  pl.bm = pl.small_tiles ? 128 : 256;
-  pl.bn = 128;
-  pl.tiles_m = (int)((M + pl.bm - 1) / pl.bm);
-  pl.tiles_n = (int)((N + pl.bn - 1) / pl.bn);
-  pl.k_tiles = (int)(pl.Kp / stage_depth_of(mode));
-  const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
-  int splits = 1;
-  if (tiles < 192) {
-    splits = (int)((512 + tiles - 1) / tiles);
-    const int max_by_depth = (int)(pl.Kp / 512);  // at least 512 of depth per block
-    if (splits > max_by_depth) splits = max_by_depth;
-    if (splits > 64) splits = 64;
-    if (splits < 1) splits = 1;
+  pl.shape = &kShapes[(int)mode][(int)shape - 1];
+  if (pl.shape->product == nullptr) {
+    pl.shape = nullptr;
+    return pl;
   }
-  pl.k_splits = splits;
+  const int bm = pl.shape->bm, bn = pl.shape->bn;
+  pl.tiles_m = (int)((M + bm - 1) / bm);
+  pl.tiles_n = (int)((N + bn - 1) / bn);
+  pl.k_tiles = (int)(pl.Kp / pl.shape->bk);
+  const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+  const int64_t slots = (int64_t)kPlanComputeUnits * pl.shape->blocks_per_cu;
+  const int64_t tail = tiles % slots;
+  int64_t splits = tail > 0 ? slots / tail : 1;
+  splits = std::min<int64_t>(splits, pl.Kp / 512);
+  splits = std::max<int64_t>(1, std::min<int64_t>(splits, 64));
+  pl.tail_splits = (int)splits;
+  pl.tail_tiles = splits > 1 ? (int)tail : 0;
+  pl.full_tiles = (int)(tiles - pl.tail_tiles);
   pl.a_bytes = align256(packed_bytes(M, K, mode));
   pl.b_bytes = align256(packed_bytes(N, K, mode));
-  pl.partial_bytes = splits > 1 ? align256((size_t)splits * pl.Mp * pl.Np * sizeof(float)) : 0;
+  pl.partial_bytes = splits > 1 ? align256((size_t)splits * tail * bm * bn * sizeof(float)) : 0;
   pl.total_bytes = pl.a_bytes + pl.b_bytes + pl.partial_bytes;
   return pl;
+}
+
+// The plan of a call.  Which shape a problem gets when the caller has not fixed one comes from product-kernel timings
+// of all three shapes on 30 sizes from 1024^3 to 24576 x 24576 x 4096:
+//   * if the 256 x 128 tiles cannot give every CU an item even after slicing (1024^3: 64 items; 1536^3: 216), the
+//     128 x 128 shape X2, which makes twice as many: 24 us against 33 (W8) and 36 (W4) at 1024^3, FP16 mode;
+//   * otherwise W8: ahead of W4 by 3-8 % (FP16 mode) and 4-9 % (BF16 mode) from 2048^3 to 8192^3 and at
+//     16384 x 16384 x 256..4096, and ahead of X2 by 1-5 %;
+//   * except in FP16 mode from 0.75 GiB of packed operands up, where W4 takes over: tie at 12288^3 and
+//     8192 x 8192 x 16384, W4 ahead by 3 % at 14336^3, 4 % at 24576 x 24576 x 4096, 6 % at 16384^3, 10 % at 20480^3
+//     (in BF16 mode W8 stays ahead, by 3 % at 16384^3).
+// The comparison methods have the W4 shape only.
+Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+  if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
+  if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
+  const Plan w8 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W8);
+  if (w8.items() < kPlanComputeUnits) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
+  if (mode == ECGEMM_MODE_FP16_SPLIT && w8.a_bytes + w8.b_bytes >= (size_t)768 << 20) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
+  return w8;
 }
 
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {
@@ -196,9 +235,11 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.b_packed = static_cast<const char*>(b_packed);
   pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
   pp.k_tiles = pl.k_tiles;
-  pp.k_splits = pl.k_splits;
   pp.tiles_m = pl.tiles_m;
   pp.tiles_n = pl.tiles_n;
+  pp.full_tiles = pl.full_tiles;
+  pp.tail_tiles = pl.tail_tiles;
+  pp.tail_splits = pl.tail_splits;
   pp.M = M;
   pp.N = N;
   pp.ldc = ldc;
@@ -207,38 +248,18 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.out_scale = std::ldexp(1.0f, log2_out_scale);
   pp.C = C;
   pp.partials = partials;
-  pp.Mp = pl.Mp;
-  pp.Np = pl.Np;
-  // Grid, always a multiple of the 8 XCDs.  Items of moderate depth on the 256 x 128 kernels: a persistent grid, one
-  // block per CU, each block walking through several items with the next item's loads in flight during its epilogue.
-  // Otherwise one block per item, handed out in order by the hardware as CUs free up, which keeps the tiles an XCD
-  // works on at any time next to each other: blocks of a persistent grid drift apart over long items and lose L2
-  // hits (72 % instead of 82 % at K = 16384), and two co-resident 128 x 128 blocks already cover each other's epilogue.
-  const int64_t items = (int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits;
-  const int64_t slots = (int64_t)h->compute_units * (pl.small_tiles ? 2 : 1);
-  const int64_t depth_per_item = (pl.Kp + pl.k_splits - 1) / pl.k_splits;
-  const bool persistent = !pl.small_tiles && depth_per_item <= ECGEMM_PERSISTENT_MAX_K;
-  const dim3 grid((unsigned)(items < slots || !persistent ? round_up(items, 8) : slots));
-  if (pl.small_tiles) {
-    if (mode == ECGEMM_MODE_BF16_FULL)
-      hipLaunchKernelGGL(product_kernel<SmallBf16Config>, grid, dim3(SmallBf16Config::THREADS), 0, h->stream, pp);
-    else
-      hipLaunchKernelGGL(product_kernel<SmallFp16Config>, grid, dim3(SmallFp16Config::THREADS), 0, h->stream, pp);
-  } else
-  switch (mode) {
-    case ECGEMM_MODE_FP16_SPLIT: hipLaunchKernelGGL(product_kernel<Fp16Config>, grid, dim3(Fp16Config::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_BF16_FULL: hipLaunchKernelGGL(product_kernel<Bf16Config>, grid, dim3(Bf16Config::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_FP16_MARKIDIS: hipLaunchKernelGGL(product_kernel<MarkidisConfig>, grid, dim3(MarkidisConfig::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_FP16_UNSCALED: hipLaunchKernelGGL(product_kernel<UnscaledConfig>, grid, dim3(UnscaledConfig::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_FP16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainFp16Config>, grid, dim3(PlainFp16Config::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_BF16_PLAIN: hipLaunchKernelGGL(product_kernel<PlainBf16Config>, grid, dim3(PlainBf16Config::THREADS), 0, h->stream, pp); break;
-    case ECGEMM_MODE_FP16_OUTSIDE_ACC: hipLaunchKernelGGL(product_kernel<OutsideConfig>, grid, dim3(OutsideConfig::THREADS), 0, h->stream, pp); break;
-  }
-  ECGEMM_HIP(h, hipGetLastError());
-  if (pl.k_splits > 1) {
-    const dim3 rgrid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
-    hipLaunchKernelGGL(reduce_partials_kernel, rgrid, dim3(256), 0, h->stream, partials, pl.k_splits, pl.Mp, pl.Np, M, N, alpha,
-                       beta, C, ldc);
+  // Grid, always a multiple of the 8 XCDs: one block per item, or a persistent grid (see Shape::persistent_max_k).
+  const int64_t tail_items = (int64_t)pl.tail_tiles * pl.tail_splits;
+  const int64_t one_block_per_item = 8 * ((pl.full_tiles + 7) / 8 + (tail_items + 7) / 8);  // every XCD's list, padded
+  const int64_t slots = (int64_t)h->compute_units * pl.shape->blocks_per_cu;
+  const bool persistent = pl.Kp <= pl.shape->persistent_max_k;
+  const dim3 grid((unsigned)(one_block_per_item <= slots || !persistent ? one_block_per_item : slots));
+  void* args[] = {&pp};
+  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->product), grid, dim3(pl.shape->threads), args, 0, h->stream));
+  if (pl.tail_splits > 1) {
+    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bn / 16));
+    hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -346,11 +367,22 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void* hip_stream) {
   return ECGEMM_OK;
 }
 
+ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!valid_shape(shape)) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_shape: unknown shape");
+  handle->shape = shape;
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
                                       ecgemm_mode_t mode, size_t* bytes) {
   if (!bytes || M < 0 || N < 0 || K < 0 || !valid_mode(mode))
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_workspace_size: bad argument");
-  *bytes = (M == 0 || N == 0 || K == 0) ? 0 : make_plan(M, N, K, mode).total_bytes;
+  *bytes = 0;
+  if (M == 0 || N == 0 || K == 0) return ECGEMM_OK;
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
+  *bytes = pl.total_bytes;
   return ECGEMM_OK;
 }
 
@@ -526,15 +558,16 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
 
   ecgemm_status_t st = check_sizes(h, M, N, K, mode);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode);
-  if ((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits > 0x7fffffffLL)
+  const Plan pl = make_plan(M, N, K, mode, h->shape);
+  if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
+  if (pl.items() + 16 > 0x7fffffffLL)
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: too many tiles");
   char* ws = nullptr;
   st = acquire_workspace(h, pl.total_bytes, &ws);
   if (st != ECGEMM_OK) return st;
   char* a_packed = ws;
   char* b_packed = ws + pl.a_bytes;
-  float* partials = pl.k_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
+  float* partials = pl.tail_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
 
   // Events for the optional timing go back to the handle's pool whenever the call does not complete.
   struct EventLease {
@@ -595,8 +628,9 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: packed operand is null or not 16-byte aligned");
   ecgemm_status_t st = check_sizes(h, M, N, K, mode);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode);
-  if ((int64_t)pl.tiles_m * pl.tiles_n * pl.k_splits > 0x7fffffffLL)
+  const Plan pl = make_plan(M, N, K, mode, h->shape);
+  if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not exist for this mode");
+  if (pl.items() + 16 > 0x7fffffffLL)
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: too many tiles");
   char* ws = nullptr;
   st = acquire_workspace(h, pl.partial_bytes, &ws);

@@ -44,15 +44,32 @@ struct ProductParams {
   const char* b_packed;     // [Np/32][k_steps][NP][64][8] 16-bit
   int64_t row_block_bytes;  // k_steps * NP * 1024
   int k_tiles;              // depth_padded / (16 * K_STEPS): LDS stages along K
-  int k_splits;             // blocks along K per output tile
   int tiles_m, tiles_n;
+  // Work items: the first full_tiles output tiles (in the order of tile_coordinates) are one item each, over the whole
+  // depth; each of the remaining tail_tiles is tail_splits items, one per slice of the depth, which leave raw sums in
+  // `partials` for reduce_tail_kernel.  tail_splits == 1: those tiles are whole items too and nothing goes to partials.
+  int full_tiles, tail_tiles, tail_splits;
   int64_t M, N, ldc;
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
   float* C;
-  float* partials;          // [k_splits][Np][Mp] when k_splits > 1
-  int64_t Mp, Np;
+  float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
 };
+
+#ifndef ECGEMM_GROUP_M
+#define ECGEMM_GROUP_M 4
+#endif
+// Output tile number -> tile coordinates: groups of ECGEMM_GROUP_M tile rows, walked column by column, so that tiles
+// with neighbouring numbers share A and B panels.
+__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  constexpr int kGroupM = ECGEMM_GROUP_M;
+  const int group_size = kGroupM * tiles_n;
+  const int group = pid / group_size;
+  const int first_m = group * kGroupM;
+  const int group_m = min(tiles_m - first_m, kGroupM);
+  tile_m = first_m + (pid % group_size) % group_m;
+  tile_n = (pid % group_size) / group_m;
+}
 
 template <bool BF16>
 struct Mfma;
@@ -139,51 +156,62 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 
   // ---- work items (an item = one output tile x one K slice).  The host launches either one block per item or
   // a persistent grid of one block per CU whose blocks each walk through several items.  Blocks are dealt
-  // round-robin to the 8 XCDs, so block b lives on XCD b % 8; that XCD owns one contiguous range of items and its
-  // blocks stride through it together, so the ~32 tiles an XCD works on at any time are neighbours that share
-  // A and B panels in its L2.
+  // round-robin to the 8 XCDs, so block b lives on XCD b % 8; that XCD owns one contiguous run of the whole-tile
+  // items, followed by one contiguous run of the sliced items, and its blocks stride through that list together, so
+  // the ~32 tiles an XCD works on at any time are neighbours that share A and B panels in its L2.
   struct Work {
-    int tile_m, tile_n, split, kt_begin, kt_count;
+    int tile_m, tile_n, kt_begin, kt_count;
+    int partial;  // index of the [BN][BM] partial tile this item writes, or -1 if it writes C
   };
-  const int tiles = p.tiles_m * p.tiles_n;
 #ifndef ECGEMM_XCD_REMAP
 #define ECGEMM_XCD_REMAP 1
 #endif
-#ifndef ECGEMM_GROUP_M
-#define ECGEMM_GROUP_M 4
-#endif
+  const int tail_items = p.tail_tiles * p.tail_splits;
   auto locate = [&](int item) {
     Work w;
-    w.split = item / tiles;
-    const int pid = item - w.split * tiles;
-    constexpr int kGroupM = ECGEMM_GROUP_M;
-    const int group_size = kGroupM * p.tiles_n;
-    const int group = pid / group_size;
-    const int first_m = group * kGroupM;
-    const int group_m = min(p.tiles_m - first_m, kGroupM);
-    w.tile_m = first_m + (pid % group_size) % group_m;
-    w.tile_n = (pid % group_size) / group_m;
-    const int kt_per_split = (p.k_tiles + p.k_splits - 1) / p.k_splits;
-    w.kt_begin = w.split * kt_per_split;
-    w.kt_count = max(0, min(p.k_tiles, w.kt_begin + kt_per_split) - w.kt_begin);
+    int pid = item;
+    w.kt_begin = 0;
+    w.kt_count = p.k_tiles;
+    w.partial = -1;
+    if (item >= p.full_tiles) {
+      const int j = item - p.full_tiles, split = j / p.tail_tiles;
+      pid = p.full_tiles + j % p.tail_tiles;
+      if (p.tail_splits > 1) {
+        const int kt_per_split = (p.k_tiles + p.tail_splits - 1) / p.tail_splits;
+        w.kt_begin = split * kt_per_split;
+        w.kt_count = max(0, min(p.k_tiles, w.kt_begin + kt_per_split) - w.kt_begin);
+        w.partial = j;
+      }
+    }
+    tile_coordinates(pid, p.tiles_m, p.tiles_n, w.tile_m, w.tile_n);
     return w;
   };
-  const int items = tiles * p.k_splits;
-  int item, item_end, item_stride;
+  // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.
+  int slot, slot_end, slot_stride, full_start = 0, full_count = p.full_tiles, tail_start = 0;
   if (ECGEMM_XCD_REMAP) {
     constexpr int kXcds = 8;  // gridDim.x is a multiple of 8
-    const int xcd = blockIdx.x % kXcds, base = items / kXcds, rem = items % kXcds;
-    const int start = xcd < rem ? xcd * (base + 1) : rem * (base + 1) + (xcd - rem) * base;
-    item = start + blockIdx.x / kXcds;
-    item_end = start + base + (xcd < rem ? 1 : 0);
-    item_stride = gridDim.x / kXcds;
+    const int xcd = blockIdx.x % kXcds;
+    auto share = [&](int n, int& start, int& count) {  // XCD x's part of n things dealt out in contiguous runs
+      const int base = n / kXcds, rem = n % kXcds;
+      start = xcd * base + min(xcd, rem);
+      count = base + (xcd < rem ? 1 : 0);
+    };
+    int tail_count;
+    share(p.full_tiles, full_start, full_count);
+    share(tail_items, tail_start, tail_count);
+    slot = blockIdx.x / kXcds;
+    slot_end = full_count + tail_count;
+    slot_stride = gridDim.x / kXcds;
   } else {
-    item = blockIdx.x;
-    item_end = items;
-    item_stride = gridDim.x;
+    slot = blockIdx.x;
+    slot_end = p.full_tiles + tail_items;
+    slot_stride = gridDim.x;
   }
-  if (item >= item_end) return;
-  Work work = locate(item);
+  auto item_at = [&](int position) {
+    return position < full_count ? full_start + position : p.full_tiles + tail_start + (position - full_count);
+  };
+  if (slot >= slot_end) return;
+  Work work = locate(item_at(slot));
 
   // ---- global -> LDS: wave w moves the 1 KiB chunks w, w + WAVES, ... of a stage; A_CHUNKS is a
   // multiple of WAVES, so whether load i fetches from A or from B is known at compile time.  Source
@@ -420,20 +448,27 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   // ---- next item: once every wave is done with the LDS ring, its first stages are requested, so that they travel
   // while this item's results are written out.
   const Work done = work;
-  const int next_item = item + item_stride;
-  const bool more = next_item < item_end;
+  slot += slot_stride;
+  const bool more = slot < slot_end;
   if (more) {
     stage_barrier(none_t{});
-    work = locate(next_item);
+    work = locate(item_at(slot));
     request_first_stages(work);
   }
 
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
-  const int tile_m = done.tile_m, tile_n = done.tile_n, split = done.split;
+  const int tile_m = done.tile_m, tile_n = done.tile_n;
   const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
-  const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane & 31);
-  const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane >> 5);
+  // The compiler must not carry this item's 128 store addresses (or their lane-dependent parts) through the main
+  // loop of the next item, where it would have to spill them: what they are computed from is made opaque here, so
+  // they are recomputed per item.
+  int lane_here = lane;
+  int64_t ldc = p.ldc;
+  float* c_base = p.C;
+  asm volatile("" : "+v"(lane_here), "+s"(ldc), "+s"(c_base));
+  const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane_here & 31);
+  const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane_here >> 5);
   auto for_each_output = [&](auto&& store) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -445,26 +480,26 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
                 (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
   };
   const bool interior = (int64_t)(tile_m + 1) * Cfg::BM <= p.M && (int64_t)(tile_n + 1) * Cfg::BN <= p.N;
-  if (p.k_splits > 1) {
-    float* out = p.partials + (int64_t)split * p.Np * p.Mp;
-    for_each_output([&](int64_t m, int64_t n, float c) { out[n * p.Mp + m] = c; });
+  if (done.partial >= 0) {
+    float* out = p.partials + (int64_t)done.partial * (Cfg::BM * Cfg::BN);
+    const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
+    for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * Cfg::BM + (m - m0)] = c; });
   } else if (interior && p.beta == 0.0f) {
-    for_each_output([&](int64_t m, int64_t n, float c) { p.C[m + n * p.ldc] = p.alpha * c; });
+    for_each_output([&](int64_t m, int64_t n, float c) { c_base[m + n * ldc] = p.alpha * c; });
   } else if (interior) {
     for_each_output([&](int64_t m, int64_t n, float c) {
-      float* dst = p.C + m + n * p.ldc;
+      float* dst = c_base + m + n * ldc;
       *dst = p.alpha * c + p.beta * *dst;
     });
   } else {
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
-        float* dst = p.C + m + n * p.ldc;
+        float* dst = c_base + m + n * ldc;
         *dst = (p.beta == 0.0f) ? p.alpha * c : p.alpha * c + p.beta * *dst;
       }
     });
   }
   if (!more) break;
-  item = next_item;
   }  // items
 }
 
@@ -516,15 +551,25 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
   sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// Split-K tail: sums the k_splits partial tiles in a fixed order, then alpha / beta.
-__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ partials, int k_splits,
-                                                              int64_t Mp, int64_t Np, int64_t M, int64_t N,
-                                                              float alpha, float beta, float* __restrict__ C, int64_t ldc) {
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+// Sums the slices of the sliced tiles in a fixed order (bitwise reproducible, no atomics), then alpha / beta.
+// partials is [tail_splits][tail_tiles][BN][BM]; block (t, c) handles 16 columns of tail tile t.
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
+                                                          int full_tiles, int tiles_m, int tiles_n, int64_t M, int64_t N,
+                                                          float alpha, float beta, float* __restrict__ C, int64_t ldc) {
+  static_assert(256 % BM == 0 && BN % 16 == 0, "tile shape");
+  int tile_m, tile_n;
+  tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int m_local = threadIdx.x % BM;
+  const int64_t m = (int64_t)tile_m * BM + m_local;
   if (m >= M) return;
-  for (int64_t n = blockIdx.y; n < N; n += gridDim.y) {
+  for (int c = threadIdx.x / BM; c < 16; c += 256 / BM) {
+    const int n_local = blockIdx.y * 16 + c;
+    const int64_t n = (int64_t)tile_n * BN + n_local;
+    if (n >= N) break;
     float sum = 0.0f;
-    for (int s = 0; s < k_splits; ++s) sum += partials[((int64_t)s * Np + n) * Mp + m];
+    for (int s = 0; s < tail_splits; ++s)
+      sum += partials[(((int64_t)s * tail_tiles + blockIdx.x) * BN + n_local) * BM + m_local];
     float* dst = C + m + n * ldc;
     *dst = (beta == 0.0f) ? alpha * sum : alpha * sum + beta * *dst;
   }

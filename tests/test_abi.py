@@ -46,8 +46,8 @@ def test_product_path_does_not_touch_the_oracle():
 
 
 def test_workspace_plan_needs_no_gpu():
-    """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and K divided
-    among blocks (with one partial C per slice) only when the tiles alone cannot fill the chip."""
+    """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and the output
+    tiles left over after whole rounds of the chip's 256 CUs cut into slices along K (one partial tile per slice)."""
     import paper_2203_03341_amd as ec
     n = 16384
     assert ec.workspace_size(n, n, n, ec.MODE_FP16_SPLIT) == 2 * n * n * 4              # two packed operands, no split-K
@@ -55,11 +55,14 @@ def test_workspace_plan_needs_no_gpu():
     assert ec.workspace_size(n, n, n, ec.MODE_FP16_PLAIN) == 2 * n * n * 2
     assert ec.workspace_size(1, 1, 1, ec.MODE_FP16_SPLIT) == 2 * 256 * 32 * 4
     assert ec.workspace_size(0, 5, 5, ec.MODE_FP16_SPLIT) == 0
+    # 32 output tiles of 256 x 128 on 256 CUs: every tile is cut into 8 slices along K, one partial tile per slice
     deep = ec.workspace_size(1024, 1024, 65536, ec.MODE_FP16_SPLIT)
-    operands = 2 * 1024 * 65536 * 4
-    slices = (deep - operands) // (1024 * 1024 * 4)
-    assert deep > operands and (deep - operands) % (1024 * 1024 * 4) == 0 and 2 <= slices <= 64
-    assert ec.workspace_size(4095, 3001, 5003, ec.MODE_BF16_FULL) == (4096 + 3072) * 5024 * 6
+    assert deep == 2 * 1024 * 65536 * 4 + 8 * 32 * (256 * 128 * 4)
+    # 16 x 24 = 384 tiles: 256 are done whole, the other 128 in two slices each
+    odd = ec.workspace_size(4095, 3001, 5003, ec.MODE_BF16_FULL)
+    assert odd == (4096 + 3072) * 5024 * 6 + 2 * 128 * (256 * 128 * 4)
+    # shallow K is never sliced
+    assert ec.workspace_size(1024, 1024, 512, ec.MODE_FP16_SPLIT) == 2 * 1024 * 512 * 4
     import pytest
     with pytest.raises(ec.EcgemmError):
         ec.workspace_size(-1, 1, 1, ec.MODE_FP16_SPLIT)

@@ -40,10 +40,17 @@ def _model(mode, opA, opB):
             "plainbf": lambda: model.gemm_plain(opA, opB, "bf16")}[mode]()
 
 
-def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None):
+def _shapes():
+    import paper_2203_03341_amd as ec
+    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "w8": ec.SHAPE_256x128_W8, "x2": ec.SHAPE_128x128_X2}
+
+
+def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None, shape=None):
     import torch
     import paper_2203_03341_amd as ec
     h = handle or ec.Handle()
+    if shape is not None:
+        h.set_shape(_shapes()[shape])
     dA, dB = to_device(A), to_device(B)
     ldc = ldc or (C.shape[0] if C is not None else M)
     if C is not None:
@@ -73,10 +80,10 @@ def _inputs(M, N, K, transA, transB, dist, seed, pad=0):
 
 
 def _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=0, pad=0, rows=None, elementwise=True,
-           ratio_rule=True):
+           ratio_rule=True, shape=None):
     A, B = _inputs(M, N, K, transA, transB, dist, seed, pad)
     C = si.urand(M, N, seed, si.ID_C, ld=M + pad) if beta != 0 else None
-    got_store = _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=M + pad)
+    got_store = _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=M + pad, shape=shape)
     got = got_store[:M, :N]
     if pad and beta != 0:
         # rows beyond M belong to the caller and must be left alone (they hold NaN from the generator)
@@ -257,6 +264,50 @@ def test_tall_skinny(mode):
 def test_odd_sizes_transA(mode):
     M, N, K = 1023, 751, 1251          # config 5's 4095 x 3001 x 5003 at a quarter of the size, same raggedness
     _check("T", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=9)
+
+
+# ----- every kernel shape on its own (the automatic choice exercises only one per size)
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+@pytest.mark.parametrize("shape", ["w4", "w8", "x2"])
+def test_every_kernel_shape(mode, shape):
+    _check("T", "N", 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1, shape=shape)        # ragged, several tiles
+    _check("N", "T", 700, 900, 1500, 1.5, 0.5, mode, "urand", seed=3, shape=shape)               # every tile sliced along K
+    _check("N", "N", 1, 1, 1, 1.0, 0.0, mode, "urand", seed=4, ratio_rule=False, shape=shape)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+@pytest.mark.parametrize("shape", ["w4", "w8", "x2"])
+def test_whole_tiles_followed_by_a_sliced_tail(mode, shape):
+    """3000 x 3000: 288 tiles of 256 x 128 (256 whole + 32 in two slices) or 576 of 128 x 128 (512 whole + 64 sliced)."""
+    rows = si.sample_indices(3000, 160, seed=2)
+    _check("N", "N", 3000, 3000, 1100, 1.0, 0.5, mode, "urand", seed=5, rows=rows, shape=shape)
+
+
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
+    """Every shape adds up the k steps of an element in the same order; only slicing along K changes the bits."""
+    M, N, K = 600, 500, 400
+    A, B = _inputs(M, N, K, "N", "N", "urand", 6)
+    outs = [_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh) for sh in ("w4", "w8", "x2", None)]
+    for other in outs[1:]:
+        assert np.array_equal(outs[0].view(np.uint32), other.view(np.uint32))
+
+
+def test_a_shape_the_mode_has_no_kernel_for_is_refused():
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    h.set_shape(ec.SHAPE_256x128_W8)
+    A, B = _inputs(64, 64, 64, "N", "N", "urand", 0)
+    dA, dB, dC = to_device(A), to_device(B), empty_colmajor(64, 64, fill=0.0)
+    with pytest.raises(ec.EcgemmError) as err:
+        h.sgemm(ec.OP_N, ec.OP_N, 64, 64, 64, 1.0, dA, 64, dB, 64, 0.0, dC, 64, ec.MODE_FP16_MARKIDIS)
+    assert err.value.status == ec.ERR_UNSUPPORTED
+    with pytest.raises(ec.EcgemmError):
+        h.set_shape(7)
+    h.set_shape(ec.SHAPE_AUTO)
+    h.sgemm(ec.OP_N, ec.OP_N, 64, 64, 64, 1.0, dA, 64, dB, 64, 0.0, dC, 64, ec.MODE_FP16_MARKIDIS)
+    h.destroy()
 
 
 # ----- exponent ranges (section "Effect of the exponent range of input matrices")
