@@ -32,8 +32,8 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 # workload; None where no counter run has been made for that workload.
 MEASURED_TRAFFIC_BYTES = {
     # FETCH_SIZE x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE x 1.0, in bytes
-    "c3_16384_fp16_exprand15": 3.86e10,      # profiles/product_kernel_fp16_16384cubed.md: 37.5 GB + 1.11 GB
-    "c4_8192_bf16_widerange": 7.1e9,         # profiles/product_kernel_bf16_8192cubed.md: 6.8 GB + 0.29 GB
+    "c3_16384_fp16_exprand15": 3.55e10,      # profiles/product_kernel_fp16_16384cubed.md: 34.4 GB + 1.08 GB
+    "c4_8192_bf16_widerange": 7.0e9,         # profiles/product_kernel_bf16_8192cubed.md: 6.7 GB + 0.27 GB
 }
 
 WORKLOADS = {
@@ -73,8 +73,11 @@ def make_inputs(M, N, K, transA, transB, dist, beta, seed=0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 20, more for workloads under a millisecond so that 0.1 s is timed)")
+    ap.add_argument("--warmup", type=int, default=None,
+                    help="untimed warm-up steps (default: 3, more for short workloads so that the board, which drops "
+                         "its clocks when idle, has run for 50 ms)")
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle (no error figures, no cpu_baseline)")
     ap.add_argument("--seed", type=int, default=0)
@@ -99,6 +102,11 @@ def main():
     import seeded_inputs as si
 
     M, N, K, transA, transB, mode, alpha, beta, dist, oracle_rows = WORKLOADS[args.workload]
+    expected_ms = max(0.02, 2.0 * M * N * K / 3.0e14 * 1e3)     # at 300 TFLOP/s; only sizes the default step counts
+    if args.warmup is None:
+        args.warmup = int(min(500, max(3, np.ceil(50.0 / expected_ms))))
+    if args.steps is None:
+        args.steps = int(min(1000, max(20, np.ceil(100.0 / expected_ms))))
     parts_products = {"fp16": 3, "bf16": 6}[mode]
     mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL}[mode]
     ops = {"N": ec.OP_N, "T": ec.OP_T}

@@ -126,17 +126,15 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
  * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for every later ecgemm_sgemm / ecgemm_product /
  * ecgemm_workspace_size on the handle:
  *   256x128_W4  block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
- *   256x128_W8  block tile 256 x 128, 8 waves of 64 x 64, one block per compute unit (the two modes of the method);
  *   128x128_X2  block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method).
- * All shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
+ * Both shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
  * the tail of the tile grid is sliced along K differently.  A call whose mode has no kernel of the forced shape
  * returns ECGEMM_ERR_UNSUPPORTED.
  */
 typedef enum {
   ECGEMM_SHAPE_AUTO = 0,
   ECGEMM_SHAPE_256x128_W4 = 1,
-  ECGEMM_SHAPE_256x128_W8 = 2,
-  ECGEMM_SHAPE_128x128_X2 = 3
+  ECGEMM_SHAPE_128x128_X2 = 2
 } ecgemm_shape_t;
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 

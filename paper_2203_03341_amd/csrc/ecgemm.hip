@@ -41,15 +41,13 @@ namespace {
 
 // Kernel shapes: block tile, waves per block, k steps per LDS stage, stages, resident blocks per CU.
 //   W4: 256 x 128, 4 waves (one per SIMD) of 128 x 64.  Least LDS and L2 traffic per flop.
-//   W8: 256 x 128, 8 waves (two per SIMD) of 64 x 64.  A third more LDS reads per flop, but a SIMD always has a second
-//       wave to issue from while the first waits.
 //   X2: 128 x 128, 4 waves of 64 x 64, two blocks per CU.  A third more LDS reads and L2 traffic per flop; one block's
-//       epilogue and pipeline fill hide behind the other's main loop.
+//       epilogue and pipeline fill hide behind the other's main loop, and a problem makes twice as many tiles.
+// (A 256 x 128 shape with 8 waves of 64 x 64, two per SIMD, was also built and timed on 60 sizes: never more than
+// 2 % ahead of W4, usually 1 % behind.)
 typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
-typedef ProductConfig<kMethodFp16Split, 256, 128, 64, 64, 2, 3, 1> Fp16W8;
 typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 2, 2, 2> Fp16X2;      // 2 x 32 KiB of LDS per block
 typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 1, 4, 1> Bf16W4;      // 4 x 36 KiB
-typedef ProductConfig<kMethodBf16Full, 256, 128, 64, 64, 2, 2, 1> Bf16W8;       // 2 x 72 KiB
 typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
 // comparison methods: the W4 shape only
 typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisConfig;
@@ -66,10 +64,8 @@ struct Shape {
   // Deepest K for which the kernel runs as a persistent grid: one block per CU, each walking through several items
   // with the next item's first loads in flight during its epilogue.  Beyond it, one block per item, handed out in
   // order by the hardware as CUs free up, which keeps the tiles an XCD works on at any time next to each other: blocks
-  // of a persistent grid drift apart over long items and lose L2 hits (72 % instead of 82 % at 16384^3, W4).
-  // Measured at 16384 x 16384 x K, persistent against one block per item: K = 1024: -6 % (FP16 W4), -9 % (FP16 W8),
-  // -5 % (BF16 W8); K = 4096: -5 %, +3 %, -2 %; K = 8192: -1 %, +3 %, 0.  Two co-resident X2 blocks already cover each
-  // other's epilogue and never gain.
+  // of a persistent grid drift apart over long items and lose L2 hits (72 % instead of 82 % at 16384^3).
+  // Two co-resident X2 blocks already cover each other's epilogue and never gain.
   int persistent_max_k;
 };
 template <class Cfg>
@@ -79,14 +75,17 @@ constexpr Shape shape_of(int persistent_max_k) {
 }
 constexpr Shape kNoShape{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
-const Shape kShapes[7][3] = {
-    {shape_of<Fp16W4>(4096), shape_of<Fp16W8>(2048), shape_of<Fp16X2>(0)},
-    {shape_of<Bf16W4>(4096), shape_of<Bf16W8>(4096), shape_of<Bf16X2>(0)},
-    {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
-    {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
-    {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
-    {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
-    {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
+#ifndef ECGEMM_PERSISTENT_MAX_K
+#define ECGEMM_PERSISTENT_MAX_K 4096
+#endif
+const Shape kShapes[7][2] = {
+    {shape_of<Fp16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Fp16X2>(0)},
+    {shape_of<Bf16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Bf16X2>(0)},
+    {shape_of<MarkidisConfig>(4096), kNoShape},
+    {shape_of<UnscaledConfig>(4096), kNoShape},
+    {shape_of<PlainFp16Config>(4096), kNoShape},
+    {shape_of<PlainBf16Config>(4096), kNoShape},
+    {shape_of<OutsideConfig>(4096), kNoShape},
 };
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -153,22 +152,19 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 }
 
 // The plan of a call.  Which shape a problem gets when the caller has not fixed one comes from product-kernel timings
-// of all three shapes on 30 sizes from 1024^3 to 24576 x 24576 x 4096:
-//   * if the 256 x 128 tiles cannot give every CU an item even after slicing (1024^3: 64 items; 1536^3: 216), the
-//     128 x 128 shape X2, which makes twice as many: 24 us against 33 (W8) and 36 (W4) at 1024^3, FP16 mode;
-//   * otherwise W8: ahead of W4 by 3-8 % (FP16 mode) and 4-9 % (BF16 mode) from 2048^3 to 8192^3 and at
-//     16384 x 16384 x 256..4096, and ahead of X2 by 1-5 %;
-//   * except in FP16 mode from 0.75 GiB of packed operands up, where W4 takes over: tie at 12288^3 and
-//     8192 x 8192 x 16384, W4 ahead by 3 % at 14336^3, 4 % at 24576 x 24576 x 4096, 6 % at 16384^3, 10 % at 20480^3
-//     (in BF16 mode W8 stays ahead, by 3 % at 16384^3).
-// The comparison methods have the W4 shape only.
+// of both shapes on 60 sizes from 512^3 to 24576 x 24576 x 4096, in both modes.  X2 wins where items are short or few:
+//   * an item of the W4 plan is at most 512 deep: 16384 x 16384 x 256: 437 us against 574 (FP16), 656 against 750
+//     (BF16); x 512: 742 against 808; 512 x 512 x 16384 (32 slices of 512): 90 against 153; tie at x 768;
+//   * the W4 plan cannot give every CU an item even after slicing: 1024^3: 22 us against 31; 1536^3: 36 against 43.
+// Everywhere else W4 is ahead, by 2-5 % from 4096^3 to 8192^3 and at 16384 x 16384 x 2048..8192, by 8-10 % from
+// 12288^3 up.  The comparison methods have the W4 shape only.
 Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
   if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
-  if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
-  const Plan w8 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W8);
-  if (w8.items() < kPlanComputeUnits) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
-  if (mode == ECGEMM_MODE_FP16_SPLIT && w8.a_bytes + w8.b_bytes >= (size_t)768 << 20) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
-  return w8;
+  const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
+  if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
+  const int64_t depth_per_item = w4.tail_tiles > 0 && w4.full_tiles == 0 ? (w4.Kp + w4.tail_splits - 1) / w4.tail_splits : w4.Kp;
+  if (depth_per_item <= 512 || w4.items() < kPlanComputeUnits) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
+  return w4;
 }
 
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {

@@ -32,6 +32,7 @@
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "split_kernels.hpp"
 
@@ -111,6 +112,31 @@ __host__ __device__ constexpr int products_of(int method) {
        : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : 1;
 }
 
+// Term t of a method's product list: the parts of B and A it multiplies and the accumulator set it goes to.  One
+// term at a time runs over all tiles of a wave, so consecutive matrix instructions never share an accumulator.
+struct ProductTerm {
+  int qb, qa;
+  bool correction;
+};
+__host__ __device__ constexpr ProductTerm product_term(int method, int t) {
+  if (method == kMethodFp16Markidis)  // everything into one accumulator, smallest first
+    return t == 0 ? ProductTerm{1, 1, false} : t == 1 ? ProductTerm{1, 0, false} : t == 2 ? ProductTerm{0, 1, false} : ProductTerm{0, 0, false};
+  if (method == kMethodBf16Full)
+    return t == 0 ? ProductTerm{0, 0, false} : t == 1 ? ProductTerm{2, 0, true} : t == 2 ? ProductTerm{0, 2, true}
+         : t == 3 ? ProductTerm{1, 1, true} : t == 4 ? ProductTerm{1, 0, true} : ProductTerm{0, 1, true};
+  // kMethodFp16Split, kMethodFp16Unscaled, kMethodFp16Outside; the plain methods stop after the first term
+  return t == 0 ? ProductTerm{0, 0, false} : t == 1 ? ProductTerm{1, 0, true} : ProductTerm{0, 1, true};
+}
+
+template <class F, int... I>
+__device__ __forceinline__ void static_for_each(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {  // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>)
+  static_for_each(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int METHOD, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAGES_, int BLOCKS_PER_CU_ = 1>
 struct ProductConfig {
   static constexpr int BLOCKS_PER_CU = BLOCKS_PER_CU_;            // resident workgroups per CU (registers and LDS permitting)
@@ -131,6 +157,29 @@ struct ProductConfig {
   static constexpr int LOADS = (A_CHUNKS + B_CHUNKS) / WAVES;     // global_load_lds instructions per wave per stage
   static constexpr int FRAG_READS = (TM + TN) * NP;               // ds_read_b128 per wave per k step
   static constexpr int MFMAS = TM * TN * PRODUCTS;                // matrix instructions per wave per k step
+  // Fragment reads of a k step in the order in which its matrix instructions first need them.
+  struct ReadOrder {
+    bool from_b[FRAG_READS];
+    int tile[FRAG_READS], part[FRAG_READS];
+  };
+  static constexpr ReadOrder read_order() {
+    ReadOrder r{};
+    bool seen_a[TM][NP] = {}, seen_b[TN][NP] = {};
+    int n = 0;
+    for (int m = 0; m < MFMAS; ++m) {
+      const ProductTerm t = product_term(METHOD, m / (TM * TN));
+      const int i = (m % (TM * TN)) / TN, j = m % TN;
+      if (!seen_b[j][t.qb]) {
+        seen_b[j][t.qb] = true;
+        r.from_b[n] = true, r.tile[n] = j, r.part[n] = t.qb, ++n;
+      }
+      if (!seen_a[i][t.qa]) {
+        seen_a[i][t.qa] = true;
+        r.from_b[n] = false, r.tile[n] = i, r.part[n] = t.qa, ++n;
+      }
+    }
+    return r;
+  }
   static_assert(K_STEPS == 1 || K_STEPS == 2, "one or two k steps per stage");
   static_assert(STAGES >= 2 && (STAGES - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
   static_assert(LDS_BYTES * BLOCKS_PER_CU <= 160 * 1024, "LDS budget");
@@ -275,66 +324,69 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         }
   };
 
-  // One product at a time over all TM x TN tiles: consecutive instructions never share an accumulator.
-  auto multiply = [&](int set) {
-#define ECGEMM_PRODUCT(ACC, QB, QA)                                                    \
-  _Pragma("unroll") for (int i = 0; i < TM; ++i) _Pragma("unroll") for (int j = 0; j < TN; ++j) \
-      ACC[i][j] = Mfma<Cfg::kBf16>::run(fb[set][j][QB], fa[set][i][QA], ACC[i][j]);
-    if constexpr (Cfg::kMethod == kMethodFp16Markidis) {  // everything into one accumulator, smallest first
-      ECGEMM_PRODUCT(acc_main, 1, 1)
-      ECGEMM_PRODUCT(acc_main, 1, 0)
-      ECGEMM_PRODUCT(acc_main, 0, 1)
-      ECGEMM_PRODUCT(acc_main, 0, 0)
-    } else {
-      if constexpr (Cfg::kMethod == kMethodFp16Outside) {
+  // One k step, in a fixed order.  Matrix instruction m of the step (term by term over all TM x TN tiles) is followed
+  // by its share of the step's other work: at most one LDS-DMA load of the tile being requested (LOAD != 0) and at
+  // most one fragment read for a later k step (READ_SET >= 0), each spread evenly over the step.  A matrix instruction
+  // occupies the pipe for 8 passes, so whatever is issued behind it is free.  The fence after every slot keeps the
+  // compiler's scheduler from regrouping them: left to itself it issued the loads in one burst and put dependent
+  // matrix instructions next to each other.
+  auto fused_step = [&](auto set_c, auto load_c, auto read_set_c, int load_buf, int read_buf, auto read_ks_c) {
+    constexpr int SET = decltype(set_c)::value, READ_SET = decltype(read_set_c)::value, READ_KS = decltype(read_ks_c)::value;
+    constexpr int LOADS = decltype(load_c)::value != 0 ? kLoads : 0, READS = READ_SET >= 0 ? Cfg::FRAG_READS : 0;
+    constexpr int M = Cfg::MFMAS;
+    char* load_stage = lds + load_buf * Cfg::STAGE_BYTES + wave * 1024;
+    const char* read_stage = lds + read_buf * Cfg::STAGE_BYTES;
+    // one 32-bit vector offset per requested tile; kept opaque so that every address folds to "scalar base + vector
+    // offset" and the scalar bases never change
+    unsigned voff = lane_bytes + k_off;
+    if constexpr (LOADS > 0) {
+      asm volatile("" : "+v"(voff));
+      k_off += Cfg::ROW_CHUNKS * 1024;
+    }
+    static_for<M>([&](auto m_c) {
+      constexpr int m = decltype(m_c)::value;
+      constexpr ProductTerm term = product_term(Cfg::kMethod, m / (TM * TN));
+      constexpr int i = (m % (TM * TN)) / TN, j = m % TN;
+      if constexpr (Cfg::kMethod == kMethodFp16Outside && !term.correction) {
         // the matrix unit only multiplies: its accumulator input is zero and the running sum is kept by FP32 vector adds
+        float16_t zero;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+        const float16_t tmp = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], zero);
 #pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            float16_t zero;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-            const float16_t tmp = Mfma<Cfg::kBf16>::run(fb[set][j][0], fa[set][i][0], zero);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc_main[i][j][v] += tmp[v];
-          }
+        for (int v = 0; v < 16; ++v) acc_main[i][j][v] += tmp[v];
+      } else if constexpr (term.correction) {
+        acc_corr[i][j] = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_corr[i][j]);
       } else {
-        ECGEMM_PRODUCT(acc_main, 0, 0)
+        acc_main[i][j] = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_main[i][j]);
       }
-      if constexpr (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Unscaled ||
-                    Cfg::kMethod == kMethodFp16Outside) {
-        ECGEMM_PRODUCT(acc_corr, 1, 0)
-        ECGEMM_PRODUCT(acc_corr, 0, 1)
-      } else if constexpr (Cfg::kMethod == kMethodBf16Full) {
-        ECGEMM_PRODUCT(acc_corr, 2, 0)
-        ECGEMM_PRODUCT(acc_corr, 0, 2)
-        ECGEMM_PRODUCT(acc_corr, 1, 1)
-        ECGEMM_PRODUCT(acc_corr, 1, 0)
-        ECGEMM_PRODUCT(acc_corr, 0, 1)
-      }
-    }
-#undef ECGEMM_PRODUCT
-  };
-
-  // Asks the scheduler to thread the memory instructions of a k step between its matrix instructions
-  // (one matrix instruction occupies the pipe for 8 passes; anything issued meanwhile is free):
-  // `vmem` LDS-DMA loads and `ds` fragment reads, one of each per matrix instruction, then the rest.
-  auto interleave = [&](auto vmem_c, auto ds_c) {
-    constexpr int vmem = decltype(vmem_c)::value, ds = decltype(ds_c)::value;
-    constexpr int slots = vmem > ds ? vmem : ds;
-    static_assert(slots <= Cfg::MFMAS, "more memory instructions than matrix instructions");
-#pragma unroll
-    for (int i = 0; i < slots; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      if (i < vmem) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
-      if (i < ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x008, Cfg::MFMAS - slots, 0);
+      static_for<(m + 1) * LOADS / M - m * LOADS / M>([&](auto d_c) {
+        constexpr int l = m * LOADS / M + decltype(d_c)::value;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[l] + voff),
+                                         (void __attribute__((address_space(3)))*)(load_stage + l * Cfg::WAVES * 1024), 16, 0, 0);
+      });
+      static_for<(m + 1) * READS / M - m * READS / M>([&](auto d_c) {
+        constexpr int r = m * READS / M + decltype(d_c)::value;
+        constexpr typename Cfg::ReadOrder order = Cfg::read_order();
+        constexpr int tile = order.tile[r], part = order.part[r];
+        constexpr bool from_b = order.from_b[r];
+        if constexpr (from_b)
+          fb[READ_SET < 0 ? 0 : READ_SET][tile][part] =
+              *reinterpret_cast<const frag_t*>(read_stage + b_frag_off + ((tile * Cfg::K_STEPS + READ_KS) * NP + part) * 1024);
+        else
+          fa[READ_SET < 0 ? 0 : READ_SET][tile][part] =
+              *reinterpret_cast<const frag_t*>(read_stage + a_frag_off + ((tile * Cfg::K_STEPS + READ_KS) * NP + part) * 1024);
+      });
+      __builtin_amdgcn_sched_barrier(0);
+    });
   };
   typedef std::integral_constant<int, 0> none_t;
-  typedef std::integral_constant<int, Cfg::LOADS> loads_t;
-  typedef std::integral_constant<int, Cfg::FRAG_READS> reads_t;
+  typedef std::integral_constant<int, 1> loads_t;
+  typedef std::integral_constant<int, -1> no_reads_t;
+  typedef std::integral_constant<int, 0> set0_t;
+  typedef std::integral_constant<int, 1> set1_t;
+  typedef std::integral_constant<int, 0> ks0_t;
+  typedef std::integral_constant<int, 1> ks1_t;
 
   // Matrix instructions have no memory side effects, so the compiler would move the barrier across them;
   // the fences pin it.  The wait lets the newest STAGES - 2 tiles stay in flight (or none, near the end).
@@ -376,29 +428,19 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     if constexpr (Cfg::K_STEPS == 2) {
       int t = 0;
       for (; t < steady; ++t) {
-        read_frags(1, buf, 1);
-        multiply(0);
-        interleave(none_t{}, reads_t{});
+        fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
         stage_barrier(steady_t{});
-        issue_stage(buf);
-        read_frags(0, next, 0);
-        multiply(1);
-        interleave(loads_t{}, reads_t{});
+        fused_step(set1_t{}, loads_t{}, set0_t{}, buf, next, ks0_t{});
         advance();
       }
       for (; t < kt_count - 1; ++t) {
-        read_frags(1, buf, 1);
-        multiply(0);
-        interleave(none_t{}, reads_t{});
+        fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
         stage_barrier(none_t{});
-        read_frags(0, next, 0);
-        multiply(1);
-        interleave(none_t{}, reads_t{});
+        fused_step(set1_t{}, none_t{}, set0_t{}, 0, next, ks0_t{});
         advance();
       }
-      read_frags(1, buf, 1);
-      multiply(0);
-      multiply(1);
+      fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
+      fused_step(set1_t{}, none_t{}, no_reads_t{}, 0, 0, ks0_t{});
     } else {
       // One k step per stage: tile t is multiplied from fragment set t & 1 while set (t + 1) & 1 is filled.
       // Register arrays must be indexed statically, so the loops advance two tiles at a time and an odd
@@ -406,14 +448,11 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
       auto step = [&](auto set_c, auto issue_c, auto pending_c) {
         constexpr int set = decltype(set_c)::value;
         stage_barrier(pending_c);
-        if constexpr (decltype(issue_c)::value != 0) issue_stage(buf);
-        read_frags(set ^ 1, next, 0);
-        multiply(set);
-        interleave(issue_c, reads_t{});
+        fused_step(set_c, issue_c, std::integral_constant<int, set ^ 1>{}, buf, next, ks0_t{});
         advance();
       };
       auto odd_step = [&](auto issue_c, auto pending_c) {
-        step(std::integral_constant<int, 0>{}, issue_c, pending_c);
+        step(set0_t{}, issue_c, pending_c);
 #pragma unroll
         for (int q = 0; q < NP; ++q) {
 #pragma unroll
@@ -422,8 +461,6 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
           for (int j = 0; j < TN; ++j) fb[0][j][q] = fb[1][j][q];
         }
       };
-      typedef std::integral_constant<int, 0> set0_t;
-      typedef std::integral_constant<int, 1> set1_t;
       int t = 0;
       if (steady > 0 && (steady & 1)) {
         odd_step(loads_t{}, steady_t{});
@@ -441,7 +478,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         step(set0_t{}, none_t{}, none_t{});
         step(set1_t{}, none_t{}, none_t{});
       }
-      multiply(0);
+      fused_step(set0_t{}, none_t{}, no_reads_t{}, 0, 0, ks0_t{});
     }
   }
 

@@ -42,7 +42,7 @@ def _model(mode, opA, opB):
 
 def _shapes():
     import paper_2203_03341_amd as ec
-    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "w8": ec.SHAPE_256x128_W8, "x2": ec.SHAPE_128x128_X2}
+    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2}
 
 
 def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None, shape=None):
@@ -269,7 +269,7 @@ def test_odd_sizes_transA(mode):
 # ----- every kernel shape on its own (the automatic choice exercises only one per size)
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("shape", ["w4", "w8", "x2"])
+@pytest.mark.parametrize("shape", ["w4", "x2"])
 def test_every_kernel_shape(mode, shape):
     _check("T", "N", 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1, shape=shape)        # ragged, several tiles
     _check("N", "T", 700, 900, 1500, 1.5, 0.5, mode, "urand", seed=3, shape=shape)               # every tile sliced along K
@@ -277,7 +277,7 @@ def test_every_kernel_shape(mode, shape):
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("shape", ["w4", "w8", "x2"])
+@pytest.mark.parametrize("shape", ["w4", "x2"])
 def test_whole_tiles_followed_by_a_sliced_tail(mode, shape):
     """3000 x 3000: 288 tiles of 256 x 128 (256 whole + 32 in two slices) or 576 of 128 x 128 (512 whole + 64 sliced)."""
     rows = si.sample_indices(3000, 160, seed=2)
@@ -289,7 +289,7 @@ def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
     """Every shape adds up the k steps of an element in the same order; only slicing along K changes the bits."""
     M, N, K = 600, 500, 400
     A, B = _inputs(M, N, K, "N", "N", "urand", 6)
-    outs = [_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh) for sh in ("w4", "w8", "x2", None)]
+    outs = [_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh) for sh in ("w4", "x2", None)]
     for other in outs[1:]:
         assert np.array_equal(outs[0].view(np.uint32), other.view(np.uint32))
 
@@ -297,7 +297,7 @@ def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
 def test_a_shape_the_mode_has_no_kernel_for_is_refused():
     import paper_2203_03341_amd as ec
     h = ec.Handle()
-    h.set_shape(ec.SHAPE_256x128_W8)
+    h.set_shape(ec.SHAPE_128x128_X2)
     A, B = _inputs(64, 64, 64, "N", "N", "urand", 0)
     dA, dB, dC = to_device(A), to_device(B), empty_colmajor(64, 64, fill=0.0)
     with pytest.raises(ec.EcgemmError) as err:
