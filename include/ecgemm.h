@@ -13,7 +13,7 @@
  * Every function returns an ecgemm_status_t and never throws or aborts; on any status other
  * than ECGEMM_OK no work has been enqueued by that call.  A handle may be used by one host
  * thread at a time.  Results are bitwise reproducible for equal inputs and equal settings
- * (no floating-point atomics; the split-K reduction has a fixed order).
+ * (no floating-point atomics; the sums of tiles cut along K are added in a fixed order).
  */
 #ifndef ECGEMM_H
 #define ECGEMM_H

@@ -493,7 +493,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     request_first_stages(work);
   }
 
-  // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums under split-K).
+  // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums for a slice of a tile).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
   const int tile_m = done.tile_m, tile_n = done.tile_n;
   const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
