@@ -51,6 +51,8 @@ WORKLOADS = {
     "c5_deepk_bf16": (1024, 1024, 65536, "N", "N", "bf16", 1.0, 0.0, "urand", 256),
     "c5_odd_transA_fp16": (4095, 3001, 5003, "T", "N", "fp16", 1.0, 0.0, "urand", 1024),
     "c5_odd_transA_bf16": (4095, 3001, 5003, "T", "N", "bf16", 1.0, 0.0, "urand", 1024),
+    # not a baseline config: the size at which the one-kernel (fused) shape is compared with the split-first path
+    "x_1024_fp16_urand": (1024, 1024, 1024, "N", "N", "fp16", 1.0, 0.0, "urand", None),
 }
 DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
 
@@ -79,6 +81,8 @@ def main():
                     help="untimed warm-up steps (default: 3, more for short workloads so that the board, which drops "
                          "its clocks when idle, has run for 50 ms)")
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
+    ap.add_argument("--shape", default="auto", choices=["auto", "w4", "x2", "fused"],
+                    help="kernel shape (ecgemm_set_shape); auto lets the library choose")
     ap.add_argument("--no-oracle", action="store_true", help="skip the CPU oracle (no error figures, no cpu_baseline)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--power-seconds", type=float, default=2.5,
@@ -122,6 +126,8 @@ def main():
     stream = torch.cuda.current_stream()
     h = ec.Handle()
     h.set_stream(stream.cuda_stream)
+    h.set_shape({"auto": ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2,
+                 "fused": ec.SHAPE_128x128_FUSED}[args.shape])
     ws_bytes = h.workspace_size(M, N, K, mode_id)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     h.set_workspace(ws, ws_bytes)
@@ -219,7 +225,8 @@ def main():
         "vs_baseline": None, "dtype": "f16" if mode == "fp16" else "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": transA, "transB": transB,
                    "mode": mode, "alpha": alpha, "beta": beta, "products": parts_products,
-                   "inputs": "urand(-1,1)" if dist == "urand" else f"exp_rand{dist[0]} x exp_rand{dist[1]}", "seed": args.seed},
+                   "inputs": "urand(-1,1)" if dist == "urand" else f"exp_rand{dist[0]} x exp_rand{dist[1]}", "seed": args.seed,
+                   "shape": args.shape},
         "split_ms": round(split_ms / calls, 4), "product_ms": round(product_ms_avg, 4),
         "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
         "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",

@@ -126,15 +126,19 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
  * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for every later ecgemm_sgemm / ecgemm_product /
  * ecgemm_workspace_size on the handle:
  *   256x128_W4  block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
- *   128x128_X2  block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method).
- * Both shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
+ *   128x128_X2  block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
+ *   128x128_FUSED  the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
+ *               one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
+ *               packed operands in the workspace (the two modes of the method; ecgemm_sgemm only).
+ * All shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
  * the tail of the tile grid is sliced along K differently.  A call whose mode has no kernel of the forced shape
  * returns ECGEMM_ERR_UNSUPPORTED.
  */
 typedef enum {
   ECGEMM_SHAPE_AUTO = 0,
   ECGEMM_SHAPE_256x128_W4 = 1,
-  ECGEMM_SHAPE_128x128_X2 = 2
+  ECGEMM_SHAPE_128x128_X2 = 2,
+  ECGEMM_SHAPE_128x128_FUSED = 3
 } ecgemm_shape_t;
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 

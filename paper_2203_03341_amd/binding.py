@@ -18,7 +18,7 @@ OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
 MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_FP16_OUTSIDE_ACC = 2, 3, 4, 5, 6  # comparisons
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
-SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2 = 0, 1, 2
+SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
            "ecgemm_sgemm", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",

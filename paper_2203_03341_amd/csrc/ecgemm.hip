@@ -11,6 +11,7 @@
 #include <string>
 #include <vector>
 
+#include "fused_kernel.hpp"
 #include "product_kernel.hpp"
 #include "split_kernels.hpp"
 
@@ -58,7 +59,8 @@ typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideCon
 
 typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
 struct Shape {
-  void (*product)(ProductParams);
+  void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
+  void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
   reduce_fn_t reduce;
   int bm, bn, bk, threads, blocks_per_cu;
   // Deepest K for which the kernel runs as a persistent grid: one block per CU, each walking through several items
@@ -70,22 +72,26 @@ struct Shape {
 };
 template <class Cfg>
 constexpr Shape shape_of(int persistent_max_k) {
-  return Shape{product_kernel<Cfg>, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::THREADS, Cfg::BLOCKS_PER_CU,
-               persistent_max_k};
+  return Shape{product_kernel<Cfg>, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::THREADS,
+               Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
-constexpr Shape kNoShape{nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+template <int METHOD>
+constexpr Shape fused_shape() {
+  return Shape{nullptr, fused_kernel<METHOD>, reduce_tail_kernel<128, 128>, 128, 128, 32, 256, 1, 0};
+}
+constexpr Shape kNoShape{nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
 #ifndef ECGEMM_PERSISTENT_MAX_K
 #define ECGEMM_PERSISTENT_MAX_K 4096
 #endif
-const Shape kShapes[7][2] = {
-    {shape_of<Fp16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Fp16X2>(0)},
-    {shape_of<Bf16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Bf16X2>(0)},
-    {shape_of<MarkidisConfig>(4096), kNoShape},
-    {shape_of<UnscaledConfig>(4096), kNoShape},
-    {shape_of<PlainFp16Config>(4096), kNoShape},
-    {shape_of<PlainBf16Config>(4096), kNoShape},
-    {shape_of<OutsideConfig>(4096), kNoShape},
+const Shape kShapes[7][3] = {
+    {shape_of<Fp16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
+    {shape_of<Bf16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
+    {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
+    {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
+    {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
+    {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
+    {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
 };
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -99,7 +105,7 @@ static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEM
               (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain &&
               (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside,
               "mode numbering");
-inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_X2; }
+inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_FUSED; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
 
 size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
@@ -127,7 +133,7 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   Plan pl;
   pl.Kp = round_up(K, kDepthPad);
   pl.shape = &kShapes[(int)mode][(int)shape - 1];
-  if (pl.shape->product == nullptr) {
+  if (pl.shape->product == nullptr && pl.shape->fused == nullptr) {
     pl.shape = nullptr;
     return pl;
   }
@@ -137,15 +143,16 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   pl.k_tiles = (int)(pl.Kp / pl.shape->bk);
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   const int64_t slots = (int64_t)kPlanComputeUnits * pl.shape->blocks_per_cu;
-  const int64_t tail = tiles % slots;
+  // (the fused kernel slices either every tile or none)
+  const int64_t tail = pl.shape->fused ? (tiles < slots ? tiles : 0) : tiles % slots;
   int64_t splits = tail > 0 ? slots / tail : 1;
   splits = std::min<int64_t>(splits, pl.Kp / 512);
   splits = std::max<int64_t>(1, std::min<int64_t>(splits, 64));
   pl.tail_splits = (int)splits;
   pl.tail_tiles = splits > 1 ? (int)tail : 0;
   pl.full_tiles = (int)(tiles - pl.tail_tiles);
-  pl.a_bytes = align256(packed_bytes(M, K, mode));
-  pl.b_bytes = align256(packed_bytes(N, K, mode));
+  pl.a_bytes = pl.shape->fused ? 0 : align256(packed_bytes(M, K, mode));
+  pl.b_bytes = pl.shape->fused ? 0 : align256(packed_bytes(N, K, mode));
   pl.partial_bytes = splits > 1 ? align256((size_t)splits * tail * bm * bn * sizeof(float)) : 0;
   pl.total_bytes = pl.a_bytes + pl.b_bytes + pl.partial_bytes;
   return pl;
@@ -256,6 +263,47 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bn / 16));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
                        pl.full_tiles, pl.tiles_m, pl.tiles_n, M, N, alpha, beta, C, ldc);
+    ECGEMM_HIP(h, hipGetLastError());
+  }
+  return ECGEMM_OK;
+}
+
+// Steps 1 to 5 in one kernel, on the caller's FP32 operands (small products).
+ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
+                             int64_t K, float alpha, const float* A, int64_t lda, const float* B, int64_t ldb, float beta,
+                             float* C, int64_t ldc, float* partials) {
+  FusedParams fp;
+  fp.A = A;
+  fp.B = B;
+  fp.lda = lda;
+  fp.ldb = ldb;
+  fp.a_k_contiguous = transA == ECGEMM_OP_T;
+  fp.b_k_contiguous = transB == ECGEMM_OP_N;
+  fp.a_vec = fp.a_k_contiguous && lda % 4 == 0 && (uintptr_t)A % 16 == 0;
+  fp.b_vec = fp.b_k_contiguous && ldb % 4 == 0 && (uintptr_t)B % 16 == 0;
+  fp.prescale_a = std::ldexp(1.0f, h->log2_scale_a);
+  fp.prescale_b = std::ldexp(1.0f, h->log2_scale_b);
+  fp.M = M;
+  fp.N = N;
+  fp.K = K;
+  fp.ldc = ldc;
+  fp.stages = (int)(pl.Kp / 32);
+  fp.tiles_m = pl.tiles_m;
+  fp.tiles_n = pl.tiles_n;
+  fp.splits = pl.tail_splits;
+  fp.alpha = alpha;
+  fp.beta = beta;
+  fp.out_scale = std::ldexp(1.0f, -(h->log2_scale_a + h->log2_scale_b));
+  fp.C = C;
+  fp.partials = partials;
+  const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+  void* args[] = {&fp};
+  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused), dim3((unsigned)(tiles * pl.tail_splits)), dim3(256),
+                                args, 0, h->stream));
+  if (pl.tail_splits > 1) {
+    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 / 16));
+    hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
+                       pl.tiles_m, pl.tiles_n, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -585,6 +633,18 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
     ECGEMM_HIP(h, hipEventRecord(tc.start, h->stream));
   }
 
+  if (pl.shape->fused) {
+    if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
+    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, partials);
+    if (st != ECGEMM_OK) return st;
+    if (h->timing) {
+      ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
+      h->timed.push_back(tc);
+      lease.keep = true;
+    }
+    return ECGEMM_OK;
+  }
+
   // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
   // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
   st = launch_split(h, transA, M, K, A, lda, mode, a_packed, h->log2_scale_a);
@@ -625,7 +685,8 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
   ecgemm_status_t st = check_sizes(h, M, N, K, mode);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
-  if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not exist for this mode");
+  if (!pl.shape || pl.shape->fused)
+    return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not take packed operands in this mode");
   if (pl.items() + 16 > 0x7fffffffLL)
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: too many tiles");
   char* ws = nullptr;

@@ -57,6 +57,12 @@ struct ProductParams {
   float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
 };
 
+// alpha c + beta C_in with the roundings fixed (alpha c rounded, then one fused multiply-add), so that the compiler
+// cannot pick a different contraction in each kernel and every kernel shape gives the same bits.
+__device__ __forceinline__ float scaled_sum(float alpha, float c, float beta, float c_in) {
+  return __builtin_fmaf(beta, c_in, alpha * c);
+}
+
 #ifndef ECGEMM_GROUP_M
 #define ECGEMM_GROUP_M 4
 #endif
@@ -526,13 +532,13 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   } else if (interior) {
     for_each_output([&](int64_t m, int64_t n, float c) {
       float* dst = c_base + m + n * ldc;
-      *dst = p.alpha * c + p.beta * *dst;
+      *dst = scaled_sum(p.alpha, c, p.beta, *dst);
     });
   } else {
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
         float* dst = c_base + m + n * ldc;
-        *dst = (p.beta == 0.0f) ? p.alpha * c : p.alpha * c + p.beta * *dst;
+        *dst = (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst);
       }
     });
   }
@@ -608,7 +614,7 @@ __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restric
     for (int s = 0; s < tail_splits; ++s)
       sum += partials[(((int64_t)s * tail_tiles + blockIdx.x) * BN + n_local) * BM + m_local];
     float* dst = C + m + n * ldc;
-    *dst = (beta == 0.0f) ? alpha * sum : alpha * sum + beta * *dst;
+    *dst = (beta == 0.0f) ? alpha * sum : scaled_sum(alpha, sum, beta, *dst);
   }
 }
 

@@ -59,24 +59,22 @@ struct Splitter {
       if constexpr (kParts == 2) {
         float residual = v - (float)hi;                                  // exact
         if constexpr (KIND == kSplitFp16Scaled) residual *= 2048.0f;     // exact
-        _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
-        if (__builtin_isinf((float)hi)) lo = (_Float16)0.0f;
-        out[1] = __builtin_bit_cast(unsigned short, lo);
+        const _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
+        // an infinite input keeps only its high part (selected on the bits: no branch around the conversion)
+        const unsigned short keep = (__builtin_bit_cast(unsigned short, hi) & 0x7fffu) == 0x7c00u ? 0u : 0xffffu;
+        out[1] = __builtin_bit_cast(unsigned short, lo) & keep;
       }
     } else {
       const __bf16 b0 = (__bf16)saturate_finite(v, kBf16Max);
       out[0] = __builtin_bit_cast(unsigned short, b0);
       if constexpr (kParts == 3) {
         const float r1 = v - (float)b0;
-        __bf16 b1 = (__bf16)saturate_finite(r1, kBf16Max);
+        const __bf16 b1 = (__bf16)saturate_finite(r1, kBf16Max);
         const float r2 = r1 - (float)b1;
-        __bf16 b2 = (__bf16)saturate_finite(r2, kBf16Max);
-        if (__builtin_isinf((float)b0)) {
-          b1 = (__bf16)0.0f;
-          b2 = (__bf16)0.0f;
-        }
-        out[1] = __builtin_bit_cast(unsigned short, b1);
-        out[2] = __builtin_bit_cast(unsigned short, b2);
+        const __bf16 b2 = (__bf16)saturate_finite(r2, kBf16Max);
+        const unsigned short keep = (out[0] & 0x7fffu) == 0x7f80u ? 0u : 0xffffu;  // infinite input: high part only
+        out[1] = __builtin_bit_cast(unsigned short, b1) & keep;
+        out[2] = __builtin_bit_cast(unsigned short, b2) & keep;
       }
     }
   }

@@ -42,7 +42,7 @@ def _model(mode, opA, opB):
 
 def _shapes():
     import paper_2203_03341_amd as ec
-    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2}
+    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2, "fused": ec.SHAPE_128x128_FUSED}
 
 
 def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None, shape=None):
@@ -131,9 +131,11 @@ def test_config1_256_cubed(mode):
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
 @pytest.mark.parametrize("transA", ["N", "T"])
 @pytest.mark.parametrize("transB", ["N", "T"])
-def test_transposes_ragged_and_alpha_beta(mode, transA, transB):
-    _check(transA, transB, 300, 200, 77, 1.5, 0.5, mode, "urand", seed=1, pad=3)
-    _check(transA, transB, 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1)
+@pytest.mark.parametrize("shape", [None, "fused"])
+def test_transposes_ragged_and_alpha_beta(mode, transA, transB, shape):
+    _check(transA, transB, 300, 200, 77, 1.5, 0.5, mode, "urand", seed=1, pad=3, shape=shape)
+    _check(transA, transB, 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1, shape=shape)
+    _check(transA, transB, 260, 132, 96, 1.0, 0.0, mode, "urand", seed=3, pad=0, shape=shape)   # 16-byte aligned rows
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
@@ -269,7 +271,7 @@ def test_odd_sizes_transA(mode):
 # ----- every kernel shape on its own (the automatic choice exercises only one per size)
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("shape", ["w4", "x2"])
+@pytest.mark.parametrize("shape", ["w4", "x2", "fused"])
 def test_every_kernel_shape(mode, shape):
     _check("T", "N", 513, 259, 130, -1.0, 1.0, mode, "urand", seed=2, pad=1, shape=shape)        # ragged, several tiles
     _check("N", "T", 700, 900, 1500, 1.5, 0.5, mode, "urand", seed=3, shape=shape)               # every tile sliced along K
@@ -277,7 +279,7 @@ def test_every_kernel_shape(mode, shape):
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("shape", ["w4", "x2"])
+@pytest.mark.parametrize("shape", ["w4", "x2", "fused"])
 def test_whole_tiles_followed_by_a_sliced_tail(mode, shape):
     """3000 x 3000: 288 tiles of 256 x 128 (256 whole + 32 in two slices) or 576 of 128 x 128 (512 whole + 64 sliced)."""
     rows = si.sample_indices(3000, 160, seed=2)
@@ -289,7 +291,7 @@ def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
     """Every shape adds up the k steps of an element in the same order; only slicing along K changes the bits."""
     M, N, K = 600, 500, 400
     A, B = _inputs(M, N, K, "N", "N", "urand", 6)
-    outs = [_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh) for sh in ("w4", "x2", None)]
+    outs = [_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh) for sh in ("w4", "x2", "fused", None)]
     for other in outs[1:]:
         assert np.array_equal(outs[0].view(np.uint32), other.view(np.uint32))
 
@@ -307,6 +309,12 @@ def test_a_shape_the_mode_has_no_kernel_for_is_refused():
         h.set_shape(7)
     h.set_shape(ec.SHAPE_AUTO)
     h.sgemm(ec.OP_N, ec.OP_N, 64, 64, 64, 1.0, dA, 64, dB, 64, 0.0, dC, 64, ec.MODE_FP16_MARKIDIS)
+    # the fused shape has no use for operands split beforehand
+    h.set_shape(ec.SHAPE_128x128_FUSED)
+    packed = empty_colmajor(ec.split_size(64, 64, ec.MODE_FP16_SPLIT) // 4, 1, fill=0.0)
+    with pytest.raises(ec.EcgemmError) as err:
+        h.product(64, 64, 64, 1.0, packed, packed, 0.0, dC, 64, ec.MODE_FP16_SPLIT)
+    assert err.value.status == ec.ERR_UNSUPPORTED
     h.destroy()
 
 
@@ -451,6 +459,10 @@ def test_prescaling_brings_small_inputs_into_the_fp16_window():
     h.set_scaling(shift, shift)
     scaled = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
     assert gemm.relative_residual(c64, scaled) <= RATIO * r_cpu
+    h.set_shape(ec.SHAPE_128x128_FUSED)                            # the one-kernel path scales in its own split
+    fused = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
+    assert np.array_equal(fused.view(np.uint32), scaled.view(np.uint32))
+    h.set_shape(ec.SHAPE_AUTO)
     h.set_scaling(0, 0)
     again = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
     assert np.array_equal(again.view(np.uint32), plain.view(np.uint32))
