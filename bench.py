@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--power-seconds", type=float, default=2.5,
                     help="after the timed steps, loop the same call for this long while sampling board power from sysfs "
                          "every 20 ms (the paper samples NVML every 0.02 s over >= 2 s); 0 disables")
+    ap.add_argument("--library-sgemm", action="store_true",
+                    help="also time (and power-sample) the vendor library's FP32 GEMM on the same operands, for context")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the matrix-instruction-only rate measurement")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, for scaling "
@@ -181,42 +183,72 @@ def main():
         ceiling = probe_flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
 
     # ---- board power while the same call runs back to back
-    power = None
-    if args.power_seconds > 0:
+    def power_while(call, seconds):
         import glob
         import threading
         paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
-        if paths:
-            samples, stop_flag = [], threading.Event()
+        if not paths:
+            return None
+        samples, stop_flag = [], threading.Event()
 
-            def sampler():
-                while not stop_flag.is_set():
-                    try:
-                        with open(paths[0]) as f:
-                            samples.append(int(f.read()) * 1e-6)
-                    except OSError:
-                        pass
-                    time.sleep(0.02)
+        def sampler():
+            while not stop_flag.is_set():
+                try:
+                    with open(paths[0]) as f:
+                        samples.append(int(f.read()) * 1e-6)
+                except OSError:
+                    pass
+                time.sleep(0.02)
 
-            th = threading.Thread(target=sampler)
-            t_begin = time.perf_counter()
-            calls_done = 0
-            th.start()
-            while time.perf_counter() - t_begin < args.power_seconds:
-                for _ in range(4):
-                    step()
-                torch.cuda.synchronize()
-                calls_done += 4
-            elapsed = time.perf_counter() - t_begin
-            stop_flag.set()
-            th.join()
-            steady = samples[len(samples) // 4:]        # drop the ramp-up quarter
-            if steady:
-                watts = float(np.mean(steady))
-                rate = flops * calls_done / elapsed
-                power = {"avg_w": round(watts, 1), "max_w": round(float(np.max(steady)), 1), "samples": len(steady),
-                         "interval_s": 0.02, "seconds": round(elapsed, 2), "source": paths[0],
-                         "tflops_during": round(rate / 1e12, 1), "gflops_per_w": round(rate / 1e9 / watts, 1)}
+        th = threading.Thread(target=sampler)
+        t_begin = time.perf_counter()
+        calls_done = 0
+        th.start()
+        while time.perf_counter() - t_begin < seconds:
+            for _ in range(4):
+                call()
+            torch.cuda.synchronize()
+            calls_done += 4
+        elapsed = time.perf_counter() - t_begin
+        stop_flag.set()
+        th.join()
+        steady = samples[len(samples) // 4:]        # drop the ramp-up quarter
+        if not steady:
+            return None
+        watts = float(np.mean(steady))
+        rate = flops * calls_done / elapsed
+        return {"avg_w": round(watts, 1), "max_w": round(float(np.max(steady)), 1), "samples": len(steady),
+                "interval_s": 0.02, "seconds": round(elapsed, 2), "source": paths[0],
+                "tflops_during": round(rate / 1e12, 1), "gflops_per_w": round(rate / 1e9 / watts, 1)}
+
+    power = power_while(step, args.power_seconds) if args.power_seconds > 0 else None
+
+    # ---- context only: the vendor library's FP32 GEMM (rocBLAS / hipBLASLt behind torch.matmul) on the same operands,
+    # timed and power-sampled the same way (the paper sets its method against cuBLAS SGEMM)
+    library = None
+    if args.library_sgemm:
+        opA_T = dA if transA == "N" else dA.T        # K x M as a row-major tensor
+        opB_T = dB if transB == "N" else dB.T        # N x K
+        ref = torch.empty((N, M), dtype=torch.float32, device="cuda")
+
+        def library_call():
+            torch.matmul(opB_T, opA_T, out=ref)
+
+        for _ in range(3):
+            library_call()
+        torch.cuda.synchronize()
+        l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = max(3, min(args.steps, int(np.ceil(1000.0 / max(expected_ms * 4, 0.05)))))
+        l0.record(stream)
+        for _ in range(reps):
+            library_call()
+        l1.record(stream)
+        torch.cuda.synchronize()
+        lib_ms = l0.elapsed_time(l1) / reps
+        library = {"what": "torch.matmul, float32, allow_tf32 off", "ms_per_call": round(lib_ms, 4),
+                   "tflops": round(flops / (lib_ms * 1e-3) / 1e12, 2),
+                   "power": power_while(library_call, args.power_seconds) if args.power_seconds > 0 else None}
+        del ref
 
     got = dC.cpu().numpy().T          # logical M x N
     result = {
@@ -237,6 +269,7 @@ def main():
                      "mfma_only_random_operands_tflops": None if ceiling is None else round(ceiling, 1),
                      "frac_of_mfma_only": None if ceiling is None else round(mfma_tflops / ceiling, 4)},
         "power": power,
+        "library_sgemm": library,
     }
 
     if not args.no_oracle:
