@@ -63,7 +63,7 @@ typedef enum {
     ECGEMM_ERR_INVALID_ARG = 1, /* bad enum, negative size, leading dimension too small, null pointer */
     ECGEMM_ERR_ALLOC = 2,       /* device workspace could not be allocated, or the caller's is too small */
     ECGEMM_ERR_HIP = 3,         /* a HIP runtime call failed; see ecgemm_last_error_string */
-    ECGEMM_ERR_UNSUPPORTED = 4  /* device is not gfx950 */
+    ECGEMM_ERR_UNSUPPORTED = 4  /* device is not gfx950, or the forced kernel shape does not exist for the mode */
 } ecgemm_status_t;
 
 /* Creates a handle bound to the current HIP device.  Allocates no device memory.  The device must
@@ -78,8 +78,10 @@ ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle);
  * Default: the null stream. */
 ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 
-/* Bytes of device workspace ecgemm_sgemm needs for this problem (the handle is not used and may be NULL): the split operands in matrix-unit
- * fragment order, zero-padded to whole tiles, plus the partial sums when K is divided among blocks.
+/* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit fragment order,
+ * zero-padded to whole tiles, plus at most 32 MiB of partial sums for output tiles that are cut into slices along K.
+ * The plan behind it is made for the 256 compute units of the MI355X, so the size depends on the problem, the mode and
+ * the kernel shape only; `handle` supplies the shape set with ecgemm_set_shape and may be NULL (automatic choice).
  * `bytes` is a host pointer. */
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
                                       ecgemm_mode_t mode, size_t *bytes);
@@ -100,7 +102,7 @@ ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void *device_buffer
  *      not propagate when beta == 0), written for all M x N elements.  C must not overlap A or B.
  *   alpha, beta: host scalars.
  *
- * Steps (each a kernel on the handle's stream):
+ * Steps (each a kernel on the handle's stream; the fused kernel shape does all three in one):
  *   1. split: A and B are read once and written to the workspace as FP16 (v16, dv16 = (v - v16) * 2^11;
  *      Eqs. corr-1-1024 .. corr-4-1024) or as three BF16 terms, round to nearest even, K-contiguous,
  *      in the lane order the matrix instruction wants, zero-padded to tile multiples.  A finite input
@@ -121,18 +123,19 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
- * Kernel shape of the product (steps 2 to 5); a tuning and test knob.  The paper's counterpart are the block and warp
- * tile sizes that it picks for each matrix size by grid search (section "Parameter tuning of CUTLASS").
- * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for every later ecgemm_sgemm / ecgemm_product /
- * ecgemm_workspace_size on the handle:
- *   256x128_W4  block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
- *   128x128_X2  block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
+ * Kernel shape of the product (steps 2 and 3 of ecgemm_sgemm); a tuning and test knob.  The paper's counterpart are the
+ * block and warp tile sizes that it picks for each matrix size by grid search (section "Parameter tuning of CUTLASS").
+ * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for
+ * every later ecgemm_sgemm / ecgemm_product / ecgemm_workspace_size on the handle:
+ *   256x128_W4     block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
+ *   128x128_X2     block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
  *   128x128_FUSED  the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
- *               one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
- *               packed operands in the workspace (the two modes of the method; ecgemm_sgemm only).
- * All shapes compute the same products in the same per-element order; results agree bit for bit between shapes unless
- * the tail of the tile grid is sliced along K differently.  A call whose mode has no kernel of the forced shape
- * returns ECGEMM_ERR_UNSUPPORTED.
+ *                  one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
+ *                  packed operands in the workspace (the two modes of the method; ecgemm_sgemm only).  Slower than
+ *                  the other two at every size on this hardware; never picked automatically.
+ * All shapes form the same products in the same per-element order; results agree bit for bit between shapes unless
+ * output tiles are sliced along K differently.  A call whose mode has no kernel of the forced shape returns
+ * ECGEMM_ERR_UNSUPPORTED.
  */
 typedef enum {
   ECGEMM_SHAPE_AUTO = 0,
@@ -182,8 +185,9 @@ ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, e
  *     packed[row_block][k_step][part][lane][8]   (16-bit elements)
  * with row_block = r / 32, k_step = k / 16, lane = ((k % 16) / 8) * 32 + r % 32, element k % 8;
  * part 0 is the high part; there are 2 parts in the FP16 pair modes, 3 in ECGEMM_MODE_BF16_FULL, 1 in the plain
- * modes.  Rows are padded to a multiple of 256 and depth to a multiple of 32, with zeros.  src: device, FP32, column-major with leading dimension ld; op == N means X(r, k) =
- * src[r + k * ld] (ld >= rows), op == T means X(r, k) = src[k + r * ld] (ld >= depth).
+ * modes.  Rows are padded to a multiple of 256 and depth to a multiple of 32, with zeros.  src: device, FP32,
+ * column-major with leading dimension ld; op == N means X(r, k) = src[r + k * ld] (ld >= rows), op == T means
+ * X(r, k) = src[k + r * ld] (ld >= depth).
  */
 ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth,
                              const float *src, int64_t ld, ecgemm_mode_t mode, void *packed);
@@ -194,7 +198,7 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
  * given as the outputs of ecgemm_split(handle, ..., rows = M or N, depth = K, ..., mode, packed) for the SAME mode.
  * For op(B) that means: ecgemm_split(op = T if B is stored K x N (transB == N), op = N if stored N x K).  packedA,
  * packedB: device, read only.  C, ldc, alpha, beta as in ecgemm_sgemm.  Uses the workspace only for the partial sums
- * of a divided K.  The result is bitwise what ecgemm_sgemm returns for the same operands.
+ * of tiles sliced along K.  The result is bitwise what ecgemm_sgemm returns for the same operands and kernel shape.
  */
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
                                const void *packedA, const void *packedB, float beta, float *C, int64_t ldc,
