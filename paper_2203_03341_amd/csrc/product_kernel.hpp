@@ -221,6 +221,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #ifndef ECGEMM_XCD_REMAP
 #define ECGEMM_XCD_REMAP 1
 #endif
+#ifndef ECGEMM_READ_TAIL
+#define ECGEMM_READ_TAIL 6
+#endif
   const int tail_items = p.tail_tiles * p.tail_splits;
   auto locate = [&](int item) {
     Work w;
@@ -371,8 +374,12 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[l] + voff),
                                          (void __attribute__((address_space(3)))*)(load_stage + l * Cfg::WAVES * 1024), 16, 0, 0);
       });
-      static_for<(m + 1) * READS / M - m * READS / M>([&](auto d_c) {
-        constexpr int r = m * READS / M + decltype(d_c)::value;
+      // (the reads stop ECGEMM_READ_TAIL slots before the end of the step, so that the last of them has arrived
+      // when the wave gets to the wait in front of the barrier or of the next step)
+      constexpr int SPAN = M > 2 * ECGEMM_READ_TAIL ? M - ECGEMM_READ_TAIL : M;
+      constexpr int r_begin = m < SPAN ? m * READS / SPAN : READS, r_end = m + 1 < SPAN ? (m + 1) * READS / SPAN : READS;
+      static_for<r_end - r_begin>([&](auto d_c) {
+        constexpr int r = r_begin + decltype(d_c)::value;
         constexpr typename Cfg::ReadOrder order = Cfg::read_order();
         constexpr int tile = order.tile[r], part = order.part[r];
         constexpr bool from_b = order.from_b[r];
