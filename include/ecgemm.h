@@ -157,6 +157,31 @@ ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int log2_scale_b);
 
 /*
+ * Per-row / per-column power-of-two pre-scaling, for matrices whose rows (of op(A)) or columns (of op(B)) differ in
+ * magnitude by more than the exponent window of the FP16 pair lets one global factor absorb: the same remedy as
+ * ecgemm_set_scaling (end of section "Effect of the exponent range of input matrices"), applied vector-wise.
+ *
+ * ecgemm_sgemm_scaled is ecgemm_sgemm with row m of op(A) multiplied by 2^row_log2_scale_a[m] and column n of op(B) by
+ * 2^col_log2_scale_b[n] before the split (exact), and element (m, n) of the product multiplied by 2^-row_log2_scale_a[m]
+ * and then by 2^-col_log2_scale_b[n] (exact unless the result leaves the FP32 range) before alpha / beta.  The vectors
+ * are device arrays of M and N 32-bit integers in [-126, 126], read during the call and not kept; both NULL gives
+ * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.  Not available with the fused kernel shape.
+ *
+ * ecgemm_row_scales writes such a vector: for each row r of X = op(src) (rows x depth; op and ld as in ecgemm_split)
+ * the exponent that moves the row's largest non-zero finite element into the binade 2^target_exponent, 0 for a row
+ * without one.  For the columns of op(B) pass B the way ecgemm_split takes it: op = T if B is stored K x N
+ * (transB == N), op = N if stored N x K, rows = N, depth = K.  Runs on the handle's stream without waiting for it.
+ * A target of 14 puts every row's largest binade at the top of the window in which the FP16 pair is fully precise.
+ */
+ecgemm_status_t ecgemm_row_scales(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth, const float *src,
+                                  int64_t ld, int target_exponent, int32_t *log2_scale);
+ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                    int64_t M, int64_t N, int64_t K, float alpha,
+                                    const float *A, int64_t lda, const float *B, int64_t ldb,
+                                    float beta, float *C, int64_t ldc, ecgemm_mode_t mode,
+                                    const int32_t *row_log2_scale_a, const int32_t *col_log2_scale_b);
+
+/*
  * Helper for choosing a mode or a pre-scaling: binary exponents (floor(log2 |x|)) of the smallest and the largest
  * non-zero finite element of a column-major rows x cols FP32 matrix (src: device, ld >= rows).  Subnormals count as
  * -127; a matrix without such elements gives (INT_MAX, INT_MIN).  Unlike the other calls this one waits for the

@@ -191,7 +191,8 @@ ecgemm_status_t hip_fail(ecgemm_handle_t h, hipError_t e, const char* where) {
 
 // X = op(src) is rows x depth.  op == N: X(r, k) = src[r + k * ld]; op == T: X(r, k) = src[k + r * ld].
 ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
-                             int64_t ld, ecgemm_mode_t mode, void* packed, int log2_prescale = 0) {
+                             int64_t ld, ecgemm_mode_t mode, void* packed, int log2_prescale = 0,
+                             const int* row_log2_scale = nullptr) {
   const float prescale = std::ldexp(1.0f, log2_prescale);
   const int64_t Rp = round_up(rows, kRowPad), Kp = round_up(depth, kDepthPad);
   const int64_t k_steps = Kp / 16;
@@ -206,16 +207,16 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
   do {                                                                                                                     \
     if (!k_contiguous && vec)                                                                                              \
       hipLaunchKernelGGL((split_r_contiguous_wide<KIND>), grid256, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
-                         prescale, out, (unsigned)(Rp / 256));                                                             \
+                         prescale, row_log2_scale, out, (unsigned)(Rp / 256));                                             \
     else if (!k_contiguous)                                                                                                \
       hipLaunchKernelGGL((split_r_contiguous<KIND>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, \
-                         out, (unsigned)(Rp / 64));                                                                        \
+                         row_log2_scale, out, (unsigned)(Rp / 64));                                                        \
     else if (vec)                                                                                                          \
       hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
-                         prescale, out, k_tiles);                                                                          \
+                         prescale, row_log2_scale, out, k_tiles);                                                          \
     else                                                                                                                   \
       hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,    \
-                         prescale, out, k_tiles);                                                                          \
+                         prescale, row_log2_scale, out, k_tiles);                                                          \
   } while (0)
   switch (split_kind_of((int)mode)) {
     case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;
@@ -232,7 +233,7 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
                                const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials,
-                               int log2_out_scale = 0) {
+                               int log2_out_scale = 0, const int* row_log2_scale = nullptr, const int* col_log2_scale = nullptr) {
   ProductParams pp;
   pp.a_packed = static_cast<const char*>(a_packed);
   pp.b_packed = static_cast<const char*>(b_packed);
@@ -249,6 +250,8 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.alpha = alpha;
   pp.beta = beta;
   pp.out_scale = std::ldexp(1.0f, log2_out_scale);
+  pp.row_log2_scale = row_log2_scale;
+  pp.col_log2_scale = col_log2_scale;
   pp.C = C;
   pp.partials = partials;
   // Grid, always a multiple of the 8 XCDs: one block per item, or a persistent grid (see Shape::persistent_max_k).
@@ -493,6 +496,31 @@ ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int6
   return ECGEMM_OK;
 }
 
+ecgemm_status_t ecgemm_row_scales(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
+                                  int64_t ld, int target_exponent, int32_t* log2_scale) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!valid_op(op) || rows < 0 || depth < 0 || target_exponent < -126 || target_exponent > 126)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: bad argument");
+  if (rows == 0) return ECGEMM_OK;
+  if (!log2_scale) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: null output");
+  if (depth > 0 && (!src || ld < (op == ECGEMM_OP_N ? rows : depth)))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: null source or leading dimension too small");
+  const int64_t row_blocks = (rows + 255) / 256, slabs = (depth + 2047) / 2048;
+  if (row_blocks > 0x7fffffff || rows > 0x1fffffffLL || slabs > 65535)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: operand too large");
+  hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)row_blocks), dim3(256), 0, handle->stream, log2_scale, rows, INT_MIN);
+  if (depth > 0) {
+    const bool k_contiguous = op == ECGEMM_OP_T;
+    const dim3 grid((unsigned)(k_contiguous ? (rows + 3) / 4 : row_blocks), (unsigned)slabs);
+    hipLaunchKernelGGL(row_max_exponent_kernel, grid, dim3(256), 0, handle->stream, src, ld, rows, depth, (int)k_contiguous,
+                       log2_scale);
+  }
+  hipLaunchKernelGGL(finish_row_scales_kernel, dim3((unsigned)row_blocks), dim3(256), 0, handle->stream, log2_scale, rows,
+                     target_exponent);
+  ECGEMM_HIP(handle, hipGetLastError());
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                                    int64_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
                                    ecgemm_mode_t* mode, int* log2_scale_a, int* log2_scale_b) {
@@ -581,6 +609,14 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              int64_t M, int64_t N, int64_t K, float alpha,
                              const float* A, int64_t lda, const float* B, int64_t ldb,
                              float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
+  return ecgemm_sgemm_scaled(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr);
+}
+
+ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                    int64_t M, int64_t N, int64_t K, float alpha,
+                                    const float* A, int64_t lda, const float* B, int64_t ldb,
+                                    float beta, float* C, int64_t ldc, ecgemm_mode_t mode,
+                                    const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
   ecgemm_handle_t h = handle;
   if (!h) return ECGEMM_ERR_INVALID_ARG;
   if (!valid_op(transA) || !valid_op(transB) || !valid_mode(mode))
@@ -604,6 +640,10 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
   if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
+  if ((row_log2_scale_a == nullptr) != (col_log2_scale_b == nullptr))
+    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm_scaled: give both scaling vectors or neither");
+  if (row_log2_scale_a && pl.shape->fused)
+    return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm_scaled: the fused kernel shape takes no scaling vectors");
   if (pl.items() + 16 > 0x7fffffffLL)
     return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: too many tiles");
   char* ws = nullptr;
@@ -647,15 +687,16 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
 
   // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
   // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
-  st = launch_split(h, transA, M, K, A, lda, mode, a_packed, h->log2_scale_a);
+  st = launch_split(h, transA, M, K, A, lda, mode, a_packed, h->log2_scale_a, row_log2_scale_a);
   if (st != ECGEMM_OK) return st;
-  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed, h->log2_scale_b);
+  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed, h->log2_scale_b,
+                    col_log2_scale_b);
   if (st != ECGEMM_OK) return st;
   if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
 
   // steps 2 and 3
   st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials,
-                      -(h->log2_scale_a + h->log2_scale_b));
+                      -(h->log2_scale_a + h->log2_scale_b), row_log2_scale_a, col_log2_scale_b);
   if (st != ECGEMM_OK) return st;
   if (h->timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));

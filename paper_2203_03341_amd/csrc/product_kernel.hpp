@@ -53,9 +53,16 @@ struct ProductParams {
   int64_t M, N, ldc;
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
+  // per-row / per-column pre-scaling (both null, or both set): element (m, n) of the product is multiplied by
+  // 2^-row_log2_scale[m] and then by 2^-col_log2_scale[n] before alpha / beta
+  const int* row_log2_scale;  // device, M entries
+  const int* col_log2_scale;  // device, N entries
   float* C;
   float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
 };
+
+// 2^e as a float, e in [-126, 127]
+__device__ __forceinline__ float exp2_int(int e) { return __builtin_bit_cast(float, (unsigned)(e + 127) << 23); }
 
 // alpha c + beta C_in with the roundings fixed (alpha c rounded, then one fused multiply-add), so that the compiler
 // cannot pick a different contraction in each kernel and every kernel shape gives the same bits.
@@ -530,7 +537,27 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
                 (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
   };
   const bool interior = (int64_t)(tile_m + 1) * Cfg::BM <= p.M && (int64_t)(tile_n + 1) * Cfg::BN <= p.N;
-  if (done.partial >= 0) {
+  if (p.row_log2_scale != nullptr) {
+    // rows of op(A) and columns of op(B) were scaled one by one before the split: undo that per element
+    const int* row_scale = p.row_log2_scale;
+    const int* col_scale = p.col_log2_scale;
+    asm volatile("" : "+s"(row_scale), "+s"(col_scale));
+    float* out = done.partial >= 0 ? p.partials + (int64_t)done.partial * (Cfg::BM * Cfg::BN) : nullptr;
+    const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
+    for_each_output([&](int64_t m, int64_t n, float c) {
+      if (m < p.M && n < p.N) {
+        c = c * exp2_int(-row_scale[m]) * exp2_int(-col_scale[n]);
+        if (out) {
+          out[(n - n0) * Cfg::BM + (m - m0)] = c;
+        } else {
+          float* dst = c_base + m + n * ldc;
+          *dst = (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst);
+        }
+      } else if (out) {
+        out[(n - n0) * Cfg::BM + (m - m0)] = 0.0f;
+      }
+    });
+  } else if (done.partial >= 0) {
     float* out = p.partials + (int64_t)done.partial * (Cfg::BM * Cfg::BN);
     const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
     for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * Cfg::BM + (m - m0)] = c; });

@@ -49,6 +49,9 @@ __host__ __device__ constexpr bool split_is_bf16(int kind) { return kind == kSpl
 
 constexpr float kBf16Max = 3.3895313892515355e+38f;  // largest finite BF16
 
+// 2^e for a per-row scaling exponent e in [-126, 127]
+__device__ __forceinline__ float row_scale_factor(int e) { return __builtin_bit_cast(float, (unsigned)(e + 127) << 23); }
+
 template <int KIND>
 struct Splitter {
   static constexpr int kParts = parts_of_split(KIND);
@@ -105,10 +108,12 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
 template <int KIND, bool VEC>
 __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
                                                           int64_t depth, int64_t k_steps_total, float prescale,
+                                                          const int* __restrict__ row_log2_scale,
                                                           unsigned short* __restrict__ packed, unsigned k_tiles) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)(blockIdx.x / k_tiles) * 64 + (t >> 2);
   const int64_t k = (int64_t)(blockIdx.x % k_tiles) * 32 + (t & 3) * 8;
+  if (row_log2_scale != nullptr && r < rows) prescale *= row_scale_factor(row_log2_scale[r]);
   float v[8];
   if (r < rows && k + 8 <= depth && VEC) {
     const float4 lo = *reinterpret_cast<const float4*>(src + r * ld + k);
@@ -129,11 +134,13 @@ __global__ void __launch_bounds__(256) split_k_contiguous(const float* __restric
 // run.  Blocks are numbered with the row tile fastest: neighbours in the launch order read neighbouring runs.
 template <int KIND>
 __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                      int64_t depth, int64_t k_steps_total, float prescale,
-                                                      unsigned short* __restrict__ packed, unsigned row_tiles) {
+                                                          int64_t depth, int64_t k_steps_total, float prescale,
+                                                          const int* __restrict__ row_log2_scale,
+                                                          unsigned short* __restrict__ packed, unsigned row_tiles) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)(blockIdx.x % row_tiles) * 64 + (t & 63);
   const int64_t k = (int64_t)(blockIdx.x / row_tiles) * 32 + (t >> 6) * 8;
+  if (row_log2_scale != nullptr && r < rows) prescale *= row_scale_factor(row_log2_scale[r]);
   float v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r + (k + e) * ld] * prescale : 0.0f;
@@ -147,6 +154,7 @@ __global__ void __launch_bounds__(256) split_r_contiguous(const float* __restric
 template <int KIND>
 __global__ void __launch_bounds__(256) split_r_contiguous_wide(const float* __restrict__ src, int64_t ld, int64_t rows,
                                                                int64_t depth, int64_t k_steps_total, float prescale,
+                                                               const int* __restrict__ row_log2_scale,
                                                                unsigned short* __restrict__ packed, unsigned row_tiles) {
   __shared__ float tile[32 * 256];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -168,6 +176,7 @@ __global__ void __launch_bounds__(256) split_r_contiguous_wide(const float* __re
     *reinterpret_cast<float4*>(&tile[kk * 256 + 4 * lane]) = x;
   }
   __syncthreads();
+  if (row_log2_scale != nullptr && r0 + t < rows) prescale *= row_scale_factor(row_log2_scale[r0 + t]);
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     float v[8];
@@ -195,6 +204,49 @@ __global__ void __launch_bounds__(256) exponent_range_kernel(const float* __rest
     atomicMin(&range[0], lo);
     atomicMax(&range[1], hi);
   }
+}
+
+// Per-row scaling exponents, in three small kernels on one stream.  (1) row_max[r] <- INT_MIN.
+__global__ void __launch_bounds__(256) fill_int_kernel(int* __restrict__ dst, int64_t count, int value) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < count) dst[i] = value;
+}
+
+// (2) row_max[r] <- largest binary exponent among the non-zero finite elements of row r of X (subnormals count as
+// -127), X(r, k) = src[r + k * ld] or src[k + r * ld].  blockIdx.y takes a slab of 2048 k; lanes run along the
+// contiguous direction.
+__global__ void __launch_bounds__(256) row_max_exponent_kernel(const float* __restrict__ src, int64_t ld, int64_t rows,
+                                                               int64_t depth, int k_contiguous, int* __restrict__ row_max) {
+  const int64_t k_begin = (int64_t)blockIdx.y * 2048, k_end = k_begin + 2048 < depth ? k_begin + 2048 : depth;
+  auto exponent_of = [](float v) {
+    const unsigned bits = __builtin_bit_cast(unsigned, v) & 0x7fffffffu;
+    return (bits != 0 && bits < 0x7f800000u) ? (int)(bits >> 23) - 127 : -0x7fffffff - 1;
+  };
+  int hi = -0x7fffffff - 1;
+  if (!k_contiguous) {
+    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r >= rows) return;
+    for (int64_t k = k_begin; k < k_end; ++k) hi = max(hi, exponent_of(src[r + k * ld]));
+    if (hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
+  } else {
+    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wave per row
+    if (r >= rows) return;
+    for (int64_t k = k_begin + (threadIdx.x & 63); k < k_end; k += 64) hi = max(hi, exponent_of(src[k + r * ld]));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) hi = max(hi, __shfl_xor(hi, d, 64));
+    if ((threadIdx.x & 63) == 0 && hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
+  }
+}
+
+// (3) in place: the exponent that moves the row's largest binade to 2^target (0 for a row without non-zero finite
+// elements), kept inside what one power-of-two factor can express.
+__global__ void __launch_bounds__(256) finish_row_scales_kernel(int* __restrict__ row_scale, int64_t rows, int target) {
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  const int hi = row_scale[r];
+  int e = hi == -0x7fffffff - 1 ? 0 : target - hi;
+  e = e < -126 ? -126 : e > 126 ? 126 : e;
+  row_scale[r] = e;
 }
 
 }  // namespace ecgemm

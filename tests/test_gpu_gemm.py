@@ -471,6 +471,74 @@ def test_prescaling_brings_small_inputs_into_the_fp16_window():
     h.destroy()
 
 
+@pytest.mark.parametrize("transA,transB", [("N", "N"), ("T", "T")])
+def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
+    """Rows of op(A) and columns of op(B) spread over 2^-60 .. 2^20: no single factor brings them all into the FP16
+    window, one power of two per row / column does.  The exponents come from the library (bit for bit what numpy
+    computes), the scaling is exact, and the FP16 mode meets the FP32 bar again."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 520, 390, 1100           # several tiles, ragged; K deep enough that the tiles are sliced along K
+    rng = np.random.default_rng(11)
+    ea = rng.integers(-60, 21, size=M)
+    eb = rng.integers(-60, 21, size=N)
+    opA = np.ldexp(si.urand(M, K, 3, si.ID_A)[:M, :K], ea[:, None]).astype(np.float32)
+    opB = np.ldexp(si.urand(K, N, 3, si.ID_B)[:K, :N], eb[None, :]).astype(np.float32)
+    opA[7, :] = 0.0                    # a row without a non-zero element gets the exponent 0
+    A = np.asfortranarray(opA if transA == "N" else opA.T)
+    B = np.asfortranarray(opB if transB == "N" else opB.T)
+    C = si.urand(M, N, 3, si.ID_C)[:M, :N].copy(order="F")
+    C *= np.float32(2.0 ** -20)
+    c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, 1.5, A, B, 0.5, C)
+    c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, 1.5, A, B, 0.5, C)
+    ops = {"N": ec.OP_N, "T": ec.OP_T}
+    h = ec.Handle()
+    dA, dB = to_device(A), to_device(B)
+    sa = torch.full((M,), 12345, dtype=torch.int32, device="cuda")
+    sb = torch.full((N,), 12345, dtype=torch.int32, device="cuda")
+    h.row_scales(ops[transA], M, K, dA, A.shape[0], 14, sa)
+    h.row_scales(ec.OP_T if transB == "N" else ec.OP_N, N, K, dB, B.shape[0], 14, sb)
+    torch.cuda.synchronize()
+
+    def expected(rows):
+        amax = np.max(np.abs(rows), axis=1)
+        return np.where(amax > 0, 14 - (np.frexp(amax)[1] - 1), 0)       # frexp: amax = f * 2^e with f in [0.5, 1)
+
+    assert np.array_equal(sa.cpu().numpy(), expected(opA))
+    assert np.array_equal(sb.cpu().numpy(), expected(opB.T))
+
+    def run(scaled):
+        dC = to_device(C)
+        if scaled:
+            h.sgemm_scaled(ops[transA], ops[transB], M, N, K, 1.5, dA, A.shape[0], dB, B.shape[0], 0.5, dC, M,
+                           ec.MODE_FP16_SPLIT, sa, sb)
+        else:
+            h.sgemm(ops[transA], ops[transB], M, N, K, 1.5, dA, A.shape[0], dB, B.shape[0], 0.5, dC, M, ec.MODE_FP16_SPLIT)
+        torch.cuda.synchronize()
+        return to_host(dC, M, N)
+
+    # the residual norm is dominated by the largest rows and columns; what the scaling saves are the small ones, so
+    # the check runs row by row: relative residual of every row of C against the FP32 product's
+    def row_residuals(x):
+        return np.linalg.norm((c64 - x).astype(np.float64), axis=1) / np.maximum(np.linalg.norm(c64, axis=1), 1e-300)
+
+    r_cpu = row_residuals(c32)
+    plain = row_residuals(run(False))
+    scaled = run(True)
+    assert np.all(np.isfinite(scaled))
+    r_gpu = row_residuals(scaled)
+    live = np.linalg.norm(c64, axis=1) > 0
+    with np.errstate(invalid="ignore", divide="ignore"):
+        lost = ~np.isfinite(plain) | (plain > 10 * r_cpu)
+    assert np.mean(lost[live]) > 0.5                                 # most rows are lost without the scaling
+    assert np.all(r_gpu[live] <= 2.0 * r_cpu[live] + 1e-12)          # every single row is as good as FP32's
+    assert gemm.relative_residual(c64, scaled) <= RATIO * gemm.relative_residual(c64, c32)
+    with pytest.raises(ec.EcgemmError):                              # one vector without the other
+        h.sgemm_scaled(ops[transA], ops[transB], M, N, K, 1.0, dA, A.shape[0], dB, B.shape[0], 0.0, to_device(C), M,
+                       ec.MODE_FP16_SPLIT, sa, None)
+    h.destroy()
+
+
 def test_accumulating_outside_the_matrix_unit_as_the_paper_does():
     """The paper's listing verbatim (zeroed temporary, FP32 vector adds every k step): meets the same bar as the
     default FP16 mode; one FP32 rounding per 16 products instead of per 8, so the element-wise bound holds too."""
