@@ -258,7 +258,7 @@ def main():
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": transA, "transB": transB,
                    "mode": mode, "alpha": alpha, "beta": beta, "products": parts_products,
                    "inputs": "urand(-1,1)" if dist == "urand" else f"exp_rand{dist[0]} x exp_rand{dist[1]}", "seed": args.seed,
-                   "shape": args.shape},
+                   "shape": args.shape, "plan": h.plan_info(M, N, K, mode_id)},
         "split_ms": round(split_ms / calls, 4), "product_ms": round(product_ms_avg, 4),
         "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
         "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",

@@ -86,6 +86,24 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
                                       ecgemm_mode_t mode, size_t *bytes);
 
+/* How ecgemm_sgemm would run this problem (host logic only; no GPU work, `handle` as in ecgemm_workspace_size):
+ * the kernel shape, the output tiles, how many of them are one work item over the whole depth and how many are cut
+ * into how many slices along K, whether the product kernel is launched as a persistent grid, its grid size on a
+ * 256-CU device, and the workspace bytes.  `info` is a host pointer. */
+typedef struct {
+    int shape;          /* ecgemm_shape_t actually used (never ECGEMM_SHAPE_AUTO) */
+    int tile_m, tile_n; /* block tile */
+    int tiles_m, tiles_n;
+    int whole_tiles;    /* tiles that are one work item */
+    int sliced_tiles;   /* tiles cut into `slices` work items each; their sums are added by a second kernel */
+    int slices;         /* 1 if sliced_tiles == 0 */
+    int persistent;     /* 1: one workgroup per CU walks through several work items */
+    int64_t grid;       /* workgroups of the product (or fused) kernel */
+    size_t workspace_bytes;
+} ecgemm_plan_info_t;
+ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
+                                 ecgemm_plan_info_t *info);
+
 /* Hands the library a caller-owned device buffer (256-byte aligned) to use as workspace from now on;
  * (NULL, 0) returns to the handle-owned workspace, which is allocated on first need and only ever
  * grows.  With a caller buffer the library never allocates: a too small one makes ecgemm_sgemm return

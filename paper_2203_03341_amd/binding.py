@@ -20,9 +20,20 @@ MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_F
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
-EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_set_workspace",
+EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
            "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
+
+
+class PlanInfo(ctypes.Structure):
+    """ecgemm_plan_info_t"""
+    _fields_ = [("shape", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("tiles_m", ctypes.c_int),
+                ("tiles_n", ctypes.c_int), ("whole_tiles", ctypes.c_int), ("sliced_tiles", ctypes.c_int),
+                ("slices", ctypes.c_int), ("persistent", ctypes.c_int), ("grid", ctypes.c_int64),
+                ("workspace_bytes", ctypes.c_size_t)]
+
+    def as_dict(self) -> dict:
+        return {name: int(getattr(self, name)) for name, _ in self._fields_}
 
 
 def _load() -> ctypes.CDLL:
@@ -36,6 +47,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_set_stream.argtypes = [vp, vp]
     lib.ecgemm_workspace_size.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
     lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
+    lib.ecgemm_plan_info.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(PlanInfo)]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
     lib.ecgemm_sgemm_scaled.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
@@ -116,6 +128,11 @@ class Handle:
         self._check(_lib.ecgemm_workspace_size(self._h, M, N, K, mode, ctypes.byref(out)))
         return out.value
 
+    def plan_info(self, M: int, N: int, K: int, mode: int) -> dict:
+        info = PlanInfo()
+        self._check(_lib.ecgemm_plan_info(self._h, M, N, K, mode, ctypes.byref(info)))
+        return info.as_dict()
+
     def set_workspace(self, buffer, nbytes: int):
         self._check(_lib.ecgemm_set_workspace(self._h, _ptr(buffer), nbytes))
 
@@ -182,6 +199,15 @@ def workspace_size(M: int, N: int, K: int, mode: int) -> int:
     if st != OK:
         raise EcgemmError(st, "ecgemm_workspace_size")
     return out.value
+
+
+def plan_info(M: int, N: int, K: int, mode: int) -> dict:
+    """ecgemm_plan_info without a handle (automatic kernel shape)."""
+    info = PlanInfo()
+    st = _lib.ecgemm_plan_info(None, M, N, K, mode, ctypes.byref(info))
+    if st != OK:
+        raise EcgemmError(st, "ecgemm_plan_info")
+    return info.as_dict()
 
 
 def split_size(rows: int, depth: int, mode: int) -> int:

@@ -230,6 +230,17 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, in
   return ECGEMM_OK;
 }
 
+// Workgroups of the product kernel: one per item (every XCD's list padded to the same length), or one per workgroup
+// slot when the shape runs this depth as a persistent grid and there are more items than slots.
+int64_t product_grid(const Plan& pl, int compute_units, bool* persistent_out) {
+  const int64_t tail_items = (int64_t)pl.tail_tiles * pl.tail_splits;
+  const int64_t one_block_per_item = 8 * ((pl.full_tiles + 7) / 8 + (tail_items + 7) / 8);
+  const int64_t slots = (int64_t)compute_units * pl.shape->blocks_per_cu;
+  const bool persistent = pl.Kp <= pl.shape->persistent_max_k && one_block_per_item > slots;
+  if (persistent_out) *persistent_out = persistent;
+  return persistent ? slots : one_block_per_item;
+}
+
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
                                const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials,
@@ -255,11 +266,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.C = C;
   pp.partials = partials;
   // Grid, always a multiple of the 8 XCDs: one block per item, or a persistent grid (see Shape::persistent_max_k).
-  const int64_t tail_items = (int64_t)pl.tail_tiles * pl.tail_splits;
-  const int64_t one_block_per_item = 8 * ((pl.full_tiles + 7) / 8 + (tail_items + 7) / 8);  // every XCD's list, padded
-  const int64_t slots = (int64_t)h->compute_units * pl.shape->blocks_per_cu;
-  const bool persistent = pl.Kp <= pl.shape->persistent_max_k;
-  const dim3 grid((unsigned)(one_block_per_item <= slots || !persistent ? one_block_per_item : slots));
+  const dim3 grid((unsigned)product_grid(pl, h->compute_units, nullptr));
   void* args[] = {&pp};
   ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->product), grid, dim3(pl.shape->threads), args, 0, h->stream));
   if (pl.tail_splits > 1) {
@@ -430,6 +437,27 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
   *bytes = pl.total_bytes;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
+                                 ecgemm_plan_info_t* info) {
+  if (!info || M <= 0 || N <= 0 || K <= 0 || !valid_mode(mode))
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_plan_info: bad argument (sizes must be positive)");
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_plan_info: the handle's kernel shape does not exist for this mode");
+  info->shape = (int)(pl.shape - &kShapes[(int)mode][0]) + 1;
+  info->tile_m = pl.shape->bm;
+  info->tile_n = pl.shape->bn;
+  info->tiles_m = pl.tiles_m;
+  info->tiles_n = pl.tiles_n;
+  info->whole_tiles = pl.full_tiles;
+  info->sliced_tiles = pl.tail_tiles;
+  info->slices = pl.tail_splits;
+  bool persistent = false;
+  info->grid = pl.shape->fused ? (int64_t)pl.tiles_m * pl.tiles_n * pl.tail_splits : product_grid(pl, kPlanComputeUnits, &persistent);
+  info->persistent = persistent ? 1 : 0;
+  info->workspace_bytes = pl.total_bytes;
   return ECGEMM_OK;
 }
 

@@ -45,6 +45,42 @@ def test_product_path_does_not_touch_the_oracle():
                 assert "oracle" not in text.lower(), os.path.join(dirpath, f)
 
 
+def test_plan_of_the_baseline_configs():
+    """Host logic: which kernel shape a problem gets, how its tiles become work items, how the kernel is launched."""
+    import paper_2203_03341_amd as ec
+    W4, X2 = ec.SHAPE_256x128_W4, ec.SHAPE_128x128_X2
+    p = ec.plan_info(16384, 16384, 16384, ec.MODE_FP16_SPLIT)          # headline: 8192 whole tiles, one workgroup each
+    assert (p["shape"], p["tile_m"], p["tile_n"], p["whole_tiles"], p["sliced_tiles"], p["persistent"], p["grid"]) == \
+        (W4, 256, 128, 8192, 0, 0, 8192)
+    assert p["workspace_bytes"] == 2 * 16384 * 16384 * 4
+    p = ec.plan_info(4096, 4096, 4096, ec.MODE_BF16_FULL)              # K <= 4096: persistent grid of one block per CU
+    assert (p["shape"], p["whole_tiles"], p["persistent"], p["grid"]) == (W4, 512, 1, 256)
+    p = ec.plan_info(16384, 16384, 256, ec.MODE_FP16_SPLIT)            # shallow K: 128 x 128 tiles, two blocks per CU
+    assert (p["shape"], p["tile_m"], p["whole_tiles"], p["slices"], p["persistent"]) == (X2, 128, 128 * 128, 1, 0)
+    p = ec.plan_info(1024, 1024, 65536, ec.MODE_FP16_SPLIT)            # 32 tiles: all cut into 8 slices = 256 items
+    assert (p["shape"], p["whole_tiles"], p["sliced_tiles"], p["slices"], p["grid"]) == (W4, 0, 32, 8, 256)
+    p = ec.plan_info(4095, 3001, 5003, ec.MODE_BF16_FULL)              # 384 tiles: 256 whole, 128 in two slices
+    assert (p["shape"], p["tiles_m"], p["tiles_n"], p["whole_tiles"], p["sliced_tiles"], p["slices"]) == (W4, 16, 24, 256, 128, 2)
+    p = ec.plan_info(1024, 1024, 1024, ec.MODE_FP16_SPLIT)             # 32 tiles x 2 slices would leave CUs idle: smaller tiles
+    assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 64, 2, 128)
+    p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # slices of 512: short items, smaller tiles
+    assert (p["shape"], p["sliced_tiles"], p["slices"]) == (X2, 16, 32)
+    p = ec.plan_info(300, 200, 100, ec.MODE_FP16_MARKIDIS)             # comparison methods: one shape
+    assert (p["shape"], p["tiles_m"], p["tiles_n"]) == (W4, 2, 2)
+    for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
+        for (M, N, K) in [(1, 1, 1), (257, 129, 33), (5000, 7000, 900), (20000, 300, 70000)]:
+            p = ec.plan_info(M, N, K, mode)
+            assert p["tiles_m"] * p["tiles_n"] == p["whole_tiles"] + p["sliced_tiles"]
+            assert p["tiles_m"] == -(-M // p["tile_m"]) and p["tiles_n"] == -(-N // p["tile_n"])
+            assert (p["slices"] == 1) == (p["sliced_tiles"] == 0)
+            assert p["workspace_bytes"] == ec.workspace_size(M, N, K, mode)
+            if p["slices"] > 1:
+                assert -(-K // p["slices"]) >= 512 - 32                  # a slice is never shallower than 512 (padded)
+    import pytest
+    with pytest.raises(ec.EcgemmError):
+        ec.plan_info(0, 1, 1, ec.MODE_FP16_SPLIT)
+
+
 def test_workspace_plan_needs_no_gpu():
     """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and the output
     tiles left over after whole rounds of the chip's 256 CUs cut into slices along K (one partial tile per slice)."""
