@@ -190,33 +190,49 @@ ecgemm_status_t hip_fail(ecgemm_handle_t h, hipError_t e, const char* where) {
   } while (0)
 
 // X = op(src) is rows x depth.  op == N: X(r, k) = src[r + k * ld]; op == T: X(r, k) = src[k + r * ld].
-ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
-                             int64_t ld, ecgemm_mode_t mode, void* packed, int log2_prescale = 0,
-                             const int* row_log2_scale = nullptr) {
-  const float prescale = std::ldexp(1.0f, log2_prescale);
+ecgemm_status_t make_split_job(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src, int64_t ld,
+                               void* packed, int log2_prescale, const int* row_log2_scale, SplitJob* job) {
   const int64_t Rp = round_up(rows, kRowPad), Kp = round_up(depth, kDepthPad);
-  const int64_t k_steps = Kp / 16;
   const int64_t blocks64 = (Kp / 32) * (Rp / 64);
   if (blocks64 > 0x7fffffff) return fail(h, ECGEMM_ERR_INVALID_ARG, "operand has more than 2^42 elements");
-  const dim3 block(256), grid64((unsigned)blocks64), grid256((unsigned)(blocks64 / 4));
-  const unsigned k_tiles = (unsigned)(Kp / 32);
-  unsigned short* out = static_cast<unsigned short*>(packed);
   const bool k_contiguous = op == ECGEMM_OP_T;
   const bool vec = (ld % 4 == 0) && ((uintptr_t)src % 16 == 0);
-#define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                          \
-  do {                                                                                                                     \
-    if (!k_contiguous && vec)                                                                                              \
-      hipLaunchKernelGGL((split_r_contiguous_wide<KIND>), grid256, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
-                         prescale, row_log2_scale, out, (unsigned)(Rp / 256));                                             \
-    else if (!k_contiguous)                                                                                                \
-      hipLaunchKernelGGL((split_r_contiguous<KIND>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps, prescale, \
-                         row_log2_scale, out, (unsigned)(Rp / 64));                                                        \
-    else if (vec)                                                                                                          \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, true>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,     \
-                         prescale, row_log2_scale, out, k_tiles);                                                          \
-    else                                                                                                                   \
-      hipLaunchKernelGGL((split_k_contiguous<KIND, false>), grid64, block, 0, h->stream, src, ld, rows, depth, k_steps,    \
-                         prescale, row_log2_scale, out, k_tiles);                                                          \
+  job->src = src;
+  job->ld = ld;
+  job->rows = rows;
+  job->depth = depth;
+  job->k_steps_total = Kp / 16;
+  job->prescale = std::ldexp(1.0f, log2_prescale);
+  job->row_log2_scale = row_log2_scale;
+  job->packed = static_cast<unsigned short*>(packed);
+  job->variant = k_contiguous ? (vec ? kSplitKContiguousVec : kSplitKContiguous) : (vec ? kSplitRContiguousWide : kSplitRContiguous);
+  job->fast_tiles = (unsigned)(k_contiguous ? Kp / 32 : job->variant == kSplitRContiguousWide ? Rp / 256 : Rp / 64);
+  job->blocks = (unsigned)(job->variant == kSplitRContiguousWide ? blocks64 / 4 : blocks64);
+  return ECGEMM_OK;
+}
+
+template <int KIND>
+void launch_split_job(hipStream_t stream, const SplitJob& job) {
+  const dim3 grid(job.blocks), block(256);
+  switch (job.variant) {
+    case kSplitRContiguousWide: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguousWide>), grid, block, 0, stream, job); break;
+    case kSplitRContiguous: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguous>), grid, block, 0, stream, job); break;
+    case kSplitKContiguousVec: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguousVec>), grid, block, 0, stream, job); break;
+    default: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguous>), grid, block, 0, stream, job); break;
+  }
+}
+
+// Step 1 for one operand, or (b != nullptr) for both operands of a product.  Small pairs go out as one launch.
+ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_mode_t mode, const SplitJob& a, const SplitJob* b = nullptr) {
+  const bool pair = b != nullptr && (uint64_t)a.blocks + b->blocks <= 8192;
+#define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                       \
+  do {                                                                                                                  \
+    if (pair) {                                                                                                         \
+      hipLaunchKernelGGL((split_pair_kernel<KIND>), dim3(a.blocks + b->blocks), dim3(256), 0, h->stream, a, *b);        \
+    } else {                                                                                                            \
+      launch_split_job<KIND>(h->stream, a);                                                                             \
+      if (b) launch_split_job<KIND>(h->stream, *b);                                                                     \
+    }                                                                                                                   \
   } while (0)
   switch (split_kind_of((int)mode)) {
     case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;
@@ -486,7 +502,10 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: null or misaligned pointer");
   if (ld < (op == ECGEMM_OP_N ? rows : depth))
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: leading dimension too small");
-  return launch_split(handle, op, rows, depth, src, ld, mode, packed);
+  SplitJob job;
+  const ecgemm_status_t st = make_split_job(handle, op, rows, depth, src, ld, packed, 0, nullptr, &job);
+  if (st != ECGEMM_OK) return st;
+  return launch_split(handle, mode, job);
 }
 
 ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int log2_scale_b) {
@@ -715,10 +734,13 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
 
   // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
   // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
-  st = launch_split(h, transA, M, K, A, lda, mode, a_packed, h->log2_scale_a, row_log2_scale_a);
+  SplitJob job_a, job_b;
+  st = make_split_job(h, transA, M, K, A, lda, a_packed, h->log2_scale_a, row_log2_scale_a, &job_a);
   if (st != ECGEMM_OK) return st;
-  st = launch_split(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, mode, b_packed, h->log2_scale_b,
-                    col_log2_scale_b);
+  st = make_split_job(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, b_packed, h->log2_scale_b,
+                      col_log2_scale_b, &job_b);
+  if (st != ECGEMM_OK) return st;
+  st = launch_split(h, mode, job_a, &job_b);
   if (st != ECGEMM_OK) return st;
   if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
 

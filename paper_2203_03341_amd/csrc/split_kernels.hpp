@@ -103,86 +103,124 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
   for (int p = 0; p < NP; ++p) *reinterpret_cast<ushort8_t*>(chunk + p * kChunkElems) = parts[p];
 }
 
+// One operand to split: X = op(src), rows x depth, into `packed`.
+struct SplitJob {
+  const float* src;
+  int64_t ld, rows, depth;
+  int64_t k_steps_total;      // padded depth / 16
+  float prescale;             // a power of two chosen by the caller (1 by default): exact
+  const int* row_log2_scale;  // optional per-row exponents, applied on top of prescale
+  unsigned short* packed;
+  unsigned fast_tiles;        // tiles along the direction in which the blocks are numbered first
+  unsigned blocks;
+  int variant;                // SplitVariant
+};
+enum SplitVariant { kSplitKContiguousVec = 0, kSplitKContiguous = 1, kSplitRContiguous = 2, kSplitRContiguousWide = 3 };
+
 // Source with k contiguous: X(r, k) = src[k + r * ld].  One block: 64 rows x 32 k, 256 threads,
 // thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4).  Blocks are numbered with the k tile fastest.
 template <int KIND, bool VEC>
-__global__ void __launch_bounds__(256) split_k_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                          int64_t depth, int64_t k_steps_total, float prescale,
-                                                          const int* __restrict__ row_log2_scale,
-                                                          unsigned short* __restrict__ packed, unsigned k_tiles) {
+__device__ __forceinline__ void split_block_k_contiguous(const SplitJob& job, unsigned block) {
   const int t = threadIdx.x;
-  const int64_t r = (int64_t)(blockIdx.x / k_tiles) * 64 + (t >> 2);
-  const int64_t k = (int64_t)(blockIdx.x % k_tiles) * 32 + (t & 3) * 8;
-  if (row_log2_scale != nullptr && r < rows) prescale *= row_scale_factor(row_log2_scale[r]);
+  const int64_t r = (int64_t)(block / job.fast_tiles) * 64 + (t >> 2);
+  const int64_t k = (int64_t)(block % job.fast_tiles) * 32 + (t & 3) * 8;
+  float prescale = job.prescale;
+  if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
+  const float* src = job.src;
   float v[8];
-  if (r < rows && k + 8 <= depth && VEC) {
-    const float4 lo = *reinterpret_cast<const float4*>(src + r * ld + k);
-    const float4 hi = *reinterpret_cast<const float4*>(src + r * ld + k + 4);
+  if (r < job.rows && k + 8 <= job.depth && VEC) {
+    const float4 lo = *reinterpret_cast<const float4*>(src + r * job.ld + k);
+    const float4 hi = *reinterpret_cast<const float4*>(src + r * job.ld + k + 4);
     v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
     v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
   } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r * ld + k + e] : 0.0f;
+    for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? src[r * job.ld + k + e] : 0.0f;
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] *= prescale;  // a power of two chosen by the caller (1 by default): exact
-  store_fragment_row<KIND>(packed, k_steps_total, r, k, v);
+  for (int e = 0; e < 8; ++e) v[e] *= prescale;
+  store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k, v);
 }
 
 // Source with r contiguous: X(r, k) = src[r + k * ld], any alignment.  One block: 64 rows x 32 k.  Lanes run along r,
 // so a thread reads the 8 consecutive-k values of its row directly and each read instruction of a wave is a 256-byte
 // run.  Blocks are numbered with the row tile fastest: neighbours in the launch order read neighbouring runs.
 template <int KIND>
-__global__ void __launch_bounds__(256) split_r_contiguous(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                          int64_t depth, int64_t k_steps_total, float prescale,
-                                                          const int* __restrict__ row_log2_scale,
-                                                          unsigned short* __restrict__ packed, unsigned row_tiles) {
+__device__ __forceinline__ void split_block_r_contiguous(const SplitJob& job, unsigned block) {
   const int t = threadIdx.x;
-  const int64_t r = (int64_t)(blockIdx.x % row_tiles) * 64 + (t & 63);
-  const int64_t k = (int64_t)(blockIdx.x / row_tiles) * 32 + (t >> 6) * 8;
-  if (row_log2_scale != nullptr && r < rows) prescale *= row_scale_factor(row_log2_scale[r]);
+  const int64_t r = (int64_t)(block % job.fast_tiles) * 64 + (t & 63);
+  const int64_t k = (int64_t)(block / job.fast_tiles) * 32 + (t >> 6) * 8;
+  float prescale = job.prescale;
+  if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
   float v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = (r < rows && k + e < depth) ? src[r + (k + e) * ld] * prescale : 0.0f;
-  store_fragment_row<KIND>(packed, k_steps_total, r, k, v);
+  for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? job.src[r + (k + e) * job.ld] * prescale : 0.0f;
+  store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k, v);
 }
 
 // Source with r contiguous, base and leading dimension multiples of 16 bytes.  One block: 256 rows x 32 k through
-// LDS.  A wave reads one k line of 256 rows per instruction (1 KiB runs, 16 bytes per lane); after the barrier thread t
-// owns row t and picks its 8-value groups out of LDS along k (lanes on consecutive words: no bank conflicts).
-// 5.4 TB/s at 16384^2 against 3.9 TB/s for the 64-row kernel above.
+// 32 KiB of LDS (`tile`).  A wave reads one k line of 256 rows per instruction (1 KiB runs, 16 bytes per lane); after
+// the barrier thread t owns row t and picks its 8-value groups out of LDS along k (lanes on consecutive words: no bank
+// conflicts).  5.4 TB/s at 16384^2 against 3.9 TB/s for the 64-row kernel above.
 template <int KIND>
-__global__ void __launch_bounds__(256) split_r_contiguous_wide(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                               int64_t depth, int64_t k_steps_total, float prescale,
-                                                               const int* __restrict__ row_log2_scale,
-                                                               unsigned short* __restrict__ packed, unsigned row_tiles) {
-  __shared__ float tile[32 * 256];
+__device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& job, unsigned block, float* tile) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int64_t r0 = (int64_t)(blockIdx.x % row_tiles) * 256, k0 = (int64_t)(blockIdx.x / row_tiles) * 32;
+  const int64_t r0 = (int64_t)(block % job.fast_tiles) * 256, k0 = (int64_t)(block / job.fast_tiles) * 32;
+  const float* src = job.src;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const int kk = wave + 4 * j;
     const int64_t k = k0 + kk, r = r0 + 4 * lane;
     float4 x = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (k < depth) {
-      if (r + 4 <= rows) {
-        x = *reinterpret_cast<const float4*>(src + r + k * ld);
+    if (k < job.depth) {
+      if (r + 4 <= job.rows) {
+        x = *reinterpret_cast<const float4*>(src + r + k * job.ld);
       } else {
-        if (r + 0 < rows) x.x = src[r + 0 + k * ld];
-        if (r + 1 < rows) x.y = src[r + 1 + k * ld];
-        if (r + 2 < rows) x.z = src[r + 2 + k * ld];
+        if (r + 0 < job.rows) x.x = src[r + 0 + k * job.ld];
+        if (r + 1 < job.rows) x.y = src[r + 1 + k * job.ld];
+        if (r + 2 < job.rows) x.z = src[r + 2 + k * job.ld];
       }
     }
     *reinterpret_cast<float4*>(&tile[kk * 256 + 4 * lane]) = x;
   }
   __syncthreads();
-  if (row_log2_scale != nullptr && r0 + t < rows) prescale *= row_scale_factor(row_log2_scale[r0 + t]);
+  float prescale = job.prescale;
+  if (job.row_log2_scale != nullptr && r0 + t < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r0 + t]);
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = tile[(8 * g + e) * 256 + t] * prescale;
-    store_fragment_row<KIND>(packed, k_steps_total, r0 + t, k0 + 8 * g, v);
+    store_fragment_row<KIND>(job.packed, job.k_steps_total, r0 + t, k0 + 8 * g, v);
+  }
+}
+
+// One operand per launch; VARIANT is fixed at compile time so that only the wide kernel holds LDS.
+template <int KIND, int VARIANT>
+__global__ void __launch_bounds__(256) split_kernel(const SplitJob job) {
+  if constexpr (VARIANT == kSplitRContiguousWide) {
+    __shared__ float tile[32 * 256];
+    split_block_r_contiguous_wide<KIND>(job, blockIdx.x, tile);
+  } else if constexpr (VARIANT == kSplitRContiguous) {
+    split_block_r_contiguous<KIND>(job, blockIdx.x);
+  } else {
+    split_block_k_contiguous<KIND, VARIANT == kSplitKContiguousVec>(job, blockIdx.x);
+  }
+}
+
+// Both operands of a product in one launch, for small operands where a launch costs more than the work: blocks
+// 0 .. a.blocks - 1 split A, the rest split B.
+template <int KIND>
+__global__ void __launch_bounds__(256) split_pair_kernel(const SplitJob a, const SplitJob b) {
+  __shared__ float tile[32 * 256];
+  const bool second = blockIdx.x >= a.blocks;  // block-uniform
+  const SplitJob& job = second ? b : a;
+  const unsigned block = second ? blockIdx.x - a.blocks : blockIdx.x;
+  switch (job.variant) {
+    case kSplitRContiguousWide: split_block_r_contiguous_wide<KIND>(job, block, tile); break;
+    case kSplitRContiguous: split_block_r_contiguous<KIND>(job, block); break;
+    case kSplitKContiguousVec: split_block_k_contiguous<KIND, true>(job, block); break;
+    default: split_block_k_contiguous<KIND, false>(job, block); break;
   }
 }
 
