@@ -12,7 +12,9 @@
  * All work is enqueued on the handle's stream and the calls return without waiting for it.
  * Every function returns an ecgemm_status_t and never throws or aborts; on any status other
  * than ECGEMM_OK no work has been enqueued by that call.  A handle may be used by one host
- * thread at a time.  Results are bitwise reproducible for equal inputs and equal settings
+ * thread at a time.  With a caller-provided workspace and timing off, ecgemm_sgemm and ecgemm_product only launch
+ * kernels (no allocation, no memset, no wait), so they can be recorded into a HIP graph.
+ * Results are bitwise reproducible for equal inputs and equal settings
  * (no floating-point atomics; the sums of tiles cut along K are added in a fixed order).
  */
 #ifndef ECGEMM_H

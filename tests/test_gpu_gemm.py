@@ -249,6 +249,49 @@ def test_bitwise_reproducible_and_stream(mode):
     assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_a_call_can_be_captured_in_a_graph_and_replayed(mode):
+    """With a caller workspace the call only launches kernels (no allocation, no memset, no wait), so it can be recorded
+    into a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager bits."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 1024, 768, 1536          # split pair + product with every tile sliced along K + reduction: three kernels
+    A, B = _inputs(M, N, K, "N", "T", "urand", 12)
+    C = si.urand(M, N, 12, si.ID_C)
+    mode_id = _modes()[mode]
+    h = ec.Handle()
+    stream = torch.cuda.Stream()
+    h.set_stream(stream.cuda_stream)
+    nbytes = h.workspace_size(M, N, K, mode_id)
+    workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    h.set_workspace(workspace, nbytes)
+    dA, dB, dC_in = to_device(A), to_device(B), to_device(C)
+    dC = torch.empty_like(dC_in)
+    other = torch.empty_like(dC_in)
+
+    def call(out):
+        out.copy_(dC_in)
+        h.sgemm(ec.OP_N, ec.OP_T, M, N, K, 1.5, dA, A.shape[0], dB, B.shape[0], 0.5, out, M, mode_id)
+
+    with torch.cuda.stream(stream):
+        call(dC)
+    stream.synchronize()
+    eager = dC.cpu().numpy().copy()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call(dC)
+    for _ in range(3):
+        with torch.cuda.stream(stream):
+            dC.fill_(float("nan"))
+            h.sgemm(ec.OP_N, ec.OP_T, M, N, K, -2.0, dA, A.shape[0], dB, B.shape[0], 0.0, other, M, mode_id)  # eager work
+        stream.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy().view(np.uint32), eager.view(np.uint32))
+    del graph
+    h.destroy()
+
+
 # ----- the shape sweep of the baseline (config 5), reduced in size where the full oracle would take minutes
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
