@@ -27,6 +27,7 @@ sys.path.insert(0, ROOT)
 METRIC = "FP32-equivalent TFLOP/s (2MNK/t) at 16384^3 + rel. error vs FP64 ref"
 PEAK_MFMA_16BIT_TFLOPS = 2516.6     # 256 CU x 4096 flop/clk x 2.4 GHz, dense FP16 / BF16
 PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0             # HBM3E, published
 
 # HBM bytes per product-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
 # workload; None where no counter run has been made for that workload.
@@ -167,6 +168,9 @@ def main():
     tflops = flops / (ms_per_step * 1e-3) / 1e12
     product_ms_avg = product_ms / calls
     mfma_tflops = parts_products * flops / (product_ms_avg * 1e-3) / 1e12
+    pad = lambda v, m: -(-v // m) * m
+    bytes_per_element = {"fp16": 4, "bf16": 6}[mode]
+    product_bytes = (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bytes_per_element + M * N * 4 * (2 if beta != 0 else 1)
 
     # ---- what the matrix pipes sustain on this board with random operands and no memory traffic (same dtype)
     ceiling = None
@@ -268,6 +272,12 @@ def main():
                      # the same matrix instructions with random operands and nothing else running, this board, this run
                      "mfma_only_random_operands_tflops": None if ceiling is None else round(ceiling, 1),
                      "frac_of_mfma_only": None if ceiling is None else round(mfma_tflops / ceiling, 4)},
+        # the same kernel against the HBM roof (it matters for shallow K, where writing C is most of the bytes):
+        # algorithmic bytes = packed operands once + C written once (+ read once when beta != 0)
+        "roofline_hbm": {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS, "kernel": "product_kernel",
+                         "bytes_per_launch": product_bytes,
+                         "achieved": round(product_bytes / (product_ms_avg * 1e-3) / 1e9, 1),
+                         "frac": round(product_bytes / (product_ms_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         "power": power,
         "library_sgemm": library,
     }
