@@ -187,7 +187,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
         float* dst = p.C + m + n * p.ldc;
-        *dst = (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst);
+        store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
       }
     });
   }

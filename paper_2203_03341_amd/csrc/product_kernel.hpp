@@ -64,6 +64,11 @@ struct ProductParams {
 // 2^e as a float, e in [-126, 127]
 __device__ __forceinline__ float exp2_int(int e) { return __builtin_bit_cast(float, (unsigned)(e + 127) << 23); }
 
+// An element of C is written once and not read again by this call: a non-temporal store keeps it from pushing the
+// operand panels out of the L2 (measured: 19 % off the 256 x 128 kernel and 4 % off the 128 x 128 kernel at
+// 16384 x 16384 x 256, where C is most of the traffic; nothing lost at 16384^3).
+__device__ __forceinline__ void store_result(float* dst, float value) { __builtin_nontemporal_store(value, dst); }
+
 // alpha c + beta C_in with the roundings fixed (alpha c rounded, then one fused multiply-add), so that the compiler
 // cannot pick a different contraction in each kernel and every kernel shape gives the same bits.
 __device__ __forceinline__ float scaled_sum(float alpha, float c, float beta, float c_in) {
@@ -551,7 +556,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
           out[(n - n0) * Cfg::BM + (m - m0)] = c;
         } else {
           float* dst = c_base + m + n * ldc;
-          *dst = (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst);
+          store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
         }
       } else if (out) {
         out[(n - n0) * Cfg::BM + (m - m0)] = 0.0f;
@@ -562,17 +567,17 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
     for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * Cfg::BM + (m - m0)] = c; });
   } else if (interior && p.beta == 0.0f) {
-    for_each_output([&](int64_t m, int64_t n, float c) { c_base[m + n * ldc] = p.alpha * c; });
+    for_each_output([&](int64_t m, int64_t n, float c) { store_result(c_base + m + n * ldc, p.alpha * c); });
   } else if (interior) {
     for_each_output([&](int64_t m, int64_t n, float c) {
       float* dst = c_base + m + n * ldc;
-      *dst = scaled_sum(p.alpha, c, p.beta, *dst);
+      store_result(dst, scaled_sum(p.alpha, c, p.beta, *dst));
     });
   } else {
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
         float* dst = c_base + m + n * ldc;
-        *dst = (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst);
+        store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
       }
     });
   }
@@ -648,7 +653,7 @@ __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restric
     for (int s = 0; s < tail_splits; ++s)
       sum += partials[(((int64_t)s * tail_tiles + blockIdx.x) * BN + n_local) * BM + m_local];
     float* dst = C + m + n * ldc;
-    *dst = (beta == 0.0f) ? alpha * sum : scaled_sum(alpha, sum, beta, *dst);
+    store_result(dst, (beta == 0.0f) ? alpha * sum : scaled_sum(alpha, sum, beta, *dst));
   }
 }
 
