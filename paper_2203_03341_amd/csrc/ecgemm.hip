@@ -160,8 +160,8 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 
 // The plan of a call.  Which shape a problem gets when the caller has not fixed one comes from product-kernel timings
 // of both shapes on 60 sizes from 512^3 to 24576 x 24576 x 4096, in both modes.  X2 wins where items are short or few:
-//   * an item of the W4 plan is at most 512 deep: 16384 x 16384 x 256: 437 us against 574 (FP16), 656 against 750
-//     (BF16); x 512: 742 against 808; 512 x 512 x 16384 (32 slices of 512): 90 against 153; tie at x 768;
+//   * an item of the W4 plan is at most 512 deep: 16384 x 16384 x 256: 440 us against 461 (FP16), 656 against 708
+//     (BF16); 4096 x 4096 x 256: 31 against 39; 512 x 512 x 16384 (32 slices of 512): 91 against 153; tie at x 768;
 //   * the W4 plan cannot give every CU an item even after slicing: 1024^3: 22 us against 31; 1536^3: 36 against 43.
 // Everywhere else W4 is ahead, by 2-5 % from 4096^3 to 8192^3 and at 16384 x 16384 x 2048..8192, by 8-10 % from
 // 12288^3 up.  The comparison methods have the W4 shape only.
