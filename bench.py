@@ -171,6 +171,7 @@ def main():
     pad = lambda v, m: -(-v // m) * m
     bytes_per_element = {"fp16": 4, "bf16": 6}[mode]
     product_bytes = (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bytes_per_element + M * N * 4 * (2 if beta != 0 else 1)
+    split_bytes = (M + N) * K * 4 + (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bytes_per_element
 
     # ---- what the matrix pipes sustain on this board with random operands and no memory traffic (same dtype)
     ceiling = None
@@ -278,6 +279,11 @@ def main():
                          "bytes_per_launch": product_bytes,
                          "achieved": round(product_bytes / (product_ms_avg * 1e-3) / 1e9, 1),
                          "frac": round(product_bytes / (product_ms_avg * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        # step 1 against the HBM roof: every FP32 element read once, its 16-bit parts written once
+        "roofline_split": {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS, "kernel": "split_kernel (both operands)",
+                           "bytes_per_call": split_bytes,
+                           "achieved": None if split_ms <= 0 else round(split_bytes / (split_ms / calls * 1e-3) / 1e9, 1),
+                           "frac": None if split_ms <= 0 else round(split_bytes / (split_ms / calls * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         "power": power,
         "library_sgemm": library,
     }
