@@ -311,6 +311,26 @@ def test_odd_sizes_transA(mode):
     _check("T", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=9)
 
 
+# ----- seeded random shapes: tile and slice boundaries nobody thought of by hand
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_random_shapes_transposes_and_scalars(seed):
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(8):
+        M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        K = int(rng.choice([rng.integers(1, 130), rng.integers(130, 1100), rng.integers(1100, 2600)]))
+        transA, transB = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+        alpha = float(rng.choice([1.0, -1.0, 0.5, 1.5]))
+        beta = float(rng.choice([0.0, 0.0, 1.0, -0.5]))
+        mode = str(rng.choice(["fp16", "bf16"]))
+        shape = rng.choice([None, None, "w4", "x2", "fused"])
+        shape = None if shape is None else str(shape)
+        pad = int(rng.integers(0, 4))
+        print(f"case {seed}.{case}: {transA}{transB} {M}x{N}x{K} alpha {alpha} beta {beta} {mode} shape {shape} pad {pad}", flush=True)
+        _check(transA, transB, M, N, K, alpha, beta, mode, "urand", seed=seed * 100 + case, pad=pad, shape=shape,
+               ratio_rule=K >= 64)
+
+
 # ----- every kernel shape on its own (the automatic choice exercises only one per size)
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
