@@ -254,6 +254,30 @@ def main():
                    "tflops": round(flops / (lib_ms * 1e-3) / 1e12, 2),
                    "power": power_while(library_call, args.power_seconds) if args.power_seconds > 0 else None}
         del ref
+        # the same comparison inside this code base: FP32 operands on the FP32 matrix instruction, same kernels
+        own_bytes = h.workspace_size(M, N, K, ec.MODE_FP32_MFMA)
+        own_ws = torch.empty(own_bytes, dtype=torch.uint8, device="cuda")
+        h.set_workspace(own_ws, own_bytes)
+        own_out = torch.empty((N, M), dtype=torch.float32, device="cuda")
+
+        def own_call():
+            h.sgemm(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], 0.0, own_out, M, ec.MODE_FP32_MFMA)
+
+        for _ in range(3):
+            own_call()
+        torch.cuda.synchronize()
+        l0.record(stream)
+        for _ in range(reps):
+            own_call()
+        l1.record(stream)
+        torch.cuda.synchronize()
+        own_ms = l0.elapsed_time(l1) / reps
+        library["fp32_mode_of_this_library"] = {
+            "what": "ecgemm_sgemm, ECGEMM_MODE_FP32_MFMA", "ms_per_call": round(own_ms, 4),
+            "tflops": round(flops / (own_ms * 1e-3) / 1e12, 2),
+            "power": power_while(own_call, args.power_seconds) if args.power_seconds > 0 else None}
+        h.set_workspace(ws, ws_bytes)
+        del own_out, own_ws
 
     got = dC.cpu().numpy().T          # logical M x N
     result = {

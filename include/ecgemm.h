@@ -57,7 +57,11 @@ typedef enum {
      * added to the running sum outside the matrix unit, every k step (section "Avoiding RZ during Tensor Core
      * accumulation").  On this hardware the matrix unit already rounds to nearest, so this only costs time; it is kept
      * to show that. */
-    ECGEMM_MODE_FP16_OUTSIDE_ACC = 6
+    ECGEMM_MODE_FP16_OUTSIDE_ACC = 6,
+    /* No splitting at all: A B in FP32 on the matrix unit (v_mfma_f32_32x32x2_f32), through the same repacking pass
+     * and the same product kernel.  The FP32 GEMM that the paper sets its method against (its cuBLAS SGEMM column),
+     * on this hardware and in this code base, for throughput, energy and error comparisons. */
+    ECGEMM_MODE_FP32_MFMA = 7
 } ecgemm_mode_t;
 
 typedef enum {

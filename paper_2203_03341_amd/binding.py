@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("ECGEMM_LIB") or os.path.join(HERE, "libecgemm.so")
 OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
 MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_FP16_OUTSIDE_ACC = 2, 3, 4, 5, 6  # comparisons
+MODE_FP32_MFMA = 7  # plain FP32 on the matrix unit
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 

@@ -56,6 +56,7 @@ typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, 2, 3, 1> UnscaledC
 typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3, 1> PlainFp16Config;
 typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Config;
 typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
+typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 
 typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
 struct Shape {
@@ -84,7 +85,7 @@ constexpr Shape kNoShape{nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 #ifndef ECGEMM_PERSISTENT_MAX_K
 #define ECGEMM_PERSISTENT_MAX_K 4096
 #endif
-const Shape kShapes[7][3] = {
+const Shape kShapes[8][3] = {
     {shape_of<Fp16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
     {shape_of<Bf16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
@@ -92,18 +93,19 @@ const Shape kShapes[7][3] = {
     {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
     {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
     {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
+    {shape_of<Fp32Config>(4096), kNoShape, kNoShape},
 };
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // the ecgemm_mode_t values are the ProductMethod values
 inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
-inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_FP16_OUTSIDE_ACC; }
+inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_FP32_MFMA; }
 static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
               (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
               (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
               (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain &&
-              (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside,
+              (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside && (int)ECGEMM_MODE_FP32_MFMA == (int)kMethodFp32,
               "mode numbering");
 inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_FUSED; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
@@ -239,6 +241,7 @@ ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_mode_t mode, const SplitJ
     case kSplitBf16x3: ECGEMM_LAUNCH_SPLIT(kSplitBf16x3); break;
     case kSplitFp16Unscaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Unscaled); break;
     case kSplitFp16Plain: ECGEMM_LAUNCH_SPLIT(kSplitFp16Plain); break;
+    case kSplitFp32: ECGEMM_LAUNCH_SPLIT(kSplitFp32); break;
     default: ECGEMM_LAUNCH_SPLIT(kSplitBf16Plain); break;
   }
 #undef ECGEMM_LAUNCH_SPLIT

@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   constexpr int ROW_CHUNKS = K_STEPS * NP;                 // 1 KiB chunks per 32 rows per stage
   constexpr int A_CHUNKS = (BM / 32) * ROW_CHUNKS;
   constexpr int STAGE_BYTES = (A_CHUNKS + (BN / 32) * ROW_CHUNKS) * 1024;
-  typedef typename Mfma<BF16>::frag_t frag_t;
+  typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
 
   const int t = threadIdx.x, lane = t & 63;
@@ -143,9 +143,9 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
         constexpr ProductTerm term = product_term(METHOD, m / (TM * TN));
         constexpr int i = (m % (TM * TN)) / TN, j = m % TN;
         if constexpr (term.correction)
-          acc_corr[i][j] = Mfma<BF16>::run(fb[j][term.qb], fa[i][term.qa], acc_corr[i][j]);
+          acc_corr[i][j] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[j][term.qb], fa[i][term.qa], acc_corr[i][j]);
         else
-          acc_main[i][j] = Mfma<BF16>::run(fb[j][term.qb], fa[i][term.qa], acc_main[i][j]);
+          acc_main[i][j] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[j][term.qb], fa[i][term.qa], acc_main[i][j]);
       });
     }
   };

@@ -90,20 +90,30 @@ __device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles
   tile_n = (pid % group_size) / group_m;
 }
 
-template <bool BF16>
+// The matrix instruction per element type of the packed operands.  `sub` picks one of the four 2-deep steps that an
+// FP32 fragment (four floats per lane) holds; the 16-bit fragments are consumed whole.
+enum ElementKind { kElemFp16 = 0, kElemBf16 = 1, kElemFp32 = 2 };
+template <int ELEM>
 struct Mfma;
 template <>
-struct Mfma<false> {
+struct Mfma<kElemFp16> {
   typedef half8_t frag_t;
-  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc) {
+  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc, int = 0) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, acc, 0, 0, 0);
   }
 };
 template <>
-struct Mfma<true> {
+struct Mfma<kElemBf16> {
   typedef bf16x8_t frag_t;
-  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc) {
+  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc, int = 0) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
+  }
+};
+template <>
+struct Mfma<kElemFp32> {
+  typedef float frag_t __attribute__((ext_vector_type(4)));
+  __device__ static __forceinline__ float16_t run(frag_t x, frag_t y, float16_t acc, int sub) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(x[sub], y[sub], acc, 0, 0, 0);
   }
 };
 
@@ -115,19 +125,23 @@ enum ProductMethod {
   kMethodFp16Unscaled = 3,  // the method's three products and two accumulators on Markidis' unscaled residual
   kMethodFp16Plain = 4,     // A16 B16 only (listing "A simple matrix-matrix multiplication ... on Tensor Cores")
   kMethodBf16Plain = 5,     // toBF16(A) toBF16(B) only
-  kMethodFp16Outside = 6    // kMethodFp16Split with A16 B16 added to its accumulator outside the matrix unit, every k
+  kMethodFp16Outside = 6,   // kMethodFp16Split with A16 B16 added to its accumulator outside the matrix unit, every k
                             // step, through a zeroed temporary (frag_tmp of the paper's listing; its contribution 1)
+  kMethodFp32 = 7           // A B in FP32 on the matrix unit (v_mfma_f32_32x32x2_f32): what the method is measured against
 };
 
 __host__ __device__ constexpr int split_kind_of(int method) {
   return (method == kMethodFp16Split || method == kMethodFp16Outside) ? kSplitFp16Scaled
        : method == kMethodBf16Full ? kSplitBf16x3
        : (method == kMethodFp16Markidis || method == kMethodFp16Unscaled) ? kSplitFp16Unscaled
-       : method == kMethodFp16Plain ? kSplitFp16Plain : kSplitBf16Plain;
+       : method == kMethodFp16Plain ? kSplitFp16Plain : method == kMethodFp32 ? kSplitFp32 : kSplitBf16Plain;
+}
+__host__ __device__ constexpr int element_kind_of(int method) {
+  return method == kMethodFp32 ? kElemFp32 : split_is_bf16(split_kind_of(method)) ? kElemBf16 : kElemFp16;
 }
 __host__ __device__ constexpr int products_of(int method) {
   return method == kMethodFp16Split || method == kMethodFp16Unscaled || method == kMethodFp16Outside ? 3
-       : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : 1;
+       : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : method == kMethodFp32 ? 8 : 1;
 }
 
 // Term t of a method's product list: the parts of B and A it multiplies and the accumulator set it goes to.  One
@@ -135,15 +149,19 @@ __host__ __device__ constexpr int products_of(int method) {
 struct ProductTerm {
   int qb, qa;
   bool correction;
+  int sub;  // FP32 only: which of the four 2-deep steps of the fragment pair
 };
 __host__ __device__ constexpr ProductTerm product_term(int method, int t) {
   if (method == kMethodFp16Markidis)  // everything into one accumulator, smallest first
-    return t == 0 ? ProductTerm{1, 1, false} : t == 1 ? ProductTerm{1, 0, false} : t == 2 ? ProductTerm{0, 1, false} : ProductTerm{0, 0, false};
+    return t == 0 ? ProductTerm{1, 1, false, 0} : t == 1 ? ProductTerm{1, 0, false, 0} : t == 2 ? ProductTerm{0, 1, false, 0}
+                                                                                                 : ProductTerm{0, 0, false, 0};
   if (method == kMethodBf16Full)
-    return t == 0 ? ProductTerm{0, 0, false} : t == 1 ? ProductTerm{2, 0, true} : t == 2 ? ProductTerm{0, 2, true}
-         : t == 3 ? ProductTerm{1, 1, true} : t == 4 ? ProductTerm{1, 0, true} : ProductTerm{0, 1, true};
+    return t == 0 ? ProductTerm{0, 0, false, 0} : t == 1 ? ProductTerm{2, 0, true, 0} : t == 2 ? ProductTerm{0, 2, true, 0}
+         : t == 3 ? ProductTerm{1, 1, true, 0} : t == 4 ? ProductTerm{1, 0, true, 0} : ProductTerm{0, 1, true, 0};
+  if (method == kMethodFp32)  // the two 8-deep halves of the k step, four 2-deep matrix instructions each, k ascending
+    return ProductTerm{t / 4, t / 4, false, t % 4};
   // kMethodFp16Split, kMethodFp16Unscaled, kMethodFp16Outside; the plain methods stop after the first term
-  return t == 0 ? ProductTerm{0, 0, false} : t == 1 ? ProductTerm{1, 0, true} : ProductTerm{0, 1, true};
+  return t == 0 ? ProductTerm{0, 0, false, 0} : t == 1 ? ProductTerm{1, 0, true, 0} : ProductTerm{0, 1, true, 0};
 }
 
 template <class F, int... I>
@@ -159,7 +177,7 @@ template <int METHOD, int BM_, int BN_, int WM_, int WN_, int K_STEPS_, int STAG
 struct ProductConfig {
   static constexpr int BLOCKS_PER_CU = BLOCKS_PER_CU_;            // resident workgroups per CU (registers and LDS permitting)
   static constexpr int kMethod = METHOD;
-  static constexpr bool kBf16 = split_is_bf16(split_kind_of(METHOD));
+  static constexpr int kElem = element_kind_of(METHOD);
   static constexpr int NP = parts_of_split(split_kind_of(METHOD));  // parts per value
   static constexpr int PRODUCTS = products_of(METHOD);              // matrix products formed
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
@@ -214,7 +232,7 @@ __device__ __forceinline__ void wait_loads_and_lds() {  // at most N global load
 template <class Cfg>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kernel(const ProductParams p) {
   constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::STAGES;
-  typedef typename Mfma<Cfg::kBf16>::frag_t frag_t;
+  typedef typename Mfma<Cfg::kElem>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
   const int lane = threadIdx.x & 63;
@@ -373,13 +391,13 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         float16_t zero;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-        const float16_t tmp = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], zero);
+        const float16_t tmp = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], zero, term.sub);
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc_main[i][j][v] += tmp[v];
       } else if constexpr (term.correction) {
-        acc_corr[i][j] = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_corr[i][j]);
+        acc_corr[i][j] = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_corr[i][j], term.sub);
       } else {
-        acc_main[i][j] = Mfma<Cfg::kBf16>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_main[i][j]);
+        acc_main[i][j] = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_main[i][j], term.sub);
       }
       static_for<(m + 1) * LOADS / M - m * LOADS / M>([&](auto d_c) {
         constexpr int l = m * LOADS / M + decltype(d_c)::value;
@@ -591,12 +609,12 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 template <bool BF16>
 __global__ void __launch_bounds__(64) single_mfma_kernel(const unsigned short* __restrict__ a, const unsigned short* __restrict__ b,
                                                          const float* __restrict__ c, float* __restrict__ d) {
-  typedef typename Mfma<BF16>::frag_t frag_t;
+  typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   const int64_t slot = (int64_t)blockIdx.x * 64 + threadIdx.x;
   const frag_t fa = *reinterpret_cast<const frag_t*>(a + slot * 8);
   const frag_t fb = *reinterpret_cast<const frag_t*>(b + slot * 8);
   float16_t acc = *reinterpret_cast<const float16_t*>(c + slot * 16);
-  acc = Mfma<BF16>::run(fa, fb, acc);
+  acc = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fa, fb, acc);
   *reinterpret_cast<float16_t*>(d + slot * 16) = acc;
 }
 
@@ -607,7 +625,7 @@ __global__ void __launch_bounds__(64) single_mfma_kernel(const unsigned short* _
 template <bool BF16>
 __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short* __restrict__ operands, float* __restrict__ sink,
                                                            int iters) {
-  typedef typename Mfma<BF16>::frag_t frag_t;
+  typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   frag_t fa[6], fb[6];
 #pragma unroll
   for (int i = 0; i < 6; ++i) {
@@ -623,7 +641,7 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = Mfma<BF16>::run(fa[(i + 2 * r) % 6], fb[(i * 5 + r) % 6], acc[i]);
+      for (int i = 0; i < 8; ++i) acc[i] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fa[(i + 2 * r) % 6], fb[(i * 5 + r) % 6], acc[i]);
   }
   float s = 0.0f;
 #pragma unroll

@@ -39,9 +39,12 @@ enum SplitKind {
   kSplitBf16x3 = 1,        // three exact BF16 terms
   kSplitFp16Unscaled = 2,  // v16, v - v16               Eqs. corr-elm-1, corr-elm-2 ("Markidis' halfhalf")
   kSplitFp16Plain = 3,     // v16 only
-  kSplitBf16Plain = 4      // toBF16(v) only
+  kSplitBf16Plain = 4,     // toBF16(v) only
+  kSplitFp32 = 5           // v itself, repacked for the FP32 matrix instruction (the baseline the method is set against)
 };
 
+// 1 KiB chunks per (32 rows x 16 k).  kSplitFp32 has two as well, but they are the two 8-deep halves of the k step,
+// 32 rows x 8 k of 32-bit elements each, not two parts of every element.
 __host__ __device__ constexpr int parts_of_split(int kind) {
   return kind == kSplitBf16x3 ? 3 : (kind == kSplitFp16Plain || kind == kSplitBf16Plain) ? 1 : 2;
 }
@@ -87,6 +90,18 @@ struct Splitter {
 template <int KIND>
 __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ packed, int64_t k_steps_total,
                                                    int64_t r, int64_t k, const float (&v)[8]) {
+  if constexpr (KIND == kSplitFp32) {
+    // v_mfma_f32_32x32x2_f32 takes one float per lane: lane l supplies row l % 32 and k = l / 32 of a 2-deep step.
+    // A 1 KiB chunk holds four such steps, 16 bytes per lane: element k % 8 of the row goes to lane
+    // (k % 2) * 32 + r % 32, float (k % 8) / 2.
+    typedef float native4 __attribute__((ext_vector_type(4)));
+    const int64_t chunk_index = ((r >> 5) * k_steps_total + (k >> 4)) * 2 + ((k >> 3) & 1);
+    float* chunk = reinterpret_cast<float*>(packed) + chunk_index * (kChunkElems / 2) + (int)(r & 31) * 4;
+    native4 even = {v[0], v[2], v[4], v[6]}, odd = {v[1], v[3], v[5], v[7]};
+    *reinterpret_cast<native4*>(chunk) = even;
+    *reinterpret_cast<native4*>(chunk + 32 * 4) = odd;
+    return;
+  }
   constexpr int NP = Splitter<KIND>::kParts;
   ushort8_t parts[NP];
 #pragma unroll

@@ -27,7 +27,7 @@ def _modes():
     import paper_2203_03341_amd as ec
     return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "markidis": ec.MODE_FP16_MARKIDIS,
             "unscaled": ec.MODE_FP16_UNSCALED, "plain16": ec.MODE_FP16_PLAIN, "plainbf": ec.MODE_BF16_PLAIN,
-            "outside": ec.MODE_FP16_OUTSIDE_ACC}
+            "outside": ec.MODE_FP16_OUTSIDE_ACC, "fp32": ec.MODE_FP32_MFMA}
 
 
 def _model(mode, opA, opB):
@@ -37,7 +37,8 @@ def _model(mode, opA, opB):
             "markidis": lambda: model.gemm_fp16_mode(opA, opB, products=4, scaled=False),
             "unscaled": lambda: model.gemm_fp16_mode(opA, opB, products=3, scaled=False),
             "plain16": lambda: model.gemm_plain(opA, opB, "fp16"),
-            "plainbf": lambda: model.gemm_plain(opA, opB, "bf16")}[mode]()
+            "plainbf": lambda: model.gemm_plain(opA, opB, "bf16"),
+            "fp32": lambda: opA.astype(np.float64) @ opB.astype(np.float64)}[mode]()
 
 
 def _shapes():
@@ -458,6 +459,19 @@ def test_comparison_methods_match_their_models(mode):
         mag = np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64)
         slack = 2.0 if mode == "markidis" else 1.0     # one accumulator: the small products are aligned to the big sum
         assert np.all(np.abs(got - _model(mode, opA, opB)) <= slack * (K / 8 + 4) * 2.0 ** -23 * mag)
+
+
+def test_fp32_on_the_matrix_unit_is_an_fp32_gemm():
+    """ECGEMM_MODE_FP32_MFMA, the baseline of the comparison: no splitting, FP32 products and sums on the matrix unit.
+    It must be as good as the naive FP32 loop (it adds two products per rounding), element by element within the FP32
+    accumulation bound, and exact on small integers; the method's two modes must not be worse than it."""
+    for (tA, tB, M, N, K, alpha, beta, pad) in [("N", "N", 300, 200, 77, 1.5, 0.5, 3), ("T", "T", 513, 259, 130, -1.0, 1.0, 1),
+                                                ("N", "T", 700, 900, 1500, 1.0, 0.0, 0), ("T", "N", 1, 1, 1, 1.0, 0.0, 0)]:
+        _check(tA, tB, M, N, K, alpha, beta, "fp32", "urand", seed=21, pad=pad, ratio_rule=K >= 64)
+    rows = si.sample_indices(3000, 128, seed=3)
+    r32, r_cpu = _check("N", "N", 3000, 3000, 1100, 1.0, 0.0, "fp32", "urand", seed=22, rows=rows)
+    r16, _ = _check("N", "N", 3000, 3000, 1100, 1.0, 0.0, "fp16", "urand", seed=22, rows=rows)
+    assert r16 <= 1.25 * r32 and r32 <= 1.25 * r_cpu
 
 
 def test_error_ordering_of_the_papers_first_figure():

@@ -4,7 +4,7 @@ import pytest
 
 import seeded_inputs as si
 from oracle import split
-from gpu_util import pack_fragment_order, to_device
+from gpu_util import pack_fp32_fragment_order, pack_fragment_order, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -14,7 +14,7 @@ def _mode_id(mode):
     if isinstance(mode, bool):
         return ec.MODE_BF16_FULL if mode else ec.MODE_FP16_SPLIT
     return {"unscaled": ec.MODE_FP16_UNSCALED, "markidis": ec.MODE_FP16_MARKIDIS, "plain16": ec.MODE_FP16_PLAIN,
-            "plainbf": ec.MODE_BF16_PLAIN}[mode]
+            "plainbf": ec.MODE_BF16_PLAIN, "fp32": ec.MODE_FP32_MFMA}[mode]
 
 
 def _expected(op, store, rows, depth, mode):
@@ -26,6 +26,8 @@ def _expected(op, store, rows, depth, mode):
         parts = [p.view(np.uint16) for p in split.split_fp16(X)]
     elif mode in ("unscaled", "markidis"):
         parts = [p.view(np.uint16) for p in split.split_fp16(X, scaled=False)]
+    elif mode == "fp32":
+        return pack_fp32_fragment_order(X)
     elif mode == "plain16":
         parts = [split.to_fp16_rn(X).view(np.uint16)]
     else:
@@ -106,7 +108,7 @@ def test_split_edge_values(mode_bf16):
             assert (bits & 0x7C00) == 0x7C00 and (bits & 0x3FF) != 0
 
 
-@pytest.mark.parametrize("mode", ["unscaled", "markidis", "plain16", "plainbf"])
+@pytest.mark.parametrize("mode", ["unscaled", "markidis", "plain16", "plainbf", "fp32"])
 @pytest.mark.parametrize("op", ["N", "T"])
 def test_split_of_comparison_methods(mode, op):
     """Markidis' unscaled residual (Eqs. corr-elm-1, corr-elm-2) and the plain conversions, bit for bit."""
