@@ -89,8 +89,9 @@ def main():
     ap.add_argument("--power-seconds", type=float, default=2.5,
                     help="after the timed steps, loop the same call for this long while sampling board power from sysfs "
                          "every 20 ms (the paper samples NVML every 0.02 s over >= 2 s); 0 disables")
-    ap.add_argument("--library-sgemm", action="store_true",
-                    help="also time (and power-sample) the vendor library's FP32 GEMM on the same operands, for context")
+    ap.add_argument("--no-library-sgemm", dest="library_sgemm", action="store_false",
+                    help="skip the context measurement: the vendor library's FP32 GEMM and this library's own FP32 mode "
+                         "on the same operands, timed and power-sampled after the run proper")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the matrix-instruction-only rate measurement")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one device-to-device copy of 1 GiB (a kernel of known HBM traffic, for scaling "
