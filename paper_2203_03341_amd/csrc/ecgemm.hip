@@ -58,7 +58,7 @@ typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Con
 typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
 typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 
-typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
+typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
   void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
@@ -260,6 +260,42 @@ int64_t product_grid(const Plan& pl, int compute_units, bool* persistent_out) {
   return persistent ? slots : one_block_per_item;
 }
 
+// How the 8 XCDs are laid over the tile grid (ProductParams::xcd_grid_n).  Each XCD has its own L2, and what misses
+// there is served by the memory-side cache that all XCDs share (256 MiB), else by HBM.  With xm x (8 / xm) XCDs, each
+// walking its own rectangle of tiles along N, xm panels of A (group_m tile rows x K each) are live at a time; they are
+// re-used by every patch of the walk while B streams past once per xm panels.  So xm should be as large as lets the
+// live panels of A stay in that cache: measured best when they take at most half of it (16384^3: 2 x 4 and 4 x 2 are
+// 2.2 % ahead of 8 x 1; 8192^3: 4 x 2 by 2.2 %; 16384 x 16384 x 4096, where 8 panels are 128 MiB: 8 x 1 is 2 % ahead
+// of 2 x 4).  Used when every tile is a whole item, the rectangles are equal, and each holds at least the patch of
+// tiles an XCD works on at one time; otherwise each XCD takes a contiguous run of the tile order (0).
+int xcd_grid_n(const Plan& pl, int group_m, ecgemm_mode_t mode) {
+#ifdef ECGEMM_XCD_GRID_N
+  if (ECGEMM_XCD_GRID_N == 0) return 0;
+#endif
+  if (pl.tail_tiles > 0) return 0;
+  const int patch_n = 32 * pl.shape->blocks_per_cu / group_m;
+  const int64_t panel_bytes = (int64_t)group_m * pl.shape->bm * pl.Kp * 2 * parts_of(mode);
+  for (int xm = 8; xm >= 1; xm /= 2) {
+    const int n = 8 / xm;
+#ifdef ECGEMM_XCD_GRID_N
+    if (n != ECGEMM_XCD_GRID_N) continue;
+#else
+    if (xm > 1 && xm * panel_bytes > (128ll << 20)) continue;
+#endif
+    if (pl.tiles_m % xm == 0 && pl.tiles_n % n == 0 && pl.tiles_m / xm >= group_m && pl.tiles_n / n >= patch_n) return n;
+  }
+  return 0;
+}
+
+// Tile rows per group of the tile order.  The 32 compute units of an XCD work on consecutive tiles, and the nearer to
+// square the patch of C these cover, the fewer distinct panel rows they request per k step: 4 x 8 tiles of 256 x 128.
+// For the 128 x 128 shape (64 tiles at a time) 8 x 8 is ahead only on the shallow products the shape is chosen for
+// (2.5 % at 16384 x 16384 x 256 and x 512; 4 x 16 is 4 % ahead at 8192^3).
+#ifndef ECGEMM_GROUP_M
+#define ECGEMM_GROUP_M 4
+#endif
+int group_m_of(const Plan& pl) { return (pl.shape->bm == 128 && pl.Kp <= 512) ? 2 * ECGEMM_GROUP_M : ECGEMM_GROUP_M; }
+
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
                                const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials,
@@ -274,6 +310,8 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.full_tiles = pl.full_tiles;
   pp.tail_tiles = pl.tail_tiles;
   pp.tail_splits = pl.tail_splits;
+  pp.group_m = group_m_of(pl);
+  pp.xcd_grid_n = xcd_grid_n(pl, pp.group_m, mode);
   pp.M = M;
   pp.N = N;
   pp.ldc = ldc;
@@ -291,7 +329,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bn / 16));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
-                       pl.full_tiles, pl.tiles_m, pl.tiles_n, M, N, alpha, beta, C, ldc);
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, pp.group_m, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -332,7 +370,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 / 16));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
-                       pl.tiles_m, pl.tiles_n, M, N, alpha, beta, C, ldc);
+                       pl.tiles_m, pl.tiles_n, 4, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;

@@ -50,6 +50,10 @@ struct ProductParams {
   // depth; each of the remaining tail_tiles is tail_splits items, one per slice of the depth, which leave raw sums in
   // `partials` for reduce_tail_kernel.  tail_splits == 1: those tiles are whole items too and nothing goes to partials.
   int full_tiles, tail_tiles, tail_splits;
+  int group_m;  // tile rows per group of the tile order (tile_coordinates)
+  // 0: each XCD owns one contiguous run of the tile order.  n in {1, 2, 4, 8} (whole tiles only, tiles_m a multiple of
+  // 8 / n, tiles_n a multiple of n): the XCDs are laid out (8 / n) x n over the tile grid and each walks its own rectangle.
+  int xcd_grid_n;
   int64_t M, N, ldc;
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
@@ -75,19 +79,15 @@ __device__ __forceinline__ float scaled_sum(float alpha, float c, float beta, fl
   return __builtin_fmaf(beta, c_in, alpha * c);
 }
 
-#ifndef ECGEMM_GROUP_M
-#define ECGEMM_GROUP_M 4
-#endif
-// Output tile number -> tile coordinates: groups of ECGEMM_GROUP_M tile rows, walked column by column, so that tiles
-// with neighbouring numbers share A and B panels.
-__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
-  constexpr int kGroupM = ECGEMM_GROUP_M;
-  const int group_size = kGroupM * tiles_n;
+// Output tile number -> tile coordinates: groups of group_m tile rows, walked column by column, so that tiles with
+// neighbouring numbers share A and B panels.
+__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int group_m, int& tile_m, int& tile_n) {
+  const int group_size = group_m * tiles_n;
   const int group = pid / group_size;
-  const int first_m = group * kGroupM;
-  const int group_m = min(tiles_m - first_m, kGroupM);
-  tile_m = first_m + (pid % group_size) % group_m;
-  tile_n = (pid % group_size) / group_m;
+  const int first_m = group * group_m;
+  const int rows_here = min(tiles_m - first_m, group_m);
+  tile_m = first_m + (pid % group_size) % rows_here;
+  tile_n = (pid % group_size) / rows_here;
 }
 
 // The matrix instruction per element type of the packed operands.  `sub` picks one of the four 2-deep steps that an
@@ -255,6 +255,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #define ECGEMM_READ_TAIL 6
 #endif
   const int tail_items = p.tail_tiles * p.tail_splits;
+  const int xcd_grid_n = ECGEMM_XCD_REMAP ? p.xcd_grid_n : 0;
   auto locate = [&](int item) {
     Work w;
     int pid = item;
@@ -271,7 +272,16 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         w.partial = j;
       }
     }
-    tile_coordinates(pid, p.tiles_m, p.tiles_n, w.tile_m, w.tile_n);
+    if (xcd_grid_n > 0) {
+      // whole tiles only: item = xcd * tiles_per_xcd + position inside the XCD's own rectangle of the tile grid
+      const int sub_m = p.tiles_m / (8 / xcd_grid_n), sub_n = p.tiles_n / xcd_grid_n;
+      const int x = item / (sub_m * sub_n), pos = item % (sub_m * sub_n);
+      tile_coordinates(pos, sub_m, sub_n, p.group_m, w.tile_m, w.tile_n);
+      w.tile_m += (x / xcd_grid_n) * sub_m;
+      w.tile_n += (x % xcd_grid_n) * sub_n;
+      return w;
+    }
+    tile_coordinates(pid, p.tiles_m, p.tiles_n, p.group_m, w.tile_m, w.tile_n);
     return w;
   };
   // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.
@@ -655,11 +665,12 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 // partials is [tail_splits][tail_tiles][BN][BM]; block (t, c) handles 16 columns of tail tile t.
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
-                                                          int full_tiles, int tiles_m, int tiles_n, int64_t M, int64_t N,
+                                                          int full_tiles, int tiles_m, int tiles_n, int group_m, int64_t M,
+                                                          int64_t N,
                                                           float alpha, float beta, float* __restrict__ C, int64_t ldc) {
   static_assert(256 % BM == 0 && BN % 16 == 0, "tile shape");
   int tile_m, tile_n;
-  tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
   const int m_local = threadIdx.x % BM;
   const int64_t m = (int64_t)tile_m * BM + m_local;
   if (m >= M) return;
