@@ -94,8 +94,8 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t
 
 /* How ecgemm_sgemm would run this problem (host logic only; no GPU work, `handle` as in ecgemm_workspace_size):
  * the kernel shape, the output tiles, how many of them are one work item over the whole depth and how many are cut
- * into how many slices along K, whether the product kernel is launched as a persistent grid, its grid size on a
- * 256-CU device, and the workspace bytes.  `info` is a host pointer. */
+ * into how many slices along K, whether the product kernel is launched as a persistent grid, in which order the tiles
+ * go to the XCDs, its grid size on a 256-CU device, and the workspace bytes.  `info` is a host pointer. */
 typedef struct {
     int shape;          /* ecgemm_shape_t actually used (never ECGEMM_SHAPE_AUTO) */
     int tile_m, tile_n; /* block tile */
@@ -104,6 +104,9 @@ typedef struct {
     int sliced_tiles;   /* tiles cut into `slices` work items each; their sums are added by a second kernel */
     int slices;         /* 1 if sliced_tiles == 0 */
     int persistent;     /* 1: one workgroup per CU walks through several work items */
+    int group_m;        /* tile rows per group of the order in which tiles are handed out (groups are walked along N) */
+    int xcd_grid_n;     /* n > 0: the 8 XCDs are laid out (8 / n) x n over the tile grid, each walking its own rectangle;
+                           0: each XCD takes a contiguous run of the tile order */
     int64_t grid;       /* workgroups of the product (or fused) kernel */
     size_t workspace_bytes;
 } ecgemm_plan_info_t;

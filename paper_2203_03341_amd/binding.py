@@ -30,7 +30,8 @@ class PlanInfo(ctypes.Structure):
     """ecgemm_plan_info_t"""
     _fields_ = [("shape", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("tiles_m", ctypes.c_int),
                 ("tiles_n", ctypes.c_int), ("whole_tiles", ctypes.c_int), ("sliced_tiles", ctypes.c_int),
-                ("slices", ctypes.c_int), ("persistent", ctypes.c_int), ("grid", ctypes.c_int64),
+                ("slices", ctypes.c_int), ("persistent", ctypes.c_int), ("group_m", ctypes.c_int),
+                ("xcd_grid_n", ctypes.c_int), ("grid", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_size_t)]
 
     def as_dict(self) -> dict:

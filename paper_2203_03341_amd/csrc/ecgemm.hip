@@ -514,6 +514,8 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   bool persistent = false;
   info->grid = pl.shape->fused ? (int64_t)pl.tiles_m * pl.tiles_n * pl.tail_splits : product_grid(pl, kPlanComputeUnits, &persistent);
   info->persistent = persistent ? 1 : 0;
+  info->group_m = pl.shape->fused ? 4 : group_m_of(pl);
+  info->xcd_grid_n = pl.shape->fused ? 0 : xcd_grid_n(pl, info->group_m, mode);
   info->workspace_bytes = pl.total_bytes;
   return ECGEMM_OK;
 }
