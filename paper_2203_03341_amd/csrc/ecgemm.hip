@@ -327,7 +327,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   void* args[] = {&pp};
   ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->product), grid, dim3(pl.shape->threads), args, 0, h->stream));
   if (pl.tail_splits > 1) {
-    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bn / 16));
+    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
                        pl.full_tiles, pl.tiles_m, pl.tiles_n, pp.group_m, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
@@ -368,7 +368,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused), dim3((unsigned)(tiles * pl.tail_splits)), dim3(256),
                                 args, 0, h->stream));
   if (pl.tail_splits > 1) {
-    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 / 16));
+    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 * 128 / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
                        pl.tiles_m, pl.tiles_n, 4, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());

@@ -662,27 +662,46 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 }
 
 // Sums the slices of the sliced tiles in a fixed order (bitwise reproducible, no atomics), then alpha / beta.
-// partials is [tail_splits][tail_tiles][BN][BM]; block (t, c) handles 16 columns of tail tile t.
+// partials is [tail_splits][tail_tiles][BN][BM]; block (t, q) handles elements 1024 q .. 1024 q + 1023 of tail tile t,
+// four consecutive rows of one column per thread, so that every load is 16 bytes per lane and the loads of different
+// slices are independent of each other.
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
                                                           int full_tiles, int tiles_m, int tiles_n, int group_m, int64_t M,
-                                                          int64_t N,
-                                                          float alpha, float beta, float* __restrict__ C, int64_t ldc) {
-  static_assert(256 % BM == 0 && BN % 16 == 0, "tile shape");
+                                                          int64_t N, float alpha, float beta, float* __restrict__ C,
+                                                          int64_t ldc) {
+  static_assert(BM % 4 == 0 && (BM * BN) % 1024 == 0, "tile shape");
   int tile_m, tile_n;
   tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
-  const int m_local = threadIdx.x % BM;
-  const int64_t m = (int64_t)tile_m * BM + m_local;
-  if (m >= M) return;
-  for (int c = threadIdx.x / BM; c < 16; c += 256 / BM) {
-    const int n_local = blockIdx.y * 16 + c;
-    const int64_t n = (int64_t)tile_n * BN + n_local;
-    if (n >= N) break;
-    float sum = 0.0f;
-    for (int s = 0; s < tail_splits; ++s)
-      sum += partials[(((int64_t)s * tail_tiles + blockIdx.x) * BN + n_local) * BM + m_local];
-    float* dst = C + m + n * ldc;
-    store_result(dst, (beta == 0.0f) ? alpha * sum : scaled_sum(alpha, sum, beta, *dst));
+  const int e = (blockIdx.y * 256 + threadIdx.x) * 4;  // element of the tile, stored [n_local][m_local]
+  const int64_t m = (int64_t)tile_m * BM + e % BM, n = (int64_t)tile_n * BN + e / BM;
+  if (m >= M || n >= N) return;
+  const float* src = partials + (int64_t)blockIdx.x * (BM * BN) + e;
+  const int64_t slice_stride = (int64_t)tail_tiles * (BM * BN);
+  float4 sum = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+#pragma unroll 4
+  for (int s = 0; s < tail_splits; ++s) {
+    const float4 v = *reinterpret_cast<const float4*>(src + s * slice_stride);
+    sum.x += v.x, sum.y += v.y, sum.z += v.z, sum.w += v.w;
+  }
+  const float part[4] = {sum.x, sum.y, sum.z, sum.w};
+  float* dst = C + m + n * ldc;
+  if (m + 3 < M && (reinterpret_cast<uintptr_t>(dst) & 15) == 0) {
+    typedef float vec4_t __attribute__((ext_vector_type(4)));
+    vec4_t out;
+    if (beta == 0.0f) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) out[i] = alpha * part[i];
+    } else {
+      const vec4_t c_in = *reinterpret_cast<const vec4_t*>(dst);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) out[i] = scaled_sum(alpha, part[i], beta, c_in[i]);
+    }
+    __builtin_nontemporal_store(out, reinterpret_cast<vec4_t*>(dst));
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (m + i < M) store_result(dst + i, (beta == 0.0f) ? alpha * part[i] : scaled_sum(alpha, part[i], beta, dst[i]));
   }
 }
 
