@@ -105,8 +105,8 @@ typedef struct {
     int slices;         /* 1 if sliced_tiles == 0 */
     int persistent;     /* 1: one workgroup per CU walks through several work items */
     int group_m;        /* tile rows per group of the order in which tiles are handed out (groups are walked along N) */
-    int xcd_grid_n;     /* n > 0: the 8 XCDs are laid out (8 / n) x n over the tile grid, each walking its own rectangle;
-                           0: each XCD takes a contiguous run of the tile order */
+    int column_bands;   /* n: the tile order takes the grid in n bands of columns one after the other; each XCD takes a
+                           contiguous run of the order, so the 8 XCDs lie (8 / n) x n over the tile grid */
     int64_t grid;       /* workgroups of the product (or fused) kernel */
     size_t workspace_bytes;
 } ecgemm_plan_info_t;

@@ -31,7 +31,7 @@ class PlanInfo(ctypes.Structure):
     _fields_ = [("shape", ctypes.c_int), ("tile_m", ctypes.c_int), ("tile_n", ctypes.c_int), ("tiles_m", ctypes.c_int),
                 ("tiles_n", ctypes.c_int), ("whole_tiles", ctypes.c_int), ("sliced_tiles", ctypes.c_int),
                 ("slices", ctypes.c_int), ("persistent", ctypes.c_int), ("group_m", ctypes.c_int),
-                ("xcd_grid_n", ctypes.c_int), ("grid", ctypes.c_int64),
+                ("column_bands", ctypes.c_int), ("grid", ctypes.c_int64),
                 ("workspace_bytes", ctypes.c_size_t)]
 
     def as_dict(self) -> dict:

@@ -58,7 +58,7 @@ typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Con
 typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
 typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 
-typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
+typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
   void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
@@ -260,31 +260,30 @@ int64_t product_grid(const Plan& pl, int compute_units, bool* persistent_out) {
   return persistent ? slots : one_block_per_item;
 }
 
-// How the 8 XCDs are laid over the tile grid (ProductParams::xcd_grid_n).  Each XCD has its own L2, and what misses
-// there is served by the memory-side cache that all XCDs share (256 MiB), else by HBM.  With xm x (8 / xm) XCDs, each
-// walking its own rectangle of tiles along N, xm panels of A (group_m tile rows x K each) are live at a time; they are
-// re-used by every patch of the walk while B streams past once per xm panels.  So xm should be as large as lets the
-// live panels of A stay in that cache: measured best when they take at most half of it (16384^3: 2 x 4 and 4 x 2 are
-// 2.2 % ahead of 8 x 1; 8192^3: 4 x 2 by 2.2 %; 16384 x 16384 x 4096, where 8 panels are 128 MiB: 8 x 1 is 2 % ahead
-// of 2 x 4).  Used when every tile is a whole item, the rectangles are equal, and each holds at least the patch of
-// tiles an XCD works on at one time; otherwise each XCD takes a contiguous run of the tile order (0).
-int xcd_grid_n(const Plan& pl, int group_m, ecgemm_mode_t mode) {
-#ifdef ECGEMM_XCD_GRID_N
-  if (ECGEMM_XCD_GRID_N == 0) return 0;
+// Column bands of the tile order (ProductParams::column_bands), which decide how the 8 XCDs lie over the tile grid:
+// each XCD takes a contiguous run of the order, so with n bands the XCDs are laid out (8 / n) x n, each walking its
+// own part of the grid along N.  Each XCD has its own L2, and what misses there is served by the memory-side cache
+// that all XCDs share (256 MiB), else by HBM.  With xm = 8 / n rows of XCDs, xm panels of A (group_m tile rows x K
+// each) are live at a time; they are re-used by every patch of the walk while B streams past once per xm panels.  So
+// xm should be as large as lets the live panels of A stay in that cache: measured best when they take at most half of
+// it (16384^3: 2 x 4 and 4 x 2 are 2.2 % ahead of 8 x 1; 8192^3: 4 x 2 by 2.2 %; 16384 x 16384 x 4096, where 8 panels
+// are 128 MiB: 8 x 1 is 2 % ahead of 2 x 4).  A band is at least as wide as the patch of tiles an XCD works on at one
+// time.
+int column_bands(const Plan& pl, int group_m, ecgemm_mode_t mode) {
+#ifdef ECGEMM_COLUMN_BANDS
+  return std::max(1, std::min(ECGEMM_COLUMN_BANDS, pl.tiles_n));
 #endif
-  if (pl.tail_tiles > 0) return 0;
   const int patch_n = 32 * pl.shape->blocks_per_cu / group_m;
   const int64_t panel_bytes = (int64_t)group_m * pl.shape->bm * pl.Kp * 2 * parts_of(mode);
-  for (int xm = 8; xm >= 1; xm /= 2) {
-    const int n = 8 / xm;
-#ifdef ECGEMM_XCD_GRID_N
-    if (n != ECGEMM_XCD_GRID_N) continue;
-#else
-    if (xm > 1 && xm * panel_bytes > (128ll << 20)) continue;
-#endif
-    if (pl.tiles_m % xm == 0 && pl.tiles_n % n == 0 && pl.tiles_m / xm >= group_m && pl.tiles_n / n >= patch_n) return n;
+  const int groups = (pl.tiles_m + group_m - 1) / group_m;
+  int best = 1;
+  for (int n = 1; n <= 8; n *= 2) {
+    if (n > 1 && pl.tiles_n / n < patch_n) break;
+    best = n;
+    const int live_panels = std::min(8 / n, groups);
+    if (live_panels == 1 || live_panels * panel_bytes <= (128ll << 20)) break;
   }
-  return 0;
+  return best;
 }
 
 // Tile rows per group of the tile order.  The 32 compute units of an XCD work on consecutive tiles, and the nearer to
@@ -311,7 +310,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.tail_tiles = pl.tail_tiles;
   pp.tail_splits = pl.tail_splits;
   pp.group_m = group_m_of(pl);
-  pp.xcd_grid_n = xcd_grid_n(pl, pp.group_m, mode);
+  pp.column_bands = column_bands(pl, pp.group_m, mode);
   pp.M = M;
   pp.N = N;
   pp.ldc = ldc;
@@ -329,7 +328,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
-                       pl.full_tiles, pl.tiles_m, pl.tiles_n, pp.group_m, M, N, alpha, beta, C, ldc);
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, pp.group_m, pp.column_bands, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -370,7 +369,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 * 128 / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
-                       pl.tiles_m, pl.tiles_n, 4, M, N, alpha, beta, C, ldc);
+                       pl.tiles_m, pl.tiles_n, 4, 1, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -515,7 +514,7 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   info->grid = pl.shape->fused ? (int64_t)pl.tiles_m * pl.tiles_n * pl.tail_splits : product_grid(pl, kPlanComputeUnits, &persistent);
   info->persistent = persistent ? 1 : 0;
   info->group_m = pl.shape->fused ? 4 : group_m_of(pl);
-  info->xcd_grid_n = pl.shape->fused ? 0 : xcd_grid_n(pl, info->group_m, mode);
+  info->column_bands = pl.shape->fused ? 1 : column_bands(pl, info->group_m, mode);
   info->workspace_bytes = pl.total_bytes;
   return ECGEMM_OK;
 }

@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   const int tiles = p.tiles_m * p.tiles_n;
   const int split = blockIdx.x / tiles, pid = blockIdx.x % tiles;
   int tile_m, tile_n;
-  tile_coordinates(pid, p.tiles_m, p.tiles_n, 4, tile_m, tile_n);
+  tile_coordinates(pid, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
   const int stages_per_split = (p.stages + p.splits - 1) / p.splits;
   const int stage_begin = split * stages_per_split;
   const int stage_count = max(0, min(p.stages, stage_begin + stages_per_split) - stage_begin);

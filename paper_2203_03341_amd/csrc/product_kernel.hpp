@@ -51,9 +51,8 @@ struct ProductParams {
   // `partials` for reduce_tail_kernel.  tail_splits == 1: those tiles are whole items too and nothing goes to partials.
   int full_tiles, tail_tiles, tail_splits;
   int group_m;  // tile rows per group of the tile order (tile_coordinates)
-  // 0: each XCD owns one contiguous run of the tile order.  n in {1, 2, 4, 8} (whole tiles only, tiles_m a multiple of
-  // 8 / n, tiles_n a multiple of n): the XCDs are laid out (8 / n) x n over the tile grid and each walks its own rectangle.
-  int xcd_grid_n;
+  int column_bands;  // see tile_coordinates; with each XCD taking a contiguous run of the order, n bands of columns lay
+                     // the 8 XCDs out (8 / n) x n over the tile grid
   int64_t M, N, ldc;
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
@@ -79,15 +78,32 @@ __device__ __forceinline__ float scaled_sum(float alpha, float c, float beta, fl
   return __builtin_fmaf(beta, c_in, alpha * c);
 }
 
-// Output tile number -> tile coordinates: groups of group_m tile rows, walked column by column, so that tiles with
-// neighbouring numbers share A and B panels.
-__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int group_m, int& tile_m, int& tile_n) {
-  const int group_size = group_m * tiles_n;
+// Output tile number -> tile coordinates.  The tile grid is cut into column_bands bands of (nearly) equal width, taken
+// one after the other; inside a band the tiles go in groups of group_m tile rows, each walked column by column, so
+// that tiles with neighbouring numbers share A and B panels.  column_bands <= tiles_n.
+__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int group_m, int column_bands, int& tile_m,
+                                                 int& tile_n) {
+  const int narrow = tiles_n / column_bands, wider = tiles_n % column_bands;  // the first `wider` bands have narrow + 1 columns
+  const int tiles_wide = (narrow + 1) * tiles_m;
+  int width, first_n;
+  if (pid < wider * tiles_wide) {
+    const int band = pid / tiles_wide;
+    pid -= band * tiles_wide;
+    width = narrow + 1;
+    first_n = band * width;
+  } else {
+    pid -= wider * tiles_wide;
+    const int band = pid / (narrow * tiles_m);
+    pid -= band * (narrow * tiles_m);
+    width = narrow;
+    first_n = wider * (narrow + 1) + band * narrow;
+  }
+  const int group_size = group_m * width;
   const int group = pid / group_size;
   const int first_m = group * group_m;
   const int rows_here = min(tiles_m - first_m, group_m);
   tile_m = first_m + (pid % group_size) % rows_here;
-  tile_n = (pid % group_size) / rows_here;
+  tile_n = first_n + (pid % group_size) / rows_here;
 }
 
 // The matrix instruction per element type of the packed operands.  `sub` picks one of the four 2-deep steps that an
@@ -255,7 +271,6 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #define ECGEMM_READ_TAIL 6
 #endif
   const int tail_items = p.tail_tiles * p.tail_splits;
-  const int xcd_grid_n = ECGEMM_XCD_REMAP ? p.xcd_grid_n : 0;
   auto locate = [&](int item) {
     Work w;
     int pid = item;
@@ -272,16 +287,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         w.partial = j;
       }
     }
-    if (xcd_grid_n > 0) {
-      // whole tiles only: item = xcd * tiles_per_xcd + position inside the XCD's own rectangle of the tile grid
-      const int sub_m = p.tiles_m / (8 / xcd_grid_n), sub_n = p.tiles_n / xcd_grid_n;
-      const int x = item / (sub_m * sub_n), pos = item % (sub_m * sub_n);
-      tile_coordinates(pos, sub_m, sub_n, p.group_m, w.tile_m, w.tile_n);
-      w.tile_m += (x / xcd_grid_n) * sub_m;
-      w.tile_n += (x % xcd_grid_n) * sub_n;
-      return w;
-    }
-    tile_coordinates(pid, p.tiles_m, p.tiles_n, p.group_m, w.tile_m, w.tile_n);
+    tile_coordinates(pid, p.tiles_m, p.tiles_n, p.group_m, p.column_bands, w.tile_m, w.tile_n);
     return w;
   };
   // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.
@@ -667,12 +673,12 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 // slices are independent of each other.
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
-                                                          int full_tiles, int tiles_m, int tiles_n, int group_m, int64_t M,
-                                                          int64_t N, float alpha, float beta, float* __restrict__ C,
+                                                          int full_tiles, int tiles_m, int tiles_n, int group_m,
+                                                          int column_bands, int64_t M, int64_t N, float alpha, float beta, float* __restrict__ C,
                                                           int64_t ldc) {
   static_assert(BM % 4 == 0 && (BM * BN) % 1024 == 0, "tile shape");
   int tile_m, tile_n;
-  tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, tile_m, tile_n);
+  tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, column_bands, tile_m, tile_n);
   const int e = (blockIdx.y * 256 + threadIdx.x) * 4;  // element of the tile, stored [n_local][m_local]
   const int64_t m = (int64_t)tile_m * BM + e % BM, n = (int64_t)tile_n * BN + e / BM;
   if (m >= M || n >= N) return;

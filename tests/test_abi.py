@@ -53,21 +53,22 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["tile_m"], p["tile_n"], p["whole_tiles"], p["sliced_tiles"], p["persistent"], p["grid"]) == \
         (W4, 256, 128, 8192, 0, 0, 8192)
     assert p["workspace_bytes"] == 2 * 16384 * 16384 * 4
-    # how the 8 XCDs lie over the tile grid: as many row bands as keep the live A panels (group_m tile rows x K, packed)
-    # within 128 MiB of the shared cache
-    assert (p["group_m"], p["xcd_grid_n"]) == (4, 4)                  # 64 MiB panels: 2 x 4
-    assert ec.plan_info(8192, 8192, 8192, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == 2     # 32 MiB panels: 4 x 2
-    assert ec.plan_info(8192, 8192, 8192, ec.MODE_BF16_FULL)["xcd_grid_n"] == 4      # 48 MiB panels: 2 x 4
-    assert ec.plan_info(8192, 8192, 2048, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == 1     # 8 MiB panels: 8 x 1
-    assert ec.plan_info(4096, 4096, 4096, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == 2     # 16 tile rows: 8 bands would be thinner than a group
-    assert ec.plan_info(1024, 8192, 16416, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == 8    # one panel is over 64 MiB: 1 x 8
-    assert ec.plan_info(4095, 3001, 5003, ec.MODE_BF16_FULL)["xcd_grid_n"] == 0      # sliced tiles: contiguous runs
-    assert ec.plan_info(4096, 16384 + 128, 16384, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == 0  # 16 x 129 tiles: no equal rectangles
+    # column bands of the tile order = how the 8 XCDs lie over the tile grid: as many rows of XCDs as keep the live A
+    # panels (group_m tile rows x K, packed) within 128 MiB of the shared cache
+    assert (p["group_m"], p["column_bands"]) == (4, 4)                  # 64 MiB panels: 2 x 4
+    assert ec.plan_info(8192, 8192, 8192, ec.MODE_FP16_SPLIT)["column_bands"] == 2     # 32 MiB panels: 4 x 2
+    assert ec.plan_info(8192, 8192, 8192, ec.MODE_BF16_FULL)["column_bands"] == 4      # 48 MiB panels: 2 x 4
+    assert ec.plan_info(8192, 8192, 2048, ec.MODE_FP16_SPLIT)["column_bands"] == 1     # 8 MiB panels: 8 x 1
+    assert ec.plan_info(4096, 4096, 4096, ec.MODE_FP16_SPLIT)["column_bands"] == 1     # four groups of 16 MiB
+    assert ec.plan_info(2048, 8192, 32800, ec.MODE_FP16_SPLIT)["column_bands"] == 8    # one panel is 128 MiB: 1 x 8
+    assert ec.plan_info(1024, 8192, 32800, ec.MODE_FP16_SPLIT)["column_bands"] == 1    # a single group of tile rows
+    assert ec.plan_info(4096, 16384 + 128, 16384, ec.MODE_FP16_SPLIT)["column_bands"] == 4   # 129 tile columns: 33 + 3 x 32
+    assert ec.plan_info(16384, 512, 16384, ec.MODE_FP16_SPLIT)["column_bands"] == 1    # 4 tile columns: narrower than a patch
     p = ec.plan_info(4096, 4096, 4096, ec.MODE_BF16_FULL)              # K <= 4096: persistent grid of one block per CU
     assert (p["shape"], p["whole_tiles"], p["persistent"], p["grid"]) == (W4, 512, 1, 256)
     p = ec.plan_info(16384, 16384, 256, ec.MODE_FP16_SPLIT)            # shallow K: 128 x 128 tiles, two blocks per CU
     assert (p["shape"], p["tile_m"], p["whole_tiles"], p["slices"], p["persistent"]) == (X2, 128, 128 * 128, 1, 0)
-    assert (p["group_m"], p["xcd_grid_n"]) == (8, 1)
+    assert (p["group_m"], p["column_bands"]) == (8, 1)
     p = ec.plan_info(1024, 1024, 65536, ec.MODE_FP16_SPLIT)            # 32 tiles: all cut into 8 slices = 256 items
     assert (p["shape"], p["whole_tiles"], p["sliced_tiles"], p["slices"], p["grid"]) == (W4, 0, 32, 8, 256)
     p = ec.plan_info(4095, 3001, 5003, ec.MODE_BF16_FULL)              # 384 tiles: 256 whole, 128 in two slices

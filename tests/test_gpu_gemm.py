@@ -350,14 +350,14 @@ def test_whole_tiles_followed_by_a_sliced_tail(mode, shape):
     _check("N", "N", 3000, 3000, 1100, 1.0, 0.5, mode, "urand", seed=5, rows=rows, shape=shape)
 
 
-@pytest.mark.parametrize("case", [(8192, 8192, 2048, 1), (4096, 2048, 8192, 2), (2048, 4096, 16384, 4), (1024, 8192, 16416, 8)])
+@pytest.mark.parametrize("case", [(8192, 8192, 2048, 1), (8192, 2048, 8192, 2), (4096, 4096 + 128, 16384, 4), (2048, 8192, 32800, 8)])
 def test_every_arrangement_of_the_xcds_over_the_tile_grid(case):
     """The tile a workgroup takes depends on how the 8 XCDs are laid over the tile grid (8 x 1, 4 x 2, 2 x 4, 1 x 8, by
-    the size of a panel of A): every tile must still be computed exactly once.  All of C is compared with the FP32
+    the size of a panel of A; the third case has bands of unequal width and sliced tiles): every tile must still be computed exactly once.  All of C is compared with the FP32
     matrix-unit mode (different kernel, same arrangement rule but other panel sizes), sampled rows with the oracle."""
     import paper_2203_03341_amd as ec
     M, N, K, n = case
-    assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["xcd_grid_n"] == n
+    assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["column_bands"] == n
     _check("N", "N", M, N, K, 1.0, 0.0, "fp16", "urand", seed=9, rows=si.sample_indices(M, 48, seed=4))
     A, B = _inputs(M, N, K, "N", "N", "urand", 9)
     got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "fp16")[:M, :N]
