@@ -405,6 +405,8 @@ ecgemm_status_t acquire_workspace(ecgemm_handle_t h, size_t bytes, char** out) {
 ecgemm_status_t check_sizes(ecgemm_handle_t h, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   // tile indices are 32-bit and the byte offset along K inside a row block is a 32-bit vector offset
   if (M > (int64_t)1 << 36 || N > (int64_t)1 << 36) return fail(h, ECGEMM_ERR_INVALID_ARG, "M or N too large");
+  // work items are counted in 32 bits: at most 2^30 output tiles of 128 x 128 (C would hold 2^44 elements)
+  if (((M + 127) / 128) * ((N + 127) / 128) > ((int64_t)1 << 30)) return fail(h, ECGEMM_ERR_INVALID_ARG, "M x N too large");
   if ((round_up(K, kDepthPad) / 16) * parts_of(mode) * 1024 >= ((int64_t)1 << 32))
     return fail(h, ECGEMM_ERR_INVALID_ARG, "K too large: a packed row block must stay below 4 GiB");
   return ECGEMM_OK;
@@ -490,6 +492,8 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_workspace_size: bad argument");
   *bytes = 0;
   if (M == 0 || N == 0 || K == 0) return ECGEMM_OK;
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode);
+  if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
   *bytes = pl.total_bytes;
@@ -500,6 +504,8 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
                                  ecgemm_plan_info_t* info) {
   if (!info || M <= 0 || N <= 0 || K <= 0 || !valid_mode(mode))
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_plan_info: bad argument (sizes must be positive)");
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode);
+  if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_plan_info: the handle's kernel shape does not exist for this mode");
   info->shape = (int)(pl.shape - &kShapes[(int)mode][0]) + 1;

@@ -91,6 +91,14 @@ def test_plan_of_the_baseline_configs():
     import pytest
     with pytest.raises(ec.EcgemmError):
         ec.plan_info(0, 1, 1, ec.MODE_FP16_SPLIT)
+    # sizes whose tiles could not be counted in 32 bits, or whose packed row block would pass 4 GiB, are refused
+    for bad in [(1 << 23, 1 << 23, 32), (1 << 37, 1, 1), (4, 4, 1 << 26)]:
+        with pytest.raises(ec.EcgemmError) as err:
+            ec.plan_info(*bad, ec.MODE_FP16_SPLIT)
+        assert err.value.status == ec.ERR_INVALID_ARG
+        with pytest.raises(ec.EcgemmError):
+            ec.workspace_size(*bad, ec.MODE_FP16_SPLIT)
+    assert ec.plan_info(1 << 22, 1 << 15, 32, ec.MODE_FP16_SPLIT)["tiles_m"] == 1 << 15     # 2^30 tiles of 128 x 128: still fine
 
 
 def test_workspace_plan_needs_no_gpu():

@@ -706,4 +706,7 @@ def test_sizes_beyond_the_supported_depth_are_refused():
     with pytest.raises(ec.EcgemmError) as ei:       # nothing is read or allocated before the check
         h.sgemm(ec.OP_T, ec.OP_N, 4, 4, 1 << 26, 1.0, dummy, 1 << 26, dummy, 1 << 26, 0.0, dummy, 4, ec.MODE_FP16_SPLIT)
     assert ei.value.status == ec.ERR_INVALID_ARG
+    with pytest.raises(ec.EcgemmError) as ei:       # more output tiles than a 32-bit item count holds
+        h.sgemm(ec.OP_N, ec.OP_N, 1 << 23, 1 << 23, 1, 1.0, dummy, 1 << 23, dummy, 1, 0.0, dummy, 1 << 23, ec.MODE_FP16_SPLIT)
+    assert ei.value.status == ec.ERR_INVALID_ARG
     h.destroy()
