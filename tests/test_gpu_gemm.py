@@ -365,6 +365,16 @@ def test_every_arrangement_of_the_xcds_over_the_tile_grid(case):
     assert np.max(np.abs(got - other)) < 1e-4 * np.sqrt(K / 3.0)     # entries are about sqrt(K / 3) large
 
 
+@pytest.mark.parametrize("case", [("T", "N", 4321, 5700, 16500, "fp16", 4), ("N", "T", 6000, 3333, 9000, "bf16", 2)])
+def test_column_bands_of_unequal_width_with_ragged_edges(case):
+    """Sizes that are multiples of nothing: 17 x 45 and 24 x 27 tiles, bands of 12 + 11 + 11 + 11 and 14 + 13 tile
+    columns, partial tiles on both edges, transposed operands with padded leading dimensions, alpha and beta."""
+    import paper_2203_03341_amd as ec
+    tA, tB, M, N, K, mode, bands = case
+    assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT if mode == "fp16" else ec.MODE_BF16_FULL)["column_bands"] == bands
+    _check(tA, tB, M, N, K, 1.5, 0.5, mode, "urand", seed=13, pad=3, rows=si.sample_indices(M, 40, seed=6))
+
+
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
 def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
     """Every shape adds up the k steps of an element in the same order; only slicing along K changes the bits."""
