@@ -14,7 +14,7 @@
 //
 // Data flow per workgroup (one per CU, 4 waves, one per SIMD, up to 512 registers each, for the
 // 256 x 128 tile; two per CU for the 128 x 128 tile used when K is shallow):
-//   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS ring of 2 to 4 stages (no VGPR staging)
+//   packed operands (HBM/L2) --global_load_lds 16 B/lane--> LDS ring of 2 or 3 stages (no VGPR staging)
 //   LDS --ds_read_b128--> operand fragments, double buffered in registers
 //   v_mfma_f32_32x32x16_{f16,bf16} --> 2 x (TM x TN) accumulators of 16 floats per lane
 // Operands are stored in fragment order (see split_kernels.hpp), so both hops are linear
