@@ -208,8 +208,13 @@ ecgemm_status_t make_split_job(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, 
   job->row_log2_scale = row_log2_scale;
   job->packed = static_cast<unsigned short*>(packed);
   job->variant = k_contiguous ? (vec ? kSplitKContiguousVec : kSplitKContiguous) : (vec ? kSplitRContiguousWide : kSplitRContiguous);
-  job->fast_tiles = (unsigned)(k_contiguous ? Kp / 32 : job->variant == kSplitRContiguousWide ? Rp / 256 : Rp / 64);
-  job->blocks = (unsigned)(job->variant == kSplitRContiguousWide ? blocks64 / 4 : blocks64);
+  // blocks are 64 rows x 32 k, except 256 x 32 (wide) and 64 x 64 (k contiguous, unaligned)
+  switch (job->variant) {
+    case kSplitRContiguousWide: job->fast_tiles = (unsigned)(Rp / 256), job->blocks = (unsigned)(blocks64 / 4); break;
+    case kSplitRContiguous: job->fast_tiles = (unsigned)(Rp / 64), job->blocks = (unsigned)blocks64; break;
+    case kSplitKContiguousVec: job->fast_tiles = (unsigned)(Kp / 32), job->blocks = (unsigned)blocks64; break;
+    default: job->fast_tiles = (unsigned)((Kp + 63) / 64), job->blocks = (unsigned)((Kp + 63) / 64 * (Rp / 64)); break;
+  }
   return ECGEMM_OK;
 }
 

@@ -132,10 +132,11 @@ struct SplitJob {
 };
 enum SplitVariant { kSplitKContiguousVec = 0, kSplitKContiguous = 1, kSplitRContiguous = 2, kSplitRContiguousWide = 3 };
 
-// Source with k contiguous: X(r, k) = src[k + r * ld].  One block: 64 rows x 32 k, 256 threads,
-// thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4).  Blocks are numbered with the k tile fastest.
-template <int KIND, bool VEC>
-__device__ __forceinline__ void split_block_k_contiguous(const SplitJob& job, unsigned block) {
+// Source with k contiguous, X(r, k) = src[k + r * ld], base and leading dimension multiples of 16 bytes.  One block:
+// 64 rows x 32 k, 256 threads, thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4), two 16-byte
+// loads.  Blocks are numbered with the k tile fastest.
+template <int KIND>
+__device__ __forceinline__ void split_block_k_contiguous_vec(const SplitJob& job, unsigned block) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)(block / job.fast_tiles) * 64 + (t >> 2);
   const int64_t k = (int64_t)(block % job.fast_tiles) * 32 + (t & 3) * 8;
@@ -143,7 +144,7 @@ __device__ __forceinline__ void split_block_k_contiguous(const SplitJob& job, un
   if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
   const float* src = job.src;
   float v[8];
-  if (r < job.rows && k + 8 <= job.depth && VEC) {
+  if (r < job.rows && k + 8 <= job.depth) {
     const float4 lo = *reinterpret_cast<const float4*>(src + r * job.ld + k);
     const float4 hi = *reinterpret_cast<const float4*>(src + r * job.ld + k + 4);
     v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
@@ -155,6 +156,37 @@ __device__ __forceinline__ void split_block_k_contiguous(const SplitJob& job, un
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] *= prescale;
   store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k, v);
+}
+
+// Source with k contiguous, any alignment (rows that do not start on 16 bytes: lda = 5003).  One block: 64 rows x
+// 64 k, read with lanes along k, so that a wave instruction fetches one 256-byte run instead of 4 bytes from each of
+// 16 rows, and handed to the row's thread through LDS (`tile`, 64 x 65 floats; the odd stride keeps both the writes
+// and the reads free of bank conflicts).  Blocks are numbered with the k tile fastest.
+template <int KIND>
+__device__ __forceinline__ void split_block_k_contiguous_staged(const SplitJob& job, unsigned block, float* tile) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int64_t r0 = (int64_t)(block / job.fast_tiles) * 64, k0 = (int64_t)(block % job.fast_tiles) * 64;
+  const float* src = job.src;
+  const int64_t k_in = k0 + lane;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int row = 4 * j + wave;
+    const int64_t r = r0 + row;
+    tile[row * 65 + lane] = (r < job.rows && k_in < job.depth) ? src[r * job.ld + k_in] : 0.0f;
+  }
+  __syncthreads();
+  const int64_t r = r0 + (t >> 2);
+  float prescale = job.prescale;
+  if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int k_local = half * 32 + (t & 3) * 8;
+    if (k0 + k_local >= job.k_steps_total * 16) break;  // the padded depth is a multiple of 32, not of 64
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[(t >> 2) * 65 + k_local + e] * prescale;
+    store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k0 + k_local, v);
+  }
 }
 
 // Source with r contiguous: X(r, k) = src[r + k * ld], any alignment.  One block: 64 rows x 32 k.  Lanes run along r,
@@ -210,7 +242,7 @@ __device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& jo
   }
 }
 
-// One operand per launch; VARIANT is fixed at compile time so that only the wide kernel holds LDS.
+// One operand per launch; VARIANT is fixed at compile time so that only the kernels that stage through LDS hold any.
 template <int KIND, int VARIANT>
 __global__ void __launch_bounds__(256) split_kernel(const SplitJob job) {
   if constexpr (VARIANT == kSplitRContiguousWide) {
@@ -218,8 +250,11 @@ __global__ void __launch_bounds__(256) split_kernel(const SplitJob job) {
     split_block_r_contiguous_wide<KIND>(job, blockIdx.x, tile);
   } else if constexpr (VARIANT == kSplitRContiguous) {
     split_block_r_contiguous<KIND>(job, blockIdx.x);
+  } else if constexpr (VARIANT == kSplitKContiguousVec) {
+    split_block_k_contiguous_vec<KIND>(job, blockIdx.x);
   } else {
-    split_block_k_contiguous<KIND, VARIANT == kSplitKContiguousVec>(job, blockIdx.x);
+    __shared__ float tile[64 * 65];
+    split_block_k_contiguous_staged<KIND>(job, blockIdx.x, tile);
   }
 }
 
@@ -234,8 +269,8 @@ __global__ void __launch_bounds__(256) split_pair_kernel(const SplitJob a, const
   switch (job.variant) {
     case kSplitRContiguousWide: split_block_r_contiguous_wide<KIND>(job, block, tile); break;
     case kSplitRContiguous: split_block_r_contiguous<KIND>(job, block); break;
-    case kSplitKContiguousVec: split_block_k_contiguous<KIND, true>(job, block); break;
-    default: split_block_k_contiguous<KIND, false>(job, block); break;
+    case kSplitKContiguousVec: split_block_k_contiguous_vec<KIND>(job, block); break;
+    default: split_block_k_contiguous_staged<KIND>(job, block, tile); break;
   }
 }
 
