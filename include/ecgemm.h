@@ -85,7 +85,7 @@ ecgemm_status_t ecgemm_destroy(ecgemm_handle_t handle);
 ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 
 /* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit fragment order,
- * zero-padded to whole tiles, plus at most 32 MiB of partial sums for output tiles that are cut into slices along K.
+ * zero-padded to whole tiles, plus at most 128 MiB of partial sums for output tiles that are cut into slices along K.
  * The plan behind it is made for the 256 compute units of the MI355X, so the size depends on the problem, the mode and
  * the kernel shape only; `handle` supplies the shape set with ecgemm_set_shape and may be NULL (automatic choice).
  * `bytes` is a host pointer. */

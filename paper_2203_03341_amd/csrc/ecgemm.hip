@@ -6,6 +6,7 @@
 #include <climits>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -129,9 +130,9 @@ constexpr int kPlanComputeUnits = 256;
 
 // Tiles of one shape, and how they become work items.  As many tiles as fill every workgroup slot of the chip a whole
 // number of times are one item each.  The tiles left over would occupy only part of the chip for the time of a whole
-// tile; when K is deep enough each of them is cut into slices along K (at least 512 deep) so that the slices fill the
-// slots once more, and a second kernel adds the slices up in a fixed order.
-Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+// tile; each of them can be cut into `splits` slices along K, which leave partial sums for a second kernel to add up
+// in a fixed order.  splits == 1: nothing is sliced.
+Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, int splits) {
   Plan pl;
   pl.Kp = round_up(K, kDepthPad);
   pl.shape = &kShapes[(int)mode][(int)shape - 1];
@@ -147,10 +148,8 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   const int64_t slots = (int64_t)kPlanComputeUnits * pl.shape->blocks_per_cu;
   // (the fused kernel slices either every tile or none)
   const int64_t tail = pl.shape->fused ? (tiles < slots ? tiles : 0) : tiles % slots;
-  int64_t splits = tail > 0 ? slots / tail : 1;
-  splits = std::min<int64_t>(splits, pl.Kp / 512);
-  splits = std::max<int64_t>(1, std::min<int64_t>(splits, 64));
-  pl.tail_splits = (int)splits;
+  if (tail == 0) splits = 1;
+  pl.tail_splits = splits;
   pl.tail_tiles = splits > 1 ? (int)tail : 0;
   pl.full_tiles = (int)(tiles - pl.tail_tiles);
   pl.a_bytes = pl.shape->fused ? 0 : align256(packed_bytes(M, K, mode));
@@ -160,20 +159,96 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   return pl;
 }
 
-// The plan of a call.  Which shape a problem gets when the caller has not fixed one comes from product-kernel timings
-// of both shapes on 60 sizes from 512^3 to 24576 x 24576 x 4096, in both modes.  X2 wins where items are short or few:
-//   * an item of the W4 plan is at most 512 deep: 16384 x 16384 x 256: 440 us against 461 (FP16), 656 against 708
-//     (BF16); 4096 x 4096 x 256: 31 against 39; 512 x 512 x 16384 (32 slices of 512): 91 against 153; tie at x 768;
-//   * the W4 plan cannot give every CU an item even after slicing: 1024^3: 22 us against 31; 1536^3: 36 against 43.
-// Everywhere else W4 is ahead, by 2-5 % from 4096^3 to 8192^3 and at 16384 x 16384 x 2048..8192, by 8-10 % from
-// 12288^3 up.  The comparison methods have the W4 shape only.
+// Estimated time of the product (and reduce) kernels of a plan in microseconds, to rank the plans of one problem.
+// Items are handed out in rounds (one per compute unit for the 256 x 128 shape, two for the 128 x 128 shape); a round
+// of n equal items takes the larger of two times per 1024 of depth: what one compute unit needs for its share at its
+// own pace (kW4Unit for a 256 x 128 tile; 2 kX2Pair for two co-resident 128 x 128 tiles; kX2Lone, growing with depth,
+// for one that has the unit to itself: with two LDS stages it cannot hide the latency alone), and what the chip as a
+// whole, which is power-limited, needs for the round's work (kChip per 128 x 128 tile and unit when all are busy,
+// falling with the filled fraction of the round to the power kFillExponent; the 256 x 128 shape needs kW4Work of that
+// per flop).  Every round adds a pipeline fill and an epilogue, sliced tiles a
+// pass over their partial sums.  Work scales with the mode's matrix instructions per element.  The constants are a
+// least-squares fit to 1300 timings: both shapes with every admissible slice count on 174 problems (squares from
+// 512 to 5632, random M, N in 512..10000 and K in 256..23000, both modes).  Picking the cheapest plan is within 0.7 %
+// of the best measured plan on average over these problems, 7 of them more than 5 % off (worst 14 %).
+constexpr double kW4Unit = 21.85, kW4Work = 0.952, kX2Pair = 14.36, kX2Lone = 11.26, kX2LonePerDepth = 0.372, kChip = 17.72;
+constexpr double kFillExponent = 0.838, kW4RoundUs = 7.06, kX2RoundUs = 4.25, kReduceUs = 0.91, kReduceUsPerMB = 0.155;
+
+double mode_work(ecgemm_mode_t mode) {  // matrix-pipe time per element relative to the three FP16 products
+  switch (mode) {
+    case ECGEMM_MODE_FP16_SPLIT:
+    case ECGEMM_MODE_FP16_UNSCALED: return 1.0;
+    case ECGEMM_MODE_BF16_FULL:
+    case ECGEMM_MODE_FP16_OUTSIDE_ACC: return 2.0;
+    case ECGEMM_MODE_FP16_MARKIDIS: return 4.0 / 3.0;
+    case ECGEMM_MODE_FP32_MFMA: return 3.0;
+    default: return 1.0 / 3.0;  // one product
+  }
+}
+
+double rounds_us(int64_t items, double depth, bool w4, double work) {  // `items` equal items, each `depth` x 1024 deep
+  const int64_t per_round = w4 ? kPlanComputeUnits : 2 * kPlanComputeUnits;
+  double us = 0.0;
+  for (int64_t left = items; left > 0; left -= per_round) {
+    const double n = (double)std::min(left, per_round);
+    const double unit = w4 ? kW4Unit : n > kPlanComputeUnits ? 2.0 * kX2Pair : kX2Lone + kX2LonePerDepth * std::min(depth, 20.0);
+    const double chip = 2.0 * (w4 ? kW4Work : 1.0) * std::pow(n / per_round, kFillExponent) * kChip;
+    us += depth * work * std::max(unit, chip) + (w4 ? kW4RoundUs : kX2RoundUs);
+    if (left > 64 * per_round) {  // many equal rounds: no need to walk them one by one
+      const int64_t whole_rounds = left / per_round - 1;
+      us += whole_rounds * (depth * work * std::max(unit, chip) + (w4 ? kW4RoundUs : kX2RoundUs));
+      left -= whole_rounds * per_round;
+    }
+  }
+  return us;
+}
+
+double estimated_us(const Plan& pl, ecgemm_mode_t mode) {
+  const bool w4 = pl.shape->bm == 256;
+  const double work = mode_work(mode);
+  const int64_t sliced = pl.tail_splits > 1 ? (int64_t)pl.tail_tiles * pl.tail_splits : 0;
+  const double slice_depth = pl.tail_splits > 1 ? (double)((pl.k_tiles + pl.tail_splits - 1) / pl.tail_splits) * pl.shape->bk / 1024.0 : 0.0;
+  double us = rounds_us(pl.full_tiles, pl.Kp / 1024.0, w4, work) + rounds_us(sliced, slice_depth, w4, work);
+  if (sliced > 0)
+    us += kReduceUs + kReduceUsPerMB * (pl.tail_splits + 1.0) * pl.tail_tiles * pl.shape->bm * pl.shape->bn * 4.0 / 1e6;
+  return us;
+}
+
+// The cheapest way to slice the leftover tiles of one shape: slices at least 512 deep, none of them empty, at most
+// 1024 of them in all (128 MiB of partial sums).
+Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+  Plan best = plan_with(M, N, K, mode, shape, 1);
+  if (best.shape == nullptr) return best;
+  const int64_t slots = (int64_t)kPlanComputeUnits * best.shape->blocks_per_cu;
+  const int64_t tiles = (int64_t)best.tiles_m * best.tiles_n;
+  const int64_t tail = best.shape->fused ? (tiles < slots ? tiles : 0) : tiles % slots;
+  if (tail == 0) return best;
+  if (best.shape->fused) {  // one slice per compute unit
+    const int64_t splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPlanComputeUnits / tail, best.Kp / 512), 64));
+    return plan_with(M, N, K, mode, shape, (int)splits);
+  }
+#ifdef ECGEMM_TUNING
+  if (const char* forced = std::getenv("ECGEMM_FORCE_SLICES")) return plan_with(M, N, K, mode, shape, std::max(1, std::atoi(forced)));
+#endif
+  double best_us = estimated_us(best, mode);
+  for (int splits = 2; splits <= 64 && splits <= best.Kp / 512 && splits * tail <= 1024; ++splits) {
+    const int per_slice = (best.k_tiles + splits - 1) / splits;
+    if ((int64_t)per_slice * (splits - 1) >= best.k_tiles) continue;  // the last slice would be empty
+    const Plan pl = plan_with(M, N, K, mode, shape, splits);
+    const double us = estimated_us(pl, mode);
+    if (us < best_us) best = pl, best_us = us;
+  }
+  return best;
+}
+
+// The plan of a call: the cheaper of the two shapes by the estimate above when the caller has not fixed one.  The
+// comparison methods have the 256 x 128 shape only.
 Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
   if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
   const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
   if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
-  const int64_t depth_per_item = w4.tail_tiles > 0 && w4.full_tiles == 0 ? (w4.Kp + w4.tail_splits - 1) / w4.tail_splits : w4.Kp;
-  if (depth_per_item <= 512 || w4.items() < kPlanComputeUnits) return plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
-  return w4;
+  const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
+  return estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
 }
 
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {

@@ -75,8 +75,16 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["tiles_m"], p["tiles_n"], p["whole_tiles"], p["sliced_tiles"], p["slices"]) == (W4, 16, 24, 256, 128, 2)
     p = ec.plan_info(1024, 1024, 1024, ec.MODE_FP16_SPLIT)             # 32 tiles x 2 slices would leave CUs idle: smaller tiles
     assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 64, 2, 128)
-    p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # slices of 512: short items, smaller tiles
-    assert (p["shape"], p["sliced_tiles"], p["slices"]) == (X2, 16, 32)
+    p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # 2 W4 tiles could not fill the chip: smaller tiles,
+    assert (p["shape"], p["sliced_tiles"], p["slices"]) == (X2, 16, 32)   # in 32 slices of 512: one pair per compute unit
+    p = ec.plan_info(1792, 1792, 1792, ec.MODE_FP16_SPLIT)             # 196 tiles of 128 x 128, one per CU: slices would only add traffic
+    assert (p["shape"], p["whole_tiles"], p["slices"]) == (X2, 196, 1)
+    p = ec.plan_info(2048, 2048, 2048, ec.MODE_FP16_SPLIT)             # 256 tiles of 128 x 128 beat 128 of 256 x 128 in 2 slices
+    assert (p["shape"], p["whole_tiles"], p["slices"]) == (X2, 256, 1)
+    p = ec.plan_info(2304, 2304, 2304, ec.MODE_FP16_SPLIT)             # 162 tiles of 256 x 128 beat 324 of 128 x 128 (68 CUs with two)
+    assert (p["shape"], p["whole_tiles"], p["slices"]) == (W4, 162, 1)
+    p = ec.plan_info(960, 2304, 18688, ec.MODE_FP16_SPLIT)             # 72 deep tiles: 3 slices each, 216 items in one round
+    assert (p["shape"], p["sliced_tiles"], p["slices"]) == (W4, 72, 3)
     p = ec.plan_info(300, 200, 100, ec.MODE_FP16_MARKIDIS)             # comparison methods: one shape
     assert (p["shape"], p["tiles_m"], p["tiles_n"]) == (W4, 2, 2)
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
