@@ -48,7 +48,7 @@ namespace {
 // (A 256 x 128 shape with 8 waves of 64 x 64, two per SIMD, was also built and timed on 60 sizes: never more than
 // 2 % ahead of W4, usually 1 % behind.)
 typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
-typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 2, 2, 2> Fp16X2;      // 2 x 32 KiB of LDS per block
+typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 1, 4, 2> Fp16X2;      // 4 x 16 KiB of LDS per block
 typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 2, 2, 1> Bf16W4;      // 2 x 72 KiB (1 % ahead of 4 x 36 KiB)
 typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
 // comparison methods: the W4 shape only
@@ -163,16 +163,16 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
 // Items are handed out in rounds (one per compute unit for the 256 x 128 shape, two for the 128 x 128 shape); a round
 // of n equal items takes the larger of two times per 1024 of depth: what one compute unit needs for its share at its
 // own pace (kW4Unit for a 256 x 128 tile; 2 kX2Pair for two co-resident 128 x 128 tiles; kX2Lone, growing with depth,
-// for one that has the unit to itself: with two LDS stages it cannot hide the latency alone), and what the chip as a
+// for one that has the unit to itself: it cannot hide all of the latency alone), and what the chip as a
 // whole, which is power-limited, needs for the round's work (kChip per 128 x 128 tile and unit when all are busy,
 // falling with the filled fraction of the round to the power kFillExponent; the 256 x 128 shape needs kW4Work of that
 // per flop).  Every round adds a pipeline fill and an epilogue, sliced tiles a
 // pass over their partial sums.  Work scales with the mode's matrix instructions per element.  The constants are a
 // least-squares fit to 1300 timings: both shapes with every admissible slice count on 174 problems (squares from
-// 512 to 5632, random M, N in 512..10000 and K in 256..23000, both modes).  Picking the cheapest plan is within 0.7 %
-// of the best measured plan on average over these problems, 7 of them more than 5 % off (worst 14 %).
-constexpr double kW4Unit = 21.85, kW4Work = 0.952, kX2Pair = 14.36, kX2Lone = 11.26, kX2LonePerDepth = 0.372, kChip = 17.72;
-constexpr double kFillExponent = 0.838, kW4RoundUs = 7.06, kX2RoundUs = 4.25, kReduceUs = 0.91, kReduceUsPerMB = 0.155;
+// 512 to 5632, random M, N in 512..10000 and K in 256..23000, both modes).  Picking the cheapest plan is within 0.6 %
+// of the best measured plan on average over these problems, 3 of them more than 5 % off (worst 11 %).
+constexpr double kW4Unit = 22.03, kW4Work = 0.954, kX2Pair = 14.74, kX2Lone = 10.08, kX2LonePerDepth = 0.277, kChip = 17.46;
+constexpr double kFillExponent = 0.906, kW4RoundUs = 7.88, kX2RoundUs = 4.70, kReduceUs = 1.01, kReduceUsPerMB = 0.142;
 
 double mode_work(ecgemm_mode_t mode) {  // matrix-pipe time per element relative to the three FP16 products
   switch (mode) {

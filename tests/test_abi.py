@@ -76,7 +76,7 @@ def test_plan_of_the_baseline_configs():
     p = ec.plan_info(1024, 1024, 1024, ec.MODE_FP16_SPLIT)             # 32 tiles x 2 slices would leave CUs idle: smaller tiles
     assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 64, 2, 128)
     p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # 2 W4 tiles could not fill the chip: smaller tiles,
-    assert (p["shape"], p["sliced_tiles"], p["slices"]) == (X2, 16, 32)   # in 32 slices of 512: one pair per compute unit
+    assert (p["shape"], p["sliced_tiles"]) == (X2, 16) and 16 <= p["slices"] <= 32   # one or two slices per compute unit
     p = ec.plan_info(1792, 1792, 1792, ec.MODE_FP16_SPLIT)             # 196 tiles of 128 x 128, one per CU: slices would only add traffic
     assert (p["shape"], p["whole_tiles"], p["slices"]) == (X2, 196, 1)
     p = ec.plan_info(2048, 2048, 2048, ec.MODE_FP16_SPLIT)             # 256 tiles of 128 x 128 beat 128 of 256 x 128 in 2 slices
