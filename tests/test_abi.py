@@ -109,6 +109,38 @@ def test_plan_of_the_baseline_configs():
     assert ec.plan_info(1 << 22, 1 << 15, 32, ec.MODE_FP16_SPLIT)["tiles_m"] == 1 << 15     # 2^30 tiles of 128 x 128: still fine
 
 
+def test_plans_of_random_problems_are_well_formed():
+    """Host logic: whatever the cost estimate picks, every tile is accounted for once, slices are at least 512 deep
+    and none is empty, there are at most 1024 of them, and the workspace holds the packed operands and the partial sums."""
+    import random
+    import paper_2203_03341_amd as ec
+    rng = random.Random(7)
+    for trial in range(400):
+        M = int(2 ** rng.uniform(0, 15.5)) + rng.choice([0, 0, 1, 7])
+        N = int(2 ** rng.uniform(0, 15.5)) + rng.choice([0, 0, 3])
+        K = int(2 ** rng.uniform(0, 17.5)) + rng.choice([0, 0, 5])
+        mode = rng.choice([ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL, ec.MODE_FP16_MARKIDIS, ec.MODE_FP32_MFMA])
+        p = ec.plan_info(M, N, K, mode)
+        case = (M, N, K, mode, p)
+        assert p["tiles_m"] == -(-M // p["tile_m"]) and p["tiles_n"] == -(-N // p["tile_n"]), case
+        assert p["whole_tiles"] + p["sliced_tiles"] == p["tiles_m"] * p["tiles_n"], case
+        assert (p["slices"] == 1) == (p["sliced_tiles"] == 0), case
+        assert 1 <= p["column_bands"] <= max(1, p["tiles_n"]) and p["group_m"] in (4, 8), case
+        Kp = -(-K // 32) * 32
+        parts = {ec.MODE_FP16_SPLIT: 2, ec.MODE_BF16_FULL: 3, ec.MODE_FP16_MARKIDIS: 2, ec.MODE_FP32_MFMA: 2}[mode]
+        packed = (-(-M // 256) * 256 + -(-N // 256) * 256) * Kp * 2 * parts
+        partial = p["slices"] * p["sliced_tiles"] * p["tile_m"] * p["tile_n"] * 4 if p["slices"] > 1 else 0
+        assert packed + partial <= p["workspace_bytes"] <= packed + partial + 3 * 256, case
+        if p["slices"] > 1:
+            slots = 256 * (2 if p["tile_m"] == 128 else 1)
+            assert p["sliced_tiles"] == (p["tiles_m"] * p["tiles_n"]) % slots, case      # only the leftover tiles are sliced
+            assert p["slices"] <= min(64, Kp // 512) and p["slices"] * p["sliced_tiles"] <= 1024, case
+            stage = 16 if p["tile_m"] == 128 else 32                                        # depth of an LDS stage
+            stages = Kp // stage
+            per_slice = -(-stages // p["slices"])
+            assert per_slice * (p["slices"] - 1) < stages, case                            # the last slice is not empty
+
+
 def test_workspace_plan_needs_no_gpu():
     """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and the output
     tiles left over after whole rounds of the chip's 256 CUs cut into slices along K (one partial tile per slice)."""
