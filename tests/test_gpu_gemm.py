@@ -375,6 +375,23 @@ def test_column_bands_of_unequal_width_with_ragged_edges(case):
     _check(tA, tB, M, N, K, 1.5, 0.5, mode, "urand", seed=13, pad=3, rows=si.sample_indices(M, 40, seed=6))
 
 
+@pytest.mark.parametrize("case", [(960, 2304, 18688, "fp16"), (512, 512, 16384, "bf16"), (3000, 3000, 1100, "fp16"),
+                                  (640, 832, 9509, "bf16")])
+def test_slice_counts_picked_by_the_cost_estimate(case):
+    """Plans whose leftover tiles are cut into 3, 27, 2 and a dozen slices (whatever the estimate finds cheapest): the
+    slices must cover the depth exactly once, ragged last slice included, and the fixed-order sum must give the same
+    bits on every run."""
+    import paper_2203_03341_amd as ec
+    M, N, K, mode = case
+    p = ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT if mode == "fp16" else ec.MODE_BF16_FULL)
+    assert p["slices"] > 1 and p["sliced_tiles"] > 0
+    _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=17, rows=si.sample_indices(M, 32, seed=8))
+    A, B = _inputs(M, N, K, "N", "N", "urand", 17)
+    first = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)
+    again = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)
+    assert np.array_equal(first.view(np.uint32), again.view(np.uint32))
+
+
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
 def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
     """Every shape adds up the k steps of an element in the same order; only slicing along K changes the bits."""
