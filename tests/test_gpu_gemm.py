@@ -194,6 +194,25 @@ def test_degenerate_cases(mode):
     h.destroy()
 
 
+@pytest.mark.parametrize("mode", ["fp16", "bf16", "fp32"])
+def test_non_finite_inputs_stay_in_their_rows_and_columns(mode):
+    """A NaN in A poisons its row of C, an infinity in B its column, and nothing else: exactly the entries that are not
+    finite in the FP64 product.  (Whether an entry comes out as an infinity or as NaN is not promised: the parts of an
+    infinity are an infinity and zero, and a correction product may turn the sum into NaN.)"""
+    M, N, K = 300, 200, 150
+    A, B = _inputs(M, N, K, "N", "N", "urand", 31)
+    A, B = A.copy(order="F"), B.copy(order="F")
+    A[3, 5] = np.nan            # A is M x K (column-major storage as a (ld, cols) array indexed [row, col])
+    B[7, 2] = np.inf            # B is K x N
+    got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)[:M, :N]
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = A.astype(np.float64) @ B.astype(np.float64)
+    assert np.array_equal(np.isfinite(got), np.isfinite(ref))
+    assert np.all(np.isnan(got[3, :])) and not np.any(np.isfinite(got[:, 2]))
+    finite = np.isfinite(ref)
+    assert np.max(np.abs(got[finite] - ref[finite])) < 1e-4
+
+
 def test_invalid_arguments_are_rejected():
     import paper_2203_03341_amd as ec
     h = ec.Handle()
