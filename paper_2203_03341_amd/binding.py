@@ -42,6 +42,13 @@ def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                           "(there is no fallback path)")
+    # PyTorch ships its own copy of the HIP runtime.  If this library were loaded first it would pull in the system's
+    # copy, torch would then find a second runtime in the process and report no GPU: let torch load its copy first
+    # (the library then binds to the one already there).
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     i64, f32, vp, sz = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
     lib.ecgemm_create.argtypes = [ctypes.POINTER(vp)]

@@ -171,6 +171,8 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
 // least-squares fit to 1300 timings: both shapes with every admissible slice count on 174 problems (squares from
 // 512 to 5632, random M, N in 512..10000 and K in 256..23000, both modes).  Picking the cheapest plan is within 0.6 %
 // of the best measured plan on average over these problems, 3 of them more than 5 % off (worst 11 %).
+// calibrate_plans.py beside this library takes the timings (with a build whose slice count can be forced, below) and
+// refits the constants.
 constexpr double kW4Unit = 22.03, kW4Work = 0.954, kX2Pair = 14.74, kX2Lone = 10.08, kX2LonePerDepth = 0.277, kChip = 17.46;
 constexpr double kFillExponent = 0.906, kW4RoundUs = 7.88, kX2RoundUs = 4.70, kReduceUs = 1.01, kReduceUsPerMB = 0.142;
 

@@ -194,6 +194,19 @@ def test_degenerate_cases(mode):
     h.destroy()
 
 
+def test_importing_the_package_before_torch_leaves_the_gpu_usable():
+    """PyTorch ships its own HIP runtime; the binding must not bring the system's copy into the process ahead of it
+    (torch then reports no GPU).  Checked in a fresh interpreter, package first."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import paper_2203_03341_amd as ec, torch; assert torch.cuda.is_available(); "
+            "h = ec.Handle(); x = torch.ones(4, device='cuda'); torch.cuda.synchronize(); h.destroy(); print('ok')")
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and "ok" in res.stdout, res.stderr[-2000:]
+
+
 @pytest.mark.parametrize("mode", ["fp16", "bf16", "fp32"])
 def test_non_finite_inputs_stay_in_their_rows_and_columns(mode):
     """A NaN in A poisons its row of C, an infinity in B its column, and nothing else: exactly the entries that are not
