@@ -397,6 +397,19 @@ def test_every_arrangement_of_the_xcds_over_the_tile_grid(case):
     assert np.max(np.abs(got - other)) < 1e-4 * np.sqrt(K / 3.0)     # entries are about sqrt(K / 3) large
 
 
+def test_column_bands_under_a_persistent_grid():
+    """K <= 4096 runs as one workgroup per CU walking through its XCD's list; with BF16 panels of 24 MiB that list is
+    laid out in two column bands."""
+    import paper_2203_03341_amd as ec
+    p = ec.plan_info(8192, 8192, 4096, ec.MODE_BF16_FULL)
+    assert (p["persistent"], p["column_bands"]) == (1, 2)
+    _check("N", "N", 8192, 8192, 4096, 1.0, 0.0, "bf16", "urand", seed=23, rows=si.sample_indices(8192, 32, seed=9))
+    A, B = _inputs(8192, 8192, 4096, "N", "N", "urand", 23)
+    got = _gpu_sgemm("N", "N", 8192, 8192, 4096, 1.0, A, B, 0.0, None, "bf16")[:8192, :8192]
+    other = _gpu_sgemm("N", "N", 8192, 8192, 4096, 1.0, A, B, 0.0, None, "fp16")[:8192, :8192]
+    assert np.max(np.abs(got - other)) < 1e-4 * np.sqrt(4096 / 3.0)
+
+
 @pytest.mark.parametrize("case", [("T", "N", 4321, 5700, 16500, "fp16", 4), ("N", "T", 6000, 3333, 9000, "bf16", 2)])
 def test_column_bands_of_unequal_width_with_ragged_edges(case):
     """Sizes that are multiples of nothing: 17 x 45 and 24 x 27 tiles, bands of 12 + 11 + 11 + 11 and 14 + 13 tile
