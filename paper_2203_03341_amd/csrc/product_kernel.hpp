@@ -422,7 +422,8 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
       });
       // (the reads stop ECGEMM_READ_TAIL slots before the end of the step, so that the last of them has arrived
       // when the wave gets to the wait in front of the barrier or of the next step)
-      constexpr int SPAN = M > 2 * ECGEMM_READ_TAIL ? M - ECGEMM_READ_TAIL : M;
+      // (two slots in a step of twelve instructions or fewer, the 128 x 128 FP16 shape: 1 to 2 %)
+      constexpr int SPAN = M > 2 * ECGEMM_READ_TAIL ? M - ECGEMM_READ_TAIL : M > 4 ? M - 2 : M;
       constexpr int r_begin = m < SPAN ? m * READS / SPAN : READS, r_end = m + 1 < SPAN ? (m + 1) * READS / SPAN : READS;
       static_for<r_end - r_begin>([&](auto d_c) {
         constexpr int r = r_begin + decltype(d_c)::value;
