@@ -18,6 +18,35 @@ def test_header_declares_the_north_star_entry_points():
         assert required in names
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: a C99 program that includes the header, calls the entry points that need no GPU and
+    links against the shared library must build with gcc and run."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        import pytest
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.join(root, "paper_2203_03341_amd")
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "ecgemm.h"\n'
+        "int main(void) {\n"
+        "  size_t bytes = 0; ecgemm_plan_info_t info;\n"
+        "  if (ecgemm_workspace_size(NULL, 4096, 4096, 4096, ECGEMM_MODE_FP16_SPLIT, &bytes) != ECGEMM_OK) return 1;\n"
+        "  if (ecgemm_plan_info(NULL, 4096, 4096, 4096, ECGEMM_MODE_BF16_FULL, &info) != ECGEMM_OK) return 2;\n"
+        "  if (ecgemm_plan_info(NULL, 0, 1, 1, ECGEMM_MODE_BF16_FULL, &info) != ECGEMM_ERR_INVALID_ARG) return 3;\n"
+        '  printf("%zu %d %s\\n", bytes, info.tile_m, ecgemm_status_string(ECGEMM_ERR_UNSUPPORTED));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "use_header"
+    build = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src),
+                            "-L", lib_dir, "-lecgemm", "-Wl,-rpath," + lib_dir, "-o", str(exe)], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0, (run.returncode, run.stderr)
+    assert run.stdout.split() == [str(2 * 4096 * 4096 * 4), "256", "ECGEMM_ERR_UNSUPPORTED"]
+
+
 def test_library_exports_every_declared_symbol():
     from paper_2203_03341_amd import binding
     lib = ctypes.CDLL(binding.LIB_PATH)
