@@ -497,14 +497,15 @@ def test_fp16_mode_fails_outside_its_range_like_the_paper_says():
 
 # ----- the baseline's own sizes, in the launch configuration bench.py times; oracle on seeded sample rows of C
 
-def _full_size(M, N, K, transA, transB, alpha, beta, mode, dist, nrows):
-    rows = si.sample_indices(M, nrows, seed=11)
-    return _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=0, rows=rows)
+def _full_size(M, N, K, transA, transB, alpha, beta, mode, dist, nrows, seed=0):
+    rows = si.sample_indices(M, nrows, seed=11 + seed)
+    return _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=seed, rows=rows)
 
 
+@pytest.mark.parametrize("seed", [0, 1, 2])
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-def test_config2_4096_cubed(mode):
-    _full_size(4096, 4096, 4096, "N", "N", 1.0, 0.0, mode, "urand", 256)
+def test_config2_4096_cubed(mode, seed):
+    _full_size(4096, 4096, 4096, "N", "N", 1.0, 0.0, mode, "urand", 256, seed=seed)
 
 
 def test_config3_16384_cubed_fp16_limited_exponent():
