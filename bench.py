@@ -54,6 +54,10 @@ WORKLOADS = {
     "c5_odd_transA_bf16": (4095, 3001, 5003, "T", "N", "bf16", 1.0, 0.0, "urand", 1024),
     # not a baseline config: the size at which the one-kernel (fused) shape is compared with the split-first path
     "x_1024_fp16_urand": (1024, 1024, 1024, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    # not baseline configs either: the method with the leading product accumulated outside the matrix unit, as the
+    # paper's listing does against round-toward-zero, next to the default (inside) at the same size
+    "x_8192_fp16_urand": (8192, 8192, 8192, "N", "N", "fp16", 1.0, 0.0, "urand", 256),
+    "x_8192_fp16_outside_urand": (8192, 8192, 8192, "N", "N", "fp16_outside", 1.0, 0.0, "urand", 256),
 }
 DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
 
@@ -115,8 +119,8 @@ def main():
         args.warmup = int(min(500, max(3, np.ceil(50.0 / expected_ms))))
     if args.steps is None:
         args.steps = int(min(1000, max(20, np.ceil(100.0 / expected_ms))))
-    parts_products = {"fp16": 3, "bf16": 6}[mode]
-    mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL}[mode]
+    parts_products = {"fp16": 3, "bf16": 6, "fp16_outside": 3}[mode]
+    mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "fp16_outside": ec.MODE_FP16_OUTSIDE_ACC}[mode]
     ops = {"N": ec.OP_N, "T": ec.OP_T}
 
     t0 = time.time()
@@ -170,7 +174,7 @@ def main():
     product_ms_avg = product_ms / calls
     mfma_tflops = parts_products * flops / (product_ms_avg * 1e-3) / 1e12
     pad = lambda v, m: -(-v // m) * m
-    bytes_per_element = {"fp16": 4, "bf16": 6}[mode]
+    bytes_per_element = {"fp16": 4, "bf16": 6, "fp16_outside": 4}[mode]
     product_bytes = (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bytes_per_element + M * N * 4 * (2 if beta != 0 else 1)
     split_bytes = (M + N) * K * 4 + (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bytes_per_element
 
@@ -284,7 +288,7 @@ def main():
     result = {
         "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16" if mode == "fp16" else "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16" if mode == "bf16" else "f16", "data": "synthetic",
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": transA, "transB": transB,
                    "mode": mode, "alpha": alpha, "beta": beta, "products": parts_products,
                    "inputs": "urand(-1,1)" if dist == "urand" else f"exp_rand{dist[0]} x exp_rand{dist[1]}", "seed": args.seed,
