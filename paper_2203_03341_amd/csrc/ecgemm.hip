@@ -245,12 +245,33 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 
 // The plan of a call: the cheaper of the two shapes by the estimate above when the caller has not fixed one.  The
 // comparison methods have the 256 x 128 shape only.
-Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
   if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
   const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
   if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
   const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
   return estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
+}
+
+// A plan is a pure function of its arguments, and loops call the library with the same ones over and over: the last
+// plan of each thread is kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to a
+// 12 us call).
+Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+#ifdef ECGEMM_TUNING
+  return choose_plan(M, N, K, mode, shape);  // the forced slice count is not part of the key
+#else
+  struct Key {
+    int64_t M, N, K;
+    int mode, shape;
+  };
+  thread_local Key last = {-1, -1, -1, -1, -1};
+  thread_local Plan plan;
+  if (last.M != M || last.N != N || last.K != K || last.mode != (int)mode || last.shape != (int)shape) {
+    plan = choose_plan(M, N, K, mode, shape);
+    last = Key{M, N, K, (int)mode, (int)shape};
+  }
+  return plan;
+#endif
 }
 
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {
