@@ -397,6 +397,18 @@ def test_every_arrangement_of_the_xcds_over_the_tile_grid(case):
     assert np.max(np.abs(got - other)) < 1e-4 * np.sqrt(K / 3.0)     # entries are about sqrt(K / 3) large
 
 
+def test_deep_k_in_one_item_keeps_fp32_accuracy():
+    """693 tiles over a depth of 32279 with no slices: every element is one FP32 accumulator over 2018 matrix
+    instructions.  The rounding of that accumulator is what is left of the error; it must stay under the naive FP32
+    product's (measured: 0.35 of it)."""
+    import paper_2203_03341_amd as ec
+    M, N, K = 2235, 9758, 32279
+    assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["slices"] == 1
+    for mode in ("fp16", "bf16"):
+        r_gpu, r_cpu = _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=29, pad=1, rows=si.sample_indices(M, 24, seed=3))
+        assert r_gpu < 0.6 * r_cpu
+
+
 def test_column_bands_under_a_persistent_grid():
     """K <= 4096 runs as one workgroup per CU walking through its XCD's list; with BF16 panels of 24 MiB that list is
     laid out in two column bands."""
