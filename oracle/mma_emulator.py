@@ -48,7 +48,8 @@ def mma_rz(A, B, C):
 
 
 def gemm_blocked(A, B, mma_fn, block_k: int = 8) -> np.ndarray:
-    """A B computed as a chain of multiply-accumulates over k blocks, the accumulator fed back through C."""
+    """A B computed as a chain of multiply-accumulates over k blocks of `block_k` (the last one may be shorter),
+    k ascending, the FP32 accumulator fed back through C: what a kernel built on such an instruction does."""
     acc = np.zeros((A.shape[0], B.shape[1]), dtype=np.float32)
     for k0 in range(0, A.shape[1], block_k):
         acc = mma_fn(A[:, k0:k0 + block_k], B[k0:k0 + block_k, :], acc)

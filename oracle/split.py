@@ -18,7 +18,10 @@ with round to nearest even; 8 + 8 + 8 significand bits cover FP32's 24.
 Readings where the paper is silent (the HIP kernel follows the same ones):
   * saturation: a finite input never produces an infinite part.  toFP16 / toBF16 results
     that would round to +-Inf are replaced by the largest finite value of the format
-    (65504 for FP16); the residual then carries the remainder.
+    (65504 for FP16); the residual then carries the remainder.  The scaled residual
+    saturates too: a residual beyond +-32 (whose 2^11-fold is beyond FP16 anyway) is cut
+    to +-32 before the multiplication, so that the multiplication itself cannot overflow
+    FP32 for inputs of magnitude 2^117 and more.
   * Inf input: the high part is +-Inf and every lower part is 0.  NaN: all parts NaN.
 """
 from __future__ import annotations
@@ -65,7 +68,7 @@ def split_fp16(x: np.ndarray, scaled: bool = True, rounding: str = "rn"):
     with np.errstate(invalid="ignore", over="ignore"):
         residual = x - v16.astype(np.float32)
         if scaled:
-            residual = residual * RESIDUAL_SCALE
+            residual = np.clip(residual, np.float32(-32.0), np.float32(32.0)) * RESIDUAL_SCALE   # NaN stays NaN
         dv16 = conv(residual)
     dv16 = np.where(np.isinf(v16), np.float16(0.0), dv16).astype(np.float16)
     return v16, dv16

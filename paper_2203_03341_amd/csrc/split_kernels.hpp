@@ -64,7 +64,9 @@ struct Splitter {
       out[0] = __builtin_bit_cast(unsigned short, hi);
       if constexpr (kParts == 2) {
         float residual = v - (float)hi;                                  // exact
-        if constexpr (KIND == kSplitFp16Scaled) residual *= 2048.0f;     // exact
+        // exact; a residual beyond +-32 saturates the low part anyway, and cutting it there first keeps the
+        // multiplication from overflowing FP32 for inputs of magnitude 2^117 and more
+        if constexpr (KIND == kSplitFp16Scaled) residual = saturate_finite(residual, 32.0f) * 2048.0f;
         const _Float16 lo = (_Float16)saturate_finite(residual, 65504.0f);
         // an infinite input keeps only its high part (selected on the bits: no branch around the conversion)
         const unsigned short keep = (__builtin_bit_cast(unsigned short, hi) & 0x7fffu) == 0x7c00u ? 0u : 0xffffu;

@@ -85,7 +85,8 @@ def test_split_edge_values(mode_bf16):
     """Saturation, signed zeros, values that only the scaled residual can hold, FP32 subnormals, Inf, NaN."""
     vals = [0.0, -0.0, 65504.0, 65519.996, 65520.0, 65535.996, -65535.996, 2.0 ** -24, 2.0 ** -25, 2.0 ** -35,
             2.0 ** -36, 1.5 * 2.0 ** -36, 1e-45, -1e-40, 2.0 ** -126, 3.4028234e38, -3.4028234e38, 3.39e38,
-            np.inf, -np.inf, 1.0, -1.0, 0.1, 2.0 ** -14, 2.0 ** -15, 1.9999999 * 2.0 ** -15, 6.1e-5, 100000.0, 1e30]
+            np.inf, -np.inf, 1.0, -1.0, 0.1, 2.0 ** -14, 2.0 ** -15, 1.9999999 * 2.0 ** -15, 6.1e-5, 100000.0, 1e30,
+            2.0 ** 116, 2.0 ** 117, -2.0 ** 117, 1e36, -1e38]
     vals = np.array(vals, dtype=np.float32)
     rows, depth = 8, vals.size
     store = np.asfortranarray(np.tile(vals, (rows, 1)) * np.array([[1], [-1], [1], [-1], [1], [-1], [1], [-1]], np.float32))
@@ -95,17 +96,22 @@ def test_split_edge_values(mode_bf16):
         got = _run(op, st, rows, depth, mode_bf16)
         want = _expected(op, st, rows, depth, mode_bf16)
         assert np.array_equal(got, want), np.flatnonzero(got != want)[:10]
-    # NaN: every part is a NaN (payload bits are not compared)
-    nan_store = np.full((4, 4), np.nan, dtype=np.float32, order="F")
-    got = _run("N", nan_store, 4, 4, mode_bf16)
-    nparts = 3 if mode_bf16 else 2
-    first = got.reshape(-1, nparts, 64, 8)[0]
-    for p in range(nparts):
-        bits = first[p, 0, 0]
+    # NaN among ordinary values: where the oracle's parts are NaN the kernel's are (payload bits are not compared), and
+    # every other position agrees bit for bit
+    mixed = np.asfortranarray(np.tile(np.array([1.0, np.nan, -0.1, 65536.0, np.nan, 3.0e-5, -np.nan, 7.0], np.float32), (6, 1)))
+    mixed[2, :] = np.nan
+    for op in ("N", "T"):
+        st = mixed if op == "N" else np.asfortranarray(mixed.T)
+        got = _run(op, st, 6, 8, mode_bf16)
+        want = _expected(op, st, 6, 8, mode_bf16)
         if mode_bf16:
-            assert (bits & 0x7F80) == 0x7F80 and (bits & 0x7F) != 0
+            nan_of = lambda bits: ((bits & 0x7F80) == 0x7F80) & ((bits & 0x7F) != 0)
         else:
-            assert (bits & 0x7C00) == 0x7C00 and (bits & 0x3FF) != 0
+            nan_of = lambda bits: ((bits & 0x7C00) == 0x7C00) & ((bits & 0x3FF) != 0)
+        want_nan = nan_of(want)
+        assert want_nan.sum() == (3 if mode_bf16 else 2) * int(np.isnan(mixed).sum())
+        assert np.array_equal(nan_of(got), want_nan)
+        assert np.array_equal(got[~want_nan], want[~want_nan])
 
 
 @pytest.mark.parametrize("mode", ["unscaled", "markidis", "plain16", "plainbf", "fp32"])

@@ -203,6 +203,31 @@ def test_split_edge_values():
     parts = split.split_bf16x3(big)
     assert np.all(np.isfinite(split.bf16_triple_value(*parts)))
     assert np.all(np.abs(split.bf16_triple_value(*parts) - big) <= np.abs(big) * 2.0 ** -22)
+    # far outside the FP16 window both parts saturate; in particular the 2^11-fold of the residual, which would
+    # overflow FP32 from 2^117 upward, does not turn into an infinity (an infinite part times a zero of the other
+    # operand would put a NaN where the FP32 product is finite)
+    huge = np.array([2.0 ** 116, 2.0 ** 117, -2.0 ** 117, 1e36, -1e38, np.finfo(np.float32).max, 100000.0, -1e30],
+                    dtype=np.float32)
+    v16, dv16 = split.split_fp16(huge)
+    assert np.array_equal(v16, np.copysign(np.float16(65504), huge).astype(np.float16))
+    assert np.array_equal(dv16, np.copysign(np.float16(65504), huge).astype(np.float16))
+    v16, dv16 = split.split_fp16(huge, scaled=False)
+    assert np.all(np.isfinite(v16)) and np.all(np.isfinite(dv16))
+
+
+def test_split_of_nan_is_nan_in_every_part():
+    """Reading for non-numbers: a NaN input gives a NaN in every part of either split (so that whichever products are
+    kept, the NaN reaches C); an infinity keeps only its high part (pinned in test_split_edge_values)."""
+    x = np.array([np.nan, -np.nan, 1.0, np.float32(np.nan)], dtype=np.float32)
+    x[3] = np.array([0x7F800001], dtype=np.uint32).view(np.float32)[0]      # a signalling pattern
+    is_nan = np.array([True, True, False, True])
+    for scaled in (True, False):
+        v16, dv16 = split.split_fp16(x, scaled=scaled)
+        assert np.array_equal(np.isnan(v16), is_nan) and np.array_equal(np.isnan(dv16), is_nan)
+    for part in split.split_bf16x3(x):
+        assert np.array_equal(np.isnan(split.bf16_bits_to_fp32(part)), is_nan)
+    assert np.isnan(split.fp16_pair_value(*split.split_fp16(x)))[is_nan].all()
+    assert np.isnan(split.bf16_triple_value(*split.split_bf16x3(x)))[is_nan].all()
 
 
 # ----------------------------------------------------------------------------- GEMMs
@@ -460,3 +485,34 @@ def test_mma_emulators():
         err["fp32"].append(gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", 16, 16, k, 1.0, A32, B32)))
     rn, rz, fp32 = (float(np.mean(err[n])) for n in ("rn", "rz", "fp32"))
     assert rn <= 1.25 * fp32 and rz > 2 * rn
+
+
+def test_gemm_blocked_chains_the_blocks_in_ascending_k():
+    """gemm_blocked: exact on small integers whatever the block depth (ragged last block included); equal to the chain
+    of single multiply-accumulates written out by hand; and on a case where the order of the blocks decides the result
+    (2^24, then 1, then -2^24: ascending gives 0 because 2^24 + 1 ties to 2^24; descending gives 1) it gives the
+    ascending answer, with both emulators."""
+    from oracle import mma_emulator as emu
+    rng = np.random.default_rng(1)
+    A = rng.integers(-7, 8, (5, 20)).astype(np.float32)
+    B = rng.integers(-7, 8, (20, 3)).astype(np.float32)
+    exact = (A.astype(np.int64) @ B.astype(np.int64)).astype(np.float32)
+    for block_k in (1, 3, 8, 16, 20, 64):
+        for fn in (emu.mma_rn, emu.mma_rz):
+            assert np.array_equal(emu.gemm_blocked(A, B, fn, block_k), exact), block_k
+    # the hand-written chain on values whose FP32 sum depends on the order
+    A32 = si.urand(4, 40, 3, si.ID_A)
+    B32 = si.urand(40, 4, 3, si.ID_B)
+    a16 = split.to_fp16_rn(A32).astype(np.float32)
+    b16 = split.to_fp16_rn(B32).astype(np.float32)
+    for fn in (emu.mma_rn, emu.mma_rz):
+        acc = np.zeros((4, 4), dtype=np.float32)
+        for k0 in (0, 8, 16, 24, 32):
+            acc = fn(a16[:, k0:k0 + 8], b16[k0:k0 + 8, :], acc)
+        assert np.array_equal(emu.gemm_blocked(a16, b16, fn, 8), acc)
+    # block order: one product per block
+    a = np.array([[2.0 ** 12, 1.0, -2.0 ** 12]], dtype=np.float32)
+    b = np.array([[2.0 ** 12], [1.0], [2.0 ** 12]], dtype=np.float32)
+    for fn in (emu.mma_rn, emu.mma_rz):
+        assert emu.gemm_blocked(a, b, fn, 1)[0, 0] == 0.0
+        assert emu.gemm_blocked(a[:, ::-1], b[::-1, :], fn, 1)[0, 0] == 1.0
