@@ -136,7 +136,7 @@ def main():
     h.set_stream(stream.cuda_stream)
     h.set_shape({"auto": ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2,
                  "fused": ec.SHAPE_128x128_FUSED}[args.shape])
-    ws_bytes = h.workspace_size(M, N, K, mode_id)
+    ws_bytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode_id)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     h.set_workspace(ws, ws_bytes)
 
@@ -260,7 +260,7 @@ def main():
                    "power": power_while(library_call, args.power_seconds) if args.power_seconds > 0 else None}
         del ref
         # the same comparison inside this code base: FP32 operands on the FP32 matrix instruction, same kernels
-        own_bytes = h.workspace_size(M, N, K, ec.MODE_FP32_MFMA)
+        own_bytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_FP32_MFMA)
         own_ws = torch.empty(own_bytes, dtype=torch.uint8, device="cuda")
         h.set_workspace(own_ws, own_bytes)
         own_out = torch.empty((N, M), dtype=torch.float32, device="cuda")

@@ -9,13 +9,32 @@
  *
  * All matrix pointers are DEVICE pointers owned by the caller.  The library only reads A
  * and B, writes C, keeps no pointer after a call returns, and never frees caller memory.
- * All work is enqueued on the handle's stream and the calls return without waiting for it.
- * Every function returns an ecgemm_status_t and never throws or aborts; on any status other
- * than ECGEMM_OK no work has been enqueued by that call.  A handle may be used by one host
- * thread at a time.  With a caller-provided workspace and timing off, ecgemm_sgemm and ecgemm_product only launch
- * kernels (no allocation, no memset, no wait), so they can be recorded into a HIP graph.
+ * All work is enqueued on the handle's stream and the calls return without waiting for it, with the
+ * exceptions stated at the functions concerned: a handle-owned workspace that has to grow (below),
+ * ecgemm_exponent_range, ecgemm_choose_mode and ecgemm_get_timing.
+ * Every function returns an ecgemm_status_t and never throws or aborts.  Enumeration arguments are read as plain
+ * integers: a value that is not one of the enumerators is refused like any other bad argument.  Arguments and sizes are checked before
+ * anything is enqueued: ECGEMM_ERR_INVALID_ARG, ECGEMM_ERR_UNSUPPORTED and ECGEMM_ERR_ALLOC mean that the call has
+ * enqueued nothing and left C untouched.  ECGEMM_ERR_HIP means that the HIP runtime refused a launch or an event in
+ * the middle of the call: kernels enqueued before that point still run, and the contents of C and of the workspace
+ * are then unspecified.  A handle may be used by one host thread at a time.
+ *
+ * Workspace.  Every product needs device memory for the split operands (ecgemm_workspace_size).  Either the caller
+ * provides it (ecgemm_set_workspace), or the handle allocates it on first need and keeps it; whenever a call needs
+ * more than the handle holds, that call waits for the handle's stream, frees the old buffer and allocates a larger
+ * one (hipStreamSynchronize, hipFree, hipMalloc) before it enqueues anything.  With a caller-provided workspace and
+ * timing off, ecgemm_sgemm and ecgemm_product only launch kernels (no allocation, no memset, no wait), so they can be
+ * recorded into a HIP graph.
+ * All calls on a handle share its workspace and nothing orders them but the stream: after ecgemm_set_stream has
+ * changed the stream, the caller makes the new stream wait for the work enqueued on the old one before the next
+ * product (or uses one handle per stream).
+ *
  * Results are bitwise reproducible for equal inputs and equal settings
  * (no floating-point atomics; the sums of tiles cut along K are added in a fixed order).
+ *
+ * This header is the production surface.  The knobs and diagnostics that only tests, tuning sweeps and the
+ * accuracy experiments use (forcing a kernel shape, the paper's comparison methods, bare matrix instructions) are
+ * declared in ecgemm_debug.h.
  */
 #ifndef ECGEMM_H
 #define ECGEMM_H
@@ -41,26 +60,14 @@ typedef enum {
      * six products of relative size >= 2^-16 are kept (same argument as section "Removing negligible
      * error correction"). */
     ECGEMM_MODE_BF16_FULL = 1,
-    /* The remaining modes are the methods the paper compares against, run through the same kernels so that its
-     * error curves can be redrawn on this hardware.  They are not meant for production use. */
-    /* Markidis' method: unscaled residual dv16 = toFP16(v - v16) (Eqs. corr-1 .. corr-4), all four products
-     * dA dB + dA B + A dB + A B summed in one accumulator (Eq. corr-5, listing "Markidis' error correction method"). */
+    /* 2 .. 7: the methods the paper compares against, run through the same kernels so that its error curves can be
+     * redrawn on this hardware.  Not meant for production use; each is described in ecgemm_debug.h (they are
+     * enumerators here because a C enumeration cannot be extended from a second header). */
     ECGEMM_MODE_FP16_MARKIDIS = 2,
-    /* The method's three products and separate correction accumulator, but on Markidis' unscaled residual: isolates
-     * what the 2^11 scaling of section "Reducing the underflow ..." buys. */
     ECGEMM_MODE_FP16_UNSCALED = 3,
-    /* toFP16(A) toFP16(B), one product, no correction (listing "A simple matrix-matrix multiplication ..."). */
     ECGEMM_MODE_FP16_PLAIN = 4,
-    /* toBF16(A) toBF16(B), one product, no correction. */
     ECGEMM_MODE_BF16_PLAIN = 5,
-    /* ECGEMM_MODE_FP16_SPLIT exactly as the paper's listing has it: A16 B16 is multiplied into a zeroed temporary and
-     * added to the running sum outside the matrix unit, every k step (section "Avoiding RZ during Tensor Core
-     * accumulation").  On this hardware the matrix unit already rounds to nearest, so this only costs time; it is kept
-     * to show that. */
     ECGEMM_MODE_FP16_OUTSIDE_ACC = 6,
-    /* No splitting at all: A B in FP32 on the matrix unit (v_mfma_f32_32x32x2_f32), through the same repacking pass
-     * and the same product kernel.  The FP32 GEMM that the paper sets its method against (its cuBLAS SGEMM column),
-     * on this hardware and in this code base, for throughput, energy and error comparisons. */
     ECGEMM_MODE_FP32_MFMA = 7
 } ecgemm_mode_t;
 
@@ -87,17 +94,19 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 /* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit fragment order,
  * zero-padded to whole tiles, plus at most 128 MiB of partial sums for output tiles that are cut into slices along K.
  * The plan behind it is made for the 256 compute units of the MI355X, so the size depends on the problem, the mode and
- * the kernel shape only; `handle` supplies the shape set with ecgemm_set_shape and may be NULL (automatic choice).
- * `bytes` is a host pointer. */
-ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
-                                      ecgemm_mode_t mode, size_t *bytes);
+ * the kernel shape only; `handle` supplies the shape forced with ecgemm_set_shape (ecgemm_debug.h) and may be NULL
+ * (automatic choice).  transA and transB are checked and otherwise do not matter: the split pass absorbs the
+ * transposes, so all four combinations need the same workspace.  `bytes` is a host pointer. */
+ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                      int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, size_t *bytes);
 
 /* How ecgemm_sgemm would run this problem (host logic only; no GPU work, `handle` as in ecgemm_workspace_size):
  * the kernel shape, the output tiles, how many of them are one work item over the whole depth and how many are cut
  * into how many slices along K, whether the product kernel is launched as a persistent grid, in which order the tiles
  * go to the XCDs, its grid size on a 256-CU device, and the workspace bytes.  `info` is a host pointer. */
 typedef struct {
-    int shape;          /* ecgemm_shape_t actually used (never ECGEMM_SHAPE_AUTO) */
+    int shape;          /* kernel shape used: 1 = block tile 256 x 128, 2 = 128 x 128 two per compute unit, 3 = 128 x 128
+                           with the split fused in (the ecgemm_shape_t values of ecgemm_debug.h; never 0 = automatic) */
     int tile_m, tile_n; /* block tile */
     int tiles_m, tiles_n;
     int whole_tiles;    /* tiles that are one work item */
@@ -109,14 +118,17 @@ typedef struct {
                            contiguous run of the order, so the 8 XCDs lie (8 / n) x n over the tile grid */
     int64_t grid;       /* workgroups of the product (or fused) kernel */
     size_t workspace_bytes;
+    double estimated_us; /* the cost estimate by which this plan was preferred to the others (product and reduce kernels,
+                            microseconds on a power-limited MI355X; 0 for the fused shape, which is never ranked) */
 } ecgemm_plan_info_t;
 ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
                                  ecgemm_plan_info_t *info);
 
 /* Hands the library a caller-owned device buffer (256-byte aligned) to use as workspace from now on;
  * (NULL, 0) returns to the handle-owned workspace, which is allocated on first need and only ever
- * grows.  With a caller buffer the library never allocates: a too small one makes ecgemm_sgemm return
- * ECGEMM_ERR_ALLOC.  The workspace must not overlap A, B or C. */
+ * grows (the call that makes it grow waits for the stream and allocates, see the top of this file).  With a caller
+ * buffer the library never allocates: a too small one makes ecgemm_sgemm return ECGEMM_ERR_ALLOC.  The workspace must
+ * not overlap A, B or C, and stays the caller's: ecgemm_destroy does not free it. */
 ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void *device_buffer, size_t bytes);
 
 /*
@@ -150,29 +162,6 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
- * Kernel shape of the product (steps 2 and 3 of ecgemm_sgemm); a tuning and test knob.  The paper's counterpart are the
- * block and warp tile sizes that it picks for each matrix size by grid search (section "Parameter tuning of CUTLASS").
- * ECGEMM_SHAPE_AUTO (the default) picks per call from the mode and the problem size.  The others force one shape for
- * every later ecgemm_sgemm / ecgemm_product / ecgemm_workspace_size on the handle:
- *   256x128_W4     block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
- *   128x128_X2     block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
- *   128x128_FUSED  the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
- *                  one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
- *                  packed operands in the workspace (the two modes of the method; ecgemm_sgemm only).  Slower than
- *                  the other two at every size on this hardware; never picked automatically.
- * All shapes form the same products in the same per-element order; results agree bit for bit between shapes unless
- * output tiles are sliced along K differently.  A call whose mode has no kernel of the forced shape returns
- * ECGEMM_ERR_UNSUPPORTED.
- */
-typedef enum {
-  ECGEMM_SHAPE_AUTO = 0,
-  ECGEMM_SHAPE_256x128_W4 = 1,
-  ECGEMM_SHAPE_128x128_X2 = 2,
-  ECGEMM_SHAPE_128x128_FUSED = 3
-} ecgemm_shape_t;
-ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
-
-/*
  * Power-of-two pre-scaling: the remedy the paper names, at the end of section "Effect of the exponent range of input
  * matrices", for inputs whose elements are all too small for the FP16 pair.  From now on
  * ecgemm_sgemm on this handle splits op(A) * 2^log2_scale_a and op(B) * 2^log2_scale_b and multiplies the product by
@@ -192,7 +181,7 @@ ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int
  * 2^col_log2_scale_b[n] before the split (exact), and element (m, n) of the product multiplied by 2^-row_log2_scale_a[m]
  * and then by 2^-col_log2_scale_b[n] (exact unless the result leaves the FP32 range) before alpha / beta.  The vectors
  * are device arrays of M and N 32-bit integers in [-126, 126], read during the call and not kept; both NULL gives
- * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.  Not available with the fused kernel shape.
+ * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.  Not available with the fused kernel shape (ecgemm_debug.h).
  *
  * ecgemm_row_scales writes such a vector: for each row r of X = op(src) (rows x depth; op and ld as in ecgemm_split)
  * the exponent that moves the row's largest non-zero finite element into the binade 2^target_exponent, 0 for a row
@@ -259,28 +248,6 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
 /* Bytes ecgemm_split writes for a rows x depth operand.  `bytes` is a host pointer. */
 ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mode, size_t *bytes);
 
-/*
- * Diagnostic: executes `count` independent v_mfma_f32_32x32x16_f16 (bf16 == 0) or _bf16 (bf16 != 0) instructions,
- * D = A B + C with A 32 x 16, B 16 x 32, C and D 32 x 32, on registers given lane by lane, so that tests can state what
- * the matrix unit does (the method's accumulation discipline, section "Avoiding RZ during Tensor Core accumulation",
- * depends on it).  For problem p and lane l (0..63): a[(p*64 + l)*8 + e] = A(l % 32, 8*(l/32) + e),
- * b[(p*64 + l)*8 + e] = B(8*(l/32) + e, l % 32), c and d [(p*64 + l)*16 + v] = element (8*(v/4) + 4*(l/32) + v%4, l % 32).
- * a, b: device, 16-bit patterns, 16-byte aligned; c, d: device FP32, 64-byte aligned; d may equal c.
- */
-ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void *a, const void *b,
-                                  const float *c, float *d);
-
-/*
- * Diagnostic: enqueues a kernel of `blocks` workgroups x 4 waves that does nothing but `iters` x 24 matrix
- * instructions per wave (FP16 if bf16 == 0, else BF16) on operands read once from `operands` (device, 12 x 256 x 8
- * 16-bit values = 48 KiB, 16-byte aligned).  `sink`: device, blocks x 256 floats, receives a checksum.  `flops`
- * (host pointer) receives the floating-point operations the kernel performs; timing it (the caller brackets it with
- * events on the handle's stream) gives the rate the matrix pipes sustain for that operand content on this device,
- * against which the product kernel's rate can be read.
- */
-ecgemm_status_t ecgemm_debug_mfma_rate(ecgemm_handle_t handle, int bf16, const void *operands, float *sink, int blocks,
-                                       int iters, double *flops);
-
 /* When enabled, every ecgemm_sgemm brackets its split kernels and its product kernel with HIP events on
  * the handle's stream so that their device durations can be read back; off by default. */
 ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled);
@@ -292,6 +259,11 @@ ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int *calls, float *spl
 
 /* Human-readable text for the last failure on this handle (host string owned by the handle). */
 const char *ecgemm_last_error_string(ecgemm_handle_t handle);
+
+/* Position (1 = the handle, 2 = the next parameter, ...) in the failing function's parameter list of the first
+ * argument that the last failed call on this handle found invalid; 0 when that failure was not about one argument
+ * (a HIP error, a workspace that is too small) or when no call has failed yet.  -1 for a NULL handle. */
+int ecgemm_last_error_argument(ecgemm_handle_t handle);
 
 /* Static name of a status code. */
 const char *ecgemm_status_string(ecgemm_status_t status);

@@ -11,8 +11,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# ECGEMM_LIB points the binding at another build of the same library (used to time tile-shape variants)
-LIB_PATH = os.environ.get("ECGEMM_LIB") or os.path.join(HERE, "libecgemm.so")
+LIB_PATH = os.path.join(HERE, "libecgemm.so")
 
 OP_N, OP_T = 0, 1
 MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
@@ -22,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -32,10 +31,10 @@ class PlanInfo(ctypes.Structure):
                 ("tiles_n", ctypes.c_int), ("whole_tiles", ctypes.c_int), ("sliced_tiles", ctypes.c_int),
                 ("slices", ctypes.c_int), ("persistent", ctypes.c_int), ("group_m", ctypes.c_int),
                 ("column_bands", ctypes.c_int), ("grid", ctypes.c_int64),
-                ("workspace_bytes", ctypes.c_size_t)]
+                ("workspace_bytes", ctypes.c_size_t), ("estimated_us", ctypes.c_double)]
 
     def as_dict(self) -> dict:
-        return {name: int(getattr(self, name)) for name, _ in self._fields_}
+        return {name: (float if name == "estimated_us" else int)(getattr(self, name)) for name, _ in self._fields_}
 
 
 def _load() -> ctypes.CDLL:
@@ -54,11 +53,12 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_create.argtypes = [ctypes.POINTER(vp)]
     lib.ecgemm_destroy.argtypes = [vp]
     lib.ecgemm_set_stream.argtypes = [vp, vp]
-    lib.ecgemm_workspace_size.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
+    lib.ecgemm_workspace_size.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, ctypes.c_int, ctypes.POINTER(sz)]
     lib.ecgemm_set_workspace.argtypes = [vp, vp, sz]
     lib.ecgemm_plan_info.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(PlanInfo)]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
+    lib.ecgemm_last_error_argument.argtypes = [vp]
     lib.ecgemm_sgemm_scaled.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                         ctypes.c_int, vp, vp]
     lib.ecgemm_row_scales.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
@@ -78,7 +78,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_last_error_string.restype = ctypes.c_char_p
     lib.ecgemm_status_string.argtypes = [ctypes.c_int]
     lib.ecgemm_status_string.restype = ctypes.c_char_p
-    for name in EXPORTS:
+    for name in EXPORTS:       # (ecgemm_last_error_argument returns a plain int as well)
         if getattr(lib, name).restype is not ctypes.c_char_p:
             getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -88,8 +88,9 @@ _lib = _load()
 
 
 class EcgemmError(RuntimeError):
-    def __init__(self, status: int, detail: str):
+    def __init__(self, status: int, detail: str, argument: int = 0):
         self.status = status
+        self.argument = argument        # ecgemm_last_error_argument at the time of the failure
         super().__init__(f"{_lib.ecgemm_status_string(status).decode()}: {detail}")
 
 
@@ -114,7 +115,10 @@ class Handle:
 
     def _check(self, st: int):
         if st != OK:
-            raise EcgemmError(st, _lib.ecgemm_last_error_string(self._h).decode())
+            raise EcgemmError(st, _lib.ecgemm_last_error_string(self._h).decode(), _lib.ecgemm_last_error_argument(self._h))
+
+    def last_error_argument(self) -> int:
+        return _lib.ecgemm_last_error_argument(self._h)
 
     def destroy(self):
         if self._h:
@@ -132,9 +136,9 @@ class Handle:
     def set_stream(self, stream_ptr: int):
         self._check(_lib.ecgemm_set_stream(self._h, stream_ptr))
 
-    def workspace_size(self, M: int, N: int, K: int, mode: int) -> int:
+    def workspace_size(self, transA: int, transB: int, M: int, N: int, K: int, mode: int) -> int:
         out = ctypes.c_size_t()
-        self._check(_lib.ecgemm_workspace_size(self._h, M, N, K, mode, ctypes.byref(out)))
+        self._check(_lib.ecgemm_workspace_size(self._h, transA, transB, M, N, K, mode, ctypes.byref(out)))
         return out.value
 
     def plan_info(self, M: int, N: int, K: int, mode: int) -> dict:
@@ -201,10 +205,10 @@ class Handle:
         return calls.value, a.value, b.value
 
 
-def workspace_size(M: int, N: int, K: int, mode: int) -> int:
+def workspace_size(transA: int, transB: int, M: int, N: int, K: int, mode: int) -> int:
     """ecgemm_workspace_size without a handle (none is needed)."""
     out = ctypes.c_size_t()
-    st = _lib.ecgemm_workspace_size(None, M, N, K, mode, ctypes.byref(out))
+    st = _lib.ecgemm_workspace_size(None, transA, transB, M, N, K, mode, ctypes.byref(out))
     if st != OK:
         raise EcgemmError(st, "ecgemm_workspace_size")
     return out.value

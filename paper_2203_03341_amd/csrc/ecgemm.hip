@@ -1,5 +1,6 @@
 // Host side of the ecgemm C-ABI (see include/ecgemm.h): argument checks, workspace, kernel launches.
 #include "../../include/ecgemm.h"
+#include "../../include/ecgemm_debug.h"
 
 #include <hip/hip_runtime.h>
 
@@ -12,9 +13,8 @@
 #include <string>
 #include <vector>
 
-#include "fused_kernel.hpp"
-#include "product_kernel.hpp"
-#include "split_kernels.hpp"
+#include "helper_kernels.hpp"
+#include "kernel_list.hpp"
 
 using namespace ecgemm;
 
@@ -34,30 +34,13 @@ struct ecgemm_context {
   int log2_scale_a = 0, log2_scale_b = 0;
   ecgemm_shape_t shape = ECGEMM_SHAPE_AUTO;
   int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
+  int last_error_argument = 0;
   std::vector<TimedCall> timed;
   std::vector<hipEvent_t> free_events;
   std::string last_error;
 };
 
 namespace {
-
-// Kernel shapes: block tile, waves per block, k steps per LDS stage, stages, resident blocks per CU.
-//   W4: 256 x 128, 4 waves (one per SIMD) of 128 x 64.  Least LDS and L2 traffic per flop.
-//   X2: 128 x 128, 4 waves of 64 x 64, two blocks per CU.  A third more LDS reads and L2 traffic per flop; one block's
-//       epilogue and pipeline fill hide behind the other's main loop, and a problem makes twice as many tiles.
-// (A 256 x 128 shape with 8 waves of 64 x 64, two per SIMD, was also built and timed on 60 sizes: never more than
-// 2 % ahead of W4, usually 1 % behind.)
-typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
-typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 1, 4, 2> Fp16X2;      // 4 x 16 KiB of LDS per block
-typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 2, 2, 1> Bf16W4;      // 2 x 72 KiB (1 % ahead of 4 x 36 KiB)
-typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
-// comparison methods: the W4 shape only
-typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisConfig;
-typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, 2, 3, 1> UnscaledConfig;
-typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3, 1> PlainFp16Config;
-typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Config;
-typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
-typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 
 typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
 struct Shape {
@@ -171,8 +154,6 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
 // least-squares fit to 1300 timings: both shapes with every admissible slice count on 174 problems (squares from
 // 512 to 5632, random M, N in 512..10000 and K in 256..23000, both modes).  Picking the cheapest plan is within 0.6 %
 // of the best measured plan on average over these problems, 3 of them more than 5 % off (worst 11 %).
-// calibrate_plans.py beside this library takes the timings (with a build whose slice count can be forced, below) and
-// refits the constants.
 constexpr double kW4Unit = 22.03, kW4Work = 0.954, kX2Pair = 14.74, kX2Lone = 10.08, kX2LonePerDepth = 0.277, kChip = 17.46;
 constexpr double kFillExponent = 0.906, kW4RoundUs = 7.88, kX2RoundUs = 4.70, kReduceUs = 1.01, kReduceUsPerMB = 0.142;
 
@@ -229,9 +210,6 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
     const int64_t splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPlanComputeUnits / tail, best.Kp / 512), 64));
     return plan_with(M, N, K, mode, shape, (int)splits);
   }
-#ifdef ECGEMM_TUNING
-  if (const char* forced = std::getenv("ECGEMM_FORCE_SLICES")) return plan_with(M, N, K, mode, shape, std::max(1, std::atoi(forced)));
-#endif
   double best_us = estimated_us(best, mode);
   for (int splits = 2; splits <= 64 && splits <= best.Kp / 512 && splits * tail <= 1024; ++splits) {
     const int per_slice = (best.k_tiles + splits - 1) / splits;
@@ -257,9 +235,6 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_sha
 // plan of each thread is kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to a
 // 12 us call).
 Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
-#ifdef ECGEMM_TUNING
-  return choose_plan(M, N, K, mode, shape);  // the forced slice count is not part of the key
-#else
   struct Key {
     int64_t M, N, K;
     int mode, shape;
@@ -271,12 +246,16 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
     last = Key{M, N, K, (int)mode, (int)shape};
   }
   return plan;
-#endif
 }
 
-ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what) {
-  if (h) h->last_error = what;
+ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what, int argument = 0) {
+  if (h) h->last_error = what, h->last_error_argument = argument;
   return st;
+}
+
+// ECGEMM_ERR_INVALID_ARG for the argument at `position` of the failing function's parameter list (1 = the handle)
+ecgemm_status_t bad_arg(ecgemm_handle_t h, int position, const char* what) {
+  return fail(h, ECGEMM_ERR_INVALID_ARG, what, position);
 }
 
 ecgemm_status_t hip_fail(ecgemm_handle_t h, hipError_t e, const char* where) {
@@ -505,13 +484,15 @@ ecgemm_status_t acquire_workspace(ecgemm_handle_t h, size_t bytes, char** out) {
   return ECGEMM_OK;
 }
 
-ecgemm_status_t check_sizes(ecgemm_handle_t h, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
+// `m_position`: where M stands in the calling function's parameter list (N and K follow it)
+ecgemm_status_t check_sizes(ecgemm_handle_t h, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, int m_position) {
   // tile indices are 32-bit and the byte offset along K inside a row block is a 32-bit vector offset
-  if (M > (int64_t)1 << 36 || N > (int64_t)1 << 36) return fail(h, ECGEMM_ERR_INVALID_ARG, "M or N too large");
+  if (M > (int64_t)1 << 36) return bad_arg(h, m_position, "M too large");
+  if (N > (int64_t)1 << 36) return bad_arg(h, m_position + 1, "N too large");
   // work items are counted in 32 bits: at most 2^30 output tiles of 128 x 128 (C would hold 2^44 elements)
-  if (((M + 127) / 128) * ((N + 127) / 128) > ((int64_t)1 << 30)) return fail(h, ECGEMM_ERR_INVALID_ARG, "M x N too large");
-  if ((round_up(K, kDepthPad) / 16) * parts_of(mode) * 1024 >= ((int64_t)1 << 32))
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "K too large: a packed row block must stay below 4 GiB");
+  if (((M + 127) / 128) * ((N + 127) / 128) > ((int64_t)1 << 30)) return bad_arg(h, m_position, "M x N too large");
+  if (K > ((int64_t)1 << 26) || (round_up(K, kDepthPad) / 16) * parts_of(mode) * 1024 >= ((int64_t)1 << 32))
+    return bad_arg(h, m_position + 2, "K too large: a packed row block must stay below 4 GiB");
   return ECGEMM_OK;
 }
 
@@ -544,6 +525,8 @@ const char* ecgemm_status_string(ecgemm_status_t status) {
 const char* ecgemm_last_error_string(ecgemm_handle_t handle) {
   return handle ? handle->last_error.c_str() : "null handle";
 }
+
+int ecgemm_last_error_argument(ecgemm_handle_t handle) { return handle ? handle->last_error_argument : -1; }
 
 ecgemm_status_t ecgemm_create(ecgemm_handle_t* handle) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
@@ -584,18 +567,23 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void* hip_stream) {
 
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!valid_shape(shape)) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_shape: unknown shape");
+  if (!valid_shape(shape)) return bad_arg(handle, 2, "ecgemm_set_shape: unknown shape");
   handle->shape = shape;
   return ECGEMM_OK;
 }
 
-ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K,
-                                      ecgemm_mode_t mode, size_t* bytes) {
-  if (!bytes || M < 0 || N < 0 || K < 0 || !valid_mode(mode))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_workspace_size: bad argument");
+ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
+                                      int64_t K, ecgemm_mode_t mode, size_t* bytes) {
+  if (!valid_op(transA)) return bad_arg(handle, 2, "ecgemm_workspace_size: bad transA");
+  if (!valid_op(transB)) return bad_arg(handle, 3, "ecgemm_workspace_size: bad transB");
+  if (M < 0) return bad_arg(handle, 4, "ecgemm_workspace_size: negative M");
+  if (N < 0) return bad_arg(handle, 5, "ecgemm_workspace_size: negative N");
+  if (K < 0) return bad_arg(handle, 6, "ecgemm_workspace_size: negative K");
+  if (!valid_mode(mode)) return bad_arg(handle, 7, "ecgemm_workspace_size: unknown mode");
+  if (!bytes) return bad_arg(handle, 8, "ecgemm_workspace_size: null output");
   *bytes = 0;
   if (M == 0 || N == 0 || K == 0) return ECGEMM_OK;
-  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode);
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
@@ -605,9 +593,12 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, int64_t M, int64_t
 
 ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
                                  ecgemm_plan_info_t* info) {
-  if (!info || M <= 0 || N <= 0 || K <= 0 || !valid_mode(mode))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_plan_info: bad argument (sizes must be positive)");
-  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode);
+  if (M <= 0) return bad_arg(handle, 2, "ecgemm_plan_info: M must be positive");
+  if (N <= 0) return bad_arg(handle, 3, "ecgemm_plan_info: N must be positive");
+  if (K <= 0) return bad_arg(handle, 4, "ecgemm_plan_info: K must be positive");
+  if (!valid_mode(mode)) return bad_arg(handle, 5, "ecgemm_plan_info: unknown mode");
+  if (!info) return bad_arg(handle, 6, "ecgemm_plan_info: null output");
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_plan_info: the handle's kernel shape does not exist for this mode");
@@ -625,13 +616,14 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   info->group_m = pl.shape->fused ? 4 : group_m_of(pl);
   info->column_bands = pl.shape->fused ? 1 : column_bands(pl, info->group_m, mode);
   info->workspace_bytes = pl.total_bytes;
+  info->estimated_us = pl.shape->fused ? 0.0 : estimated_us(pl, mode);
   return ECGEMM_OK;
 }
 
 ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void* device_buffer, size_t bytes) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if ((device_buffer == nullptr) != (bytes == 0) || ((uintptr_t)device_buffer % 256) != 0)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_workspace: buffer must be 256-byte aligned, or (NULL, 0)");
+  if (((uintptr_t)device_buffer % 256) != 0) return bad_arg(handle, 2, "ecgemm_set_workspace: buffer must be 256-byte aligned");
+  if ((device_buffer == nullptr) != (bytes == 0)) return bad_arg(handle, 3, "ecgemm_set_workspace: a buffer with its size, or (NULL, 0)");
   handle->user_workspace = device_buffer;
   handle->user_bytes = bytes;
   return ECGEMM_OK;
@@ -646,13 +638,14 @@ ecgemm_status_t ecgemm_split_size(int64_t rows, int64_t depth, ecgemm_mode_t mod
 ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth,
                              const float* src, int64_t ld, ecgemm_mode_t mode, void* packed) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!valid_op(op) || !valid_mode(mode) || rows < 0 || depth < 0)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: bad enum or negative size");
+  if (!valid_op(op)) return bad_arg(handle, 2, "ecgemm_split: bad op");
+  if (rows < 0) return bad_arg(handle, 3, "ecgemm_split: negative rows");
+  if (depth < 0) return bad_arg(handle, 4, "ecgemm_split: negative depth");
+  if (!valid_mode(mode)) return bad_arg(handle, 7, "ecgemm_split: unknown mode");
   if (rows == 0 || depth == 0) return ECGEMM_OK;
-  if (!src || !packed || ((uintptr_t)packed % 16) != 0)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: null or misaligned pointer");
-  if (ld < (op == ECGEMM_OP_N ? rows : depth))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_split: leading dimension too small");
+  if (!src) return bad_arg(handle, 5, "ecgemm_split: null source");
+  if (ld < (op == ECGEMM_OP_N ? rows : depth)) return bad_arg(handle, 6, "ecgemm_split: leading dimension too small");
+  if (!packed || ((uintptr_t)packed % 16) != 0) return bad_arg(handle, 8, "ecgemm_split: null or misaligned output");
   SplitJob job;
   const ecgemm_status_t st = make_split_job(handle, op, rows, depth, src, ld, packed, 0, nullptr, &job);
   if (st != ECGEMM_OK) return st;
@@ -661,8 +654,9 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
 
 ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int log2_scale_b) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (std::abs(log2_scale_a) > 126 || std::abs(log2_scale_b) > 126 || std::abs(log2_scale_a + log2_scale_b) > 126)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_set_scaling: exponents (and their sum) must stay within +-126");
+  if (std::abs(log2_scale_a) > 126) return bad_arg(handle, 2, "ecgemm_set_scaling: exponent beyond +-126");
+  if (std::abs(log2_scale_b) > 126 || std::abs(log2_scale_a + log2_scale_b) > 126)
+    return bad_arg(handle, 3, "ecgemm_set_scaling: exponents (and their sum) must stay within +-126");
   handle->log2_scale_a = log2_scale_a;
   handle->log2_scale_b = log2_scale_b;
   return ECGEMM_OK;
@@ -671,11 +665,14 @@ ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int
 ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int64_t cols, const float* src, int64_t ld,
                                       int* min_exponent, int* max_exponent) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!min_exponent || !max_exponent || rows < 0 || cols < 0)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_exponent_range: bad argument");
+  if (rows < 0) return bad_arg(handle, 2, "ecgemm_exponent_range: negative rows");
+  if (cols < 0) return bad_arg(handle, 3, "ecgemm_exponent_range: negative cols");
+  if (!min_exponent) return bad_arg(handle, 6, "ecgemm_exponent_range: null output");
+  if (!max_exponent) return bad_arg(handle, 7, "ecgemm_exponent_range: null output");
   int host[2] = {INT_MAX, INT_MIN};
   if (rows > 0 && cols > 0) {
-    if (!src || ld < rows) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_exponent_range: null source or ld < rows");
+    if (!src) return bad_arg(handle, 4, "ecgemm_exponent_range: null source");
+    if (ld < rows) return bad_arg(handle, 5, "ecgemm_exponent_range: ld < rows");
     if (!handle->range_buffer && hipMalloc(&handle->range_buffer, 2 * sizeof(int)) != hipSuccess) {
       handle->range_buffer = nullptr;
       (void)hipGetLastError();
@@ -697,15 +694,17 @@ ecgemm_status_t ecgemm_exponent_range(ecgemm_handle_t handle, int64_t rows, int6
 ecgemm_status_t ecgemm_row_scales(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
                                   int64_t ld, int target_exponent, int32_t* log2_scale) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!valid_op(op) || rows < 0 || depth < 0 || target_exponent < -126 || target_exponent > 126)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: bad argument");
+  if (!valid_op(op)) return bad_arg(handle, 2, "ecgemm_row_scales: bad op");
+  if (rows < 0) return bad_arg(handle, 3, "ecgemm_row_scales: negative rows");
+  if (depth < 0) return bad_arg(handle, 4, "ecgemm_row_scales: negative depth");
+  if (target_exponent < -126 || target_exponent > 126) return bad_arg(handle, 7, "ecgemm_row_scales: target exponent beyond +-126");
   if (rows == 0) return ECGEMM_OK;
-  if (!log2_scale) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: null output");
-  if (depth > 0 && (!src || ld < (op == ECGEMM_OP_N ? rows : depth)))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: null source or leading dimension too small");
+  if (!log2_scale) return bad_arg(handle, 8, "ecgemm_row_scales: null output");
+  if (depth > 0 && !src) return bad_arg(handle, 5, "ecgemm_row_scales: null source");
+  if (depth > 0 && ld < (op == ECGEMM_OP_N ? rows : depth)) return bad_arg(handle, 6, "ecgemm_row_scales: leading dimension too small");
   const int64_t row_blocks = (rows + 255) / 256, slabs = (depth + 2047) / 2048;
-  if (row_blocks > 0x7fffffff || rows > 0x1fffffffLL || slabs > 65535)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_row_scales: operand too large");
+  if (row_blocks > 0x7fffffff || rows > 0x1fffffffLL) return bad_arg(handle, 3, "ecgemm_row_scales: too many rows");
+  if (slabs > 65535) return bad_arg(handle, 4, "ecgemm_row_scales: operand too deep");
   hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)row_blocks), dim3(256), 0, handle->stream, log2_scale, rows, INT_MIN);
   if (depth > 0) {
     const bool k_contiguous = op == ECGEMM_OP_T;
@@ -723,14 +722,26 @@ ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, e
                                    int64_t K, const float* A, int64_t lda, const float* B, int64_t ldb,
                                    ecgemm_mode_t* mode, int* log2_scale_a, int* log2_scale_b) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!mode || !log2_scale_a || !log2_scale_b || !valid_op(transA) || !valid_op(transB) || M < 0 || N < 0 || K < 0)
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_choose_mode: bad argument");
+  if (!valid_op(transA)) return bad_arg(handle, 2, "ecgemm_choose_mode: bad transA");
+  if (!valid_op(transB)) return bad_arg(handle, 3, "ecgemm_choose_mode: bad transB");
+  if (M < 0) return bad_arg(handle, 4, "ecgemm_choose_mode: negative M");
+  if (N < 0) return bad_arg(handle, 5, "ecgemm_choose_mode: negative N");
+  if (K < 0) return bad_arg(handle, 6, "ecgemm_choose_mode: negative K");
+  if (!mode) return bad_arg(handle, 11, "ecgemm_choose_mode: null output");
+  if (!log2_scale_a) return bad_arg(handle, 12, "ecgemm_choose_mode: null output");
+  if (!log2_scale_b) return bad_arg(handle, 13, "ecgemm_choose_mode: null output");
   int lo[2] = {0, 0}, hi[2] = {0, 0};
   ecgemm_status_t st = ecgemm_exponent_range(handle, transA == ECGEMM_OP_N ? M : K, transA == ECGEMM_OP_N ? K : M, A, lda,
                                              &lo[0], &hi[0]);
-  if (st != ECGEMM_OK) return st;
+  if (st != ECGEMM_OK) {
+    if (handle->last_error_argument) handle->last_error_argument += 3;  // src, ld of that call are A, lda (7, 8) here
+    return st;
+  }
   st = ecgemm_exponent_range(handle, transB == ECGEMM_OP_N ? K : N, transB == ECGEMM_OP_N ? N : K, B, ldb, &lo[1], &hi[1]);
-  if (st != ECGEMM_OK) return st;
+  if (st != ECGEMM_OK) {
+    if (handle->last_error_argument) handle->last_error_argument += 5;  // B, ldb (9, 10)
+    return st;
+  }
   // The FP16 pair is fully precise for magnitudes 2^-14 .. 2^15 (top binade kept one below the saturation point):
   // an operand fits if its non-zero elements span at most 29 binades; its top binade is then moved to 2^14.
   int scale[2] = {0, 0};
@@ -750,10 +761,12 @@ ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, e
 ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t count, const void* a, const void* b,
                                   const float* c, float* d) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (count < 0 || count > 0x7fffffff) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma: bad count");
+  if (count < 0 || count > 0x7fffffff) return bad_arg(handle, 3, "ecgemm_debug_mfma: bad count");
   if (count == 0) return ECGEMM_OK;
-  if (!a || !b || !c || !d || ((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 64) || ((uintptr_t)d % 64))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma: null or misaligned pointer");
+  if (!a || ((uintptr_t)a % 16)) return bad_arg(handle, 4, "ecgemm_debug_mfma: null or misaligned pointer");
+  if (!b || ((uintptr_t)b % 16)) return bad_arg(handle, 5, "ecgemm_debug_mfma: null or misaligned pointer");
+  if (!c || ((uintptr_t)c % 64)) return bad_arg(handle, 6, "ecgemm_debug_mfma: null or misaligned pointer");
+  if (!d || ((uintptr_t)d % 64)) return bad_arg(handle, 7, "ecgemm_debug_mfma: null or misaligned pointer");
   const unsigned short* ua = static_cast<const unsigned short*>(a);
   const unsigned short* ub = static_cast<const unsigned short*>(b);
   if (bf16) hipLaunchKernelGGL(single_mfma_kernel<true>, dim3((unsigned)count), dim3(64), 0, handle->stream, ua, ub, c, d);
@@ -765,8 +778,11 @@ ecgemm_status_t ecgemm_debug_mfma(ecgemm_handle_t handle, int bf16, int64_t coun
 ecgemm_status_t ecgemm_debug_mfma_rate(ecgemm_handle_t handle, int bf16, const void* operands, float* sink, int blocks,
                                        int iters, double* flops) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!operands || !sink || !flops || blocks <= 0 || iters <= 0 || ((uintptr_t)operands % 16))
-    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_debug_mfma_rate: bad argument");
+  if (!operands || ((uintptr_t)operands % 16)) return bad_arg(handle, 3, "ecgemm_debug_mfma_rate: null or misaligned operands");
+  if (!sink) return bad_arg(handle, 4, "ecgemm_debug_mfma_rate: null sink");
+  if (blocks <= 0) return bad_arg(handle, 5, "ecgemm_debug_mfma_rate: blocks must be positive");
+  if (iters <= 0) return bad_arg(handle, 6, "ecgemm_debug_mfma_rate: iters must be positive");
+  if (!flops) return bad_arg(handle, 7, "ecgemm_debug_mfma_rate: null output");
   const unsigned short* ops = static_cast<const unsigned short*>(operands);
   if (bf16) hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, handle->stream, ops, sink, iters);
   else hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, handle->stream, ops, sink, iters);
@@ -783,7 +799,9 @@ ecgemm_status_t ecgemm_set_timing(ecgemm_handle_t handle, int enabled) {
 
 ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int* calls, float* split_ms, float* product_ms) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
-  if (!calls || !split_ms || !product_ms) return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_get_timing: null output");
+  if (!calls) return bad_arg(handle, 2, "ecgemm_get_timing: null output");
+  if (!split_ms) return bad_arg(handle, 3, "ecgemm_get_timing: null output");
+  if (!product_ms) return bad_arg(handle, 4, "ecgemm_get_timing: null output");
   *calls = 0;
   *split_ms = 0.0f;
   *product_ms = 0.0f;
@@ -803,25 +821,25 @@ ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int* calls, float* spl
   return ECGEMM_OK;
 }
 
-ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
-                             int64_t M, int64_t N, int64_t K, float alpha,
-                             const float* A, int64_t lda, const float* B, int64_t ldb,
-                             float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
-  return ecgemm_sgemm_scaled(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr);
-}
+}  // extern "C"
 
-ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
-                                    int64_t M, int64_t N, int64_t K, float alpha,
-                                    const float* A, int64_t lda, const float* B, int64_t ldb,
-                                    float beta, float* C, int64_t ldc, ecgemm_mode_t mode,
-                                    const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
-  ecgemm_handle_t h = handle;
+namespace {
+
+// ecgemm_sgemm and ecgemm_sgemm_scaled: the same parameter list up to `mode` (the positions reported for bad arguments
+// count it), then the scaling vectors.  Everything that can be refused is checked before the first launch.
+ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N, int64_t K, float alpha,
+                             const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
+                             ecgemm_mode_t mode, const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
   if (!h) return ECGEMM_ERR_INVALID_ARG;
-  if (!valid_op(transA) || !valid_op(transB) || !valid_mode(mode))
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: bad transA / transB / mode");
-  if (M < 0 || N < 0 || K < 0) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: negative size");
+  if (!valid_op(transA)) return bad_arg(h, 2, "ecgemm_sgemm: bad transA");
+  if (!valid_op(transB)) return bad_arg(h, 3, "ecgemm_sgemm: bad transB");
+  if (M < 0) return bad_arg(h, 4, "ecgemm_sgemm: negative M");
+  if (N < 0) return bad_arg(h, 5, "ecgemm_sgemm: negative N");
+  if (K < 0) return bad_arg(h, 6, "ecgemm_sgemm: negative K");
+  if (!valid_mode(mode)) return bad_arg(h, 15, "ecgemm_sgemm: unknown mode");
   if (M == 0 || N == 0) return ECGEMM_OK;
-  if (!C || ldc < M) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: C is null or ldc < M");
+  if (!C) return bad_arg(h, 13, "ecgemm_sgemm: C is null");
+  if (ldc < M) return bad_arg(h, 14, "ecgemm_sgemm: ldc < M");
 
   const dim3 block256(256);
   if (K == 0 || alpha == 0.0f) {
@@ -830,26 +848,36 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
     ECGEMM_HIP(h, hipGetLastError());
     return ECGEMM_OK;
   }
-  if (!A || !B) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: A or B is null");
-  if (lda < (transA == ECGEMM_OP_N ? M : K)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: lda too small");
-  if (ldb < (transB == ECGEMM_OP_N ? K : N)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: ldb too small");
+  if (!A) return bad_arg(h, 8, "ecgemm_sgemm: A is null");
+  if (lda < (transA == ECGEMM_OP_N ? M : K)) return bad_arg(h, 9, "ecgemm_sgemm: lda too small");
+  if (!B) return bad_arg(h, 10, "ecgemm_sgemm: B is null");
+  if (ldb < (transB == ECGEMM_OP_N ? K : N)) return bad_arg(h, 11, "ecgemm_sgemm: ldb too small");
 
-  ecgemm_status_t st = check_sizes(h, M, N, K, mode);
+  ecgemm_status_t st = check_sizes(h, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
   if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
   if ((row_log2_scale_a == nullptr) != (col_log2_scale_b == nullptr))
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm_scaled: give both scaling vectors or neither");
+    return bad_arg(h, row_log2_scale_a == nullptr ? 16 : 17, "ecgemm_sgemm_scaled: give both scaling vectors or neither");
   if (row_log2_scale_a && pl.shape->fused)
     return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm_scaled: the fused kernel shape takes no scaling vectors");
-  if (pl.items() + 16 > 0x7fffffffLL)
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_sgemm: too many tiles");
+  if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
+  SplitJob job_a, job_b;
   char* ws = nullptr;
   st = acquire_workspace(h, pl.total_bytes, &ws);
   if (st != ECGEMM_OK) return st;
   char* a_packed = ws;
   char* b_packed = ws + pl.a_bytes;
   float* partials = pl.tail_splits > 1 ? reinterpret_cast<float*>(ws + pl.a_bytes + pl.b_bytes) : nullptr;
+  if (!pl.shape->fused) {
+    // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
+    // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
+    st = make_split_job(h, transA, M, K, A, lda, a_packed, h->log2_scale_a, row_log2_scale_a, &job_a);
+    if (st != ECGEMM_OK) return st;
+    st = make_split_job(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, b_packed, h->log2_scale_b,
+                        col_log2_scale_b, &job_b);
+    if (st != ECGEMM_OK) return st;
+  }
 
   // Events for the optional timing go back to the handle's pool whenever the call does not complete.
   struct EventLease {
@@ -863,7 +891,8 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
     }
   } lease{h};
   TimedCall& tc = lease.tc;
-  if (h->timing) {
+  const bool timing = h->timing;
+  if (timing) {
     tc.start = take_event(h);
     tc.split_done = take_event(h);
     tc.product_done = take_event(h);
@@ -872,34 +901,18 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
   }
 
   if (pl.shape->fused) {
-    if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
+    if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
     st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, partials);
+  } else {
+    st = launch_split(h, mode, job_a, &job_b);
     if (st != ECGEMM_OK) return st;
-    if (h->timing) {
-      ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
-      h->timed.push_back(tc);
-      lease.keep = true;
-    }
-    return ECGEMM_OK;
+    if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
+    // steps 2 and 3
+    st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials,
+                        -(h->log2_scale_a + h->log2_scale_b), row_log2_scale_a, col_log2_scale_b);
   }
-
-  // step 1: op(A) is M x K with rows m; op(B)^T is N x K with rows n.  For B the roles of N and T swap:
-  // B stored K x N (transB == N) has k contiguous, i.e. it is the "T" case of the splitter.
-  SplitJob job_a, job_b;
-  st = make_split_job(h, transA, M, K, A, lda, a_packed, h->log2_scale_a, row_log2_scale_a, &job_a);
   if (st != ECGEMM_OK) return st;
-  st = make_split_job(h, transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N, N, K, B, ldb, b_packed, h->log2_scale_b,
-                      col_log2_scale_b, &job_b);
-  if (st != ECGEMM_OK) return st;
-  st = launch_split(h, mode, job_a, &job_b);
-  if (st != ECGEMM_OK) return st;
-  if (h->timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
-
-  // steps 2 and 3
-  st = launch_product(h, pl, M, N, alpha, a_packed, b_packed, beta, C, ldc, mode, partials,
-                      -(h->log2_scale_a + h->log2_scale_b), row_log2_scale_a, col_log2_scale_b);
-  if (st != ECGEMM_OK) return st;
-  if (h->timing) {
+  if (timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
     h->timed.push_back(tc);
     lease.keep = true;
@@ -907,30 +920,52 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
   return ECGEMM_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                             int64_t M, int64_t N, int64_t K, float alpha,
+                             const float* A, int64_t lda, const float* B, int64_t ldb,
+                             float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
+  return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr);
+}
+
+ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                    int64_t M, int64_t N, int64_t K, float alpha,
+                                    const float* A, int64_t lda, const float* B, int64_t ldb,
+                                    float beta, float* C, int64_t ldc, ecgemm_mode_t mode,
+                                    const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
+  return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, row_log2_scale_a,
+                      col_log2_scale_b);
+}
+
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
                                const void* packedA, const void* packedB, float beta, float* C, int64_t ldc,
                                ecgemm_mode_t mode) {
   ecgemm_handle_t h = handle;
   if (!h) return ECGEMM_ERR_INVALID_ARG;
-  if (!valid_mode(mode)) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: bad mode");
-  if (M < 0 || N < 0 || K < 0) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: negative size");
+  if (M < 0) return bad_arg(h, 2, "ecgemm_product: negative M");
+  if (N < 0) return bad_arg(h, 3, "ecgemm_product: negative N");
+  if (K < 0) return bad_arg(h, 4, "ecgemm_product: negative K");
+  if (!valid_mode(mode)) return bad_arg(h, 11, "ecgemm_product: unknown mode");
   if (M == 0 || N == 0) return ECGEMM_OK;
-  if (!C || ldc < M) return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: C is null or ldc < M");
+  if (!C) return bad_arg(h, 9, "ecgemm_product: C is null");
+  if (ldc < M) return bad_arg(h, 10, "ecgemm_product: ldc < M");
   if (K == 0 || alpha == 0.0f) {
     const dim3 grid((unsigned)((M + 255) / 256), (unsigned)(N < 65535 ? N : 65535));
     hipLaunchKernelGGL(scale_c_kernel, grid, dim3(256), 0, h->stream, M, N, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
     return ECGEMM_OK;
   }
-  if (!packedA || !packedB || ((uintptr_t)packedA % 16) != 0 || ((uintptr_t)packedB % 16) != 0)
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: packed operand is null or not 16-byte aligned");
-  ecgemm_status_t st = check_sizes(h, M, N, K, mode);
+  if (!packedA || ((uintptr_t)packedA % 16) != 0) return bad_arg(h, 6, "ecgemm_product: packed operand is null or not 16-byte aligned");
+  if (!packedB || ((uintptr_t)packedB % 16) != 0) return bad_arg(h, 7, "ecgemm_product: packed operand is null or not 16-byte aligned");
+  ecgemm_status_t st = check_sizes(h, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
   if (!pl.shape || pl.shape->fused)
     return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not take packed operands in this mode");
-  if (pl.items() + 16 > 0x7fffffffLL)
-    return fail(h, ECGEMM_ERR_INVALID_ARG, "ecgemm_product: too many tiles");
+  if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 2, "ecgemm_product: too many tiles");
   char* ws = nullptr;
   st = acquire_workspace(h, pl.partial_bytes, &ws);
   if (st != ECGEMM_OK) return st;

@@ -1,0 +1,94 @@
+// The kernel instantiations of the library, and which translation unit compiles which of them.
+//
+// Each kernels_*.hip file defines ECGEMM_INSTANTIATE_<group> before including this header and so compiles that group;
+// everywhere else (the host code in ecgemm.hip) the same lines are `extern template` declarations, so that the host
+// code can take the kernels' addresses without compiling them again.  The groups only exist to let the build compile
+// them side by side.
+#pragma once
+#include "fused_kernel.hpp"
+#include "product_kernel.hpp"
+#include "split_kernels.hpp"
+
+namespace ecgemm {
+
+// Kernel shapes: block tile, waves per block, k steps per LDS stage, stages, resident blocks per CU.
+//   W4: 256 x 128, 4 waves (one per SIMD) of 128 x 64.  Least LDS and L2 traffic per flop.
+//   X2: 128 x 128, 4 waves of 64 x 64, two blocks per CU.  A third more LDS reads and L2 traffic per flop; one block's
+//       epilogue and pipeline fill hide behind the other's main loop, and a problem makes twice as many tiles.
+// (A 256 x 128 shape with 8 waves of 64 x 64, two per SIMD, was also built and timed on 60 sizes: never more than
+// 2 % ahead of W4, usually 1 % behind.)
+typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
+typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 1, 4, 2> Fp16X2;      // 4 x 16 KiB of LDS per block
+typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 2, 2, 1> Bf16W4;      // 2 x 72 KiB (1 % ahead of 4 x 36 KiB)
+typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
+// comparison methods: the W4 shape only
+typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisConfig;
+typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, 2, 3, 1> UnscaledConfig;
+typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3, 1> PlainFp16Config;
+typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Config;
+typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
+typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
+
+#ifdef ECGEMM_INSTANTIATE_FP16
+#define ECGEMM_FP16_GROUP
+#else
+#define ECGEMM_FP16_GROUP extern
+#endif
+#ifdef ECGEMM_INSTANTIATE_BF16
+#define ECGEMM_BF16_GROUP
+#else
+#define ECGEMM_BF16_GROUP extern
+#endif
+#ifdef ECGEMM_INSTANTIATE_COMPARE_A
+#define ECGEMM_COMPARE_A_GROUP
+#else
+#define ECGEMM_COMPARE_A_GROUP extern
+#endif
+#ifdef ECGEMM_INSTANTIATE_COMPARE_B
+#define ECGEMM_COMPARE_B_GROUP
+#else
+#define ECGEMM_COMPARE_B_GROUP extern
+#endif
+#ifdef ECGEMM_INSTANTIATE_FUSED
+#define ECGEMM_FUSED_GROUP
+#else
+#define ECGEMM_FUSED_GROUP extern
+#endif
+#ifdef ECGEMM_INSTANTIATE_SPLIT
+#define ECGEMM_SPLIT_GROUP
+#else
+#define ECGEMM_SPLIT_GROUP extern
+#endif
+
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4>(const ProductParams);
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2>(const ProductParams);
+ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<256, 128>(const float*, int, int, int, int, int, int, int, int64_t,
+                                                                       int64_t, float, float, float*, int64_t);
+ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<128, 128>(const float*, int, int, int, int, int, int, int, int64_t,
+                                                                       int64_t, float, float, float*, int64_t);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4>(const ProductParams);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<MarkidisConfig>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<UnscaledConfig>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<OutsideConfig>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainFp16Config>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainBf16Config>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<Fp32Config>(const ProductParams);
+ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodFp16Split>(const FusedParams);
+ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodBf16Full>(const FusedParams);
+
+#define ECGEMM_SPLIT_KERNELS_OF(KIND)                                                                     \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguousVec>(const SplitJob);   \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguous>(const SplitJob);      \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguous>(const SplitJob);      \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguousWide>(const SplitJob);  \
+  ECGEMM_SPLIT_GROUP template __global__ void split_pair_kernel<KIND>(const SplitJob, const SplitJob);
+ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Scaled)
+ECGEMM_SPLIT_KERNELS_OF(kSplitBf16x3)
+ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Unscaled)
+ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Plain)
+ECGEMM_SPLIT_KERNELS_OF(kSplitBf16Plain)
+ECGEMM_SPLIT_KERNELS_OF(kSplitFp32)
+#undef ECGEMM_SPLIT_KERNELS_OF
+
+}  // namespace ecgemm

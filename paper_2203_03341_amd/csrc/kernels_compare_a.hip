@@ -1,0 +1,3 @@
+// Compiles one group of the kernels listed in kernel_list.hpp.
+#define ECGEMM_INSTANTIATE_COMPARE_A
+#include "kernel_list.hpp"

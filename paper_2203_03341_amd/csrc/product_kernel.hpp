@@ -620,54 +620,6 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   }  // items
 }
 
-// One v_mfma_f32_32x32x16 per wave on caller-supplied registers, for tests that pin down what the matrix unit does
-// (lane map, rounding, subnormals): lane l of problem p reads a[(p * 64 + l) * 8 .. +8], b likewise, c[(p * 64 + l) * 16
-// .. +16] and writes d at the same place.
-template <bool BF16>
-__global__ void __launch_bounds__(64) single_mfma_kernel(const unsigned short* __restrict__ a, const unsigned short* __restrict__ b,
-                                                         const float* __restrict__ c, float* __restrict__ d) {
-  typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
-  const int64_t slot = (int64_t)blockIdx.x * 64 + threadIdx.x;
-  const frag_t fa = *reinterpret_cast<const frag_t*>(a + slot * 8);
-  const frag_t fb = *reinterpret_cast<const frag_t*>(b + slot * 8);
-  float16_t acc = *reinterpret_cast<const float16_t*>(c + slot * 16);
-  acc = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fa, fb, acc);
-  *reinterpret_cast<float16_t*>(d + slot * 16) = acc;
-}
-
-// Matrix instructions only, no memory traffic in the loop: every wave of the grid issues `iters` x 24
-// v_mfma_f32_32x32x16 on operands it read once (12 fragments per lane from `operands`, 256 lanes x 16 bytes each).
-// Timed by the caller, this gives the rate the matrix pipes sustain for a given operand content; with random
-// operands it is well below the nominal peak because the clock drops under load.
-template <bool BF16>
-__global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short* __restrict__ operands, float* __restrict__ sink,
-                                                           int iters) {
-  typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
-  frag_t fa[6], fb[6];
-#pragma unroll
-  for (int i = 0; i < 6; ++i) {
-    fa[i] = *reinterpret_cast<const frag_t*>(operands + (i * 256 + threadIdx.x) * 8);
-    fb[i] = *reinterpret_cast<const frag_t*>(operands + ((6 + i) * 256 + threadIdx.x) * 8);
-  }
-  float16_t acc[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int r = 0; r < 3; ++r)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fa[(i + 2 * r) % 6], fb[(i * 5 + r) % 6], acc[i]);
-  }
-  float s = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s += acc[i][v];
-  sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
-}
-
 // Sums the slices of the sliced tiles in a fixed order (bitwise reproducible, no atomics), then alpha / beta.
 // partials is [tail_splits][tail_tiles][BN][BM]; block (t, q) handles elements 1024 q .. 1024 q + 1023 of tail tile t,
 // four consecutive rows of one column per thread, so that every load is 16 bytes per lane and the loads of different
@@ -709,16 +661,6 @@ __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restric
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (m + i < M) store_result(dst + i, (beta == 0.0f) ? alpha * part[i] : scaled_sum(alpha, part[i], beta, dst[i]));
-  }
-}
-
-// K == 0 or alpha == 0: C <- beta * C, and C <- 0 without reading it when beta == 0.
-__global__ void __launch_bounds__(256) scale_c_kernel(int64_t M, int64_t N, float beta, float* __restrict__ C, int64_t ldc) {
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (m >= M) return;
-  for (int64_t n = blockIdx.y; n < N; n += gridDim.y) {
-    float* dst = C + m + n * ldc;
-    *dst = (beta == 0.0f) ? 0.0f : beta * *dst;
   }
 }
 

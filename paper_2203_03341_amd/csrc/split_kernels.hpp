@@ -287,67 +287,4 @@ __global__ void __launch_bounds__(256) split_pair_kernel(const SplitJob a, const
   }
 }
 
-// Smallest and largest binary exponent among the non-zero finite elements of a column-major rows x cols matrix
-// (subnormals count as exponent -127).  range[0] must start at INT_MAX and range[1] at INT_MIN.
-__global__ void __launch_bounds__(256) exponent_range_kernel(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                             int64_t cols, int* __restrict__ range) {
-  int lo = 0x7fffffff, hi = -0x7fffffff - 1;
-  for (int64_t c = blockIdx.y; c < cols; c += gridDim.y)
-    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < rows; r += (int64_t)gridDim.x * 256) {
-      const unsigned bits = __builtin_bit_cast(unsigned, src[r + c * ld]) & 0x7fffffffu;
-      if (bits != 0 && bits < 0x7f800000u) {
-        const int e = (int)(bits >> 23) - 127;
-        lo = e < lo ? e : lo;
-        hi = e > hi ? e : hi;
-      }
-    }
-  if (lo <= hi) {
-    atomicMin(&range[0], lo);
-    atomicMax(&range[1], hi);
-  }
-}
-
-// Per-row scaling exponents, in three small kernels on one stream.  (1) row_max[r] <- INT_MIN.
-__global__ void __launch_bounds__(256) fill_int_kernel(int* __restrict__ dst, int64_t count, int value) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < count) dst[i] = value;
-}
-
-// (2) row_max[r] <- largest binary exponent among the non-zero finite elements of row r of X (subnormals count as
-// -127), X(r, k) = src[r + k * ld] or src[k + r * ld].  blockIdx.y takes a slab of 2048 k; lanes run along the
-// contiguous direction.
-__global__ void __launch_bounds__(256) row_max_exponent_kernel(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                               int64_t depth, int k_contiguous, int* __restrict__ row_max) {
-  const int64_t k_begin = (int64_t)blockIdx.y * 2048, k_end = k_begin + 2048 < depth ? k_begin + 2048 : depth;
-  auto exponent_of = [](float v) {
-    const unsigned bits = __builtin_bit_cast(unsigned, v) & 0x7fffffffu;
-    return (bits != 0 && bits < 0x7f800000u) ? (int)(bits >> 23) - 127 : -0x7fffffff - 1;
-  };
-  int hi = -0x7fffffff - 1;
-  if (!k_contiguous) {
-    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (r >= rows) return;
-    for (int64_t k = k_begin; k < k_end; ++k) hi = max(hi, exponent_of(src[r + k * ld]));
-    if (hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
-  } else {
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wave per row
-    if (r >= rows) return;
-    for (int64_t k = k_begin + (threadIdx.x & 63); k < k_end; k += 64) hi = max(hi, exponent_of(src[k + r * ld]));
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) hi = max(hi, __shfl_xor(hi, d, 64));
-    if ((threadIdx.x & 63) == 0 && hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
-  }
-}
-
-// (3) in place: the exponent that moves the row's largest binade to 2^target (0 for a row without non-zero finite
-// elements), kept inside what one power-of-two factor can express.
-__global__ void __launch_bounds__(256) finish_row_scales_kernel(int* __restrict__ row_scale, int64_t rows, int target) {
-  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (r >= rows) return;
-  const int hi = row_scale[r];
-  int e = hi == -0x7fffffff - 1 ? 0 : target - hi;
-  e = e < -126 ? -126 : e > 126 ? 126 : e;
-  row_scale[r] = e;
-}
-
 }  // namespace ecgemm

@@ -7,9 +7,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "ecgemm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ecgemm_[a-z_]+)\s*\(", text)))
+    """Every function declared in include/*.h (ecgemm.h: the production surface; ecgemm_debug.h: test and tuning knobs)."""
+    import glob
+    names = set()
+    for header in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names.update(re.findall(r"\b(ecgemm_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_north_star_entry_points():
@@ -33,7 +37,7 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
         '#include <stdio.h>\n#include "ecgemm.h"\n'
         "int main(void) {\n"
         "  size_t bytes = 0; ecgemm_plan_info_t info;\n"
-        "  if (ecgemm_workspace_size(NULL, 4096, 4096, 4096, ECGEMM_MODE_FP16_SPLIT, &bytes) != ECGEMM_OK) return 1;\n"
+        "  if (ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_T, 4096, 4096, 4096, ECGEMM_MODE_FP16_SPLIT, &bytes) != ECGEMM_OK) return 1;\n"
         "  if (ecgemm_plan_info(NULL, 4096, 4096, 4096, ECGEMM_MODE_BF16_FULL, &info) != ECGEMM_OK) return 2;\n"
         "  if (ecgemm_plan_info(NULL, 0, 1, 1, ECGEMM_MODE_BF16_FULL, &info) != ECGEMM_ERR_INVALID_ARG) return 3;\n"
         '  printf("%zu %d %s\\n", bytes, info.tile_m, ecgemm_status_string(ECGEMM_ERR_UNSUPPORTED));\n'
@@ -122,7 +126,7 @@ def test_plan_of_the_baseline_configs():
             assert p["tiles_m"] * p["tiles_n"] == p["whole_tiles"] + p["sliced_tiles"]
             assert p["tiles_m"] == -(-M // p["tile_m"]) and p["tiles_n"] == -(-N // p["tile_n"])
             assert (p["slices"] == 1) == (p["sliced_tiles"] == 0)
-            assert p["workspace_bytes"] == ec.workspace_size(M, N, K, mode)
+            assert p["workspace_bytes"] == ec.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode)
             if p["slices"] > 1:
                 assert -(-K // p["slices"]) >= 512 - 32                  # a slice is never shallower than 512 (padded)
     import pytest
@@ -134,7 +138,7 @@ def test_plan_of_the_baseline_configs():
             ec.plan_info(*bad, ec.MODE_FP16_SPLIT)
         assert err.value.status == ec.ERR_INVALID_ARG
         with pytest.raises(ec.EcgemmError):
-            ec.workspace_size(*bad, ec.MODE_FP16_SPLIT)
+            ec.workspace_size(ec.OP_N, ec.OP_T, *bad, ec.MODE_FP16_SPLIT)
     assert ec.plan_info(1 << 22, 1 << 15, 32, ec.MODE_FP16_SPLIT)["tiles_m"] == 1 << 15     # 2^30 tiles of 128 x 128: still fine
 
 
@@ -175,21 +179,21 @@ def test_workspace_plan_needs_no_gpu():
     tiles left over after whole rounds of the chip's 256 CUs cut into slices along K (one partial tile per slice)."""
     import paper_2203_03341_amd as ec
     n = 16384
-    assert ec.workspace_size(n, n, n, ec.MODE_FP16_SPLIT) == 2 * n * n * 4              # two packed operands, no split-K
-    assert ec.workspace_size(n, n, n, ec.MODE_BF16_FULL) == 2 * n * n * 6
-    assert ec.workspace_size(n, n, n, ec.MODE_FP16_PLAIN) == 2 * n * n * 2
-    assert ec.workspace_size(1, 1, 1, ec.MODE_FP16_SPLIT) == 2 * 256 * 32 * 4
-    assert ec.workspace_size(0, 5, 5, ec.MODE_FP16_SPLIT) == 0
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_FP16_SPLIT) == 2 * n * n * 4              # two packed operands, no split-K
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_BF16_FULL) == 2 * n * n * 6
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_FP16_PLAIN) == 2 * n * n * 2
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1, 1, 1, ec.MODE_FP16_SPLIT) == 2 * 256 * 32 * 4
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 0, 5, 5, ec.MODE_FP16_SPLIT) == 0
     # 32 output tiles of 256 x 128 on 256 CUs: every tile is cut into 8 slices along K, one partial tile per slice
-    deep = ec.workspace_size(1024, 1024, 65536, ec.MODE_FP16_SPLIT)
+    deep = ec.workspace_size(ec.OP_N, ec.OP_N, 1024, 1024, 65536, ec.MODE_FP16_SPLIT)
     assert deep == 2 * 1024 * 65536 * 4 + 8 * 32 * (256 * 128 * 4)
     # 16 x 24 = 384 tiles: 256 are done whole, the other 128 in two slices each
-    odd = ec.workspace_size(4095, 3001, 5003, ec.MODE_BF16_FULL)
+    odd = ec.workspace_size(ec.OP_N, ec.OP_N, 4095, 3001, 5003, ec.MODE_BF16_FULL)
     assert odd == (4096 + 3072) * 5024 * 6 + 2 * 128 * (256 * 128 * 4)
     # shallow K is never sliced
-    assert ec.workspace_size(1024, 1024, 512, ec.MODE_FP16_SPLIT) == 2 * 1024 * 512 * 4
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1024, 1024, 512, ec.MODE_FP16_SPLIT) == 2 * 1024 * 512 * 4
     import pytest
     with pytest.raises(ec.EcgemmError):
-        ec.workspace_size(-1, 1, 1, ec.MODE_FP16_SPLIT)
+        ec.workspace_size(ec.OP_N, ec.OP_N, -1, 1, 1, ec.MODE_FP16_SPLIT)
     with pytest.raises(ec.EcgemmError):
-        ec.workspace_size(1, 1, 1, 99)
+        ec.workspace_size(ec.OP_N, ec.OP_N, 1, 1, 1, 99)

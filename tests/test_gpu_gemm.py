@@ -233,25 +233,33 @@ def test_invalid_arguments_are_rejected():
     A, B = _inputs(M, N, K, "N", "N", "urand", 0)
     dA, dB = to_device(A), to_device(B)
     dC = empty_colmajor(M, N, fill=1.0)
+    # (what is wrong, position of that argument in ecgemm_sgemm's parameter list, the handle being 1)
     bad_calls = [
-        dict(transA=7), dict(transB=-1), dict(mode=99), dict(mode=-1), dict(M=-1), dict(K=-3), dict(lda=M - 1), dict(ldb=K - 1),
-        dict(ldc=M - 1), dict(A=None), dict(B=None), dict(C=None),
+        (dict(transA=7), 2), (dict(transB=-1), 3), (dict(mode=99), 15), (dict(mode=-1), 15), (dict(M=-1), 4), (dict(N=-2), 5),
+        (dict(K=-3), 6), (dict(lda=M - 1), 9), (dict(ldb=K - 1), 11), (dict(ldc=M - 1), 14), (dict(A=None), 8), (dict(B=None), 10),
+        (dict(C=None), 13), (dict(transA=5, C=None), 2),
     ]
     base = dict(transA=ec.OP_N, transB=ec.OP_N, M=M, N=N, K=K, alpha=1.0, A=dA, lda=M, B=dB, ldb=K, beta=0.0, C=dC,
                 ldc=M, mode=ec.MODE_FP16_SPLIT)
-    for bad in bad_calls:
-        args = dict(base, **bad)
-        with pytest.raises(ec.EcgemmError) as ei:
-            h.sgemm(**args)
-        assert ei.value.status == ec.ERR_INVALID_ARG, bad
+    assert h.last_error_argument() == 0
+    for call in (h.sgemm,):
+        for bad, position in bad_calls:
+            args = dict(base, **bad)
+            with pytest.raises(ec.EcgemmError) as ei:
+                call(**args)
+            assert ei.value.status == ec.ERR_INVALID_ARG, bad
+            assert ei.value.argument == position == h.last_error_argument(), (bad, ei.value.argument)
+    torch_sync = __import__("torch").cuda.synchronize
+    torch_sync()
+    assert np.all(to_host(dC, M, N) == 1.0)          # none of the refused calls touched C
     # a caller workspace that is too small is refused before anything is launched
     import torch
     ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
     h.set_workspace(ws, 1024)
     with pytest.raises(ec.EcgemmError) as ei:
         h.sgemm(**base)
-    assert ei.value.status == ec.ERR_ALLOC
-    need = h.workspace_size(M, N, K, ec.MODE_FP16_SPLIT)
+    assert ei.value.status == ec.ERR_ALLOC and ei.value.argument == 0
+    need = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_FP16_SPLIT)
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     h.set_workspace(ws, need)
     h.sgemm(**base)
@@ -295,7 +303,7 @@ def test_a_call_can_be_captured_in_a_graph_and_replayed(mode):
     h = ec.Handle()
     stream = torch.cuda.Stream()
     h.set_stream(stream.cuda_stream)
-    nbytes = h.workspace_size(M, N, K, mode_id)
+    nbytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode_id)
     workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     h.set_workspace(workspace, nbytes)
     dA, dB, dC_in = to_device(A), to_device(B), to_device(C)
