@@ -24,7 +24,7 @@
  * more than the handle holds, that call waits for the handle's stream, frees the old buffer and allocates a larger
  * one (hipStreamSynchronize, hipFree, hipMalloc) before it enqueues anything.  With a caller-provided workspace and
  * timing off, ecgemm_sgemm and ecgemm_product only launch kernels (no allocation, no memset, no wait), so they can be
- * recorded into a HIP graph.
+ * recorded into a HIP graph; ecgemm_sgemm_noalloc does the same on a workspace built into the library.
  * All calls on a handle share its workspace and nothing orders them but the stream: after ecgemm_set_stream has
  * changed the stream, the caller makes the new stream wait for the work enqueued on the old one before the next
  * product (or uses one handle per stream).
@@ -160,6 +160,26 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              int64_t M, int64_t N, int64_t K, float alpha,
                              const float *A, int64_t lda, const float *B, int64_t ldb,
                              float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
+
+/*
+ * ecgemm_sgemm for callers that cannot allocate device memory and have no workspace to hand over: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bitwise the same result as ecgemm_sgemm, but the workspace is a fixed array of ECGEMM_NOALLOC_WORKSPACE_BYTES that
+ * is part of the library's device code (each GPU the library runs on holds its copy until the process ends; its
+ * address on the handle's device is looked up once, in ecgemm_create).  The call only launches kernels: no hipMalloc,
+ * no hipFree, no memset, no event, no wait; the handle's workspace setting and its timing switch are ignored.
+ * A problem whose workspace (ecgemm_workspace_size) exceeds the array returns ECGEMM_ERR_ALLOC and enqueues nothing;
+ * 64 MiB hold, for example, 2048^3 in either mode or 1024 x 1024 x 8192 in FP16 mode.
+ * Every call on a GPU, from any handle, uses that GPU's one array, which keeps the previous call's contents (nothing
+ * in it needs clearing: every byte a product reads has been written by the same call's split pass or slices before).
+ * Calls that overlap in time on one GPU - two streams, two handles, two host threads - therefore race; calls on one
+ * stream are ordered by it.
+ */
+#define ECGEMM_NOALLOC_WORKSPACE_BYTES ((size_t)64 << 20)
+ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                     int64_t M, int64_t N, int64_t K, float alpha,
+                                     const float *A, int64_t lda, const float *B, int64_t ldb,
+                                     float beta, float *C, int64_t ldc, ecgemm_mode_t mode);
 
 /*
  * Power-of-two pre-scaling: the remedy the paper names, at the end of section "Effect of the exponent range of input

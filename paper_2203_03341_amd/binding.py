@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_plan_info.argtypes = [vp, i64, i64, i64, ctypes.c_int, ctypes.POINTER(PlanInfo)]
     lib.ecgemm_sgemm.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                  ctypes.c_int]
+    lib.ecgemm_sgemm_noalloc.argtypes = lib.ecgemm_sgemm.argtypes
     lib.ecgemm_last_error_argument.argtypes = [vp]
     lib.ecgemm_sgemm_scaled.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                         ctypes.c_int, vp, vp]
@@ -85,6 +86,9 @@ def _load() -> ctypes.CDLL:
 
 
 _lib = _load()
+
+
+NOALLOC_WORKSPACE_BYTES = 64 << 20      # ECGEMM_NOALLOC_WORKSPACE_BYTES
 
 
 class EcgemmError(RuntimeError):
@@ -153,6 +157,11 @@ class Handle:
               beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
+
+    def sgemm_noalloc(self, transA: int, transB: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int,
+                      beta: float, C, ldc: int, mode: int):
+        self._check(_lib.ecgemm_sgemm_noalloc(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
+                                              _ptr(C), ldc, mode))
 
     def sgemm_scaled(self, transA: int, transB: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int,
                      beta: float, C, ldc: int, mode: int, row_log2_scale_a, col_log2_scale_b):

@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -34,6 +35,7 @@ struct ecgemm_context {
   int log2_scale_a = 0, log2_scale_b = 0;
   ecgemm_shape_t shape = ECGEMM_SHAPE_AUTO;
   int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
+  char* builtin_workspace = nullptr;  // this device's copy of the library's built-in workspace (ecgemm_sgemm_noalloc)
   int last_error_argument = 0;
   std::vector<TimedCall> timed;
   std::vector<hipEvent_t> free_events;
@@ -458,10 +460,19 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
 }
 
 // Device memory for this call: the caller's workspace if one is set (never allocating), else the handle's own,
-// grown on demand.
-ecgemm_status_t acquire_workspace(ecgemm_handle_t h, size_t bytes, char** out) {
+// grown on demand; or the library's built-in one (never allocating either).
+enum WorkspaceKind { kWorkspaceOfHandle, kWorkspaceBuiltIn };
+ecgemm_status_t acquire_workspace(ecgemm_handle_t h, size_t bytes, char** out, WorkspaceKind kind = kWorkspaceOfHandle) {
   *out = nullptr;
   if (bytes == 0) return ECGEMM_OK;
+  if (kind == kWorkspaceBuiltIn) {
+    if (bytes > ECGEMM_NOALLOC_WORKSPACE_BYTES)
+      return fail(h, ECGEMM_ERR_ALLOC, "ecgemm_sgemm_noalloc: the problem needs " + std::to_string(bytes) +
+                                           " bytes of workspace, the built-in one has " +
+                                           std::to_string(ECGEMM_NOALLOC_WORKSPACE_BYTES));
+    *out = h->builtin_workspace;
+    return ECGEMM_OK;
+  }
   if (h->user_workspace) {
     if (h->user_bytes < bytes) return fail(h, ECGEMM_ERR_ALLOC, "caller workspace too small");
     *out = static_cast<char*>(h->user_workspace);
@@ -494,6 +505,29 @@ ecgemm_status_t check_sizes(ecgemm_handle_t h, int64_t M, int64_t N, int64_t K, 
   if (K > ((int64_t)1 << 26) || (round_up(K, kDepthPad) / 16) * parts_of(mode) * 1024 >= ((int64_t)1 << 32))
     return bad_arg(h, m_position + 2, "K too large: a packed row block must stay below 4 GiB");
   return ECGEMM_OK;
+}
+
+// ---- the workspace built into the library, for ecgemm_sgemm_noalloc.  In host code `scratch` is only a stand-in for
+// the device array: its device address, one per GPU, comes from hipGetSymbolAddress with that GPU current, and that
+// address is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[ECGEMM_NOALLOC_WORKSPACE_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_address[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.
+hipError_t builtin_workspace_of(int device, char** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_address[device] == nullptr) {
+    void* address = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&address, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (address == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_address[device] = address;
+  }
+  *out = static_cast<char*>(g_scratch_address[device]);
+  return hipSuccess;
 }
 
 hipEvent_t take_event(ecgemm_handle_t h) {
@@ -536,10 +570,16 @@ ecgemm_status_t ecgemm_create(ecgemm_handle_t* handle) {
   hipDeviceProp_t prop;
   if (hipGetDeviceProperties(&prop, device) != hipSuccess) return ECGEMM_ERR_HIP;
   if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return ECGEMM_ERR_UNSUPPORTED;
+  char* builtin = nullptr;
+  if (builtin_workspace_of(device, &builtin) != hipSuccess) {
+    (void)hipGetLastError();
+    return ECGEMM_ERR_HIP;
+  }
   ecgemm_context* ctx = new (std::nothrow) ecgemm_context();
   if (!ctx) return ECGEMM_ERR_ALLOC;
   ctx->device = device;
   ctx->compute_units = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
+  ctx->builtin_workspace = builtin;
   *handle = ctx;
   return ECGEMM_OK;
 }
@@ -825,11 +865,13 @@ ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int* calls, float* spl
 
 namespace {
 
-// ecgemm_sgemm and ecgemm_sgemm_scaled: the same parameter list up to `mode` (the positions reported for bad arguments
-// count it), then the scaling vectors.  Everything that can be refused is checked before the first launch.
+// ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc: the same parameter list up to `mode` (the positions
+// reported for bad arguments count it), then the scaling vectors and where the workspace comes from.  Everything that
+// can be refused is checked before the first launch.
 ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N, int64_t K, float alpha,
                              const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
-                             ecgemm_mode_t mode, const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
+                             ecgemm_mode_t mode, const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b,
+                             WorkspaceKind workspace_kind) {
   if (!h) return ECGEMM_ERR_INVALID_ARG;
   if (!valid_op(transA)) return bad_arg(h, 2, "ecgemm_sgemm: bad transA");
   if (!valid_op(transB)) return bad_arg(h, 3, "ecgemm_sgemm: bad transB");
@@ -864,7 +906,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
   SplitJob job_a, job_b;
   char* ws = nullptr;
-  st = acquire_workspace(h, pl.total_bytes, &ws);
+  st = acquire_workspace(h, pl.total_bytes, &ws, workspace_kind);
   if (st != ECGEMM_OK) return st;
   char* a_packed = ws;
   char* b_packed = ws + pl.a_bytes;
@@ -891,7 +933,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
     }
   } lease{h};
   TimedCall& tc = lease.tc;
-  const bool timing = h->timing;
+  const bool timing = h->timing && workspace_kind != kWorkspaceBuiltIn;  // (creating an event allocates)
   if (timing) {
     tc.start = take_event(h);
     tc.split_done = take_event(h);
@@ -928,7 +970,8 @@ ecgemm_status_t ecgemm_sgemm(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_
                              int64_t M, int64_t N, int64_t K, float alpha,
                              const float* A, int64_t lda, const float* B, int64_t ldb,
                              float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
-  return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr);
+  return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr,
+                      kWorkspaceOfHandle);
 }
 
 ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
@@ -937,7 +980,15 @@ ecgemm_status_t ecgemm_sgemm_scaled(ecgemm_handle_t handle, ecgemm_op_t transA, 
                                     float beta, float* C, int64_t ldc, ecgemm_mode_t mode,
                                     const int32_t* row_log2_scale_a, const int32_t* col_log2_scale_b) {
   return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, row_log2_scale_a,
-                      col_log2_scale_b);
+                      col_log2_scale_b, kWorkspaceOfHandle);
+}
+
+ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB,
+                                     int64_t M, int64_t N, int64_t K, float alpha,
+                                     const float* A, int64_t lda, const float* B, int64_t ldb,
+                                     float beta, float* C, int64_t ldc, ecgemm_mode_t mode) {
+  return sgemm_common(handle, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, mode, nullptr, nullptr,
+                      kWorkspaceBuiltIn);
 }
 
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,

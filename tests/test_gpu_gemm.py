@@ -242,7 +242,7 @@ def test_invalid_arguments_are_rejected():
     base = dict(transA=ec.OP_N, transB=ec.OP_N, M=M, N=N, K=K, alpha=1.0, A=dA, lda=M, B=dB, ldb=K, beta=0.0, C=dC,
                 ldc=M, mode=ec.MODE_FP16_SPLIT)
     assert h.last_error_argument() == 0
-    for call in (h.sgemm,):
+    for call in (h.sgemm, h.sgemm_noalloc):
         for bad, position in bad_calls:
             args = dict(base, **bad)
             with pytest.raises(ec.EcgemmError) as ei:

@@ -80,6 +80,7 @@ int main(void) {
   CHECK(ecgemm_set_timing(NULL, 1) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_get_timing(NULL, &i, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_sgemm(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_sgemm_noalloc(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_sgemm_scaled(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_product(NULL, 1, 1, 1, 1.0f, NULL, NULL, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_split(NULL, ECGEMM_OP_N, 1, 1, NULL, 1, ECGEMM_MODE_FP16_SPLIT, NULL) == ECGEMM_ERR_INVALID_ARG);
