@@ -62,6 +62,19 @@ typedef enum {
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 
 /*
+ * Experiment knob for the order in which output tiles are handed to the compute units (it decides what the eight XCDs'
+ * L2 caches share; the defaults are what measurements picked).  xcd_remap = 1 (default): each XCD owns a contiguous run
+ * of the tile order; 0: tiles go to workgroups in launch order and the hardware's round-robin spreads neighbours over all
+ * XCDs.  group_m > 0 forces the number of tile rows per group of the order (default 0: 4, or 8 for the 128 x 128 shape
+ * on shallow products; a value of at least the number of tile rows gives plain column-major order).  column_bands in
+ * 1 .. 8 forces the number of column bands (default 0: chosen from the size of the operand panels).  Every element is
+ * still summed in the same order, so results do not change - except that the tiles which are cut into slices along K
+ * are the last of the order, whichever those are, and a tile sums differently (to FP32 rounding) sliced than whole.
+ * Affects later ecgemm_sgemm / ecgemm_product / ecgemm_plan_info on the handle.
+ */
+ecgemm_status_t ecgemm_debug_set_tile_order(ecgemm_handle_t handle, int xcd_remap, int group_m, int column_bands);
+
+/*
  * Diagnostic: executes `count` independent v_mfma_f32_32x32x16_f16 (bf16 == 0) or _bf16 (bf16 != 0) instructions,
  * D = A B + C with A 32 x 16, B 16 x 32, C and D 32 x 32, on registers given lane by lane, so that tests can state what
  * the matrix unit does (the method's accumulation discipline, section "Avoiding RZ during Tensor Core accumulation",

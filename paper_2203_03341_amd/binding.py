@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
                                         ctypes.c_int, vp, vp]
     lib.ecgemm_row_scales.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_set_shape.argtypes = [vp, ctypes.c_int]
+    lib.ecgemm_debug_set_tile_order.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.ecgemm_set_scaling.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.ecgemm_exponent_range.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_choose_mode.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64,
@@ -173,6 +174,9 @@ class Handle:
 
     def set_shape(self, shape: int):
         self._check(_lib.ecgemm_set_shape(self._h, shape))
+
+    def debug_set_tile_order(self, xcd_remap: int, group_m: int, column_bands: int):
+        self._check(_lib.ecgemm_debug_set_tile_order(self._h, xcd_remap, group_m, column_bands))
 
     def set_scaling(self, log2_scale_a: int, log2_scale_b: int):
         self._check(_lib.ecgemm_set_scaling(self._h, log2_scale_a, log2_scale_b))

@@ -34,6 +34,7 @@ struct ecgemm_context {
   bool timing = false;
   int log2_scale_a = 0, log2_scale_b = 0;
   ecgemm_shape_t shape = ECGEMM_SHAPE_AUTO;
+  int xcd_remap = 1, forced_group_m = 0, forced_column_bands = 0;  // ecgemm_debug_set_tile_order
   int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
   char* builtin_workspace = nullptr;  // this device's copy of the library's built-in workspace (ecgemm_sgemm_noalloc)
   int last_error_argument = 0;
@@ -68,12 +69,10 @@ constexpr Shape fused_shape() {
 }
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
-#ifndef ECGEMM_PERSISTENT_MAX_K
-#define ECGEMM_PERSISTENT_MAX_K 4096
-#endif
+constexpr int kPersistentMaxK = 4096;
 const Shape kShapes[8][3] = {
-    {shape_of<Fp16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
-    {shape_of<Bf16W4>(ECGEMM_PERSISTENT_MAX_K), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
+    {shape_of<Fp16W4>(kPersistentMaxK), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
+    {shape_of<Bf16W4>(kPersistentMaxK), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
     {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
     {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
@@ -353,10 +352,8 @@ int64_t product_grid(const Plan& pl, int compute_units, bool* persistent_out) {
 // it (16384^3: 2 x 4 and 4 x 2 are 2.2 % ahead of 8 x 1; 8192^3: 4 x 2 by 2.2 %; 16384 x 16384 x 4096, where 8 panels
 // are 128 MiB: 8 x 1 is 2 % ahead of 2 x 4).  A band is at least as wide as the patch of tiles an XCD works on at one
 // time.
-int column_bands(const Plan& pl, int group_m, ecgemm_mode_t mode) {
-#ifdef ECGEMM_COLUMN_BANDS
-  return std::max(1, std::min(ECGEMM_COLUMN_BANDS, pl.tiles_n));
-#endif
+int column_bands(const Plan& pl, int group_m, ecgemm_mode_t mode, int forced = 0) {
+  if (forced > 0) return std::max(1, std::min(forced, pl.tiles_n));
   const int patch_n = 32 * pl.shape->blocks_per_cu / group_m;
   const int64_t panel_bytes = (int64_t)group_m * pl.shape->bm * pl.Kp * 2 * parts_of(mode);
   const int groups = (pl.tiles_m + group_m - 1) / group_m;
@@ -374,10 +371,10 @@ int column_bands(const Plan& pl, int group_m, ecgemm_mode_t mode) {
 // square the patch of C these cover, the fewer distinct panel rows they request per k step: 4 x 8 tiles of 256 x 128.
 // For the 128 x 128 shape (64 tiles at a time) 8 x 8 is ahead only on the shallow products the shape is chosen for
 // (2.5 % at 16384 x 16384 x 256 and x 512; 4 x 16 is 4 % ahead at 8192^3).
-#ifndef ECGEMM_GROUP_M
-#define ECGEMM_GROUP_M 4
-#endif
-int group_m_of(const Plan& pl) { return (pl.shape->bm == 128 && pl.Kp <= 512) ? 2 * ECGEMM_GROUP_M : ECGEMM_GROUP_M; }
+int group_m_of(const Plan& pl, int forced = 0) {
+  if (forced > 0) return forced;
+  return (pl.shape->bm == 128 && pl.Kp <= 512) ? 8 : 4;
+}
 
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
@@ -393,8 +390,9 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.full_tiles = pl.full_tiles;
   pp.tail_tiles = pl.tail_tiles;
   pp.tail_splits = pl.tail_splits;
-  pp.group_m = group_m_of(pl);
-  pp.column_bands = column_bands(pl, pp.group_m, mode);
+  pp.group_m = group_m_of(pl, h->forced_group_m);
+  pp.column_bands = column_bands(pl, pp.group_m, mode, h->forced_column_bands);
+  pp.xcd_remap = h->xcd_remap;
   pp.M = M;
   pp.N = N;
   pp.ldc = ldc;
@@ -612,6 +610,17 @@ ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape) {
   return ECGEMM_OK;
 }
 
+ecgemm_status_t ecgemm_debug_set_tile_order(ecgemm_handle_t handle, int xcd_remap, int group_m, int column_bands) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (xcd_remap != 0 && xcd_remap != 1) return bad_arg(handle, 2, "ecgemm_debug_set_tile_order: xcd_remap is 0 or 1");
+  if (group_m < 0 || group_m > (1 << 20)) return bad_arg(handle, 3, "ecgemm_debug_set_tile_order: bad group_m");
+  if (column_bands < 0 || column_bands > 8) return bad_arg(handle, 4, "ecgemm_debug_set_tile_order: 0 to 8 column bands");
+  handle->xcd_remap = xcd_remap;
+  handle->forced_group_m = group_m;
+  handle->forced_column_bands = column_bands;
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                                       int64_t K, ecgemm_mode_t mode, size_t* bytes) {
   if (!valid_op(transA)) return bad_arg(handle, 2, "ecgemm_workspace_size: bad transA");
@@ -653,8 +662,8 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   bool persistent = false;
   info->grid = pl.shape->fused ? (int64_t)pl.tiles_m * pl.tiles_n * pl.tail_splits : product_grid(pl, kPlanComputeUnits, &persistent);
   info->persistent = persistent ? 1 : 0;
-  info->group_m = pl.shape->fused ? 4 : group_m_of(pl);
-  info->column_bands = pl.shape->fused ? 1 : column_bands(pl, info->group_m, mode);
+  info->group_m = pl.shape->fused ? 4 : group_m_of(pl, handle ? handle->forced_group_m : 0);
+  info->column_bands = pl.shape->fused ? 1 : column_bands(pl, info->group_m, mode, handle ? handle->forced_column_bands : 0);
   info->workspace_bytes = pl.total_bytes;
   info->estimated_us = pl.shape->fused ? 0.0 : estimated_us(pl, mode);
   return ECGEMM_OK;

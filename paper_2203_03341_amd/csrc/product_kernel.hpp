@@ -53,6 +53,8 @@ struct ProductParams {
   int group_m;  // tile rows per group of the tile order (tile_coordinates)
   int column_bands;  // see tile_coordinates; with each XCD taking a contiguous run of the order, n bands of columns lay
                      // the 8 XCDs out (8 / n) x n over the tile grid
+  int xcd_remap;     // 1 (always, outside experiments): each XCD owns a contiguous run of the tile order; 0: workgroup b
+                     // takes item b, b + gridDim.x, ... and the hardware's round-robin decides which XCD that is
   int64_t M, N, ldc;
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
@@ -264,12 +266,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     int tile_m, tile_n, kt_begin, kt_count;
     int partial;  // index of the [BN][BM] partial tile this item writes, or -1 if it writes C
   };
-#ifndef ECGEMM_XCD_REMAP
-#define ECGEMM_XCD_REMAP 1
-#endif
-#ifndef ECGEMM_READ_TAIL
-#define ECGEMM_READ_TAIL 6
-#endif
+  constexpr int kReadTail = 6;  // matrix-instruction slots at the end of a k step that carry no fragment read
   const int tail_items = p.tail_tiles * p.tail_splits;
   auto locate = [&](int item) {
     Work w;
@@ -292,7 +289,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   };
   // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.
   int slot, slot_end, slot_stride, full_start = 0, full_count = p.full_tiles, tail_start = 0;
-  if (ECGEMM_XCD_REMAP) {
+  if (p.xcd_remap) {
     constexpr int kXcds = 8;  // gridDim.x is a multiple of 8
     const int xcd = blockIdx.x % kXcds;
     auto share = [&](int n, int& start, int& count) {  // XCD x's part of n things dealt out in contiguous runs
@@ -420,10 +417,10 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[l] + voff),
                                          (void __attribute__((address_space(3)))*)(load_stage + l * Cfg::WAVES * 1024), 16, 0, 0);
       });
-      // (the reads stop ECGEMM_READ_TAIL slots before the end of the step, so that the last of them has arrived
+      // (the reads stop kReadTail slots before the end of the step, so that the last of them has arrived
       // when the wave gets to the wait in front of the barrier or of the next step)
       // (two slots in a step of twelve instructions or fewer, the 128 x 128 FP16 shape: 1 to 2 %)
-      constexpr int SPAN = M > 2 * ECGEMM_READ_TAIL ? M - ECGEMM_READ_TAIL : M > 4 ? M - 2 : M;
+      constexpr int SPAN = M > 2 * kReadTail ? M - kReadTail : M > 4 ? M - 2 : M;
       constexpr int r_begin = m < SPAN ? m * READS / SPAN : READS, r_end = m + 1 < SPAN ? (m + 1) * READS / SPAN : READS;
       static_for<r_end - r_begin>([&](auto d_c) {
         constexpr int r = r_begin + decltype(d_c)::value;

@@ -467,6 +467,35 @@ def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
         assert np.array_equal(outs[0].view(np.uint32), other.view(np.uint32))
 
 
+def test_the_tile_order_knob_moves_tiles_between_xcds_and_changes_no_bit():
+    """ecgemm_debug_set_tile_order (the experiment knob behind the block-order profiles): hardware round-robin instead
+    of contiguous runs per XCD, plain column-major order, forced column bands.  Where no tile is sliced along K the
+    result is the same bit for bit; where the last tiles of the order are sliced, which tiles those are moves with the
+    order, and the results agree to FP32 rounding."""
+    import torch
+    import paper_2203_03341_amd as ec
+    for K, sliced in ((768, False), (1536, True)):
+        M, N = 2048 + 256, 4096 + 128
+        A, B = _inputs(M, N, K, "N", "T", "urand", 21)
+        h = ec.Handle()
+        ref = _gpu_sgemm("N", "T", M, N, K, 1.0, A, B, 0.0, None, "fp16", handle=h)
+        assert (h.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["sliced_tiles"] > 0) == sliced
+        for order in [(0, 0, 0), (0, 1024, 1), (1, 1, 8), (1, 3, 5), (0, 2, 2)]:
+            h.debug_set_tile_order(*order)
+            info = h.plan_info(M, N, K, ec.MODE_FP16_SPLIT)
+            assert (order[1] == 0 or info["group_m"] == order[1]) and (order[2] == 0 or info["column_bands"] == order[2])
+            got = _gpu_sgemm("N", "T", M, N, K, 1.0, A, B, 0.0, None, "fp16", handle=h)
+            if sliced:
+                assert gemm.relative_residual(ref, got) < 2e-7, order
+            else:
+                assert np.array_equal(got, ref), order
+        with pytest.raises(ec.EcgemmError) as err:
+            h.debug_set_tile_order(2, 0, 0)
+        assert err.value.argument == 2
+        h.destroy()
+    torch.cuda.synchronize()
+
+
 def test_a_shape_the_mode_has_no_kernel_for_is_refused():
     import paper_2203_03341_amd as ec
     h = ec.Handle()

@@ -77,6 +77,7 @@ int main(void) {
   CHECK(ecgemm_set_workspace(NULL, NULL, 0) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_set_shape(NULL, ECGEMM_SHAPE_AUTO) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_set_scaling(NULL, 0, 0) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_debug_set_tile_order(NULL, 1, 0, 0) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_set_timing(NULL, 1) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_get_timing(NULL, &i, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_sgemm(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
