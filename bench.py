@@ -257,17 +257,22 @@ def power_while(torch, call, flops, seconds):
         return None
     watts, mhz, stop_flag = [], [], threading.Event()
 
-    def read(name, scale, into):
-        try:
-            with open(os.path.join(node, name)) as f:
-                into.append(int(f.read()) * scale)
-        except (OSError, ValueError):
-            pass
+    clock_file = os.path.join(node, "..", "..", "pp_dpm_sclk")      # the device's shader clock: the starred line is current
 
     def sampler():
         while not stop_flag.is_set():
-            read("power1_input", 1e-6, watts)        # microwatts
-            read("freq1_input", 1e-6, mhz)           # hertz (the shader clock)
+            try:
+                with open(os.path.join(node, "power1_input")) as f:
+                    watts.append(int(f.read()) * 1e-6)               # microwatts
+            except (OSError, ValueError):
+                pass
+            try:
+                with open(clock_file) as f:
+                    for line in f:
+                        if line.rstrip().endswith("*"):              # e.g. "1: 1290Mhz *"
+                            mhz.append(float(line.split(":")[1].lower().split("mhz")[0]))
+            except (OSError, ValueError, IndexError):
+                pass
             time.sleep(0.02)
 
     th = threading.Thread(target=sampler)

@@ -75,6 +75,16 @@ ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 ecgemm_status_t ecgemm_debug_set_tile_order(ecgemm_handle_t handle, int xcd_remap, int group_m, int column_bands);
 
 /*
+ * Host only, for tests: the coordinates of output tile number 0, 1, ... in the order in which ecgemm_sgemm on this
+ * handle would hand the tiles of this problem out (ecgemm_plan_info gives tiles_m x tiles_n, the size the two host
+ * arrays must have; `handle` may be NULL as there).  The kernels find a tile's coordinates with multiplications by
+ * reciprocals that the host prepares; `disagreements` (host pointer) receives the number of tiles for which that
+ * arithmetic and plain integer division give different coordinates, which must be 0.  Not for the fused shape.
+ */
+ecgemm_status_t ecgemm_debug_tile_order(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
+                                        int32_t *tile_m, int32_t *tile_n, int64_t *disagreements);
+
+/*
  * Diagnostic: executes `count` independent v_mfma_f32_32x32x16_f16 (bf16 == 0) or _bf16 (bf16 != 0) instructions,
  * D = A B + C with A 32 x 16, B 16 x 32, C and D 32 x 32, on registers given lane by lane, so that tests can state what
  * the matrix unit does (the method's accumulation discipline, section "Avoiding RZ during Tensor Core accumulation",

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_debug_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -65,6 +65,7 @@ def _load() -> ctypes.CDLL:
     lib.ecgemm_row_scales.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
     lib.ecgemm_set_shape.argtypes = [vp, ctypes.c_int]
     lib.ecgemm_debug_set_tile_order.argtypes = [vp, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.ecgemm_debug_tile_order.argtypes = [vp, i64, i64, i64, ctypes.c_int, vp, vp, ctypes.POINTER(i64)]
     lib.ecgemm_set_scaling.argtypes = [vp, ctypes.c_int, ctypes.c_int]
     lib.ecgemm_exponent_range.argtypes = [vp, i64, i64, vp, i64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_choose_mode.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, vp, i64, vp, i64,
@@ -234,6 +235,24 @@ def plan_info(M: int, N: int, K: int, mode: int) -> dict:
     if st != OK:
         raise EcgemmError(st, "ecgemm_plan_info")
     return info.as_dict()
+
+
+def debug_tile_order(M: int, N: int, K: int, mode: int, handle=None):
+    """(tile_m, tile_n, disagreements): coordinates of the output tiles in hand-out order (numpy int32 arrays) and the
+    number of tiles on which the kernels' reciprocal arithmetic and plain division disagree."""
+    import numpy as np
+    info = PlanInfo()
+    h = handle._h if handle is not None else None
+    st = _lib.ecgemm_plan_info(h, M, N, K, mode, ctypes.byref(info))
+    if st != OK:
+        raise EcgemmError(st, "ecgemm_plan_info")
+    tiles = info.tiles_m * info.tiles_n
+    tile_m, tile_n = np.full(tiles, -1, dtype=np.int32), np.full(tiles, -1, dtype=np.int32)
+    bad = ctypes.c_int64(-1)
+    st = _lib.ecgemm_debug_tile_order(h, M, N, K, mode, tile_m.ctypes.data, tile_n.ctypes.data, ctypes.byref(bad))
+    if st != OK:
+        raise EcgemmError(st, "ecgemm_debug_tile_order")
+    return tile_m, tile_n, bad.value
 
 
 def split_size(rows: int, depth: int, mode: int) -> int:

@@ -35,6 +35,15 @@ def _run(cmd):
     return err
 
 
+def _check_no_kernel_left_undefined(lib: str) -> None:
+    """Every kernel is compiled in one translation unit and only declared in the others; a kernel that its own unit
+    failed to emit would stay an undefined symbol of the library and only show when it is first launched."""
+    res = subprocess.run(["nm", "-D", "-C", "--undefined-only", lib], capture_output=True, text=True)
+    missing = [l.strip() for l in res.stdout.splitlines() if "ecgemm::" in l]
+    if missing:
+        raise RuntimeError("kernels declared but compiled nowhere:\n" + "\n".join(missing))
+
+
 def build(verbose: bool = False, extra_flags=(), lib: str = LIB, obj_dir: str = OBJ_DIR) -> str:
     os.makedirs(obj_dir, exist_ok=True)
     srcs = sources()
@@ -43,6 +52,7 @@ def build(verbose: bool = False, extra_flags=(), lib: str = LIB, obj_dir: str = 
     with ThreadPoolExecutor(jobs) as pool:
         logs = list(pool.map(lambda so: _run([HIPCC, *FLAGS, *extra_flags, "-c", so[0], "-o", so[1]]), zip(srcs, objs)))
     logs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]))
+    _check_no_kernel_left_undefined(lib)
     if verbose:
         for log in logs:
             if log.strip():

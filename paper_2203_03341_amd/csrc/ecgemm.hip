@@ -385,13 +385,14 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   pp.b_packed = static_cast<const char*>(b_packed);
   pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
   pp.k_tiles = pl.k_tiles;
-  pp.tiles_m = pl.tiles_m;
-  pp.tiles_n = pl.tiles_n;
   pp.full_tiles = pl.full_tiles;
   pp.tail_tiles = pl.tail_tiles;
   pp.tail_splits = pl.tail_splits;
-  pp.group_m = group_m_of(pl, h->forced_group_m);
-  pp.column_bands = column_bands(pl, pp.group_m, mode, h->forced_column_bands);
+  pp.kt_per_split = (pl.k_tiles + pl.tail_splits - 1) / pl.tail_splits;
+  pp.by_tail_tiles = fast_divisor(pl.tail_tiles);
+  const int group_m = group_m_of(pl, h->forced_group_m);
+  const int bands = column_bands(pl, group_m, mode, h->forced_column_bands);
+  pp.order = make_tile_order(pl.tiles_m, pl.tiles_n, group_m, bands);
   pp.xcd_remap = h->xcd_remap;
   pp.M = M;
   pp.N = N;
@@ -410,7 +411,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
-                       pl.full_tiles, pl.tiles_m, pl.tiles_n, pp.group_m, pp.column_bands, M, N, alpha, beta, C, ldc);
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, group_m, bands, M, N, alpha, beta, C, ldc);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -618,6 +619,33 @@ ecgemm_status_t ecgemm_debug_set_tile_order(ecgemm_handle_t handle, int xcd_rema
   handle->xcd_remap = xcd_remap;
   handle->forced_group_m = group_m;
   handle->forced_column_bands = column_bands;
+  return ECGEMM_OK;
+}
+
+ecgemm_status_t ecgemm_debug_tile_order(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
+                                        int32_t* tile_m, int32_t* tile_n, int64_t* disagreements) {
+  if (M <= 0) return bad_arg(handle, 2, "ecgemm_debug_tile_order: M must be positive");
+  if (N <= 0) return bad_arg(handle, 3, "ecgemm_debug_tile_order: N must be positive");
+  if (K <= 0) return bad_arg(handle, 4, "ecgemm_debug_tile_order: K must be positive");
+  if (!valid_mode(mode)) return bad_arg(handle, 5, "ecgemm_debug_tile_order: unknown mode");
+  if (!tile_m) return bad_arg(handle, 6, "ecgemm_debug_tile_order: null output");
+  if (!tile_n) return bad_arg(handle, 7, "ecgemm_debug_tile_order: null output");
+  if (!disagreements) return bad_arg(handle, 8, "ecgemm_debug_tile_order: null output");
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
+  if (st != ECGEMM_OK) return st;
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  if (!pl.shape || pl.shape->fused) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_debug_tile_order: no product kernel of this shape and mode");
+  const int group_m = group_m_of(pl, handle ? handle->forced_group_m : 0);
+  const int bands = column_bands(pl, group_m, mode, handle ? handle->forced_column_bands : 0);
+  const TileOrder order = make_tile_order(pl.tiles_m, pl.tiles_n, group_m, bands);
+  *disagreements = 0;
+  for (int pid = 0; pid < pl.tiles_m * pl.tiles_n; ++pid) {
+    int m = -1, n = -1, m_plain = -1, n_plain = -1;
+    tile_coordinates(pid, order, m, n);
+    tile_coordinates(pid, pl.tiles_m, pl.tiles_n, group_m, bands, m_plain, n_plain);
+    if (m != m_plain || n != n_plain) *disagreements += 1;
+    tile_m[pid] = m, tile_n[pid] = n;
+  }
   return ECGEMM_OK;
 }
 

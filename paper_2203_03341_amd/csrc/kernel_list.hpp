@@ -19,7 +19,7 @@ namespace ecgemm {
 // 2 % ahead of W4, usually 1 % behind.)
 typedef ProductConfig<kMethodFp16Split, 256, 128, 128, 64, 2, 3, 1> Fp16W4;     // 3 x 48 KiB of LDS
 typedef ProductConfig<kMethodFp16Split, 128, 128, 64, 64, 1, 4, 2> Fp16X2;      // 4 x 16 KiB of LDS per block
-typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 2, 2, 1> Bf16W4;      // 2 x 72 KiB (1 % ahead of 4 x 36 KiB)
+typedef ProductConfig<kMethodBf16Full, 256, 128, 128, 64, 2, 2, 1> Bf16W4;      // 2 x 72 KiB (4 x 36 and 3 x 36 KiB: within 0.5 %)
 typedef ProductConfig<kMethodBf16Full, 128, 128, 64, 64, 1, 3, 2> Bf16X2;       // 3 x 24 KiB per block
 // comparison methods: the W4 shape only
 typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisConfig;

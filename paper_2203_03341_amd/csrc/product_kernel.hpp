@@ -40,31 +40,6 @@ namespace ecgemm {
 
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
-struct ProductParams {
-  const char* a_packed;     // [Mp/32][k_steps][NP][64][8] 16-bit
-  const char* b_packed;     // [Np/32][k_steps][NP][64][8] 16-bit
-  int64_t row_block_bytes;  // k_steps * NP * 1024
-  int k_tiles;              // depth_padded / (16 * K_STEPS): LDS stages along K
-  int tiles_m, tiles_n;
-  // Work items: the first full_tiles output tiles (in the order of tile_coordinates) are one item each, over the whole
-  // depth; each of the remaining tail_tiles is tail_splits items, one per slice of the depth, which leave raw sums in
-  // `partials` for reduce_tail_kernel.  tail_splits == 1: those tiles are whole items too and nothing goes to partials.
-  int full_tiles, tail_tiles, tail_splits;
-  int group_m;  // tile rows per group of the tile order (tile_coordinates)
-  int column_bands;  // see tile_coordinates; with each XCD taking a contiguous run of the order, n bands of columns lay
-                     // the 8 XCDs out (8 / n) x n over the tile grid
-  int xcd_remap;     // 1 (always, outside experiments): each XCD owns a contiguous run of the tile order; 0: workgroup b
-                     // takes item b, b + gridDim.x, ... and the hardware's round-robin decides which XCD that is
-  int64_t M, N, ldc;
-  float alpha, beta;
-  float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
-  // per-row / per-column pre-scaling (both null, or both set): element (m, n) of the product is multiplied by
-  // 2^-row_log2_scale[m] and then by 2^-col_log2_scale[n] before alpha / beta
-  const int* row_log2_scale;  // device, M entries
-  const int* col_log2_scale;  // device, N entries
-  float* C;
-  float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
-};
 
 // 2^e as a float, e in [-126, 127]
 __device__ __forceinline__ float exp2_int(int e) { return __builtin_bit_cast(float, (unsigned)(e + 127) << 23); }
@@ -72,7 +47,16 @@ __device__ __forceinline__ float exp2_int(int e) { return __builtin_bit_cast(flo
 // An element of C is written once and not read again by this call: a non-temporal store keeps it from pushing the
 // operand panels out of the L2 (measured: 19 % off the 256 x 128 kernel and 4 % off the 128 x 128 kernel at
 // 16384 x 16384 x 256, where C is most of the traffic; nothing lost at 16384^3).
-__device__ __forceinline__ void store_result(float* dst, float value) { __builtin_nontemporal_store(value, dst); }
+// (Through a pointer known to be global memory: a generic pointer makes these FLAT instructions, which also count
+// against the LDS counter that the fragment reads of the main loop wait on.)
+typedef __attribute__((address_space(1))) float global_float_t;
+__device__ __forceinline__ void store_result(float* dst, float value) {
+  __builtin_nontemporal_store(value, (global_float_t*)dst);
+}
+__device__ __forceinline__ float load_global(const float* src) { return *(const global_float_t*)src; }
+__device__ __forceinline__ int load_global(const int* src) { return *(const __attribute__((address_space(1))) int*)src; }
+// partial sums are read again soon by the kernel that adds the slices: an ordinary store
+__device__ __forceinline__ void store_partial(float* dst, float value) { *(global_float_t*)dst = value; }
 
 // alpha c + beta C_in with the roundings fixed (alpha c rounded, then one fused multiply-add), so that the compiler
 // cannot pick a different contraction in each kernel and every kernel shape gives the same bits.
@@ -83,8 +67,8 @@ __device__ __forceinline__ float scaled_sum(float alpha, float c, float beta, fl
 // Output tile number -> tile coordinates.  The tile grid is cut into column_bands bands of (nearly) equal width, taken
 // one after the other; inside a band the tiles go in groups of group_m tile rows, each walked column by column, so
 // that tiles with neighbouring numbers share A and B panels.  column_bands <= tiles_n.
-__device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int group_m, int column_bands, int& tile_m,
-                                                 int& tile_n) {
+__host__ __device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles_n, int group_m, int column_bands,
+                                                          int& tile_m, int& tile_n) {
   const int narrow = tiles_n / column_bands, wider = tiles_n % column_bands;  // the first `wider` bands have narrow + 1 columns
   const int tiles_wide = (narrow + 1) * tiles_m;
   int width, first_n;
@@ -103,10 +87,102 @@ __device__ __forceinline__ void tile_coordinates(int pid, int tiles_m, int tiles
   const int group_size = group_m * width;
   const int group = pid / group_size;
   const int first_m = group * group_m;
-  const int rows_here = min(tiles_m - first_m, group_m);
+  const int rows_here = tiles_m - first_m < group_m ? tiles_m - first_m : group_m;
   tile_m = first_m + (pid % group_size) % rows_here;
   tile_n = first_n + (pid % group_size) / rows_here;
 }
+
+// Division of 0 <= n < 2^31 by a divisor known to the host before the launch: one multiply-high and a shift instead of
+// the forty-odd instructions of a 32-bit division (the tile arithmetic of an item sits on the critical path between
+// two main loops, and a wave issues one instruction every four or five cycles).  With l = ceil(log2 d) and
+// mul = ceil(2^(31 + l) / d), floor(n mul / 2^(31 + l)) = floor(n / d) for every n < 2^31.  mul == 0 stands for d == 1.
+struct FastDivisor {
+  unsigned mul, shift;
+};
+inline FastDivisor fast_divisor(int d) {  // d >= 1
+  if (d <= 1) return FastDivisor{0u, 0u};
+  unsigned l = 0;
+  while ((1ull << l) < (unsigned long long)d) ++l;  // l = ceil(log2 d) >= 1
+  const unsigned long long two = 1ull << (31 + l);
+  return FastDivisor{(unsigned)((two + d - 1) / d), l - 1};
+}
+__host__ __device__ __forceinline__ int fast_div(int n, FastDivisor f) {
+  return f.mul ? (int)((unsigned)(((unsigned long long)(unsigned)n * f.mul) >> 32) >> f.shift) : n;
+}
+
+// The tile order of tile_coordinates with everything that does not depend on the tile number worked out on the host.
+struct TileOrder {
+  int tiles_m, tiles_n, group_m, column_bands;
+  int narrow, wider;             // tiles_n / column_bands and tiles_n % column_bands: the first `wider` bands have narrow + 1 columns
+  int tiles_wide, tiles_narrow;  // tiles of a band of either width
+  FastDivisor by_tiles_wide, by_tiles_narrow, by_group_wide, by_group_narrow, by_group_m, by_last_rows;
+};
+inline TileOrder make_tile_order(int tiles_m, int tiles_n, int group_m, int column_bands) {
+  TileOrder o;
+  o.tiles_m = tiles_m, o.tiles_n = tiles_n, o.group_m = group_m, o.column_bands = column_bands;
+  o.narrow = tiles_n / column_bands, o.wider = tiles_n % column_bands;
+  o.tiles_wide = (o.narrow + 1) * tiles_m, o.tiles_narrow = o.narrow * tiles_m;
+  o.by_tiles_wide = fast_divisor(o.tiles_wide);
+  o.by_tiles_narrow = fast_divisor(o.tiles_narrow);
+  o.by_group_wide = fast_divisor(group_m * (o.narrow + 1));
+  o.by_group_narrow = fast_divisor(group_m * o.narrow);
+  o.by_group_m = fast_divisor(group_m);
+  o.by_last_rows = fast_divisor(tiles_m % group_m);  // rows of the last, shorter group of tile rows (if there is one)
+  return o;
+}
+// tile_coordinates(pid, o.tiles_m, o.tiles_n, o.group_m, o.column_bands, ...) without a division
+__host__ __device__ __forceinline__ void tile_coordinates(int pid, const TileOrder& o, int& tile_m, int& tile_n) {
+  int width, first_n;
+  FastDivisor by_group;
+  if (pid < o.wider * o.tiles_wide) {
+    const int band = fast_div(pid, o.by_tiles_wide);
+    pid -= band * o.tiles_wide;
+    width = o.narrow + 1;
+    first_n = band * width;
+    by_group = o.by_group_wide;
+  } else {
+    pid -= o.wider * o.tiles_wide;
+    const int band = fast_div(pid, o.by_tiles_narrow);
+    pid -= band * o.tiles_narrow;
+    width = o.narrow;
+    first_n = o.wider * (o.narrow + 1) + band * o.narrow;
+    by_group = o.by_group_narrow;
+  }
+  const int group = fast_div(pid, by_group);
+  const int first_m = group * o.group_m;
+  const int rest = pid - group * (o.group_m * width);
+  const int rows_here = o.tiles_m - first_m < o.group_m ? o.tiles_m - first_m : o.group_m;
+  const int column = fast_div(rest, rows_here == o.group_m ? o.by_group_m : o.by_last_rows);
+  tile_m = first_m + (rest - column * rows_here);
+  tile_n = first_n + column;
+}
+
+struct ProductParams {
+  const char* a_packed;     // [Mp/32][k_steps][NP][64][8] 16-bit
+  const char* b_packed;     // [Np/32][k_steps][NP][64][8] 16-bit
+  int64_t row_block_bytes;  // k_steps * NP * 1024
+  int k_tiles;              // depth_padded / (16 * K_STEPS): LDS stages along K
+  // Work items: the first full_tiles output tiles (in the order of tile_coordinates) are one item each, over the whole
+  // depth; each of the remaining tail_tiles is tail_splits items, one per slice of the depth, which leave raw sums in
+  // `partials` for reduce_tail_kernel.  tail_splits == 1: those tiles are whole items too and nothing goes to partials.
+  int full_tiles, tail_tiles, tail_splits;
+  int kt_per_split;            // ceil(k_tiles / tail_splits)
+  FastDivisor by_tail_tiles;
+  // Tile order (tile_coordinates): group_m tile rows per group; with each XCD taking a contiguous run of the order,
+  // column_bands bands of columns lay the 8 XCDs out (8 / column_bands) x column_bands over the tile grid
+  TileOrder order;
+  int xcd_remap;     // 1 (always, outside experiments): each XCD owns a contiguous run of the tile order; 0: workgroup b
+                     // takes item b, b + gridDim.x, ... and the hardware's round-robin decides which XCD that is
+  int64_t M, N, ldc;
+  float alpha, beta;
+  float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
+  // per-row / per-column pre-scaling (both null, or both set): element (m, n) of the product is multiplied by
+  // 2^-row_log2_scale[m] and then by 2^-col_log2_scale[n] before alpha / beta
+  const int* row_log2_scale;  // device, M entries
+  const int* col_log2_scale;  // device, N entries
+  float* C;
+  float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
+};
 
 // The matrix instruction per element type of the packed operands.  `sub` picks one of the four 2-deep steps that an
 // FP32 fragment (four floats per lane) holds; the 16-bit fragments are consumed whole.
@@ -251,6 +327,8 @@ template <class Cfg>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kernel(const ProductParams p) {
   constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::STAGES;
   typedef typename Mfma<Cfg::kElem>::frag_t frag_t;
+  // The ring of stages.  (It must stay the only LDS object of the kernel: with a second one the compiler starts to guard
+  // every fragment read with a wait for all LDS-DMA loads in flight, which serialises the ring: 30 % slower.)
   __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
   const int lane = threadIdx.x & 63;
@@ -275,19 +353,21 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     w.kt_count = p.k_tiles;
     w.partial = -1;
     if (item >= p.full_tiles) {
-      const int j = item - p.full_tiles, split = j / p.tail_tiles;
-      pid = p.full_tiles + j % p.tail_tiles;
+      const int j = item - p.full_tiles, split = fast_div(j, p.by_tail_tiles);
+      pid = p.full_tiles + (j - split * p.tail_tiles);
       if (p.tail_splits > 1) {
-        const int kt_per_split = (p.k_tiles + p.tail_splits - 1) / p.tail_splits;
-        w.kt_begin = split * kt_per_split;
-        w.kt_count = max(0, min(p.k_tiles, w.kt_begin + kt_per_split) - w.kt_begin);
+        w.kt_begin = split * p.kt_per_split;
+        w.kt_count = max(0, min(p.k_tiles, w.kt_begin + p.kt_per_split) - w.kt_begin);
         w.partial = j;
       }
     }
-    tile_coordinates(pid, p.tiles_m, p.tiles_n, p.group_m, p.column_bands, w.tile_m, w.tile_n);
+    tile_coordinates(pid, p.order, w.tile_m, w.tile_n);
     return w;
   };
-  // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.
+  // This block's list of items: position `slot`, slot + slot_stride, ... below slot_end.  (Handing the items of a
+  // persistent grid out through atomic counters instead, so that workgroups that finish early take more, was built
+  // and measured for the two-per-unit shape: 3 to 30 % slower than one workgroup per item, which the hardware
+  // dispatches as slots free up.)
   int slot, slot_end, slot_stride, full_start = 0, full_count = p.full_tiles, tail_start = 0;
   if (p.xcd_remap) {
     constexpr int kXcds = 8;  // gridDim.x is a multiple of 8
@@ -319,29 +399,40 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   // addresses are wave-uniform (scalar registers) plus 16 bytes per lane.
   constexpr int kLoads = Cfg::LOADS, kALoads = Cfg::A_CHUNKS / Cfg::WAVES;
   const unsigned lane_bytes = lane * 16;
-  unsigned k_off = 0;  // bytes from the first tile of the current item to the next tile to request
-  const char* src[kLoads];
-  auto point_sources = [&](const Work& w) {
+  // What changes from item to item are two addresses, those of the item's first tile in A and in B; this wave's load i
+  // starts a fixed distance behind one of them.
+  struct Source {
+    const char* a;
+    const char* b;
+  };
+  auto source_of = [&](const Work& w) {
+    const int64_t first_tile = (int64_t)w.kt_begin * (Cfg::ROW_CHUNKS * 1024);
+    return Source{p.a_packed + (int64_t)w.tile_m * (Cfg::BM / 32) * p.row_block_bytes + first_tile,
+                  p.b_packed + (int64_t)w.tile_n * (Cfg::BN / 32) * p.row_block_bytes + first_tile};
+  };
+  const char* src[kLoads];  // of the item whose tiles are being requested
+  unsigned k_off = 0;       // bytes from the first tile of that item to the next tile to request
+  auto point_sources = [&](const Source& from) {
     k_off = 0;
 #pragma unroll
     for (int i = 0; i < kLoads; ++i) {
-      const bool from_a = i < kALoads;
-      const int c = (from_a ? i : i - kALoads) * Cfg::WAVES + wave;
-      const int64_t first_row_block = from_a ? (int64_t)w.tile_m * (Cfg::BM / 32) : (int64_t)w.tile_n * (Cfg::BN / 32);
-      src[i] = (from_a ? p.a_packed : p.b_packed) + (first_row_block + c / Cfg::ROW_CHUNKS) * p.row_block_bytes +
-               (int64_t)w.kt_begin * (Cfg::ROW_CHUNKS * 1024) + (c % Cfg::ROW_CHUNKS) * 1024;
+      const int c = (i < kALoads ? i : i - kALoads) * Cfg::WAVES + wave;
+      src[i] = (i < kALoads ? from.a : from.b) + (int64_t)(c / Cfg::ROW_CHUNKS) * p.row_block_bytes + (c % Cfg::ROW_CHUNKS) * 1024;
     }
   };
+  // (returned as a plain pointer: a lambda whose return type carries an address space silently invalidates the host
+  // side's instantiation of the kernel, and with it the launch stub)
+  auto load_address = [&](int i, unsigned voff) { return src[i] + voff; };
   auto issue_stage = [&](int buf) {  // requests the next tile not yet requested, then moves on by one tile
     char* stage = lds + buf * Cfg::STAGE_BYTES + wave * 1024;
     // one 32-bit vector offset per tile; kept opaque inside this block so that every address folds to
-    // "scalar base + vector offset" and the scalar bases never change
+    // "scalar base + vector offset"
     unsigned voff = lane_bytes + k_off;
     asm volatile("" : "+v"(voff));
 #pragma unroll
     for (int i = 0; i < kLoads; ++i)
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + voff),
-                                       (void __attribute__((address_space(3)))*)(stage + i * Cfg::WAVES * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)load_address(i, voff), (void __attribute__((address_space(3)))*)(stage + i * Cfg::WAVES * 1024),
+                                       16, 0, 0);
     k_off += Cfg::ROW_CHUNKS * 1024;
   };
 
@@ -364,16 +455,38 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   };
 
   float16_t acc_main[TM][TN], acc_corr[TM][TN];
+  // Zeroing through the matrix unit: 0 x 0 + 0 written by one instruction per 32 x 32 tile instead of sixteen register
+  // writes (256 instructions for the 256 x 128 shape: a microsecond per item at one instruction every four or five
+  // cycles, while the matrix pipes have nothing to do).  The zero fragment is opaque so that nothing is folded away.
   auto clear_accumulators = [&]() {
+    if constexpr (Cfg::BLOCKS_PER_CU > 1) {
+      frag_t zero_fragment;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+      for (int e = 0; e < (int)(sizeof(frag_t) / sizeof(zero_fragment[0])); ++e) zero_fragment[e] = 0;
+      asm volatile("" : "+v"(zero_fragment));
+      float16_t zero;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          acc_main[i][j][v] = 0.0f;
-          acc_corr[i][j][v] = 0.0f;
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc_main[i][j] = Mfma<Cfg::kElem>::run(zero_fragment, zero_fragment, zero, 0);
+          acc_corr[i][j] = Mfma<Cfg::kElem>::run(zero_fragment, zero_fragment, zero, 0);
         }
+    } else {
+      // (the 256 x 128 shape, with every register in use, is spilled by the compiler when its accumulators are set by
+      // matrix instructions here; it keeps the plain writes)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            acc_main[i][j][v] = 0.0f;
+            acc_corr[i][j][v] = 0.0f;
+          }
+    }
   };
 
   // One k step, in a fixed order.  Matrix instruction m of the step (term by term over all TM x TN tiles) is followed
@@ -382,8 +495,11 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   // occupies the pipe for 8 passes, so whatever is issued behind it is free.  The fence after every slot keeps the
   // compiler's scheduler from regrouping them: left to itself it issued the loads in one burst and put dependent
   // matrix instructions next to each other.
-  auto fused_step = [&](auto set_c, auto load_c, auto read_set_c, int load_buf, int read_buf, auto read_ks_c) {
+  auto fused_step = [&](auto set_c, auto load_c, auto read_set_c, int load_buf, int read_buf, auto read_ks_c, bool load_now = true) {
     constexpr int SET = decltype(set_c)::value, READ_SET = decltype(read_set_c)::value, READ_KS = decltype(read_ks_c)::value;
+    // load_c: 0 no loads, 1 loads, 2 loads if load_now (each load under a scalar branch of its own, so that the matrix
+    // instructions stay one straight line whichever way it goes)
+    constexpr bool kLoadsDecidedHere = decltype(load_c)::value == 2;
     constexpr int LOADS = decltype(load_c)::value != 0 ? kLoads : 0, READS = READ_SET >= 0 ? Cfg::FRAG_READS : 0;
     constexpr int M = Cfg::MFMAS;
     char* load_stage = lds + load_buf * Cfg::STAGE_BYTES + wave * 1024;
@@ -393,7 +509,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     unsigned voff = lane_bytes + k_off;
     if constexpr (LOADS > 0) {
       asm volatile("" : "+v"(voff));
-      k_off += Cfg::ROW_CHUNKS * 1024;
+      if (!kLoadsDecidedHere || load_now) k_off += Cfg::ROW_CHUNKS * 1024;
     }
     static_for<M>([&](auto m_c) {
       constexpr int m = decltype(m_c)::value;
@@ -414,8 +530,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
       }
       static_for<(m + 1) * LOADS / M - m * LOADS / M>([&](auto d_c) {
         constexpr int l = m * LOADS / M + decltype(d_c)::value;
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[l] + voff),
-                                         (void __attribute__((address_space(3)))*)(load_stage + l * Cfg::WAVES * 1024), 16, 0, 0);
+        if (!kLoadsDecidedHere || load_now)
+          __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)load_address(l, voff), (void __attribute__((address_space(3)))*)(load_stage + l * Cfg::WAVES * 1024),
+                                           16, 0, 0);
       });
       // (the reads stop kReadTail slots before the end of the step, so that the last of them has arrived
       // when the wave gets to the wait in front of the barrier or of the next step)
@@ -439,6 +556,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   };
   typedef std::integral_constant<int, 0> none_t;
   typedef std::integral_constant<int, 1> loads_t;
+  typedef std::integral_constant<int, 2> loads_if_t;
   typedef std::integral_constant<int, -1> no_reads_t;
   typedef std::integral_constant<int, 0> set0_t;
   typedef std::integral_constant<int, 1> set1_t;
@@ -454,62 +572,130 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
   };
-  typedef std::integral_constant<int, (S - 2) * Cfg::LOADS> steady_t;
 
-  // ---- main loop of one item.  Tile t lives in buffer t % STAGES; tiles t + 1 .. t + STAGES - 1 are in flight
-  // while tile t is multiplied.  The barrier of iteration t comes when every wave holds the last fragments of
-  // buffer t % STAGES in registers: the buffer is then refilled with tile t + STAGES, and the first
-  // fragments of tile t + 1 are fetched under the matrix instructions that follow.
-  auto request_first_stages = [&](const Work& w) {
-    point_sources(w);
-    const int prefetched = min(S, w.kt_count);
-    for (int s = 0; s < prefetched; ++s) issue_stage(s);
+  // ---- the stream of tiles.  The tiles (LDS stages) of this block's items form one sequence: all tiles of its first
+  // item, then all tiles of its second item, and so on.  Tile g of the sequence lives in ring buffer g % STAGES, and
+  // requests run up to STAGES tiles ahead of the multiplications - across the boundary to the next item, so that its
+  // first tiles travel while the last tiles of this one are multiplied and while its results are written out.  (Asking
+  // for them after the loop instead leaves the matrix pipes idle for as long as the vector memory path needs to take
+  // STAGES stages in: 1.7 us for 144 KiB at 64 bytes per cycle.)
+  //   multiply side:  work = item being multiplied, buf = buffer of the tile being multiplied
+  //   request side:   req_src / k_off = where the next tile to request starts, req_left = tiles still to request of the
+  //                   item that requests are in (the one being multiplied, or the one after it once req_ahead is set;
+  //                   requests never look further ahead), fill_buf = the buffer the next request goes to,
+  //                   pending = tiles requested whose arrival has not been waited for yet
+  int req_left = 0, fill_buf = 0, pending = 0;
+  bool req_ahead = false, have_next = false;
+  Source next_src{nullptr, nullptr};
+  int next_tiles = 0;
+  auto look_ahead = [&](int next_slot) {  // the item after the one being multiplied, if there is one
+    have_next = next_slot < slot_end;
+    if (have_next) {
+      const Work w = locate(item_at(next_slot));
+      next_src = source_of(w);
+      next_tiles = w.kt_count;
+    }
   };
-  request_first_stages(work);
+  auto tile_requested = [&]() {  // after the loads of one tile have been issued into fill_buf
+    fill_buf = (fill_buf + 1 == S) ? 0 : fill_buf + 1;
+    ++pending;
+    if (--req_left == 0 && !req_ahead && have_next) {  // on to the first tile of the next item
+      req_ahead = true;
+      point_sources(next_src);
+      req_left = next_tiles;
+    }
+  };
+  auto top_up = [&]() {  // as many requests as there are free buffers (start of the kernel; after items of few tiles)
+    while (pending < S && req_left > 0) {
+      issue_stage(fill_buf);
+      tile_requested();
+    }
+  };
+  // waits until at most `tiles` of the tiles requested by this wave are still in flight (and for its LDS reads)
+  auto wait_for_tiles = [&](int tiles) {
+    static_assert(S <= 4, "wait_for_tiles knows up to three tiles in flight");
+    if (tiles <= 0) wait_loads_and_lds<0>();
+    else if (tiles == 1) wait_loads_and_lds<Cfg::LOADS>();
+    else if (tiles == 2) wait_loads_and_lds<(S > 2 ? 2 : 0) * Cfg::LOADS>();
+    else wait_loads_and_lds<(S > 3 ? 3 : 0) * Cfg::LOADS>();
+  };
+  // The next tile to multiply has been requested (it always has: it is at most one item ahead); when this returns it
+  // has landed for every wave.  Matrix instructions have no memory side effects: the fences pin the barrier.
+  auto tile_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    wait_for_tiles(pending - 1);
+    --pending;
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // barrier that only protects a buffer about to be refilled (no tile is waited for)
+  auto refill_barrier = [&]() { stage_barrier(std::integral_constant<int, 63>{}); };
+
+  point_sources(source_of(work));
+  req_left = work.kt_count;
+  look_ahead(slot + slot_stride);
+  if (req_left == 0 && have_next) {
+    req_ahead = true;
+    point_sources(next_src);
+    req_left = next_tiles;
+  }
+  top_up();
+
+  int buf = 0;
   while (true) {
   const int kt_count = work.kt_count;
   clear_accumulators();
   if (kt_count > 0) {
-    // (stores of the previous item's epilogue may still be in flight behind the loads: waiting for "all but the
-    // newest n operations" then waits for more than needed, never for less)
-    if (kt_count >= S) wait_loads_and_lds<(S - 1) * Cfg::LOADS>(); else wait_loads_and_lds<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    read_frags(0, 0, 0);
-    int buf = 0, next = (S > 1 && kt_count > 1) ? 1 : 0;
+    // The first tile of the item must have landed.  (Stores of the previous item's epilogue may still be in flight
+    // behind the loads: waiting for "all but the newest n operations" then waits for more than needed, never for less.)
+    tile_barrier();
+    read_frags(0, buf, 0);
+    int next = (buf + 1 == S) ? 0 : buf + 1;
     auto advance = [&]() {
       buf = next;
       next = (next + 1 == S) ? 0 : next + 1;
     };
-    const int steady = kt_count - S;  // iterations that still have a tile to request
+    // The loops below keep the matrix instructions of an iteration in one straight line (a branch with matrix
+    // instructions on both sides makes the register allocator shuffle the accumulators where the sides join).
+    // Steady state - the ring is full (STAGES - 1 tiles requested beyond the one being multiplied) and the next
+    // request stays within the same item - runs in a loop of its own with fixed waits and no bookkeeping; the iterations
+    // after it (the last few of an item, or all of a short one) count tiles and take their loads under scalar branches.
+    typedef std::integral_constant<int, (S - 2) * Cfg::LOADS> steady_t;
     if constexpr (Cfg::K_STEPS == 2) {
-      int t = 0;
-      for (; t < steady; ++t) {
+      // Iteration t multiplies tile t: its first k step from fragment set 0 while set 1 is read, then, once every wave
+      // holds the tile's last fragments (barrier), its second k step while the buffer is refilled and the first
+      // fragments of tile t + 1 are read.
+      const int steady = (pending == S - 1 && req_left >= 2) ? min(kt_count - 1, req_left - 1) : 0;
+      for (int i = 0; i < steady; ++i) {
         fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
         stage_barrier(steady_t{});
         fused_step(set1_t{}, loads_t{}, set0_t{}, buf, next, ks0_t{});
         advance();
       }
-      for (; t < kt_count - 1; ++t) {
+      req_left -= steady;
+      if (steady > 0) fill_buf = buf;  // (with the ring full, the buffer to fill is the one being multiplied from)
+      for (int t = steady; t < kt_count - 1; ++t) {
         fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
-        stage_barrier(none_t{});
-        fused_step(set1_t{}, none_t{}, set0_t{}, 0, next, ks0_t{});
+        tile_barrier();
+        const bool request = req_left > 0;
+        fused_step(set1_t{}, loads_if_t{}, set0_t{}, fill_buf, next, ks0_t{}, request);
+        if (request) tile_requested();
         advance();
       }
+      // the last tile of the item: nothing of this item is left to read
       fused_step(set0_t{}, none_t{}, set1_t{}, 0, buf, ks1_t{});
-      fused_step(set1_t{}, none_t{}, no_reads_t{}, 0, 0, ks0_t{});
+      const bool request = req_left > 0;
+      if (request) refill_barrier();
+      fused_step(set1_t{}, loads_if_t{}, no_reads_t{}, fill_buf, 0, ks0_t{}, request);
+      if (request) tile_requested();
+      advance();
     } else {
-      // One k step per stage: tile t is multiplied from fragment set t & 1 while set (t + 1) & 1 is filled.
-      // Register arrays must be indexed statically, so the loops advance two tiles at a time and an odd
-      // leftover step is followed by a register copy that puts the live fragments back into set 0.
-      auto step = [&](auto set_c, auto issue_c, auto pending_c) {
-        constexpr int set = decltype(set_c)::value;
-        stage_barrier(pending_c);
-        fused_step(set_c, issue_c, std::integral_constant<int, set ^ 1>{}, buf, next, ks0_t{});
-        advance();
-      };
-      auto odd_step = [&](auto issue_c, auto pending_c) {
-        step(set0_t{}, issue_c, pending_c);
+      // One k step per stage: tile t is multiplied from one fragment set while the other is filled with the fragments
+      // of tile t + 1.  The barrier in front of a step comes when every wave holds the fragments of tile t, whose
+      // buffer is then refilled.  Register arrays must be indexed statically, so the steady loop advances two tiles at
+      // a time; a single step is followed by a register copy that puts the live fragments back into set 0.
+      auto fragments_back_to_set0 = [&]() {
 #pragma unroll
         for (int q = 0; q < NP; ++q) {
 #pragma unroll
@@ -518,36 +704,54 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
           for (int j = 0; j < TN; ++j) fb[0][j][q] = fb[1][j][q];
         }
       };
-      int t = 0;
-      if (steady > 0 && (steady & 1)) {
-        odd_step(loads_t{}, steady_t{});
-        t = 1;
+      auto steady_step = [&](auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        stage_barrier(steady_t{});
+        fused_step(set_c, loads_t{}, std::integral_constant<int, set ^ 1>{}, buf, next, ks0_t{});
+        advance();
+      };
+      const int steady = (pending == S - 1 && req_left >= 2) ? min(kt_count - 1, req_left - 1) : 0;
+      if (steady & 1) {
+        steady_step(set0_t{});
+        fragments_back_to_set0();
       }
-      for (; t < steady; t += 2) {
-        step(set0_t{}, loads_t{}, steady_t{});
-        step(set1_t{}, loads_t{}, steady_t{});
+      for (int i = steady & 1; i < steady; i += 2) {
+        steady_step(set0_t{});
+        steady_step(set1_t{});
       }
-      if ((kt_count - 1 - t) & 1) {
-        odd_step(none_t{}, none_t{});
-        ++t;
+      req_left -= steady;
+      if (steady > 0) fill_buf = buf;
+      for (int t = steady; t < kt_count - 1; ++t) {
+        tile_barrier();
+        const bool request = req_left > 0;
+        fused_step(set0_t{}, loads_if_t{}, set1_t{}, fill_buf, next, ks0_t{}, request);
+        if (request) tile_requested();
+        advance();
+        fragments_back_to_set0();
       }
-      for (; t < kt_count - 1; t += 2) {
-        step(set0_t{}, none_t{}, none_t{});
-        step(set1_t{}, none_t{}, none_t{});
-      }
-      fused_step(set0_t{}, none_t{}, no_reads_t{}, 0, 0, ks0_t{});
+      // the last tile of the item
+      const bool request = req_left > 0;
+      if (request) refill_barrier();
+      fused_step(set0_t{}, loads_if_t{}, no_reads_t{}, fill_buf, 0, ks0_t{}, request);
+      if (request) tile_requested();
+      advance();
     }
   }
-
-  // ---- next item: once every wave is done with the LDS ring, its first stages are requested, so that they travel
-  // while this item's results are written out.
+  // ---- next item (its first tiles have been on their way since the last iterations above)
   const Work done = work;
   slot += slot_stride;
   const bool more = slot < slot_end;
   if (more) {
-    stage_barrier(none_t{});
     work = locate(item_at(slot));
-    request_first_stages(work);
+    const bool stalled = req_left == 0;  // every tile of the new item has been requested already
+    req_ahead = false;
+    look_ahead(slot + slot_stride);
+    if (stalled && have_next) {
+      req_ahead = true;
+      point_sources(next_src);
+      req_left = next_tiles;
+    }
+    top_up();
   }
 
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums for a slice of a tile).
@@ -556,11 +760,14 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
   // The compiler must not carry this item's 128 store addresses (or their lane-dependent parts) through the main
   // loop of the next item, where it would have to spill them: what they are computed from is made opaque here, so
-  // they are recomputed per item.
-  int lane_here = lane;
+  // they are recomputed per item.  The lane number itself is counted afresh (two instructions) rather than kept: with
+  // all 512 registers of the 256 x 128 shape in use, keeping it alive through the loop cost a trip to scratch memory
+  // per item, whose wait also drained the next item's first loads.
+  int lane_here;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_here));
   int64_t ldc = p.ldc;
   float* c_base = p.C;
-  asm volatile("" : "+v"(lane_here), "+s"(ldc), "+s"(c_base));
+  asm volatile("" : "+s"(ldc), "+s"(c_base));
   const int64_t m_base = (int64_t)tile_m * Cfg::BM + wave_m * Cfg::WM + (lane_here & 31);
   const int64_t n_base = (int64_t)tile_n * Cfg::BN + wave_n * Cfg::WN + 4 * (lane_here >> 5);
   auto for_each_output = [&](auto&& store) {
@@ -583,33 +790,58 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
-        c = c * exp2_int(-row_scale[m]) * exp2_int(-col_scale[n]);
+        c = c * exp2_int(-load_global(row_scale + m)) * exp2_int(-load_global(col_scale + n));
         if (out) {
-          out[(n - n0) * Cfg::BM + (m - m0)] = c;
+          store_partial(out + (n - n0) * Cfg::BM + (m - m0), c);
         } else {
           float* dst = c_base + m + n * ldc;
-          store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
+          store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, load_global(dst)));
         }
       } else if (out) {
-        out[(n - n0) * Cfg::BM + (m - m0)] = 0.0f;
+        store_partial(out + (n - n0) * Cfg::BM + (m - m0), 0.0f);
       }
     });
   } else if (done.partial >= 0) {
     float* out = p.partials + (int64_t)done.partial * (Cfg::BM * Cfg::BN);
     const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
-    for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * Cfg::BM + (m - m0)] = c; });
+    for_each_output([&](int64_t m, int64_t n, float c) { store_partial(out + (n - n0) * Cfg::BM + (m - m0), c); });
   } else if (interior && p.beta == 0.0f) {
-    for_each_output([&](int64_t m, int64_t n, float c) { store_result(c_base + m + n * ldc, p.alpha * c); });
+    // (multiplying by an out_scale or an alpha of exactly 1 changes no bit, so the common case may skip both)
+    if (p.alpha == 1.0f && p.out_scale == 1.0f) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            store_result(c_base + (m_base + i * 32) + (n_base + j * 32 + 8 * (v / 4) + (v % 4)) * ldc,
+                         acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale);
+    } else {
+      for_each_output([&](int64_t m, int64_t n, float c) { store_result(c_base + m + n * ldc, p.alpha * c); });
+    }
   } else if (interior) {
-    for_each_output([&](int64_t m, int64_t n, float c) {
-      float* dst = c_base + m + n * ldc;
-      store_result(dst, scaled_sum(p.alpha, c, p.beta, *dst));
-    });
+    // beta != 0: the elements of C that a 32 x 32 tile updates are requested together, then merged and written, so that
+    // their latencies overlap (taken one by one, every load would be waited for before the store in front of the next)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        float* dst[16];
+        float c_in[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          dst[v] = c_base + (m_base + i * 32) + (n_base + j * 32 + 8 * (v / 4) + (v % 4)) * ldc;
+          c_in[v] = load_global(dst[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          store_result(dst[v], scaled_sum(p.alpha, (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale, p.beta, c_in[v]));
+      }
   } else {
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
         float* dst = c_base + m + n * ldc;
-        store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
+        store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, load_global(dst)));
       }
     });
   }

@@ -174,6 +174,26 @@ def test_plans_of_random_problems_are_well_formed():
             assert per_slice * (p["slices"] - 1) < stages, case                            # the last slice is not empty
 
 
+def test_tile_order_reciprocal_arithmetic_agrees_with_division():
+    """The kernels locate a tile with multiplications by reciprocals prepared on the host.  For grids of many shapes
+    (bands of equal and unequal width, a shorter last group of tile rows, one row, one column, forced orders) every
+    tile number must give the coordinates that plain division gives, and the order must visit every tile once."""
+    import numpy as np
+    import paper_2203_03341_amd as ec
+    rng = np.random.default_rng(5)
+    problems = [(1, 1, 32), (256, 128, 64), (300, 5000, 96), (5000, 300, 96), (16384, 16384, 256), (4095, 3001, 5003),
+                (2304, 4224, 1536), (20000, 130, 40000), (129, 20000, 64), (8192, 8192, 8192)]
+    problems += [(int(rng.integers(1, 12000)), int(rng.integers(1, 12000)), int(rng.integers(1, 20000))) for _ in range(60)]
+    for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
+        for (M, N, K) in problems:
+            tm, tn, bad = ec.debug_tile_order(M, N, K, mode)
+            p = ec.plan_info(M, N, K, mode)
+            assert bad == 0, (M, N, K, mode)
+            seen = np.zeros((p["tiles_m"], p["tiles_n"]), dtype=np.int32)
+            np.add.at(seen, (tm, tn), 1)
+            assert seen.min() == 1 and seen.max() == 1, (M, N, K, mode)
+
+
 def test_workspace_plan_needs_no_gpu():
     """Host logic: operands padded to 256 rows x 32 depth, 2 / 3 / 1 sixteen-bit parts per element, and the output
     tiles left over after whole rounds of the chip's 256 CUs cut into slices along K (one partial tile per slice)."""

@@ -90,6 +90,19 @@ int main(void) {
   CHECK(ecgemm_choose_mode(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, NULL, 1, NULL, 1, NULL, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_debug_mfma(NULL, 0, 1, NULL, NULL, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_debug_mfma_rate(NULL, 0, NULL, NULL, 1, 1, NULL) == ECGEMM_ERR_INVALID_ARG);
+  /* the tile order: reciprocal arithmetic against division over whole grids */
+  {
+    static int32_t tm[1 << 16], tn[1 << 16];
+    int64_t bad = -1;
+    for (i = 0; i < 200; ++i) {
+      const int64_t M = 1 + (int64_t)(next() % 20000), N = 1 + (int64_t)(next() % 20000), K = 1 + (int64_t)(next() % 9000);
+      mode = (int)(next() % 2);
+      CHECK(ecgemm_plan_info(NULL, M, N, K, (ecgemm_mode_t)mode, &info) == ECGEMM_OK);
+      if ((int64_t)info.tiles_m * info.tiles_n > (1 << 16)) continue;
+      CHECK(ecgemm_debug_tile_order(NULL, M, N, K, (ecgemm_mode_t)mode, tm, tn, &bad) == ECGEMM_OK && bad == 0);
+    }
+    CHECK(ecgemm_debug_tile_order(NULL, 5, 5, 5, ECGEMM_MODE_FP16_SPLIT, NULL, tn, &bad) == ECGEMM_ERR_INVALID_ARG);
+  }
   printf("host side clean\n");
   return 0;
 }
