@@ -60,6 +60,8 @@ WORKLOADS = {
     # paper's listing does against round-toward-zero, next to the default (inside) at the same size
     "x_8192_fp16_urand": (8192, 8192, 8192, "N", "N", "fp16", 1.0, 0.0, "urand", 256),
     "x_8192_fp16_outside_urand": (8192, 8192, 8192, "N", "N", "fp16_outside", 1.0, 0.0, "urand", 256),
+    "x_8192_fp16_outside4_urand": (8192, 8192, 8192, "N", "N", "fp16_outside4", 1.0, 0.0, "urand", 256),
+    "x_8192_fp16_outside16_urand": (8192, 8192, 8192, "N", "N", "fp16_outside16", 1.0, 0.0, "urand", 256),
 }
 DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
 # what the default run times after the headline: every other baseline configuration, both modes
@@ -68,8 +70,8 @@ OTHER_WORKLOADS = ["c4_8192_bf16_widerange", "c2_4096_fp16_urand", "c2_4096_bf16
                    "c1_256_fp16_urand"]
 OTHER_ORACLE_ROWS = 256      # the oracle's sample of rows of C for those (the headline keeps its own, larger one)
 
-PRODUCTS = {"fp16": 3, "bf16": 6, "fp16_outside": 3}
-PACKED_BYTES_PER_ELEMENT = {"fp16": 4, "bf16": 6, "fp16_outside": 4}
+PRODUCTS = {"fp16": 3, "bf16": 6, "fp16_outside": 3, "fp16_outside4": 3, "fp16_outside16": 3}
+PACKED_BYTES_PER_ELEMENT = {"fp16": 4, "bf16": 6, "fp16_outside": 4, "fp16_outside4": 4, "fp16_outside16": 4}
 
 
 def make_inputs(M, N, K, transA, transB, dist, beta, seed=0):
@@ -127,7 +129,8 @@ class Workload:
         self.ec, self.torch, self.name, self.seed = ec, torch, name, seed
         (self.M, self.N, self.K, self.transA, self.transB, self.mode, self.alpha, self.beta, self.dist,
          self.oracle_rows) = WORKLOADS[name]
-        self.mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "fp16_outside": ec.MODE_FP16_OUTSIDE_ACC}[self.mode]
+        self.mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "fp16_outside": ec.MODE_FP16_OUTSIDE_ACC,
+                        "fp16_outside4": ec.MODE_FP16_OUTSIDE_ACC_4, "fp16_outside16": ec.MODE_FP16_OUTSIDE_ACC_16}[self.mode]
         self.ops = {"N": ec.OP_N, "T": ec.OP_T}
         t0 = time.time()
         self.A, self.B, self.C = make_inputs(self.M, self.N, self.K, self.transA, self.transB, self.dist, self.beta, seed)

@@ -60,7 +60,7 @@ typedef enum {
      * six products of relative size >= 2^-16 are kept (same argument as section "Removing negligible
      * error correction"). */
     ECGEMM_MODE_BF16_FULL = 1,
-    /* 2 .. 7: the methods the paper compares against, run through the same kernels so that its error curves can be
+    /* 2 .. 9: the methods the paper compares against, run through the same kernels so that its error curves can be
      * redrawn on this hardware.  Not meant for production use; each is described in ecgemm_debug.h (they are
      * enumerators here because a C enumeration cannot be extended from a second header). */
     ECGEMM_MODE_FP16_MARKIDIS = 2,
@@ -68,7 +68,9 @@ typedef enum {
     ECGEMM_MODE_FP16_PLAIN = 4,
     ECGEMM_MODE_BF16_PLAIN = 5,
     ECGEMM_MODE_FP16_OUTSIDE_ACC = 6,
-    ECGEMM_MODE_FP32_MFMA = 7
+    ECGEMM_MODE_FP32_MFMA = 7,
+    ECGEMM_MODE_FP16_OUTSIDE_ACC_4 = 8,
+    ECGEMM_MODE_FP16_OUTSIDE_ACC_16 = 9
 } ecgemm_mode_t;
 
 typedef enum {

@@ -35,7 +35,14 @@ extern "C" {
  *                                     sets its method against (its cuBLAS SGEMM column), on this hardware and in this code
  *                                     base, for throughput, energy and error comparisons.
  *
- * They exist in the 256 x 128 kernel shape only.
+ *   ECGEMM_MODE_FP16_OUTSIDE_ACC_4 (8), ECGEMM_MODE_FP16_OUTSIDE_ACC_16 (9)
+ *                                     between that listing and the default: A16 B16 stays in the matrix unit's accumulator
+ *                                     for 4 or 16 k steps of 16 (64 or 256 deep) and only then joins the running sum kept
+ *                                     outside, which shows how much of the listing's small accuracy gain a longer interval
+ *                                     keeps, and at what cost.
+ *
+ * They exist in one kernel shape each (block tile 256 x 128; the three "outside" modes 128 x 128, one block per unit),
+ * addressed as ECGEMM_SHAPE_256x128_W4.
  */
 
 /*

@@ -70,7 +70,7 @@ constexpr Shape fused_shape() {
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
 constexpr int kPersistentMaxK = 4096;
-const Shape kShapes[8][3] = {
+const Shape kShapes[kMethods][3] = {
     {shape_of<Fp16W4>(kPersistentMaxK), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
     {shape_of<Bf16W4>(kPersistentMaxK), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
@@ -79,18 +79,22 @@ const Shape kShapes[8][3] = {
     {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
     {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
     {shape_of<Fp32Config>(4096), kNoShape, kNoShape},
+    {shape_of<Outside4Config>(4096), kNoShape, kNoShape},
+    {shape_of<Outside16Config>(4096), kNoShape, kNoShape},
 };
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // the ecgemm_mode_t values are the ProductMethod values
 inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
-inline bool valid_mode(int mode) { return mode >= ECGEMM_MODE_FP16_SPLIT && mode <= ECGEMM_MODE_FP32_MFMA; }
+inline bool valid_mode(int mode) { return mode >= 0 && mode < kMethods; }
 static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
               (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
               (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
               (int)ECGEMM_MODE_FP16_PLAIN == (int)kMethodFp16Plain && (int)ECGEMM_MODE_BF16_PLAIN == (int)kMethodBf16Plain &&
-              (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside && (int)ECGEMM_MODE_FP32_MFMA == (int)kMethodFp32,
+              (int)ECGEMM_MODE_FP16_OUTSIDE_ACC == (int)kMethodFp16Outside && (int)ECGEMM_MODE_FP32_MFMA == (int)kMethodFp32 &&
+                  (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_4 == (int)kMethodFp16Outside4 &&
+                  (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_16 == (int)kMethodFp16Outside16,
               "mode numbering");
 inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_FUSED; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
@@ -164,6 +168,8 @@ double mode_work(ecgemm_mode_t mode) {  // matrix-pipe time per element relative
     case ECGEMM_MODE_FP16_UNSCALED: return 1.0;
     case ECGEMM_MODE_BF16_FULL:
     case ECGEMM_MODE_FP16_OUTSIDE_ACC: return 2.0;
+    case ECGEMM_MODE_FP16_OUTSIDE_ACC_4:
+    case ECGEMM_MODE_FP16_OUTSIDE_ACC_16: return 1.2;
     case ECGEMM_MODE_FP16_MARKIDIS: return 4.0 / 3.0;
     case ECGEMM_MODE_FP32_MFMA: return 3.0;
     default: return 1.0 / 3.0;  // one product

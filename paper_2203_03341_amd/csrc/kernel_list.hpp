@@ -26,7 +26,10 @@ typedef ProductConfig<kMethodFp16Markidis, 256, 128, 128, 64, 2, 3, 1> MarkidisC
 typedef ProductConfig<kMethodFp16Unscaled, 256, 128, 128, 64, 2, 3, 1> UnscaledConfig;
 typedef ProductConfig<kMethodFp16Plain, 256, 128, 128, 64, 2, 3, 1> PlainFp16Config;
 typedef ProductConfig<kMethodBf16Plain, 256, 128, 128, 64, 2, 3, 1> PlainBf16Config;
-typedef ProductConfig<kMethodFp16Outside, 256, 128, 128, 64, 2, 3, 1> OutsideConfig;
+// (the "outside" methods keep a third accumulator set: 128 x 128 tiles of 64 x 64 per wave, one workgroup per unit)
+typedef ProductConfig<kMethodFp16Outside, 128, 128, 64, 64, 1, 4, 1> OutsideConfig;
+typedef ProductConfig<kMethodFp16Outside4, 128, 128, 64, 64, 1, 4, 1> Outside4Config;
+typedef ProductConfig<kMethodFp16Outside16, 128, 128, 64, 64, 1, 4, 1> Outside16Config;
 typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 
 #ifdef ECGEMM_INSTANTIATE_FP16
@@ -71,6 +74,8 @@ ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2>(const ProductP
 ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<MarkidisConfig>(const ProductParams);
 ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<UnscaledConfig>(const ProductParams);
 ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<OutsideConfig>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside4Config>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside16Config>(const ProductParams);
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainFp16Config>(const ProductParams);
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainBf16Config>(const ProductParams);
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<Fp32Config>(const ProductParams);

@@ -221,11 +221,21 @@ enum ProductMethod {
   kMethodBf16Plain = 5,     // toBF16(A) toBF16(B) only
   kMethodFp16Outside = 6,   // kMethodFp16Split with A16 B16 added to its accumulator outside the matrix unit, every k
                             // step, through a zeroed temporary (frag_tmp of the paper's listing; its contribution 1)
-  kMethodFp32 = 7           // A B in FP32 on the matrix unit (v_mfma_f32_32x32x2_f32): what the method is measured against
+  kMethodFp32 = 7,          // A B in FP32 on the matrix unit (v_mfma_f32_32x32x2_f32): what the method is measured against
+  kMethodFp16Outside4 = 8,  // kMethodFp16Outside with A16 B16 left in the matrix unit's accumulator for 4 k steps (64 deep)
+  kMethodFp16Outside16 = 9  // ... for 16 k steps (256 deep) before it is added to the running sum outside
 };
+constexpr int kMethods = 10;
+
+// For the "outside" methods: the number of 16-deep k steps whose leading products the matrix unit sums by itself before
+// that sum is added, by FP32 vector instructions, to the running sum kept outside it.  1 is the paper's listing
+// (section "Avoiding RZ during Tensor Core accumulation"); 0: the running sum is the matrix unit's accumulator.
+__host__ __device__ constexpr int flush_interval_of(int method) {
+  return method == kMethodFp16Outside ? 1 : method == kMethodFp16Outside4 ? 4 : method == kMethodFp16Outside16 ? 16 : 0;
+}
 
 __host__ __device__ constexpr int split_kind_of(int method) {
-  return (method == kMethodFp16Split || method == kMethodFp16Outside) ? kSplitFp16Scaled
+  return (method == kMethodFp16Split || flush_interval_of(method) > 0) ? kSplitFp16Scaled
        : method == kMethodBf16Full ? kSplitBf16x3
        : (method == kMethodFp16Markidis || method == kMethodFp16Unscaled) ? kSplitFp16Unscaled
        : method == kMethodFp16Plain ? kSplitFp16Plain : method == kMethodFp32 ? kSplitFp32 : kSplitBf16Plain;
@@ -234,7 +244,7 @@ __host__ __device__ constexpr int element_kind_of(int method) {
   return method == kMethodFp32 ? kElemFp32 : split_is_bf16(split_kind_of(method)) ? kElemBf16 : kElemFp16;
 }
 __host__ __device__ constexpr int products_of(int method) {
-  return method == kMethodFp16Split || method == kMethodFp16Unscaled || method == kMethodFp16Outside ? 3
+  return method == kMethodFp16Split || method == kMethodFp16Unscaled || flush_interval_of(method) > 0 ? 3
        : method == kMethodBf16Full ? 6 : method == kMethodFp16Markidis ? 4 : method == kMethodFp32 ? 8 : 1;
 }
 
@@ -254,7 +264,7 @@ __host__ __device__ constexpr ProductTerm product_term(int method, int t) {
          : t == 3 ? ProductTerm{1, 1, true, 0} : t == 4 ? ProductTerm{1, 0, true, 0} : ProductTerm{0, 1, true, 0};
   if (method == kMethodFp32)  // the two 8-deep halves of the k step, four 2-deep matrix instructions each, k ascending
     return ProductTerm{t / 4, t / 4, false, t % 4};
-  // kMethodFp16Split, kMethodFp16Unscaled, kMethodFp16Outside; the plain methods stop after the first term
+  // kMethodFp16Split, kMethodFp16Unscaled, the outside methods; the plain methods stop after the first term
   return t == 0 ? ProductTerm{0, 0, false, 0} : t == 1 ? ProductTerm{1, 0, true, 0} : ProductTerm{0, 1, true, 0};
 }
 
@@ -455,6 +465,27 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   };
 
   float16_t acc_main[TM][TN], acc_corr[TM][TN];
+  // "Outside" methods only: the sum that the matrix unit keeps for FLUSH k steps, added to acc_main (which the matrix
+  // unit then never touches) by vector instructions, after which it starts from zero again.
+  constexpr int FLUSH = flush_interval_of(Cfg::kMethod);
+  float16_t acc_inside[FLUSH > 0 ? TM : 1][FLUSH > 0 ? TN : 1];
+  int steps_inside = 0;
+  auto flush_inside = [&]() {
+    if constexpr (FLUSH > 0) {
+      float16_t zero;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc_main[i][j][v] += acc_inside[i][j][v];
+          acc_inside[i][j] = zero;
+        }
+      steps_inside = 0;
+    }
+  };
   // Zeroing through the matrix unit: 0 x 0 + 0 written by one instruction per 32 x 32 tile instead of sixteen register
   // writes (256 instructions for the 256 x 128 shape: a microsecond per item at one instruction every four or five
   // cycles, while the matrix pipes have nothing to do).  The zero fragment is opaque so that nothing is folded away.
@@ -485,8 +516,10 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
           for (int v = 0; v < 16; ++v) {
             acc_main[i][j][v] = 0.0f;
             acc_corr[i][j][v] = 0.0f;
+            if constexpr (FLUSH > 0) acc_inside[i][j][v] = 0.0f;
           }
     }
+    steps_inside = 0;
   };
 
   // One k step, in a fixed order.  Matrix instruction m of the step (term by term over all TM x TN tiles) is followed
@@ -515,14 +548,8 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
       constexpr int m = decltype(m_c)::value;
       constexpr ProductTerm term = product_term(Cfg::kMethod, m / (TM * TN));
       constexpr int i = (m % (TM * TN)) / TN, j = m % TN;
-      if constexpr (Cfg::kMethod == kMethodFp16Outside && !term.correction) {
-        // the matrix unit only multiplies: its accumulator input is zero and the running sum is kept by FP32 vector adds
-        float16_t zero;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) zero[v] = 0.0f;
-        const float16_t tmp = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], zero, term.sub);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc_main[i][j][v] += tmp[v];
+      if constexpr (FLUSH > 0 && !term.correction) {
+        acc_inside[i][j] = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_inside[i][j], term.sub);
       } else if constexpr (term.correction) {
         acc_corr[i][j] = Mfma<Cfg::kElem>::run(fb[SET][j][term.qb], fa[SET][i][term.qa], acc_corr[i][j], term.sub);
       } else {
@@ -553,6 +580,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
       });
       __builtin_amdgcn_sched_barrier(0);
     });
+    if constexpr (FLUSH > 0) {
+      if (++steps_inside == FLUSH) flush_inside();
+    }
   };
   typedef std::integral_constant<int, 0> none_t;
   typedef std::integral_constant<int, 1> loads_t;
@@ -757,7 +787,9 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   // ---- epilogue: merge the two accumulators, then alpha / beta (or raw partial sums for a slice of a tile).
   // Lane l holds row m = m_base + 32 i and, in register v of tile (i, j), column n_base + 32 j + 8 (v / 4) + v % 4.
   const int tile_m = done.tile_m, tile_n = done.tile_n;
-  const float corr_scale = (Cfg::kMethod == kMethodFp16Split || Cfg::kMethod == kMethodFp16Outside) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
+  const float corr_scale = (Cfg::kMethod == kMethodFp16Split || FLUSH > 0) ? 0x1p-11f : 1.0f;  // unused accumulators stay zero
+  if constexpr (FLUSH > 0) flush_inside();  // what the matrix unit still holds of the leading product
+  auto merged = [&](int i, int j, int v) { return acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale; };
   // The compiler must not carry this item's 128 store addresses (or their lane-dependent parts) through the main
   // loop of the next item, where it would have to spill them: what they are computed from is made opaque here, so
   // they are recomputed per item.  The lane number itself is counted afresh (two instructions) rather than kept: with
@@ -778,7 +810,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #pragma unroll
         for (int v = 0; v < 16; ++v)
           store(m_base + i * 32, n_base + j * 32 + 8 * (v / 4) + (v % 4),
-                (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
+                merged(i, j, v) * p.out_scale);
   };
   const bool interior = (int64_t)(tile_m + 1) * Cfg::BM <= p.M && (int64_t)(tile_n + 1) * Cfg::BN <= p.N;
   if (p.row_log2_scale != nullptr) {
@@ -815,7 +847,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #pragma unroll
           for (int v = 0; v < 16; ++v)
             store_result(c_base + (m_base + i * 32) + (n_base + j * 32 + 8 * (v / 4) + (v % 4)) * ldc,
-                         acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale);
+                         merged(i, j, v));
     } else {
       for_each_output([&](int64_t m, int64_t n, float c) { store_result(c_base + m + n * ldc, p.alpha * c); });
     }
@@ -835,7 +867,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-          store_result(dst[v], scaled_sum(p.alpha, (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale, p.beta, c_in[v]));
+          store_result(dst[v], scaled_sum(p.alpha, merged(i, j, v) * p.out_scale, p.beta, c_in[v]));
       }
   } else {
     for_each_output([&](int64_t m, int64_t n, float c) {

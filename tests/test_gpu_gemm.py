@@ -27,13 +27,15 @@ def _modes():
     import paper_2203_03341_amd as ec
     return {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "markidis": ec.MODE_FP16_MARKIDIS,
             "unscaled": ec.MODE_FP16_UNSCALED, "plain16": ec.MODE_FP16_PLAIN, "plainbf": ec.MODE_BF16_PLAIN,
-            "outside": ec.MODE_FP16_OUTSIDE_ACC, "fp32": ec.MODE_FP32_MFMA}
+            "outside": ec.MODE_FP16_OUTSIDE_ACC, "outside4": ec.MODE_FP16_OUTSIDE_ACC_4,
+            "outside16": ec.MODE_FP16_OUTSIDE_ACC_16, "fp32": ec.MODE_FP32_MFMA}
 
 
 def _model(mode, opA, opB):
     """Exact-accumulation model of a mode (FP64 sums of the same low-precision parts)."""
     return {"fp16": lambda: model.gemm_fp16_mode(opA, opB), "bf16": lambda: model.gemm_bf16_mode(opA, opB),
-            "outside": lambda: model.gemm_fp16_mode(opA, opB),
+            "outside": lambda: model.gemm_fp16_mode(opA, opB), "outside4": lambda: model.gemm_fp16_mode(opA, opB),
+            "outside16": lambda: model.gemm_fp16_mode(opA, opB),
             "markidis": lambda: model.gemm_fp16_mode(opA, opB, products=4, scaled=False),
             "unscaled": lambda: model.gemm_fp16_mode(opA, opB, products=3, scaled=False),
             "plain16": lambda: model.gemm_plain(opA, opB, "fp16"),
@@ -753,13 +755,16 @@ def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
     h.destroy()
 
 
-def test_accumulating_outside_the_matrix_unit_as_the_paper_does():
-    """The paper's listing verbatim (zeroed temporary, FP32 vector adds every k step): meets the same bar as the
-    default FP16 mode; one FP32 rounding per 16 products instead of per 8, so the element-wise bound holds too."""
-    _check("N", "N", 300, 200, 77, 1.5, 0.5, "outside", "urand", seed=1, pad=3)
-    _check("T", "N", 512, 384, 4096, 1.0, 0.0, "outside", "urand", seed=2)
+@pytest.mark.parametrize("mode", ["outside", "outside4", "outside16"])
+def test_accumulating_outside_the_matrix_unit_as_the_paper_does(mode):
+    """The paper's listing verbatim (zeroed temporary, FP32 vector adds every k step), and the same with the matrix unit
+    left to sum 4 or 16 k steps by itself before its sum joins the one kept outside: each meets the same bar as the
+    default FP16 mode; one FP32 rounding per 16 products or more instead of per 8, so the element-wise bound holds too."""
+    _check("N", "N", 300, 200, 77, 1.5, 0.5, mode, "urand", seed=1, pad=3)
+    _check("T", "N", 512, 384, 4096, 1.0, 0.0, mode, "urand", seed=2)
+    _check("N", "T", 640, 130, 16 * 37, 1.0, 0.0, mode, "urand", seed=4)      # a depth that ends in the middle of an interval
     rows = si.sample_indices(4096, 128, seed=3)
-    r_out, r_cpu = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "outside", "urand", seed=0, rows=rows)
+    r_out, r_cpu = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, mode, "urand", seed=0, rows=rows)
     r_def, _ = _check("N", "N", 4096, 4096, 4096, 1.0, 0.0, "fp16", "urand", seed=0, rows=rows)
     assert r_out < r_cpu and r_def < r_cpu          # neither needs the detour to beat the FP32 sum here
 
