@@ -62,6 +62,11 @@ WORKLOADS = {
     "x_8192_fp16_outside_urand": (8192, 8192, 8192, "N", "N", "fp16_outside", 1.0, 0.0, "urand", 256),
     "x_8192_fp16_outside4_urand": (8192, 8192, 8192, "N", "N", "fp16_outside4", 1.0, 0.0, "urand", 256),
     "x_8192_fp16_outside16_urand": (8192, 8192, 8192, "N", "N", "fp16_outside16", 1.0, 0.0, "urand", 256),
+    # the automatic mode choice (made on the GPU during the split pass) next to the fixed modes on the same inputs:
+    # x_8192_fp16_urand, c4_8192_bf16_widerange and x_1024_fp16_urand
+    "x_8192_auto_urand": (8192, 8192, 8192, "N", "N", "auto", 1.0, 0.0, "urand", 256),
+    "x_8192_auto_widerange": (8192, 8192, 8192, "N", "N", "auto", 1.5, 0.5, ((-100, 100), (-15, 14)), 512),
+    "x_1024_auto_urand": (1024, 1024, 1024, "N", "N", "auto", 1.0, 0.0, "urand", None),
 }
 DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
 # what the default run times after the headline: every other baseline configuration, both modes
@@ -130,7 +135,9 @@ class Workload:
         (self.M, self.N, self.K, self.transA, self.transB, self.mode, self.alpha, self.beta, self.dist,
          self.oracle_rows) = WORKLOADS[name]
         self.mode_id = {"fp16": ec.MODE_FP16_SPLIT, "bf16": ec.MODE_BF16_FULL, "fp16_outside": ec.MODE_FP16_OUTSIDE_ACC,
-                        "fp16_outside4": ec.MODE_FP16_OUTSIDE_ACC_4, "fp16_outside16": ec.MODE_FP16_OUTSIDE_ACC_16}[self.mode]
+                        "fp16_outside4": ec.MODE_FP16_OUTSIDE_ACC_4, "fp16_outside16": ec.MODE_FP16_OUTSIDE_ACC_16,
+                        "auto": ec.MODE_AUTO}[self.mode]
+        self.auto = self.mode == "auto"
         self.ops = {"N": ec.OP_N, "T": ec.OP_T}
         t0 = time.time()
         self.A, self.B, self.C = make_inputs(self.M, self.N, self.K, self.transA, self.transB, self.dist, self.beta, seed)
@@ -151,6 +158,11 @@ class Workload:
         self.h.set_workspace(self.ws, self.ws_bytes)
         self.flops = 2.0 * self.M * self.N * self.K
         self.expected_ms = max(0.02, self.flops / 3.0e14 * 1e3)     # at 300 TFLOP/s; only sizes the default step counts
+        self.plan_mode_id = self.mode_id
+        if self.auto:       # which mode the library picks for these inputs: from here on `mode` names that one
+            self.step()
+            self.plan_mode_id = self.h.auto_choice()
+            self.mode = "fp16" if self.plan_mode_id == ec.MODE_FP16_SPLIT else "bf16"
 
     def step(self):
         if self.dC0 is not None:
@@ -211,6 +223,8 @@ class Workload:
         packed = (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bpe
         product_bytes = packed + M * N * 4 * (2 if self.beta != 0 else 1)
         split_bytes = (M + N) * K * 4 + packed
+        if self.auto and self.mode == "bf16":      # the FP16 split that measured the operands ran first and is discarded
+            split_bytes += (M + N) * K * 4 + (pad(M, 256) + pad(N, 256)) * pad(K, 32) * PACKED_BYTES_PER_ELEMENT["fp16"]
         mfma_tflops = PRODUCTS[self.mode] * self.flops / (product_ms * 1e-3) / 1e12
         mfma = {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(mfma_tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(self.name),
@@ -439,7 +453,7 @@ def main():
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": w.transA, "transB": w.transB,
                    "mode": mode, "alpha": w.alpha, "beta": w.beta, "products": PRODUCTS[mode],
                    "inputs": "urand(-1,1)" if w.dist == "urand" else f"exp_rand{w.dist[0]} x exp_rand{w.dist[1]}", "seed": args.seed,
-                   "shape": args.shape, "tile_order": args.tile_order, "plan": h.plan_info(M, N, K, w.mode_id)},
+                   "shape": args.shape, "tile_order": args.tile_order, "plan": h.plan_info(M, N, K, w.plan_mode_id), "mode_chosen_by_the_library": w.auto},
         "split_ms": round(split_ms, 4), "product_ms": round(product_ms, 4),
         "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
         "roofline": roofline, "roofline_hbm": roofline_hbm, "roofline_split": roofline_split,
@@ -473,7 +487,7 @@ def main():
                      "frac_of_fp32_vector_peak": round(o_tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
                      "product_ms": round(o_product_ms, 4), "split_ms": round(o_split_ms, 4),
                      "roofline_frac": o_mfma["frac"], "roofline_hbm_frac": o_hbm["frac"], "traffic": o_mfma["traffic"],
-                     "plan_shape": o.h.plan_info(o.M, o.N, o.K, o.mode_id)["shape"]}
+                     "plan_shape": o.h.plan_info(o.M, o.N, o.K, o.plan_mode_id)["shape"]}
             if not args.no_oracle:
                 acc, _, _ = o.accuracy(OTHER_ORACLE_ROWS if o.oracle_rows is not None else None)
                 entry.update({k: acc[k] for k in ("relres_gpu", "relres_fp32_oracle", "relres_ratio", "accuracy_pass",

@@ -80,6 +80,30 @@ def fp16_pair_value(v16: np.ndarray, dv16: np.ndarray, scaled: bool = True) -> n
     return v16.astype(np.float64) + dv16.astype(np.float64) * s
 
 
+def fp16_pair_lost_fraction(x: np.ndarray) -> float:
+    """|x - (v16 + dv16 2^-11)|_F / |x|_F in FP64: how much of an operand the halfhalf pair fails to represent.
+
+    The quantity behind the library's automatic choice between the FP16 pair and the full-range mode (the trade-off
+    of section "Effect of the exponent range of input matrices", taken from the data instead of left to the user).
+    0 for an all-zero operand; NaN if the operand holds a NaN."""
+    x = np.asarray(x, dtype=np.float32)
+    exact = x.astype(np.float64)
+    with np.errstate(invalid="ignore", over="ignore"):
+        lost = exact - fp16_pair_value(*split_fp16(x))
+        err2, norm2 = float(np.sum(lost * lost)), float(np.sum(exact * exact))
+    if norm2 == 0.0 and err2 == 0.0:
+        return 0.0
+    return float(np.sqrt(err2 / norm2)) if np.isfinite(err2) and np.isfinite(norm2) else float("nan")
+
+
+def fp16_pair_represents(opA: np.ndarray, opB: np.ndarray, tolerance: float = 2.0 ** -24) -> bool:
+    """The automatic choice: True (FP16 pair) iff both operands lose at most `tolerance`, relative, in the Frobenius norm.
+
+    2^-24 is the unit roundoff of FP32: the pair must represent each operand as well as FP32 rounding would have.
+    A NaN (comparison false) or a value beyond the FP16 range (lost fraction near 1) gives False."""
+    return bool(fp16_pair_lost_fraction(opA) <= tolerance and fp16_pair_lost_fraction(opB) <= tolerance)
+
+
 BF16_MAX_BITS = np.uint32(0x7F7F)
 
 

@@ -18,11 +18,12 @@ MODE_FP16_SPLIT, MODE_BF16_FULL = 0, 1
 MODE_FP16_MARKIDIS, MODE_FP16_UNSCALED, MODE_FP16_PLAIN, MODE_BF16_PLAIN, MODE_FP16_OUTSIDE_ACC = 2, 3, 4, 5, 6  # comparisons
 MODE_FP32_MFMA = 7  # plain FP32 on the matrix unit
 MODE_FP16_OUTSIDE_ACC_4, MODE_FP16_OUTSIDE_ACC_16 = 8, 9
+MODE_AUTO = 10
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_128x128_FUSED = 0, 1, 2, 3
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
-           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_debug_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
+           "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_auto_choice", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_debug_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",
            "ecgemm_last_error_string", "ecgemm_status_string"]
 
 
@@ -61,6 +62,7 @@ def _load() -> ctypes.CDLL:
                                  ctypes.c_int]
     lib.ecgemm_sgemm_noalloc.argtypes = lib.ecgemm_sgemm.argtypes
     lib.ecgemm_last_error_argument.argtypes = [vp]
+    lib.ecgemm_auto_choice.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_sgemm_scaled.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                         ctypes.c_int, vp, vp]
     lib.ecgemm_row_scales.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
@@ -160,6 +162,12 @@ class Handle:
               beta: float, C, ldc: int, mode: int):
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
+
+    def auto_choice(self) -> int:
+        """The mode that the last sgemm / sgemm_noalloc call chose (MODE_AUTO); waits for the stream."""
+        mode = ctypes.c_int(-1)
+        self._check(_lib.ecgemm_auto_choice(self._h, ctypes.byref(mode)))
+        return mode.value
 
     def sgemm_noalloc(self, transA: int, transB: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int,
                       beta: float, C, ldc: int, mode: int):

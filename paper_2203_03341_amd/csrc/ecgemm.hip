@@ -38,6 +38,7 @@ struct ecgemm_context {
   int* range_buffer = nullptr;  // two ints of device memory for ecgemm_exponent_range
   char* builtin_workspace = nullptr;  // this device's copy of the library's built-in workspace (ecgemm_sgemm_noalloc)
   int last_error_argument = 0;
+  const int* auto_choice = nullptr;  // device: where the last ecgemm_sgemm call, if ECGEMM_MODE_AUTO, leaves its choice
   std::vector<TimedCall> timed;
   std::vector<hipEvent_t> free_events;
   std::string last_error;
@@ -45,7 +46,8 @@ struct ecgemm_context {
 
 namespace {
 
-typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t);
+typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t,
+                            const int*, int);
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
   void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
@@ -87,7 +89,8 @@ inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 // the ecgemm_mode_t values are the ProductMethod values
 inline int parts_of(ecgemm_mode_t mode) { return parts_of_split(split_kind_of((int)mode)); }
-inline bool valid_mode(int mode) { return mode >= 0 && mode < kMethods; }
+inline bool valid_mode(int mode) { return mode >= 0 && mode < kMethods; }  // a mode with kernels of its own
+inline bool valid_mode_or_auto(int mode) { return valid_mode(mode) || mode == (int)ECGEMM_MODE_AUTO; }
 static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEMM_MODE_BF16_FULL == (int)kMethodBf16Full &&
               (int)ECGEMM_MODE_FP16_MARKIDIS == (int)kMethodFp16Markidis &&
               (int)ECGEMM_MODE_FP16_UNSCALED == (int)kMethodFp16Unscaled &&
@@ -239,20 +242,48 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_sha
 }
 
 // A plan is a pure function of its arguments, and loops call the library with the same ones over and over: the last
-// plan of each thread is kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to a
-// 12 us call).
+// few plans of each thread are kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to
+// a 12 us call; the automatic mode needs two plans per call).
 Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
-  struct Key {
-    int64_t M, N, K;
-    int mode, shape;
+  struct Entry {
+    int64_t M = -1, N = -1, K = -1;
+    int mode = -1, shape = -1;
+    Plan plan;
   };
-  thread_local Key last = {-1, -1, -1, -1, -1};
-  thread_local Plan plan;
-  if (last.M != M || last.N != N || last.K != K || last.mode != (int)mode || last.shape != (int)shape) {
-    plan = choose_plan(M, N, K, mode, shape);
-    last = Key{M, N, K, (int)mode, (int)shape};
-  }
-  return plan;
+  constexpr int kEntries = 4;
+  thread_local Entry cache[kEntries];
+  thread_local int next = 0;
+  for (const Entry& e : cache)
+    if (e.M == M && e.N == N && e.K == K && e.mode == (int)mode && e.shape == (int)shape) return e.plan;
+  Entry& e = cache[next];
+  next = (next + 1) % kEntries;
+  e.plan = choose_plan(M, N, K, mode, shape);
+  e.M = M, e.N = N, e.K = K, e.mode = (int)mode, e.shape = (int)shape;
+  return e.plan;
+}
+
+// ECGEMM_MODE_AUTO: both candidate plans, and a workspace that serves either.  The statistics arrays have one entry per
+// 64 x 32 block of the padded operand, the most any split kernel variant launches (which variant runs depends on the
+// operands' alignment, and the workspace size must not).
+constexpr double kAutoTolerance = 0x1p-24;
+struct AutoPlan {
+  Plan fp16, bf16;
+  bool exists;
+  size_t packed_bytes, partial_bytes, stats_a_bytes, stats_b_bytes, total_bytes;
+};
+AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
+  AutoPlan ap;
+  ap.fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape);
+  ap.bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape);
+  ap.exists = ap.fp16.shape && ap.bf16.shape && !ap.fp16.shape->fused && !ap.bf16.shape->fused;
+  if (!ap.exists) return ap;
+  const size_t blocks_per_row_block = (size_t)(round_up(K, kDepthPad) / 32);
+  ap.packed_bytes = std::max(ap.fp16.a_bytes + ap.fp16.b_bytes, ap.bf16.a_bytes + ap.bf16.b_bytes);
+  ap.partial_bytes = std::max(ap.fp16.partial_bytes, ap.bf16.partial_bytes);
+  ap.stats_a_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(M, kRowPad) / 64));
+  ap.stats_b_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(N, kRowPad) / 64));
+  ap.total_bytes = ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes + 256;
+  return ap;
 }
 
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what, int argument = 0) {
@@ -291,6 +322,9 @@ ecgemm_status_t make_split_job(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, 
   job->prescale = std::ldexp(1.0f, log2_prescale);
   job->row_log2_scale = row_log2_scale;
   job->packed = static_cast<unsigned short*>(packed);
+  job->stats = nullptr;
+  job->gate = nullptr;
+  job->gate_value = 0;
   job->variant = k_contiguous ? (vec ? kSplitKContiguousVec : kSplitKContiguous) : (vec ? kSplitRContiguousWide : kSplitRContiguous);
   // blocks are 64 rows x 32 k, except 256 x 32 (wide) and 64 x 64 (k contiguous, unaligned)
   switch (job->variant) {
@@ -302,38 +336,42 @@ ecgemm_status_t make_split_job(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, 
   return ECGEMM_OK;
 }
 
-template <int KIND>
+template <int KIND, bool STATS>
 void launch_split_job(hipStream_t stream, const SplitJob& job) {
   const dim3 grid(job.blocks), block(256);
   switch (job.variant) {
-    case kSplitRContiguousWide: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguousWide>), grid, block, 0, stream, job); break;
-    case kSplitRContiguous: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguous>), grid, block, 0, stream, job); break;
-    case kSplitKContiguousVec: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguousVec>), grid, block, 0, stream, job); break;
-    default: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguous>), grid, block, 0, stream, job); break;
+    case kSplitRContiguousWide: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguousWide, STATS>), grid, block, 0, stream, job); break;
+    case kSplitRContiguous: hipLaunchKernelGGL((split_kernel<KIND, kSplitRContiguous, STATS>), grid, block, 0, stream, job); break;
+    case kSplitKContiguousVec: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguousVec, STATS>), grid, block, 0, stream, job); break;
+    default: hipLaunchKernelGGL((split_kernel<KIND, kSplitKContiguous, STATS>), grid, block, 0, stream, job); break;
   }
 }
 
-// Step 1 for one operand, or (b != nullptr) for both operands of a product.  Small pairs go out as one launch.
-ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_mode_t mode, const SplitJob& a, const SplitJob* b = nullptr) {
-  const bool pair = b != nullptr && (uint64_t)a.blocks + b->blocks <= 8192;
-#define ECGEMM_LAUNCH_SPLIT(KIND)                                                                                       \
-  do {                                                                                                                  \
-    if (pair) {                                                                                                         \
-      hipLaunchKernelGGL((split_pair_kernel<KIND>), dim3(a.blocks + b->blocks), dim3(256), 0, h->stream, a, *b);        \
-    } else {                                                                                                            \
-      launch_split_job<KIND>(h->stream, a);                                                                             \
-      if (b) launch_split_job<KIND>(h->stream, *b);                                                                     \
-    }                                                                                                                   \
-  } while (0)
-  switch (split_kind_of((int)mode)) {
-    case kSplitFp16Scaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Scaled); break;
-    case kSplitBf16x3: ECGEMM_LAUNCH_SPLIT(kSplitBf16x3); break;
-    case kSplitFp16Unscaled: ECGEMM_LAUNCH_SPLIT(kSplitFp16Unscaled); break;
-    case kSplitFp16Plain: ECGEMM_LAUNCH_SPLIT(kSplitFp16Plain); break;
-    case kSplitFp32: ECGEMM_LAUNCH_SPLIT(kSplitFp32); break;
-    default: ECGEMM_LAUNCH_SPLIT(kSplitBf16Plain); break;
+template <int KIND, bool STATS = false>
+void launch_split_kind(hipStream_t stream, const SplitJob& a, const SplitJob* b) {
+  if (b != nullptr && (uint64_t)a.blocks + b->blocks <= 8192) {  // small pairs go out as one launch
+    hipLaunchKernelGGL((split_pair_kernel<KIND, STATS>), dim3(a.blocks + b->blocks), dim3(256), 0, stream, a, *b);
+  } else {
+    launch_split_job<KIND, STATS>(stream, a);
+    if (b) launch_split_job<KIND, STATS>(stream, *b);
   }
-#undef ECGEMM_LAUNCH_SPLIT
+}
+
+// Step 1 for one operand, or (b != nullptr) for both operands of a product.  `measuring` (FP16 pair only): the kernels
+// also leave the statistics of the automatic mode choice in a.stats and b->stats.
+ecgemm_status_t launch_split(ecgemm_handle_t h, ecgemm_mode_t mode, const SplitJob& a, const SplitJob* b = nullptr,
+                             bool measuring = false) {
+  switch (split_kind_of((int)mode)) {
+    case kSplitFp16Scaled:
+      if (measuring) launch_split_kind<kSplitFp16Scaled, true>(h->stream, a, b);
+      else launch_split_kind<kSplitFp16Scaled>(h->stream, a, b);
+      break;
+    case kSplitBf16x3: launch_split_kind<kSplitBf16x3>(h->stream, a, b); break;
+    case kSplitFp16Unscaled: launch_split_kind<kSplitFp16Unscaled>(h->stream, a, b); break;
+    case kSplitFp16Plain: launch_split_kind<kSplitFp16Plain>(h->stream, a, b); break;
+    case kSplitFp32: launch_split_kind<kSplitFp32>(h->stream, a, b); break;
+    default: launch_split_kind<kSplitBf16Plain>(h->stream, a, b); break;
+  }
   ECGEMM_HIP(h, hipGetLastError());
   return ECGEMM_OK;
 }
@@ -385,8 +423,11 @@ int group_m_of(const Plan& pl, int forced = 0) {
 // Steps 2 and 3 on operands already in fragment order (padded as ecgemm_split pads them, or tighter).
 ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int64_t N, float alpha, const void* a_packed,
                                const void* b_packed, float beta, float* C, int64_t ldc, ecgemm_mode_t mode, float* partials,
-                               int log2_out_scale = 0, const int* row_log2_scale = nullptr, const int* col_log2_scale = nullptr) {
+                               int log2_out_scale = 0, const int* row_log2_scale = nullptr, const int* col_log2_scale = nullptr,
+                               const int* gate = nullptr, int gate_value = 0) {
   ProductParams pp;
+  pp.gate = gate;
+  pp.gate_value = gate_value;
   pp.a_packed = static_cast<const char*>(a_packed);
   pp.b_packed = static_cast<const char*>(b_packed);
   pp.row_block_bytes = (pl.Kp / 16) * parts_of(mode) * 1024;
@@ -417,7 +458,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
-                       pl.full_tiles, pl.tiles_m, pl.tiles_n, group_m, bands, M, N, alpha, beta, C, ldc);
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, group_m, bands, M, N, alpha, beta, C, ldc, gate, gate_value);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -458,7 +499,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 * 128 / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
-                       pl.tiles_m, pl.tiles_n, 4, 1, M, N, alpha, beta, C, ldc);
+                       pl.tiles_m, pl.tiles_n, 4, 1, M, N, alpha, beta, C, ldc, (const int*)nullptr, 0);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -662,12 +703,18 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA
   if (M < 0) return bad_arg(handle, 4, "ecgemm_workspace_size: negative M");
   if (N < 0) return bad_arg(handle, 5, "ecgemm_workspace_size: negative N");
   if (K < 0) return bad_arg(handle, 6, "ecgemm_workspace_size: negative K");
-  if (!valid_mode(mode)) return bad_arg(handle, 7, "ecgemm_workspace_size: unknown mode");
+  if (!valid_mode_or_auto(mode)) return bad_arg(handle, 7, "ecgemm_workspace_size: unknown mode");
   if (!bytes) return bad_arg(handle, 8, "ecgemm_workspace_size: null output");
   *bytes = 0;
   if (M == 0 || N == 0 || K == 0) return ECGEMM_OK;
-  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 4);
+  const ecgemm_status_t st = check_sizes(handle, M, N, K, mode == ECGEMM_MODE_AUTO ? ECGEMM_MODE_BF16_FULL : mode, 4);
   if (st != ECGEMM_OK) return st;
+  if (mode == ECGEMM_MODE_AUTO) {
+    const AutoPlan ap = make_auto_plan(M, N, K, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+    if (!ap.exists) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: ECGEMM_MODE_AUTO does not run with the fused kernel shape");
+    *bytes = ap.total_bytes;
+    return ECGEMM_OK;
+  }
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
   *bytes = pl.total_bytes;
@@ -709,6 +756,7 @@ ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void* device_buffer
   if ((device_buffer == nullptr) != (bytes == 0)) return bad_arg(handle, 3, "ecgemm_set_workspace: a buffer with its size, or (NULL, 0)");
   handle->user_workspace = device_buffer;
   handle->user_bytes = bytes;
+  handle->auto_choice = nullptr;
   return ECGEMM_OK;
 }
 
@@ -908,6 +956,92 @@ ecgemm_status_t ecgemm_get_timing(ecgemm_handle_t handle, int* calls, float* spl
 
 namespace {
 
+// Events for the optional timing go back to the handle's pool whenever the call does not complete.
+struct EventLease {
+  ecgemm_handle_t h;
+  TimedCall tc{};
+  bool keep = false;
+  ~EventLease() {
+    if (keep) return;
+    for (hipEvent_t e : {tc.start, tc.split_done, tc.product_done})
+      if (e) h->free_events.push_back(e);
+  }
+};
+
+// ECGEMM_MODE_AUTO (arguments already checked).  Nothing here waits for the GPU: the kernels of both modes are
+// enqueued, each product, reduction and the BF16 split gated on the choice that choose_mode_kernel leaves in device
+// memory, so the ones of the mode not chosen return at once.
+//   1. the FP16 pair split of A and of B, which also leave per block the squared Frobenius norm of the operand and of
+//      what the pair fails to represent of it
+//   2. the choice: FP16 if both operands are represented to within kAutoTolerance, relative, else BF16
+//   3. the BF16 three-term split of both operands (gated), over the FP16 parts, which are no longer needed then
+//   4. the FP16 product (gated), the BF16 product (gated)
+ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N, int64_t K, float alpha,
+                           const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
+                           WorkspaceKind workspace_kind) {
+  ecgemm_status_t st = check_sizes(h, M, N, K, ECGEMM_MODE_BF16_FULL, 4);
+  if (st != ECGEMM_OK) return st;
+  const AutoPlan ap = make_auto_plan(M, N, K, h->shape);
+  if (!ap.exists) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: ECGEMM_MODE_AUTO does not run with the fused kernel shape");
+  if (ap.fp16.items() + 16 > 0x7fffffffLL || ap.bf16.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
+  char* ws = nullptr;
+  st = acquire_workspace(h, ap.total_bytes, &ws, workspace_kind);
+  if (st != ECGEMM_OK) return st;
+  float* partials = ap.partial_bytes ? reinterpret_cast<float*>(ws + ap.packed_bytes) : nullptr;
+  double* stats_a = reinterpret_cast<double*>(ws + ap.packed_bytes + ap.partial_bytes);
+  double* stats_b = reinterpret_cast<double*>(ws + ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes);
+  int* choice = reinterpret_cast<int*>(ws + ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes);
+  const ecgemm_op_t op_b = transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N;  // as in sgemm_common
+  SplitJob fp16_a, fp16_b, bf16_a, bf16_b;
+  st = make_split_job(h, transA, M, K, A, lda, ws, h->log2_scale_a, nullptr, &fp16_a);
+  if (st != ECGEMM_OK) return st;
+  st = make_split_job(h, op_b, N, K, B, ldb, ws + ap.fp16.a_bytes, h->log2_scale_b, nullptr, &fp16_b);
+  if (st != ECGEMM_OK) return st;
+  st = make_split_job(h, transA, M, K, A, lda, ws, h->log2_scale_a, nullptr, &bf16_a);
+  if (st != ECGEMM_OK) return st;
+  st = make_split_job(h, op_b, N, K, B, ldb, ws + ap.bf16.a_bytes, h->log2_scale_b, nullptr, &bf16_b);
+  if (st != ECGEMM_OK) return st;
+  if (16 * (size_t)fp16_a.blocks > ap.stats_a_bytes || 16 * (size_t)fp16_b.blocks > ap.stats_b_bytes)
+    return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: internal error, statistics array too small");
+  fp16_a.stats = stats_a;
+  fp16_b.stats = stats_b;
+  bf16_a.gate = bf16_b.gate = choice;
+  bf16_a.gate_value = bf16_b.gate_value = 1;
+
+  EventLease lease{h};
+  TimedCall& tc = lease.tc;
+  const bool timing = h->timing && workspace_kind != kWorkspaceBuiltIn;
+  if (timing) {
+    tc.start = take_event(h);
+    tc.split_done = take_event(h);
+    tc.product_done = take_event(h);
+    if (!tc.start || !tc.split_done || !tc.product_done) return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: hipEventCreate failed");
+    ECGEMM_HIP(h, hipEventRecord(tc.start, h->stream));
+  }
+  st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
+  if (st != ECGEMM_OK) return st;
+  hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(256), 0, h->stream, stats_a, fp16_a.blocks, stats_b, fp16_b.blocks,
+                     kAutoTolerance, choice);
+  ECGEMM_HIP(h, hipGetLastError());
+  h->auto_choice = choice;
+  st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);
+  if (st != ECGEMM_OK) return st;
+  if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
+  const int log2_out_scale = -(h->log2_scale_a + h->log2_scale_b);
+  st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
+                      log2_out_scale, nullptr, nullptr, choice, 0);
+  if (st != ECGEMM_OK) return st;
+  st = launch_product(h, ap.bf16, M, N, alpha, ws, ws + ap.bf16.a_bytes, beta, C, ldc, ECGEMM_MODE_BF16_FULL, partials,
+                      log2_out_scale, nullptr, nullptr, choice, 1);
+  if (st != ECGEMM_OK) return st;
+  if (timing) {
+    ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
+    h->timed.push_back(tc);
+    lease.keep = true;
+  }
+  return ECGEMM_OK;
+}
+
 // ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc: the same parameter list up to `mode` (the positions
 // reported for bad arguments count it), then the scaling vectors and where the workspace comes from.  Everything that
 // can be refused is checked before the first launch.
@@ -921,7 +1055,8 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   if (M < 0) return bad_arg(h, 4, "ecgemm_sgemm: negative M");
   if (N < 0) return bad_arg(h, 5, "ecgemm_sgemm: negative N");
   if (K < 0) return bad_arg(h, 6, "ecgemm_sgemm: negative K");
-  if (!valid_mode(mode)) return bad_arg(h, 15, "ecgemm_sgemm: unknown mode");
+  if (!valid_mode_or_auto(mode)) return bad_arg(h, 15, "ecgemm_sgemm: unknown mode");
+  h->auto_choice = nullptr;
   if (M == 0 || N == 0) return ECGEMM_OK;
   if (!C) return bad_arg(h, 13, "ecgemm_sgemm: C is null");
   if (ldc < M) return bad_arg(h, 14, "ecgemm_sgemm: ldc < M");
@@ -938,12 +1073,16 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   if (!B) return bad_arg(h, 10, "ecgemm_sgemm: B is null");
   if (ldb < (transB == ECGEMM_OP_N ? K : N)) return bad_arg(h, 11, "ecgemm_sgemm: ldb too small");
 
+  if ((row_log2_scale_a == nullptr) != (col_log2_scale_b == nullptr))
+    return bad_arg(h, row_log2_scale_a == nullptr ? 16 : 17, "ecgemm_sgemm_scaled: give both scaling vectors or neither");
+  if (mode == ECGEMM_MODE_AUTO) {
+    if (row_log2_scale_a) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm_scaled: ECGEMM_MODE_AUTO takes no scaling vectors");
+    return sgemm_auto(h, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, workspace_kind);
+  }
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
   if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
-  if ((row_log2_scale_a == nullptr) != (col_log2_scale_b == nullptr))
-    return bad_arg(h, row_log2_scale_a == nullptr ? 16 : 17, "ecgemm_sgemm_scaled: give both scaling vectors or neither");
   if (row_log2_scale_a && pl.shape->fused)
     return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm_scaled: the fused kernel shape takes no scaling vectors");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
@@ -964,17 +1103,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
     if (st != ECGEMM_OK) return st;
   }
 
-  // Events for the optional timing go back to the handle's pool whenever the call does not complete.
-  struct EventLease {
-    ecgemm_handle_t h;
-    TimedCall tc{};
-    bool keep = false;
-    ~EventLease() {
-      if (keep) return;
-      for (hipEvent_t e : {tc.start, tc.split_done, tc.product_done})
-        if (e) h->free_events.push_back(e);
-    }
-  } lease{h};
+  EventLease lease{h};
   TimedCall& tc = lease.tc;
   const bool timing = h->timing && workspace_kind != kWorkspaceBuiltIn;  // (creating an event allocates)
   if (timing) {
@@ -1034,6 +1163,18 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
                       kWorkspaceBuiltIn);
 }
 
+ecgemm_status_t ecgemm_auto_choice(ecgemm_handle_t handle, ecgemm_mode_t* mode) {
+  if (!handle) return ECGEMM_ERR_INVALID_ARG;
+  if (!mode) return bad_arg(handle, 2, "ecgemm_auto_choice: null output");
+  if (!handle->auto_choice)
+    return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_auto_choice: the handle's last product call made no choice (not ECGEMM_MODE_AUTO, or empty)", 1);
+  int choice = -1;
+  ECGEMM_HIP(handle, hipMemcpyAsync(&choice, handle->auto_choice, sizeof(int), hipMemcpyDeviceToHost, handle->stream));
+  ECGEMM_HIP(handle, hipStreamSynchronize(handle->stream));
+  *mode = choice == 0 ? ECGEMM_MODE_FP16_SPLIT : ECGEMM_MODE_BF16_FULL;
+  return ECGEMM_OK;
+}
+
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
                                const void* packedA, const void* packedB, float beta, float* C, int64_t ldc,
                                ecgemm_mode_t mode) {
@@ -1043,6 +1184,7 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
   if (N < 0) return bad_arg(h, 3, "ecgemm_product: negative N");
   if (K < 0) return bad_arg(h, 4, "ecgemm_product: negative K");
   if (!valid_mode(mode)) return bad_arg(h, 11, "ecgemm_product: unknown mode");
+  h->auto_choice = nullptr;
   if (M == 0 || N == 0) return ECGEMM_OK;
   if (!C) return bad_arg(h, 9, "ecgemm_product: C is null");
   if (ldc < M) return bad_arg(h, 10, "ecgemm_product: ldc < M");

@@ -126,4 +126,30 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
   sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Automatic mode choice: from the blocks' statistics of both operands, *choice = 0 (the FP16 pair represents both
+// operands to within `tolerance`, relative, in the Frobenius norm) or 1 (it does not: three BF16 terms).  One block of
+// 256 threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere gives 1.
+__global__ void __launch_bounds__(256) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a,
+                                                          const double* __restrict__ stats_b, unsigned blocks_b,
+                                                          double tolerance, int* __restrict__ choice) {
+  __shared__ double partial[256][4];
+  double sums[4] = {0.0, 0.0, 0.0, 0.0};
+  for (unsigned i = threadIdx.x; i < blocks_a; i += 256) sums[0] += stats_a[2 * (size_t)i], sums[1] += stats_a[2 * (size_t)i + 1];
+  for (unsigned i = threadIdx.x; i < blocks_b; i += 256) sums[2] += stats_b[2 * (size_t)i], sums[3] += stats_b[2 * (size_t)i + 1];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] = sums[q];
+  __syncthreads();
+  for (int half = 128; half >= 1; half >>= 1) {
+    if ((int)threadIdx.x < half)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] += partial[threadIdx.x + half][q];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double t2 = tolerance * tolerance;
+    const bool fits = partial[0][0] <= t2 * partial[0][1] && partial[0][2] <= t2 * partial[0][3];
+    *choice = fits ? 0 : 1;
+  }
+}
+
 }  // namespace ecgemm

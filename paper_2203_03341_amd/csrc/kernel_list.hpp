@@ -66,9 +66,9 @@ typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4>(const ProductParams);
 ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2>(const ProductParams);
 ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<256, 128>(const float*, int, int, int, int, int, int, int, int64_t,
-                                                                       int64_t, float, float, float*, int64_t);
+                                                                       int64_t, float, float, float*, int64_t, const int*, int);
 ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<128, 128>(const float*, int, int, int, int, int, int, int, int64_t,
-                                                                       int64_t, float, float, float*, int64_t);
+                                                                       int64_t, float, float, float*, int64_t, const int*, int);
 ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4>(const ProductParams);
 ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2>(const ProductParams);
 ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<MarkidisConfig>(const ProductParams);
@@ -83,11 +83,11 @@ ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodFp16Split>(const
 ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodBf16Full>(const FusedParams);
 
 #define ECGEMM_SPLIT_KERNELS_OF(KIND)                                                                     \
-  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguousVec>(const SplitJob);   \
-  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguous>(const SplitJob);      \
-  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguous>(const SplitJob);      \
-  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguousWide>(const SplitJob);  \
-  ECGEMM_SPLIT_GROUP template __global__ void split_pair_kernel<KIND>(const SplitJob, const SplitJob);
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguousVec, false>(const SplitJob);   \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguous, false>(const SplitJob);      \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguous, false>(const SplitJob);      \
+  ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitRContiguousWide, false>(const SplitJob);  \
+  ECGEMM_SPLIT_GROUP template __global__ void split_pair_kernel<KIND, false>(const SplitJob, const SplitJob);
 ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Scaled)
 ECGEMM_SPLIT_KERNELS_OF(kSplitBf16x3)
 ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Unscaled)
@@ -95,5 +95,11 @@ ECGEMM_SPLIT_KERNELS_OF(kSplitFp16Plain)
 ECGEMM_SPLIT_KERNELS_OF(kSplitBf16Plain)
 ECGEMM_SPLIT_KERNELS_OF(kSplitFp32)
 #undef ECGEMM_SPLIT_KERNELS_OF
+// (the FP16 pair split that also measures what the pair loses: automatic mode choice)
+ECGEMM_SPLIT_GROUP template __global__ void split_kernel<kSplitFp16Scaled, kSplitKContiguousVec, true>(const SplitJob);
+ECGEMM_SPLIT_GROUP template __global__ void split_kernel<kSplitFp16Scaled, kSplitKContiguous, true>(const SplitJob);
+ECGEMM_SPLIT_GROUP template __global__ void split_kernel<kSplitFp16Scaled, kSplitRContiguous, true>(const SplitJob);
+ECGEMM_SPLIT_GROUP template __global__ void split_kernel<kSplitFp16Scaled, kSplitRContiguousWide, true>(const SplitJob);
+ECGEMM_SPLIT_GROUP template __global__ void split_pair_kernel<kSplitFp16Scaled, true>(const SplitJob, const SplitJob);
 
 }  // namespace ecgemm

@@ -182,6 +182,9 @@ struct ProductParams {
   const int* col_log2_scale;  // device, N entries
   float* C;
   float* partials;          // [tail_splits][tail_tiles][BN][BM] when tail_splits > 1
+  // Automatic mode choice only, else null: the kernel does nothing unless *gate == gate_value
+  const int* gate;
+  int gate_value;
 };
 
 // The matrix instruction per element type of the packed operands.  `sub` picks one of the four 2-deep steps that an
@@ -340,6 +343,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
   // The ring of stages.  (It must stay the only LDS object of the kernel: with a second one the compiler starts to guard
   // every fragment read with a wait for all LDS-DMA loads in flight, which serialises the ring: 30 % slower.)
   __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
+  if (!gate_open(p.gate, p.gate_value)) return;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -889,8 +893,9 @@ template <int BM, int BN>
 __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
                                                           int full_tiles, int tiles_m, int tiles_n, int group_m,
                                                           int column_bands, int64_t M, int64_t N, float alpha, float beta, float* __restrict__ C,
-                                                          int64_t ldc) {
+                                                          int64_t ldc, const int* gate, int gate_value) {
   static_assert(BM % 4 == 0 && (BM * BN) % 1024 == 0, "tile shape");
+  if (!gate_open(gate, gate_value)) return;
   int tile_m, tile_n;
   tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, column_bands, tile_m, tile_n);
   const int e = (blockIdx.y * 256 + threadIdx.x) * 4;  // element of the tile, stored [n_local][m_local]

@@ -88,10 +88,16 @@ struct Splitter {
   }
 };
 
+// What the automatic mode choice needs to know about an operand: how much of it the FP16 pair loses.  Per thread, then
+// per block: the sums of (x - (v16 + dv16 2^-11))^2 and of x^2 over the elements handled, in FP64.
+struct SplitStats {
+  double err2 = 0.0, norm2 = 0.0;
+};
+
 // Writes the eight consecutive-k values `v` of row r (global indices) to their place in `packed`.
-template <int KIND>
+template <int KIND, bool STATS = false>
 __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ packed, int64_t k_steps_total,
-                                                   int64_t r, int64_t k, const float (&v)[8]) {
+                                                   int64_t r, int64_t k, const float (&v)[8], SplitStats* stats = nullptr) {
   if constexpr (KIND == kSplitFp32) {
     // v_mfma_f32_32x32x2_f32 takes one float per lane: lane l supplies row l % 32 and k = l / 32 of a 2-deep step.
     // A 1 KiB chunk holds four such steps, 16 bytes per lane: element k % 8 of the row goes to lane
@@ -112,6 +118,12 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
     Splitter<KIND>::split(v[e], s);
 #pragma unroll
     for (int p = 0; p < NP; ++p) parts[p][e] = s[p];
+    if constexpr (STATS && KIND == kSplitFp16Scaled) {
+      const float kept = (float)__builtin_bit_cast(_Float16, s[0]) + (float)__builtin_bit_cast(_Float16, s[1]) * 0x1p-11f;
+      const double lost = (double)v[e] - (double)kept, x = (double)v[e];
+      stats->err2 += lost * lost;
+      stats->norm2 += x * x;
+    }
   }
   const int64_t row_block = r >> 5, k_step = k >> 4;
   const int lane = (int)((k >> 3) & 1) * 32 + (int)(r & 31);
@@ -131,14 +143,36 @@ struct SplitJob {
   unsigned fast_tiles;        // tiles along the direction in which the blocks are numbered first
   unsigned blocks;
   int variant;                // SplitVariant
+  // Automatic mode choice only, else null: block b leaves its SplitStats at stats[2 b], stats[2 b + 1]
+  double* stats;
+  // Automatic mode choice only, else null: the kernel does nothing unless *gate == gate_value
+  const int* gate;
+  int gate_value;
 };
+
+// Sums the threads' statistics over the block in a fixed order and stores them (all 256 threads call this).
+__device__ __forceinline__ void store_block_stats(const SplitStats& mine, double* __restrict__ out, double* scratch8) {
+  double e = mine.err2, n = mine.norm2;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    e += __shfl_xor(e, d, 64);
+    n += __shfl_xor(n, d, 64);
+  }
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) scratch8[2 * wave] = e, scratch8[2 * wave + 1] = n;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    out[0] = (scratch8[0] + scratch8[2]) + (scratch8[4] + scratch8[6]);
+    out[1] = (scratch8[1] + scratch8[3]) + (scratch8[5] + scratch8[7]);
+  }
+}
 enum SplitVariant { kSplitKContiguousVec = 0, kSplitKContiguous = 1, kSplitRContiguous = 2, kSplitRContiguousWide = 3 };
 
 // Source with k contiguous, X(r, k) = src[k + r * ld], base and leading dimension multiples of 16 bytes.  One block:
 // 64 rows x 32 k, 256 threads, thread t handles row t / 4 and the 8 values starting at k = 8 * (t % 4), two 16-byte
 // loads.  Blocks are numbered with the k tile fastest.
-template <int KIND>
-__device__ __forceinline__ void split_block_k_contiguous_vec(const SplitJob& job, unsigned block) {
+template <int KIND, bool STATS = false>
+__device__ __forceinline__ void split_block_k_contiguous_vec(const SplitJob& job, unsigned block, SplitStats* stats = nullptr) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)(block / job.fast_tiles) * 64 + (t >> 2);
   const int64_t k = (int64_t)(block % job.fast_tiles) * 32 + (t & 3) * 8;
@@ -157,15 +191,15 @@ __device__ __forceinline__ void split_block_k_contiguous_vec(const SplitJob& job
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] *= prescale;
-  store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k, v);
+  store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k, v, stats);
 }
 
 // Source with k contiguous, any alignment (rows that do not start on 16 bytes: lda = 5003).  One block: 64 rows x
 // 64 k, read with lanes along k, so that a wave instruction fetches one 256-byte run instead of 4 bytes from each of
 // 16 rows, and handed to the row's thread through LDS (`tile`, 64 x 65 floats; the odd stride keeps both the writes
 // and the reads free of bank conflicts).  Blocks are numbered with the k tile fastest.
-template <int KIND>
-__device__ __forceinline__ void split_block_k_contiguous_staged(const SplitJob& job, unsigned block, float* tile) {
+template <int KIND, bool STATS = false>
+__device__ __forceinline__ void split_block_k_contiguous_staged(const SplitJob& job, unsigned block, float* tile, SplitStats* stats = nullptr) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t r0 = (int64_t)(block / job.fast_tiles) * 64, k0 = (int64_t)(block % job.fast_tiles) * 64;
   const float* src = job.src;
@@ -187,15 +221,15 @@ __device__ __forceinline__ void split_block_k_contiguous_staged(const SplitJob& 
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = tile[(t >> 2) * 65 + k_local + e] * prescale;
-    store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k0 + k_local, v);
+    store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k0 + k_local, v, stats);
   }
 }
 
 // Source with r contiguous: X(r, k) = src[r + k * ld], any alignment.  One block: 64 rows x 32 k.  Lanes run along r,
 // so a thread reads the 8 consecutive-k values of its row directly and each read instruction of a wave is a 256-byte
 // run.  Blocks are numbered with the row tile fastest: neighbours in the launch order read neighbouring runs.
-template <int KIND>
-__device__ __forceinline__ void split_block_r_contiguous(const SplitJob& job, unsigned block) {
+template <int KIND, bool STATS = false>
+__device__ __forceinline__ void split_block_r_contiguous(const SplitJob& job, unsigned block, SplitStats* stats = nullptr) {
   const int t = threadIdx.x;
   const int64_t r = (int64_t)(block % job.fast_tiles) * 64 + (t & 63);
   const int64_t k = (int64_t)(block / job.fast_tiles) * 32 + (t >> 6) * 8;
@@ -204,15 +238,15 @@ __device__ __forceinline__ void split_block_r_contiguous(const SplitJob& job, un
   float v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? job.src[r + (k + e) * job.ld] * prescale : 0.0f;
-  store_fragment_row<KIND>(job.packed, job.k_steps_total, r, k, v);
+  store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k, v, stats);
 }
 
 // Source with r contiguous, base and leading dimension multiples of 16 bytes.  One block: 256 rows x 32 k through
 // 32 KiB of LDS (`tile`).  A wave reads one k line of 256 rows per instruction (1 KiB runs, 16 bytes per lane); after
 // the barrier thread t owns row t and picks its 8-value groups out of LDS along k (lanes on consecutive words: no bank
 // conflicts).  5.4 TB/s at 16384^2 against 3.9 TB/s for the 64-row kernel above.
-template <int KIND>
-__device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& job, unsigned block, float* tile) {
+template <int KIND, bool STATS = false>
+__device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& job, unsigned block, float* tile, SplitStats* stats = nullptr) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int64_t r0 = (int64_t)(block % job.fast_tiles) * 256, k0 = (int64_t)(block / job.fast_tiles) * 32;
   const float* src = job.src;
@@ -240,7 +274,7 @@ __device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& jo
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = tile[(8 * g + e) * 256 + t] * prescale;
-    store_fragment_row<KIND>(job.packed, job.k_steps_total, r0 + t, k0 + 8 * g, v);
+    store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r0 + t, k0 + 8 * g, v, stats);
   }
 }
 
@@ -255,35 +289,55 @@ __device__ __forceinline__ unsigned xcd_run_position(unsigned b, unsigned n) {
   return x * per + (x < rem ? x : rem) + b / 8;
 }
 
+// Whether a gated kernel is to run (automatic mode choice: both candidates' kernels are enqueued, and the ones of the
+// mode not chosen return at once).
+__device__ __forceinline__ bool gate_open(const int* gate, int gate_value) {
+  return gate == nullptr || *gate == gate_value;
+}
+
 // One operand per launch; VARIANT is fixed at compile time so that only the kernels that stage through LDS hold any.
-template <int KIND, int VARIANT>
+// STATS (automatic mode choice): block b also leaves its SplitStats at job.stats[2 b], [2 b + 1].
+template <int KIND, int VARIANT, bool STATS = false>
 __global__ void __launch_bounds__(256) split_kernel(const SplitJob job) {
+  if (!gate_open(job.gate, job.gate_value)) return;
+  SplitStats stats;
   if constexpr (VARIANT == kSplitRContiguousWide) {
     __shared__ float tile[32 * 256];
-    split_block_r_contiguous_wide<KIND>(job, blockIdx.x, tile);
+    split_block_r_contiguous_wide<KIND, STATS>(job, blockIdx.x, tile, &stats);
   } else if constexpr (VARIANT == kSplitRContiguous) {
-    split_block_r_contiguous<KIND>(job, blockIdx.x);
+    split_block_r_contiguous<KIND, STATS>(job, blockIdx.x, &stats);
   } else if constexpr (VARIANT == kSplitKContiguousVec) {
-    split_block_k_contiguous_vec<KIND>(job, blockIdx.x);
+    split_block_k_contiguous_vec<KIND, STATS>(job, blockIdx.x, &stats);
   } else {
     __shared__ float tile[64 * 65];
-    split_block_k_contiguous_staged<KIND>(job, xcd_run_position(blockIdx.x, job.blocks), tile);
+    split_block_k_contiguous_staged<KIND, STATS>(job, xcd_run_position(blockIdx.x, job.blocks), tile, &stats);
+  }
+  if constexpr (STATS) {
+    __shared__ double sums[8];
+    // (indexed by the launch's block number: the choice adds all blocks of an operand, in that order)
+    store_block_stats(stats, job.stats + 2 * (size_t)blockIdx.x, sums);
   }
 }
 
 // Both operands of a product in one launch, for small operands where a launch costs more than the work: blocks
 // 0 .. a.blocks - 1 split A, the rest split B.
-template <int KIND>
+template <int KIND, bool STATS = false>
 __global__ void __launch_bounds__(256) split_pair_kernel(const SplitJob a, const SplitJob b) {
+  if (!gate_open(a.gate, a.gate_value)) return;
   __shared__ float tile[32 * 256];
   const bool second = blockIdx.x >= a.blocks;  // block-uniform
   const SplitJob& job = second ? b : a;
   const unsigned block = second ? blockIdx.x - a.blocks : blockIdx.x;
+  SplitStats stats;
   switch (job.variant) {
-    case kSplitRContiguousWide: split_block_r_contiguous_wide<KIND>(job, block, tile); break;
-    case kSplitRContiguous: split_block_r_contiguous<KIND>(job, block); break;
-    case kSplitKContiguousVec: split_block_k_contiguous_vec<KIND>(job, block); break;
-    default: split_block_k_contiguous_staged<KIND>(job, xcd_run_position(block, job.blocks), tile); break;
+    case kSplitRContiguousWide: split_block_r_contiguous_wide<KIND, STATS>(job, block, tile, &stats); break;
+    case kSplitRContiguous: split_block_r_contiguous<KIND, STATS>(job, block, &stats); break;
+    case kSplitKContiguousVec: split_block_k_contiguous_vec<KIND, STATS>(job, block, &stats); break;
+    default: split_block_k_contiguous_staged<KIND, STATS>(job, xcd_run_position(block, job.blocks), tile, &stats); break;
+  }
+  if constexpr (STATS) {
+    __shared__ double sums[8];
+    store_block_stats(stats, job.stats + 2 * (size_t)block, sums);
   }
 }
 

@@ -1,0 +1,227 @@
+"""ECGEMM_MODE_AUTO through the C-ABI: the choice against the oracle's criterion, the result against the chosen mode.
+
+The choice is an integer decided by floating point: both sides sum the same FP64 terms (|x|^2 and the squared part
+the FP16 pair loses), in different orders, and compare against 2^-24.  The test inputs sit well away from that
+threshold (2^-24.6 or below on the FP16 side, 2^-20.4 or above on the other), so the order cannot decide.
+What the call returns must be, bit for bit, what ecgemm_sgemm returns in the chosen mode.
+"""
+import numpy as np
+import pytest
+
+import seeded_inputs as si
+from oracle import gemm, split
+from gpu_util import empty_colmajor, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+TYPE1, TYPE3, TYPE4 = (-15, 14), (-35, -15), (-100, -35)       # exp_rand ranges of the paper's input types
+
+
+def _draw(rows, cols, dist, seed, matrix_id, pad):
+    if dist == "urand":
+        return si.urand(rows, cols, seed, matrix_id, ld=rows + pad)
+    return si.exp_rand(rows, cols, dist[0], dist[1], seed, matrix_id, ld=rows + pad)
+
+
+def _problem(transA, transB, M, N, K, dist_a, dist_b, seed, pad):
+    ar, ac = (M, K) if transA == "N" else (K, M)
+    br, bc = (K, N) if transB == "N" else (N, K)
+    return _draw(ar, ac, dist_a, seed, si.ID_A, pad), _draw(br, bc, dist_b, seed, si.ID_B, pad), si.urand(M, N, seed, si.ID_C)
+
+
+def _run(h, call, transA, transB, M, N, K, alpha, A, B, beta, C, mode):
+    import torch
+    import paper_2203_03341_amd as ec
+    ops = {"N": ec.OP_N, "T": ec.OP_T}
+    dA, dB, dC = to_device(A), to_device(B), to_device(C)
+    call(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], beta, dC, C.shape[0], mode)
+    torch.cuda.synchronize()
+    return to_host(dC, C.shape[0], N)
+
+
+def _check(h, transA, transB, M, N, K, dist_a, dist_b, seed=0, pad=0, alpha=1.5, beta=0.5, noalloc=False):
+    import paper_2203_03341_amd as ec
+    A, B, C = _problem(transA, transB, M, N, K, dist_a, dist_b, seed, pad)
+    opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)
+    want_mode = ec.MODE_FP16_SPLIT if split.fp16_pair_represents(opA, opB) else ec.MODE_BF16_FULL
+    got = _run(h, h.sgemm_noalloc if noalloc else h.sgemm, transA, transB, M, N, K, alpha, A, B, beta, C, ec.MODE_AUTO)
+    assert h.auto_choice() == want_mode, (dist_a, dist_b, split.fp16_pair_lost_fraction(opA), split.fp16_pair_lost_fraction(opB))
+    direct = _run(h, h.sgemm, transA, transB, M, N, K, alpha, A, B, beta, C, want_mode)
+    assert np.array_equal(got.view(np.uint32), direct.view(np.uint32))
+    # and the point of choosing: the result meets the accuracy bar of the method whatever the inputs
+    c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C)
+    c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C)
+    assert gemm.relative_residual(c64, got[:M, :]) <= 1.25 * gemm.relative_residual(c64, c32)
+    return want_mode
+
+
+@pytest.mark.parametrize("transA,transB,pad", [("N", "N", 0), ("T", "T", 0), ("N", "T", 1), ("T", "N", 3)])
+def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
+    """Every split kernel variant (both storage orders, aligned and not) measures the same thing; ragged sizes with
+    several blocks per operand; either operand alone can force the full-range mode."""
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    M, N, K = 300, 260, 200
+    chosen = [
+        _check(h, transA, transB, M, N, K, "urand", "urand", seed=1, pad=pad),
+        _check(h, transA, transB, M, N, K, TYPE1, TYPE1, seed=2, pad=pad),
+        _check(h, transA, transB, M, N, K, TYPE3, TYPE3, seed=3, pad=pad),
+        _check(h, transA, transB, M, N, K, TYPE4, TYPE1, seed=4, pad=pad),
+        _check(h, transA, transB, M, N, K, TYPE1, TYPE3, seed=5, pad=pad),
+    ]
+    assert chosen == [ec.MODE_FP16_SPLIT, ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL, ec.MODE_BF16_FULL, ec.MODE_BF16_FULL]
+    h.destroy()
+
+
+def test_sliced_tiles_large_operands_and_the_builtin_workspace():
+    """Deep K (tiles sliced along K, gated reduction kernels), operands of more than 8192 split blocks (one launch per
+    operand instead of the pair launch), and the entry point that allocates nothing."""
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    for dist in ("urand", TYPE3):
+        _check(h, "N", "N", 512, 384, 4608, dist, dist, seed=6)
+        _check(h, "T", "N", 1100, 900, 1300, dist, dist, seed=7, pad=1, noalloc=True)
+        _check(h, "N", "T", 2304, 2048, 2080, dist, dist, seed=8, alpha=1.0, beta=0.0)
+    h.destroy()
+
+
+def test_special_values_and_prescaling():
+    import torch
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    M, N, K = 200, 150, 96
+    A, B, C = _problem("N", "N", M, N, K, "urand", "urand", 9, 0)
+    ops = (ec.OP_N, ec.OP_N)
+
+    def choice_for(A_host, B_host):
+        dA, dB, dC = to_device(A_host), to_device(B_host), to_device(C)
+        h.sgemm(*ops, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
+        return h.auto_choice(), to_host(dC, M, N)
+
+    assert choice_for(A, B)[0] == ec.MODE_FP16_SPLIT
+    for poison in (np.nan, np.inf, np.float32(1e6)):          # NaN, infinity, a value beyond the FP16 range
+        bad = A.copy(order="F")
+        bad[17, 5] = poison
+        assert choice_for(bad, B)[0] == ec.MODE_BF16_FULL
+        assert choice_for(A, B)[0] == ec.MODE_FP16_SPLIT          # (and the previous call's choice does not stick)
+    zeros = np.zeros_like(A)
+    mode, out = choice_for(zeros, B)                          # nothing to lose in an all-zero operand
+    assert mode == ec.MODE_FP16_SPLIT and np.all(out == 0.0)
+    # the handle's pre-scaling moves Type 3 inputs into the window of the pair: the choice is made after it
+    A3, B3, _ = _problem("N", "N", M, N, K, TYPE3, TYPE3, 10, 0)
+    assert choice_for(A3, B3)[0] == ec.MODE_BF16_FULL
+    h.set_scaling(29, 29)
+    mode, scaled = choice_for(A3, B3)
+    assert mode == ec.MODE_FP16_SPLIT
+    direct = _run(h, h.sgemm, "N", "N", M, N, K, 1.0, A3, B3, 0.0, C, ec.MODE_FP16_SPLIT)
+    assert np.array_equal(scaled.view(np.uint32), direct.view(np.uint32))
+    h.set_scaling(0, 0)
+    h.destroy()
+
+
+def test_workspace_size_caller_workspace_and_refusals():
+    import torch
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    M, N, K = 700, 520, 3000
+    A, B, C = _problem("N", "N", M, N, K, TYPE3, TYPE3, 11, 0)
+    dA, dB, dC = to_device(A), to_device(B), to_device(C)
+    need = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_AUTO)
+    assert need > max(h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, m) for m in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL))
+    want = _run(h, h.sgemm, "N", "N", M, N, K, 1.0, A, B, 0.0, C, ec.MODE_BF16_FULL)
+    guard = 4096
+    buf = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device="cuda")
+    h.set_workspace(buf, need)
+    h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
+    assert h.auto_choice() == ec.MODE_BF16_FULL
+    assert np.array_equal(to_host(dC, M, N).view(np.uint32), want.view(np.uint32))
+    assert bool((buf[need:] == 0x5A).all())                     # nothing is written past the size asked for
+    h.set_workspace(buf, need - 256)
+    with pytest.raises(ec.EcgemmError) as err:
+        h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
+    assert err.value.status == ec.ERR_ALLOC
+    h.set_workspace(None, 0)
+    # no choice to report: the last call failed, was in a fixed mode, or did nothing
+    for make_call in (lambda: None,
+                      lambda: h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_FP16_SPLIT),
+                      lambda: h.sgemm(ec.OP_N, ec.OP_N, M, N, 0, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)):
+        make_call()
+        with pytest.raises(ec.EcgemmError) as err:
+            h.auto_choice()
+        assert err.value.status == ec.ERR_INVALID_ARG and err.value.argument == 1
+    # where the automatic mode does not exist
+    scales_a = torch.zeros(M, dtype=torch.int32, device="cuda")
+    scales_b = torch.zeros(N, dtype=torch.int32, device="cuda")
+    with pytest.raises(ec.EcgemmError) as err:
+        h.sgemm_scaled(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO, scales_a, scales_b)
+    assert err.value.status == ec.ERR_UNSUPPORTED
+    h.set_shape(ec.SHAPE_128x128_FUSED)
+    with pytest.raises(ec.EcgemmError) as err:
+        h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
+    assert err.value.status == ec.ERR_UNSUPPORTED
+    with pytest.raises(ec.EcgemmError) as err:
+        h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_AUTO)
+    assert err.value.status == ec.ERR_UNSUPPORTED
+    h.set_shape(ec.SHAPE_AUTO)
+    packed = torch.empty(ec.split_size(M, K, ec.MODE_BF16_FULL), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ec.EcgemmError) as err:
+        h.split(ec.OP_N, M, K, dA, M, ec.MODE_AUTO, packed)
+    assert err.value.status == ec.ERR_INVALID_ARG and err.value.argument == 7
+    with pytest.raises(ec.EcgemmError) as err:
+        h.product(M, N, K, 1.0, packed, packed, 0.0, dC, M, ec.MODE_AUTO)
+    assert err.value.status == ec.ERR_INVALID_ARG and err.value.argument == 11
+    with pytest.raises(ec.EcgemmError) as err:
+        ec.plan_info(M, N, K, ec.MODE_AUTO)
+    assert err.value.status == ec.ERR_INVALID_ARG
+    h.destroy()
+
+
+def test_one_captured_graph_takes_either_branch_depending_on_the_data():
+    """The call never waits for the GPU, so it can be recorded into a HIP graph; the choice is made again on every
+    replay, from whatever the operand buffers hold then."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 640, 512, 1536
+    inputs = {"fp16": _problem("N", "T", M, N, K, "urand", "urand", 13, 0),
+              "bf16": _problem("N", "T", M, N, K, TYPE3, TYPE4, 14, 0)}
+    h = ec.Handle()
+    stream = torch.cuda.Stream()
+    h.set_stream(stream.cuda_stream)
+    nbytes = h.workspace_size(ec.OP_N, ec.OP_T, M, N, K, ec.MODE_AUTO)
+    workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    h.set_workspace(workspace, nbytes)
+    dev = {k: tuple(to_device(x) for x in v) for k, v in inputs.items()}
+    dA, dB, dC_in = (torch.empty_like(t) for t in dev["fp16"])
+    dC = torch.empty_like(dC_in)
+
+    def load(which):
+        for dst, src in zip((dA, dB, dC_in), dev[which]):
+            dst.copy_(src)
+
+    def call(mode):
+        dC.copy_(dC_in)
+        h.sgemm(ec.OP_N, ec.OP_T, M, N, K, 1.5, dA, M, dB, N, 0.5, dC, M, mode)
+
+    eager = {}
+    with torch.cuda.stream(stream):
+        for which, mode in (("fp16", ec.MODE_FP16_SPLIT), ("bf16", ec.MODE_BF16_FULL)):
+            load(which)
+            call(mode)
+            stream.synchronize()
+            eager[which] = dC.cpu().numpy().copy()
+        load("fp16")
+        call(ec.MODE_AUTO)                      # once eagerly, so that nothing is created during the capture
+        stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        call(ec.MODE_AUTO)
+    for which in ("bf16", "fp16", "fp16", "bf16"):
+        with torch.cuda.stream(stream):
+            load(which)
+            dC.fill_(float("nan"))
+        stream.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy().view(np.uint32), eager[which].view(np.uint32)), which
+    del graph
+    h.destroy()

@@ -38,7 +38,18 @@ int main(void) {
     CHECK(ecgemm_plan_info(NULL, 300, 200, 100, (ecgemm_mode_t)mode, &info) == ECGEMM_OK && info.workspace_bytes == bytes);
   }
   CHECK(ecgemm_split_size(-1, 1, ECGEMM_MODE_FP16_SPLIT, &bytes) == ECGEMM_ERR_INVALID_ARG);
-  CHECK(ecgemm_split_size(1, 1, (ecgemm_mode_t)10, &bytes) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_split_size(1, 1, ECGEMM_MODE_AUTO, &bytes) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_split_size(1, 1, (ecgemm_mode_t)11, &bytes) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_plan_info(NULL, 300, 200, 100, ECGEMM_MODE_AUTO, &info) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, (ecgemm_mode_t)11, &bytes) == ECGEMM_ERR_INVALID_ARG);
+  { /* the automatic mode's workspace serves either candidate and holds its statistics */
+    size_t fp16 = 0, bf16 = 0, both = 0;
+    CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_T, 3000, 2000, 5000, ECGEMM_MODE_FP16_SPLIT, &fp16) == ECGEMM_OK);
+    CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_T, 3000, 2000, 5000, ECGEMM_MODE_BF16_FULL, &bf16) == ECGEMM_OK);
+    CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_T, 3000, 2000, 5000, ECGEMM_MODE_AUTO, &both) == ECGEMM_OK);
+    CHECK(both > fp16 && both > bf16 && both % 256 == 0 && both < bf16 + fp16);
+    CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_T, 0, 2000, 5000, ECGEMM_MODE_AUTO, &both) == ECGEMM_OK && both == 0);
+  }
   CHECK(ecgemm_split_size(1, 1, ECGEMM_MODE_FP16_SPLIT, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_workspace_size(NULL, (ecgemm_op_t)2, ECGEMM_OP_N, 1, 1, 1, ECGEMM_MODE_FP16_SPLIT, &bytes) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, (ecgemm_mode_t)-1, &bytes) == ECGEMM_ERR_INVALID_ARG);

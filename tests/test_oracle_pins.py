@@ -516,3 +516,38 @@ def test_gemm_blocked_chains_the_blocks_in_ascending_k():
     for fn in (emu.mma_rn, emu.mma_rz):
         assert emu.gemm_blocked(a, b, fn, 1)[0, 0] == 0.0
         assert emu.gemm_blocked(a[:, ::-1], b[::-1, :], fn, 1)[0, 0] == 1.0
+
+
+def test_fp16_pair_lost_fraction_and_the_automatic_choice():
+    """The criterion of the automatic mode, against values worked out by hand and against what it is for.
+
+    By hand (halfhalf, round to nearest even): an 11 + 11 bit value is represented exactly; 1 + 2^-12 + 2^-23 has
+    v16 = 1 and a scaled residual 2^-1 + 2^-12 that ties down to 2^-1, so exactly 2^-23 is lost; 2^-40 is below
+    everything the pair can hold (all of it is lost); 70000 saturates at 65504, and the scaled residual (32 x 2^11 after the cut) at 65504 too.
+    For what it is for: on the paper's input types the choice agrees with which of the two models reaches the accuracy
+    of FP32 (section "Effect of the exponent range of input matrices")."""
+    assert split.fp16_pair_lost_fraction(np.float32([1.0 + 2.0 ** -10 + 2.0 ** -21, -3.5, 0.0])) == 0.0
+    x = np.float32([1.0 + 2.0 ** -12 + 2.0 ** -23])
+    assert split.fp16_pair_lost_fraction(x) == pytest.approx(2.0 ** -23 / float(x[0]), rel=1e-12)
+    assert split.fp16_pair_lost_fraction(np.float32([2.0 ** -40])) == 1.0
+    assert split.fp16_pair_lost_fraction(np.float32([70000.0])) == pytest.approx((70000.0 - 65504.0 - 65504.0 / 2048.0) / 70000.0, rel=1e-12)
+    assert split.fp16_pair_lost_fraction(np.zeros(5, np.float32)) == 0.0
+    assert np.isnan(split.fp16_pair_lost_fraction(np.float32([1.0, np.nan])))
+    # two elements: sqrt((e1^2 + e2^2) / (x1^2 + x2^2)), not a mean of ratios
+    pair = np.float32([1.0 + 2.0 ** -12 + 2.0 ** -23, 4.0])
+    assert split.fp16_pair_lost_fraction(pair) == pytest.approx(2.0 ** -23 / np.sqrt(float(pair[0]) ** 2 + 16.0), rel=1e-12)
+    one = np.float32([[1.0]])
+    assert split.fp16_pair_represents(one, one)
+    assert not split.fp16_pair_represents(one, np.float32([[1.0, np.nan]]))
+    assert not split.fp16_pair_represents(np.float32([[2.0 ** -40]]), one)      # either operand decides
+    assert not split.fp16_pair_represents(one, np.float32([[70000.0]]))
+    assert split.fp16_pair_represents(x, x, tolerance=2.0 ** -23) and not split.fp16_pair_represents(x, x)
+
+    n = 192
+    for a_rng, b_rng in (((-15, 14), (-15, 14)), ((-35, -15), (-35, -15)), ((-100, -35), (-15, 14)), (None, None)):
+        A = si.urand(n, n, 0, si.ID_A) if a_rng is None else si.exp_rand(n, n, *a_rng, 0, si.ID_A)
+        B = si.urand(n, n, 0, si.ID_B) if b_rng is None else si.exp_rand(n, n, *b_rng, 0, si.ID_B)
+        c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+        r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
+        r16 = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B))
+        assert split.fp16_pair_represents(A, B) == (r16 <= r32), (a_rng, b_rng, r16, r32)
