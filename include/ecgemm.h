@@ -234,7 +234,7 @@ ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int
  * 2^col_log2_scale_b[n] before the split (exact), and element (m, n) of the product multiplied by 2^-row_log2_scale_a[m]
  * and then by 2^-col_log2_scale_b[n] (exact unless the result leaves the FP32 range) before alpha / beta.  The vectors
  * are device arrays of M and N 32-bit integers in [-126, 126], read during the call and not kept; both NULL gives
- * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.  Not available with the fused kernel shape (ecgemm_debug.h).
+ * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.
  *
  * ecgemm_row_scales writes such a vector: for each row r of X = op(src) (rows x depth; op and ld as in ecgemm_split)
  * the exponent that moves the row's largest non-zero finite element into the binade 2^target_exponent, 0 for a row

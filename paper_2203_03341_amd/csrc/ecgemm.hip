@@ -467,8 +467,10 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
 // Steps 1 to 5 in one kernel, on the caller's FP32 operands (small products).
 ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                              int64_t K, float alpha, const float* A, int64_t lda, const float* B, int64_t ldb, float beta,
-                             float* C, int64_t ldc, float* partials) {
+                             float* C, int64_t ldc, float* partials, const int* row_log2_scale, const int* col_log2_scale) {
   FusedParams fp;
+  fp.row_log2_scale = row_log2_scale;
+  fp.col_log2_scale = col_log2_scale;
   fp.A = A;
   fp.B = B;
   fp.lda = lda;
@@ -1083,8 +1085,6 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape);
   if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
-  if (row_log2_scale_a && pl.shape->fused)
-    return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm_scaled: the fused kernel shape takes no scaling vectors");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
   SplitJob job_a, job_b;
   char* ws = nullptr;
@@ -1116,7 +1116,8 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
 
   if (pl.shape->fused) {
     if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
-    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, partials);
+    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, partials, row_log2_scale_a,
+                      col_log2_scale_b);
   } else {
     st = launch_split(h, mode, job_a, &job_b);
     if (st != ECGEMM_OK) return st;

@@ -25,6 +25,9 @@ struct FusedParams {
   int stages;                          // ceil(K / 32)
   int tiles_m, tiles_n, splits;        // splits > 1: every tile is cut into slices along K, raw sums go to partials
   float alpha, beta, out_scale;
+  // per-row / per-column pre-scaling as in ProductParams (both null, or both set)
+  const int* row_log2_scale;           // device, M entries
+  const int* col_log2_scale;           // device, N entries
   float* C;
   float* partials;                     // [splits][tiles][128][128]
 };
@@ -60,9 +63,10 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   const int64_t ld = for_b ? p.ldb : p.lda;
   const bool k_contiguous = for_b ? p.b_k_contiguous : p.a_k_contiguous;
   const bool vec = for_b ? p.b_vec : p.a_vec;
-  const float prescale = for_b ? p.prescale_b : p.prescale_a;
   const int64_t row = (for_b ? (int64_t)tile_n * BN : (int64_t)tile_m * BM) + u;
   const bool row_ok = row < (for_b ? p.N : p.M);
+  float prescale = for_b ? p.prescale_b : p.prescale_a;
+  if (p.row_log2_scale != nullptr && row_ok) prescale *= row_scale_factor((for_b ? p.col_log2_scale : p.row_log2_scale)[row]);
   // Requests the 32 values X(row, k0 .. k0 + 31) of a stage.  Every load is unconditional on a clamped, valid address
   // (a load under a per-lane condition would make the compiler wait for it at the end of its branch, one load at a
   // time); what lies beyond the matrix is replaced by zeros in deposit(), after the multiplications that the loads
@@ -179,7 +183,24 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
           store(m_base + i * 32, n_base + j * 32 + 8 * (v / 4) + (v % 4),
                 (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
   };
-  if (p.splits > 1) {
+  if (p.row_log2_scale != nullptr) {
+    // rows of op(A) and columns of op(B) were scaled one by one before the split: undo that per element
+    float* out = p.splits > 1 ? p.partials + ((int64_t)split * tiles + pid) * (BM * BN) : nullptr;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    for_each_output([&](int64_t m, int64_t n, float c) {
+      if (m < p.M && n < p.N) {
+        c = c * exp2_int(-p.row_log2_scale[m]) * exp2_int(-p.col_log2_scale[n]);
+        if (out) {
+          out[(n - n0) * BM + (m - m0)] = c;
+        } else {
+          float* dst = p.C + m + n * p.ldc;
+          store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
+        }
+      } else if (out) {
+        out[(n - n0) * BM + (m - m0)] = 0.0f;
+      }
+    });
+  } else if (p.splits > 1) {
     float* out = p.partials + ((int64_t)split * tiles + pid) * (BM * BN);
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * BM + (m - m0)] = c; });

@@ -100,5 +100,14 @@ def sample_indices(n: int, count: int, seed: int) -> np.ndarray:
     return np.sort(np.argsort(keys, kind="stable")[:count]).astype(np.int64)
 
 
+def stratified_indices(n: int, stride: int, seed: int) -> np.ndarray:
+    """One index out of every block of `stride` consecutive ones in range(n) (the last block may be shorter),
+    sorted, reproducible from `seed`: a sample of rows that leaves no tile row of C out."""
+    starts = np.arange(0, n, stride, dtype=np.int64)
+    sizes = np.minimum(stride, n - starts)
+    keys = _splitmix64(starts.astype(np.uint64) + _U64(_counter_base(seed, 14)))
+    return starts + (keys % sizes.astype(np.uint64)).astype(np.int64)
+
+
 # Matrix ids used throughout: keep A, B and C draws of one problem independent.
 ID_A, ID_B, ID_C = 0, 1, 2

@@ -400,7 +400,7 @@ def test_every_arrangement_of_the_xcds_over_the_tile_grid(case):
     import paper_2203_03341_amd as ec
     M, N, K, n = case
     assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["column_bands"] == n
-    _check("N", "N", M, N, K, 1.0, 0.0, "fp16", "urand", seed=9, rows=si.sample_indices(M, 48, seed=4))
+    _check("N", "N", M, N, K, 1.0, 0.0, "fp16", "urand", seed=9, rows=si.stratified_indices(M, 64, seed=4))
     A, B = _inputs(M, N, K, "N", "N", "urand", 9)
     got = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "fp16")[:M, :N]
     other = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, "fp32")[:M, :N]
@@ -415,7 +415,7 @@ def test_deep_k_in_one_item_keeps_fp32_accuracy():
     M, N, K = 2235, 9758, 32279
     assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT)["slices"] == 1
     for mode in ("fp16", "bf16"):
-        r_gpu, r_cpu = _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=29, pad=1, rows=si.sample_indices(M, 24, seed=3))
+        r_gpu, r_cpu = _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=29, pad=1, rows=si.stratified_indices(M, 64, seed=3))
         assert r_gpu < 0.6 * r_cpu
 
 
@@ -425,7 +425,7 @@ def test_column_bands_under_a_persistent_grid():
     import paper_2203_03341_amd as ec
     p = ec.plan_info(8192, 8192, 4096, ec.MODE_BF16_FULL)
     assert (p["persistent"], p["column_bands"]) == (1, 2)
-    _check("N", "N", 8192, 8192, 4096, 1.0, 0.0, "bf16", "urand", seed=23, rows=si.sample_indices(8192, 32, seed=9))
+    _check("N", "N", 8192, 8192, 4096, 1.0, 0.0, "bf16", "urand", seed=23, rows=si.stratified_indices(8192, 64, seed=9))
     A, B = _inputs(8192, 8192, 4096, "N", "N", "urand", 23)
     got = _gpu_sgemm("N", "N", 8192, 8192, 4096, 1.0, A, B, 0.0, None, "bf16")[:8192, :8192]
     other = _gpu_sgemm("N", "N", 8192, 8192, 4096, 1.0, A, B, 0.0, None, "fp16")[:8192, :8192]
@@ -439,7 +439,7 @@ def test_column_bands_of_unequal_width_with_ragged_edges(case):
     import paper_2203_03341_amd as ec
     tA, tB, M, N, K, mode, bands = case
     assert ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT if mode == "fp16" else ec.MODE_BF16_FULL)["column_bands"] == bands
-    _check(tA, tB, M, N, K, 1.5, 0.5, mode, "urand", seed=13, pad=3, rows=si.sample_indices(M, 40, seed=6))
+    _check(tA, tB, M, N, K, 1.5, 0.5, mode, "urand", seed=13, pad=3, rows=si.stratified_indices(M, 64, seed=6))
 
 
 @pytest.mark.parametrize("case", [(960, 2304, 18688, "fp16"), (512, 512, 16384, "bf16"), (3000, 3000, 1100, "fp16"),
@@ -452,7 +452,7 @@ def test_slice_counts_picked_by_the_cost_estimate(case):
     M, N, K, mode = case
     p = ec.plan_info(M, N, K, ec.MODE_FP16_SPLIT if mode == "fp16" else ec.MODE_BF16_FULL)
     assert p["slices"] > 1 and p["sliced_tiles"] > 0
-    _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=17, rows=si.sample_indices(M, 32, seed=8))
+    _check("N", "N", M, N, K, 1.0, 0.0, mode, "urand", seed=17, rows=si.stratified_indices(M, 64, seed=8))
     A, B = _inputs(M, N, K, "N", "N", "urand", 17)
     first = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)
     again = _gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode)
@@ -549,7 +549,10 @@ def test_fp16_mode_fails_outside_its_range_like_the_paper_says():
 # ----- the baseline's own sizes, in the launch configuration bench.py times; oracle on seeded sample rows of C
 
 def _full_size(M, N, K, transA, transB, alpha, beta, mode, dist, nrows, seed=0):
-    rows = si.sample_indices(M, nrows, seed=11 + seed)
+    """The oracle on `nrows` rows of C, one out of every M / nrows consecutive rows (at most 64 apart in every test
+    below), all columns: no output tile, and no wave's part of one, is left uncompared."""
+    assert M / nrows <= 64
+    rows = si.stratified_indices(M, -(-M // nrows), seed=11 + seed)
     return _check(transA, transB, M, N, K, alpha, beta, mode, dist, seed=seed, rows=rows)
 
 
@@ -559,8 +562,9 @@ def test_config2_4096_cubed(mode, seed):
     _full_size(4096, 4096, 4096, "N", "N", 1.0, 0.0, mode, "urand", 256, seed=seed)
 
 
+@pytest.mark.timeout(400)          # the oracle's two products over 256 rows of 16384 x 16384 take most of a minute
 def test_config3_16384_cubed_fp16_limited_exponent():
-    _full_size(16384, 16384, 16384, "N", "N", 1.0, 0.0, "fp16", ((-15, 15), (-15, 15)), 64)
+    _full_size(16384, 16384, 16384, "N", "N", 1.0, 0.0, "fp16", ((-15, 15), (-15, 15)), 256)
 
 
 def test_config4_8192_cubed_bf16_wide_exponent():
@@ -749,6 +753,25 @@ def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
     assert np.mean(lost[live]) > 0.5                                 # most rows are lost without the scaling
     assert np.all(r_gpu[live] <= 2.0 * r_cpu[live] + 1e-12)          # every single row is as good as FP32's
     assert gemm.relative_residual(c64, scaled) <= RATIO * gemm.relative_residual(c64, c32)
+    # the one-kernel shape scales in its own split: held to the same bar, and where nothing is sliced along K the
+    # same bits as the split-first shapes
+    h.set_shape(ec.SHAPE_128x128_FUSED)
+    fused = run(True)
+    r_fused = row_residuals(fused)
+    assert np.all(np.isfinite(fused)) and np.all(r_fused[live] <= 2.0 * r_cpu[live] + 1e-12)
+    shallow = 96                                                      # too shallow for any shape to slice
+    outs = []
+    for shape in (ec.SHAPE_128x128_FUSED, ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4):
+        h.set_shape(shape)
+        assert h.plan_info(M, N, shallow, ec.MODE_FP16_SPLIT)["slices"] == 1
+        dC = to_device(C)
+        h.sgemm_scaled(ops[transA], ops[transB], M, N, shallow, 1.5, dA, A.shape[0], dB, B.shape[0], 0.5, dC, M,
+                       ec.MODE_FP16_SPLIT, sa, sb)
+        torch.cuda.synchronize()
+        outs.append(to_host(dC, M, N))
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    assert np.array_equal(outs[1].view(np.uint32), outs[2].view(np.uint32))
+    h.set_shape(ec.SHAPE_AUTO)
     with pytest.raises(ec.EcgemmError):                              # one vector without the other
         h.sgemm_scaled(ops[transA], ops[transB], M, N, K, 1.0, dA, A.shape[0], dB, B.shape[0], 0.0, to_device(C), M,
                        ec.MODE_FP16_SPLIT, sa, None)
