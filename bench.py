@@ -35,8 +35,12 @@ PEAK_HBM_GBS = 8000.0             # HBM3E, published
 # inside the run, so these are recorded figures, keyed by workload; None where no counter run exists.
 # FETCH_SIZE x 2.0 (the counter shows half of a known 1 GiB read) + WRITE_SIZE x 1.0, in bytes.
 MEASURED_TRAFFIC_BYTES = {
-    "c3_16384_fp16_exprand15": 3.55e10,      # profiles/product_kernel_fp16_16384cubed.md: 34.4 GB + 1.08 GB
-    "c4_8192_bf16_widerange": 7.0e9,         # profiles/product_kernel_bf16_8192cubed.md: 6.7 GB + 0.27 GB
+    "c3_16384_fp16_exprand15": 3.55e10,      # profiles/product_kernel_fp16_16384cubed.md: 34.4 GB + 1.07 GB
+    "c4_8192_bf16_widerange": 6.98e9,        # profiles/product_kernel_bf16_8192cubed.md: 6.71 GB + 0.27 GB
+    "c5_tallskinny_fp16": 1.36e9,            # profiles/product_kernel_fp16_tallskinny_16384x16384x256.md: 0.285 GB + 1.07 GB
+    "c2_4096_fp16_urand": 6.04e8,            # profiles/product_kernel_fp16_4096cubed_persistent.md: 537 MB + 67 MB
+    "c5_deepk_fp16": 5.71e8,                 # profiles/product_kernel_fp16_deepk_1024x1024x65536.md: 537 MB + 33.5 MB
+                                             # (product kernel; its reduction moves another 38 MB)
 }
 
 WORKLOADS = {
