@@ -11,6 +11,9 @@ with HIP events on the launch stream), the relative residual against an FP64 ref
 naive FP32 product (both from the CPU oracle, on a seeded sample of rows of C), and the oracle's own speed
 on the host cores as `cpu_baseline`.  After the headline the default run also times the other baseline
 configurations (both modes) and lists them under `other_workloads`, each with its own accuracy check.
+Energy: board power and shader clock are sampled while the headline call loops (`power`), while the same operands go
+through this library's FP32 mode (`fp32_mode_of_this_library`, the FP32 baseline of the comparison) and while the
+BF16 8192^3 configuration loops (its entry in `other_workloads`).
 """
 from __future__ import annotations
 
@@ -342,8 +345,9 @@ def main():
                     help="after the timed steps, loop the same call for this long while sampling board power and shader "
                          "clock from sysfs every 20 ms (the paper samples NVML every 0.02 s over >= 2 s); 0 disables")
     ap.add_argument("--library-sgemm", action="store_true",
-                    help="context measurement, off by default: the vendor library's FP32 GEMM and this library's own FP32 "
-                         "mode on the same operands, timed and power-sampled after the run proper")
+                    help="context measurement, off by default: the vendor library's FP32 GEMM on the same operands, timed "
+                         "and power-sampled after the run proper (this library's own FP32 mode always is, as the energy "
+                         "baseline, unless --power-seconds is 0)")
     ap.add_argument("--no-other-workloads", dest="others", action="store_false",
                     help="with the default workload: do not time the other baseline configurations afterwards")
     ap.add_argument("--no-ceiling", action="store_true", help="skip the matrix-instruction-only rate measurement")
@@ -398,33 +402,12 @@ def main():
     # ---- board power and clock while the same call runs back to back
     power = power_while(torch, w.step, w.flops, args.power_seconds) if args.power_seconds > 0 else None
 
-    # ---- context only, on request: the vendor library's FP32 GEMM (rocBLAS / hipBLASLt behind torch.matmul) on the same
-    # operands, timed and power-sampled the same way (the paper sets its method against cuBLAS SGEMM)
-    library = None
-    if args.library_sgemm:
-        opA_T = w.dA if w.transA == "N" else w.dA.T        # K x M as a row-major tensor
-        opB_T = w.dB if w.transB == "N" else w.dB.T        # N x K
-        ref = torch.empty((N, M), dtype=torch.float32, device="cuda")
-
-        def library_call():
-            torch.matmul(opB_T, opA_T, out=ref)
-
-        for _ in range(3):
-            library_call()
-        torch.cuda.synchronize()
-        l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = max(3, min(steps, int(np.ceil(1000.0 / max(w.expected_ms * 4, 0.05)))))
-        l0.record(stream)
-        for _ in range(reps):
-            library_call()
-        l1.record(stream)
-        torch.cuda.synchronize()
-        lib_ms = l0.elapsed_time(l1) / reps
-        library = {"what": "torch.matmul, float32, allow_tf32 off", "ms_per_call": round(lib_ms, 4),
-                   "tflops": round(w.flops / (lib_ms * 1e-3) / 1e12, 2),
-                   "power": power_while(torch, library_call, w.flops, args.power_seconds) if args.power_seconds > 0 else None}
-        del ref
-        # the same comparison inside this code base: FP32 operands on the FP32 matrix instruction, same kernels
+    # ---- the FP32 baseline inside this code base (the paper's power comparison is against FP32 GEMM): the same
+    # operands through the same kernels on the FP32 matrix instruction, timed and power-sampled the same way
+    l0, l1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(3, min(steps, int(np.ceil(1000.0 / max(w.expected_ms * 4, 0.05)))))
+    fp32_mode = None
+    if args.power_seconds > 0 and not w.auto:
         own_bytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_FP32_MFMA)
         own_ws = torch.empty(own_bytes, dtype=torch.uint8, device="cuda")
         h.set_workspace(own_ws, own_bytes)
@@ -443,12 +426,36 @@ def main():
         l1.record(stream)
         torch.cuda.synchronize()
         own_ms = l0.elapsed_time(l1) / reps
-        library["fp32_mode_of_this_library"] = {
-            "what": "ecgemm_sgemm, ECGEMM_MODE_FP32_MFMA", "ms_per_call": round(own_ms, 4),
-            "tflops": round(w.flops / (own_ms * 1e-3) / 1e12, 2),
-            "power": power_while(torch, own_call, w.flops, args.power_seconds) if args.power_seconds > 0 else None}
+        fp32_mode = {"what": "ecgemm_sgemm, ECGEMM_MODE_FP32_MFMA, same operands", "ms_per_call": round(own_ms, 4),
+                     "tflops": round(w.flops / (own_ms * 1e-3) / 1e12, 2),
+                     "power": power_while(torch, own_call, w.flops, args.power_seconds)}
         h.set_workspace(w.ws, w.ws_bytes)
         del own_out, own_ws
+
+    # ---- context only, on request: the vendor library's FP32 GEMM (rocBLAS / hipBLASLt behind torch.matmul) on the same
+    # operands (the paper sets its method against cuBLAS SGEMM)
+    library = None
+    if args.library_sgemm:
+        opA_T = w.dA if w.transA == "N" else w.dA.T        # K x M as a row-major tensor
+        opB_T = w.dB if w.transB == "N" else w.dB.T        # N x K
+        ref = torch.empty((N, M), dtype=torch.float32, device="cuda")
+
+        def library_call():
+            torch.matmul(opB_T, opA_T, out=ref)
+
+        for _ in range(3):
+            library_call()
+        torch.cuda.synchronize()
+        l0.record(stream)
+        for _ in range(reps):
+            library_call()
+        l1.record(stream)
+        torch.cuda.synchronize()
+        lib_ms = l0.elapsed_time(l1) / reps
+        library = {"what": "torch.matmul, float32, allow_tf32 off", "ms_per_call": round(lib_ms, 4),
+                   "tflops": round(w.flops / (lib_ms * 1e-3) / 1e12, 2),
+                   "power": power_while(torch, library_call, w.flops, args.power_seconds) if args.power_seconds > 0 else None}
+        del ref
 
     result = {
         "metric": METRIC, "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
@@ -461,7 +468,7 @@ def main():
         "split_ms": round(split_ms, 4), "product_ms": round(product_ms, 4),
         "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
         "roofline": roofline, "roofline_hbm": roofline_hbm, "roofline_split": roofline_split,
-        "power": power, "library_sgemm": library,
+        "power": power, "fp32_mode_of_this_library": fp32_mode, "library_sgemm": library,
     }
 
     if not args.no_oracle:
@@ -492,6 +499,8 @@ def main():
                      "product_ms": round(o_product_ms, 4), "split_ms": round(o_split_ms, 4),
                      "roofline_frac": o_mfma["frac"], "roofline_hbm_frac": o_hbm["frac"], "traffic": o_mfma["traffic"],
                      "plan_shape": o.h.plan_info(o.M, o.N, o.K, o.plan_mode_id)["shape"]}
+            if name == "c4_8192_bf16_widerange" and args.power_seconds > 0:     # the energy figure of the other mode
+                entry["power"] = power_while(torch, o.step, o.flops, args.power_seconds)
             if not args.no_oracle:
                 acc, _, _ = o.accuracy(OTHER_ORACLE_ROWS if o.oracle_rows is not None else None)
                 entry.update({k: acc[k] for k in ("relres_gpu", "relres_fp32_oracle", "relres_ratio", "accuracy_pass",
