@@ -76,8 +76,9 @@ WORKLOADS = {
     "x_1024_auto_urand": (1024, 1024, 1024, "N", "N", "auto", 1.0, 0.0, "urand", None),
 }
 DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
-# what the default run times after the headline: every other baseline configuration, both modes
-OTHER_WORKLOADS = ["c4_8192_bf16_widerange", "c2_4096_fp16_urand", "c2_4096_bf16_urand", "c5_tallskinny_fp16",
+# what the default run times after the headline: every other baseline configuration, both modes (and the inputs of
+# configuration 4 once more in the automatic mode, which runs them as FP16 on row / column scaled operands)
+OTHER_WORKLOADS = ["c4_8192_bf16_widerange", "x_8192_auto_widerange", "c2_4096_fp16_urand", "c2_4096_bf16_urand", "c5_tallskinny_fp16",
                    "c5_tallskinny_bf16", "c5_deepk_fp16", "c5_deepk_bf16", "c5_odd_transA_fp16", "c5_odd_transA_bf16",
                    "c1_256_fp16_urand"]
 OTHER_ORACLE_ROWS = 256      # the oracle's sample of rows of C for those (the headline keeps its own, larger one)
@@ -145,6 +146,7 @@ class Workload:
                         "fp16_outside4": ec.MODE_FP16_OUTSIDE_ACC_4, "fp16_outside16": ec.MODE_FP16_OUTSIDE_ACC_16,
                         "auto": ec.MODE_AUTO}[self.mode]
         self.auto = self.mode == "auto"
+        self.auto_scaled = False
         self.ops = {"N": ec.OP_N, "T": ec.OP_T}
         t0 = time.time()
         self.A, self.B, self.C = make_inputs(self.M, self.N, self.K, self.transA, self.transB, self.dist, self.beta, seed)
@@ -168,7 +170,7 @@ class Workload:
         self.plan_mode_id = self.mode_id
         if self.auto:       # which mode the library picks for these inputs: from here on `mode` names that one
             self.step()
-            self.plan_mode_id = self.h.auto_choice()
+            self.plan_mode_id, self.auto_scaled = self.h.auto_choice()
             self.mode = "fp16" if self.plan_mode_id == ec.MODE_FP16_SPLIT else "bf16"
 
     def step(self):
@@ -230,8 +232,11 @@ class Workload:
         packed = (pad(M, 256) + pad(N, 256)) * pad(K, 32) * bpe
         product_bytes = packed + M * N * 4 * (2 if self.beta != 0 else 1)
         split_bytes = (M + N) * K * 4 + packed
-        if self.auto and self.mode == "bf16":      # the FP16 split that measured the operands ran first and is discarded
-            split_bytes += (M + N) * K * 4 + (pad(M, 256) + pad(N, 256)) * pad(K, 32) * PACKED_BYTES_PER_ELEMENT["fp16"]
+        fp16_pass = (M + N) * K * 4 + (pad(M, 256) + pad(N, 256)) * pad(K, 32) * PACKED_BYTES_PER_ELEMENT["fp16"]
+        if self.auto and self.auto_scaled:         # the unscaled FP16 split is discarded; the exponents cost a read of A and B
+            split_bytes += fp16_pass + (M + N) * K * 4
+        if self.auto and self.mode == "bf16":      # both FP16 splits and the exponents
+            split_bytes += 2 * fp16_pass + (M + N) * K * 4
         mfma_tflops = PRODUCTS[self.mode] * self.flops / (product_ms * 1e-3) / 1e12
         mfma = {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(mfma_tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(self.name),
@@ -464,7 +469,8 @@ def main():
         "config": {"workload": args.workload, "M": M, "N": N, "K": K, "transA": w.transA, "transB": w.transB,
                    "mode": mode, "alpha": w.alpha, "beta": w.beta, "products": PRODUCTS[mode],
                    "inputs": "urand(-1,1)" if w.dist == "urand" else f"exp_rand{w.dist[0]} x exp_rand{w.dist[1]}", "seed": args.seed,
-                   "shape": args.shape, "tile_order": args.tile_order, "plan": h.plan_info(M, N, K, w.plan_mode_id), "mode_chosen_by_the_library": w.auto},
+                   "shape": args.shape, "tile_order": args.tile_order, "plan": h.plan_info(M, N, K, w.plan_mode_id), "mode_chosen_by_the_library": w.auto,
+                   "on_row_and_column_scaled_operands": w.auto_scaled},
         "split_ms": round(split_ms, 4), "product_ms": round(product_ms, 4),
         "frac_of_fp32_vector_peak": round(tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
         "roofline": roofline, "roofline_hbm": roofline_hbm, "roofline_split": roofline_split,
@@ -493,7 +499,8 @@ def main():
             o_ms, o_split_ms, o_product_ms = o.time(o_steps, o_warmup)
             o_tflops = o.flops / (o_ms * 1e-3) / 1e12
             o_mfma, o_hbm, _ = o.rooflines(o_split_ms, o_product_ms)
-            entry = {"workload": name, "mode": o.mode, "M": o.M, "N": o.N, "K": o.K, "steps": o_steps, "warmup": o_warmup,
+            entry = {"workload": name, "mode": o.mode, "mode_chosen_by_the_library": o.auto,
+                     "on_row_and_column_scaled_operands": o.auto_scaled, "M": o.M, "N": o.N, "K": o.K, "steps": o_steps, "warmup": o_warmup,
                      "ms_per_step": round(o_ms, 4), "tflops": round(o_tflops, 2),
                      "frac_of_fp32_vector_peak": round(o_tflops / PEAK_FP32_VECTOR_TFLOPS, 3),
                      "product_ms": round(o_product_ms, 4), "split_ms": round(o_split_ms, 4),

@@ -72,8 +72,8 @@ typedef enum {
     ECGEMM_MODE_FP16_OUTSIDE_ACC_4 = 8,
     ECGEMM_MODE_FP16_OUTSIDE_ACC_16 = 9,
     /* ecgemm_sgemm, ecgemm_sgemm_noalloc and ecgemm_workspace_size only: ECGEMM_MODE_FP16_SPLIT if the FP16 pair
-     * represents both operands well enough, else ECGEMM_MODE_BF16_FULL, decided on the GPU during the split pass (see
-     * "Automatic mode" below).  The trade the paper leaves to the user (section "Effect of the exponent range of input
+     * represents both operands well enough, as they are or after scaling their rows and columns by powers of two, else
+     * ECGEMM_MODE_BF16_FULL, decided on the GPU during the split pass (see "Automatic mode" below).  The trade the paper leaves to the user (section "Effect of the exponent range of input
      * matrices": halfhalf is faster, tf32tf32 covers the range) made from the data. */
     ECGEMM_MODE_AUTO = 10
 } ecgemm_mode_t;
@@ -192,27 +192,37 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
  * Automatic mode (mode == ECGEMM_MODE_AUTO).  The call enqueues, without ever waiting for the GPU:
  *   1. the FP16 pair split of A and B (after the handle's pre-scaling, if any), whose kernels also sum, in FP64 and in
  *      a fixed order, |x|^2 and |x - (v16 + dv16 * 2^-11)|^2 over each operand;
- *   2. a one-workgroup kernel that chooses FP16 if for both operands the second sum is at most 2^-48 times the first,
- *      that is, if the pair represents each operand to a relative error of 2^-24 (the unit roundoff of FP32) in the
- *      Frobenius norm, and BF16 otherwise (also when an operand holds a NaN or a value beyond the FP16 range);
- *   3. the three-term BF16 split, the FP16 product and the BF16 product, each of which reads the choice from device
- *      memory when it starts and returns at once if it is not the one chosen.
- * The result is bitwise that of ecgemm_sgemm in the chosen mode.  The criterion is about the inputs, so it holds for
- * any product of them: with Delta A, Delta B the parts the pair loses, |Delta A B + A Delta B| is bounded by
+ *   2. a one-workgroup kernel that chooses the FP16 mode if for both operands the second sum is at most 2^-48 times the
+ *      first, that is, if the pair represents each operand to a relative error of 2^-24 (the unit roundoff of FP32) in
+ *      the Frobenius norm;
+ *   3. otherwise: the scaling exponents of ecgemm_row_scales for the rows of op(A) and the columns of op(B) (largest
+ *      binade of each to 2^14), the FP16 pair split of the operands scaled by them with the same sums, and a second
+ *      choice by the same rule: the FP16 mode on the scaled operands, with the factors divided out element by element
+ *      as in ecgemm_sgemm_scaled (a row-wise and column-wise guarantee: the error of element (m, n) is then bounded
+ *      relative to |row m of op(A)| |column n of op(B)|), or else the BF16 mode (an operand holds a NaN or an infinity);
+ *   4. the three-term BF16 split and the three products, each of which reads the choice from device memory when it
+ *      starts and returns at once if it is not the one chosen.
+ * The result is bitwise that of ecgemm_sgemm in FP16 mode, of ecgemm_row_scales (target 14) + ecgemm_sgemm_scaled in
+ * FP16 mode, or of ecgemm_sgemm in BF16 mode.  The criterion is about the inputs, so it holds for any product of them:
+ * with Delta A, Delta B the parts the pair loses, |Delta A B + A Delta B| is bounded by
  * (|Delta A| / |A| + |Delta B| / |B|) |A| |B| in the Frobenius norm.  Uniform(-1, 1) and the paper's Type 1 inputs
- * choose FP16; Types 2 to 4 (exponents down to 2^-35 and below) choose BF16.  Cost over calling the chosen mode
- * directly: the statistics in the split (it stays bound by memory traffic), about five more kernel launches that do
- * nothing, and for BF16 the FP16 split that is thrown away.  Workspace: that of the BF16 mode plus 16 bytes per
- * 64 x 32 block of each operand plus 256 (ecgemm_workspace_size with ECGEMM_MODE_AUTO).  Not available with scaling
- * vectors, ecgemm_split / ecgemm_product, ecgemm_plan_info or the fused kernel shape (ECGEMM_ERR_UNSUPPORTED or
+ * choose the plain FP16 mode; Types 2 to 4 and inputs spread over the whole FP32 exponent range choose the scaled one
+ * and run at the FP16 mode's speed.  What the scaled FP16 mode does not give is element-wise accuracy for elements far
+ * below their row's or column's largest: a caller who needs every element of A and B honoured to 24 bits whatever its
+ * size asks for ECGEMM_MODE_BF16_FULL.  Cost over calling the chosen arrangement directly: the statistics in the split
+ * (it stays bound by memory traffic), about a dozen kernel launches that do nothing, and for the later candidates the
+ * splits that are thrown away.  Workspace: that of the BF16 mode plus 16 bytes per 64 x 32 block of each operand, 4 (M + N)
+ * bytes and 256 (ecgemm_workspace_size with ECGEMM_MODE_AUTO).  Not available with caller-given scaling vectors,
+ * ecgemm_split / ecgemm_product, ecgemm_plan_info or the fused kernel shape (ECGEMM_ERR_UNSUPPORTED or
  * ECGEMM_ERR_INVALID_ARG for the mode).
  *
- * ecgemm_auto_choice reports which mode the handle's last ecgemm_sgemm / ecgemm_sgemm_noalloc call chose.  It waits
- * for the handle's stream (the only part of the automatic mode that does), so it is for tests and logs, not for inner
- * loops.  ECGEMM_ERR_INVALID_ARG (argument 1) if that call was not in automatic mode, did nothing (M, N or K zero,
- * alpha zero), or the workspace has been replaced since.  `mode` is a host pointer.
+ * ecgemm_auto_choice reports what the handle's last ecgemm_sgemm / ecgemm_sgemm_noalloc call chose: the mode, and
+ * whether it ran on row / column scaled operands (1) or not (0).  It waits for the handle's stream (the only part of
+ * the automatic mode that does), so it is for tests and logs, not for inner loops.  ECGEMM_ERR_INVALID_ARG
+ * (argument 1) if that call was not in automatic mode, did nothing (M, N or K zero, alpha zero), or the workspace has
+ * been replaced since.  `mode` and `scaling_vectors` are host pointers.
  */
-ecgemm_status_t ecgemm_auto_choice(ecgemm_handle_t handle, ecgemm_mode_t *mode);
+ecgemm_status_t ecgemm_auto_choice(ecgemm_handle_t handle, ecgemm_mode_t *mode, int *scaling_vectors);
 
 /*
  * Power-of-two pre-scaling: the remedy the paper names, at the end of section "Effect of the exponent range of input

@@ -104,6 +104,37 @@ def fp16_pair_represents(opA: np.ndarray, opB: np.ndarray, tolerance: float = 2.
     return bool(fp16_pair_lost_fraction(opA) <= tolerance and fp16_pair_lost_fraction(opB) <= tolerance)
 
 
+def row_scale_exponents(x: np.ndarray, target: int = 14) -> np.ndarray:
+    """Per-row power-of-two scaling (the remedy named at the end of section "Effect of the exponent range of input
+    matrices", applied row by row): for each row of x the exponent e that moves the row's largest non-zero finite
+    element into the binade 2^target, i.e. target - floor(log2 max|x|), with FP32 subnormals counted as 2^-127, kept
+    within [-126, 126]; 0 for a row without such an element."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float32))
+    field = ((x.view(np.uint32) >> np.uint32(23)) & np.uint32(0xFF)).astype(np.int64)      # biased exponent
+    counts = (x != 0) & (field != 255)
+    top = np.where(counts, field - 127, -(1 << 40)).max(axis=1)
+    return np.where(top > -(1 << 40), np.clip(target - top, -126, 126), 0).astype(np.int64)
+
+
+def scale_rows(x: np.ndarray, exponents: np.ndarray) -> np.ndarray:
+    """x with row r multiplied by 2^exponents[r], in FP32 (exact unless the result leaves the normal range)."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float32))
+    with np.errstate(over="ignore", under="ignore", invalid="ignore"):
+        return (x * np.ldexp(np.float32(1.0), np.asarray(exponents, dtype=np.int32))[:, None]).astype(np.float32)
+
+
+def automatic_choice(opA: np.ndarray, opB: np.ndarray, tolerance: float = 2.0 ** -24, target: int = 14) -> str:
+    """What the library's automatic mode runs for op(A) (M x K) and op(B) (K x N): "fp16" if the pair represents both
+    operands as they are; else "fp16 scaled" if it represents them once every row of op(A) and every column of op(B)
+    has its largest binade at 2^target; else "bf16"."""
+    if fp16_pair_represents(opA, opB, tolerance):
+        return "fp16"
+    bt = np.asarray(opB, dtype=np.float32).T
+    scaled_a = scale_rows(opA, row_scale_exponents(opA, target))
+    scaled_b = scale_rows(bt, row_scale_exponents(bt, target))
+    return "fp16 scaled" if fp16_pair_represents(scaled_a, scaled_b, tolerance) else "bf16"
+
+
 BF16_MAX_BITS = np.uint32(0x7F7F)
 
 

@@ -62,7 +62,7 @@ def _load() -> ctypes.CDLL:
                                  ctypes.c_int]
     lib.ecgemm_sgemm_noalloc.argtypes = lib.ecgemm_sgemm.argtypes
     lib.ecgemm_last_error_argument.argtypes = [vp]
-    lib.ecgemm_auto_choice.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]
+    lib.ecgemm_auto_choice.argtypes = [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
     lib.ecgemm_sgemm_scaled.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, i64, i64, f32, vp, i64, vp, i64, f32, vp, i64,
                                         ctypes.c_int, vp, vp]
     lib.ecgemm_row_scales.argtypes = [vp, ctypes.c_int, i64, i64, vp, i64, ctypes.c_int, vp]
@@ -163,11 +163,11 @@ class Handle:
         self._check(_lib.ecgemm_sgemm(self._h, transA, transB, M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta,
                                       _ptr(C), ldc, mode))
 
-    def auto_choice(self) -> int:
-        """The mode that the last sgemm / sgemm_noalloc call chose (MODE_AUTO); waits for the stream."""
-        mode = ctypes.c_int(-1)
-        self._check(_lib.ecgemm_auto_choice(self._h, ctypes.byref(mode)))
-        return mode.value
+    def auto_choice(self):
+        """(mode, on row / column scaled operands?) of the last sgemm / sgemm_noalloc call (MODE_AUTO); waits for the stream."""
+        mode, scaled = ctypes.c_int(-1), ctypes.c_int(-1)
+        self._check(_lib.ecgemm_auto_choice(self._h, ctypes.byref(mode), ctypes.byref(scaled)))
+        return mode.value, bool(scaled.value)
 
     def sgemm_noalloc(self, transA: int, transB: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int,
                       beta: float, C, ldc: int, mode: int):

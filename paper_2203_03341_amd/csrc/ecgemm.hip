@@ -50,6 +50,7 @@ typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int
                             const int*, int);
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
+  void (*product_scaled)(ProductParams);  // the instance to prefer for calls with scaling vectors, if the mode has one
   void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
   reduce_fn_t reduce;
   int bm, bn, bk, threads, blocks_per_cu;
@@ -60,21 +61,23 @@ struct Shape {
   // Two co-resident X2 blocks already cover each other's epilogue and never gain.
   int persistent_max_k;
 };
-template <class Cfg>
+template <class Cfg, bool WITH_SCALED = false>
 constexpr Shape shape_of(int persistent_max_k) {
-  return Shape{product_kernel<Cfg>, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK, Cfg::THREADS,
-               Cfg::BLOCKS_PER_CU, persistent_max_k};
+  void (*scaled)(ProductParams) = nullptr;
+  if constexpr (WITH_SCALED) scaled = product_kernel<Cfg, true>;
+  return Shape{product_kernel<Cfg, false>, scaled, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK,
+               Cfg::THREADS, Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
 template <int METHOD>
 constexpr Shape fused_shape() {
-  return Shape{nullptr, fused_kernel<METHOD>, reduce_tail_kernel<128, 128>, 128, 128, 32, 256, 1, 0};
+  return Shape{nullptr, nullptr, fused_kernel<METHOD>, reduce_tail_kernel<128, 128>, 128, 128, 32, 256, 1, 0};
 }
-constexpr Shape kNoShape{nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+constexpr Shape kNoShape{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
 constexpr int kPersistentMaxK = 4096;
 const Shape kShapes[kMethods][3] = {
-    {shape_of<Fp16W4>(kPersistentMaxK), shape_of<Fp16X2>(0), fused_shape<kMethodFp16Split>()},
-    {shape_of<Bf16W4>(kPersistentMaxK), shape_of<Bf16X2>(0), fused_shape<kMethodBf16Full>()},
+    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape<kMethodFp16Split>()},
+    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape<kMethodBf16Full>()},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
     {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
     {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
@@ -269,7 +272,7 @@ constexpr double kAutoTolerance = 0x1p-24;
 struct AutoPlan {
   Plan fp16, bf16;
   bool exists;
-  size_t packed_bytes, partial_bytes, stats_a_bytes, stats_b_bytes, total_bytes;
+  size_t packed_bytes, partial_bytes, stats_a_bytes, stats_b_bytes, scales_a_bytes, scales_b_bytes, total_bytes;
 };
 AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
   AutoPlan ap;
@@ -282,7 +285,10 @@ AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
   ap.partial_bytes = std::max(ap.fp16.partial_bytes, ap.bf16.partial_bytes);
   ap.stats_a_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(M, kRowPad) / 64));
   ap.stats_b_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(N, kRowPad) / 64));
-  ap.total_bytes = ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes + 256;
+  ap.scales_a_bytes = align256(sizeof(int32_t) * (size_t)M);
+  ap.scales_b_bytes = align256(sizeof(int32_t) * (size_t)N);
+  ap.total_bytes = ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes + ap.scales_a_bytes +
+                   ap.scales_b_bytes + 256;
   return ap;
 }
 
@@ -454,7 +460,8 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   // Grid, always a multiple of the 8 XCDs: one block per item, or a persistent grid (see Shape::persistent_max_k).
   const dim3 grid((unsigned)product_grid(pl, h->compute_units, nullptr));
   void* args[] = {&pp};
-  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->product), grid, dim3(pl.shape->threads), args, 0, h->stream));
+  const void* kernel = reinterpret_cast<const void*>(row_log2_scale && pl.shape->product_scaled ? pl.shape->product_scaled : pl.shape->product);
+  ECGEMM_HIP(h, hipLaunchKernel(kernel, grid, dim3(pl.shape->threads), args, 0, h->stream));
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
@@ -576,6 +583,32 @@ hipError_t builtin_workspace_of(int device, char** out) {
   }
   *out = static_cast<char*>(g_scratch_address[device]);
   return hipSuccess;
+}
+
+// One operand's part of ecgemm_row_scales.  INVALID_ARG (positions as in ecgemm_row_scales) if the operand has more
+// rows or more depth than the kernels' grids hold.
+ecgemm_status_t make_row_scale_job(ecgemm_handle_t handle, ecgemm_op_t op, int64_t rows, int64_t depth, const float* src,
+                                   int64_t ld, int target_exponent, int32_t* log2_scale, RowScaleJob* job) {
+  const bool k_contiguous = op == ECGEMM_OP_T;
+  const int slab = (!k_contiguous && depth <= 128 * 65535) ? 128 : 2048;  // k per workgroup (see the kernel)
+  const int64_t grid_x = k_contiguous ? (rows + 3) / 4 : (rows + 255) / 256, slabs = (depth + slab - 1) / slab;
+  if (rows > 0x1fffffffLL) return bad_arg(handle, 3, "ecgemm_row_scales: too many rows");
+  if (slabs > 65535 || grid_x * slabs > 0x3fffffffLL) return bad_arg(handle, 4, "ecgemm_row_scales: operand too large");
+  *job = RowScaleJob{src, ld, rows, depth, slab, (int)k_contiguous, target_exponent, (unsigned)grid_x,
+                     (unsigned)(grid_x * slabs), log2_scale};
+  return ECGEMM_OK;
+}
+
+// The three kernels of ecgemm_row_scales for one job or two (b.rows == 0: one), optionally gated.
+ecgemm_status_t launch_row_scales(ecgemm_handle_t handle, const RowScaleJob& a, const RowScaleJob& b, const int* gate,
+                                  int gate_value) {
+  const unsigned per_row = (unsigned)((a.rows + b.rows + 255) / 256);
+  hipLaunchKernelGGL(row_scales_clear_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
+  if (a.blocks + b.blocks > 0)
+    hipLaunchKernelGGL(row_max_exponent_kernel, dim3(a.blocks + b.blocks), dim3(256), 0, handle->stream, a, b, gate, gate_value);
+  hipLaunchKernelGGL(row_scales_finish_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
+  ECGEMM_HIP(handle, hipGetLastError());
+  return ECGEMM_OK;
 }
 
 hipEvent_t take_event(ecgemm_handle_t h) {
@@ -835,20 +868,10 @@ ecgemm_status_t ecgemm_row_scales(ecgemm_handle_t handle, ecgemm_op_t op, int64_
   if (!log2_scale) return bad_arg(handle, 8, "ecgemm_row_scales: null output");
   if (depth > 0 && !src) return bad_arg(handle, 5, "ecgemm_row_scales: null source");
   if (depth > 0 && ld < (op == ECGEMM_OP_N ? rows : depth)) return bad_arg(handle, 6, "ecgemm_row_scales: leading dimension too small");
-  const int64_t row_blocks = (rows + 255) / 256, slabs = (depth + 2047) / 2048;
-  if (row_blocks > 0x7fffffff || rows > 0x1fffffffLL) return bad_arg(handle, 3, "ecgemm_row_scales: too many rows");
-  if (slabs > 65535) return bad_arg(handle, 4, "ecgemm_row_scales: operand too deep");
-  hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)row_blocks), dim3(256), 0, handle->stream, log2_scale, rows, INT_MIN);
-  if (depth > 0) {
-    const bool k_contiguous = op == ECGEMM_OP_T;
-    const dim3 grid((unsigned)(k_contiguous ? (rows + 3) / 4 : row_blocks), (unsigned)slabs);
-    hipLaunchKernelGGL(row_max_exponent_kernel, grid, dim3(256), 0, handle->stream, src, ld, rows, depth, (int)k_contiguous,
-                       log2_scale);
-  }
-  hipLaunchKernelGGL(finish_row_scales_kernel, dim3((unsigned)row_blocks), dim3(256), 0, handle->stream, log2_scale, rows,
-                     target_exponent);
-  ECGEMM_HIP(handle, hipGetLastError());
-  return ECGEMM_OK;
+  RowScaleJob job;
+  const ecgemm_status_t st = make_row_scale_job(handle, op, rows, depth, src, ld, target_exponent, log2_scale, &job);
+  if (st != ECGEMM_OK) return st;
+  return launch_row_scales(handle, job, RowScaleJob{}, nullptr, 0);
 }
 
 ecgemm_status_t ecgemm_choose_mode(ecgemm_handle_t handle, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
@@ -970,14 +993,19 @@ struct EventLease {
   }
 };
 
-// ECGEMM_MODE_AUTO (arguments already checked).  Nothing here waits for the GPU: the kernels of both modes are
-// enqueued, each product, reduction and the BF16 split gated on the choice that choose_mode_kernel leaves in device
-// memory, so the ones of the mode not chosen return at once.
+// ECGEMM_MODE_AUTO (arguments already checked).  Nothing here waits for the GPU: the kernels of every candidate are
+// enqueued, each gated on the word `choice` in device memory, so the ones that are not wanted return at once.
 //   1. the FP16 pair split of A and of B, which also leave per block the squared Frobenius norm of the operand and of
 //      what the pair fails to represent of it
-//   2. the choice: FP16 if both operands are represented to within kAutoTolerance, relative, else BF16
-//   3. the BF16 three-term split of both operands (gated), over the FP16 parts, which are no longer needed then
-//   4. the FP16 product (gated), the BF16 product (gated)
+//   2. first choice: kChoiceFp16 if both operands are represented to within kAutoTolerance, relative; else undecided
+//   3. if undecided: the per-row / per-column scaling exponents of both operands (largest binade of every row of op(A)
+//      and column of op(B) to 2^14), the FP16 pair split of the scaled operands with the same statistics, and the
+//      second choice: kChoiceFp16Scaled if that fits, else kChoiceBf16
+//   4. the BF16 three-term split of both operands (if kChoiceBf16), over the FP16 parts, which are no longer needed then
+//   5. the FP16 product, the FP16 product that undoes the scaling vectors, the BF16 product: one of them runs
+enum AutoChoice { kChoiceFp16 = 0, kChoiceBf16 = 1, kChoiceFp16Scaled = 2, kChoiceUndecided = 3 };
+constexpr int kAutoScaleTarget = 14;  // where the scaled candidate puts the largest binade of every row and column
+
 ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N, int64_t K, float alpha,
                            const float* A, int64_t lda, const float* B, int64_t ldb, float beta, float* C, int64_t ldc,
                            WorkspaceKind workspace_kind) {
@@ -986,15 +1014,26 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   const AutoPlan ap = make_auto_plan(M, N, K, h->shape);
   if (!ap.exists) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: ECGEMM_MODE_AUTO does not run with the fused kernel shape");
   if (ap.fp16.items() + 16 > 0x7fffffffLL || ap.bf16.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
+  // (the scaled candidate is left out for operands beyond what the kernels that find the exponents take: 2^29 rows)
+  RowScaleJob rows_a{}, rows_b{};
+  const ecgemm_op_t op_b = transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N;  // as in sgemm_common
+  const bool try_scaled =
+      make_row_scale_job(h, transA, M, K, A, lda, kAutoScaleTarget - h->log2_scale_a, nullptr, &rows_a) == ECGEMM_OK &&
+      make_row_scale_job(h, op_b, N, K, B, ldb, kAutoScaleTarget - h->log2_scale_b, nullptr, &rows_b) == ECGEMM_OK &&
+      (uint64_t)rows_a.blocks + rows_b.blocks <= 0x7fffffffu;
   char* ws = nullptr;
   st = acquire_workspace(h, ap.total_bytes, &ws, workspace_kind);
   if (st != ECGEMM_OK) return st;
   float* partials = ap.partial_bytes ? reinterpret_cast<float*>(ws + ap.packed_bytes) : nullptr;
-  double* stats_a = reinterpret_cast<double*>(ws + ap.packed_bytes + ap.partial_bytes);
-  double* stats_b = reinterpret_cast<double*>(ws + ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes);
-  int* choice = reinterpret_cast<int*>(ws + ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes);
-  const ecgemm_op_t op_b = transB == ECGEMM_OP_N ? ECGEMM_OP_T : ECGEMM_OP_N;  // as in sgemm_common
-  SplitJob fp16_a, fp16_b, bf16_a, bf16_b;
+  char* at = ws + ap.packed_bytes + ap.partial_bytes;
+  double* stats_a = reinterpret_cast<double*>(at);
+  double* stats_b = reinterpret_cast<double*>(at += ap.stats_a_bytes);
+  int32_t* scales_a = reinterpret_cast<int32_t*>(at += ap.stats_b_bytes);
+  int32_t* scales_b = reinterpret_cast<int32_t*>(at += ap.scales_a_bytes);
+  int* choice = reinterpret_cast<int*>(at += ap.scales_b_bytes);
+  rows_a.scale = scales_a;
+  rows_b.scale = scales_b;
+  SplitJob fp16_a, fp16_b, scaled_a, scaled_b, bf16_a, bf16_b;
   st = make_split_job(h, transA, M, K, A, lda, ws, h->log2_scale_a, nullptr, &fp16_a);
   if (st != ECGEMM_OK) return st;
   st = make_split_job(h, op_b, N, K, B, ldb, ws + ap.fp16.a_bytes, h->log2_scale_b, nullptr, &fp16_b);
@@ -1007,8 +1046,14 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
     return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: internal error, statistics array too small");
   fp16_a.stats = stats_a;
   fp16_b.stats = stats_b;
+  scaled_a = fp16_a;
+  scaled_b = fp16_b;
+  scaled_a.row_log2_scale = scales_a;
+  scaled_b.row_log2_scale = scales_b;
+  scaled_a.gate = scaled_b.gate = choice;
+  scaled_a.gate_value = scaled_b.gate_value = kChoiceUndecided;
   bf16_a.gate = bf16_b.gate = choice;
-  bf16_a.gate_value = bf16_b.gate_value = 1;
+  bf16_a.gate_value = bf16_b.gate_value = kChoiceBf16;
 
   EventLease lease{h};
   TimedCall& tc = lease.tc;
@@ -1023,18 +1068,36 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
   if (st != ECGEMM_OK) return st;
   hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(256), 0, h->stream, stats_a, fp16_a.blocks, stats_b, fp16_b.blocks,
-                     kAutoTolerance, choice);
+                     kAutoTolerance, choice, (int)kChoiceFp16, (int)(try_scaled ? kChoiceUndecided : kChoiceBf16),
+                     (const int*)nullptr, 0);
   ECGEMM_HIP(h, hipGetLastError());
   h->auto_choice = choice;
+  if (try_scaled) {
+    // the exponents are found on the operands as the caller passed them; the handle's global pre-scaling, a common
+    // factor of every row, comes on top in the split and is undone with the product's output scale
+    st = launch_row_scales(h, rows_a, rows_b, choice, kChoiceUndecided);
+    if (st != ECGEMM_OK) return st;
+    st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, scaled_a, &scaled_b, true);
+    if (st != ECGEMM_OK) return st;
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(256), 0, h->stream, stats_a, scaled_a.blocks, stats_b, scaled_b.blocks,
+                       kAutoTolerance, choice, (int)kChoiceFp16Scaled, (int)kChoiceBf16, (const int*)choice,
+                       (int)kChoiceUndecided);
+    ECGEMM_HIP(h, hipGetLastError());
+  }
   st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);
   if (st != ECGEMM_OK) return st;
   if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
   const int log2_out_scale = -(h->log2_scale_a + h->log2_scale_b);
   st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
-                      log2_out_scale, nullptr, nullptr, choice, 0);
+                      log2_out_scale, nullptr, nullptr, choice, kChoiceFp16);
   if (st != ECGEMM_OK) return st;
+  if (try_scaled) {
+    st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
+                        log2_out_scale, scales_a, scales_b, choice, kChoiceFp16Scaled);
+    if (st != ECGEMM_OK) return st;
+  }
   st = launch_product(h, ap.bf16, M, N, alpha, ws, ws + ap.bf16.a_bytes, beta, C, ldc, ECGEMM_MODE_BF16_FULL, partials,
-                      log2_out_scale, nullptr, nullptr, choice, 1);
+                      log2_out_scale, nullptr, nullptr, choice, kChoiceBf16);
   if (st != ECGEMM_OK) return st;
   if (timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));
@@ -1164,15 +1227,17 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
                       kWorkspaceBuiltIn);
 }
 
-ecgemm_status_t ecgemm_auto_choice(ecgemm_handle_t handle, ecgemm_mode_t* mode) {
+ecgemm_status_t ecgemm_auto_choice(ecgemm_handle_t handle, ecgemm_mode_t* mode, int* scaling_vectors) {
   if (!handle) return ECGEMM_ERR_INVALID_ARG;
   if (!mode) return bad_arg(handle, 2, "ecgemm_auto_choice: null output");
+  if (!scaling_vectors) return bad_arg(handle, 3, "ecgemm_auto_choice: null output");
   if (!handle->auto_choice)
     return fail(handle, ECGEMM_ERR_INVALID_ARG, "ecgemm_auto_choice: the handle's last product call made no choice (not ECGEMM_MODE_AUTO, or empty)", 1);
   int choice = -1;
   ECGEMM_HIP(handle, hipMemcpyAsync(&choice, handle->auto_choice, sizeof(int), hipMemcpyDeviceToHost, handle->stream));
   ECGEMM_HIP(handle, hipStreamSynchronize(handle->stream));
-  *mode = choice == 0 ? ECGEMM_MODE_FP16_SPLIT : ECGEMM_MODE_BF16_FULL;
+  *mode = (choice == kChoiceFp16 || choice == kChoiceFp16Scaled) ? ECGEMM_MODE_FP16_SPLIT : ECGEMM_MODE_BF16_FULL;
+  *scaling_vectors = choice == kChoiceFp16Scaled ? 1 : 0;
   return ECGEMM_OK;
 }
 

@@ -35,47 +35,85 @@ __global__ void __launch_bounds__(256) exponent_range_kernel(const float* __rest
   }
 }
 
-// Per-row scaling exponents, in three small kernels on one stream.  (1) row_max[r] <- INT_MIN.
-__global__ void __launch_bounds__(256) fill_int_kernel(int* __restrict__ dst, int64_t count, int value) {
+// Per-row scaling exponents of one operand, or of both operands of a product, in three small kernels on one stream.
+// Each takes a gate like the split and product kernels (null: always runs).
+struct RowScaleJob {
+  const float* src;  // X(r, k) = src[r + k * ld] or src[k + r * ld]
+  int64_t ld, rows, depth;
+  int slab;          // k per workgroup in step 2
+  int k_contiguous;
+  int target;        // where step 3 puts the row's largest binade
+  unsigned grid_x;   // step 2: workgroups along the rows (256 rows each, or 4 when k is contiguous: one wave per row) ...
+  unsigned blocks;   // ... times slabs
+  int* scale;        // device, `rows` entries: the largest exponent after step 2, the scaling exponent after step 3
+};
+
+// (1) scale[r] <- INT_MIN, both jobs (b.rows may be 0)
+__global__ void __launch_bounds__(256) row_scales_clear_kernel(const RowScaleJob a, const RowScaleJob b, const int* gate,
+                                                               int gate_value) {
+  if (!gate_open(gate, gate_value)) return;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < count) dst[i] = value;
+  if (i < a.rows) a.scale[i] = -0x7fffffff - 1;
+  else if (i - a.rows < b.rows) b.scale[i - a.rows] = -0x7fffffff - 1;
 }
 
-// (2) row_max[r] <- largest binary exponent among the non-zero finite elements of row r of X (subnormals count as
-// -127), X(r, k) = src[r + k * ld] or src[k + r * ld].  blockIdx.y takes a slab of 2048 k; lanes run along the
-// contiguous direction.
-__global__ void __launch_bounds__(256) row_max_exponent_kernel(const float* __restrict__ src, int64_t ld, int64_t rows,
-                                                               int64_t depth, int k_contiguous, int* __restrict__ row_max) {
-  const int64_t k_begin = (int64_t)blockIdx.y * 2048, k_end = k_begin + 2048 < depth ? k_begin + 2048 : depth;
+// (2) scale[r] <- largest binary exponent among the non-zero finite elements of row r of X (subnormals count as
+// -127).  A workgroup takes a slab of `slab` k of its rows; lanes run along the contiguous direction.  (r contiguous:
+// a thread walks its row's slab eight independent loads at a time; the host keeps those slabs short, 128 k, so that
+// a matrix makes thousands of workgroups and not a hundred.)  Workgroups 0 .. a.blocks - 1 work on a, the rest on b.
+__global__ void __launch_bounds__(256) row_max_exponent_kernel(const RowScaleJob a, const RowScaleJob b, const int* gate,
+                                                               int gate_value) {
+  if (!gate_open(gate, gate_value)) return;
+  const bool second = blockIdx.x >= a.blocks;  // block-uniform
+  const RowScaleJob& job = second ? b : a;
+  const unsigned block = second ? blockIdx.x - a.blocks : blockIdx.x;
+  const unsigned bx = block % job.grid_x, by = block / job.grid_x;
+  const float* src = job.src;
+  const int64_t ld = job.ld, rows = job.rows;
+  const int64_t k_begin = (int64_t)by * job.slab, k_end = k_begin + job.slab < job.depth ? k_begin + job.slab : job.depth;
   auto exponent_of = [](float v) {
     const unsigned bits = __builtin_bit_cast(unsigned, v) & 0x7fffffffu;
     return (bits != 0 && bits < 0x7f800000u) ? (int)(bits >> 23) - 127 : -0x7fffffff - 1;
   };
   int hi = -0x7fffffff - 1;
-  if (!k_contiguous) {
-    const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (!job.k_contiguous) {
+    const int64_t r = (int64_t)bx * 256 + threadIdx.x;
     if (r >= rows) return;
-    for (int64_t k = k_begin; k < k_end; ++k) hi = max(hi, exponent_of(src[r + k * ld]));
-    if (hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
+    const float* at = src + r + k_begin * ld;
+    int64_t k = k_begin;
+    for (; k + 8 <= k_end; k += 8, at += 8 * ld) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = at[u * ld];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) hi = max(hi, exponent_of(v[u]));
+    }
+    for (; k < k_end; ++k, at += ld) hi = max(hi, exponent_of(*at));
+    if (hi != -0x7fffffff - 1) atomicMax(&job.scale[r], hi);
   } else {
-    const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // one wave per row
+    const int64_t r = (int64_t)bx * 4 + (threadIdx.x >> 6);  // one wave per row
     if (r >= rows) return;
     for (int64_t k = k_begin + (threadIdx.x & 63); k < k_end; k += 64) hi = max(hi, exponent_of(src[k + r * ld]));
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) hi = max(hi, __shfl_xor(hi, d, 64));
-    if ((threadIdx.x & 63) == 0 && hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
+    if ((threadIdx.x & 63) == 0 && hi != -0x7fffffff - 1) atomicMax(&job.scale[r], hi);
   }
 }
 
 // (3) in place: the exponent that moves the row's largest binade to 2^target (0 for a row without non-zero finite
 // elements), kept inside what one power-of-two factor can express.
-__global__ void __launch_bounds__(256) finish_row_scales_kernel(int* __restrict__ row_scale, int64_t rows, int target) {
-  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (r >= rows) return;
-  const int hi = row_scale[r];
-  int e = hi == -0x7fffffff - 1 ? 0 : target - hi;
+__global__ void __launch_bounds__(256) row_scales_finish_kernel(const RowScaleJob a, const RowScaleJob b, const int* gate,
+                                                                int gate_value) {
+  if (!gate_open(gate, gate_value)) return;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const bool second = i >= a.rows;
+  const RowScaleJob& job = second ? b : a;
+  const int64_t r = second ? i - a.rows : i;
+  if (r >= job.rows) return;
+  const int hi = job.scale[r];
+  int e = hi == -0x7fffffff - 1 ? 0 : job.target - hi;
   e = e < -126 ? -126 : e > 126 ? 126 : e;
-  row_scale[r] = e;
+  job.scale[r] = e;
 }
 
 // One v_mfma_f32_32x32x16 per wave on caller-supplied registers, for tests that pin down what the matrix unit does
@@ -126,12 +164,15 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
   sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// Automatic mode choice: from the blocks' statistics of both operands, *choice = 0 (the FP16 pair represents both
-// operands to within `tolerance`, relative, in the Frobenius norm) or 1 (it does not: three BF16 terms).  One block of
-// 256 threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere gives 1.
+// Automatic mode choice: from the blocks' statistics of both operands, *choice = if_fits (the FP16 pair represents both
+// operands as they were split to within `tolerance`, relative, in the Frobenius norm) or if_not.  One block of 256
+// threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere gives if_not.
+// Gated like the other kernels, on the word it writes: the second round of the choice runs only if the first failed.
 __global__ void __launch_bounds__(256) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a,
                                                           const double* __restrict__ stats_b, unsigned blocks_b,
-                                                          double tolerance, int* __restrict__ choice) {
+                                                          double tolerance, int* __restrict__ choice, int if_fits, int if_not,
+                                                          const int* gate, int gate_value) {
+  if (!gate_open(gate, gate_value)) return;
   __shared__ double partial[256][4];
   double sums[4] = {0.0, 0.0, 0.0, 0.0};
   for (unsigned i = threadIdx.x; i < blocks_a; i += 256) sums[0] += stats_a[2 * (size_t)i], sums[1] += stats_a[2 * (size_t)i + 1];
@@ -148,7 +189,7 @@ __global__ void __launch_bounds__(256) choose_mode_kernel(const double* __restri
   if (threadIdx.x == 0) {
     const double t2 = tolerance * tolerance;
     const bool fits = partial[0][0] <= t2 * partial[0][1] && partial[0][2] <= t2 * partial[0][3];
-    *choice = fits ? 0 : 1;
+    *choice = fits ? if_fits : if_not;
   }
 }
 

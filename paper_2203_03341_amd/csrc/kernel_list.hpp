@@ -63,22 +63,26 @@ typedef ProductConfig<kMethodFp32, 256, 128, 128, 64, 2, 3, 1> Fp32Config;
 #define ECGEMM_SPLIT_GROUP extern
 #endif
 
-ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4>(const ProductParams);
-ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2>(const ProductParams);
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4, false>(const ProductParams);
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2, false>(const ProductParams);
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4, true>(const ProductParams);  // for calls with scaling vectors
+ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2, true>(const ProductParams);
 ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<256, 128>(const float*, int, int, int, int, int, int, int, int64_t,
                                                                        int64_t, float, float, float*, int64_t, const int*, int);
 ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<128, 128>(const float*, int, int, int, int, int, int, int, int64_t,
                                                                        int64_t, float, float, float*, int64_t, const int*, int);
-ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4>(const ProductParams);
-ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2>(const ProductParams);
-ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<MarkidisConfig>(const ProductParams);
-ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<UnscaledConfig>(const ProductParams);
-ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<OutsideConfig>(const ProductParams);
-ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside4Config>(const ProductParams);
-ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside16Config>(const ProductParams);
-ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainFp16Config>(const ProductParams);
-ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainBf16Config>(const ProductParams);
-ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<Fp32Config>(const ProductParams);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4, false>(const ProductParams);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2, false>(const ProductParams);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4, true>(const ProductParams);
+ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2, true>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<MarkidisConfig, false>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<UnscaledConfig, false>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<OutsideConfig, false>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside4Config, false>(const ProductParams);
+ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside16Config, false>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainFp16Config, false>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainBf16Config, false>(const ProductParams);
+ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<Fp32Config, false>(const ProductParams);
 ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodFp16Split>(const FusedParams);
 ECGEMM_FUSED_GROUP template __global__ void fused_kernel<kMethodBf16Full>(const FusedParams);
 

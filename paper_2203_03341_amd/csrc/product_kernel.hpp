@@ -336,7 +336,11 @@ __device__ __forceinline__ void wait_loads_and_lds() {  // at most N global load
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(N) : "memory");
 }
 
-template <class Cfg>
+// Every instance undoes per-row / per-column scaling in its epilogue when p.row_log2_scale is set, element by element.
+// FAST_SCALED instances, which exist for the method's two modes, do it with the factors and the elements of C fetched
+// ahead, as the unscaled paths do; they are instances of their own because that epilogue, though it only runs in
+// scaled calls, would weigh on the register allocation of the kernel every call uses.
+template <class Cfg, bool FAST_SCALED = false>
 __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kernel(const ProductParams p) {
   constexpr int NP = Cfg::NP, TM = Cfg::TM, TN = Cfg::TN, S = Cfg::STAGES;
   typedef typename Mfma<Cfg::kElem>::frag_t frag_t;
@@ -824,7 +828,41 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     asm volatile("" : "+s"(row_scale), "+s"(col_scale));
     float* out = done.partial >= 0 ? p.partials + (int64_t)done.partial * (Cfg::BM * Cfg::BN) : nullptr;
     const int64_t m0 = (int64_t)tile_m * Cfg::BM, n0 = (int64_t)tile_n * Cfg::BN;
-    for_each_output([&](int64_t m, int64_t n, float c) {
+    bool written = false;
+    if constexpr (FAST_SCALED) {
+      if (interior && out == nullptr) {
+        written = true;
+        // a lane needs the factors of its TM rows and, per 32 x 32 block, of 16 columns
+        float row_factor[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) row_factor[i] = exp2_int(-load_global(row_scale + m_base + i * 32));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          float col_factor[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) col_factor[v] = exp2_int(-load_global(col_scale + n_base + j * 32 + 8 * (v / 4) + (v % 4)));
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            float* dst = c_base + (m_base + i * 32) + (n_base + j * 32) * ldc;
+            if (p.beta != 0.0f) {
+              float c_in[16];
+#pragma unroll
+              for (int v = 0; v < 16; ++v) c_in[v] = load_global(dst + (8 * (v / 4) + (v % 4)) * ldc);
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                store_result(dst + (8 * (v / 4) + (v % 4)) * ldc,
+                             scaled_sum(p.alpha, merged(i, j, v) * p.out_scale * row_factor[i] * col_factor[v], p.beta, c_in[v]));
+            } else {
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                store_result(dst + (8 * (v / 4) + (v % 4)) * ldc,
+                             p.alpha * (merged(i, j, v) * p.out_scale * row_factor[i] * col_factor[v]));
+            }
+          }
+        }
+      }
+    }
+    if (!written) for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
         c = c * exp2_int(-load_global(row_scale + m)) * exp2_int(-load_global(col_scale + n));
         if (out) {

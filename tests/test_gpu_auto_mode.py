@@ -1,9 +1,11 @@
-"""ECGEMM_MODE_AUTO through the C-ABI: the choice against the oracle's criterion, the result against the chosen mode.
+"""ECGEMM_MODE_AUTO through the C-ABI: the choice against the oracle's criterion, the result against the chosen arrangement.
 
-The choice is an integer decided by floating point: both sides sum the same FP64 terms (|x|^2 and the squared part
-the FP16 pair loses), in different orders, and compare against 2^-24.  The test inputs sit well away from that
-threshold (2^-24.6 or below on the FP16 side, 2^-20.4 or above on the other), so the order cannot decide.
-What the call returns must be, bit for bit, what ecgemm_sgemm returns in the chosen mode.
+The choice (FP16 mode, FP16 mode on row / column scaled operands, BF16 mode) is an integer decided by floating
+point: both sides sum the same FP64 terms (|x|^2 and the squared part the FP16 pair loses), in different orders,
+and compare against 2^-24.  The test inputs sit well away from that threshold (2^-24.6 or below on the passing side,
+2^-20.4 or above on the other), so the order cannot decide.  What the call returns must be, bit for bit, what the
+chosen arrangement returns when called directly: ecgemm_sgemm in that mode, or ecgemm_row_scales (target 14) followed
+by ecgemm_sgemm_scaled in FP16 mode.
 """
 import numpy as np
 import pytest
@@ -39,26 +41,48 @@ def _run(h, call, transA, transB, M, N, K, alpha, A, B, beta, C, mode):
     return to_host(dC, C.shape[0], N)
 
 
+def _run_scaled(h, transA, transB, M, N, K, alpha, A, B, beta, C):
+    """ecgemm_row_scales (target 14) for both operands, then ecgemm_sgemm_scaled in FP16 mode; also the exponents."""
+    import torch
+    import paper_2203_03341_amd as ec
+    ops = {"N": ec.OP_N, "T": ec.OP_T}
+    dA, dB, dC = to_device(A), to_device(B), to_device(C)
+    sa = torch.empty(M, dtype=torch.int32, device="cuda")
+    sb = torch.empty(N, dtype=torch.int32, device="cuda")
+    h.row_scales(ops[transA], M, K, dA, A.shape[0], 14, sa)
+    h.row_scales(ec.OP_T if transB == "N" else ec.OP_N, N, K, dB, B.shape[0], 14, sb)
+    h.sgemm_scaled(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], beta, dC, C.shape[0],
+                   ec.MODE_FP16_SPLIT, sa, sb)
+    torch.cuda.synchronize()
+    return to_host(dC, C.shape[0], N), sa.cpu().numpy(), sb.cpu().numpy()
+
+
 def _check(h, transA, transB, M, N, K, dist_a, dist_b, seed=0, pad=0, alpha=1.5, beta=0.5, noalloc=False):
     import paper_2203_03341_amd as ec
     A, B, C = _problem(transA, transB, M, N, K, dist_a, dist_b, seed, pad)
     opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)
-    want_mode = ec.MODE_FP16_SPLIT if split.fp16_pair_represents(opA, opB) else ec.MODE_BF16_FULL
+    want = split.automatic_choice(opA, opB)
     got = _run(h, h.sgemm_noalloc if noalloc else h.sgemm, transA, transB, M, N, K, alpha, A, B, beta, C, ec.MODE_AUTO)
-    assert h.auto_choice() == want_mode, (dist_a, dist_b, split.fp16_pair_lost_fraction(opA), split.fp16_pair_lost_fraction(opB))
-    direct = _run(h, h.sgemm, transA, transB, M, N, K, alpha, A, B, beta, C, want_mode)
+    chosen = h.auto_choice()
+    assert chosen == {"fp16": (ec.MODE_FP16_SPLIT, False), "fp16 scaled": (ec.MODE_FP16_SPLIT, True),
+                      "bf16": (ec.MODE_BF16_FULL, False)}[want], (dist_a, dist_b, want, chosen)
+    if want == "fp16 scaled":
+        direct, sa, sb = _run_scaled(h, transA, transB, M, N, K, alpha, A, B, beta, C)
+        assert np.array_equal(sa, split.row_scale_exponents(opA)) and np.array_equal(sb, split.row_scale_exponents(opB.T))
+    else:
+        direct = _run(h, h.sgemm, transA, transB, M, N, K, alpha, A, B, beta, C, chosen[0])
     assert np.array_equal(got.view(np.uint32), direct.view(np.uint32))
     # and the point of choosing: the result meets the accuracy bar of the method whatever the inputs
     c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C)
     c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C)
     assert gemm.relative_residual(c64, got[:M, :]) <= 1.25 * gemm.relative_residual(c64, c32)
-    return want_mode
+    return want
 
 
 @pytest.mark.parametrize("transA,transB,pad", [("N", "N", 0), ("T", "T", 0), ("N", "T", 1), ("T", "N", 3)])
 def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
     """Every split kernel variant (both storage orders, aligned and not) measures the same thing; ragged sizes with
-    several blocks per operand; either operand alone can force the full-range mode."""
+    several blocks per operand; either operand alone takes the call out of the plain FP16 mode."""
     import paper_2203_03341_amd as ec
     h = ec.Handle()
     M, N, K = 300, 260, 200
@@ -69,7 +93,7 @@ def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
         _check(h, transA, transB, M, N, K, TYPE4, TYPE1, seed=4, pad=pad),
         _check(h, transA, transB, M, N, K, TYPE1, TYPE3, seed=5, pad=pad),
     ]
-    assert chosen == [ec.MODE_FP16_SPLIT, ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL, ec.MODE_BF16_FULL, ec.MODE_BF16_FULL]
+    assert chosen == ["fp16", "fp16", "fp16 scaled", "fp16 scaled", "fp16 scaled"]
     h.destroy()
 
 
@@ -78,10 +102,11 @@ def test_sliced_tiles_large_operands_and_the_builtin_workspace():
     operand instead of the pair launch), and the entry point that allocates nothing."""
     import paper_2203_03341_amd as ec
     h = ec.Handle()
-    for dist in ("urand", TYPE3):
-        _check(h, "N", "N", 512, 384, 4608, dist, dist, seed=6)
-        _check(h, "T", "N", 1100, 900, 1300, dist, dist, seed=7, pad=1, noalloc=True)
-        _check(h, "N", "T", 2304, 2048, 2080, dist, dist, seed=8, alpha=1.0, beta=0.0)
+    wide = (-100, 100)          # an operand spread over the FP32 exponent range (the other stays moderate, or C overflows)
+    for dist_a, dist_b in (("urand", "urand"), (TYPE3, TYPE3), (wide, TYPE1)):
+        _check(h, "N", "N", 512, 384, 4608, dist_a, dist_b, seed=6)
+        _check(h, "T", "N", 1100, 900, 1300, dist_a, dist_b, seed=7, pad=1, noalloc=True)
+        _check(h, "N", "T", 2304, 2048, 2080, dist_a, dist_b, seed=8, alpha=1.0, beta=0.0)
     h.destroy()
 
 
@@ -92,30 +117,42 @@ def test_special_values_and_prescaling():
     M, N, K = 200, 150, 96
     A, B, C = _problem("N", "N", M, N, K, "urand", "urand", 9, 0)
     ops = (ec.OP_N, ec.OP_N)
+    FP16, SCALED, BF16 = (ec.MODE_FP16_SPLIT, False), (ec.MODE_FP16_SPLIT, True), (ec.MODE_BF16_FULL, False)
 
     def choice_for(A_host, B_host):
         dA, dB, dC = to_device(A_host), to_device(B_host), to_device(C)
         h.sgemm(*ops, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
         return h.auto_choice(), to_host(dC, M, N)
 
-    assert choice_for(A, B)[0] == ec.MODE_FP16_SPLIT
-    for poison in (np.nan, np.inf, np.float32(1e6)):          # NaN, infinity, a value beyond the FP16 range
+    assert choice_for(A, B)[0] == FP16
+    # a NaN or an infinity leaves only the full-range mode; a finite value beyond the FP16 range is an ordinary row
+    # maximum once its row is scaled
+    for poison, want in ((np.nan, BF16), (np.inf, BF16), (np.float32(1e6), SCALED)):
         bad = A.copy(order="F")
         bad[17, 5] = poison
-        assert choice_for(bad, B)[0] == ec.MODE_BF16_FULL
-        assert choice_for(A, B)[0] == ec.MODE_FP16_SPLIT          # (and the previous call's choice does not stick)
+        assert choice_for(bad, B)[0] == want, poison
+        assert choice_for(A, B)[0] == FP16                    # (and the previous call's choice does not stick)
     zeros = np.zeros_like(A)
     mode, out = choice_for(zeros, B)                          # nothing to lose in an all-zero operand
-    assert mode == ec.MODE_FP16_SPLIT and np.all(out == 0.0)
+    assert mode == FP16 and np.all(out == 0.0)
     # the handle's pre-scaling moves Type 3 inputs into the window of the pair: the choice is made after it
     A3, B3, _ = _problem("N", "N", M, N, K, TYPE3, TYPE3, 10, 0)
-    assert choice_for(A3, B3)[0] == ec.MODE_BF16_FULL
+    assert choice_for(A3, B3)[0] == SCALED
     h.set_scaling(29, 29)
     mode, scaled = choice_for(A3, B3)
-    assert mode == ec.MODE_FP16_SPLIT
+    assert mode == FP16
     direct = _run(h, h.sgemm, "N", "N", M, N, K, 1.0, A3, B3, 0.0, C, ec.MODE_FP16_SPLIT)
     assert np.array_equal(scaled.view(np.uint32), direct.view(np.uint32))
+    # a global factor that does not help (Type 4 stays out of reach of one factor of 2^29): the scaled candidate takes
+    # it into account, its rows end up at 2^14 all the same, and the result is that of the direct calls on this handle
+    A4, B4, _ = _problem("N", "N", M, N, K, TYPE4, TYPE1, 11, 0)
+    mode, out4 = choice_for(A4, B4)
+    assert mode == SCALED
     h.set_scaling(0, 0)
+    mode, out4_plain = choice_for(A4, B4)
+    assert mode == SCALED and np.array_equal(out4.view(np.uint32), out4_plain.view(np.uint32))
+    c64 = gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.0, A4, B4)
+    assert gemm.relative_residual(c64, out4) <= 1.25 * gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.0, A4, B4))
     h.destroy()
 
 
@@ -128,12 +165,12 @@ def test_workspace_size_caller_workspace_and_refusals():
     dA, dB, dC = to_device(A), to_device(B), to_device(C)
     need = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, ec.MODE_AUTO)
     assert need > max(h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, m) for m in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL))
-    want = _run(h, h.sgemm, "N", "N", M, N, K, 1.0, A, B, 0.0, C, ec.MODE_BF16_FULL)
+    want, _, _ = _run_scaled(h, "N", "N", M, N, K, 1.0, A, B, 0.0, C)
     guard = 4096
     buf = torch.full((need + guard,), 0x5A, dtype=torch.uint8, device="cuda")
     h.set_workspace(buf, need)
     h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
-    assert h.auto_choice() == ec.MODE_BF16_FULL
+    assert h.auto_choice() == (ec.MODE_FP16_SPLIT, True)
     assert np.array_equal(to_host(dC, M, N).view(np.uint32), want.view(np.uint32))
     assert bool((buf[need:] == 0x5A).all())                     # nothing is written past the size asked for
     h.set_workspace(buf, need - 256)
@@ -183,7 +220,9 @@ def test_one_captured_graph_takes_either_branch_depending_on_the_data():
     import paper_2203_03341_amd as ec
     M, N, K = 640, 512, 1536
     inputs = {"fp16": _problem("N", "T", M, N, K, "urand", "urand", 13, 0),
-              "bf16": _problem("N", "T", M, N, K, TYPE3, TYPE4, 14, 0)}
+              "scaled": _problem("N", "T", M, N, K, TYPE3, TYPE4, 14, 0),
+              "bf16": _problem("N", "T", M, N, K, "urand", TYPE1, 15, 0)}
+    inputs["bf16"][0][3, 4] = np.nan            # only the full-range mode is left
     h = ec.Handle()
     stream = torch.cuda.Stream()
     h.set_stream(stream.cuda_stream)
@@ -209,19 +248,30 @@ def test_one_captured_graph_takes_either_branch_depending_on_the_data():
             call(mode)
             stream.synchronize()
             eager[which] = dC.cpu().numpy().copy()
+        load("scaled")
+        dC.copy_(dC_in)
+        sa = torch.empty(M, dtype=torch.int32, device="cuda")
+        sb = torch.empty(N, dtype=torch.int32, device="cuda")
+        h.row_scales(ec.OP_N, M, K, dA, M, 14, sa)
+        h.row_scales(ec.OP_N, N, K, dB, N, 14, sb)          # B is stored N x K (transB == T): its columns are the rows here
+        h.sgemm_scaled(ec.OP_N, ec.OP_T, M, N, K, 1.5, dA, M, dB, N, 0.5, dC, M, ec.MODE_FP16_SPLIT, sa, sb)
+        stream.synchronize()
+        eager["scaled"] = dC.cpu().numpy().copy()
         load("fp16")
         call(ec.MODE_AUTO)                      # once eagerly, so that nothing is created during the capture
         stream.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=stream):
         call(ec.MODE_AUTO)
-    for which in ("bf16", "fp16", "fp16", "bf16"):
+    for which in ("bf16", "fp16", "scaled", "scaled", "fp16", "bf16"):
         with torch.cuda.stream(stream):
             load(which)
             dC.fill_(float("nan"))
         stream.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert np.array_equal(dC.cpu().numpy().view(np.uint32), eager[which].view(np.uint32)), which
+        got, want = dC.cpu().numpy(), eager[which]
+        assert np.array_equal(np.isnan(got), np.isnan(want)), which
+        assert np.array_equal(got.view(np.uint32)[~np.isnan(got)], want.view(np.uint32)[~np.isnan(want)]), which
     del graph
     h.destroy()

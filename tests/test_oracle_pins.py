@@ -551,3 +551,40 @@ def test_fp16_pair_lost_fraction_and_the_automatic_choice():
         r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
         r16 = gemm.relative_residual(c64, model.gemm_fp16_mode(A, B))
         assert split.fp16_pair_represents(A, B) == (r16 <= r32), (a_rng, b_rng, r16, r32)
+
+
+def test_row_scaling_and_the_three_way_automatic_choice():
+    """Scaling exponents against hand-worked rows; the scaled FP16 candidate against what it is for: on the paper's
+    input types that the unscaled pair cannot hold (Types 2 to 4), the pair applied to row / column scaled operands,
+    with the factors divided out again, is as accurate as the FP32 product (modelled with exact accumulation)."""
+    rows = np.float32([[3.0, -0.5, 0.0], [0.0, 0.0, 0.0], [np.inf, 0.25, -0.125], [2.0 ** 100, 1.0, -2.0 ** 99],
+                       [1e-45, 0.0, 2e-45], [np.nan, 2.0 ** -126, 0.0]])
+    # largest binades: 2^1, none, 2^-2 (the infinity does not count), 2^100, subnormal = 2^-127, 2^-126 (NaN does not count)
+    assert list(split.row_scale_exponents(rows, 14)) == [13, 0, 16, -86, 126, 126]
+    assert list(split.row_scale_exponents(rows, 0)) == [-1, 0, 2, -100, 126, 126]
+    assert list(split.row_scale_exponents(np.float32([[2.0 ** -120]]), -126)) == [-6]
+    assert list(split.row_scale_exponents(np.float32([[2.0 ** 120]]), -126)) == [-126]          # clipped from -246
+    scaled = split.scale_rows(rows[[0, 3]], [13, -86])
+    assert np.array_equal(scaled, np.float32([[3.0 * 8192, -4096.0, 0.0], [16384.0, 2.0 ** -86, -8192.0]]))
+
+    n = 192
+    for a_rng, b_rng, want in (((-15, 14), (-15, 14), "fp16"), ((-15, 14), (-100, -35), "fp16 scaled"),
+                               ((-35, -15), (-35, -15), "fp16 scaled"), ((-100, -35), (-100, -35), "fp16 scaled"),
+                               ((-100, 100), (-15, 14), "fp16 scaled")):
+        A = si.exp_rand(n, n, *a_rng, 0, si.ID_A)
+        B = si.exp_rand(n, n, *b_rng, 0, si.ID_B)
+        assert split.automatic_choice(A, B) == want, (a_rng, b_rng)
+        if want == "fp16 scaled":
+            ea, eb = split.row_scale_exponents(A), split.row_scale_exponents(B.T)
+            with np.errstate(over="ignore"):
+                c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
+                r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
+            product = model.gemm_fp16_mode(split.scale_rows(A, ea), split.scale_rows(B.T, eb).T.copy())
+            unscaled = np.ldexp(np.ldexp(product, -ea[:, None].astype(np.int32)), -eb[None, :].astype(np.int32))
+            assert gemm.relative_residual(c64, unscaled) <= r32, (a_rng, b_rng)
+    poisoned = si.urand(n, n, 1, si.ID_A).copy()
+    poisoned[5, 7] = np.nan
+    assert split.automatic_choice(poisoned, si.urand(n, n, 1, si.ID_B)) == "bf16"
+    huge = si.urand(n, n, 1, si.ID_A).copy()
+    huge[5, 7] = 1e30                     # beyond the FP16 range as it is, an ordinary row maximum once scaled
+    assert split.automatic_choice(huge, si.urand(n, n, 1, si.ID_B)) == "fp16 scaled"
