@@ -31,7 +31,7 @@ def main():
 
     modes = [("ours FP16", ec.MODE_FP16_SPLIT), ("ours BF16x3", ec.MODE_BF16_FULL), ("unscaled", ec.MODE_FP16_UNSCALED),
              ("Markidis", ec.MODE_FP16_MARKIDIS), ("ours FP16, outside acc. every k step", ec.MODE_FP16_OUTSIDE_ACC), ("every 4", ec.MODE_FP16_OUTSIDE_ACC_4), ("every 16", ec.MODE_FP16_OUTSIDE_ACC_16), ("plain FP16", ec.MODE_FP16_PLAIN), ("plain BF16", ec.MODE_BF16_PLAIN),
-             ("FP32 on the matrix unit", ec.MODE_FP32_MFMA), ("automatic (FP16 or BF16x3, chosen from the data)", ec.MODE_AUTO)]
+             ("FP32 on the matrix unit", ec.MODE_FP32_MFMA), ("automatic (arrangement chosen from the data)", ec.MODE_AUTO)]
     h = ec.Handle()
     h.set_stream(torch.cuda.current_stream().cuda_stream)
 
