@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 import seeded_inputs as si
-from oracle import gemm, split
+from oracle import gemm, model, split
 from gpu_util import empty_colmajor, to_device, to_host
 
 pytestmark = pytest.mark.gpu
@@ -76,6 +76,21 @@ def _check(h, transA, transB, M, N, K, dist_a, dist_b, seed=0, pad=0, alpha=1.5,
     c64 = gemm.sgemm_fp64_ref(transA, transB, M, N, K, alpha, A, B, beta, C)
     c32 = gemm.sgemm_fp32_naive(transA, transB, M, N, K, alpha, A, B, beta, C)
     assert gemm.relative_residual(c64, got[:M, :]) <= 1.25 * gemm.relative_residual(c64, c32)
+    # element by element against the exact-accumulation model of the chosen arrangement: the GPU differs from it only
+    # by its FP32 accumulation (one rounding per eight products) and the rounding of alpha c + beta C
+    if want == "fp16 scaled":
+        ea, eb = split.row_scale_exponents(opA), split.row_scale_exponents(opB.T)
+        sA, sB = split.scale_rows(opA, ea), split.scale_rows(opB.T, eb).T.copy()
+        undo = lambda x: np.ldexp(np.ldexp(x, -ea[:, None].astype(np.int32)), -eb[None, :].astype(np.int32))
+        mdl = undo(model.gemm_fp16_mode(sA, sB))
+        mag = undo(np.abs(sA).astype(np.float64) @ np.abs(sB).astype(np.float64))
+    else:
+        mdl = model.gemm_fp16_mode(opA, opB) if want == "fp16" else model.gemm_bf16_mode(opA, opB)
+        mag = np.abs(opA).astype(np.float64) @ np.abs(opB).astype(np.float64)
+    cin = C[:M, :N].astype(np.float64)
+    expect = alpha * mdl + beta * cin
+    bound = (K / 8 + 4) * 2.0 ** -23 * abs(alpha) * mag + 2.0 ** -22 * (np.abs(expect) + np.abs(beta * cin))
+    assert np.max(np.abs(got[:M, :] - expect) / (bound + 1e-300)) <= 1.0, (want, dist_a, dist_b)
     return want
 
 
