@@ -11,7 +11,7 @@
  * and B, writes C, keeps no pointer after a call returns, and never frees caller memory.
  * All work is enqueued on the handle's stream and the calls return without waiting for it, with the
  * exceptions stated at the functions concerned: a handle-owned workspace that has to grow (below),
- * ecgemm_exponent_range, ecgemm_choose_mode and ecgemm_get_timing.
+ * ecgemm_exponent_range, ecgemm_choose_mode, ecgemm_auto_choice and ecgemm_get_timing.
  * Every function returns an ecgemm_status_t and never throws or aborts.  Enumeration arguments are read as plain
  * integers: a value that is not one of the enumerators is refused like any other bad argument.  Arguments and sizes are checked before
  * anything is enqueued: ECGEMM_ERR_INVALID_ARG, ECGEMM_ERR_UNSUPPORTED and ECGEMM_ERR_ALLOC mean that the call has
