@@ -1067,7 +1067,7 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   }
   st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
   if (st != ECGEMM_OK) return st;
-  hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(256), 0, h->stream, stats_a, fp16_a.blocks, stats_b, fp16_b.blocks,
+  hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, fp16_a.blocks, stats_b, fp16_b.blocks,
                      kAutoTolerance, choice, (int)kChoiceFp16, (int)(try_scaled ? kChoiceUndecided : kChoiceBf16),
                      (const int*)nullptr, 0);
   ECGEMM_HIP(h, hipGetLastError());
@@ -1079,7 +1079,7 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
     if (st != ECGEMM_OK) return st;
     st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, scaled_a, &scaled_b, true);
     if (st != ECGEMM_OK) return st;
-    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(256), 0, h->stream, stats_a, scaled_a.blocks, stats_b, scaled_b.blocks,
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, scaled_a.blocks, stats_b, scaled_b.blocks,
                        kAutoTolerance, choice, (int)kChoiceFp16Scaled, (int)kChoiceBf16, (const int*)choice,
                        (int)kChoiceUndecided);
     ECGEMM_HIP(h, hipGetLastError());

@@ -165,22 +165,37 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 }
 
 // Automatic mode choice: from the blocks' statistics of both operands, *choice = if_fits (the FP16 pair represents both
-// operands as they were split to within `tolerance`, relative, in the Frobenius norm) or if_not.  One block of 256
+// operands as they were split to within `tolerance`, relative, in the Frobenius norm) or if_not.  One block of 1024
 // threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere gives if_not.
 // Gated like the other kernels, on the word it writes: the second round of the choice runs only if the first failed.
-__global__ void __launch_bounds__(256) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a,
-                                                          const double* __restrict__ stats_b, unsigned blocks_b,
-                                                          double tolerance, int* __restrict__ choice, int if_fits, int if_not,
-                                                          const int* gate, int gate_value) {
+__global__ void __launch_bounds__(1024) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a,
+                                                           const double* __restrict__ stats_b, unsigned blocks_b,
+                                                           double tolerance, int* __restrict__ choice, int if_fits, int if_not,
+                                                           const int* gate, int gate_value) {
   if (!gate_open(gate, gate_value)) return;
-  __shared__ double partial[256][4];
-  double sums[4] = {0.0, 0.0, 0.0, 0.0};
-  for (unsigned i = threadIdx.x; i < blocks_a; i += 256) sums[0] += stats_a[2 * (size_t)i], sums[1] += stats_a[2 * (size_t)i + 1];
-  for (unsigned i = threadIdx.x; i < blocks_b; i += 256) sums[2] += stats_b[2 * (size_t)i], sums[3] += stats_b[2 * (size_t)i + 1];
+  constexpr int kThreads = 1024;
+  __shared__ double partial[kThreads][4];
+  // Thread t adds entries t, t + 1024, ... of an operand in that order; eight of them are fetched at a time (a large
+  // operand leaves 100000 entries, and one workgroup taking them one by one would be bound by the latency of each).
+  auto sum_of = [&](const double* stats, unsigned blocks, double& err2, double& norm2) {
+    err2 = 0.0, norm2 = 0.0;
+    unsigned i = threadIdx.x;
+    for (; (uint64_t)i + 7 * kThreads < blocks; i += 8 * kThreads) {
+      double e[8], n[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) e[u] = stats[2 * (size_t)(i + u * kThreads)], n[u] = stats[2 * (size_t)(i + u * kThreads) + 1];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) err2 += e[u], norm2 += n[u];
+    }
+    for (; i < blocks; i += kThreads) err2 += stats[2 * (size_t)i], norm2 += stats[2 * (size_t)i + 1];
+  };
+  double sums[4];
+  sum_of(stats_a, blocks_a, sums[0], sums[1]);
+  sum_of(stats_b, blocks_b, sums[2], sums[3]);
 #pragma unroll
   for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] = sums[q];
   __syncthreads();
-  for (int half = 128; half >= 1; half >>= 1) {
+  for (int half = kThreads / 2; half >= 1; half >>= 1) {
     if ((int)threadIdx.x < half)
 #pragma unroll
       for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] += partial[threadIdx.x + half][q];
