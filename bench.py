@@ -44,6 +44,9 @@ MEASURED_TRAFFIC_BYTES = {
     "c2_4096_fp16_urand": 6.04e8,            # profiles/product_kernel_fp16_4096cubed_persistent.md: 537 MB + 67 MB
     "c5_deepk_fp16": 5.71e8,                 # profiles/product_kernel_fp16_deepk_1024x1024x65536.md: 537 MB + 33.5 MB
                                              # (product kernel; its reduction moves another 38 MB)
+    # profiles/product_kernel_hbm_traffic_other_workloads.md:
+    "c2_4096_bf16_urand": 8.73e8, "c5_tallskinny_bf16": 1.50e9, "c5_deepk_bf16": 8.39e8, "c1_256_fp16_urand": 1.4e6,
+    "c5_odd_transA_fp16": 5.73e8, "c5_odd_transA_bf16": 8.18e8,
 }
 
 WORKLOADS = {
