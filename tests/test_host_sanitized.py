@@ -94,6 +94,8 @@ int main(void) {
   CHECK(ecgemm_sgemm(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_sgemm_noalloc(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_sgemm_scaled(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT, NULL, NULL) == ECGEMM_ERR_INVALID_ARG);
+  CHECK(ecgemm_sgemm(NULL, ECGEMM_OP_N, ECGEMM_OP_N, 1, 1, 1, 1.0f, NULL, 1, NULL, 1, 0.0f, NULL, 1, ECGEMM_MODE_AUTO) == ECGEMM_ERR_INVALID_ARG);
+  { ecgemm_mode_t chosen; int scaled; CHECK(ecgemm_auto_choice(NULL, &chosen, &scaled) == ECGEMM_ERR_INVALID_ARG); }
   CHECK(ecgemm_product(NULL, 1, 1, 1, 1.0f, NULL, NULL, 0.0f, NULL, 1, ECGEMM_MODE_FP16_SPLIT) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_split(NULL, ECGEMM_OP_N, 1, 1, NULL, 1, ECGEMM_MODE_FP16_SPLIT, NULL) == ECGEMM_ERR_INVALID_ARG);
   CHECK(ecgemm_row_scales(NULL, ECGEMM_OP_N, 1, 1, NULL, 1, 14, NULL) == ECGEMM_ERR_INVALID_ARG);
