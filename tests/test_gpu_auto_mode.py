@@ -125,6 +125,29 @@ def test_sliced_tiles_large_operands_and_the_builtin_workspace():
     h.destroy()
 
 
+def test_tiny_and_degenerate_shapes():
+    """One element, one row, one column, depths that end inside the first block: the choice and the bits still equal
+    the oracle's choice and the direct calls' bits."""
+    import torch
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    for (M, N, K) in [(1, 1, 1), (2, 3, 5), (17, 5, 8), (31, 33, 15), (64, 1, 100), (1, 257, 33)]:
+        for dist in ("urand", TYPE4):
+            A, B, C = _problem("N", "T", M, N, K, dist, dist, M + N + K, 2)
+            opA, opB = gemm.logical("N", A, M, K), gemm.logical("T", B, K, N)
+            want = split.automatic_choice(opA, opB)
+            got = _run(h, h.sgemm, "N", "T", M, N, K, 1.0, A, B, 0.0, C, ec.MODE_AUTO)
+            chosen = h.auto_choice()
+            assert chosen == {"fp16": (ec.MODE_FP16_SPLIT, False), "fp16 scaled": (ec.MODE_FP16_SPLIT, True),
+                              "bf16": (ec.MODE_BF16_FULL, False)}[want], (M, N, K, dist, want, chosen)
+            if want == "fp16 scaled":
+                direct, _, _ = _run_scaled(h, "N", "T", M, N, K, 1.0, A, B, 0.0, C)
+            else:
+                direct = _run(h, h.sgemm, "N", "T", M, N, K, 1.0, A, B, 0.0, C, chosen[0])
+            assert np.array_equal(got.view(np.uint32), direct.view(np.uint32)), (M, N, K, dist)
+    h.destroy()
+
+
 def test_special_values_and_prescaling():
     import torch
     import paper_2203_03341_amd as ec
