@@ -335,6 +335,36 @@ def test_a_call_can_be_captured_in_a_graph_and_replayed(mode):
     h.destroy()
 
 
+def test_two_handles_on_two_streams_do_not_interfere():
+    """Each handle owns its workspace and its settings; calls enqueued alternately on two streams, in different modes
+    and with different pre-scaling, give the bits each gives alone."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 900, 700, 1300
+    A, B = _inputs(M, N, K, "N", "N", "urand", 21)
+    dA, dB = to_device(A), to_device(B)
+    handles, streams, outs, alone = [], [], [], []
+    for i, (mode, scale) in enumerate((("fp16", 3), ("bf16", 0))):
+        h = ec.Handle()
+        h.set_scaling(scale, -scale)
+        alone.append(_gpu_sgemm("N", "N", M, N, K, 1.0, A, B, 0.0, None, mode, handle=h))
+        st = torch.cuda.Stream()
+        h.set_stream(st.cuda_stream)
+        handles.append((h, _modes()[mode]))
+        streams.append(st)
+        outs.append(empty_colmajor(M, N, fill=float("nan")))
+    torch.cuda.synchronize()
+    for _ in range(6):
+        for (h, mode_id), st, out in zip(handles, streams, outs):
+            with torch.cuda.stream(st):
+                h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, out, M, mode_id)
+    torch.cuda.synchronize()
+    for out, want in zip(outs, alone):
+        assert np.array_equal(to_host(out, M, N).view(np.uint32), want.view(np.uint32))
+    for h, _ in handles:
+        h.destroy()
+
+
 # ----- the shape sweep of the baseline (config 5), reduced in size where the full oracle would take minutes
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
