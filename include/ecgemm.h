@@ -241,8 +241,9 @@ ecgemm_status_t ecgemm_set_scaling(ecgemm_handle_t handle, int log2_scale_a, int
  * ecgemm_set_scaling (end of section "Effect of the exponent range of input matrices"), applied vector-wise.
  *
  * ecgemm_sgemm_scaled is ecgemm_sgemm with row m of op(A) multiplied by 2^row_log2_scale_a[m] and column n of op(B) by
- * 2^col_log2_scale_b[n] before the split (exact), and element (m, n) of the product multiplied by 2^-row_log2_scale_a[m]
- * and then by 2^-col_log2_scale_b[n] (exact unless the result leaves the FP32 range) before alpha / beta.  The vectors
+ * 2^col_log2_scale_b[n] before the split (exact), and element (m, n) of the product multiplied by
+ * 2^-(row_log2_scale_a[m] + col_log2_scale_b[n]) (exact unless the result leaves the normal FP32 range; the two
+ * exponents are added first, so one of them alone may be far outside what the product could bear) before alpha / beta.  The vectors
  * are device arrays of M and N 32-bit integers in [-126, 126], read during the call and not kept; both NULL gives
  * ecgemm_sgemm.  The handle's global scaling, if any, is applied as well.
  *

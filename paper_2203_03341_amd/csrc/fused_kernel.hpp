@@ -189,7 +189,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
-        c = c * exp2_int(-p.row_log2_scale[m]) * exp2_int(-p.col_log2_scale[n]);
+        c = unscale(c, p.row_log2_scale[m], p.col_log2_scale[n]);
         if (out) {
           out[(n - n0) * BM + (m - m0)] = c;
         } else {

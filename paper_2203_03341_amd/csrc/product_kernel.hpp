@@ -44,6 +44,15 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 // 2^e as a float, e in [-126, 127]
 __device__ __forceinline__ float exp2_int(int e) { return __builtin_bit_cast(float, (unsigned)(e + 127) << 23); }
 
+// c * 2^-(row_exponent + col_exponent), exact whenever the result is a normal FP32 number.  The exponents are in
+// [-126, 126] each, so their sum may be beyond what one factor expresses: it is applied in two halves, which keeps
+// the intermediate between c and the result (taking the two exponents one after the other would not: 2^-row alone
+// can overflow where the product of both is an ordinary number).
+__device__ __forceinline__ float unscale(float c, int row_exponent, int col_exponent) {
+  const int total = -(row_exponent + col_exponent), half = total / 2;
+  return c * exp2_int(half) * exp2_int(total - half);
+}
+
 // An element of C is written once and not read again by this call: a non-temporal store keeps it from pushing the
 // operand panels out of the L2 (measured: 19 % off the 256 x 128 kernel and 4 % off the 128 x 128 kernel at
 // 16384 x 16384 x 256, where C is most of the traffic; nothing lost at 16384^3).
@@ -177,7 +186,7 @@ struct ProductParams {
   float alpha, beta;
   float out_scale;          // power of two that undoes the caller's pre-scaling of A and B (1 by default)
   // per-row / per-column pre-scaling (both null, or both set): element (m, n) of the product is multiplied by
-  // 2^-row_log2_scale[m] and then by 2^-col_log2_scale[n] before alpha / beta
+  // 2^-(row_log2_scale[m] + col_log2_scale[n]) before alpha / beta (see unscale())
   const int* row_log2_scale;  // device, M entries
   const int* col_log2_scale;  // device, N entries
   float* C;
@@ -832,15 +841,15 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     if constexpr (FAST_SCALED) {
       if (interior && out == nullptr) {
         written = true;
-        // a lane needs the factors of its TM rows and, per 32 x 32 block, of 16 columns
-        float row_factor[TM];
+        // a lane needs the exponents of its TM rows and, per 32 x 32 block, of 16 columns
+        int row_exponent[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) row_factor[i] = exp2_int(-load_global(row_scale + m_base + i * 32));
+        for (int i = 0; i < TM; ++i) row_exponent[i] = load_global(row_scale + m_base + i * 32);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          float col_factor[16];
+          int col_exponent[16];
 #pragma unroll
-          for (int v = 0; v < 16; ++v) col_factor[v] = exp2_int(-load_global(col_scale + n_base + j * 32 + 8 * (v / 4) + (v % 4)));
+          for (int v = 0; v < 16; ++v) col_exponent[v] = load_global(col_scale + n_base + j * 32 + 8 * (v / 4) + (v % 4));
 #pragma unroll
           for (int i = 0; i < TM; ++i) {
             float* dst = c_base + (m_base + i * 32) + (n_base + j * 32) * ldc;
@@ -851,12 +860,12 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
 #pragma unroll
               for (int v = 0; v < 16; ++v)
                 store_result(dst + (8 * (v / 4) + (v % 4)) * ldc,
-                             scaled_sum(p.alpha, merged(i, j, v) * p.out_scale * row_factor[i] * col_factor[v], p.beta, c_in[v]));
+                             scaled_sum(p.alpha, unscale(merged(i, j, v) * p.out_scale, row_exponent[i], col_exponent[v]), p.beta, c_in[v]));
             } else {
 #pragma unroll
               for (int v = 0; v < 16; ++v)
                 store_result(dst + (8 * (v / 4) + (v % 4)) * ldc,
-                             p.alpha * (merged(i, j, v) * p.out_scale * row_factor[i] * col_factor[v]));
+                             p.alpha * unscale(merged(i, j, v) * p.out_scale, row_exponent[i], col_exponent[v]));
             }
           }
         }
@@ -864,7 +873,7 @@ __global__ void __launch_bounds__(Cfg::THREADS, Cfg::BLOCKS_PER_CU) product_kern
     }
     if (!written) for_each_output([&](int64_t m, int64_t n, float c) {
       if (m < p.M && n < p.N) {
-        c = c * exp2_int(-load_global(row_scale + m)) * exp2_int(-load_global(col_scale + n));
+        c = unscale(c, load_global(row_scale + m), load_global(col_scale + n));
         if (out) {
           store_partial(out + (n - n0) * Cfg::BM + (m - m0), c);
         } else {

@@ -808,6 +808,35 @@ def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
     h.destroy()
 
 
+@pytest.mark.parametrize("shape", [None, "x2", "fused"])
+def test_scaling_exponents_that_only_cancel_together(shape):
+    """Rows of op(A) near 2^120 and columns of op(B) near 2^-125: the product is an ordinary number, but either scaling
+    exponent alone (-106, +126) would push the scaled product out of the FP32 range before the other brings it back.
+    The two are undone as one sum."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 200, 260, 96
+    opA = np.ldexp(si.urand(M, K, 5, si.ID_A)[:M, :K], 120).astype(np.float32)
+    opB = np.ldexp(si.urand(K, N, 5, si.ID_B)[:K, :N], -125).astype(np.float32)
+    A, B = np.asfortranarray(opA), np.asfortranarray(opB)
+    h = ec.Handle()
+    h.set_shape(_shapes()[shape])
+    dA, dB = to_device(A), to_device(B)
+    sa = torch.empty(M, dtype=torch.int32, device="cuda")
+    sb = torch.empty(N, dtype=torch.int32, device="cuda")
+    h.row_scales(ec.OP_N, M, K, dA, M, 14, sa)
+    h.row_scales(ec.OP_T, N, K, dB, K, 14, sb)
+    dC = empty_colmajor(M, N, fill=float("nan"))
+    h.sgemm_scaled(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_FP16_SPLIT, sa, sb)
+    torch.cuda.synchronize()
+    got = to_host(dC, M, N)
+    assert sa.cpu().numpy().min() <= -105 and sb.cpu().numpy().max() >= 125
+    c64 = gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.0, A, B)
+    c32 = gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.0, A, B)
+    assert np.all(np.isfinite(got)) and gemm.relative_residual(c64, got) <= RATIO * gemm.relative_residual(c64, c32)
+    h.destroy()
+
+
 @pytest.mark.parametrize("mode", ["outside", "outside4", "outside16"])
 def test_accumulating_outside_the_matrix_unit_as_the_paper_does(mode):
     """The paper's listing verbatim (zeroed temporary, FP32 vector adds every k step), and the same with the matrix unit
