@@ -194,12 +194,17 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
  *      a fixed order, |x|^2 and |x - (v16 + dv16 * 2^-11)|^2 over each operand;
  *   2. a one-workgroup kernel that chooses the FP16 mode if for both operands the second sum is at most 2^-48 times the
  *      first, that is, if the pair represents each operand to a relative error of 2^-24 (the unit roundoff of FP32) in
- *      the Frobenius norm;
+ *      the Frobenius norm, and if at least one operand spreads the weight of a row over 16 elements or more, measured by
+ *      (sum |x|)^2 / (rows * sum x^2) (the kernels sum |x| as well): the pair holds 22.75 of FP32's 24 bits, which
+ *      matches an FP32 product only where that product's own summation error outweighs the missing bit, not for dot
+ *      products carried by a handful of terms (very short K, or exponents spread so widely that a few elements dominate
+ *      each row);
  *   3. otherwise: the scaling exponents of ecgemm_row_scales for the rows of op(A) and the columns of op(B) (largest
  *      binade of each to 2^14), the FP16 pair split of the operands scaled by them with the same sums, and a second
  *      choice by the same rule: the FP16 mode on the scaled operands, with the factors divided out element by element
  *      as in ecgemm_sgemm_scaled (a row-wise and column-wise guarantee: the error of element (m, n) is then bounded
- *      relative to |row m of op(A)| |column n of op(B)|), or else the BF16 mode (an operand holds a NaN or an infinity);
+ *      relative to |row m of op(A)| |column n of op(B)|), or else the BF16 mode (an operand holds a NaN or an infinity, or
+ *      the rows are too short in the sense of step 2);
  *   4. the three-term BF16 split and the three products, each of which reads the choice from device memory when it
  *      starts and returns at once if it is not the one chosen.
  * The result is bitwise that of ecgemm_sgemm in FP16 mode, of ecgemm_row_scales (target 14) + ecgemm_sgemm_scaled in
@@ -211,7 +216,7 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
  * below their row's or column's largest: a caller who needs every element of A and B honoured to 24 bits whatever its
  * size asks for ECGEMM_MODE_BF16_FULL.  Cost over calling the chosen arrangement directly: the statistics in the split
  * (it stays bound by memory traffic), about a dozen kernel launches that do nothing, and for the later candidates the
- * splits that are thrown away.  Workspace: that of the BF16 mode plus 16 bytes per 64 x 32 block of each operand, 4 (M + N)
+ * splits that are thrown away.  Workspace: that of the BF16 mode plus 24 bytes per 64 x 32 block of each operand, 4 (M + N)
  * bytes and 256 (ecgemm_workspace_size with ECGEMM_MODE_AUTO).  Not available with caller-given scaling vectors,
  * ecgemm_split / ecgemm_product, ecgemm_plan_info or the fused kernel shape (ECGEMM_ERR_UNSUPPORTED or
  * ECGEMM_ERR_INVALID_ARG for the mode).

@@ -123,16 +123,38 @@ def scale_rows(x: np.ndarray, exponents: np.ndarray) -> np.ndarray:
         return (x * np.ldexp(np.float32(1.0), np.asarray(exponents, dtype=np.int32))[:, None]).astype(np.float32)
 
 
-def automatic_choice(opA: np.ndarray, opB: np.ndarray, tolerance: float = 2.0 ** -24, target: int = 14) -> str:
-    """What the library's automatic mode runs for op(A) (M x K) and op(B) (K x N): "fp16" if the pair represents both
-    operands as they are; else "fp16 scaled" if it represents them once every row of op(A) and every column of op(B)
+def participation(x: np.ndarray) -> float:
+    """(sum |x|)^2 / (rows sum x^2) in FP64: about how many elements of a row of x carry the row's weight (rows of
+    equal elements give the row length, a row with one non-zero element gives 1).  Infinite for an all-zero x."""
+    x = np.atleast_2d(np.asarray(x, dtype=np.float32)).astype(np.float64)
+    with np.errstate(invalid="ignore", over="ignore", divide="ignore"):
+        norm2 = float(np.sum(x * x))
+        return float("inf") if norm2 == 0.0 else float(np.sum(np.abs(x)) ** 2 / (x.shape[0] * norm2))
+
+
+def fp16_pair_suffices(rows_a: np.ndarray, rows_b: np.ndarray, tolerance: float = 2.0 ** -24, min_terms: float = 16.0) -> bool:
+    """The test both candidates of the automatic mode have to pass, on op(A) (M x K) and op(B)^T (N x K) as they
+    would be split: the pair represents both to within `tolerance` (fp16_pair_represents), and at least one of them
+    spreads a row's weight over `min_terms` elements or more.  The pair holds 22.75 of FP32's 24 bits (the paper's
+    mantissa-length table); that is as good as an FP32 product only where the product's own summation error
+    outweighs the missing bit, i.e. not for dot products carried by a handful of terms (the small-k end of the
+    paper's error-against-k figure)."""
+    if not fp16_pair_represents(rows_a, rows_b, tolerance):
+        return False
+    return bool(participation(rows_a) >= min_terms or participation(rows_b) >= min_terms)
+
+
+def automatic_choice(opA: np.ndarray, opB: np.ndarray, tolerance: float = 2.0 ** -24, target: int = 14,
+                     min_terms: float = 16.0) -> str:
+    """What the library's automatic mode runs for op(A) (M x K) and op(B) (K x N): "fp16" if the pair suffices for
+    both operands as they are; else "fp16 scaled" if it suffices once every row of op(A) and every column of op(B)
     has its largest binade at 2^target; else "bf16"."""
-    if fp16_pair_represents(opA, opB, tolerance):
-        return "fp16"
     bt = np.asarray(opB, dtype=np.float32).T
+    if fp16_pair_suffices(opA, bt, tolerance, min_terms):
+        return "fp16"
     scaled_a = scale_rows(opA, row_scale_exponents(opA, target))
     scaled_b = scale_rows(bt, row_scale_exponents(bt, target))
-    return "fp16 scaled" if fp16_pair_represents(scaled_a, scaled_b, tolerance) else "bf16"
+    return "fp16 scaled" if fp16_pair_suffices(scaled_a, scaled_b, tolerance, min_terms) else "bf16"
 
 
 BF16_MAX_BITS = np.uint32(0x7F7F)

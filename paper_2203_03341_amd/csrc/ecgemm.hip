@@ -269,6 +269,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
 // 64 x 32 block of the padded operand, the most any split kernel variant launches (which variant runs depends on the
 // operands' alignment, and the workspace size must not).
 constexpr double kAutoTolerance = 0x1p-24;
+constexpr double kAutoMinTerms = 16.0;  // see choose_mode_kernel
 struct AutoPlan {
   Plan fp16, bf16;
   bool exists;
@@ -283,8 +284,9 @@ AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
   const size_t blocks_per_row_block = (size_t)(round_up(K, kDepthPad) / 32);
   ap.packed_bytes = std::max(ap.fp16.a_bytes + ap.fp16.b_bytes, ap.bf16.a_bytes + ap.bf16.b_bytes);
   ap.partial_bytes = std::max(ap.fp16.partial_bytes, ap.bf16.partial_bytes);
-  ap.stats_a_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(M, kRowPad) / 64));
-  ap.stats_b_bytes = align256(16 * blocks_per_row_block * (size_t)(round_up(N, kRowPad) / 64));
+  const size_t per_block = kStatsPerBlock * sizeof(double);
+  ap.stats_a_bytes = align256(per_block * blocks_per_row_block * (size_t)(round_up(M, kRowPad) / 64));
+  ap.stats_b_bytes = align256(per_block * blocks_per_row_block * (size_t)(round_up(N, kRowPad) / 64));
   ap.scales_a_bytes = align256(sizeof(int32_t) * (size_t)M);
   ap.scales_b_bytes = align256(sizeof(int32_t) * (size_t)N);
   ap.total_bytes = ap.packed_bytes + ap.partial_bytes + ap.stats_a_bytes + ap.stats_b_bytes + ap.scales_a_bytes +
@@ -1042,7 +1044,8 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   if (st != ECGEMM_OK) return st;
   st = make_split_job(h, op_b, N, K, B, ldb, ws + ap.bf16.a_bytes, h->log2_scale_b, nullptr, &bf16_b);
   if (st != ECGEMM_OK) return st;
-  if (16 * (size_t)fp16_a.blocks > ap.stats_a_bytes || 16 * (size_t)fp16_b.blocks > ap.stats_b_bytes)
+  if (kStatsPerBlock * sizeof(double) * fp16_a.blocks > ap.stats_a_bytes ||
+      kStatsPerBlock * sizeof(double) * fp16_b.blocks > ap.stats_b_bytes)
     return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: internal error, statistics array too small");
   fp16_a.stats = stats_a;
   fp16_b.stats = stats_b;
@@ -1067,9 +1070,9 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   }
   st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
   if (st != ECGEMM_OK) return st;
-  hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, fp16_a.blocks, stats_b, fp16_b.blocks,
-                     kAutoTolerance, choice, (int)kChoiceFp16, (int)(try_scaled ? kChoiceUndecided : kChoiceBf16),
-                     (const int*)nullptr, 0);
+  hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, fp16_a.blocks, (double)M, stats_b,
+                     fp16_b.blocks, (double)N, kAutoTolerance, kAutoMinTerms, choice, (int)kChoiceFp16,
+                     (int)(try_scaled ? kChoiceUndecided : kChoiceBf16), (const int*)nullptr, 0);
   ECGEMM_HIP(h, hipGetLastError());
   h->auto_choice = choice;
   if (try_scaled) {
@@ -1079,9 +1082,9 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
     if (st != ECGEMM_OK) return st;
     st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, scaled_a, &scaled_b, true);
     if (st != ECGEMM_OK) return st;
-    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, scaled_a.blocks, stats_b, scaled_b.blocks,
-                       kAutoTolerance, choice, (int)kChoiceFp16Scaled, (int)kChoiceBf16, (const int*)choice,
-                       (int)kChoiceUndecided);
+    hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, scaled_a.blocks, (double)M, stats_b,
+                       scaled_b.blocks, (double)N, kAutoTolerance, kAutoMinTerms, choice, (int)kChoiceFp16Scaled,
+                       (int)kChoiceBf16, (const int*)choice, (int)kChoiceUndecided);
     ECGEMM_HIP(h, hipGetLastError());
   }
   st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);

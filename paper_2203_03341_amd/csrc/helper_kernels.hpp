@@ -164,47 +164,64 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
   sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-// Automatic mode choice: from the blocks' statistics of both operands, *choice = if_fits (the FP16 pair represents both
-// operands as they were split to within `tolerance`, relative, in the Frobenius norm) or if_not.  One block of 1024
-// threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere gives if_not.
-// Gated like the other kernels, on the word it writes: the second round of the choice runs only if the first failed.
-__global__ void __launch_bounds__(1024) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a,
-                                                           const double* __restrict__ stats_b, unsigned blocks_b,
-                                                           double tolerance, int* __restrict__ choice, int if_fits, int if_not,
-                                                           const int* gate, int gate_value) {
+// Automatic mode choice: from the blocks' statistics of both operands, *choice = if_fits or if_not.  It fits if
+//   * the FP16 pair represents both operands as they were split to within `tolerance`, relative, in the Frobenius
+//     norm, and
+//   * at least one operand spreads the weight of a row over `min_terms` elements or more, measured by the
+//     participation ratio (sum |x|)^2 / (rows sum x^2): the pair holds 22.75 of FP32's 24 bits, which is as good as
+//     an FP32 product only where that product's own summation error outweighs the missing bit; a dot product carried
+//     by a handful of terms is rounded a handful of times by FP32 and is better served by the exact three-term split.
+// One block of 1024 threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere
+// gives if_not.  Gated like the other kernels, on the word it writes: the second round runs only if the first failed.
+__global__ void __launch_bounds__(1024) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a, double rows_a,
+                                                           const double* __restrict__ stats_b, unsigned blocks_b, double rows_b,
+                                                           double tolerance, double min_terms, int* __restrict__ choice,
+                                                           int if_fits, int if_not, const int* gate, int gate_value) {
   if (!gate_open(gate, gate_value)) return;
-  constexpr int kThreads = 1024;
-  __shared__ double partial[kThreads][4];
+  constexpr int kThreads = 1024, kS = kStatsPerBlock;
+  __shared__ double partial[kThreads][2 * kS];
   // Thread t adds entries t, t + 1024, ... of an operand in that order; eight of them are fetched at a time (a large
   // operand leaves 100000 entries, and one workgroup taking them one by one would be bound by the latency of each).
-  auto sum_of = [&](const double* stats, unsigned blocks, double& err2, double& norm2) {
-    err2 = 0.0, norm2 = 0.0;
+  auto sum_of = [&](const double* stats, unsigned blocks, double* sums) {
+#pragma unroll
+    for (int q = 0; q < kS; ++q) sums[q] = 0.0;
     unsigned i = threadIdx.x;
     for (; (uint64_t)i + 7 * kThreads < blocks; i += 8 * kThreads) {
-      double e[8], n[8];
+      double v[8][kS];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) e[u] = stats[2 * (size_t)(i + u * kThreads)], n[u] = stats[2 * (size_t)(i + u * kThreads) + 1];
+      for (int u = 0; u < 8; ++u)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) err2 += e[u], norm2 += n[u];
+        for (int q = 0; q < kS; ++q) v[u][q] = stats[kS * (size_t)(i + u * kThreads) + q];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int q = 0; q < kS; ++q) sums[q] += v[u][q];
     }
-    for (; i < blocks; i += kThreads) err2 += stats[2 * (size_t)i], norm2 += stats[2 * (size_t)i + 1];
-  };
-  double sums[4];
-  sum_of(stats_a, blocks_a, sums[0], sums[1]);
-  sum_of(stats_b, blocks_b, sums[2], sums[3]);
+    for (; i < blocks; i += kThreads)
 #pragma unroll
-  for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] = sums[q];
+      for (int q = 0; q < kS; ++q) sums[q] += stats[kS * (size_t)i + q];
+  };
+  double sums[2 * kS];
+  sum_of(stats_a, blocks_a, sums);
+  sum_of(stats_b, blocks_b, sums + kS);
+#pragma unroll
+  for (int q = 0; q < 2 * kS; ++q) partial[threadIdx.x][q] = sums[q];
   __syncthreads();
   for (int half = kThreads / 2; half >= 1; half >>= 1) {
     if ((int)threadIdx.x < half)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) partial[threadIdx.x][q] += partial[threadIdx.x + half][q];
+      for (int q = 0; q < 2 * kS; ++q) partial[threadIdx.x][q] += partial[threadIdx.x + half][q];
     __syncthreads();
   }
   if (threadIdx.x == 0) {
+    const double* a = partial[0];      // err2, norm2, abs1 of A
+    const double* b = partial[0] + kS;  // ... of B
     const double t2 = tolerance * tolerance;
-    const bool fits = partial[0][0] <= t2 * partial[0][1] && partial[0][2] <= t2 * partial[0][3];
-    *choice = fits ? if_fits : if_not;
+    const bool represented = a[0] <= t2 * a[1] && b[0] <= t2 * b[1];
+    // (sum |x|)^2 >= min_terms rows sum x^2, for either operand; an all-zero operand has nothing to lose
+    const bool spread = a[2] * a[2] >= min_terms * rows_a * a[1] || b[2] * b[2] >= min_terms * rows_b * b[1] ||
+                        a[1] == 0.0 || b[1] == 0.0;
+    *choice = (represented && spread) ? if_fits : if_not;
   }
 }
 

@@ -88,11 +88,13 @@ struct Splitter {
   }
 };
 
-// What the automatic mode choice needs to know about an operand: how much of it the FP16 pair loses.  Per thread, then
-// per block: the sums of (x - (v16 + dv16 2^-11))^2 and of x^2 over the elements handled, in FP64.
+// What the automatic mode choice needs to know about an operand: how much of it the FP16 pair loses, and how many
+// elements of a row carry its weight.  Per thread, then per block: the sums of (x - (v16 + dv16 2^-11))^2, of x^2 and
+// of |x| over the elements handled, in FP64.
 struct SplitStats {
-  double err2 = 0.0, norm2 = 0.0;
+  double err2 = 0.0, norm2 = 0.0, abs1 = 0.0;
 };
+constexpr int kStatsPerBlock = 3;  // doubles a block leaves: err2, norm2, abs1
 
 // Writes the eight consecutive-k values `v` of row r (global indices) to their place in `packed`.
 template <int KIND, bool STATS = false>
@@ -123,6 +125,7 @@ __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ 
       const double lost = (double)v[e] - (double)kept, x = (double)v[e];
       stats->err2 += lost * lost;
       stats->norm2 += x * x;
+      stats->abs1 += __builtin_fabs(x);
     }
   }
   const int64_t row_block = r >> 5, k_step = k >> 4;
@@ -143,7 +146,7 @@ struct SplitJob {
   unsigned fast_tiles;        // tiles along the direction in which the blocks are numbered first
   unsigned blocks;
   int variant;                // SplitVariant
-  // Automatic mode choice only, else null: block b leaves its SplitStats at stats[2 b], stats[2 b + 1]
+  // Automatic mode choice only, else null: block b leaves its SplitStats at stats[kStatsPerBlock b ...]
   double* stats;
   // Automatic mode choice only, else null: the kernel does nothing unless *gate == gate_value
   const int* gate;
@@ -151,20 +154,19 @@ struct SplitJob {
 };
 
 // Sums the threads' statistics over the block in a fixed order and stores them (all 256 threads call this).
-__device__ __forceinline__ void store_block_stats(const SplitStats& mine, double* __restrict__ out, double* scratch8) {
-  double e = mine.err2, n = mine.norm2;
+__device__ __forceinline__ void store_block_stats(const SplitStats& mine, double* __restrict__ out, double* scratch12) {
+  double e = mine.err2, n = mine.norm2, a = mine.abs1;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
     e += __shfl_xor(e, d, 64);
     n += __shfl_xor(n, d, 64);
+    a += __shfl_xor(a, d, 64);
   }
   const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) scratch8[2 * wave] = e, scratch8[2 * wave + 1] = n;
+  if ((threadIdx.x & 63) == 0) scratch12[3 * wave] = e, scratch12[3 * wave + 1] = n, scratch12[3 * wave + 2] = a;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    out[0] = (scratch8[0] + scratch8[2]) + (scratch8[4] + scratch8[6]);
-    out[1] = (scratch8[1] + scratch8[3]) + (scratch8[5] + scratch8[7]);
-  }
+  if (threadIdx.x < kStatsPerBlock)
+    out[threadIdx.x] = (scratch12[threadIdx.x] + scratch12[3 + threadIdx.x]) + (scratch12[6 + threadIdx.x] + scratch12[9 + threadIdx.x]);
 }
 enum SplitVariant { kSplitKContiguousVec = 0, kSplitKContiguous = 1, kSplitRContiguous = 2, kSplitRContiguousWide = 3 };
 
@@ -313,9 +315,9 @@ __global__ void __launch_bounds__(256) split_kernel(const SplitJob job) {
     split_block_k_contiguous_staged<KIND, STATS>(job, xcd_run_position(blockIdx.x, job.blocks), tile, &stats);
   }
   if constexpr (STATS) {
-    __shared__ double sums[8];
+    __shared__ double sums[12];
     // (indexed by the launch's block number: the choice adds all blocks of an operand, in that order)
-    store_block_stats(stats, job.stats + 2 * (size_t)blockIdx.x, sums);
+    store_block_stats(stats, job.stats + kStatsPerBlock * (size_t)blockIdx.x, sums);
   }
 }
 
@@ -336,8 +338,8 @@ __global__ void __launch_bounds__(256) split_pair_kernel(const SplitJob a, const
     default: split_block_k_contiguous_staged<KIND, STATS>(job, xcd_run_position(block, job.blocks), tile, &stats); break;
   }
   if constexpr (STATS) {
-    __shared__ double sums[8];
-    store_block_stats(stats, job.stats + 2 * (size_t)block, sums);
+    __shared__ double sums[12];
+    store_block_stats(stats, job.stats + kStatsPerBlock * (size_t)block, sums);
   }
 }
 

@@ -152,7 +152,7 @@ def test_special_values_and_prescaling():
     import torch
     import paper_2203_03341_amd as ec
     h = ec.Handle()
-    M, N, K = 200, 150, 96
+    M, N, K = 200, 150, 512
     A, B, C = _problem("N", "N", M, N, K, "urand", "urand", 9, 0)
     ops = (ec.OP_N, ec.OP_N)
     FP16, SCALED, BF16 = (ec.MODE_FP16_SPLIT, False), (ec.MODE_FP16_SPLIT, True), (ec.MODE_BF16_FULL, False)
@@ -191,6 +191,15 @@ def test_special_values_and_prescaling():
     assert mode == SCALED and np.array_equal(out4.view(np.uint32), out4_plain.view(np.uint32))
     c64 = gemm.sgemm_fp64_ref("N", "N", M, N, K, 1.0, A4, B4)
     assert gemm.relative_residual(c64, out4) <= 1.25 * gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", M, N, K, 1.0, A4, B4))
+    # rows too short for either FP16 arrangement to be worth it (a handful of elements carry each dot product): the
+    # exact three-term split, although the pair would represent the scaled operands
+    short = 96
+    A5, B5, _ = _problem("N", "N", M, N, short, TYPE3, TYPE3, 12, 0)
+    assert split.fp16_pair_represents(split.scale_rows(A5[:M, :short], split.row_scale_exponents(A5[:M, :short])),
+                                      split.scale_rows(B5[:short, :N].T, split.row_scale_exponents(B5[:short, :N].T)))
+    dA, dB, dC = to_device(A5), to_device(B5), to_device(C)
+    h.sgemm(*ops, M, N, short, 1.0, dA, M, dB, short, 0.0, dC, M, ec.MODE_AUTO)
+    assert h.auto_choice() == BF16 and split.automatic_choice(A5[:M, :short], B5[:short, :N]) == "bf16"
     h.destroy()
 
 

@@ -567,21 +567,40 @@ def test_row_scaling_and_the_three_way_automatic_choice():
     scaled = split.scale_rows(rows[[0, 3]], [13, -86])
     assert np.array_equal(scaled, np.float32([[3.0 * 8192, -4096.0, 0.0], [16384.0, 2.0 ** -86, -8192.0]]))
 
+    # how many elements carry a row: equal elements give the row length, a single one gives 1
+    assert split.participation(np.ones((3, 7), np.float32)) == pytest.approx(7.0)
+    assert split.participation(np.float32([[0, -5, 0, 0]])) == pytest.approx(1.0)
+    assert split.participation(np.float32([[1, 1, 1, 1], [2, 0, 0, 0]])) == pytest.approx(36.0 / 16.0)
+    assert split.participation(np.zeros((2, 3), np.float32)) == float("inf")
+    assert split.participation(si.urand(64, 4096, 0, si.ID_A)) == pytest.approx(0.75 * 4096, rel=0.02)   # (E|x|)^2 / E x^2 = 3/4
+
+    def run(n, k, a_rng, b_rng):
+        A = si.exp_rand(n, k, *a_rng, 0, si.ID_A)
+        B = si.exp_rand(k, n, *b_rng, 0, si.ID_B)
+        choice = split.automatic_choice(A, B)
+        ea, eb = split.row_scale_exponents(A), split.row_scale_exponents(B.T)
+        with np.errstate(over="ignore"):
+            c64 = gemm.sgemm_fp64_ref("N", "N", n, n, k, 1.0, A, B)
+            r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, k, 1.0, A, B))
+        product = model.gemm_fp16_mode(split.scale_rows(A, ea), split.scale_rows(B.T, eb).T.copy())
+        unscaled = np.ldexp(np.ldexp(product, -ea[:, None].astype(np.int32)), -eb[None, :].astype(np.int32))
+        return choice, gemm.relative_residual(c64, unscaled) / r32
+
+    # Long enough rows: the scaled arrangement is chosen and is at least as accurate as the FP32 product.
+    for k, a_rng, b_rng, want in ((192, (-15, 14), (-15, 14), "fp16"), (192, (-15, 14), (-100, -35), "fp16 scaled"),
+                                  (192, (-35, -15), (-35, -15), "fp16 scaled"), (1024, (-100, -35), (-100, -35), "fp16 scaled"),
+                                  (192, (-100, 100), (-15, 14), "fp16 scaled"), (4096, (-100, 100), (-100, 0), "fp16 scaled")):
+        choice, ratio = run(160, k, a_rng, b_rng)
+        assert choice == want and ratio <= 1.0, (k, a_rng, b_rng, choice, ratio)
+    # Dot products carried by a handful of terms (wide exponent ranges over short rows): the FP32 product barely rounds,
+    # the pair's missing bit shows (ratio above 1), and the choice is the exact three-term split.
+    for k, a_rng, b_rng in ((300, (-100, 100), (-100, 0)), (300, (-60, 60), (-60, 60))):
+        choice, ratio = run(160, k, a_rng, b_rng)
+        assert choice == "bf16" and ratio > 1.0, (k, a_rng, b_rng, choice, ratio)
+    # (the threshold errs on the safe side: Type 4 over rows of 192 is sent the same way with the margin not yet gone)
+    choice, ratio = run(160, 192, (-100, -35), (-100, -35))
+    assert choice == "bf16" and 0.5 < ratio < 1.0
     n = 192
-    for a_rng, b_rng, want in (((-15, 14), (-15, 14), "fp16"), ((-15, 14), (-100, -35), "fp16 scaled"),
-                               ((-35, -15), (-35, -15), "fp16 scaled"), ((-100, -35), (-100, -35), "fp16 scaled"),
-                               ((-100, 100), (-15, 14), "fp16 scaled")):
-        A = si.exp_rand(n, n, *a_rng, 0, si.ID_A)
-        B = si.exp_rand(n, n, *b_rng, 0, si.ID_B)
-        assert split.automatic_choice(A, B) == want, (a_rng, b_rng)
-        if want == "fp16 scaled":
-            ea, eb = split.row_scale_exponents(A), split.row_scale_exponents(B.T)
-            with np.errstate(over="ignore"):
-                c64 = gemm.sgemm_fp64_ref("N", "N", n, n, n, 1.0, A, B)
-                r32 = gemm.relative_residual(c64, gemm.sgemm_fp32_naive("N", "N", n, n, n, 1.0, A, B))
-            product = model.gemm_fp16_mode(split.scale_rows(A, ea), split.scale_rows(B.T, eb).T.copy())
-            unscaled = np.ldexp(np.ldexp(product, -ea[:, None].astype(np.int32)), -eb[None, :].astype(np.int32))
-            assert gemm.relative_residual(c64, unscaled) <= r32, (a_rng, b_rng)
     poisoned = si.urand(n, n, 1, si.ID_A).copy()
     poisoned[5, 7] = np.nan
     assert split.automatic_choice(poisoned, si.urand(n, n, 1, si.ID_B)) == "bf16"
