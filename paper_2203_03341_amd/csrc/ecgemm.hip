@@ -333,6 +333,7 @@ ecgemm_status_t make_split_job(ecgemm_handle_t h, ecgemm_op_t op, int64_t rows, 
   job->stats = nullptr;
   job->gate = nullptr;
   job->gate_value = 0;
+  job->row_max = nullptr;
   job->variant = k_contiguous ? (vec ? kSplitKContiguousVec : kSplitKContiguous) : (vec ? kSplitRContiguousWide : kSplitRContiguous);
   // blocks are 64 rows x 32 k, except 256 x 32 (wide) and 64 x 64 (k contiguous, unaligned)
   switch (job->variant) {
@@ -601,14 +602,18 @@ ecgemm_status_t make_row_scale_job(ecgemm_handle_t handle, ecgemm_op_t op, int64
   return ECGEMM_OK;
 }
 
-// The three kernels of ecgemm_row_scales for one job or two (b.rows == 0: one), optionally gated.
+// The kernels of ecgemm_row_scales for one job or two (b.rows == 0: one), optionally gated: step 1 (clear), step 2
+// (largest exponents) and step 3 (exponents to scaling exponents), or a subset of them.
+enum RowScaleSteps { kRowScaleClear = 1, kRowScaleMax = 2, kRowScaleFinish = 4, kRowScaleAll = 7 };
 ecgemm_status_t launch_row_scales(ecgemm_handle_t handle, const RowScaleJob& a, const RowScaleJob& b, const int* gate,
-                                  int gate_value) {
+                                  int gate_value, int steps = kRowScaleAll) {
   const unsigned per_row = (unsigned)((a.rows + b.rows + 255) / 256);
-  hipLaunchKernelGGL(row_scales_clear_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
-  if (a.blocks + b.blocks > 0)
+  if (steps & kRowScaleClear)
+    hipLaunchKernelGGL(row_scales_clear_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
+  if ((steps & kRowScaleMax) && a.blocks + b.blocks > 0)
     hipLaunchKernelGGL(row_max_exponent_kernel, dim3(a.blocks + b.blocks), dim3(256), 0, handle->stream, a, b, gate, gate_value);
-  hipLaunchKernelGGL(row_scales_finish_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
+  if (steps & kRowScaleFinish)
+    hipLaunchKernelGGL(row_scales_finish_kernel, dim3(per_row), dim3(256), 0, handle->stream, a, b, gate, gate_value);
   ECGEMM_HIP(handle, hipGetLastError());
   return ECGEMM_OK;
 }
@@ -998,11 +1003,11 @@ struct EventLease {
 // ECGEMM_MODE_AUTO (arguments already checked).  Nothing here waits for the GPU: the kernels of every candidate are
 // enqueued, each gated on the word `choice` in device memory, so the ones that are not wanted return at once.
 //   1. the FP16 pair split of A and of B, which also leave per block the squared Frobenius norm of the operand and of
-//      what the pair fails to represent of it
+//      what the pair fails to represent of it, and per row the largest binary exponent (for step 3)
 //   2. first choice: kChoiceFp16 if both operands are represented to within kAutoTolerance, relative; else undecided
-//   3. if undecided: the per-row / per-column scaling exponents of both operands (largest binade of every row of op(A)
-//      and column of op(B) to 2^14), the FP16 pair split of the scaled operands with the same statistics, and the
-//      second choice: kChoiceFp16Scaled if that fits, else kChoiceBf16
+//   3. if undecided: the per-row / per-column scaling exponents of both operands from step 1's exponents (largest
+//      binade of every row of op(A) and column of op(B) to 2^14), the FP16 pair split of the scaled operands with the
+//      same statistics, and the second choice: kChoiceFp16Scaled if that fits, else kChoiceBf16
 //   4. the BF16 three-term split of both operands (if kChoiceBf16), over the FP16 parts, which are no longer needed then
 //   5. the FP16 product, the FP16 product that undoes the scaling vectors, the BF16 product: one of them runs
 enum AutoChoice { kChoiceFp16 = 0, kChoiceBf16 = 1, kChoiceFp16Scaled = 2, kChoiceUndecided = 3 };
@@ -1068,6 +1073,14 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
     if (!tc.start || !tc.split_done || !tc.product_done) return fail(h, ECGEMM_ERR_HIP, "ecgemm_sgemm: hipEventCreate failed");
     ECGEMM_HIP(h, hipEventRecord(tc.start, h->stream));
   }
+  if (try_scaled) {
+    // the first split also finds every row's largest exponent (on the operands as the caller passed them), so that
+    // the scaled candidate needs no pass over A and B of its own for them
+    st = launch_row_scales(h, rows_a, rows_b, nullptr, 0, kRowScaleClear);
+    if (st != ECGEMM_OK) return st;
+    fp16_a.row_max = scales_a;
+    fp16_b.row_max = scales_b;
+  }
   st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
   if (st != ECGEMM_OK) return st;
   hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, fp16_a.blocks, (double)M, stats_b,
@@ -1078,7 +1091,7 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   if (try_scaled) {
     // the exponents are found on the operands as the caller passed them; the handle's global pre-scaling, a common
     // factor of every row, comes on top in the split and is undone with the product's output scale
-    st = launch_row_scales(h, rows_a, rows_b, choice, kChoiceUndecided);
+    st = launch_row_scales(h, rows_a, rows_b, choice, kChoiceUndecided, kRowScaleFinish);
     if (st != ECGEMM_OK) return st;
     st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, scaled_a, &scaled_b, true);
     if (st != ECGEMM_OK) return st;

@@ -71,10 +71,7 @@ __global__ void __launch_bounds__(256) row_max_exponent_kernel(const RowScaleJob
   const float* src = job.src;
   const int64_t ld = job.ld, rows = job.rows;
   const int64_t k_begin = (int64_t)by * job.slab, k_end = k_begin + job.slab < job.depth ? k_begin + job.slab : job.depth;
-  auto exponent_of = [](float v) {
-    const unsigned bits = __builtin_bit_cast(unsigned, v) & 0x7fffffffu;
-    return (bits != 0 && bits < 0x7f800000u) ? (int)(bits >> 23) - 127 : -0x7fffffff - 1;
-  };
+  auto exponent_of = [](float v) { return finite_exponent(v); };
   int hi = -0x7fffffff - 1;
   if (!job.k_contiguous) {
     const int64_t r = (int64_t)bx * 256 + threadIdx.x;

@@ -96,6 +96,26 @@ struct SplitStats {
 };
 constexpr int kStatsPerBlock = 3;  // doubles a block leaves: err2, norm2, abs1
 
+// Binary exponent of a non-zero finite value, FP32 subnormals counted as -127; INT_MIN for zero, infinities and NaN
+// (the elements that the per-row scaling exponents ignore).
+__device__ __forceinline__ int finite_exponent(float v) {
+  const unsigned bits = __builtin_bit_cast(unsigned, v) & 0x7fffffffu;
+  return (bits != 0 && bits < 0x7f800000u) ? (int)(bits >> 23) - 127 : -0x7fffffff - 1;
+}
+// max of finite_exponent over eight values (before any pre-scaling)
+__device__ __forceinline__ int finite_exponent8(const float (&v)[8]) {
+  int hi = -0x7fffffff - 1;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) hi = max(hi, finite_exponent(v[e]));
+  return hi;
+}
+// Four neighbouring lanes hold values of one row: the row's maximum goes to row_max[r] from the first of them.
+__device__ __forceinline__ void publish_row_exponent_of_4_lanes(int* __restrict__ row_max, int64_t r, bool row_exists, int hi) {
+  hi = max(hi, __shfl_xor(hi, 1, 64));
+  hi = max(hi, __shfl_xor(hi, 2, 64));
+  if ((threadIdx.x & 3) == 0 && row_exists && hi != -0x7fffffff - 1) atomicMax(&row_max[r], hi);
+}
+
 // Writes the eight consecutive-k values `v` of row r (global indices) to their place in `packed`.
 template <int KIND, bool STATS = false>
 __device__ __forceinline__ void store_fragment_row(unsigned short* __restrict__ packed, int64_t k_steps_total,
@@ -151,6 +171,10 @@ struct SplitJob {
   // Automatic mode choice only, else null: the kernel does nothing unless *gate == gate_value
   const int* gate;
   int gate_value;
+  // Automatic mode choice only, else null (STATS kernels): row_max[r] is raised to the largest finite_exponent of row
+  // r's elements as they are in `src` (the caller has set every entry to INT_MIN), so that the scaling exponents of
+  // ecgemm_row_scales need no pass of their own
+  int* row_max;
 };
 
 // Sums the threads' statistics over the block in a fixed order and stores them (all 256 threads call this).
@@ -191,6 +215,8 @@ __device__ __forceinline__ void split_block_k_contiguous_vec(const SplitJob& job
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? src[r * job.ld + k + e] : 0.0f;
   }
+  if constexpr (STATS)
+    if (job.row_max != nullptr) publish_row_exponent_of_4_lanes(job.row_max, r, r < job.rows, finite_exponent8(v));
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] *= prescale;
   store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k, v, stats);
@@ -216,15 +242,21 @@ __device__ __forceinline__ void split_block_k_contiguous_staged(const SplitJob& 
   const int64_t r = r0 + (t >> 2);
   float prescale = job.prescale;
   if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
+  int row_hi = -0x7fffffff - 1;
 #pragma unroll
   for (int half = 0; half < 2; ++half) {
     const int k_local = half * 32 + (t & 3) * 8;
     if (k0 + k_local >= job.k_steps_total * 16) break;  // the padded depth is a multiple of 32, not of 64
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = tile[(t >> 2) * 65 + k_local + e] * prescale;
+    for (int e = 0; e < 8; ++e) v[e] = tile[(t >> 2) * 65 + k_local + e];
+    if constexpr (STATS) row_hi = max(row_hi, finite_exponent8(v));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= prescale;
     store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k0 + k_local, v, stats);
   }
+  if constexpr (STATS)
+    if (job.row_max != nullptr) publish_row_exponent_of_4_lanes(job.row_max, r, r < job.rows, row_hi);
 }
 
 // Source with r contiguous: X(r, k) = src[r + k * ld], any alignment.  One block: 64 rows x 32 k.  Lanes run along r,
@@ -239,7 +271,13 @@ __device__ __forceinline__ void split_block_r_contiguous(const SplitJob& job, un
   if (job.row_log2_scale != nullptr && r < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r]);
   float v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? job.src[r + (k + e) * job.ld] * prescale : 0.0f;
+  for (int e = 0; e < 8; ++e) v[e] = (r < job.rows && k + e < job.depth) ? job.src[r + (k + e) * job.ld] : 0.0f;
+  if constexpr (STATS) {
+    const int hi = finite_exponent8(v);
+    if (job.row_max != nullptr && r < job.rows && hi != -0x7fffffff - 1) atomicMax(&job.row_max[r], hi);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] *= prescale;
   store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r, k, v, stats);
 }
 
@@ -271,13 +309,19 @@ __device__ __forceinline__ void split_block_r_contiguous_wide(const SplitJob& jo
   __syncthreads();
   float prescale = job.prescale;
   if (job.row_log2_scale != nullptr && r0 + t < job.rows) prescale *= row_scale_factor(job.row_log2_scale[r0 + t]);
+  int row_hi = -0x7fffffff - 1;
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = tile[(8 * g + e) * 256 + t] * prescale;
+    for (int e = 0; e < 8; ++e) v[e] = tile[(8 * g + e) * 256 + t];
+    if constexpr (STATS) row_hi = max(row_hi, finite_exponent8(v));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= prescale;
     store_fragment_row<KIND, STATS>(job.packed, job.k_steps_total, r0 + t, k0 + 8 * g, v, stats);
   }
+  if constexpr (STATS)
+    if (job.row_max != nullptr && r0 + t < job.rows && row_hi != -0x7fffffff - 1) atomicMax(&job.row_max[r0 + t], row_hi);
 }
 
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  For a source whose rows are not aligned to
