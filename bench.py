@@ -162,7 +162,7 @@ class Workload:
         self.h = ec.Handle()
         self.h.set_stream(self.stream.cuda_stream)
         self.h.set_shape({"auto": ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2,
-                          "fused": ec.SHAPE_128x128_FUSED}[shape])
+                          "fused": ec.SHAPE_64x64_FUSED}[shape])
         if tile_order is not None:
             self.h.debug_set_tile_order(*tile_order)
         self.ws_bytes = self.h.workspace_size(self.ops[self.transA], self.ops[self.transB], self.M, self.N, self.K, self.mode_id)

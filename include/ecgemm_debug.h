@@ -52,10 +52,12 @@ extern "C" {
  * every later ecgemm_sgemm / ecgemm_product / ecgemm_workspace_size on the handle:
  *   256x128_W4     block tile 256 x 128, 4 waves of 128 x 64, one block per compute unit (every mode);
  *   128x128_X2     block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
- *   128x128_FUSED  the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
+ *   64x64_FUSED    the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
  *                  one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
- *                  packed operands in the workspace (the two modes of the method; ecgemm_sgemm only).  Slower than
- *                  the other two at every size on this hardware; never picked automatically.
+ *                  packed operands or partial sums in the workspace, one launch (the two modes of the method;
+ *                  ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64, 4 waves of
+ *                  32 x 32, the whole depth per block; every block splits the rows of A and columns of B that it
+ *                  uses again, so this is for small products, where launches and latencies decide the time.
  * All shapes form the same products in the same per-element order; results agree bit for bit between shapes unless
  * output tiles are sliced along K differently.  A call whose mode has no kernel of the forced shape returns
  * ECGEMM_ERR_UNSUPPORTED.
@@ -64,7 +66,7 @@ typedef enum {
   ECGEMM_SHAPE_AUTO = 0,
   ECGEMM_SHAPE_256x128_W4 = 1,
   ECGEMM_SHAPE_128x128_X2 = 2,
-  ECGEMM_SHAPE_128x128_FUSED = 3
+  ECGEMM_SHAPE_64x64_FUSED = 3
 } ecgemm_shape_t;
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 

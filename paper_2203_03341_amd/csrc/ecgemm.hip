@@ -48,10 +48,20 @@ namespace {
 
 typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t,
                             const int*, int);
+struct FusedKernels {
+  void (*kernel[3][3])(FusedParams);  // [FusedLayout of A][FusedLayout of B]
+};
+template <int METHOD>
+constexpr FusedKernels fused_kernels_of() {
+  return FusedKernels{{{fused_kernel<METHOD, 0, 0>, fused_kernel<METHOD, 0, 1>, fused_kernel<METHOD, 0, 2>},
+                       {fused_kernel<METHOD, 1, 0>, fused_kernel<METHOD, 1, 1>, fused_kernel<METHOD, 1, 2>},
+                       {fused_kernel<METHOD, 2, 0>, fused_kernel<METHOD, 2, 1>, fused_kernel<METHOD, 2, 2>}}};
+}
+const FusedKernels kFusedFp16 = fused_kernels_of<kMethodFp16Split>(), kFusedBf16 = fused_kernels_of<kMethodBf16Full>();
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
   void (*product_scaled)(ProductParams);  // the instance to prefer for calls with scaling vectors, if the mode has one
-  void (*fused)(FusedParams);      // steps 1 to 5 on the FP32 operands
+  const FusedKernels* fused;       // steps 1 to 5 on the FP32 operands: one kernel per pair of operand layouts
   reduce_fn_t reduce;
   int bm, bn, bk, threads, blocks_per_cu;
   // Deepest K for which the kernel runs as a persistent grid: one block per CU, each walking through several items
@@ -68,16 +78,15 @@ constexpr Shape shape_of(int persistent_max_k) {
   return Shape{product_kernel<Cfg, false>, scaled, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK,
                Cfg::THREADS, Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
-template <int METHOD>
-constexpr Shape fused_shape() {
-  return Shape{nullptr, nullptr, fused_kernel<METHOD>, reduce_tail_kernel<128, 128>, 128, 128, 32, 256, 1, 0};
+inline Shape fused_shape(const FusedKernels* kernels) {  // 64 x 64 tiles, never sliced: no partial sums, no second kernel
+  return Shape{nullptr, nullptr, kernels, nullptr, 64, 64, 32, 256, 1, 0};
 }
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 // [mode][ecgemm_shape_t - 1]
 constexpr int kPersistentMaxK = 4096;
 const Shape kShapes[kMethods][3] = {
-    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape<kMethodFp16Split>()},
-    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape<kMethodBf16Full>()},
+    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape(&kFusedFp16)},
+    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape(&kFusedBf16)},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
     {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
     {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
@@ -102,7 +111,7 @@ static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEM
                   (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_4 == (int)kMethodFp16Outside4 &&
                   (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_16 == (int)kMethodFp16Outside16,
               "mode numbering");
-inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_128x128_FUSED; }
+inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_64x64_FUSED; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
 
 size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
@@ -140,8 +149,7 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
   pl.k_tiles = (int)(pl.Kp / pl.shape->bk);
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   const int64_t slots = (int64_t)kPlanComputeUnits * pl.shape->blocks_per_cu;
-  // (the fused kernel slices either every tile or none)
-  const int64_t tail = pl.shape->fused ? (tiles < slots ? tiles : 0) : tiles % slots;
+  const int64_t tail = pl.shape->fused ? 0 : tiles % slots;  // (the fused kernel never slices)
   if (tail == 0) splits = 1;
   pl.tail_splits = splits;
   pl.tail_tiles = splits > 1 ? (int)tail : 0;
@@ -217,12 +225,8 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   if (best.shape == nullptr) return best;
   const int64_t slots = (int64_t)kPlanComputeUnits * best.shape->blocks_per_cu;
   const int64_t tiles = (int64_t)best.tiles_m * best.tiles_n;
-  const int64_t tail = best.shape->fused ? (tiles < slots ? tiles : 0) : tiles % slots;
+  const int64_t tail = best.shape->fused ? 0 : tiles % slots;
   if (tail == 0) return best;
-  if (best.shape->fused) {  // one slice per compute unit
-    const int64_t splits = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(kPlanComputeUnits / tail, best.Kp / 512), 64));
-    return plan_with(M, N, K, mode, shape, (int)splits);
-  }
   double best_us = estimated_us(best, mode);
   for (int splits = 2; splits <= 64 && splits <= best.Kp / 512 && splits * tail <= 1024; ++splits) {
     const int per_slice = (best.k_tiles + splits - 1) / splits;
@@ -477,7 +481,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
 // Steps 1 to 5 in one kernel, on the caller's FP32 operands (small products).
 ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                              int64_t K, float alpha, const float* A, int64_t lda, const float* B, int64_t ldb, float beta,
-                             float* C, int64_t ldc, float* partials, const int* row_log2_scale, const int* col_log2_scale) {
+                             float* C, int64_t ldc, const int* row_log2_scale, const int* col_log2_scale) {
   FusedParams fp;
   fp.row_log2_scale = row_log2_scale;
   fp.col_log2_scale = col_log2_scale;
@@ -485,35 +489,27 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   fp.B = B;
   fp.lda = lda;
   fp.ldb = ldb;
-  fp.a_k_contiguous = transA == ECGEMM_OP_T;
-  fp.b_k_contiguous = transB == ECGEMM_OP_N;
-  fp.a_vec = fp.a_k_contiguous && lda % 4 == 0 && (uintptr_t)A % 16 == 0;
-  fp.b_vec = fp.b_k_contiguous && ldb % 4 == 0 && (uintptr_t)B % 16 == 0;
+  // op(A)(m, k) = A[k + m lda] if transA == T; op(B)(k, n) = B[k + n ldb] if transB == N
+  auto layout_of = [K](bool k_contiguous, const float* base, int64_t ld) {
+    return !k_contiguous ? kFusedRows : (ld % 4 == 0 && (uintptr_t)base % 16 == 0 && K % 4 == 0) ? kFusedDepthVec : kFusedDepth;
+  };
+  const int layout_a = layout_of(transA == ECGEMM_OP_T, A, lda), layout_b = layout_of(transB == ECGEMM_OP_N, B, ldb);
   fp.prescale_a = std::ldexp(1.0f, h->log2_scale_a);
   fp.prescale_b = std::ldexp(1.0f, h->log2_scale_b);
   fp.M = M;
   fp.N = N;
   fp.K = K;
   fp.ldc = ldc;
-  fp.stages = (int)(pl.Kp / 32);
   fp.tiles_m = pl.tiles_m;
   fp.tiles_n = pl.tiles_n;
-  fp.splits = pl.tail_splits;
   fp.alpha = alpha;
   fp.beta = beta;
   fp.out_scale = std::ldexp(1.0f, -(h->log2_scale_a + h->log2_scale_b));
   fp.C = C;
-  fp.partials = partials;
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   void* args[] = {&fp};
-  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused), dim3((unsigned)(tiles * pl.tail_splits)), dim3(256),
-                                args, 0, h->stream));
-  if (pl.tail_splits > 1) {
-    const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(128 * 128 / 1024));
-    hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles, 0,
-                       pl.tiles_m, pl.tiles_n, 4, 1, M, N, alpha, beta, C, ldc, (const int*)nullptr, 0);
-    ECGEMM_HIP(h, hipGetLastError());
-  }
+  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused->kernel[layout_a][layout_b]), dim3((unsigned)tiles),
+                                dim3(256), args, 0, h->stream));
   return ECGEMM_OK;
 }
 
@@ -1195,8 +1191,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
 
   if (pl.shape->fused) {
     if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
-    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, partials, row_log2_scale_a,
-                      col_log2_scale_b);
+    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, row_log2_scale_a, col_log2_scale_b);
   } else {
     st = launch_split(h, mode, job_a, &job_b);
     if (st != ECGEMM_OK) return st;

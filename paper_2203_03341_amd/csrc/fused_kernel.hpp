@@ -1,216 +1,333 @@
 // The paper's own arrangement of the method for one block (section "Incorporating our method into CUTLASS", last
 // paragraph): the block reads FP32 tiles of A and B, forms the low-precision parts in registers (Eqs. corr-1-1024 ..
 // corr-4-1024, or the three BF16 terms) and multiplies them right away; no split pass over the operands, no packed
-// copies in HBM, one launch instead of three.  Every block that touches a tile of A splits it again (N / 128 times
-// per element), so this only pays where launches, not arithmetic, decide the time: small products.
+// copies in HBM, no partial sums: one launch.  Every block that touches a tile of A splits it again (N / 64 times per
+// element), so this pays where launches and latencies, not arithmetic, decide the time: small products.
 //
-// One block: 128 x 128 of C, 4 waves of 64 x 64 (the X2 geometry of product_kernel.hpp, same fragment layout in
-// LDS, same term order, same accumulator discipline, so an element is summed in the same order as there).
-// Per 32-deep stage: waves 0 and 1 fetch and split the A tile, waves 2 and 3 the B tile; thread u of a pair of
-// waves owns row u of its tile, holds the row's 32 FP32 values of the next stage in registers while the current
-// stage is multiplied, then writes their parts to the other LDS buffer in fragment order.
+// One block: 64 x 64 of C, 4 waves of 32 x 32 (one v_mfma_f32_32x32x16 accumulator pair per wave), the whole depth
+// of the product; same fragment layout in LDS, same term order and same accumulator discipline as product_kernel.hpp,
+// so an element is summed in the same order as in an unsliced tile there.  The small tile is what makes a small
+// product many blocks: 256^3 is 16 of them, 512^3 64.
+//
+// Depth is walked in chunks of 64.  All 256 threads fetch the chunk's 64 x 64 values of op(A) and of op(B), 16 + 16
+// values per thread, with the lanes of a wave along whichever index is contiguous in memory (FusedLayout); the values
+// of the next kFusedRing chunks are in flight in registers while the current one is split, written to LDS in fragment
+// order (two buffers, one barrier per chunk) and multiplied.  The split is what bounds the loop (a chunk is 8192
+// elements per block against 12 or 24 matrix instructions per wave), so it takes a short form (FastSplit, 5 to 7
+// vector instructions per element) whenever every value a wave holds is ordinary, and Splitter, which saturates and
+// handles infinities and NaN, otherwise; both give the same bits on the values the short form accepts.
 #pragma once
 #include "product_kernel.hpp"
 
 namespace ecgemm {
 
+// How the 16 values per thread and chunk are laid over one operand's 64 rows x 64 k (X(r, k): op(A)(m, k) or
+// op(B)(k, n) with r = n):
+//   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: lane = row, wave w holds k = 16 w .. 16 w + 15 of it
+//   kFusedDepth     k contiguous, X(r, k) = src[k + r ld]: lane = k, wave w holds rows 16 w .. 16 w + 15 at that k
+//   kFusedDepthVec  k contiguous, base and ld multiples of 16 bytes, K a multiple of 4: lane l holds the four values
+//                   k = 4 (l % 16) .. + 3 of rows 16 w + 4 j + l / 16, j = 0 .. 3, one 16-byte load each
+enum FusedLayout { kFusedRows = 0, kFusedDepth = 1, kFusedDepthVec = 2 };
+constexpr int kFusedRing = 2;  // chunks in flight in registers (unrolled: a register ring is indexed statically)
+
 struct FusedParams {
   const float* A;  // device, column-major, as passed to ecgemm_sgemm
   const float* B;
   int64_t lda, ldb;
-  int a_k_contiguous, b_k_contiguous;  // op(A)(m, k) = A[k + m lda] (transA == T);  op(B)(k, n) = B[k + n ldb] (transB == N)
-  int a_vec, b_vec;                    // k contiguous and 16-byte aligned rows: float4 loads
-  float prescale_a, prescale_b;        // powers of two applied before the split (1 by default)
+  float prescale_a, prescale_b;  // powers of two applied before the split (1 by default)
   int64_t M, N, K, ldc;
-  int stages;                          // ceil(K / 32)
-  int tiles_m, tiles_n, splits;        // splits > 1: every tile is cut into slices along K, raw sums go to partials
+  int tiles_m, tiles_n;
   float alpha, beta, out_scale;
   // per-row / per-column pre-scaling as in ProductParams (both null, or both set)
-  const int* row_log2_scale;           // device, M entries
-  const int* col_log2_scale;           // device, N entries
+  const int* row_log2_scale;  // device, M entries
+  const int* col_log2_scale;  // device, N entries
   float* C;
-  float* partials;                     // [splits][tiles][128][128]
 };
 
-template <int METHOD>
+// The split for values that need no care, two at a time (the two 16-bit results of a part share a register: out[q]
+// holds part q of v0 in its low half and of v1 in its high half).  It has none of Splitter's clamps and masks; on a
+// value whose high part comes out finite both give the same bits: the high part is then at most the largest finite
+// number of the format whether or not the value was clamped to it first, the residuals are at most half a unit of
+// its last place, far inside the range of the low parts, and nothing is masked.  A value that Splitter treats
+// differently (beyond the format's range, where it saturates; infinite; NaN) shows as a high part that is infinite or
+// NaN, which high_parts_finite() finds on the packed registers.
+typedef float fused_float2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 fused_half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 fused_bf16x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short fused_ushort2_t __attribute__((ext_vector_type(2)));
+template <int KIND>
+struct FastSplit {
+  static constexpr int kParts = parts_of_split(KIND);
+  __device__ static __forceinline__ void split2(float v0, float v1, unsigned (&out)[kParts]) {
+    if constexpr (!split_is_bf16(KIND)) {
+      const fused_half2_t hi = __builtin_convertvector(fused_float2_t{v0, v1}, fused_half2_t);
+      out[0] = __builtin_bit_cast(unsigned, hi);
+      if constexpr (kParts == 2) {
+        const float scale = KIND == kSplitFp16Scaled ? 2048.0f : 1.0f;
+        const fused_float2_t residual = {(v0 - (float)hi[0]) * scale, (v1 - (float)hi[1]) * scale};  // exact
+        out[1] = __builtin_bit_cast(unsigned, __builtin_convertvector(residual, fused_half2_t));
+      }
+    } else {
+      const fused_bf16x2_t b0 = __builtin_convertvector(fused_float2_t{v0, v1}, fused_bf16x2_t);
+      out[0] = __builtin_bit_cast(unsigned, b0);
+      if constexpr (kParts == 3) {
+        const fused_float2_t r1 = {v0 - (float)b0[0], v1 - (float)b0[1]};
+        const fused_bf16x2_t b1 = __builtin_convertvector(r1, fused_bf16x2_t);
+        const fused_float2_t r2 = {r1[0] - (float)b1[0], r1[1] - (float)b1[1]};
+        out[1] = __builtin_bit_cast(unsigned, b1);
+        out[2] = __builtin_bit_cast(unsigned, __builtin_convertvector(r2, fused_bf16x2_t));
+      }
+    }
+  }
+  // true if none of the 16 high parts in `words[..][0]` is infinite or NaN
+  __device__ static __forceinline__ bool high_parts_finite(const unsigned (&words)[8][kParts]) {
+    const unsigned magnitude = 0x7fff7fffu;
+    fused_ushort2_t most = {0, 0};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      most = __builtin_elementwise_max(most, __builtin_bit_cast(fused_ushort2_t, words[e][0] & magnitude));
+    const unsigned short exponent_all_ones = split_is_bf16(KIND) ? 0x7f80 : 0x7c00;
+    return most[0] < exponent_all_ones && most[1] < exponent_all_ones;
+  }
+};
+
+// One operand of the block: where this thread's 16 values per chunk come from and where their parts go.
+template <int KIND, int LAYOUT>
+struct FusedOperand {
+  static constexpr int NP = parts_of_split(KIND);
+  static constexpr int ROWS = LAYOUT == kFusedRows ? 1 : LAYOUT == kFusedDepth ? 16 : 4;  // rows this thread holds values of
+  static constexpr int PER_ROW = 16 / ROWS;                                                // consecutive k per row
+  static constexpr int REGION_BYTES = 2 * 4 * NP * 1024;  // a chunk of one operand in LDS: [row block][k step][part] x 1 KiB
+
+  // Addresses are a part that is the same for the whole wave plus a small per-lane offset wherever the layout allows
+  // it, which leaves the address arithmetic to the scalar unit.  A row beyond the matrix reads the last row instead
+  // (its values end up in rows or columns of the tile that are never stored).
+  const float* tile;           // &X(first row of the tile, 0)
+  const float* row_ptr[ROWS];  // kFusedDepth: &X(row, 0) for the wave's 16 rows; kFusedDepthVec: for the lane's 4 rows
+  unsigned lane_offset;        // kFusedRows: the lane's row within the tile; kFusedDepth: the lane's k within the chunk
+  float factor[ROWS];          // the handle's pre-scaling times the row's own
+  int64_t ld, K;
+  int k_here;                  // k within the chunk of the thread's first value
+  int lds_offset;              // byte offset within the operand's region of the thread's first value, part 0
+
+  __device__ __forceinline__ void init(const float* src, int64_t ld_, int64_t rows, int64_t K_, int64_t tile_row0, float prescale,
+                                       const int* log2_scale, int lane, int wave) {
+    ld = ld_, K = K_;
+    const int rows_here = (int)(rows - tile_row0 < 64 ? rows - tile_row0 : 64);  // >= 1
+    tile = LAYOUT == kFusedRows ? src + tile_row0 : src + tile_row0 * ld;
+    int first_row;  // within the tile
+    if constexpr (LAYOUT == kFusedRows) {
+      first_row = lane, k_here = 16 * wave;
+      lane_offset = (unsigned)(lane < rows_here ? lane : rows_here - 1);
+    } else if constexpr (LAYOUT == kFusedDepth) {
+      first_row = 16 * wave, k_here = lane;
+      lane_offset = (unsigned)lane;
+    } else {
+      first_row = 16 * wave + (lane >> 4), k_here = 4 * (lane & 15);
+      lane_offset = 0;
+    }
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+      const int row = first_row + (LAYOUT == kFusedDepthVec ? 4 * j : j);
+      const int row_clamped = row < rows_here ? row : rows_here - 1;
+      row_ptr[j] = tile + (LAYOUT == kFusedRows ? (int64_t)row_clamped : row_clamped * ld);
+      factor[j] = prescale;
+      if (log2_scale != nullptr) factor[j] *= row_scale_factor(log2_scale[tile_row0 + row_clamped]);
+    }
+    // chunk (row / 32, k / 16, part), lane (k % 16 / 8) * 32 + row % 32, element k % 8
+    lds_offset = ((first_row >> 5) * 4 + (k_here >> 4)) * NP * 1024 + (((k_here >> 3) & 1) * 32 + (first_row & 31)) * 16 + (k_here & 7) * 2;
+  }
+
+  // Requests the values of chunk c (which exists).  Every address is valid: in the last chunk, k beyond the depth is
+  // clamped to the last k (and replaced by zero in deposit()).  No load sits under a condition and both branches
+  // issue the same number of loads, so the number in flight is the same on every path: the waits that the compiler
+  // places count them.
+  __device__ __forceinline__ void fetch(float (&x)[16], int c) const {
+    const int64_t chunk_k = (int64_t)c * 64;
+    if (chunk_k + 64 <= K) {  // block-uniform
+      if constexpr (LAYOUT == kFusedRows) {
+        const float* first = tile + (chunk_k + k_here) * ld;  // wave-uniform
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = first[i * ld + lane_offset];
+      } else if constexpr (LAYOUT == kFusedDepth) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) x[j] = (row_ptr[j] + chunk_k)[lane_offset];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 v = *reinterpret_cast<const float4*>(row_ptr[j] + chunk_k + k_here);
+          x[4 * j] = v.x, x[4 * j + 1] = v.y, x[4 * j + 2] = v.z, x[4 * j + 3] = v.w;
+        }
+      }
+    } else {
+      const int64_t k0 = chunk_k + k_here;
+      if constexpr (LAYOUT == kFusedDepthVec) {
+        // K is a multiple of 4 here (the host's condition for this layout): four values that start below K end below it
+        const int64_t k = k0 < K ? k0 : K - 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float4 v = *reinterpret_cast<const float4*>(row_ptr[j] + k);
+          x[4 * j] = v.x, x[4 * j + 1] = v.y, x[4 * j + 2] = v.z, x[4 * j + 3] = v.w;
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int64_t k = k0 + e % PER_ROW < K ? k0 + e % PER_ROW : K - 1;
+          x[e] = LAYOUT == kFusedRows ? row_ptr[0][k * ld] : row_ptr[e][k];
+        }
+      }
+    }
+  }
+
+  // Splits the values of chunk c and writes the parts to `region` where the fragment reads expect them.
+  __device__ __forceinline__ void deposit(const float (&x)[16], int c, char* region) const {
+    float v[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) v[e] = x[e] * factor[e / PER_ROW];
+    unsigned words[8][NP];  // part q of values 2 e and 2 e + 1
+    const bool whole = (int64_t)c * 64 + 64 <= K;  // block-uniform
+    bool done = false;
+    if (whole) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) FastSplit<KIND>::split2(v[2 * e], v[2 * e + 1], words[e]);
+      done = __builtin_amdgcn_ballot_w64(!FastSplit<KIND>::high_parts_finite(words)) == 0;  // wave-uniform
+    }
+    if (!done) {
+      const int64_t k0 = (int64_t)c * 64 + k_here;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        unsigned short even[NP], odd[NP];
+        Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? v[2 * e] : 0.0f, even);
+        Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? v[2 * e + 1] : 0.0f, odd);
+#pragma unroll
+        for (int q = 0; q < NP; ++q) words[e][q] = (unsigned)even[q] | ((unsigned)odd[q] << 16);
+      }
+    }
+    char* base = region + lds_offset;
+    typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
+    typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+      if constexpr (LAYOUT == kFusedRows) {  // 16 consecutive k of one row: the two halves of a k step
+        *reinterpret_cast<uint4_t*>(base + q * 1024) = uint4_t{words[0][q], words[1][q], words[2][q], words[3][q]};
+        *reinterpret_cast<uint4_t*>(base + q * 1024 + 512) = uint4_t{words[4][q], words[5][q], words[6][q], words[7][q]};
+      } else if constexpr (LAYOUT == kFusedDepth) {  // one k of 16 consecutive rows
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e) * 16) = (unsigned short)words[e][q];
+          *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e + 1) * 16) = (unsigned short)(words[e][q] >> 16);
+        }
+      } else {  // four consecutive k of rows 4 apart
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          *reinterpret_cast<uint2_t*>(base + q * 1024 + j * 64) = uint2_t{words[2 * j][q], words[2 * j + 1][q]};
+      }
+    }
+  }
+};
+
+template <int METHOD, int LAYOUT_A, int LAYOUT_B>
 __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   constexpr int KIND = split_kind_of(METHOD);
   constexpr bool BF16 = split_is_bf16(KIND);
   constexpr int NP = parts_of_split(KIND), PRODUCTS = products_of(METHOD);
-  constexpr int BM = 128, BN = 128, TM = 2, TN = 2, K_STEPS = 2;
-  constexpr int ROW_CHUNKS = K_STEPS * NP;                 // 1 KiB chunks per 32 rows per stage
-  constexpr int A_CHUNKS = (BM / 32) * ROW_CHUNKS;
-  constexpr int STAGE_BYTES = (A_CHUNKS + (BN / 32) * ROW_CHUNKS) * 1024;
+  constexpr int BM = 64, BN = 64, K_STEPS = 4;
+  typedef FusedOperand<KIND, LAYOUT_A> OperandA;
+  typedef FusedOperand<KIND, LAYOUT_B> OperandB;
+  constexpr int REGION_BYTES = OperandA::REGION_BYTES, STAGE_BYTES = 2 * REGION_BYTES;
   typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wave_m = wave % 2, wave_n = wave / 2;
-
-  const int tiles = p.tiles_m * p.tiles_n;
-  const int split = blockIdx.x / tiles, pid = blockIdx.x % tiles;
   int tile_m, tile_n;
-  tile_coordinates(pid, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
-  const int stages_per_split = (p.stages + p.splits - 1) / p.splits;
-  const int stage_begin = split * stages_per_split;
-  const int stage_count = max(0, min(p.stages, stage_begin + stages_per_split) - stage_begin);
+  tile_coordinates((int)blockIdx.x, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
 
-  // ---- this thread's row of its operand tile
-  const bool for_b = wave >= 2;  // wave-uniform
-  const int u = t & 127;
-  const float* src = for_b ? p.B : p.A;
-  const int64_t ld = for_b ? p.ldb : p.lda;
-  const bool k_contiguous = for_b ? p.b_k_contiguous : p.a_k_contiguous;
-  const bool vec = for_b ? p.b_vec : p.a_vec;
-  const int64_t row = (for_b ? (int64_t)tile_n * BN : (int64_t)tile_m * BM) + u;
-  const bool row_ok = row < (for_b ? p.N : p.M);
-  float prescale = for_b ? p.prescale_b : p.prescale_a;
-  if (p.row_log2_scale != nullptr && row_ok) prescale *= row_scale_factor((for_b ? p.col_log2_scale : p.row_log2_scale)[row]);
-  // Requests the 32 values X(row, k0 .. k0 + 31) of a stage.  Every load is unconditional on a clamped, valid address
-  // (a load under a per-lane condition would make the compiler wait for it at the end of its branch, one load at a
-  // time); what lies beyond the matrix is replaced by zeros in deposit(), after the multiplications that the loads
-  // are meant to overlap.
-  const int64_t row_clamped = row_ok ? row : (for_b ? p.N : p.M) - 1;
-  auto fetch = [&](float (&x)[32], int stage) {
-    const int64_t k0 = (int64_t)stage * 32;
-    if (k_contiguous) {
-      const float* base = src + row_clamped * ld;
-      if (vec && k0 + 32 <= p.K) {  // block-uniform
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-          const float4 v = *reinterpret_cast<const float4*>(base + k0 + 4 * g);
-          x[4 * g] = v.x, x[4 * g + 1] = v.y, x[4 * g + 2] = v.z, x[4 * g + 3] = v.w;
-        }
-      } else {
-#pragma unroll
-        for (int k = 0; k < 32; ++k) x[k] = base[min(k0 + k, p.K - 1)];
-      }
-    } else {
-      const float* base = src + row_clamped;
-#pragma unroll
-      for (int k = 0; k < 32; ++k) x[k] = base[min(k0 + k, p.K - 1) * ld];
-    }
-  };
-  // Splits the held values and writes the parts where the fragment reads below expect them: chunk
-  // (row_block, k_step, part), lane (k % 16 / 8) * 32 + row % 32, 16 bytes per lane.
-  char* my_chunks = lds + (for_b ? A_CHUNKS * 1024 : 0) + (u >> 5) * ROW_CHUNKS * 1024 + (u & 31) * 16;
-  auto deposit = [&](const float (&x)[32], int stage, int buf) {
-    char* base = my_chunks + buf * STAGE_BYTES;
-    const int64_t k0 = (int64_t)stage * 32;
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      ushort8_t parts[NP];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        unsigned short s[NP];
-        Splitter<KIND>::split((row_ok && k0 + 8 * g + e < p.K) ? x[8 * g + e] * prescale : 0.0f, s);
-#pragma unroll
-        for (int q = 0; q < NP; ++q) parts[q][e] = s[q];
-      }
-#pragma unroll
-      for (int q = 0; q < NP; ++q)
-        *reinterpret_cast<ushort8_t*>(base + ((g >> 1) * NP + q) * 1024 + (g & 1) * 512) = parts[q];
-    }
-  };
+  OperandA a;
+  OperandB b;
+  a.init(p.A, p.lda, p.M, p.K, (int64_t)tile_m * BM, p.prescale_a, p.row_log2_scale, lane, wave);
+  b.init(p.B, p.ldb, p.N, p.K, (int64_t)tile_n * BN, p.prescale_b, p.col_log2_scale, lane, wave);
+  const int chunks = (int)((p.K + 63) / 64);
 
-  // ---- fragments and accumulators
-  float16_t acc_main[TM][TN], acc_corr[TM][TN];
+  float16_t acc_main, acc_corr;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        acc_main[i][j][v] = 0.0f;
-        acc_corr[i][j][v] = 0.0f;
-      }
-  const int a_frag_off = wave_m * TM * ROW_CHUNKS * 1024 + lane * 16;
-  const int b_frag_off = A_CHUNKS * 1024 + wave_n * TN * ROW_CHUNKS * 1024 + lane * 16;
-  auto multiply_stage = [&](int buf) {
+  for (int v = 0; v < 16; ++v) acc_main[v] = 0.0f, acc_corr[v] = 0.0f;
+  const int a_frag_off = wave_m * K_STEPS * NP * 1024 + lane * 16;
+  const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024 + lane * 16;
+  auto multiply = [&](int buf) {
     const char* stage = lds + buf * STAGE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < K_STEPS; ++ks) {
-      frag_t fa[TM][NP], fb[TN][NP];
+      frag_t fa[NP], fb[NP];
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int q = 0; q < NP; ++q)
-          fa[i][q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + ((i * K_STEPS + ks) * NP + q) * 1024);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int q = 0; q < NP; ++q)
-          fb[j][q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + ((j * K_STEPS + ks) * NP + q) * 1024);
-      static_for<PRODUCTS * TM * TN>([&](auto m_c) {
-        constexpr int m = decltype(m_c)::value;
-        constexpr ProductTerm term = product_term(METHOD, m / (TM * TN));
-        constexpr int i = (m % (TM * TN)) / TN, j = m % TN;
+      for (int q = 0; q < NP; ++q) {
+        fa[q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + (ks * NP + q) * 1024);
+        fb[q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + (ks * NP + q) * 1024);
+      }
+      static_for<PRODUCTS>([&](auto m_c) {
+        constexpr ProductTerm term = product_term(METHOD, decltype(m_c)::value);
         if constexpr (term.correction)
-          acc_corr[i][j] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[j][term.qb], fa[i][term.qa], acc_corr[i][j]);
+          acc_corr = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_corr);
         else
-          acc_main[i][j] = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[j][term.qb], fa[i][term.qa], acc_main[i][j]);
+          acc_main = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_main);
       });
     }
   };
 
-  // ---- main loop: stage s is multiplied out of LDS buffer s % 2 while the values of stage s + 1 travel to registers
-  float x[32];
-  if (stage_count > 0) {
-    fetch(x, stage_begin);
-    deposit(x, stage_begin, 0);
-    __syncthreads();
-    for (int s = 0; s < stage_count; ++s) {
-      const bool more = s + 1 < stage_count;
-      if (more) fetch(x, stage_begin + s + 1);
-      multiply_stage(s & 1);
-      if (more) deposit(x, stage_begin + s + 1, (s + 1) & 1);
+  // ---- main loop: chunk c is split into LDS buffer c % 2 and multiplied while chunks c + 1 .. c + kFusedRing travel
+  static_assert(kFusedRing % 2 == 0, "a ring slot always meets the same LDS buffer");
+  float xa[kFusedRing][16], xb[kFusedRing][16];
+  // (a chunk beyond the last is requested again as the last one and never used: in the loop every fetch is
+  // unconditional; the scheduling barriers keep the requests of one ring slot together and the slots in order, which
+  // is what lets the wait in front of a slot's first use leave the younger slots' loads in flight)
+  const int last = chunks - 1;
+  static_for<kFusedRing>([&](auto r_c) {
+    constexpr int r = decltype(r_c)::value;
+    a.fetch(xa[r], r < last ? r : last), b.fetch(xb[r], r < last ? r : last);
+    __builtin_amdgcn_sched_barrier(0);
+  });
+  int c0 = 0;
+  for (; c0 + kFusedRing <= chunks; c0 += kFusedRing) {
+    static_for<kFusedRing>([&](auto r_c) {
+      constexpr int r = decltype(r_c)::value;
+      const int c = c0 + r, ahead = c + kFusedRing < last ? c + kFusedRing : last;
+      char* stage = lds + (r & 1) * STAGE_BYTES;
+      a.deposit(xa[r], c, stage);
+      b.deposit(xb[r], c, stage + REGION_BYTES);
+      __builtin_amdgcn_sched_barrier(0);
+      a.fetch(xa[r], ahead), b.fetch(xb[r], ahead);
       __syncthreads();
-    }
+      multiply(r & 1);
+    });
   }
+  static_for<kFusedRing - 1>([&](auto r_c) {  // the chunks left over: their values are on their way or here
+    constexpr int r = decltype(r_c)::value;
+    if (c0 + r < chunks) {  // block-uniform
+      char* stage = lds + (r & 1) * STAGE_BYTES;
+      a.deposit(xa[r], c0 + r, stage);
+      b.deposit(xb[r], c0 + r, stage + REGION_BYTES);
+      __syncthreads();
+      multiply(r & 1);
+    }
+  });
 
-  // ---- epilogue, as in product_kernel: lane l holds row m_base + 32 i and columns n_base + 32 j + 8 (v / 4) + v % 4
+  // ---- epilogue, as in product_kernel: lane l holds row m_base and columns n_base + 8 (v / 4) + v % 4
   const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
-  const int64_t m_base = (int64_t)tile_m * BM + wave_m * 64 + (lane & 31);
-  const int64_t n_base = (int64_t)tile_n * BN + wave_n * 64 + 4 * (lane >> 5);
-  auto for_each_output = [&](auto&& store) {
+  const int64_t m = (int64_t)tile_m * BM + wave_m * 32 + (lane & 31);
+  const int64_t n_base = (int64_t)tile_n * BN + wave_n * 32 + 4 * (lane >> 5);
+  if (m >= p.M) return;
+  const int row_exponent = p.row_log2_scale != nullptr ? p.row_log2_scale[m] : 0;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          store(m_base + i * 32, n_base + j * 32 + 8 * (v / 4) + (v % 4),
-                (acc_main[i][j][v] + acc_corr[i][j][v] * corr_scale) * p.out_scale);
-  };
-  if (p.row_log2_scale != nullptr) {
-    // rows of op(A) and columns of op(B) were scaled one by one before the split: undo that per element
-    float* out = p.splits > 1 ? p.partials + ((int64_t)split * tiles + pid) * (BM * BN) : nullptr;
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    for_each_output([&](int64_t m, int64_t n, float c) {
-      if (m < p.M && n < p.N) {
-        c = unscale(c, p.row_log2_scale[m], p.col_log2_scale[n]);
-        if (out) {
-          out[(n - n0) * BM + (m - m0)] = c;
-        } else {
-          float* dst = p.C + m + n * p.ldc;
-          store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
-        }
-      } else if (out) {
-        out[(n - n0) * BM + (m - m0)] = 0.0f;
-      }
-    });
-  } else if (p.splits > 1) {
-    float* out = p.partials + ((int64_t)split * tiles + pid) * (BM * BN);
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    for_each_output([&](int64_t m, int64_t n, float c) { out[(n - n0) * BM + (m - m0)] = c; });
-  } else {
-    for_each_output([&](int64_t m, int64_t n, float c) {
-      if (m < p.M && n < p.N) {
-        float* dst = p.C + m + n * p.ldc;
-        store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
-      }
-    });
+  for (int v = 0; v < 16; ++v) {
+    const int64_t n = n_base + 8 * (v / 4) + (v % 4);
+    if (n < p.N) {
+      float c = (acc_main[v] + acc_corr[v] * corr_scale) * p.out_scale;
+      // rows of op(A) and columns of op(B) were scaled one by one before the split: undo that per element
+      if (p.row_log2_scale != nullptr) c = unscale(c, row_exponent, p.col_log2_scale[n]);
+      float* dst = p.C + m + n * p.ldc;
+      store_result(dst, (p.beta == 0.0f) ? p.alpha * c : scaled_sum(p.alpha, c, p.beta, *dst));
+    }
   }
 }
 

@@ -239,7 +239,7 @@ def test_workspace_size_caller_workspace_and_refusals():
     with pytest.raises(ec.EcgemmError) as err:
         h.sgemm_scaled(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO, scales_a, scales_b)
     assert err.value.status == ec.ERR_UNSUPPORTED
-    h.set_shape(ec.SHAPE_128x128_FUSED)
+    h.set_shape(ec.SHAPE_64x64_FUSED)
     with pytest.raises(ec.EcgemmError) as err:
         h.sgemm(ec.OP_N, ec.OP_N, M, N, K, 1.0, dA, M, dB, K, 0.0, dC, M, ec.MODE_AUTO)
     assert err.value.status == ec.ERR_UNSUPPORTED

@@ -45,7 +45,7 @@ def _model(mode, opA, opB):
 
 def _shapes():
     import paper_2203_03341_amd as ec
-    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2, "fused": ec.SHAPE_128x128_FUSED}
+    return {None: ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2, "fused": ec.SHAPE_64x64_FUSED}
 
 
 def _gpu_sgemm(transA, transB, M, N, K, alpha, A, B, beta, C, mode, ldc=None, handle=None, shape=None):
@@ -499,6 +499,38 @@ def test_shapes_agree_bit_for_bit_when_nothing_is_sliced(mode):
         assert np.array_equal(outs[0].view(np.uint32), other.view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+@pytest.mark.parametrize("transA,transB,pad", [("N", "N", 0), ("T", "T", 0), ("N", "T", 1), ("T", "N", 3), ("T", "N", 0)])
+def test_one_launch_shape_splits_like_the_split_kernels(mode, transA, transB, pad):
+    """The one-launch shape splits in its own registers, with a short form for ordinary values and the split kernels'
+    own arithmetic for the rest (values beyond the FP16 or BF16 range, which saturate; infinities; NaN), decided per
+    wave and chunk of 64 k.  Whatever the mix, every bit of C equals what the split-first shape gives: operands with
+    such values sprinkled over some rows and depths, every operand layout (transposes, aligned and unaligned leading
+    dimensions), a depth that ends inside a chunk."""
+    M, N, K = 150, 200, 300
+    A, B = _inputs(M, N, K, transA, transB, "urand", 31, pad)
+    opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)   # views: writes go to A and B
+    awkward = np.array([70000.0, -65520.0, 65519.0, 3.39e38, -3.4e38, np.inf, -np.inf, 1e-41, 65504.0, 1e30], dtype=np.float32)
+    rng = np.random.default_rng(5)
+    for op, rows, cols in ((opA, M, K), (opB, K, N)):
+        for v in awkward:
+            for _ in range(3):
+                op[rng.integers(rows), rng.integers(cols)] = v
+    opA[7, 130] = np.nan
+    outs = [_gpu_sgemm(transA, transB, M, N, K, 1.0, A, B, 0.0, None, mode, shape=sh)[:M, :N] for sh in ("x2", "fused")]
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+    assert np.all(np.isnan(outs[1][7, :])) and np.isfinite(outs[1]).sum() > M * N // 2
+    # and with the handle's power-of-two pre-scaling, which is applied before the split
+    import paper_2203_03341_amd as ec
+    outs = []
+    for sh in ("x2", "fused"):
+        h = ec.Handle()
+        h.set_scaling(3, -2)
+        outs.append(_gpu_sgemm(transA, transB, M, N, K, 1.0, A, B, 0.0, None, mode, handle=h, shape=sh)[:M, :N])
+        h.destroy()
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
 def test_the_tile_order_knob_moves_tiles_between_xcds_and_changes_no_bit():
     """ecgemm_debug_set_tile_order (the experiment knob behind the block-order profiles): hardware round-robin instead
     of contiguous runs per XCD, plain column-major order, forced column bands.  Where no tile is sliced along K the
@@ -542,7 +574,7 @@ def test_a_shape_the_mode_has_no_kernel_for_is_refused():
     h.set_shape(ec.SHAPE_AUTO)
     h.sgemm(ec.OP_N, ec.OP_N, 64, 64, 64, 1.0, dA, 64, dB, 64, 0.0, dC, 64, ec.MODE_FP16_MARKIDIS)
     # the fused shape has no use for operands split beforehand
-    h.set_shape(ec.SHAPE_128x128_FUSED)
+    h.set_shape(ec.SHAPE_64x64_FUSED)
     packed = empty_colmajor(ec.split_size(64, 64, ec.MODE_FP16_SPLIT) // 4, 1, fill=0.0)
     with pytest.raises(ec.EcgemmError) as err:
         h.product(64, 64, 64, 1.0, packed, packed, 0.0, dC, 64, ec.MODE_FP16_SPLIT)
@@ -709,7 +741,7 @@ def test_prescaling_brings_small_inputs_into_the_fp16_window():
     h.set_scaling(shift, shift)
     scaled = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
     assert gemm.relative_residual(c64, scaled) <= RATIO * r_cpu
-    h.set_shape(ec.SHAPE_128x128_FUSED)                            # the one-kernel path scales in its own split
+    h.set_shape(ec.SHAPE_64x64_FUSED)                            # the one-kernel path scales in its own split
     fused = _gpu_sgemm("N", "N", M, N, K, 1.5, A, B, 0.5, C, "fp16", handle=h)[:M, :N]
     assert np.array_equal(fused.view(np.uint32), scaled.view(np.uint32))
     h.set_shape(ec.SHAPE_AUTO)
@@ -785,13 +817,13 @@ def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
     assert gemm.relative_residual(c64, scaled) <= RATIO * gemm.relative_residual(c64, c32)
     # the one-kernel shape scales in its own split: held to the same bar, and where nothing is sliced along K the
     # same bits as the split-first shapes
-    h.set_shape(ec.SHAPE_128x128_FUSED)
+    h.set_shape(ec.SHAPE_64x64_FUSED)
     fused = run(True)
     r_fused = row_residuals(fused)
     assert np.all(np.isfinite(fused)) and np.all(r_fused[live] <= 2.0 * r_cpu[live] + 1e-12)
     shallow = 96                                                      # too shallow for any shape to slice
     outs = []
-    for shape in (ec.SHAPE_128x128_FUSED, ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4):
+    for shape in (ec.SHAPE_64x64_FUSED, ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4):
         h.set_shape(shape)
         assert h.plan_info(M, N, shallow, ec.MODE_FP16_SPLIT)["slices"] == 1
         dC = to_device(C)
