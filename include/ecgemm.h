@@ -100,6 +100,7 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 
 /* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit fragment order,
  * zero-padded to whole tiles, plus at most 128 MiB of partial sums for output tiles that are cut into slices along K.
+ * (Small products run as one launch that needs neither; the size returned for them is what ecgemm_product needs.)
  * The plan behind it is made for the 256 compute units of the MI355X, so the size depends on the problem, the mode and
  * the kernel shape only; `handle` supplies the shape forced with ecgemm_set_shape (ecgemm_debug.h) and may be NULL
  * (automatic choice).  transA and transB are checked and otherwise do not matter: the split pass absorbs the
@@ -112,8 +113,9 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA
  * into how many slices along K, whether the product kernel is launched as a persistent grid, in which order the tiles
  * go to the XCDs, its grid size on a 256-CU device, and the workspace bytes.  `info` is a host pointer. */
 typedef struct {
-    int shape;          /* kernel shape used: 1 = block tile 256 x 128, 2 = 128 x 128 two per compute unit, 3 = 128 x 128
-                           with the split fused in (the ecgemm_shape_t values of ecgemm_debug.h; never 0 = automatic) */
+    int shape;          /* kernel shape used: 1 = block tile 256 x 128, 2 = 128 x 128 two per compute unit, 3 and 4 = one
+                           launch that splits for itself, block tile 64 x 64 and 32 x 32 (the ecgemm_shape_t values of
+                           ecgemm_debug.h; never 0 = automatic) */
     int tile_m, tile_n; /* block tile */
     int tiles_m, tiles_n;
     int whole_tiles;    /* tiles that are one work item */
@@ -126,7 +128,7 @@ typedef struct {
     int64_t grid;       /* workgroups of the product (or fused) kernel */
     size_t workspace_bytes;
     double estimated_us; /* the cost estimate by which this plan was preferred to the others (product and reduce kernels,
-                            microseconds on a power-limited MI355X; 0 for the fused shape, which is never ranked) */
+                            microseconds on a power-limited MI355X; for the one-launch shapes, the whole call) */
 } ecgemm_plan_info_t;
 ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
                                  ecgemm_plan_info_t *info);
@@ -308,7 +310,9 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
  * given as the outputs of ecgemm_split(handle, ..., rows = M or N, depth = K, ..., mode, packed) for the SAME mode.
  * For op(B) that means: ecgemm_split(op = T if B is stored K x N (transB == N), op = N if stored N x K).  packedA,
  * packedB: device, read only.  C, ldc, alpha, beta as in ecgemm_sgemm.  Uses the workspace only for the partial sums
- * of tiles sliced along K.  The result is bitwise what ecgemm_sgemm returns for the same operands and kernel shape.
+ * of tiles sliced along K.  The result is bitwise what ecgemm_sgemm returns for the same operands and kernel shape
+ * (with the automatic shape, ecgemm_sgemm may run a small product as one launch, which never slices along K, where
+ * this function slices: then the two agree to FP32 rounding).
  */
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
                                const void *packedA, const void *packedB, float beta, float *C, int64_t ldc,

@@ -58,6 +58,9 @@ extern "C" {
  *                  ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64, 4 waves of
  *                  32 x 32, the whole depth per block; every block splits the rows of A and columns of B that it
  *                  uses again, so this is for small products, where launches and latencies decide the time.
+ *   32x32_FUSED    the same with block tile 32 x 32: all four waves fetch and split, one multiplies.  Four times the
+ *                  blocks with half the split work each: for products so small that 64 x 64 tiles leave most
+ *                  compute units idle.
  * All shapes form the same products in the same per-element order; results agree bit for bit between shapes unless
  * output tiles are sliced along K differently.  A call whose mode has no kernel of the forced shape returns
  * ECGEMM_ERR_UNSUPPORTED.
@@ -66,7 +69,8 @@ typedef enum {
   ECGEMM_SHAPE_AUTO = 0,
   ECGEMM_SHAPE_256x128_W4 = 1,
   ECGEMM_SHAPE_128x128_X2 = 2,
-  ECGEMM_SHAPE_64x64_FUSED = 3
+  ECGEMM_SHAPE_64x64_FUSED = 3,
+  ECGEMM_SHAPE_32x32_FUSED = 4
 } ecgemm_shape_t;
 ecgemm_status_t ecgemm_set_shape(ecgemm_handle_t handle, ecgemm_shape_t shape);
 
@@ -88,7 +92,8 @@ ecgemm_status_t ecgemm_debug_set_tile_order(ecgemm_handle_t handle, int xcd_rema
  * handle would hand the tiles of this problem out (ecgemm_plan_info gives tiles_m x tiles_n, the size the two host
  * arrays must have; `handle` may be NULL as there).  The kernels find a tile's coordinates with multiplications by
  * reciprocals that the host prepares; `disagreements` (host pointer) receives the number of tiles for which that
- * arithmetic and plain integer division give different coordinates, which must be 0.  Not for the fused shape.
+ * arithmetic and plain integer division give different coordinates, which must be 0.  ECGEMM_ERR_UNSUPPORTED for a
+ * problem that ecgemm_sgemm runs as one launch (the one-launch shapes number their tiles with plain divisions).
  */
 ecgemm_status_t ecgemm_debug_tile_order(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode,
                                         int32_t *tile_m, int32_t *tile_n, int64_t *disagreements);

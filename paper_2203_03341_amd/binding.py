@@ -20,7 +20,7 @@ MODE_FP32_MFMA = 7  # plain FP32 on the matrix unit
 MODE_FP16_OUTSIDE_ACC_4, MODE_FP16_OUTSIDE_ACC_16 = 8, 9
 MODE_AUTO = 10
 OK, ERR_INVALID_ARG, ERR_ALLOC, ERR_HIP, ERR_UNSUPPORTED = 0, 1, 2, 3, 4
-SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_64x64_FUSED = 0, 1, 2, 3
+SHAPE_AUTO, SHAPE_256x128_W4, SHAPE_128x128_X2, SHAPE_64x64_FUSED, SHAPE_32x32_FUSED = 0, 1, 2, 3, 4
 
 EXPORTS = ["ecgemm_create", "ecgemm_destroy", "ecgemm_set_stream", "ecgemm_workspace_size", "ecgemm_plan_info", "ecgemm_set_workspace",
            "ecgemm_sgemm", "ecgemm_sgemm_scaled", "ecgemm_sgemm_noalloc", "ecgemm_auto_choice", "ecgemm_last_error_argument", "ecgemm_row_scales", "ecgemm_set_shape", "ecgemm_debug_set_tile_order", "ecgemm_debug_tile_order", "ecgemm_set_scaling", "ecgemm_exponent_range", "ecgemm_choose_mode", "ecgemm_product", "ecgemm_split", "ecgemm_split_size", "ecgemm_debug_mfma", "ecgemm_debug_mfma_rate", "ecgemm_set_timing", "ecgemm_get_timing",

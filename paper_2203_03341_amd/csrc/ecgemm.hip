@@ -51,13 +51,14 @@ typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int
 struct FusedKernels {
   void (*kernel[3][3])(FusedParams);  // [FusedLayout of A][FusedLayout of B]
 };
-template <int METHOD>
+template <int METHOD, int TILE>
 constexpr FusedKernels fused_kernels_of() {
-  return FusedKernels{{{fused_kernel<METHOD, 0, 0>, fused_kernel<METHOD, 0, 1>, fused_kernel<METHOD, 0, 2>},
-                       {fused_kernel<METHOD, 1, 0>, fused_kernel<METHOD, 1, 1>, fused_kernel<METHOD, 1, 2>},
-                       {fused_kernel<METHOD, 2, 0>, fused_kernel<METHOD, 2, 1>, fused_kernel<METHOD, 2, 2>}}};
+  return FusedKernels{{{fused_kernel<METHOD, 0, 0, TILE>, fused_kernel<METHOD, 0, 1, TILE>, fused_kernel<METHOD, 0, 2, TILE>},
+                       {fused_kernel<METHOD, 1, 0, TILE>, fused_kernel<METHOD, 1, 1, TILE>, fused_kernel<METHOD, 1, 2, TILE>},
+                       {fused_kernel<METHOD, 2, 0, TILE>, fused_kernel<METHOD, 2, 1, TILE>, fused_kernel<METHOD, 2, 2, TILE>}}};
 }
-const FusedKernels kFusedFp16 = fused_kernels_of<kMethodFp16Split>(), kFusedBf16 = fused_kernels_of<kMethodBf16Full>();
+const FusedKernels kFusedFp16Tile64 = fused_kernels_of<kMethodFp16Split, 64>(), kFusedFp16Tile32 = fused_kernels_of<kMethodFp16Split, 32>(),
+                   kFusedBf16Tile64 = fused_kernels_of<kMethodBf16Full, 64>(), kFusedBf16Tile32 = fused_kernels_of<kMethodBf16Full, 32>();
 struct Shape {
   void (*product)(ProductParams);  // steps 2 to 5 on packed operands, or
   void (*product_scaled)(ProductParams);  // the instance to prefer for calls with scaling vectors, if the mode has one
@@ -78,23 +79,24 @@ constexpr Shape shape_of(int persistent_max_k) {
   return Shape{product_kernel<Cfg, false>, scaled, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK,
                Cfg::THREADS, Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
-inline Shape fused_shape(const FusedKernels* kernels) {  // 64 x 64 tiles, never sliced: no partial sums, no second kernel
-  return Shape{nullptr, nullptr, kernels, nullptr, 64, 64, 32, 256, 1, 0};
+inline Shape fused_shape(const FusedKernels* kernels, int tile) {  // never sliced: no partial sums, no second kernel
+  return Shape{nullptr, nullptr, kernels, nullptr, tile, tile, 32, 256, 1, 0};
 }
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
+constexpr int kShapeCount = 4;
 // [mode][ecgemm_shape_t - 1]
 constexpr int kPersistentMaxK = 4096;
-const Shape kShapes[kMethods][3] = {
-    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape(&kFusedFp16)},
-    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape(&kFusedBf16)},
-    {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape},
-    {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape},
-    {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape},
-    {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape},
-    {shape_of<OutsideConfig>(4096), kNoShape, kNoShape},
-    {shape_of<Fp32Config>(4096), kNoShape, kNoShape},
-    {shape_of<Outside4Config>(4096), kNoShape, kNoShape},
-    {shape_of<Outside16Config>(4096), kNoShape, kNoShape},
+const Shape kShapes[kMethods][kShapeCount] = {
+    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape(&kFusedFp16Tile64, 64), fused_shape(&kFusedFp16Tile32, 32)},
+    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape(&kFusedBf16Tile64, 64), fused_shape(&kFusedBf16Tile32, 32)},
+    {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<PlainBf16Config>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<OutsideConfig>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<Fp32Config>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<Outside4Config>(4096), kNoShape, kNoShape, kNoShape},
+    {shape_of<Outside16Config>(4096), kNoShape, kNoShape, kNoShape},
 };
 
 inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -111,7 +113,7 @@ static_assert((int)ECGEMM_MODE_FP16_SPLIT == (int)kMethodFp16Split && (int)ECGEM
                   (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_4 == (int)kMethodFp16Outside4 &&
                   (int)ECGEMM_MODE_FP16_OUTSIDE_ACC_16 == (int)kMethodFp16Outside16,
               "mode numbering");
-inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_64x64_FUSED; }
+inline bool valid_shape(int shape) { return shape >= ECGEMM_SHAPE_AUTO && shape <= ECGEMM_SHAPE_32x32_FUSED; }
 inline bool valid_op(int op) { return op == ECGEMM_OP_N || op == ECGEMM_OP_T; }
 
 size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
@@ -238,34 +240,69 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
   return best;
 }
 
-// The plan of a call: the cheaper of the two shapes by the estimate above when the caller has not fixed one.  The
-// comparison methods have the 256 x 128 shape only.
-Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+// Estimated time of a whole call in microseconds, for the choice between splitting first and the one-launch shapes.
+// Both are fits to timings of back-to-back calls on one MI355X (squares from 64 to 1536 and a dozen other small
+// shapes, both modes).
+//   split first: the product estimate above, the launches (5.6 us), and the split pass, which costs about 1 us per MB
+//   of FP32 operands (1.4 us with three BF16 parts to write) until it is hidden behind the product's launch (8.5 us).
+//   one launch: 4.4 us, then per 64-deep chunk what a block needs to split its share, times how crowded the compute
+//   units are once there are more blocks than units (blocks share a unit's vector pipes; the 64 x 64 BF16 block
+//   needs 96 KiB of LDS, so a second one waits).  A last chunk that is not whole takes the slower, general split.
+double split_first_us(const Plan& pl, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
+  const double operand_mb = 4.0 * ((double)M + (double)N) * (double)K / 1e6;
+  return estimated_us(pl, mode) + 5.6 + std::min(8.5, (mode == ECGEMM_MODE_BF16_FULL ? 1.4 : 1.0) * operand_mb);
+}
+double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
+  const bool bf16 = mode == ECGEMM_MODE_BF16_FULL, small = pl.shape->bm == 32;
+  const double per_chunk = small ? (bf16 ? 1.3 : 0.76) : (bf16 ? 1.9 : 1.3);
+  const double blocks_per_unit = (double)pl.tiles_m * pl.tiles_n / kPlanComputeUnits;
+  const double crowding = blocks_per_unit <= 1.0 ? 1.0
+                          : small               ? 0.55 + 0.5 * blocks_per_unit
+                          : bf16                ? 1.3 * blocks_per_unit
+                                                : 0.3 + 0.75 * blocks_per_unit;
+  const double chunks = (double)(K / 64) + (K % 64 ? 2.5 : 0.0);
+  return 4.4 + chunks * per_chunk * std::max(1.0, crowding);
+}
+
+// The plan of a call.  With a shape forced by the caller, that shape.  Otherwise the cheaper of the two product shapes
+// by the product estimate (the comparison methods have the 256 x 128 shape only), unless a one-launch shape is
+// allowed (ecgemm_sgemm and what describes it; not for callers that need the packed operands) and estimated to take
+// less than 0.85 of the time: the estimates know nothing of the operands' layouts, which move either by a tenth.
+Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, bool one_launch_allowed) {
   if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
   const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
   if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
   const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
-  return estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
+  const Plan split_first = estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
+  // (a one-launch block walks the whole depth and an operand is split once per block row or column: beyond these
+  // bounds it never wins, and its tile count stays far inside 32 bits)
+  if (!one_launch_allowed || K > 8192 || M > 16384 || N > 16384) return split_first;
+  const Plan tile64 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_64x64_FUSED);
+  const Plan tile32 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_32x32_FUSED);
+  const Plan one_launch = one_launch_us(tile32, K, mode) < one_launch_us(tile64, K, mode) ? tile32 : tile64;
+  return one_launch_us(one_launch, K, mode) < 0.85 * split_first_us(split_first, M, N, K, mode) ? one_launch : split_first;
 }
 
 // A plan is a pure function of its arguments, and loops call the library with the same ones over and over: the last
 // few plans of each thread are kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to
 // a 12 us call; the automatic mode needs two plans per call).
-Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, bool one_launch_allowed) {
   struct Entry {
     int64_t M = -1, N = -1, K = -1;
     int mode = -1, shape = -1;
+    bool one_launch_allowed = false;
     Plan plan;
   };
   constexpr int kEntries = 4;
   thread_local Entry cache[kEntries];
   thread_local int next = 0;
   for (const Entry& e : cache)
-    if (e.M == M && e.N == N && e.K == K && e.mode == (int)mode && e.shape == (int)shape) return e.plan;
+    if (e.M == M && e.N == N && e.K == K && e.mode == (int)mode && e.shape == (int)shape && e.one_launch_allowed == one_launch_allowed)
+      return e.plan;
   Entry& e = cache[next];
   next = (next + 1) % kEntries;
-  e.plan = choose_plan(M, N, K, mode, shape);
-  e.M = M, e.N = N, e.K = K, e.mode = (int)mode, e.shape = (int)shape;
+  e.plan = choose_plan(M, N, K, mode, shape, one_launch_allowed);
+  e.M = M, e.N = N, e.K = K, e.mode = (int)mode, e.shape = (int)shape, e.one_launch_allowed = one_launch_allowed;
   return e.plan;
 }
 
@@ -281,8 +318,8 @@ struct AutoPlan {
 };
 AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
   AutoPlan ap;
-  ap.fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape);
-  ap.bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape);
+  ap.fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape, false);
+  ap.bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape, false);
   ap.exists = ap.fp16.shape && ap.bf16.shape && !ap.fp16.shape->fused && !ap.bf16.shape->fused;
   if (!ap.exists) return ap;
   const size_t blocks_per_row_block = (size_t)(round_up(K, kDepthPad) / 32);
@@ -718,7 +755,7 @@ ecgemm_status_t ecgemm_debug_tile_order(ecgemm_handle_t handle, int64_t M, int64
   if (!disagreements) return bad_arg(handle, 8, "ecgemm_debug_tile_order: null output");
   const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, true);  // as ecgemm_plan_info
   if (!pl.shape || pl.shape->fused) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_debug_tile_order: no product kernel of this shape and mode");
   const int group_m = group_m_of(pl, handle ? handle->forced_group_m : 0);
   const int bands = column_bands(pl, group_m, mode, handle ? handle->forced_column_bands : 0);
@@ -753,9 +790,12 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA
     *bytes = ap.total_bytes;
     return ECGEMM_OK;
   }
-  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  const ecgemm_shape_t shape = handle ? handle->shape : ECGEMM_SHAPE_AUTO;
+  const Plan pl = make_plan(M, N, K, mode, shape, true);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
   *bytes = pl.total_bytes;
+  // (ecgemm_product on the same problem never takes a one-launch shape by itself and may need room for partial sums)
+  if (pl.shape->fused && shape == ECGEMM_SHAPE_AUTO) *bytes = std::max(*bytes, make_plan(M, N, K, mode, shape, false).partial_bytes);
   return ECGEMM_OK;
 }
 
@@ -768,7 +808,7 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   if (!info) return bad_arg(handle, 6, "ecgemm_plan_info: null output");
   const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO);
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, true);
   if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_plan_info: the handle's kernel shape does not exist for this mode");
   info->shape = (int)(pl.shape - &kShapes[(int)mode][0]) + 1;
   info->tile_m = pl.shape->bm;
@@ -784,7 +824,7 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   info->group_m = pl.shape->fused ? 4 : group_m_of(pl, handle ? handle->forced_group_m : 0);
   info->column_bands = pl.shape->fused ? 1 : column_bands(pl, info->group_m, mode, handle ? handle->forced_column_bands : 0);
   info->workspace_bytes = pl.total_bytes;
-  info->estimated_us = pl.shape->fused ? 0.0 : estimated_us(pl, mode);
+  info->estimated_us = pl.shape->fused ? one_launch_us(pl, K, mode) : estimated_us(pl, mode);
   return ECGEMM_OK;
 }
 
@@ -1158,7 +1198,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   }
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, h->shape);
+  const Plan pl = make_plan(M, N, K, mode, h->shape, true);
   if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
   SplitJob job_a, job_b;
@@ -1275,7 +1315,7 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
   if (!packedB || ((uintptr_t)packedB % 16) != 0) return bad_arg(h, 7, "ecgemm_product: packed operand is null or not 16-byte aligned");
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, h->shape);
+  const Plan pl = make_plan(M, N, K, mode, h->shape, false);
   if (!pl.shape || pl.shape->fused)
     return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not take packed operands in this mode");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 2, "ecgemm_product: too many tiles");

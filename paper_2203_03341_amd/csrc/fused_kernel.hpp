@@ -4,16 +4,18 @@
 // copies in HBM, no partial sums: one launch.  Every block that touches a tile of A splits it again (N / 64 times per
 // element), so this pays where launches and latencies, not arithmetic, decide the time: small products.
 //
-// One block: 64 x 64 of C, 4 waves of 32 x 32 (one v_mfma_f32_32x32x16 accumulator pair per wave), the whole depth
-// of the product; same fragment layout in LDS, same term order and same accumulator discipline as product_kernel.hpp,
-// so an element is summed in the same order as in an unsliced tile there.  The small tile is what makes a small
-// product many blocks: 256^3 is 16 of them, 512^3 64.
+// One block: 256 threads and TILE x TILE of C over the whole depth of the product, TILE = 64 (4 waves of 32 x 32, one
+// v_mfma_f32_32x32x16 accumulator pair per wave) or 32 (one wave multiplies, all four fetch and split).  Same fragment
+// layout in LDS, same term order and same accumulator discipline as product_kernel.hpp, so an element is summed in
+// the same order as in an unsliced tile there.  Small tiles are what make a small product many blocks, and what
+// bounds a block is its split work, (TILE + TILE) x K elements: 512^3 is 64 blocks of 64 x 64 or 256 of 32 x 32 with
+// half the work each, one per compute unit.  The host picks 32 while that still leaves compute units idle.
 //
-// Depth is walked in chunks of 64.  All 256 threads fetch the chunk's 64 x 64 values of op(A) and of op(B), 16 + 16
-// values per thread, with the lanes of a wave along whichever index is contiguous in memory (FusedLayout); the values
+// Depth is walked in chunks of 64.  All 256 threads fetch the chunk's TILE x 64 values of op(A) and of op(B), TILE / 4
+// of each per thread, with the lanes of a wave along whichever index is contiguous in memory (FusedLayout); the values
 // of the next kFusedRing chunks are in flight in registers while the current one is split, written to LDS in fragment
-// order (two buffers, one barrier per chunk) and multiplied.  The split is what bounds the loop (a chunk is 8192
-// elements per block against 12 or 24 matrix instructions per wave), so it takes a short form (FastSplit, 5 to 7
+// order (two buffers, one barrier per chunk) and multiplied.  The split is what bounds the loop (a chunk of a 64 x 64
+// tile is 8192 elements per block against 12 or 24 matrix instructions per wave), so it takes a short form (FastSplit, 5 to 7
 // vector instructions per element) whenever every value a wave holds is ordinary, and Splitter, which saturates and
 // handles infinities and NaN, otherwise; both give the same bits on the values the short form accepts.
 #pragma once
@@ -21,12 +23,12 @@
 
 namespace ecgemm {
 
-// How the 16 values per thread and chunk are laid over one operand's 64 rows x 64 k (X(r, k): op(A)(m, k) or
-// op(B)(k, n) with r = n):
-//   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: lane = row, wave w holds k = 16 w .. 16 w + 15 of it
-//   kFusedDepth     k contiguous, X(r, k) = src[k + r ld]: lane = k, wave w holds rows 16 w .. 16 w + 15 at that k
-//   kFusedDepthVec  k contiguous, base and ld multiples of 16 bytes, K a multiple of 4: lane l holds the four values
-//                   k = 4 (l % 16) .. + 3 of rows 16 w + 4 j + l / 16, j = 0 .. 3, one 16-byte load each
+// How the V = TILE / 4 values per thread and chunk are laid over one operand's TILE rows x 64 k (X(r, k): op(A)(m, k)
+// or op(B)(k, n) with r = n), wave w, lane l:
+//   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: row l % TILE, the V consecutive k from 16 w + 8 (l / TILE)
+//   kFusedDepth     k contiguous, X(r, k) = src[k + r ld]: k = l, rows V w .. V w + V - 1
+//   kFusedDepthVec  k contiguous, base and ld multiples of 16 bytes, K a multiple of 4: the four values k = 4 (l % 16) ..
+//                   + 3 of rows V w + 4 j + l / 16, j = 0 .. V / 4 - 1, one 16-byte load each
 enum FusedLayout { kFusedRows = 0, kFusedDepth = 1, kFusedDepthVec = 2 };
 constexpr int kFusedRing = 2;  // chunks in flight in registers (unrolled: a register ring is indexed statically)
 
@@ -79,31 +81,34 @@ struct FastSplit {
       }
     }
   }
-  // true if none of the 16 high parts in `words[..][0]` is infinite or NaN
-  __device__ static __forceinline__ bool high_parts_finite(const unsigned (&words)[8][kParts]) {
+  // true if none of the 2 W high parts in `words[..][0]` is infinite or NaN
+  template <int W>
+  __device__ static __forceinline__ bool high_parts_finite(const unsigned (&words)[W][kParts]) {
     const unsigned magnitude = 0x7fff7fffu;
     fused_ushort2_t most = {0, 0};
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
+    for (int e = 0; e < W; ++e)
       most = __builtin_elementwise_max(most, __builtin_bit_cast(fused_ushort2_t, words[e][0] & magnitude));
     const unsigned short exponent_all_ones = split_is_bf16(KIND) ? 0x7f80 : 0x7c00;
     return most[0] < exponent_all_ones && most[1] < exponent_all_ones;
   }
 };
 
-// One operand of the block: where this thread's 16 values per chunk come from and where their parts go.
-template <int KIND, int LAYOUT>
+// One operand of the block: where this thread's V values per chunk come from and where their parts go.
+template <int KIND, int LAYOUT, int TILE>
 struct FusedOperand {
+  static_assert(TILE == 64 || TILE == 32, "tile sizes");
   static constexpr int NP = parts_of_split(KIND);
-  static constexpr int ROWS = LAYOUT == kFusedRows ? 1 : LAYOUT == kFusedDepth ? 16 : 4;  // rows this thread holds values of
-  static constexpr int PER_ROW = 16 / ROWS;                                                // consecutive k per row
-  static constexpr int REGION_BYTES = 2 * 4 * NP * 1024;  // a chunk of one operand in LDS: [row block][k step][part] x 1 KiB
+  static constexpr int V = TILE / 4;                                                     // values per thread and chunk
+  static constexpr int ROWS = LAYOUT == kFusedRows ? 1 : LAYOUT == kFusedDepth ? V : V / 4;  // rows this thread holds values of
+  static constexpr int PER_ROW = V / ROWS;                                               // consecutive k per row
+  static constexpr int REGION_BYTES = (TILE / 32) * 4 * NP * 1024;  // a chunk of one operand in LDS: [row block][k step][part] x 1 KiB
 
   // Addresses are a part that is the same for the whole wave plus a small per-lane offset wherever the layout allows
   // it, which leaves the address arithmetic to the scalar unit.  A row beyond the matrix reads the last row instead
   // (its values end up in rows or columns of the tile that are never stored).
   const float* tile;           // &X(first row of the tile, 0)
-  const float* row_ptr[ROWS];  // kFusedDepth: &X(row, 0) for the wave's 16 rows; kFusedDepthVec: for the lane's 4 rows
+  const float* row_ptr[ROWS];  // &X(row, 0) for each of the thread's rows
   unsigned lane_offset;        // kFusedRows: the lane's row within the tile; kFusedDepth: the lane's k within the chunk
   float factor[ROWS];          // the handle's pre-scaling times the row's own
   int64_t ld, K;
@@ -113,17 +118,17 @@ struct FusedOperand {
   __device__ __forceinline__ void init(const float* src, int64_t ld_, int64_t rows, int64_t K_, int64_t tile_row0, float prescale,
                                        const int* log2_scale, int lane, int wave) {
     ld = ld_, K = K_;
-    const int rows_here = (int)(rows - tile_row0 < 64 ? rows - tile_row0 : 64);  // >= 1
+    const int rows_here = (int)(rows - tile_row0 < TILE ? rows - tile_row0 : TILE);  // >= 1
     tile = LAYOUT == kFusedRows ? src + tile_row0 : src + tile_row0 * ld;
     int first_row;  // within the tile
     if constexpr (LAYOUT == kFusedRows) {
-      first_row = lane, k_here = 16 * wave;
-      lane_offset = (unsigned)(lane < rows_here ? lane : rows_here - 1);
+      first_row = lane % TILE, k_here = 16 * wave + 8 * (lane / TILE);
+      lane_offset = (unsigned)(first_row < rows_here ? first_row : rows_here - 1);
     } else if constexpr (LAYOUT == kFusedDepth) {
-      first_row = 16 * wave, k_here = lane;
+      first_row = V * wave, k_here = lane;
       lane_offset = (unsigned)lane;
     } else {
-      first_row = 16 * wave + (lane >> 4), k_here = 4 * (lane & 15);
+      first_row = V * wave + (lane >> 4), k_here = 4 * (lane & 15);
       lane_offset = 0;
     }
 #pragma unroll
@@ -142,19 +147,19 @@ struct FusedOperand {
   // clamped to the last k (and replaced by zero in deposit()).  No load sits under a condition and both branches
   // issue the same number of loads, so the number in flight is the same on every path: the waits that the compiler
   // places count them.
-  __device__ __forceinline__ void fetch(float (&x)[16], int c) const {
+  __device__ __forceinline__ void fetch(float (&x)[V], int c) const {
     const int64_t chunk_k = (int64_t)c * 64;
     if (chunk_k + 64 <= K) {  // block-uniform
       if constexpr (LAYOUT == kFusedRows) {
-        const float* first = tile + (chunk_k + k_here) * ld;  // wave-uniform
+        const float* first = tile + chunk_k * ld;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) x[i] = first[i * ld + lane_offset];
+        for (int i = 0; i < V; ++i) x[i] = first[(k_here + i) * ld + lane_offset];
       } else if constexpr (LAYOUT == kFusedDepth) {
 #pragma unroll
-        for (int j = 0; j < 16; ++j) x[j] = (row_ptr[j] + chunk_k)[lane_offset];
+        for (int j = 0; j < V; ++j) x[j] = (row_ptr[j] + chunk_k)[lane_offset];
       } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < ROWS; ++j) {
           const float4 v = *reinterpret_cast<const float4*>(row_ptr[j] + chunk_k + k_here);
           x[4 * j] = v.x, x[4 * j + 1] = v.y, x[4 * j + 2] = v.z, x[4 * j + 3] = v.w;
         }
@@ -165,13 +170,13 @@ struct FusedOperand {
         // K is a multiple of 4 here (the host's condition for this layout): four values that start below K end below it
         const int64_t k = k0 < K ? k0 : K - 4;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < ROWS; ++j) {
           const float4 v = *reinterpret_cast<const float4*>(row_ptr[j] + k);
           x[4 * j] = v.x, x[4 * j + 1] = v.y, x[4 * j + 2] = v.z, x[4 * j + 3] = v.w;
         }
       } else {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < V; ++e) {
           const int64_t k = k0 + e % PER_ROW < K ? k0 + e % PER_ROW : K - 1;
           x[e] = LAYOUT == kFusedRows ? row_ptr[0][k * ld] : row_ptr[e][k];
         }
@@ -180,22 +185,22 @@ struct FusedOperand {
   }
 
   // Splits the values of chunk c and writes the parts to `region` where the fragment reads expect them.
-  __device__ __forceinline__ void deposit(const float (&x)[16], int c, char* region) const {
-    float v[16];
+  __device__ __forceinline__ void deposit(const float (&x)[V], int c, char* region) const {
+    float v[V];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) v[e] = x[e] * factor[e / PER_ROW];
-    unsigned words[8][NP];  // part q of values 2 e and 2 e + 1
+    for (int e = 0; e < V; ++e) v[e] = x[e] * factor[e / PER_ROW];
+    unsigned words[V / 2][NP];  // part q of values 2 e and 2 e + 1
     const bool whole = (int64_t)c * 64 + 64 <= K;  // block-uniform
     bool done = false;
     if (whole) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) FastSplit<KIND>::split2(v[2 * e], v[2 * e + 1], words[e]);
+      for (int e = 0; e < V / 2; ++e) FastSplit<KIND>::split2(v[2 * e], v[2 * e + 1], words[e]);
       done = __builtin_amdgcn_ballot_w64(!FastSplit<KIND>::high_parts_finite(words)) == 0;  // wave-uniform
     }
     if (!done) {
       const int64_t k0 = (int64_t)c * 64 + k_here;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
+      for (int e = 0; e < V / 2; ++e) {
         unsigned short even[NP], odd[NP];
         Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? v[2 * e] : 0.0f, even);
         Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? v[2 * e + 1] : 0.0f, odd);
@@ -208,39 +213,42 @@ struct FusedOperand {
     typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int q = 0; q < NP; ++q) {
-      if constexpr (LAYOUT == kFusedRows) {  // 16 consecutive k of one row: the two halves of a k step
-        *reinterpret_cast<uint4_t*>(base + q * 1024) = uint4_t{words[0][q], words[1][q], words[2][q], words[3][q]};
-        *reinterpret_cast<uint4_t*>(base + q * 1024 + 512) = uint4_t{words[4][q], words[5][q], words[6][q], words[7][q]};
-      } else if constexpr (LAYOUT == kFusedDepth) {  // one k of 16 consecutive rows
+      if constexpr (LAYOUT == kFusedRows) {  // consecutive k of one row: one or both 8-deep halves of a k step
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int h = 0; h < V / 8; ++h)
+          *reinterpret_cast<uint4_t*>(base + q * 1024 + h * 512) =
+              uint4_t{words[4 * h][q], words[4 * h + 1][q], words[4 * h + 2][q], words[4 * h + 3][q]};
+      } else if constexpr (LAYOUT == kFusedDepth) {  // one k of consecutive rows
+#pragma unroll
+        for (int e = 0; e < V / 2; ++e) {
           *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e) * 16) = (unsigned short)words[e][q];
           *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e + 1) * 16) = (unsigned short)(words[e][q] >> 16);
         }
       } else {  // four consecutive k of rows 4 apart
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < ROWS; ++j)
           *reinterpret_cast<uint2_t*>(base + q * 1024 + j * 64) = uint2_t{words[2 * j][q], words[2 * j + 1][q]};
       }
     }
   }
 };
 
-template <int METHOD, int LAYOUT_A, int LAYOUT_B>
+template <int METHOD, int LAYOUT_A, int LAYOUT_B, int TILE>
 __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   constexpr int KIND = split_kind_of(METHOD);
   constexpr bool BF16 = split_is_bf16(KIND);
   constexpr int NP = parts_of_split(KIND), PRODUCTS = products_of(METHOD);
-  constexpr int BM = 64, BN = 64, K_STEPS = 4;
-  typedef FusedOperand<KIND, LAYOUT_A> OperandA;
-  typedef FusedOperand<KIND, LAYOUT_B> OperandB;
+  constexpr int BM = TILE, BN = TILE, K_STEPS = 4, V = TILE / 4;
+  typedef FusedOperand<KIND, LAYOUT_A, TILE> OperandA;
+  typedef FusedOperand<KIND, LAYOUT_B, TILE> OperandB;
   constexpr int REGION_BYTES = OperandA::REGION_BYTES, STAGE_BYTES = 2 * REGION_BYTES;
   typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wave_m = wave % 2, wave_n = wave / 2;
+  const int wave_m = TILE == 64 ? wave % 2 : 0, wave_n = TILE == 64 ? wave / 2 : 0;
+  const bool multiplies = TILE == 64 || wave == 0;  // wave-uniform
   int tile_m, tile_n;
   tile_coordinates((int)blockIdx.x, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
 
@@ -256,6 +264,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   const int a_frag_off = wave_m * K_STEPS * NP * 1024 + lane * 16;
   const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024 + lane * 16;
   auto multiply = [&](int buf) {
+    if (!multiplies) return;
     const char* stage = lds + buf * STAGE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < K_STEPS; ++ks) {
@@ -277,7 +286,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
 
   // ---- main loop: chunk c is split into LDS buffer c % 2 and multiplied while chunks c + 1 .. c + kFusedRing travel
   static_assert(kFusedRing % 2 == 0, "a ring slot always meets the same LDS buffer");
-  float xa[kFusedRing][16], xb[kFusedRing][16];
+  float xa[kFusedRing][V], xb[kFusedRing][V];
   // (a chunk beyond the last is requested again as the last one and never used: in the loop every fetch is
   // unconditional; the scheduling barriers keep the requests of one ring slot together and the slots in order, which
   // is what lets the wait in front of a slot's first use leave the younger slots' loads in flight)
@@ -316,7 +325,7 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
   const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
   const int64_t m = (int64_t)tile_m * BM + wave_m * 32 + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * BN + wave_n * 32 + 4 * (lane >> 5);
-  if (m >= p.M) return;
+  if (!multiplies || m >= p.M) return;
   const int row_exponent = p.row_log2_scale != nullptr ? p.row_log2_scale[m] : 0;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {

@@ -83,16 +83,19 @@ ECGEMM_COMPARE_A_GROUP template __global__ void product_kernel<Outside16Config, 
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainFp16Config, false>(const ProductParams);
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<PlainBf16Config, false>(const ProductParams);
 ECGEMM_COMPARE_B_GROUP template __global__ void product_kernel<Fp32Config, false>(const ProductParams);
-#define ECGEMM_FUSED_KERNELS_OF(METHOD, LAYOUT_A)                                                            \
-  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedRows>(const FusedParams);   \
-  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedDepth>(const FusedParams);  \
-  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedDepthVec>(const FusedParams);
-ECGEMM_FUSED_KERNELS_OF(kMethodFp16Split, kFusedRows)
-ECGEMM_FUSED_KERNELS_OF(kMethodFp16Split, kFusedDepth)
-ECGEMM_FUSED_KERNELS_OF(kMethodFp16Split, kFusedDepthVec)
-ECGEMM_FUSED_KERNELS_OF(kMethodBf16Full, kFusedRows)
-ECGEMM_FUSED_KERNELS_OF(kMethodBf16Full, kFusedDepth)
-ECGEMM_FUSED_KERNELS_OF(kMethodBf16Full, kFusedDepthVec)
+#define ECGEMM_FUSED_KERNELS_OF(METHOD, LAYOUT_A, TILE)                                                            \
+  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedRows, TILE>(const FusedParams);   \
+  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedDepth, TILE>(const FusedParams);  \
+  ECGEMM_FUSED_GROUP template __global__ void fused_kernel<METHOD, LAYOUT_A, kFusedDepthVec, TILE>(const FusedParams);
+#define ECGEMM_FUSED_KERNELS_OF_METHOD(METHOD)           \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedRows, 64)        \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedDepth, 64)       \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedDepthVec, 64)    \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedRows, 32)        \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedDepth, 32)       \
+  ECGEMM_FUSED_KERNELS_OF(METHOD, kFusedDepthVec, 32)
+ECGEMM_FUSED_KERNELS_OF_METHOD(kMethodFp16Split)
+ECGEMM_FUSED_KERNELS_OF_METHOD(kMethodBf16Full)
 
 #define ECGEMM_SPLIT_KERNELS_OF(KIND)                                                                     \
   ECGEMM_SPLIT_GROUP template __global__ void split_kernel<KIND, kSplitKContiguousVec, false>(const SplitJob);   \

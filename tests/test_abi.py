@@ -120,13 +120,27 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["sliced_tiles"], p["slices"]) == (W4, 72, 3)
     p = ec.plan_info(300, 200, 100, ec.MODE_FP16_MARKIDIS)             # comparison methods: one shape
     assert (p["shape"], p["tiles_m"], p["tiles_n"]) == (W4, 2, 2)
+    # small products: one launch that splits for itself, 32 x 32 tiles while those leave compute units idle, 64 x 64
+    # after that, nothing in the workspace, never sliced; the split-first shapes again once blocks crowd the units
+    F64, F32 = ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED
+    for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
+        for (M, N, K, shape) in [(1, 1, 1, F32), (256, 256, 256, F32), (512, 512, 512, F32), (300, 200, 77, F32),
+                                 (4096, 128, 128, (F32, F64)), (1024, 1024, 256, F64), (1536, 1536, 1536, X2), (128, 128, 8256, X2),
+                                 (256, 256, 4096, X2)]:
+            p = ec.plan_info(M, N, K, mode)
+            assert p["shape"] == shape or (isinstance(shape, tuple) and p["shape"] in shape), (M, N, K, mode, p)
+            if p["shape"] in (F64, F32):
+                tile = 64 if p["shape"] == F64 else 32
+                assert (p["tile_m"], p["tile_n"], p["slices"], p["sliced_tiles"], p["workspace_bytes"]) == (tile, tile, 1, 0, 0)
+                assert p["grid"] == p["tiles_m"] * p["tiles_n"] == -(-M // tile) * -(-N // tile) and p["estimated_us"] > 4
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
         for (M, N, K) in [(1, 1, 1), (257, 129, 33), (5000, 7000, 900), (20000, 300, 70000)]:
             p = ec.plan_info(M, N, K, mode)
             assert p["tiles_m"] * p["tiles_n"] == p["whole_tiles"] + p["sliced_tiles"]
             assert p["tiles_m"] == -(-M // p["tile_m"]) and p["tiles_n"] == -(-N // p["tile_n"])
             assert (p["slices"] == 1) == (p["sliced_tiles"] == 0)
-            assert p["workspace_bytes"] == ec.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode)
+            if p["shape"] in (W4, X2):
+                assert p["workspace_bytes"] == ec.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode)
             if p["slices"] > 1:
                 assert -(-K // p["slices"]) >= 512 - 32                  # a slice is never shallower than 512 (padded)
     import pytest
@@ -159,6 +173,10 @@ def test_plans_of_random_problems_are_well_formed():
         assert p["whole_tiles"] + p["sliced_tiles"] == p["tiles_m"] * p["tiles_n"], case
         assert (p["slices"] == 1) == (p["sliced_tiles"] == 0), case
         assert 1 <= p["column_bands"] <= max(1, p["tiles_n"]) and p["group_m"] in (4, 8), case
+        if p["shape"] in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):      # one launch: nothing packed, nothing sliced
+            assert (p["workspace_bytes"], p["slices"]) == (0, 1) and p["tile_m"] == p["tile_n"] == (64 if p["shape"] == 3 else 32), case
+            assert mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL) and K <= 8192 and p["tiles_m"] * p["tiles_n"] <= 2048, case
+            continue
         Kp = -(-K // 32) * 32
         parts = {ec.MODE_FP16_SPLIT: 2, ec.MODE_BF16_FULL: 3, ec.MODE_FP16_MARKIDIS: 2, ec.MODE_FP32_MFMA: 2}[mode]
         packed = (-(-M // 256) * 256 + -(-N // 256) * 256) * Kp * 2 * parts
@@ -186,8 +204,13 @@ def test_tile_order_reciprocal_arithmetic_agrees_with_division():
     problems += [(int(rng.integers(1, 12000)), int(rng.integers(1, 12000)), int(rng.integers(1, 20000))) for _ in range(60)]
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
         for (M, N, K) in problems:
-            tm, tn, bad = ec.debug_tile_order(M, N, K, mode)
             p = ec.plan_info(M, N, K, mode)
+            if p["shape"] in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):   # one launch: no reciprocal arithmetic
+                import pytest
+                with pytest.raises(ec.EcgemmError):
+                    ec.debug_tile_order(M, N, K, mode)
+                continue
+            tm, tn, bad = ec.debug_tile_order(M, N, K, mode)
             assert bad == 0, (M, N, K, mode)
             seen = np.zeros((p["tiles_m"], p["tiles_n"]), dtype=np.int32)
             np.add.at(seen, (tm, tn), 1)
@@ -202,7 +225,8 @@ def test_workspace_plan_needs_no_gpu():
     assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_FP16_SPLIT) == 2 * n * n * 4              # two packed operands, no split-K
     assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_BF16_FULL) == 2 * n * n * 6
     assert ec.workspace_size(ec.OP_N, ec.OP_N, n, n, n, ec.MODE_FP16_PLAIN) == 2 * n * n * 2
-    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1, 1, 1, ec.MODE_FP16_SPLIT) == 2 * 256 * 32 * 4
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1, 1, 1, ec.MODE_FP16_PLAIN) == 2 * 256 * 32 * 2
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1, 1, 1, ec.MODE_FP16_SPLIT) == 0      # one launch on the FP32 operands
     assert ec.workspace_size(ec.OP_N, ec.OP_N, 0, 5, 5, ec.MODE_FP16_SPLIT) == 0
     # 32 output tiles of 256 x 128 on 256 CUs: every tile is cut into 8 slices along K, one partial tile per slice
     deep = ec.workspace_size(ec.OP_N, ec.OP_N, 1024, 1024, 65536, ec.MODE_FP16_SPLIT)
@@ -211,7 +235,7 @@ def test_workspace_plan_needs_no_gpu():
     odd = ec.workspace_size(ec.OP_N, ec.OP_N, 4095, 3001, 5003, ec.MODE_BF16_FULL)
     assert odd == (4096 + 3072) * 5024 * 6 + 2 * 128 * (256 * 128 * 4)
     # shallow K is never sliced
-    assert ec.workspace_size(ec.OP_N, ec.OP_N, 1024, 1024, 512, ec.MODE_FP16_SPLIT) == 2 * 1024 * 512 * 4
+    assert ec.workspace_size(ec.OP_N, ec.OP_N, 4096, 4096, 512, ec.MODE_FP16_SPLIT) == 2 * 4096 * 512 * 4
     import pytest
     with pytest.raises(ec.EcgemmError):
         ec.workspace_size(ec.OP_N, ec.OP_N, -1, 1, 1, ec.MODE_FP16_SPLIT)

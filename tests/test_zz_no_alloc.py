@@ -56,10 +56,10 @@ def test_noalloc_entry_point_equals_sgemm_on_two_calls_in_a_row(mode):
 
 
 def test_noalloc_entry_point_with_every_kernel_shape():
-    """The forced shapes go through the same entry point (the fused one keeps only partial sums in the array)."""
+    """The forced shapes go through the same entry point (the one-launch shapes use none of the array)."""
     import paper_2203_03341_amd as ec
     h = ec.Handle()
-    for shape in (ec.SHAPE_256x128_W4, ec.SHAPE_128x128_X2, ec.SHAPE_64x64_FUSED):
+    for shape in (ec.SHAPE_256x128_W4, ec.SHAPE_128x128_X2, ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):
         h.set_shape(shape)
         _pair(h, "N", "N", 700, 520, 1536, 1.0, 0.0, ec.MODE_FP16_SPLIT, seed=13)
         _pair(h, "T", "T", 130, 90, 64, 2.0, 1.0, ec.MODE_FP16_SPLIT, seed=14)
