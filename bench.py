@@ -45,13 +45,16 @@ MEASURED_TRAFFIC_BYTES = {
     "c5_deepk_fp16": 5.71e8,                 # profiles/product_kernel_fp16_deepk_1024x1024x65536.md: 537 MB + 33.5 MB
                                              # (product kernel; its reduction moves another 38 MB)
     # profiles/product_kernel_hbm_traffic_other_workloads.md:
-    "c2_4096_bf16_urand": 8.73e8, "c5_tallskinny_bf16": 1.50e9, "c5_deepk_bf16": 8.39e8, "c1_256_fp16_urand": 1.4e6,
+    "c2_4096_bf16_urand": 8.73e8, "c5_tallskinny_bf16": 1.50e9, "c5_deepk_bf16": 8.39e8,
     "c5_odd_transA_fp16": 5.73e8, "c5_odd_transA_bf16": 8.18e8,
+    # profiles/one_launch_kernel_small_products.md (fused_kernel, 32 x 32 tiles): 1.85 MB + 0.26 MB
+    "c1_256_fp16_urand": 2.1e6, "c1_256_bf16_urand": 2.1e6,
 }
 
 WORKLOADS = {
     # name: (M, N, K, transA, transB, mode, alpha, beta, distribution, oracle rows)
     "c1_256_fp16_urand": (256, 256, 256, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "c1_256_bf16_urand": (256, 256, 256, "N", "N", "bf16", 1.0, 0.0, "urand", None),
     "c2_4096_fp16_urand": (4096, 4096, 4096, "N", "N", "fp16", 1.0, 0.0, "urand", 1024),
     "c2_4096_bf16_urand": (4096, 4096, 4096, "N", "N", "bf16", 1.0, 0.0, "urand", 1024),
     "c3_16384_fp16_exprand15": (16384, 16384, 16384, "N", "N", "fp16", 1.0, 0.0, ((-15, 15), (-15, 15)), 512),
@@ -66,6 +69,8 @@ WORKLOADS = {
     "c5_odd_transA_bf16": (4095, 3001, 5003, "T", "N", "bf16", 1.0, 0.0, "urand", 1024),
     # not a baseline config: the size at which the one-kernel (fused) shape is compared with the split-first path
     "x_1024_fp16_urand": (1024, 1024, 1024, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_512_fp16_urand": (512, 512, 512, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_512_bf16_urand": (512, 512, 512, "N", "N", "bf16", 1.0, 0.0, "urand", None),
     # not baseline configs either: the method with the leading product accumulated outside the matrix unit, as the
     # paper's listing does against round-toward-zero, next to the default (inside) at the same size
     "x_8192_fp16_urand": (8192, 8192, 8192, "N", "N", "fp16", 1.0, 0.0, "urand", 256),
@@ -83,7 +88,7 @@ DEFAULT_WORKLOAD = "c3_16384_fp16_exprand15"
 # configuration 4 once more in the automatic mode, which runs them as FP16 on row / column scaled operands)
 OTHER_WORKLOADS = ["c4_8192_bf16_widerange", "x_8192_auto_widerange", "c2_4096_fp16_urand", "c2_4096_bf16_urand", "c5_tallskinny_fp16",
                    "c5_tallskinny_bf16", "c5_deepk_fp16", "c5_deepk_bf16", "c5_odd_transA_fp16", "c5_odd_transA_bf16",
-                   "c1_256_fp16_urand"]
+                   "c1_256_fp16_urand", "c1_256_bf16_urand"]
 OTHER_ORACLE_ROWS = 256      # the oracle's sample of rows of C for those (the headline keeps its own, larger one)
 
 PRODUCTS = {"fp16": 3, "bf16": 6, "fp16_outside": 3, "fp16_outside4": 3, "fp16_outside16": 3}
@@ -162,7 +167,7 @@ class Workload:
         self.h = ec.Handle()
         self.h.set_stream(self.stream.cuda_stream)
         self.h.set_shape({"auto": ec.SHAPE_AUTO, "w4": ec.SHAPE_256x128_W4, "x2": ec.SHAPE_128x128_X2,
-                          "fused": ec.SHAPE_64x64_FUSED}[shape])
+                          "fused": ec.SHAPE_64x64_FUSED, "fused32": ec.SHAPE_32x32_FUSED}[shape])
         if tile_order is not None:
             self.h.debug_set_tile_order(*tile_order)
         self.ws_bytes = self.h.workspace_size(self.ops[self.transA], self.ops[self.transB], self.M, self.N, self.K, self.mode_id)
@@ -240,13 +245,19 @@ class Workload:
             split_bytes += fp16_pass + (M + N) * K * 4
         if self.auto and self.mode == "bf16":      # both FP16 splits and the exponents
             split_bytes += 2 * fp16_pass + (M + N) * K * 4
+        # a small product runs as one launch that reads the FP32 operands itself: no packed copies, no split kernel
+        one_launch = (not self.auto) and self.h.plan_info(M, N, K, self.plan_mode_id)["shape"] >= 3
+        kernel = "fused_kernel" if one_launch else "product_kernel"
+        if one_launch:
+            product_bytes = (M + N) * K * 4 + M * N * 4 * (2 if self.beta != 0 else 1)
+            split_bytes, split_ms = 0, 0.0
         mfma_tflops = PRODUCTS[self.mode] * self.flops / (product_ms * 1e-3) / 1e12
         mfma = {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": PEAK_MFMA_16BIT_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(mfma_tflops / PEAK_MFMA_16BIT_TFLOPS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(self.name),
-                "kernel": "product_kernel", "flops_per_launch": PRODUCTS[self.mode] * self.flops}
+                "kernel": kernel, "flops_per_launch": PRODUCTS[self.mode] * self.flops}
         # the same kernel against the HBM roof (it matters for shallow K, where writing C is most of the bytes):
         # algorithmic bytes = packed operands once + C written once (+ read once when beta != 0)
-        hbm = {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS, "kernel": "product_kernel",
+        hbm = {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS, "kernel": kernel,
                "bytes_per_launch": product_bytes, "achieved": round(product_bytes / (product_ms * 1e-3) / 1e9, 1),
                "frac": round(product_bytes / (product_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
         # step 1 against the HBM roof: every FP32 element read once, its 16-bit parts written once
@@ -341,7 +352,7 @@ def main():
                     help="untimed warm-up steps (default: 3, more for short workloads so that the board, which drops "
                          "its clocks when idle, has run for 50 ms)")
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD, choices=sorted(WORKLOADS))
-    ap.add_argument("--shape", default="auto", choices=["auto", "w4", "x2", "fused"],
+    ap.add_argument("--shape", default="auto", choices=["auto", "w4", "x2", "fused", "fused32"],
                     help="kernel shape (ecgemm_set_shape); auto lets the library choose")
     ap.add_argument("--tile-order", default=None, metavar="REMAP,GROUP_M,BANDS",
                     help="override the order in which output tiles go to the XCDs (ecgemm_debug_set_tile_order): "
