@@ -121,7 +121,8 @@ size_t packed_bytes(int64_t rows, int64_t depth, ecgemm_mode_t mode) {
 }
 
 struct Plan {
-  const Shape* shape;  // null: the requested shape does not exist for the mode
+  const Shape* shape;  // null: the requested shape does not exist for the mode, or (too_many_tiles) cannot count this problem's tiles
+  bool too_many_tiles = false;
   int64_t Kp;
   int tiles_m, tiles_n, k_tiles;
   int full_tiles, tail_tiles, tail_splits;  // see ProductParams
@@ -146,6 +147,12 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
     return pl;
   }
   const int bm = pl.shape->bm, bn = pl.shape->bn;
+  // (check_sizes bounds the tiles of 128 x 128; the smaller tiles of the one-launch shapes must fit 32 bits as well)
+  if (((M + bm - 1) / bm) * ((N + bn - 1) / bn) > ((int64_t)1 << 30)) {
+    pl.shape = nullptr;
+    pl.too_many_tiles = true;
+    return pl;
+  }
   pl.tiles_m = (int)((M + bm - 1) / bm);
   pl.tiles_n = (int)((N + bn - 1) / bn);
   pl.k_tiles = (int)(pl.Kp / pl.shape->bk);
@@ -245,21 +252,22 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 // shapes, both modes).
 //   split first: the product estimate above, the launches (5.6 us), and the split pass, which costs about 1 us per MB
 //   of FP32 operands (1.4 us with three BF16 parts to write) until it is hidden behind the product's launch (8.5 us).
-//   one launch: 4.4 us, then per 64-deep chunk what a block needs to split its share, times how crowded the compute
-//   units are once there are more blocks than units (blocks share a unit's vector pipes; the 64 x 64 BF16 block
-//   needs 96 KiB of LDS, so a second one waits).  A last chunk that is not whole takes the slower, general split.
+//   one launch: 4.4 us, then per 64-deep chunk what a block needs to split its share (0.6 / 1.1 us for 32 / 64 tiles
+//   in FP16 mode, 0.85 / 1.55 in BF16 mode), times how crowded the compute units are once there are more blocks than
+//   units (blocks share a unit's vector pipes; the 64 x 64 BF16 block needs 96 KiB of LDS, so a second one waits).
+//   A last chunk that is not whole takes the slower, general split.
 double split_first_us(const Plan& pl, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   const double operand_mb = 4.0 * ((double)M + (double)N) * (double)K / 1e6;
   return estimated_us(pl, mode) + 5.6 + std::min(8.5, (mode == ECGEMM_MODE_BF16_FULL ? 1.4 : 1.0) * operand_mb);
 }
 double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
   const bool bf16 = mode == ECGEMM_MODE_BF16_FULL, small = pl.shape->bm == 32;
-  const double per_chunk = small ? (bf16 ? 1.3 : 0.76) : (bf16 ? 1.9 : 1.3);
+  const double per_chunk = small ? (bf16 ? 0.85 : 0.6) : (bf16 ? 1.55 : 1.1);
   const double blocks_per_unit = (double)pl.tiles_m * pl.tiles_n / kPlanComputeUnits;
   const double crowding = blocks_per_unit <= 1.0 ? 1.0
-                          : small               ? 0.55 + 0.5 * blocks_per_unit
+                          : small               ? (bf16 ? 0.95 * blocks_per_unit : 0.65 + 0.5 * blocks_per_unit)
                           : bf16                ? 1.3 * blocks_per_unit
-                                                : 0.3 + 0.75 * blocks_per_unit;
+                                                : 0.2 + 0.95 * blocks_per_unit;
   const double chunks = (double)(K / 64) + (K % 64 ? 2.5 : 0.0);
   return 4.4 + chunks * per_chunk * std::max(1.0, crowding);
 }
@@ -279,7 +287,8 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_sha
   if (!one_launch_allowed || K > 8192 || M > 16384 || N > 16384) return split_first;
   const Plan tile64 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_64x64_FUSED);
   const Plan tile32 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_32x32_FUSED);
-  const Plan one_launch = one_launch_us(tile32, K, mode) < one_launch_us(tile64, K, mode) ? tile32 : tile64;
+  // (near a tie the larger tile, which is less at the mercy of the operands' layout)
+  const Plan one_launch = one_launch_us(tile32, K, mode) < 0.95 * one_launch_us(tile64, K, mode) ? tile32 : tile64;
   return one_launch_us(one_launch, K, mode) < 0.85 * split_first_us(split_first, M, N, K, mode) ? one_launch : split_first;
 }
 
@@ -338,6 +347,12 @@ AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
 ecgemm_status_t fail(ecgemm_handle_t h, ecgemm_status_t st, const std::string& what, int argument = 0) {
   if (h) h->last_error = what, h->last_error_argument = argument;
   return st;
+}
+// the refusal of a problem for which make_plan returned no shape
+ecgemm_status_t no_plan(ecgemm_handle_t h, const Plan& pl, const char* function) {
+  return fail(h, ECGEMM_ERR_UNSUPPORTED,
+              std::string(function) + (pl.too_many_tiles ? ": M x N has more than 2^30 tiles of the handle's kernel shape"
+                                                         : ": the handle's kernel shape does not exist for this mode"));
 }
 
 // ECGEMM_ERR_INVALID_ARG for the argument at `position` of the failing function's parameter list (1 = the handle)
@@ -546,7 +561,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   void* args[] = {&fp};
   ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused->kernel[layout_a][layout_b]), dim3((unsigned)tiles),
-                                dim3(256), args, 0, h->stream));
+                                dim3((unsigned)fused_threads(pl.shape->bm)), args, 0, h->stream));
   return ECGEMM_OK;
 }
 
@@ -792,7 +807,7 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA
   }
   const ecgemm_shape_t shape = handle ? handle->shape : ECGEMM_SHAPE_AUTO;
   const Plan pl = make_plan(M, N, K, mode, shape, true);
-  if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_workspace_size: the handle's kernel shape does not exist for this mode");
+  if (!pl.shape) return no_plan(handle, pl, "ecgemm_workspace_size");
   *bytes = pl.total_bytes;
   // (ecgemm_product on the same problem never takes a one-launch shape by itself and may need room for partial sums)
   if (pl.shape->fused && shape == ECGEMM_SHAPE_AUTO) *bytes = std::max(*bytes, make_plan(M, N, K, mode, shape, false).partial_bytes);
@@ -809,7 +824,7 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, true);
-  if (!pl.shape) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_plan_info: the handle's kernel shape does not exist for this mode");
+  if (!pl.shape) return no_plan(handle, pl, "ecgemm_plan_info");
   info->shape = (int)(pl.shape - &kShapes[(int)mode][0]) + 1;
   info->tile_m = pl.shape->bm;
   info->tile_n = pl.shape->bn;
@@ -1199,7 +1214,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
   const Plan pl = make_plan(M, N, K, mode, h->shape, true);
-  if (!pl.shape) return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: the handle's kernel shape does not exist for this mode");
+  if (!pl.shape) return no_plan(h, pl, "ecgemm_sgemm");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
   SplitJob job_a, job_b;
   char* ws = nullptr;

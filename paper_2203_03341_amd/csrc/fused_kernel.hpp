@@ -4,14 +4,16 @@
 // copies in HBM, no partial sums: one launch.  Every block that touches a tile of A splits it again (N / 64 times per
 // element), so this pays where launches and latencies, not arithmetic, decide the time: small products.
 //
-// One block: 256 threads and TILE x TILE of C over the whole depth of the product, TILE = 64 (4 waves of 32 x 32, one
-// v_mfma_f32_32x32x16 accumulator pair per wave) or 32 (one wave multiplies, all four fetch and split).  Same fragment
+// One block: TILE x TILE of C over the whole depth of the product, TILE = 64 or 32, made by four waves that fetch and
+// split and, next to them on the same SIMDs, one wave per 32 x 32 of the tile that multiplies (one v_mfma_f32_32x32x16
+// accumulator pair): 8 or 5 waves.  A chain of dependent matrix instructions leaves its wave waiting most of the
+// time; with the two roles in different waves the hardware fills that time with the other wave's split.  Same fragment
 // layout in LDS, same term order and same accumulator discipline as product_kernel.hpp, so an element is summed in
 // the same order as in an unsliced tile there.  Small tiles are what make a small product many blocks, and what
 // bounds a block is its split work, (TILE + TILE) x K elements: 512^3 is 64 blocks of 64 x 64 or 256 of 32 x 32 with
 // half the work each, one per compute unit.  The host picks 32 while that still leaves compute units idle.
 //
-// Depth is walked in chunks of 64.  All 256 threads fetch the chunk's TILE x 64 values of op(A) and of op(B), TILE / 4
+// Depth is walked in chunks of 64.  The 256 splitting threads fetch the chunk's TILE x 64 values of op(A) and of op(B), TILE / 4
 // of each per thread, with the lanes of a wave along whichever index is contiguous in memory (FusedLayout); the values
 // of the next kFusedRing chunks are in flight in registers while the current one is split, written to LDS in fragment
 // order (two buffers, one barrier per chunk) and multiplied.  The split is what bounds the loop (a chunk of a 64 x 64
@@ -60,13 +62,18 @@ typedef unsigned short fused_ushort2_t __attribute__((ext_vector_type(2)));
 template <int KIND>
 struct FastSplit {
   static constexpr int kParts = parts_of_split(KIND);
-  __device__ static __forceinline__ void split2(float v0, float v1, unsigned (&out)[kParts]) {
+  // `scaled0`, `scaled1`: the same two values times 2^11 (used by kSplitFp16Scaled only), so that the scaled residual
+  // is one fused multiply-add on the packed high part: hi * -2^11 + v * 2^11 = (v - hi) * 2^11, exact like the
+  // two-step form (v * 2^11 overflows only for values whose high part is not finite, which do not end up here).
+  __device__ static __forceinline__ void split2(float v0, float v1, float scaled0, float scaled1, unsigned (&out)[kParts]) {
     if constexpr (!split_is_bf16(KIND)) {
       const fused_half2_t hi = __builtin_convertvector(fused_float2_t{v0, v1}, fused_half2_t);
       out[0] = __builtin_bit_cast(unsigned, hi);
-      if constexpr (kParts == 2) {
-        const float scale = KIND == kSplitFp16Scaled ? 2048.0f : 1.0f;
-        const fused_float2_t residual = {(v0 - (float)hi[0]) * scale, (v1 - (float)hi[1]) * scale};  // exact
+      if constexpr (KIND == kSplitFp16Scaled) {
+        const fused_float2_t residual = {__builtin_fmaf((float)hi[0], -2048.0f, scaled0), __builtin_fmaf((float)hi[1], -2048.0f, scaled1)};
+        out[1] = __builtin_bit_cast(unsigned, __builtin_convertvector(residual, fused_half2_t));
+      } else if constexpr (kParts == 2) {
+        const fused_float2_t residual = {v0 - (float)hi[0], v1 - (float)hi[1]};  // exact
         out[1] = __builtin_bit_cast(unsigned, __builtin_convertvector(residual, fused_half2_t));
       }
     } else {
@@ -111,6 +118,7 @@ struct FusedOperand {
   const float* row_ptr[ROWS];  // &X(row, 0) for each of the thread's rows
   unsigned lane_offset;        // kFusedRows: the lane's row within the tile; kFusedDepth: the lane's k within the chunk
   float factor[ROWS];          // the handle's pre-scaling times the row's own
+  bool unscaled;               // every factor is 1 (the same for the whole block)
   int64_t ld, K;
   int k_here;                  // k within the chunk of the thread's first value
   int lds_offset;              // byte offset within the operand's region of the thread's first value, part 0
@@ -118,6 +126,7 @@ struct FusedOperand {
   __device__ __forceinline__ void init(const float* src, int64_t ld_, int64_t rows, int64_t K_, int64_t tile_row0, float prescale,
                                        const int* log2_scale, int lane, int wave) {
     ld = ld_, K = K_;
+    unscaled = prescale == 1.0f && log2_scale == nullptr;
     const int rows_here = (int)(rows - tile_row0 < TILE ? rows - tile_row0 : TILE);  // >= 1
     tile = LAYOUT == kFusedRows ? src + tile_row0 : src + tile_row0 * ld;
     int first_row;  // within the tile
@@ -184,17 +193,28 @@ struct FusedOperand {
     }
   }
 
+  // The short split of all V values, with (general == true) or without the multiplication by the scaling factors.
+  template <bool GENERAL>
+  __device__ __forceinline__ void split_ordinary(const float (&x)[V], unsigned (&words)[V / 2][NP]) const {
+#pragma unroll
+    for (int e = 0; e < V / 2; ++e) {
+      const float v0 = GENERAL ? x[2 * e] * factor[(2 * e) / PER_ROW] : x[2 * e];
+      const float v1 = GENERAL ? x[2 * e + 1] * factor[(2 * e + 1) / PER_ROW] : x[2 * e + 1];
+      // (times 2^11 after the factor, not with it: a factor of 2^126 is legitimate, 2^137 is not a number)
+      FastSplit<KIND>::split2(v0, v1, v0 * 2048.0f, v1 * 2048.0f, words[e]);
+    }
+  }
+
   // Splits the values of chunk c and writes the parts to `region` where the fragment reads expect them.
   __device__ __forceinline__ void deposit(const float (&x)[V], int c, char* region) const {
-    float v[V];
-#pragma unroll
-    for (int e = 0; e < V; ++e) v[e] = x[e] * factor[e / PER_ROW];
     unsigned words[V / 2][NP];  // part q of values 2 e and 2 e + 1
     const bool whole = (int64_t)c * 64 + 64 <= K;  // block-uniform
     bool done = false;
     if (whole) {
-#pragma unroll
-      for (int e = 0; e < V / 2; ++e) FastSplit<KIND>::split2(v[2 * e], v[2 * e + 1], words[e]);
+      if (unscaled)  // block-uniform: no pre-scaling, no scaling vectors: every factor is 1
+        split_ordinary<false>(x, words);
+      else
+        split_ordinary<true>(x, words);
       done = __builtin_amdgcn_ballot_w64(!FastSplit<KIND>::high_parts_finite(words)) == 0;  // wave-uniform
     }
     if (!done) {
@@ -202,8 +222,8 @@ struct FusedOperand {
 #pragma unroll
       for (int e = 0; e < V / 2; ++e) {
         unsigned short even[NP], odd[NP];
-        Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? v[2 * e] : 0.0f, even);
-        Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? v[2 * e + 1] : 0.0f, odd);
+        Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? x[2 * e] * factor[(2 * e) / PER_ROW] : 0.0f, even);
+        Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? x[2 * e + 1] * factor[(2 * e + 1) / PER_ROW] : 0.0f, odd);
 #pragma unroll
         for (int q = 0; q < NP; ++q) words[e][q] = (unsigned)even[q] | ((unsigned)odd[q] << 16);
       }
@@ -233,8 +253,11 @@ struct FusedOperand {
   }
 };
 
+constexpr int kFusedSplitWaves = 4;
+__host__ __device__ constexpr int fused_threads(int tile) { return 64 * (kFusedSplitWaves + (tile / 32) * (tile / 32)); }
+
 template <int METHOD, int LAYOUT_A, int LAYOUT_B, int TILE>
-__global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
+__global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const FusedParams p) {
   constexpr int KIND = split_kind_of(METHOD);
   constexpr bool BF16 = split_is_bf16(KIND);
   constexpr int NP = parts_of_split(KIND), PRODUCTS = products_of(METHOD);
@@ -247,25 +270,68 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wave_m = TILE == 64 ? wave % 2 : 0, wave_n = TILE == 64 ? wave / 2 : 0;
-  const bool multiplies = TILE == 64 || wave == 0;  // wave-uniform
   int tile_m, tile_n;
   tile_coordinates((int)blockIdx.x, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
+  const int chunks = (int)((p.K + 63) / 64);  // >= 1
 
-  OperandA a;
-  OperandB b;
-  a.init(p.A, p.lda, p.M, p.K, (int64_t)tile_m * BM, p.prescale_a, p.row_log2_scale, lane, wave);
-  b.init(p.B, p.ldb, p.N, p.K, (int64_t)tile_n * BN, p.prescale_b, p.col_log2_scale, lane, wave);
-  const int chunks = (int)((p.K + 63) / 64);
+  // Every wave of the block passes exactly `chunks` barriers, whichever of the two roles it has: a splitting wave one
+  // after each chunk it has written, a multiplying wave one before each chunk it reads.  Chunk c lives in LDS buffer
+  // c % 2; a splitting wave writes chunk c + 2 there only after barrier c + 1, which the multiplying waves reach when
+  // their reads of chunk c have returned.
+  if (wave < kFusedSplitWaves) {
+    // ---- splitting waves: chunk c is split into LDS while chunks c + 1 .. c + kFusedRing travel
+    OperandA a;
+    OperandB b;
+    a.init(p.A, p.lda, p.M, p.K, (int64_t)tile_m * BM, p.prescale_a, p.row_log2_scale, lane, wave);
+    b.init(p.B, p.ldb, p.N, p.K, (int64_t)tile_n * BN, p.prescale_b, p.col_log2_scale, lane, wave);
+    static_assert(kFusedRing % 2 == 0, "a ring slot always meets the same LDS buffer");
+    float xa[kFusedRing][V], xb[kFusedRing][V];
+    // (a chunk beyond the last is requested again as the last one and never used: in the loop every fetch is
+    // unconditional; the scheduling barriers keep the requests of one ring slot together and the slots in order, which
+    // is what lets the wait in front of a slot's first use leave the younger slots' loads in flight)
+    const int last = chunks - 1;
+    static_for<kFusedRing>([&](auto r_c) {
+      constexpr int r = decltype(r_c)::value;
+      a.fetch(xa[r], r < last ? r : last), b.fetch(xb[r], r < last ? r : last);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    int c0 = 0;
+    for (; c0 + kFusedRing <= chunks; c0 += kFusedRing) {
+      static_for<kFusedRing>([&](auto r_c) {
+        constexpr int r = decltype(r_c)::value;
+        const int c = c0 + r, ahead = c + kFusedRing < last ? c + kFusedRing : last;
+        char* stage = lds + (r & 1) * STAGE_BYTES;
+        a.deposit(xa[r], c, stage);
+        b.deposit(xb[r], c, stage + REGION_BYTES);
+        __builtin_amdgcn_sched_barrier(0);
+        a.fetch(xa[r], ahead), b.fetch(xb[r], ahead);
+        __syncthreads();
+      });
+    }
+    static_for<kFusedRing - 1>([&](auto r_c) {  // the chunks left over: their values are on their way or here
+      constexpr int r = decltype(r_c)::value;
+      if (c0 + r < chunks) {  // block-uniform
+        char* stage = lds + (r & 1) * STAGE_BYTES;
+        a.deposit(xa[r], c0 + r, stage);
+        b.deposit(xb[r], c0 + r, stage + REGION_BYTES);
+        __syncthreads();
+      }
+    });
+    return;
+  }
 
+  // ---- multiplying waves: one 32 x 32 block of the tile each.  They share their SIMDs with the splitting waves, whose
+  // vector instructions fill the time that a chain of dependent matrix instructions leaves.
+  const int block = wave - kFusedSplitWaves;
+  const int wave_m = block % (TILE / 32), wave_n = block / (TILE / 32);
   float16_t acc_main, acc_corr;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc_main[v] = 0.0f, acc_corr[v] = 0.0f;
   const int a_frag_off = wave_m * K_STEPS * NP * 1024 + lane * 16;
   const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024 + lane * 16;
-  auto multiply = [&](int buf) {
-    if (!multiplies) return;
-    const char* stage = lds + buf * STAGE_BYTES;
+  for (int c = 0; c < chunks; ++c) {
+    __syncthreads();
+    const char* stage = lds + (c & 1) * STAGE_BYTES;
 #pragma unroll
     for (int ks = 0; ks < K_STEPS; ++ks) {
       frag_t fa[NP], fb[NP];
@@ -282,50 +348,13 @@ __global__ void __launch_bounds__(256, 1) fused_kernel(const FusedParams p) {
           acc_main = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_main);
       });
     }
-  };
-
-  // ---- main loop: chunk c is split into LDS buffer c % 2 and multiplied while chunks c + 1 .. c + kFusedRing travel
-  static_assert(kFusedRing % 2 == 0, "a ring slot always meets the same LDS buffer");
-  float xa[kFusedRing][V], xb[kFusedRing][V];
-  // (a chunk beyond the last is requested again as the last one and never used: in the loop every fetch is
-  // unconditional; the scheduling barriers keep the requests of one ring slot together and the slots in order, which
-  // is what lets the wait in front of a slot's first use leave the younger slots' loads in flight)
-  const int last = chunks - 1;
-  static_for<kFusedRing>([&](auto r_c) {
-    constexpr int r = decltype(r_c)::value;
-    a.fetch(xa[r], r < last ? r : last), b.fetch(xb[r], r < last ? r : last);
-    __builtin_amdgcn_sched_barrier(0);
-  });
-  int c0 = 0;
-  for (; c0 + kFusedRing <= chunks; c0 += kFusedRing) {
-    static_for<kFusedRing>([&](auto r_c) {
-      constexpr int r = decltype(r_c)::value;
-      const int c = c0 + r, ahead = c + kFusedRing < last ? c + kFusedRing : last;
-      char* stage = lds + (r & 1) * STAGE_BYTES;
-      a.deposit(xa[r], c, stage);
-      b.deposit(xb[r], c, stage + REGION_BYTES);
-      __builtin_amdgcn_sched_barrier(0);
-      a.fetch(xa[r], ahead), b.fetch(xb[r], ahead);
-      __syncthreads();
-      multiply(r & 1);
-    });
   }
-  static_for<kFusedRing - 1>([&](auto r_c) {  // the chunks left over: their values are on their way or here
-    constexpr int r = decltype(r_c)::value;
-    if (c0 + r < chunks) {  // block-uniform
-      char* stage = lds + (r & 1) * STAGE_BYTES;
-      a.deposit(xa[r], c0 + r, stage);
-      b.deposit(xb[r], c0 + r, stage + REGION_BYTES);
-      __syncthreads();
-      multiply(r & 1);
-    }
-  });
 
-  // ---- epilogue, as in product_kernel: lane l holds row m_base and columns n_base + 8 (v / 4) + v % 4
+  // ---- epilogue, as in product_kernel: lane l holds row m and columns n_base + 8 (v / 4) + v % 4
   const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
   const int64_t m = (int64_t)tile_m * BM + wave_m * 32 + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * BN + wave_n * 32 + 4 * (lane >> 5);
-  if (!multiplies || m >= p.M) return;
+  if (m >= p.M) return;
   const int row_exponent = p.row_log2_scale != nullptr ? p.row_log2_scale[m] : 0;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
