@@ -533,8 +533,12 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
 // Steps 1 to 5 in one kernel, on the caller's FP32 operands (small products).
 ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                              int64_t K, float alpha, const float* A, int64_t lda, const float* B, int64_t ldb, float beta,
-                             float* C, int64_t ldc, const int* row_log2_scale, const int* col_log2_scale) {
+                             float* C, int64_t ldc, const int* row_log2_scale, const int* col_log2_scale,
+                             const int* gate = nullptr, int gate_value = 0, int gate_value_scaled = 0) {
   FusedParams fp;
+  fp.gate = gate;  // (with a gate: gate_value runs without the scaling vectors, gate_value_scaled with them)
+  fp.gate_value = gate_value;
+  fp.gate_value_scaled = gate_value_scaled;
   fp.row_log2_scale = row_log2_scale;
   fp.col_log2_scale = col_log2_scale;
   fp.A = A;
@@ -1151,20 +1155,34 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
                        (int)kChoiceBf16, (const int*)choice, (int)kChoiceUndecided);
     ECGEMM_HIP(h, hipGetLastError());
   }
-  st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);
-  if (st != ECGEMM_OK) return st;
-  if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
-  const int log2_out_scale = -(h->log2_scale_a + h->log2_scale_b);
-  st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
-                      log2_out_scale, nullptr, nullptr, choice, kChoiceFp16);
-  if (st != ECGEMM_OK) return st;
-  if (try_scaled) {
-    st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
-                        log2_out_scale, scales_a, scales_b, choice, kChoiceFp16Scaled);
+  // Every candidate runs the way ecgemm_sgemm would run it in that mode, so that the result is that call's bit for
+  // bit: a small product as one launch on the FP32 operands (the measuring splits above still write their packed
+  // parts, which nothing reads then), the others with the product kernels on the packed operands.
+  const Plan one_fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, h->shape, true);
+  const Plan one_bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, h->shape, true);
+  const bool fp16_one_launch = one_fp16.shape && one_fp16.shape->fused, bf16_one_launch = one_bf16.shape && one_bf16.shape->fused;
+  if (!bf16_one_launch) {
+    st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);
     if (st != ECGEMM_OK) return st;
   }
-  st = launch_product(h, ap.bf16, M, N, alpha, ws, ws + ap.bf16.a_bytes, beta, C, ldc, ECGEMM_MODE_BF16_FULL, partials,
-                      log2_out_scale, nullptr, nullptr, choice, kChoiceBf16);
+  if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));
+  const int log2_out_scale = -(h->log2_scale_a + h->log2_scale_b);
+  if (fp16_one_launch) {  // with and without the scaling vectors in one launch, which looks at the choice itself
+    st = launch_fused(h, one_fp16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, try_scaled ? scales_a : nullptr,
+                      try_scaled ? scales_b : nullptr, choice, kChoiceFp16, try_scaled ? kChoiceFp16Scaled : kChoiceFp16);
+    if (st != ECGEMM_OK) return st;
+  } else {
+    for (int scaled = 0; scaled <= (try_scaled ? 1 : 0); ++scaled) {
+      st = launch_product(h, ap.fp16, M, N, alpha, ws, ws + ap.fp16.a_bytes, beta, C, ldc, ECGEMM_MODE_FP16_SPLIT, partials,
+                          log2_out_scale, scaled ? scales_a : nullptr, scaled ? scales_b : nullptr, choice,
+                          scaled ? kChoiceFp16Scaled : kChoiceFp16);
+      if (st != ECGEMM_OK) return st;
+    }
+  }
+  st = bf16_one_launch ? launch_fused(h, one_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, nullptr, nullptr, choice,
+                                      kChoiceBf16, kChoiceBf16)
+                       : launch_product(h, ap.bf16, M, N, alpha, ws, ws + ap.bf16.a_bytes, beta, C, ldc, ECGEMM_MODE_BF16_FULL, partials,
+                                        log2_out_scale, nullptr, nullptr, choice, kChoiceBf16);
   if (st != ECGEMM_OK) return st;
   if (timing) {
     ECGEMM_HIP(h, hipEventRecord(tc.product_done, h->stream));

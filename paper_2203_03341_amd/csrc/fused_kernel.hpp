@@ -13,13 +13,14 @@
 // bounds a block is its split work, (TILE + TILE) x K elements: 512^3 is 64 blocks of 64 x 64 or 256 of 32 x 32 with
 // half the work each, one per compute unit.  The host picks 32 while that still leaves compute units idle.
 //
-// Depth is walked in chunks of 64.  The 256 splitting threads fetch the chunk's TILE x 64 values of op(A) and of op(B), TILE / 4
-// of each per thread, with the lanes of a wave along whichever index is contiguous in memory (FusedLayout); the values
-// of the next kFusedRing chunks are in flight in registers while the current one is split, written to LDS in fragment
-// order (two buffers, one barrier per chunk) and multiplied.  The split is what bounds the loop (a chunk of a 64 x 64
-// tile is 8192 elements per block against 12 or 24 matrix instructions per wave), so it takes a short form (FastSplit, 5 to 7
-// vector instructions per element) whenever every value a wave holds is ordinary, and Splitter, which saturates and
-// handles infinities and NaN, otherwise; both give the same bits on the values the short form accepts.
+// Depth is walked in chunks of 64.  The 256 splitting threads fetch the chunk's TILE x 64 values of op(A) and of
+// op(B), TILE / 4 of each per thread, with the lanes of a wave along whichever index is contiguous in memory
+// (FusedLayout); the values of the next kFusedRing chunks are in flight in registers while the current one is split
+// and written to LDS in fragment order (two buffers, one barrier per chunk), where the multiplying waves pick it up.
+// The split is what bounds the loop (a chunk of a 64 x 64 tile is 8192 elements per block against 12 or 24 matrix
+// instructions per multiplying wave), so it takes a short form (FastSplit, 3.5 to 7.5 vector instructions per
+// element) whenever every value a wave holds is ordinary, and Splitter, which saturates and handles infinities and
+// NaN, otherwise; both give the same bits on the values the short form accepts.
 #pragma once
 #include "product_kernel.hpp"
 
@@ -46,6 +47,10 @@ struct FusedParams {
   const int* row_log2_scale;  // device, M entries
   const int* col_log2_scale;  // device, N entries
   float* C;
+  // Automatic mode choice only, else null: the kernel runs without the scaling vectors if *gate == gate_value, with
+  // them if *gate == gate_value_scaled, and does nothing otherwise
+  const int* gate;
+  int gate_value, gate_value_scaled;
 };
 
 // The split for values that need no care, two at a time (the two 16-bit results of a part share a register: out[q]
@@ -257,7 +262,15 @@ constexpr int kFusedSplitWaves = 4;
 __host__ __device__ constexpr int fused_threads(int tile) { return 64 * (kFusedSplitWaves + (tile / 32) * (tile / 32)); }
 
 template <int METHOD, int LAYOUT_A, int LAYOUT_B, int TILE>
-__global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const FusedParams p) {
+__global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const FusedParams params) {
+  FusedParams p = params;
+  if (p.gate != nullptr) {  // the same for every thread of the grid, and before any barrier
+    const int choice = *p.gate;
+    if (choice == p.gate_value)
+      p.row_log2_scale = p.col_log2_scale = nullptr;
+    else if (choice != p.gate_value_scaled)
+      return;
+  }
   constexpr int KIND = split_kind_of(METHOD);
   constexpr bool BF16 = split_is_bf16(KIND);
   constexpr int NP = parts_of_split(KIND), PRODUCTS = products_of(METHOD);

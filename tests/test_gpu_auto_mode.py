@@ -112,6 +112,30 @@ def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
     h.destroy()
 
 
+def test_each_candidate_runs_as_its_fixed_mode_would():
+    """Sizes that a fixed mode runs as one launch on the FP32 operands (256^3), with the split-first kernels (1536^3),
+    and 1024^3, where the FP16 mode takes one launch and the BF16 mode splits first: whichever candidate wins runs
+    that way, so that the bits are the fixed mode's.  (The checks are those of every other case here: the oracle's
+    choice, bit equality with the direct call, the accuracy bar.)"""
+    import paper_2203_03341_amd as ec
+    h = ec.Handle()
+    one_launch = lambda n, mode: h.plan_info(n, n, n, mode)["shape"] >= ec.SHAPE_64x64_FUSED
+    assert one_launch(256, ec.MODE_FP16_SPLIT) and one_launch(256, ec.MODE_BF16_FULL)
+    assert one_launch(1024, ec.MODE_FP16_SPLIT) and not one_launch(1024, ec.MODE_BF16_FULL)
+    assert not one_launch(1536, ec.MODE_FP16_SPLIT) and not one_launch(1536, ec.MODE_BF16_FULL)
+    chosen = []
+    for n in (256, 1024, 1536):
+        chosen.append(_check(h, "N", "N", n, n, n, "urand", "urand", seed=21))       # plain FP16
+        chosen.append(_check(h, "N", "N", n, n, n, TYPE3, TYPE3, seed=22))           # FP16 on scaled operands
+    assert chosen == ["fp16", "fp16 scaled"] * 3
+    # the BF16 candidate: rows too short for the pair to match an FP32 sum (K = 8), at a size of one launch and at
+    # 1024 x 1024 x 8, and then a shape whose BF16 plan splits first
+    chosen = [_check(h, "N", "T", 256, 256, 8, TYPE3, TYPE3, seed=23), _check(h, "T", "N", 2500, 2500, 8, TYPE3, TYPE3, seed=24)]
+    assert chosen == ["bf16"] * 2
+    assert h.plan_info(256, 256, 8, ec.MODE_BF16_FULL)["shape"] >= ec.SHAPE_64x64_FUSED and h.plan_info(2500, 2500, 8, ec.MODE_BF16_FULL)["shape"] < ec.SHAPE_64x64_FUSED
+    h.destroy()
+
+
 def test_sliced_tiles_large_operands_and_the_builtin_workspace():
     """Deep K (tiles sliced along K, gated reduction kernels), operands of more than 8192 split blocks (one launch per
     operand instead of the pair launch), and the entry point that allocates nothing."""

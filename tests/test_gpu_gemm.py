@@ -299,12 +299,15 @@ def test_bitwise_reproducible_and_stream(mode):
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-def test_a_call_can_be_captured_in_a_graph_and_replayed(mode):
+@pytest.mark.parametrize("size", [(1024, 768, 1536), (300, 200, 260)])
+def test_a_call_can_be_captured_in_a_graph_and_replayed(mode, size):
     """With a caller workspace the call only launches kernels (no allocation, no memset, no wait), so it can be recorded
-    into a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager bits."""
+    into a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager bits.
+    The first size runs as split pair + product with every tile sliced along K + reduction, three kernels; the second
+    as one launch that needs no workspace."""
     import torch
     import paper_2203_03341_amd as ec
-    M, N, K = 1024, 768, 1536          # split pair + product with every tile sliced along K + reduction: three kernels
+    M, N, K = size
     A, B = _inputs(M, N, K, "N", "T", "urand", 12)
     C = si.urand(M, N, 12, si.ID_C)
     mode_id = _modes()[mode]
@@ -312,8 +315,9 @@ def test_a_call_can_be_captured_in_a_graph_and_replayed(mode):
     stream = torch.cuda.Stream()
     h.set_stream(stream.cuda_stream)
     nbytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode_id)
-    workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    h.set_workspace(workspace, nbytes)
+    assert (nbytes == 0) == (h.plan_info(M, N, K, mode_id)["shape"] >= ec.SHAPE_64x64_FUSED) == (M == 300)
+    workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    h.set_workspace(workspace, max(nbytes, 256))
     dA, dB, dC_in = to_device(A), to_device(B), to_device(C)
     dC = torch.empty_like(dC_in)
     other = torch.empty_like(dC_in)
@@ -517,7 +521,8 @@ def test_one_launch_shape_splits_like_the_split_kernels(mode, transA, transB, pa
     M, N, K = 150, 200, 300
     A, B = _inputs(M, N, K, transA, transB, "urand", 31, pad)
     opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)   # views: writes go to A and B
-    awkward = np.array([70000.0, -65520.0, 65519.0, 3.39e38, -3.4e38, np.inf, -np.inf, 1e-41, 65504.0, 1e30], dtype=np.float32)
+    awkward = np.array([70000.0, -65520.0, 65519.0, 3.39e38, -3.4e38, np.inf, -np.inf, 1e-41, 65504.0, 1e30,
+                        1e-6, -3e-8, 6.1e-5, 5.96e-8, -8.9e-8, 2.0 ** -14, 2.0 ** -126], dtype=np.float32)   # last row: FP16 subnormals
     rng = np.random.default_rng(5)
     for op, rows, cols in ((opA, M, K), (opB, K, N)):
         for v in awkward:
