@@ -80,7 +80,7 @@ constexpr Shape shape_of(int persistent_max_k) {
                Cfg::THREADS, Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
 inline Shape fused_shape(const FusedKernels* kernels, int tile) {  // never sliced: no partial sums, no second kernel
-  return Shape{nullptr, nullptr, kernels, nullptr, tile, tile, 32, 256, 1, 0};
+  return Shape{nullptr, nullptr, kernels, nullptr, tile, tile, 32, fused_threads(tile), 1, 0};
 }
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 constexpr int kShapeCount = 4;
@@ -565,7 +565,7 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   void* args[] = {&fp};
   ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused->kernel[layout_a][layout_b]), dim3((unsigned)tiles),
-                                dim3((unsigned)fused_threads(pl.shape->bm)), args, 0, h->stream));
+                                dim3((unsigned)pl.shape->threads), args, 0, h->stream));
   return ECGEMM_OK;
 }
 
