@@ -215,6 +215,51 @@ def test_split_edge_values():
     assert np.all(np.isfinite(v16)) and np.all(np.isfinite(dv16))
 
 
+def test_the_saturating_splits_reduce_to_the_plain_equations_where_nothing_saturates():
+    """Eqs. corr-1-1024 .. corr-4-1024 as printed have no clamps; the oracle's splits add them for values the format
+    cannot hold.  Wherever plain round-to-nearest conversion of the input gives a finite high part (|x| < 65520 for
+    FP16, |x| below the midpoint between the largest BF16 number and 2^128 for BF16), the clamps and the infinity
+    rule must be inactive: the parts equal those of the printed equations written out with numpy's own conversions,
+    bit for bit.  (The one-launch kernel relies on exactly this to split ordinary values without the clamps.)  Also
+    the scaled residual as one fused operation, hi * -2^11 + x * 2^11 rounded once, is the two-step (x - hi) * 2^11."""
+    rng = np.random.default_rng(3)
+    x = np.concatenate([
+        (rng.standard_normal(200000) * np.exp2(rng.uniform(-40, 15.9, 200000))).astype(np.float32),
+        np.array([65504.0, 65519.996, -65519.996, 65505.0, 2.0 ** -14, 2.0 ** -24, 2.0 ** -25, 6.1e-5, 5.96e-8, 1e-41, 0.0, -0.0,
+                  2.0 ** -126, 1.0, -3.0], dtype=np.float32)])
+    x = x[np.abs(x) < np.float32(65520.0)]
+    with np.errstate(over="ignore"):
+        hi = x.astype(np.float16)
+    assert np.all(np.isfinite(hi))
+    residual = (x - hi.astype(np.float32)) * np.float32(2048.0)
+    lo = residual.astype(np.float16)
+    v16, dv16 = split.split_fp16(x)
+    assert np.array_equal(v16.view(np.uint16), hi.view(np.uint16)) and np.array_equal(dv16.view(np.uint16), lo.view(np.uint16))
+    fused = (hi.astype(np.float64) * -2048.0 + x.astype(np.float64) * 2048.0).astype(np.float32)   # exact in FP64, one rounding
+    assert np.array_equal(fused.view(np.uint32), residual.view(np.uint32))
+    # beyond that bound the two differ: the plain conversion overflows, the oracle saturates
+    over = np.array([65520.0, -70000.0, 1e10], dtype=np.float32)
+    with np.errstate(over="ignore"):
+        assert np.all(np.isinf(over.astype(np.float16))) and np.all(np.isfinite(split.split_fp16(over)[0]))
+    # the BF16 triple: plain nearest-even conversions (add half an ulp of the kept part, truncate) and plain residuals
+    def bf16_plain(v):
+        u = v.view(np.uint32).astype(np.uint64)
+        return (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) & 0xFFFF).astype(np.uint16)
+    with np.errstate(over="ignore"):
+        y = np.concatenate([(rng.standard_normal(200000) * np.exp2(rng.uniform(-120, 127, 200000))).astype(np.float32),
+                            np.array([3.38e38, -3.38e38, 1e-45, 2.0 ** -126, 0.0, 1.0], dtype=np.float32)])
+    y = y[np.isfinite(y)]
+    y = y[(bf16_plain(y) & 0x7F80) != 0x7F80]               # the plain conversion stays finite
+    assert len(y) > 190000
+    b0 = bf16_plain(y)
+    r1 = y - split.bf16_bits_to_fp32(b0)
+    b1 = bf16_plain(r1)
+    r2 = r1 - split.bf16_bits_to_fp32(b1)
+    b2 = bf16_plain(r2)
+    o0, o1, o2 = split.split_bf16x3(y)
+    assert np.array_equal(o0, b0) and np.array_equal(o1, b1) and np.array_equal(o2, b2)
+
+
 def test_split_of_nan_is_nan_in_every_part():
     """Reading for non-numbers: a NaN input gives a NaN in every part of either split (so that whichever products are
     kept, the NaN reaches C); an infinity keeps only its high part (pinned in test_split_edge_values)."""
