@@ -19,7 +19,8 @@
  * the middle of the call: kernels enqueued before that point still run, and the contents of C and of the workspace
  * are then unspecified.  A handle may be used by one host thread at a time.
  *
- * Workspace.  Every product needs device memory for the split operands (ecgemm_workspace_size).  Either the caller
+ * Workspace.  A product needs device memory for the split operands (ecgemm_workspace_size; a small product, which
+ * runs as a single kernel that reads A and B itself, needs none in the modes of the method).  Either the caller
  * provides it (ecgemm_set_workspace), or the handle allocates it on first need and keeps it; whenever a call needs
  * more than the handle holds, that call waits for the handle's stream, frees the old buffer and allocates a larger
  * one (hipStreamSynchronize, hipFree, hipMalloc) before it enqueues anything.  With a caller-provided workspace and
@@ -150,7 +151,8 @@ ecgemm_status_t ecgemm_set_workspace(ecgemm_handle_t handle, void *device_buffer
  *      not propagate when beta == 0), written for all M x N elements.  C must not overlap A or B.
  *   alpha, beta: host scalars.
  *
- * Steps (each a kernel on the handle's stream; the fused kernel shape does all three in one):
+ * Steps (each a kernel on the handle's stream; for a small product, up to about 1024^3, one kernel does all three:
+ * it reads A and B itself and forms the parts in registers, as the paper's own kernel does, with the same result):
  *   1. split: A and B are read once and written to the workspace as FP16 (v16, dv16 = (v - v16) * 2^11;
  *      Eqs. corr-1-1024 .. corr-4-1024) or as three BF16 terms, round to nearest even, K-contiguous,
  *      in the lane order the matrix instruction wants, zero-padded to tile multiples.  A finite input
@@ -217,10 +219,10 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
  * and run at the FP16 mode's speed.  What the scaled FP16 mode does not give is element-wise accuracy for elements far
  * below their row's or column's largest: a caller who needs every element of A and B honoured to 24 bits whatever its
  * size asks for ECGEMM_MODE_BF16_FULL.  Cost over calling the chosen arrangement directly: the statistics in the split
- * (it stays bound by memory traffic), about a dozen kernel launches that do nothing, and for the later candidates the
+ * (it stays bound by memory traffic), eight to a dozen kernel launches that do nothing, and for the later candidates the
  * splits that are thrown away.  Workspace: that of the BF16 mode plus 24 bytes per 64 x 32 block of each operand, 4 (M + N)
  * bytes and 256 (ecgemm_workspace_size with ECGEMM_MODE_AUTO).  Not available with caller-given scaling vectors,
- * ecgemm_split / ecgemm_product, ecgemm_plan_info or the fused kernel shape (ECGEMM_ERR_UNSUPPORTED or
+ * ecgemm_split / ecgemm_product, ecgemm_plan_info or a forced one-launch kernel shape (ECGEMM_ERR_UNSUPPORTED or
  * ECGEMM_ERR_INVALID_ARG for the mode).
  *
  * ecgemm_auto_choice reports what the handle's last ecgemm_sgemm / ecgemm_sgemm_noalloc call chose: the mode, and
