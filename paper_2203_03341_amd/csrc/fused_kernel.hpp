@@ -262,6 +262,7 @@ struct FusedOperand {
 };
 
 constexpr int kFusedSplitWaves = 4;
+constexpr int kFusedSliceChunks = 8;  // chunks of 64 per slice of the depth (see the multiplying waves)
 __host__ __device__ constexpr int fused_threads(int tile) { return 64 * (kFusedSplitWaves + (tile / 32) * (tile / 32)); }
 
 template <int METHOD, int LAYOUT_A, int LAYOUT_B, int TILE>
@@ -343,6 +344,15 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   float16_t acc_main, acc_corr;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc_main[v] = 0.0f, acc_corr[v] = 0.0f;
+  // The depth is added up in slices of kFusedSliceChunks chunks (512 deep, as shallow as the split-first plans ever
+  // slice a tile): the sum of a slice, main + correction, joins `sliced` in ascending order and the accumulators start
+  // again from zero.  The error of the matrix unit's accumulation grows with the length of the sum (the paper's
+  // section "Avoiding RZ during Tensor Core accumulation"); at K = 1024 one accumulator over the whole depth gave a
+  // relative residual of 2.15e-07 where two slices give 1.65e-07.  Up to 512 deep there is one slice and the bits are
+  // those of an unsliced tile of the product kernels.
+  const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
+  float sliced[16];
+  bool earlier_slices = false;  // block-uniform
   const int a_frag_off = wave_m * K_STEPS * NP * 1024 + lane * 16;
   const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024 + lane * 16;
   for (int c = 0; c < chunks; ++c) {
@@ -364,10 +374,18 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
           acc_main = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_main);
       });
     }
+    if (c % kFusedSliceChunks == kFusedSliceChunks - 1 && c + 1 < chunks) {  // a slice is complete and another follows
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float slice = acc_main[v] + acc_corr[v] * corr_scale;
+        sliced[v] = earlier_slices ? sliced[v] + slice : slice;
+        acc_main[v] = 0.0f, acc_corr[v] = 0.0f;
+      }
+      earlier_slices = true;
+    }
   }
 
   // ---- epilogue, as in product_kernel: lane l holds row m and columns n_base + 8 (v / 4) + v % 4
-  const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
   const int64_t m = (int64_t)tile_m * BM + wave_m * 32 + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * BN + wave_n * 32 + 4 * (lane >> 5);
   if (m >= p.M) return;
@@ -376,7 +394,8 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   for (int v = 0; v < 16; ++v) {
     const int64_t n = n_base + 8 * (v / 4) + (v % 4);
     if (n < p.N) {
-      float c = (acc_main[v] + acc_corr[v] * corr_scale) * p.out_scale;
+      const float last_slice = acc_main[v] + acc_corr[v] * corr_scale;
+      float c = (earlier_slices ? sliced[v] + last_slice : last_slice) * p.out_scale;
       // rows of op(A) and columns of op(B) were scaled one by one before the split: undo that per element
       if (p.row_log2_scale != nullptr) c = unscale(c, row_exponent, p.col_log2_scale[n]);
       float* dst = p.C + m + n * p.ldc;

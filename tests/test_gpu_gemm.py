@@ -838,24 +838,18 @@ def test_row_and_column_scaling_for_rows_of_different_magnitude(transA, transB):
         lost = ~np.isfinite(plain) | (plain > 10 * r_cpu)
     assert np.mean(lost[live]) > 0.5                                 # most rows are lost without the scaling
     assert gemm.relative_residual(c64, scaled) <= RATIO * gemm.relative_residual(c64, c32)
-    # Row by row.  With the split-first shapes, which slice this depth in two, every single row is as good as FP32's
-    # (within a factor of two).  The one-launch shapes, which the library takes for this size by itself, scale in their
-    # own split and never slice along K: all 69 k steps of an element go through one accumulator of the matrix unit,
-    # and the error of that accumulation grows with its length (the paper's section "Avoiding RZ during Tensor Core
-    # accumulation").  The residual over all of C still meets the bar (0.42 of FP32's against 0.25); a single row may
-    # exceed twice FP32's (measured: one of 520, 3.0 times).  Where nothing is sliced every shape gives the same bits.
-    assert np.all(r_gpu[live] <= 4.0 * r_cpu[live] + 1e-12) and np.mean(r_gpu[live] <= 2.0 * r_cpu[live] + 1e-12) > 0.99
-    for split_first in (ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4):
-        h.set_shape(split_first)
-        r_split_first = row_residuals(run(True))
-        assert np.all(r_split_first[live] <= 2.0 * r_cpu[live] + 1e-12)
-    for one_launch in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):
-        h.set_shape(one_launch)
-        fused = run(True)
-        r_fused = row_residuals(fused)
-        assert np.all(np.isfinite(fused)) and np.all(r_fused[live] <= 4.0 * r_cpu[live] + 1e-12)
-        assert np.mean(r_fused[live] <= 2.0 * r_cpu[live] + 1e-12) > 0.99
-        assert gemm.relative_residual(c64, fused) <= RATIO * gemm.relative_residual(c64, c32)
+    # Row by row: every single row is as good as FP32's (within a factor of two), whichever shape runs it.  The
+    # library takes a one-launch shape for this size by itself; that kernel scales in its own split and adds the depth
+    # up in slices of 512, as the split-first shapes slice this depth in two, because the error of the matrix unit's
+    # accumulation grows with the length of the sum (the paper's section "Avoiding RZ during Tensor Core
+    # accumulation"; with one accumulator over all 69 k steps one row of 520 came out at 3.0 times FP32's).
+    # Where nothing is sliced every shape gives the same bits.
+    assert np.all(r_gpu[live] <= 2.0 * r_cpu[live] + 1e-12)
+    for shape in (ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4, ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):
+        h.set_shape(shape)
+        forced = run(True)
+        assert np.all(np.isfinite(forced)) and np.all(row_residuals(forced)[live] <= 2.0 * r_cpu[live] + 1e-12)
+        assert gemm.relative_residual(c64, forced) <= RATIO * gemm.relative_residual(c64, c32)
     shallow = 96                                                      # too shallow for any shape to slice
     outs = []
     for shape in (ec.SHAPE_64x64_FUSED, ec.SHAPE_128x128_X2, ec.SHAPE_256x128_W4, ec.SHAPE_32x32_FUSED):
