@@ -1138,21 +1138,27 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   }
   st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, fp16_a, &fp16_b, true);
   if (st != ECGEMM_OK) return st;
+  // (operands with few rows: the first choice also turns the rows' exponents into factors, which saves a launch)
+  const bool finish_with_choice = try_scaled && M + N <= 4096;
+  const RowScaleJob no_rows{};
   hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, fp16_a.blocks, (double)M, stats_b,
                      fp16_b.blocks, (double)N, kAutoTolerance, kAutoMinTerms, choice, (int)kChoiceFp16,
-                     (int)(try_scaled ? kChoiceUndecided : kChoiceBf16), (const int*)nullptr, 0);
+                     (int)(try_scaled ? kChoiceUndecided : kChoiceBf16), (const int*)nullptr, 0,
+                     finish_with_choice ? rows_a : no_rows, finish_with_choice ? rows_b : no_rows);
   ECGEMM_HIP(h, hipGetLastError());
   h->auto_choice = choice;
   if (try_scaled) {
     // the exponents are found on the operands as the caller passed them; the handle's global pre-scaling, a common
     // factor of every row, comes on top in the split and is undone with the product's output scale
-    st = launch_row_scales(h, rows_a, rows_b, choice, kChoiceUndecided, kRowScaleFinish);
-    if (st != ECGEMM_OK) return st;
+    if (!finish_with_choice) {
+      st = launch_row_scales(h, rows_a, rows_b, choice, kChoiceUndecided, kRowScaleFinish);
+      if (st != ECGEMM_OK) return st;
+    }
     st = launch_split(h, ECGEMM_MODE_FP16_SPLIT, scaled_a, &scaled_b, true);
     if (st != ECGEMM_OK) return st;
     hipLaunchKernelGGL(choose_mode_kernel, dim3(1), dim3(1024), 0, h->stream, stats_a, scaled_a.blocks, (double)M, stats_b,
                        scaled_b.blocks, (double)N, kAutoTolerance, kAutoMinTerms, choice, (int)kChoiceFp16Scaled,
-                       (int)kChoiceBf16, (const int*)choice, (int)kChoiceUndecided);
+                       (int)kChoiceBf16, (const int*)choice, (int)kChoiceUndecided, no_rows, no_rows);
     ECGEMM_HIP(h, hipGetLastError());
   }
   // Every candidate runs the way ecgemm_sgemm would run it in that mode, so that the result is that call's bit for

@@ -97,12 +97,8 @@ __global__ void __launch_bounds__(256) row_max_exponent_kernel(const RowScaleJob
   }
 }
 
-// (3) in place: the exponent that moves the row's largest binade to 2^target (0 for a row without non-zero finite
-// elements), kept inside what one power-of-two factor can express.
-__global__ void __launch_bounds__(256) row_scales_finish_kernel(const RowScaleJob a, const RowScaleJob b, const int* gate,
-                                                                int gate_value) {
-  if (!gate_open(gate, gate_value)) return;
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+// Step (3) for entry i of the two jobs' rows taken together (a's first).
+__device__ __forceinline__ void finish_row_scale(const RowScaleJob& a, const RowScaleJob& b, int64_t i) {
   const bool second = i >= a.rows;
   const RowScaleJob& job = second ? b : a;
   const int64_t r = second ? i - a.rows : i;
@@ -111,6 +107,15 @@ __global__ void __launch_bounds__(256) row_scales_finish_kernel(const RowScaleJo
   int e = hi == -0x7fffffff - 1 ? 0 : job.target - hi;
   e = e < -126 ? -126 : e > 126 ? 126 : e;
   job.scale[r] = e;
+}
+
+// (3) in place: the exponent that moves the row's largest binade to 2^target (0 for a row without non-zero finite
+// elements), kept inside what one power-of-two factor can express.
+__global__ void __launch_bounds__(256) row_scales_finish_kernel(const RowScaleJob a, const RowScaleJob b, const int* gate,
+                                                                int gate_value) {
+  if (!gate_open(gate, gate_value)) return;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  finish_row_scale(a, b, i);
 }
 
 // One v_mfma_f32_32x32x16 per wave on caller-supplied registers, for tests that pin down what the matrix unit does
@@ -170,11 +175,15 @@ __global__ void __launch_bounds__(256, 1) mfma_rate_kernel(const unsigned short*
 //     by a handful of terms is rounded a handful of times by FP32 and is better served by the exact three-term split.
 // One block of 1024 threads; every sum in a fixed order, so that equal inputs give an equal choice.  A NaN anywhere
 // gives if_not.  Gated like the other kernels, on the word it writes: the second round runs only if the first failed.
+// If it does not fit and `finish_a` / `finish_b` have rows, the block goes on to turn their rows' largest exponents
+// into scaling exponents (step 3 of the row scales: for operands with few rows, where that saves a launch).
 __global__ void __launch_bounds__(1024) choose_mode_kernel(const double* __restrict__ stats_a, unsigned blocks_a, double rows_a,
                                                            const double* __restrict__ stats_b, unsigned blocks_b, double rows_b,
                                                            double tolerance, double min_terms, int* __restrict__ choice,
-                                                           int if_fits, int if_not, const int* gate, int gate_value) {
+                                                           int if_fits, int if_not, const int* gate, int gate_value,
+                                                           const RowScaleJob finish_a, const RowScaleJob finish_b) {
   if (!gate_open(gate, gate_value)) return;
+  __shared__ int chosen;
   constexpr int kThreads = 1024, kS = kStatsPerBlock;
   __shared__ double partial[kThreads][2 * kS];
   // Thread t adds entries t, t + 1024, ... of an operand in that order; eight of them are fetched at a time (a large
@@ -218,8 +227,12 @@ __global__ void __launch_bounds__(1024) choose_mode_kernel(const double* __restr
     // (sum |x|)^2 >= min_terms rows sum x^2, for either operand; an all-zero operand has nothing to lose
     const bool spread = a[2] * a[2] >= min_terms * rows_a * a[1] || b[2] * b[2] >= min_terms * rows_b * b[1] ||
                         a[1] == 0.0 || b[1] == 0.0;
-    *choice = (represented && spread) ? if_fits : if_not;
+    chosen = (represented && spread) ? if_fits : if_not;
+    *choice = chosen;
   }
+  __syncthreads();
+  if (chosen == if_not)
+    for (int64_t i = threadIdx.x; i < finish_a.rows + finish_b.rows; i += kThreads) finish_row_scale(finish_a, finish_b, i);
 }
 
 }  // namespace ecgemm
