@@ -219,7 +219,7 @@ ecgemm_status_t ecgemm_sgemm_noalloc(ecgemm_handle_t handle, ecgemm_op_t transA,
  * and run at the FP16 mode's speed.  What the scaled FP16 mode does not give is element-wise accuracy for elements far
  * below their row's or column's largest: a caller who needs every element of A and B honoured to 24 bits whatever its
  * size asks for ECGEMM_MODE_BF16_FULL.  Cost over calling the chosen arrangement directly: the statistics in the split
- * (it stays bound by memory traffic), eight to a dozen kernel launches that do nothing, and for the later candidates the
+ * (it stays bound by memory traffic), seven to a dozen kernel launches, most of which do nothing, and for the later candidates the
  * splits that are thrown away.  Workspace: that of the BF16 mode plus 24 bytes per 64 x 32 block of each operand, 4 (M + N)
  * bytes and 256 (ecgemm_workspace_size with ECGEMM_MODE_AUTO).  Not available with caller-given scaling vectors,
  * ecgemm_split / ecgemm_product, ecgemm_plan_info or a forced one-launch kernel shape (ECGEMM_ERR_UNSUPPORTED or
