@@ -543,6 +543,46 @@ def test_one_launch_shape_splits_like_the_split_kernels(mode, transA, transB, pa
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
+def test_one_launch_shapes_equal_the_split_first_shape_on_random_small_problems():
+    """Random sizes up to 300 x 300 x 512 (one slice of depth in every shape), both transposes, padded leading
+    dimensions of every alignment, alpha and beta, magnitudes over 16 binades, now and then a value beyond the FP16
+    or BF16 range: the two one-launch shapes give the bits of the split-first shape."""
+    import torch
+    import paper_2203_03341_amd as ec
+    rng = np.random.default_rng(123)
+    h = ec.Handle()
+    for trial in range(80):
+        M, N, K = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 513))
+        if trial % 7 == 0:
+            K = int(rng.choice([64, 128, 256, 512, 4, 8, 63, 65]))
+        transA, transB = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+        mode = _modes()[str(rng.choice(["fp16", "bf16"]))]
+        pad_a, pad_b, pad_c = (int(rng.choice([0, 0, 1, 3, 4])) for _ in range(3))
+        ar, ac = (M, K) if transA == "N" else (K, M)
+        br, bc = (K, N) if transB == "N" else (N, K)
+        A = si.urand(ar, ac, trial, si.ID_A, ld=ar + pad_a)
+        A[:ar, :] *= np.float32(2.0 ** int(rng.integers(-8, 8)))
+        B = si.urand(br, bc, trial, si.ID_B, ld=br + pad_b)
+        if trial % 5 == 0:
+            A[int(rng.integers(0, ar)), int(rng.integers(0, ac))] = np.float32(rng.choice([7e4, -1e30, 3.39e38, 1e-7]))
+        C = si.urand(M, N, trial, si.ID_C, ld=M + pad_c)
+        alpha, beta = float(rng.choice([1.0, 1.5, -0.25])), float(rng.choice([0.0, 0.5, 1.0]))
+        dA, dB = to_device(A), to_device(B)
+        ops = {"N": ec.OP_N, "T": ec.OP_T}
+        outs = []
+        for shape in (ec.SHAPE_128x128_X2, ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):
+            h.set_shape(shape)
+            assert h.plan_info(M, N, K, mode)["slices"] == 1
+            dC = to_device(C)
+            h.sgemm(ops[transA], ops[transB], M, N, K, alpha, dA, A.shape[0], dB, B.shape[0], beta, dC, C.shape[0], mode)
+            torch.cuda.synchronize()
+            outs.append(to_host(dC, C.shape[0], N)[:M, :])
+        case = (trial, M, N, K, transA, transB, mode, pad_a, pad_b, pad_c, alpha, beta)
+        assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32)), case
+        assert np.array_equal(outs[0].view(np.uint32), outs[2].view(np.uint32)), case
+    h.destroy()
+
+
 def test_the_tile_order_knob_moves_tiles_between_xcds_and_changes_no_bit():
     """ecgemm_debug_set_tile_order (the experiment knob behind the block-order profiles): hardware round-robin instead
     of contiguous runs per XCD, plain column-major order, forced column bands.  Where no tile is sliced along K the
