@@ -37,6 +37,7 @@ enum FusedLayout { kFusedRows = 0, kFusedDepth = 1, kFusedDepthVec = 2 };
 // of two for the small tile measured slower at every size (512^3 9.7 against 9.2 us; 42 against 29 us at 1024^3, where
 // blocks share a compute unit).
 constexpr int kFusedRing = 2;
+constexpr int kFusedSplitWaves = 8;  // two per SIMD: one wave alone cannot issue the split's instructions fast enough
 
 struct FusedParams {
   const float* A;  // device, column-major, as passed to ecgemm_sgemm
@@ -78,8 +79,9 @@ struct FastSplit {
       const fused_half2_t hi = __builtin_convertvector(fused_float2_t{v0, v1}, fused_half2_t);
       out[0] = __builtin_bit_cast(unsigned, hi);
       if constexpr (KIND == kSplitFp16Scaled) {
-        const fused_float2_t residual = {__builtin_fmaf((float)hi[0], -2048.0f, scaled0), __builtin_fmaf((float)hi[1], -2048.0f, scaled1)};
-        out[1] = __builtin_bit_cast(unsigned, __builtin_convertvector(residual, fused_half2_t));
+        // (each rounded to FP16 by itself: the multiply-add then delivers its result as one half of the register)
+        const fused_half2_t lo = {(_Float16)__builtin_fmaf((float)hi[0], -2048.0f, scaled0), (_Float16)__builtin_fmaf((float)hi[1], -2048.0f, scaled1)};
+        out[1] = __builtin_bit_cast(unsigned, lo);
       } else if constexpr (kParts == 2) {
         const fused_float2_t residual = {v0 - (float)hi[0], v1 - (float)hi[1]};  // exact
         out[1] = __builtin_bit_cast(unsigned, __builtin_convertvector(residual, fused_half2_t));
@@ -109,15 +111,28 @@ struct FastSplit {
   }
 };
 
+// Where element (row, k) of a chunk lies in an operand's region of LDS, part 0 (bytes): fragment order, [row / 32]
+// [k step][part] blocks of 1 KiB, each two halves (k % 16 / 8) of 32 rows x 16 bytes, except that the rows of a half
+// are rotated by 4 (2 (k step) + half) places.  A fragment read takes a whole half either way.  The rotation is for
+// the writes of the k-contiguous layouts, where the lanes of one instruction hold few rows and many k: without it
+// their addresses differ by multiples of 512 bytes and meet in the same banks, eight at a time.
+__device__ __forceinline__ int fused_lds_rotation(int k) { return 4 * ((k >> 3) & 7); }
+template <int NP>
+__device__ __forceinline__ int fused_lds_slot(int row, int k) {
+  return ((row >> 5) * 4 + (k >> 4)) * NP * 1024 + ((k >> 3) & 1) * 512 + (((row & 31) + fused_lds_rotation(k)) & 31) * 16 + (k & 7) * 2;
+}
+
 // One operand of the block: where this thread's V values per chunk come from and where their parts go.
 template <int KIND, int LAYOUT, int TILE>
 struct FusedOperand {
   static_assert(TILE == 64 || TILE == 32, "tile sizes");
   static constexpr int NP = parts_of_split(KIND);
-  static constexpr int V = TILE / 4;                                                     // values per thread and chunk
+  static constexpr int V = TILE / kFusedSplitWaves;                                      // values per thread and chunk
   static constexpr int ROWS = LAYOUT == kFusedRows ? 1 : LAYOUT == kFusedDepth ? V : V / 4;  // rows this thread holds values of
   static constexpr int PER_ROW = V / ROWS;                                               // consecutive k per row
   static constexpr int REGION_BYTES = (TILE / 32) * 4 * NP * 1024;  // a chunk of one operand in LDS: [row block][k step][part] x 1 KiB
+  static constexpr int LOADS = LAYOUT == kFusedDepthVec ? ROWS : V;  // load instructions per thread and chunk
+  static constexpr int64_t kLargestShortLd = (int64_t)1 << 23;       // up to here every value of a chunk lies within 2^32 bytes of its first
 
   // Addresses are a part that is the same for the whole wave plus a small per-lane offset wherever the layout allows
   // it, which leaves the address arithmetic to the scalar unit.  A row beyond the matrix reads the last row instead
@@ -129,7 +144,16 @@ struct FusedOperand {
   bool unscaled;               // every factor is 1 (the same for the whole block)
   int64_t ld, K;
   int k_here;                  // k within the chunk of the thread's first value
-  int lds_offset;              // byte offset within the operand's region of the thread's first value, part 0
+  // byte offset within the operand's region, part 0, of the thread's first value (kFusedRows), of the first value of
+  // each of its rows (kFusedDepthVec); kFusedDepth: of row 0 at the thread's k, before the rotation
+  int lds_offset[LAYOUT == kFusedDepthVec ? ROWS : 1];
+  int first_row;               // within the tile
+  // A whole chunk, when ld <= kLargestShortLd: load i reads at &X(first row of the tile, 64 c) + offset[i] bytes, an
+  // address that is the same for the wave plus 32 bits per lane that never change, so a chunk's loads need no
+  // address arithmetic at all.  (kFusedDepth: a wave's rows are the same for all its lanes, row_ptr is not a vector
+  // and serves as it is.)
+  unsigned offset[LAYOUT == kFusedDepth ? 1 : LOADS];
+  int64_t chunk_bytes;         // from one chunk's first value to the next one's
 
   __device__ __forceinline__ void init(const float* src, int64_t ld_, int64_t rows, int64_t K_, int64_t tile_row0, float prescale,
                                        const int* log2_scale, int lane, int wave) {
@@ -137,9 +161,8 @@ struct FusedOperand {
     unscaled = prescale == 1.0f && log2_scale == nullptr;
     const int rows_here = (int)(rows - tile_row0 < TILE ? rows - tile_row0 : TILE);  // >= 1
     tile = LAYOUT == kFusedRows ? src + tile_row0 : src + tile_row0 * ld;
-    int first_row;  // within the tile
     if constexpr (LAYOUT == kFusedRows) {
-      first_row = lane % TILE, k_here = 16 * wave + 8 * (lane / TILE);
+      first_row = lane % TILE, k_here = (64 / kFusedSplitWaves) * wave + V * (lane / TILE);
       lane_offset = (unsigned)(first_row < rows_here ? first_row : rows_here - 1);
     } else if constexpr (LAYOUT == kFusedDepth) {
       first_row = V * wave, k_here = lane;
@@ -156,8 +179,31 @@ struct FusedOperand {
       factor[j] = prescale;
       if (log2_scale != nullptr) factor[j] *= row_scale_factor(log2_scale[tile_row0 + row_clamped]);
     }
-    // chunk (row / 32, k / 16, part), lane (k % 16 / 8) * 32 + row % 32, element k % 8
-    lds_offset = ((first_row >> 5) * 4 + (k_here >> 4)) * NP * 1024 + (((k_here >> 3) & 1) * 32 + (first_row & 31)) * 16 + (k_here & 7) * 2;
+    const bool short_ld = ld <= kLargestShortLd;  // else `offset` is not used
+    chunk_bytes = LAYOUT == kFusedRows ? 256 * ld : 256;
+    offset[0] = 0;
+    if constexpr (LAYOUT != kFusedDepth) {
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) {
+        if constexpr (LAYOUT == kFusedRows) {
+          offset[i] = short_ld ? (unsigned)(((k_here + i) * ld + lane_offset) * 4) : 0u;
+        } else {
+          const int row = first_row + 4 * i;
+          const int row_clamped = row < rows_here ? row : rows_here - 1;
+          offset[i] = short_ld ? (unsigned)((row_clamped * ld + k_here) * 4) : 0u;
+        }
+      }
+    }
+    if constexpr (LAYOUT == kFusedRows) {
+      static_assert(V <= 8, "a thread's values lie in one half of a k step");
+      lds_offset[0] = fused_lds_slot<NP>(first_row, k_here);
+    } else if constexpr (LAYOUT == kFusedDepthVec) {
+#pragma unroll
+      for (int j = 0; j < ROWS; ++j) lds_offset[j] = fused_lds_slot<NP>(first_row + 4 * j, k_here);
+    } else {
+      static_assert(V <= 32, "a thread's rows lie in one block of 32");
+      lds_offset[0] = (k_here >> 4) * NP * 1024 + ((k_here >> 3) & 1) * 512 + (k_here & 7) * 2;
+    }
   }
 
   // Requests the values of chunk c (which exists).  Every address is valid: in the last chunk, k beyond the depth is
@@ -201,6 +247,34 @@ struct FusedOperand {
     }
   }
 
+  // The same for a chunk that lies inside the depth, ld <= kLargestShortLd.
+  __device__ __forceinline__ void fetch_whole(float (&x)[V], int c) {
+    const char* first = reinterpret_cast<const char*>(tile) + c * chunk_bytes;  // the same for the whole wave
+    // (Both halves of every address are kept from the optimizer's view.  It would otherwise carry one 64-bit address
+    // per load through the loop in vector registers and advance each of them every chunk, or widen the offsets to 64
+    // bits outside the loop and add the base to each with a vector instruction.)
+    asm volatile("" : "+s"(first));
+    if constexpr (LAYOUT != kFusedDepth) {
+#pragma unroll
+      for (int i = 0; i < LOADS; ++i) asm volatile("" : "+v"(offset[i]));
+    }
+    typedef __attribute__((address_space(1))) char global_char_t;  // (what passed through the line above is no longer known to be global memory)
+    typedef float plain_float4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(1))) plain_float4_t global_float4_t;
+    const global_char_t* chunk = (const global_char_t*)first;
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      if constexpr (LAYOUT == kFusedDepth) {
+        x[i] = (row_ptr[i] + (int64_t)c * 64)[lane_offset];
+      } else if constexpr (LAYOUT == kFusedDepthVec) {
+        const plain_float4_t v = *reinterpret_cast<const global_float4_t*>(chunk + offset[i]);
+        x[4 * i] = v[0], x[4 * i + 1] = v[1], x[4 * i + 2] = v[2], x[4 * i + 3] = v[3];
+      } else {
+        x[i] = *reinterpret_cast<const global_float_t*>(chunk + offset[i]);
+      }
+    }
+  }
+
   // The short split of all V values, with (general == true) or without the multiplication by the scaling factors.
   template <bool GENERAL>
   __device__ __forceinline__ void split_ordinary(const float (&x)[V], unsigned (&words)[V / 2][NP]) const {
@@ -210,6 +284,19 @@ struct FusedOperand {
       const float v1 = GENERAL ? x[2 * e + 1] * factor[(2 * e + 1) / PER_ROW] : x[2 * e + 1];
       // (times 2^11 after the factor, not with it: a factor of 2^126 is legitimate, 2^137 is not a number)
       FastSplit<KIND>::split2(v0, v1, v0 * 2048.0f, v1 * 2048.0f, words[e]);
+    }
+  }
+
+  // Splitter on all V values; k beyond the depth (last chunk) counts as zero.
+  __device__ __forceinline__ void split_with_care(const float (&x)[V], int c, unsigned (&words)[V / 2][NP]) const {
+    const int64_t k0 = (int64_t)c * 64 + k_here;
+#pragma unroll
+    for (int e = 0; e < V / 2; ++e) {
+      unsigned short even[NP], odd[NP];
+      Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? x[2 * e] * factor[(2 * e) / PER_ROW] : 0.0f, even);
+      Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? x[2 * e + 1] * factor[(2 * e + 1) / PER_ROW] : 0.0f, odd);
+#pragma unroll
+      for (int q = 0; q < NP; ++q) words[e][q] = (unsigned)even[q] | ((unsigned)odd[q] << 16);
     }
   }
 
@@ -225,43 +312,59 @@ struct FusedOperand {
         split_ordinary<true>(x, words);
       done = __builtin_amdgcn_ballot_w64(!FastSplit<KIND>::high_parts_finite(words)) == 0;  // wave-uniform
     }
-    if (!done) {
-      const int64_t k0 = (int64_t)c * 64 + k_here;
-#pragma unroll
-      for (int e = 0; e < V / 2; ++e) {
-        unsigned short even[NP], odd[NP];
-        Splitter<KIND>::split(k0 + (2 * e) % PER_ROW < K ? x[2 * e] * factor[(2 * e) / PER_ROW] : 0.0f, even);
-        Splitter<KIND>::split(k0 + (2 * e + 1) % PER_ROW < K ? x[2 * e + 1] * factor[(2 * e + 1) / PER_ROW] : 0.0f, odd);
-#pragma unroll
-        for (int q = 0; q < NP; ++q) words[e][q] = (unsigned)even[q] | ((unsigned)odd[q] << 16);
-      }
+    if (!done) split_with_care(x, c, words);
+    write(words, region);
+  }
+
+  // The same for a chunk that lies inside the depth, with what is the same for the whole block decided by the caller:
+  // GENERAL == false if every factor is 1.
+  template <bool GENERAL>
+  __device__ __forceinline__ void deposit_whole(const float (&x)[V], int c, char* region) const {
+    unsigned words[V / 2][NP];
+    split_ordinary<GENERAL>(x, words);
+    if (__builtin_expect(__builtin_amdgcn_ballot_w64(!FastSplit<KIND>::high_parts_finite(words)) != 0, 0)) {
+      // (with a write of its own: joining the two paths in front of one write costs a register copy per word)
+      unsigned careful[V / 2][NP];
+      split_with_care(x, c, careful);
+      write(careful, region);
+    } else {
+      write(words, region);
     }
-    char* base = region + lds_offset;
+  }
+
+  __device__ __forceinline__ void write(const unsigned (&words)[V / 2][NP], char* region) const {
+    char* base = region + lds_offset[0];
     typedef unsigned uint4_t __attribute__((ext_vector_type(4)));
     typedef unsigned uint2_t __attribute__((ext_vector_type(2)));
 #pragma unroll
     for (int q = 0; q < NP; ++q) {
       if constexpr (LAYOUT == kFusedRows) {  // consecutive k of one row: one or both 8-deep halves of a k step
+        if constexpr (V >= 8) {
 #pragma unroll
-        for (int h = 0; h < V / 8; ++h)
-          *reinterpret_cast<uint4_t*>(base + q * 1024 + h * 512) =
-              uint4_t{words[4 * h][q], words[4 * h + 1][q], words[4 * h + 2][q], words[4 * h + 3][q]};
+          for (int h = 0; h < V / 8; ++h)
+            *reinterpret_cast<uint4_t*>(base + q * 1024 + h * 512) =
+                uint4_t{words[4 * h][q], words[4 * h + 1][q], words[4 * h + 2][q], words[4 * h + 3][q]};
+        } else {
+          static_assert(V == 4, "half of an 8-deep run");
+          *reinterpret_cast<uint2_t*>(base + q * 1024) = uint2_t{words[0][q], words[1][q]};
+        }
       } else if constexpr (LAYOUT == kFusedDepth) {  // one k of consecutive rows
 #pragma unroll
         for (int e = 0; e < V / 2; ++e) {
-          *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e) * 16) = (unsigned short)words[e][q];
-          *reinterpret_cast<unsigned short*>(base + q * 1024 + (2 * e + 1) * 16) = (unsigned short)(words[e][q] >> 16);
+          const int row = first_row + 2 * e, rotation = fused_lds_rotation(k_here);
+          char* block = base + (row >> 5) * 4 * NP * 1024 + q * 1024;
+          *reinterpret_cast<unsigned short*>(block + ((row + rotation) & 31) * 16) = (unsigned short)words[e][q];
+          *reinterpret_cast<unsigned short*>(block + ((row + 1 + rotation) & 31) * 16) = (unsigned short)(words[e][q] >> 16);
         }
       } else {  // four consecutive k of rows 4 apart
 #pragma unroll
         for (int j = 0; j < ROWS; ++j)
-          *reinterpret_cast<uint2_t*>(base + q * 1024 + j * 64) = uint2_t{words[2 * j][q], words[2 * j + 1][q]};
+          *reinterpret_cast<uint2_t*>(region + lds_offset[j] + q * 1024) = uint2_t{words[2 * j][q], words[2 * j + 1][q]};
       }
     }
   }
 };
 
-constexpr int kFusedSplitWaves = 4;
 constexpr int kFusedSliceChunks = 8;  // chunks of 64 per slice of the depth (see the multiplying waves)
 __host__ __device__ constexpr int fused_threads(int tile) { return 64 * (kFusedSplitWaves + (tile / 32) * (tile / 32)); }
 
@@ -278,9 +381,10 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   constexpr int KIND = split_kind_of(METHOD);
   constexpr bool BF16 = split_is_bf16(KIND);
   constexpr int NP = parts_of_split(KIND), PRODUCTS = products_of(METHOD);
-  constexpr int BM = TILE, BN = TILE, K_STEPS = 4, V = TILE / 4;
+  constexpr int BM = TILE, BN = TILE, K_STEPS = 4;
   typedef FusedOperand<KIND, LAYOUT_A, TILE> OperandA;
   typedef FusedOperand<KIND, LAYOUT_B, TILE> OperandB;
+  constexpr int V = OperandA::V;
   constexpr int REGION_BYTES = OperandA::REGION_BYTES, STAGE_BYTES = 2 * REGION_BYTES;
   typedef typename Mfma<BF16 ? kElemBf16 : kElemFp16>::frag_t frag_t;
   __shared__ __attribute__((aligned(1024))) char lds[2 * STAGE_BYTES];
@@ -313,6 +417,31 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
       __builtin_amdgcn_sched_barrier(0);
     });
     int c0 = 0;
+    // The bulk of the depth: chunks that lie inside it and whose successors in the ring do too, so that nothing in
+    // the loop depends on where the depth ends, and what is the same for the whole block (are there scaling factors?)
+    // is decided outside it.  The loop below, which decides everything chunk by chunk, takes over wherever this one
+    // stops: ring slot r holds chunk c0 + r at the top of either.
+    auto bulk = [&](auto general_c) {
+      constexpr bool GENERAL = decltype(general_c)::value;
+      const int whole_chunks = (int)(p.K / 64);
+      for (; c0 + 2 * kFusedRing <= whole_chunks; c0 += kFusedRing) {
+        static_for<kFusedRing>([&](auto r_c) {
+          constexpr int r = decltype(r_c)::value;
+          char* stage = lds + (r & 1) * STAGE_BYTES;
+          a.template deposit_whole<GENERAL>(xa[r], c0 + r, stage);
+          b.template deposit_whole<GENERAL>(xb[r], c0 + r, stage + REGION_BYTES);
+          __builtin_amdgcn_sched_barrier(0);
+          a.fetch_whole(xa[r], c0 + r + kFusedRing), b.fetch_whole(xb[r], c0 + r + kFusedRing);
+          __syncthreads();
+        });
+      }
+    };
+    if (p.lda <= OperandA::kLargestShortLd && p.ldb <= OperandB::kLargestShortLd) {  // block-uniform
+      if (a.unscaled && b.unscaled)
+        bulk(std::false_type{});
+      else
+        bulk(std::true_type{});  // (a factor of 1 changes no bit)
+    }
     for (; c0 + kFusedRing <= chunks; c0 += kFusedRing) {
       static_for<kFusedRing>([&](auto r_c) {
         constexpr int r = decltype(r_c)::value;
@@ -353,8 +482,11 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   const float corr_scale = (METHOD == kMethodFp16Split) ? 0x1p-11f : 1.0f;
   float sliced[16];
   bool earlier_slices = false;  // block-uniform
-  const int a_frag_off = wave_m * K_STEPS * NP * 1024 + lane * 16;
-  const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024 + lane * 16;
+  const int a_frag_off = wave_m * K_STEPS * NP * 1024;
+  const int b_frag_off = REGION_BYTES + wave_n * K_STEPS * NP * 1024;
+  int lane_off[K_STEPS];  // of this lane's 16 bytes within a 1 KiB block of k step ks (see fused_lds_slot)
+#pragma unroll
+  for (int ks = 0; ks < K_STEPS; ++ks) lane_off[ks] = fused_lds_slot<NP>(lane & 31, 16 * ks + 8 * (lane >> 5)) - ks * NP * 1024;
   for (int c = 0; c < chunks; ++c) {
     __syncthreads();
     const char* stage = lds + (c & 1) * STAGE_BYTES;
@@ -363,8 +495,8 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
       frag_t fa[NP], fb[NP];
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        fa[q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + (ks * NP + q) * 1024);
-        fb[q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + (ks * NP + q) * 1024);
+        fa[q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
+        fb[q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
       }
       static_for<PRODUCTS>([&](auto m_c) {
         constexpr ProductTerm term = product_term(METHOD, decltype(m_c)::value);
