@@ -31,7 +31,8 @@ namespace ecgemm {
 //   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: row l % TILE, the V consecutive k from 16 w + 8 (l / TILE)
 //   kFusedDepth     k contiguous, X(r, k) = src[k + r ld]: k = l, rows V w .. V w + V - 1
 //   kFusedDepthVec  k contiguous, base and ld multiples of 16 bytes, K a multiple of 4: the four values k = 4 (l % 16) ..
-//                   + 3 of rows V w + 4 j + l / 16, j = 0 .. V / 4 - 1, one 16-byte load each
+//                   + 3 of rows w + 8 (l / 16) + 32 j, j = 0 .. V / 4 - 1, one 16-byte load each (rows 8 apart: with
+//                   the rotation of fused_lds_slot the 64 lanes of a write then go to 64 different places of a bank period)
 enum FusedLayout { kFusedRows = 0, kFusedDepth = 1, kFusedDepthVec = 2 };
 // Chunks in flight in registers (the loop is unrolled by this: a register ring is indexed statically).  Four instead
 // of two for the small tile measured slower at every size (512^3 9.7 against 9.2 us; 42 against 29 us at 1024^3, where
@@ -113,10 +114,10 @@ struct FastSplit {
 
 // Where element (row, k) of a chunk lies in an operand's region of LDS, part 0 (bytes): fragment order, [row / 32]
 // [k step][part] blocks of 1 KiB, each two halves (k % 16 / 8) of 32 rows x 16 bytes, except that the rows of a half
-// are rotated by 4 (2 (k step) + half) places.  A fragment read takes a whole half either way.  The rotation is for
+// are rotated by 2 (k step) + half places.  A fragment read takes a whole half either way.  The rotation is for
 // the writes of the k-contiguous layouts, where the lanes of one instruction hold few rows and many k: without it
 // their addresses differ by multiples of 512 bytes and meet in the same banks, eight at a time.
-__device__ __forceinline__ int fused_lds_rotation(int k) { return 4 * ((k >> 3) & 7); }
+__device__ __forceinline__ int fused_lds_rotation(int k) { return (k >> 3) & 7; }
 template <int NP>
 __device__ __forceinline__ int fused_lds_slot(int row, int k) {
   return ((row >> 5) * 4 + (k >> 4)) * NP * 1024 + ((k >> 3) & 1) * 512 + (((row & 31) + fused_lds_rotation(k)) & 31) * 16 + (k & 7) * 2;
@@ -168,12 +169,12 @@ struct FusedOperand {
       first_row = V * wave, k_here = lane;
       lane_offset = (unsigned)lane;
     } else {
-      first_row = V * wave + (lane >> 4), k_here = 4 * (lane & 15);
+      first_row = wave + 8 * (lane >> 4), k_here = 4 * (lane & 15);
       lane_offset = 0;
     }
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-      const int row = first_row + (LAYOUT == kFusedDepthVec ? 4 * j : j);
+      const int row = first_row + (LAYOUT == kFusedDepthVec ? 32 * j : j);
       const int row_clamped = row < rows_here ? row : rows_here - 1;
       row_ptr[j] = tile + (LAYOUT == kFusedRows ? (int64_t)row_clamped : row_clamped * ld);
       factor[j] = prescale;
@@ -188,7 +189,7 @@ struct FusedOperand {
         if constexpr (LAYOUT == kFusedRows) {
           offset[i] = short_ld ? (unsigned)(((k_here + i) * ld + lane_offset) * 4) : 0u;
         } else {
-          const int row = first_row + 4 * i;
+          const int row = first_row + 32 * i;
           const int row_clamped = row < rows_here ? row : rows_here - 1;
           offset[i] = short_ld ? (unsigned)((row_clamped * ld + k_here) * 4) : 0u;
         }
@@ -199,7 +200,7 @@ struct FusedOperand {
       lds_offset[0] = fused_lds_slot<NP>(first_row, k_here);
     } else if constexpr (LAYOUT == kFusedDepthVec) {
 #pragma unroll
-      for (int j = 0; j < ROWS; ++j) lds_offset[j] = fused_lds_slot<NP>(first_row + 4 * j, k_here);
+      for (int j = 0; j < ROWS; ++j) lds_offset[j] = fused_lds_slot<NP>(first_row + 32 * j, k_here);
     } else {
       static_assert(V <= 32, "a thread's rows lie in one block of 32");
       lds_offset[0] = (k_here >> 4) * NP * 1024 + ((k_here >> 3) & 1) * 512 + (k_here & 7) * 2;
@@ -356,7 +357,7 @@ struct FusedOperand {
           *reinterpret_cast<unsigned short*>(block + ((row + rotation) & 31) * 16) = (unsigned short)words[e][q];
           *reinterpret_cast<unsigned short*>(block + ((row + 1 + rotation) & 31) * 16) = (unsigned short)(words[e][q] >> 16);
         }
-      } else {  // four consecutive k of rows 4 apart
+      } else {  // four consecutive k of each of the thread's rows
 #pragma unroll
         for (int j = 0; j < ROWS; ++j)
           *reinterpret_cast<uint2_t*>(region + lds_offset[j] + q * 1024) = uint2_t{words[2 * j][q], words[2 * j + 1][q]};
@@ -436,11 +437,15 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
         });
       }
     };
-    if (p.lda <= OperandA::kLargestShortLd && p.ldb <= OperandB::kLargestShortLd) {  // block-uniform
-      if (a.unscaled && b.unscaled)
-        bulk(std::false_type{});
-      else
-        bulk(std::true_type{});  // (a factor of 1 changes no bit)
+    // (not for kFusedDepth, the layout of last resort: with one row pointer and one factor per value it has no
+    // registers left for a second copy of the loop)
+    if constexpr (LAYOUT_A != kFusedDepth && LAYOUT_B != kFusedDepth) {
+      if (p.lda <= OperandA::kLargestShortLd && p.ldb <= OperandB::kLargestShortLd) {  // block-uniform
+        if (a.unscaled && b.unscaled)
+          bulk(std::false_type{});
+        else
+          bulk(std::true_type{});  // (a factor of 1 changes no bit)
+      }
     }
     for (; c0 + kFusedRing <= chunks; c0 += kFusedRing) {
       static_for<kFusedRing>([&](auto r_c) {
@@ -487,25 +492,49 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   int lane_off[K_STEPS];  // of this lane's 16 bytes within a 1 KiB block of k step ks (see fused_lds_slot)
 #pragma unroll
   for (int ks = 0; ks < K_STEPS; ++ks) lane_off[ks] = fused_lds_slot<NP>(lane & 31, 16 * ks + 8 * (lane >> 5)) - ks * NP * 1024;
-  for (int c = 0; c < chunks; ++c) {
-    __syncthreads();
+  // A chunk is taken in two halves of two k steps, each with a register set of its own, and the next half is requested
+  // before the matrix instructions of the one before it are issued: a half's way from LDS is covered by the other
+  // half's arithmetic, also across the barrier between two chunks.  Within a chunk the k steps are multiplied in
+  // ascending order.
+  frag_t fa[2][K_STEPS / 2][NP], fb[2][K_STEPS / 2][NP];
+  auto request = [&](auto half_c, int c) {  // the fragments of half HALF of chunk c -> register set HALF
+    constexpr int HALF = decltype(half_c)::value;
     const char* stage = lds + (c & 1) * STAGE_BYTES;
 #pragma unroll
-    for (int ks = 0; ks < K_STEPS; ++ks) {
-      frag_t fa[NP], fb[NP];
+    for (int s = 0; s < K_STEPS / 2; ++s) {
+      const int ks = HALF * (K_STEPS / 2) + s;
 #pragma unroll
       for (int q = 0; q < NP; ++q) {
-        fa[q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
-        fb[q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
+        fa[HALF][s][q] = *reinterpret_cast<const frag_t*>(stage + a_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
+        fb[HALF][s][q] = *reinterpret_cast<const frag_t*>(stage + b_frag_off + (ks * NP + q) * 1024 + lane_off[ks]);
       }
+    }
+  };
+  auto multiply = [&](auto half_c) {
+    constexpr int HALF = decltype(half_c)::value;
+#pragma unroll
+    for (int s = 0; s < K_STEPS / 2; ++s) {
       static_for<PRODUCTS>([&](auto m_c) {
         constexpr ProductTerm term = product_term(METHOD, decltype(m_c)::value);
         if constexpr (term.correction)
-          acc_corr = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_corr);
+          acc_corr = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[HALF][s][term.qb], fa[HALF][s][term.qa], acc_corr);
         else
-          acc_main = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[term.qb], fa[term.qa], acc_main);
+          acc_main = Mfma<BF16 ? kElemBf16 : kElemFp16>::run(fb[HALF][s][term.qb], fa[HALF][s][term.qa], acc_main);
       });
     }
+  };
+  __syncthreads();  // chunk 0 is there
+  request(std::integral_constant<int, 0>{}, 0);
+  for (int c = 0; c < chunks; ++c) {
+    request(std::integral_constant<int, 1>{}, c);
+    multiply(std::integral_constant<int, 0>{});
+    if (c + 1 < chunks) {  // block-uniform
+      // (this wave's reads of chunk c have returned when it passes the barrier: __syncthreads() waits for them; only
+      // then may the splitting waves overwrite the buffer)
+      __syncthreads();  // chunk c + 1 is there
+      request(std::integral_constant<int, 0>{}, c + 1);
+    }
+    multiply(std::integral_constant<int, 1>{});
     if (c % kFusedSliceChunks == kFusedSliceChunks - 1 && c + 1 < chunks) {  // a slice is complete and another follows
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
