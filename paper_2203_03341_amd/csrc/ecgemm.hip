@@ -252,24 +252,28 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 // shapes, both modes).
 //   split first: the product estimate above, the launches (5.6 us), and the split pass, which costs about 1 us per MB
 //   of FP32 operands (1.4 us with three BF16 parts to write) until it is hidden behind the product's launch (8.5 us).
-//   one launch: 4.4 us, then per 64-deep chunk what a block needs to split its share (0.6 / 1.1 us for 32 / 64 tiles
-//   in FP16 mode, 0.85 / 1.55 in BF16 mode), times how crowded the compute units are once there are more blocks than
-//   units (blocks share a unit's vector pipes; the 64 x 64 BF16 block needs 96 KiB of LDS, so a second one waits).
-//   A last chunk that is not whole takes the slower, general split.
+//   one launch: 4.4 us, then the blocks in rounds of one per compute unit (a block's 9 or 12 waves leave no registers
+//   for a second one beside it).  A round is what a block needs per 64-deep chunk (0.33 / 0.58 us for 32 / 64 tiles in
+//   FP16 mode, 0.46 / 0.76 in BF16 mode; a fifth more for 64 x 64 BF16 blocks once nearly every unit has one) plus
+//   its first loads and its stores, which are nearly free in a single round (0.4 to 1.1 us) and cost 1.6 to 3 us per
+//   round when rounds follow each other.  A last chunk that is not whole takes the slower, general split (three
+//   chunks' worth).
 double split_first_us(const Plan& pl, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   const double operand_mb = 4.0 * ((double)M + (double)N) * (double)K / 1e6;
   return estimated_us(pl, mode) + 5.6 + std::min(8.5, (mode == ECGEMM_MODE_BF16_FULL ? 1.4 : 1.0) * operand_mb);
 }
 double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
   const bool bf16 = mode == ECGEMM_MODE_BF16_FULL, small = pl.shape->bm == 32;
-  const double per_chunk = small ? (bf16 ? 0.85 : 0.6) : (bf16 ? 1.55 : 1.1);
+  const double per_chunk = small ? (bf16 ? 0.46 : 0.33) : (bf16 ? 0.76 : 0.58);
   const double blocks_per_unit = (double)pl.tiles_m * pl.tiles_n / kPlanComputeUnits;
-  const double crowding = blocks_per_unit <= 1.0 ? 1.0
-                          : small               ? (bf16 ? 0.95 * blocks_per_unit : 0.65 + 0.5 * blocks_per_unit)
-                          : bf16                ? 1.3 * blocks_per_unit
-                                                : 0.2 + 0.95 * blocks_per_unit;
-  const double chunks = (double)(K / 64) + (K % 64 ? 2.5 : 0.0);
-  return 4.4 + chunks * per_chunk * std::max(1.0, crowding);
+  const double rounds = std::max(1.0, std::ceil(blocks_per_unit - 1e-9));
+  const double chunks = (double)(K / 64) + (K % 64 ? 3.0 : 0.0);
+  if (rounds == 1.0) {
+    const double nearly_full = (!small && bf16 && blocks_per_unit > 0.9) ? 1.2 : 1.0;
+    return 4.4 + (small ? (bf16 ? 0.7 : 0.4) : (bf16 ? 1.1 : 0.8)) + chunks * per_chunk * nearly_full;
+  }
+  const double per_round = small ? (bf16 ? 2.7 : 1.6) : (bf16 ? 3.0 : 2.0);
+  return 4.4 + rounds * (per_round + chunks * per_chunk);
 }
 
 // The plan of a call.  With a shape forced by the caller, that shape.  Otherwise the cheaper of the two product shapes

@@ -106,8 +106,10 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["whole_tiles"], p["sliced_tiles"], p["slices"], p["grid"]) == (W4, 0, 32, 8, 256)
     p = ec.plan_info(4095, 3001, 5003, ec.MODE_BF16_FULL)              # 384 tiles: 256 whole, 128 in two slices
     assert (p["shape"], p["tiles_m"], p["tiles_n"], p["whole_tiles"], p["sliced_tiles"], p["slices"]) == (W4, 16, 24, 256, 128, 2)
-    p = ec.plan_info(1024, 1024, 1024, ec.MODE_BF16_FULL)              # 32 tiles x 2 slices would leave CUs idle: smaller tiles
-    assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 64, 2, 128)
+    p = ec.plan_info(1024, 1024, 1024, ec.MODE_BF16_FULL)              # one launch: 256 blocks of 64 x 64, one per compute unit
+    assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (ec.SHAPE_64x64_FUSED, 0, 1, 256)
+    p = ec.plan_info(1280, 1280, 1280, ec.MODE_BF16_FULL)              # 25 tiles x 2 slices would leave CUs idle: smaller tiles
+    assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 100, 2, 200)
     p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # 2 W4 tiles could not fill the chip: smaller tiles,
     assert (p["shape"], p["sliced_tiles"]) == (X2, 16) and 16 <= p["slices"] <= 32   # one or two slices per compute unit
     p = ec.plan_info(1792, 1792, 1792, ec.MODE_FP16_SPLIT)             # 196 tiles of 128 x 128, one per CU: slices would only add traffic

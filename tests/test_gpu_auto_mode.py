@@ -114,19 +114,20 @@ def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
 
 def test_each_candidate_runs_as_its_fixed_mode_would():
     """Sizes that a fixed mode runs as one launch on the FP32 operands (256^3), with the split-first kernels (1536^3),
-    and 1024^3, where the FP16 mode takes one launch and the BF16 mode splits first: whichever candidate wins runs
-    that way, so that the bits are the fixed mode's.  (The checks are those of every other case here: the oracle's
-    choice, bit equality with the direct call, the accuracy bar.)"""
+    and 1024 x 1024 x 2304, where the FP16 mode takes one launch and the BF16 mode splits first: whichever candidate
+    wins runs that way, so that the bits are the fixed mode's.  (The checks are those of every other case here: the
+    oracle's choice, bit equality with the direct call, the accuracy bar.)"""
     import paper_2203_03341_amd as ec
     h = ec.Handle()
-    one_launch = lambda n, mode: h.plan_info(n, n, n, mode)["shape"] >= ec.SHAPE_64x64_FUSED
-    assert one_launch(256, ec.MODE_FP16_SPLIT) and one_launch(256, ec.MODE_BF16_FULL)
-    assert one_launch(1024, ec.MODE_FP16_SPLIT) and not one_launch(1024, ec.MODE_BF16_FULL)
-    assert not one_launch(1536, ec.MODE_FP16_SPLIT) and not one_launch(1536, ec.MODE_BF16_FULL)
+    one_launch = lambda size, mode: h.plan_info(*size, mode)["shape"] >= ec.SHAPE_64x64_FUSED
+    small, mixed, large = (256, 256, 256), (1024, 1024, 2304), (1536, 1536, 1536)
+    assert one_launch(small, ec.MODE_FP16_SPLIT) and one_launch(small, ec.MODE_BF16_FULL)
+    assert one_launch(mixed, ec.MODE_FP16_SPLIT) and not one_launch(mixed, ec.MODE_BF16_FULL)
+    assert not one_launch(large, ec.MODE_FP16_SPLIT) and not one_launch(large, ec.MODE_BF16_FULL)
     chosen = []
-    for n in (256, 1024, 1536):
-        chosen.append(_check(h, "N", "N", n, n, n, "urand", "urand", seed=21))       # plain FP16
-        chosen.append(_check(h, "N", "N", n, n, n, TYPE3, TYPE3, seed=22))           # FP16 on scaled operands
+    for (m, n, k) in (small, mixed, large):
+        chosen.append(_check(h, "N", "N", m, n, k, "urand", "urand", seed=21))       # plain FP16
+        chosen.append(_check(h, "N", "N", m, n, k, TYPE3, TYPE3, seed=22))           # FP16 on scaled operands
     assert chosen == ["fp16", "fp16 scaled"] * 3
     # the BF16 candidate: rows too short for the pair to match an FP32 sum (K = 8), at a size of one launch and at
     # 1024 x 1024 x 8, and then a shape whose BF16 plan splits first
