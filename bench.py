@@ -69,8 +69,14 @@ WORKLOADS = {
     "c5_odd_transA_bf16": (4095, 3001, 5003, "T", "N", "bf16", 1.0, 0.0, "urand", 1024),
     # not a baseline config: the size at which the one-kernel (fused) shape is compared with the split-first path
     "x_1024_fp16_urand": (1024, 1024, 1024, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_1024_bf16_urand": (1024, 1024, 1024, "N", "N", "bf16", 1.0, 0.0, "urand", None),
     "x_512_fp16_urand": (512, 512, 512, "N", "N", "fp16", 1.0, 0.0, "urand", None),
     "x_512_bf16_urand": (512, 512, 512, "N", "N", "bf16", 1.0, 0.0, "urand", None),
+    # one block of the one-launch kernel by itself (with --shape fused), 64 chunks deep, in three operand layouts
+    "x_oneblock_nn_fp16": (64, 64, 4096, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_oneblock_tn_fp16": (64, 64, 4096, "T", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_oneblock_nt_fp16": (64, 64, 4096, "N", "T", "fp16", 1.0, 0.0, "urand", None),
+    "x_oneblock_nn_bf16": (64, 64, 4096, "N", "N", "bf16", 1.0, 0.0, "urand", None),
     # not baseline configs either: the method with the leading product accumulated outside the matrix unit, as the
     # paper's listing does against round-toward-zero, next to the default (inside) at the same size
     "x_8192_fp16_urand": (8192, 8192, 8192, "N", "N", "fp16", 1.0, 0.0, "urand", 256),

@@ -4,39 +4,44 @@
 // copies in HBM, no partial sums: one launch.  Every block that touches a tile of A splits it again (N / 64 times per
 // element), so this pays where launches and latencies, not arithmetic, decide the time: small products.
 //
-// One block: TILE x TILE of C over the whole depth of the product, TILE = 64 or 32, made by four waves that fetch and
+// One block: TILE x TILE of C over the whole depth of the product, TILE = 64 or 32, made by eight waves that fetch and
 // split and, next to them on the same SIMDs, one wave per 32 x 32 of the tile that multiplies (one v_mfma_f32_32x32x16
-// accumulator pair): 8 or 5 waves.  A chain of dependent matrix instructions leaves its wave waiting most of the
-// time; with the two roles in different waves the hardware fills that time with the other wave's split.  Same fragment
-// layout in LDS, same term order and same accumulator discipline as product_kernel.hpp, so an element is summed in
-// the same order as in an unsliced tile there.  Small tiles are what make a small product many blocks, and what
-// bounds a block is its split work, (TILE + TILE) x K elements: 512^3 is 64 blocks of 64 x 64 or 256 of 32 x 32 with
-// half the work each, one per compute unit.  The host picks 32 while that still leaves compute units idle.
+// accumulator pair): 12 or 9 waves.  A chain of dependent matrix instructions leaves its wave waiting most of the
+// time; with the two roles in different waves the hardware fills that time with the other waves' split, and with two
+// splitting waves per SIMD one of them can issue while the other waits.  Same term order and same accumulator
+// discipline as product_kernel.hpp, so an element is summed in the same order as in an unsliced tile there; the
+// fragments lie in LDS as they do there except for a rotation of the rows (fused_lds_slot).  Small tiles are what
+// make a small product many blocks, and what bounds a block is its split work, (TILE + TILE) x K elements: 512^3 is
+// 64 blocks of 64 x 64 or 256 of 32 x 32 with half the work each, one per compute unit.  The host picks 32 while that
+// still leaves compute units idle.
 //
-// Depth is walked in chunks of 64.  The 256 splitting threads fetch the chunk's TILE x 64 values of op(A) and of
-// op(B), TILE / 4 of each per thread, with the lanes of a wave along whichever index is contiguous in memory
+// Depth is walked in chunks of 64.  The 512 splitting threads fetch the chunk's TILE x 64 values of op(A) and of
+// op(B), TILE / 8 of each per thread, with the lanes of a wave along whichever index is contiguous in memory
 // (FusedLayout); the values of the next kFusedRing chunks are in flight in registers while the current one is split
 // and written to LDS in fragment order (two buffers, one barrier per chunk), where the multiplying waves pick it up.
-// The split is what bounds the loop (a chunk of a 64 x 64 tile is 8192 elements per block against 12 or 24 matrix
-// instructions per multiplying wave), so it takes a short form (FastSplit, 3.5 to 7.5 vector instructions per
-// element) whenever every value a wave holds is ordinary, and Splitter, which saturates and handles infinities and
-// NaN, otherwise; both give the same bits on the values the short form accepts.
+// The split takes a short form (FastSplit, 3.5 to 7.5 vector instructions per element) whenever every value a wave
+// holds is ordinary, and Splitter, which saturates and handles infinities and NaN, otherwise; both give the same
+// bits on the values the short form accepts.  Measured on single blocks, what bounded a chunk in turn was: the
+// instruction stream of one splitting wave per SIMD (hence eight waves, a loop for the bulk of the depth without
+// conditions that are the same for the whole block, loads whose addresses are a scalar base plus a constant lane
+// offset), bank conflicts of the LDS writes of k-contiguous operands (hence the rotation), and the trip of the
+// fragments from LDS in front of each chunk's first matrix instruction (hence the two half-chunk register sets of
+// the multiplying waves).
 #pragma once
 #include "product_kernel.hpp"
 
 namespace ecgemm {
 
-// How the V = TILE / 4 values per thread and chunk are laid over one operand's TILE rows x 64 k (X(r, k): op(A)(m, k)
+// How the V = TILE / 8 values per thread and chunk are laid over one operand's TILE rows x 64 k (X(r, k): op(A)(m, k)
 // or op(B)(k, n) with r = n), wave w, lane l:
-//   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: row l % TILE, the V consecutive k from 16 w + 8 (l / TILE)
+//   kFusedRows      r contiguous, X(r, k) = src[r + k ld]: row l % TILE, the V consecutive k from 8 w + V (l / TILE)
 //   kFusedDepth     k contiguous, X(r, k) = src[k + r ld]: k = l, rows V w .. V w + V - 1
 //   kFusedDepthVec  k contiguous, base and ld multiples of 16 bytes, K a multiple of 4: the four values k = 4 (l % 16) ..
 //                   + 3 of rows w + 8 (l / 16) + 32 j, j = 0 .. V / 4 - 1, one 16-byte load each (rows 8 apart: with
 //                   the rotation of fused_lds_slot the 64 lanes of a write then go to 64 different places of a bank period)
 enum FusedLayout { kFusedRows = 0, kFusedDepth = 1, kFusedDepthVec = 2 };
-// Chunks in flight in registers (the loop is unrolled by this: a register ring is indexed statically).  Four instead
-// of two for the small tile measured slower at every size (512^3 9.7 against 9.2 us; 42 against 29 us at 1024^3, where
-// blocks share a compute unit).
+// Chunks in flight in registers (the loop is unrolled by this: a register ring is indexed statically).  Four and six
+// instead of two measured slower at every size (1024^3: 18.9 and 29.6 against 18.1 us).
 constexpr int kFusedRing = 2;
 constexpr int kFusedSplitWaves = 8;  // two per SIMD: one wave alone cannot issue the split's instructions fast enough
 
