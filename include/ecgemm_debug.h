@@ -55,10 +55,11 @@ extern "C" {
  *   64x64_FUSED    the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
  *                  one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
  *                  packed operands or partial sums in the workspace, one launch (the two modes of the method;
- *                  ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64, 4 waves of
- *                  32 x 32, the whole depth per block; every block splits the rows of A and columns of B that it
- *                  uses again, so this is for small products, where launches and latencies decide the time.
- *   32x32_FUSED    the same with block tile 32 x 32: all four waves fetch and split, one multiplies.  Four times the
+ *                  ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64: eight waves
+ *                  that fetch and split, four that multiply 32 x 32 each, the whole depth per block; every block
+ *                  splits the rows of A and columns of B that it uses again, so this is for small products, where
+ *                  launches and latencies decide the time.
+ *   32x32_FUSED    the same with block tile 32 x 32: eight waves fetch and split, one multiplies.  Four times the
  *                  blocks with half the split work each: for products so small that 64 x 64 tiles leave most
  *                  compute units idle.
  * All shapes form the same products in the same per-element order; results agree bit for bit between shapes unless
