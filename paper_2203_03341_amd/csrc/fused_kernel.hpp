@@ -425,8 +425,8 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
     int c0 = 0;
     // The bulk of the depth: chunks that lie inside it and whose successors in the ring do too, so that nothing in
     // the loop depends on where the depth ends, and what is the same for the whole block (are there scaling factors?)
-    // is decided outside it.  The loop below, which decides everything chunk by chunk, takes over wherever this one
-    // stops: ring slot r holds chunk c0 + r at the top of either.
+    // is decided outside it.  Ring slot r holds chunk c0 + r at the top of every loop here.  The loops further down,
+    // which decide everything chunk by chunk, are for the calls that cannot take this one.
     auto bulk = [&](auto general_c) {
       constexpr bool GENERAL = decltype(general_c)::value;
       const int whole_chunks = (int)(p.K / 64);
@@ -440,6 +440,28 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
           a.fetch_whole(xa[r], c0 + r + kFusedRing), b.fetch_whole(xb[r], c0 + r + kFusedRing);
           __syncthreads();
         });
+      }
+      // The last chunks, whose successors in the ring do not exist or are not whole: the same split for those that
+      // lie inside the depth, the general one for the last if it does not, and the general fetch for what is left to
+      // request.  (Every condition here is the same for the whole block, and every chunk still has its one barrier.)
+      while (c0 < chunks) {
+        static_for<kFusedRing>([&](auto r_c) {
+          constexpr int r = decltype(r_c)::value;
+          const int c = c0 + r;
+          if (c < chunks) {
+            char* stage = lds + (r & 1) * STAGE_BYTES;
+            if (c < whole_chunks) {
+              a.template deposit_whole<GENERAL>(xa[r], c, stage);
+              b.template deposit_whole<GENERAL>(xb[r], c, stage + REGION_BYTES);
+            } else {
+              a.deposit(xa[r], c, stage);
+              b.deposit(xb[r], c, stage + REGION_BYTES);
+            }
+            if (c + kFusedRing < chunks) a.fetch(xa[r], c + kFusedRing), b.fetch(xb[r], c + kFusedRing);
+            __syncthreads();
+          }
+        });
+        c0 += kFusedRing;
       }
     };
     // (not for kFusedDepth, the layout of last resort: with one row pointer and one factor per value it has no
