@@ -543,6 +543,40 @@ def test_one_launch_shape_splits_like_the_split_kernels(mode, transA, transB, pa
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+def test_one_launch_shape_with_leading_dimensions_beyond_32_bit_offsets(mode):
+    """The loop that covers the bulk of the depth addresses a chunk's values with 32-bit offsets from the chunk's
+    first value, which holds up to leading dimensions of 2^23; beyond, the kernel takes its general loop.  Operands
+    with rows contiguous and a leading dimension of 2^23 + 4 (4.4 GB of zeros each, the matrix in the first rows of
+    every column) must give the bits of the same operands stored compactly."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = 100, 70, 130
+    ld = (1 << 23) + 4
+    A, B = _inputs(M, N, K, "N", "T", "urand", 41)                      # op(A) = A (M x K), op(B) = B^T with B N x K: rows contiguous in both
+    h = ec.Handle()
+    h.set_shape(ec.SHAPE_64x64_FUSED)
+    mode_id = _modes()[mode]
+    outs = []
+    for wide in (False, True):
+        if wide:
+            dA = torch.zeros((K, ld), dtype=torch.float32, device="cuda")
+            dB = torch.zeros((K, ld), dtype=torch.float32, device="cuda")
+            dA[:, :M] = to_device(A)[:, :M]
+            dB[:, :N] = to_device(B)[:, :N]
+            lda = ldb = ld
+        else:
+            dA, dB, lda, ldb = to_device(A), to_device(B), A.shape[0], B.shape[0]
+        dC = empty_colmajor(M, N, fill=float("nan"))
+        h.sgemm(ec.OP_N, ec.OP_T, M, N, K, 1.0, dA, lda, dB, ldb, 0.0, dC, M, mode_id)
+        torch.cuda.synchronize()
+        outs.append(to_host(dC, M, N))
+        del dA, dB
+    h.destroy()
+    assert np.all(np.isfinite(outs[0]))
+    assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
+
+
 def test_one_launch_shapes_equal_the_split_first_shape_on_random_small_problems():
     """Random sizes up to 300 x 300 x 512 (one slice of depth in every shape), both transposes, padded leading
     dimensions of every alignment, alpha and beta, magnitudes over 16 binades, now and then a value beyond the FP16
