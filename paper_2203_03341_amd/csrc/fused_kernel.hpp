@@ -464,9 +464,9 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
         c0 += kFusedRing;
       }
     };
-    // (not for kFusedDepth, the layout of last resort: with one row pointer and one factor per value it has no
-    // registers left for a second copy of the loop)
-    if constexpr (LAYOUT_A != kFusedDepth && LAYOUT_B != kFusedDepth) {
+    // (kFusedDepth, the layout of last resort, only next to kFusedRows: with one row pointer and one factor per
+    // value it leaves no registers for a second copy of the loop next to another depth-contiguous operand)
+    if constexpr ((LAYOUT_A != kFusedDepth && LAYOUT_B != kFusedDepth) || LAYOUT_A == kFusedRows || LAYOUT_B == kFusedRows) {
       if (p.lda <= OperandA::kLargestShortLd && p.ldb <= OperandB::kLargestShortLd) {  // block-uniform
         if (a.unscaled && b.unscaled)
           bulk(std::false_type{});
