@@ -47,7 +47,7 @@ struct ecgemm_context {
 namespace {
 
 typedef void (*reduce_fn_t)(const float*, int, int, int, int, int, int, int, int64_t, int64_t, float, float, float*, int64_t,
-                            const int*, int);
+                            const int*, int, int);
 struct FusedKernels {
   void (*kernel[3][3])(FusedParams);  // [FusedLayout of A][FusedLayout of B]
 };
@@ -79,16 +79,17 @@ constexpr Shape shape_of(int persistent_max_k) {
   return Shape{product_kernel<Cfg, false>, scaled, nullptr, reduce_tail_kernel<Cfg::BM, Cfg::BN>, Cfg::BM, Cfg::BN, Cfg::BK,
                Cfg::THREADS, Cfg::BLOCKS_PER_CU, persistent_max_k};
 }
-inline Shape fused_shape(const FusedKernels* kernels, int tile) {  // never sliced: no partial sums, no second kernel
-  return Shape{nullptr, nullptr, kernels, nullptr, tile, tile, 32, fused_threads(tile), 1, 0};
+template <int TILE>
+inline Shape fused_shape(const FusedKernels* kernels) {  // (the reduction only for plans that slice the depth)
+  return Shape{nullptr, nullptr, kernels, reduce_tail_kernel<TILE, TILE>, TILE, TILE, 32, fused_threads(TILE), 1, 0};
 }
 constexpr Shape kNoShape{nullptr, nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
 constexpr int kShapeCount = 4;
 // [mode][ecgemm_shape_t - 1]
 constexpr int kPersistentMaxK = 4096;
 const Shape kShapes[kMethods][kShapeCount] = {
-    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape(&kFusedFp16Tile64, 64), fused_shape(&kFusedFp16Tile32, 32)},
-    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape(&kFusedBf16Tile64, 64), fused_shape(&kFusedBf16Tile32, 32)},
+    {shape_of<Fp16W4, true>(kPersistentMaxK), shape_of<Fp16X2, true>(0), fused_shape<64>(&kFusedFp16Tile64), fused_shape<32>(&kFusedFp16Tile32)},
+    {shape_of<Bf16W4, true>(kPersistentMaxK), shape_of<Bf16X2, true>(0), fused_shape<64>(&kFusedBf16Tile64), fused_shape<32>(&kFusedBf16Tile32)},
     {shape_of<MarkidisConfig>(4096), kNoShape, kNoShape, kNoShape},
     {shape_of<UnscaledConfig>(4096), kNoShape, kNoShape, kNoShape},
     {shape_of<PlainFp16Config>(4096), kNoShape, kNoShape, kNoShape},
@@ -158,7 +159,8 @@ Plan plan_with(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape
   pl.k_tiles = (int)(pl.Kp / pl.shape->bk);
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   const int64_t slots = (int64_t)kPlanComputeUnits * pl.shape->blocks_per_cu;
-  const int64_t tail = pl.shape->fused ? 0 : tiles % slots;  // (the fused kernel never slices)
+  // (a one-launch plan slices every tile or none: its blocks take the whole depth unless the caller asks for slices)
+  const int64_t tail = pl.shape->fused ? (splits > 1 ? tiles : 0) : tiles % slots;
   if (tail == 0) splits = 1;
   pl.tail_splits = splits;
   pl.tail_tiles = splits > 1 ? (int)tail : 0;
@@ -229,12 +231,33 @@ double estimated_us(const Plan& pl, ecgemm_mode_t mode) {
 
 // The cheapest way to slice the leftover tiles of one shape: slices at least 512 deep, none of them empty, at most
 // 1024 of them in all (128 MiB of partial sums).
-Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape) {
+// How a caller wants the one-launch shapes: not at all (it needs packed operands), with every block over the whole
+// depth (the automatic mode, whose kernels look at the choice themselves), or also with the depth in slices.
+enum OneLaunch { kOneLaunchNever = 0, kOneLaunchWhole = 1, kOneLaunchSliced = 2 };
+double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode);
+// Chunks of 64 per slice of a one-launch plan: equal shares rounded up to whole in-register slices (512 deep).
+int64_t fused_chunks_per_slice(int64_t K, int splits) {
+  const int64_t chunks = (K + 63) / 64;
+  return round_up((chunks + splits - 1) / splits, (int64_t)kFusedSliceChunks);
+}
+Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, OneLaunch one_launch) {
   Plan best = plan_with(M, N, K, mode, shape, 1);
   if (best.shape == nullptr) return best;
   const int64_t slots = (int64_t)kPlanComputeUnits * best.shape->blocks_per_cu;
   const int64_t tiles = (int64_t)best.tiles_m * best.tiles_n;
-  const int64_t tail = best.shape->fused ? 0 : tiles % slots;
+  if (best.shape->fused) {
+    // Deep products of few tiles: slices at least 512 deep, none empty, all blocks in one round.
+    if (one_launch != kOneLaunchSliced) return best;
+    double best_us = one_launch_us(best, K, mode);
+    for (int splits = 2; splits <= 64 && splits * tiles <= kPlanComputeUnits && splits <= K / 512; ++splits) {
+      if (fused_chunks_per_slice(K, splits) * (splits - 1) >= (K + 63) / 64) continue;  // the last slice would be empty
+      const Plan pl = plan_with(M, N, K, mode, shape, splits);
+      const double us = one_launch_us(pl, K, mode);
+      if (us < best_us) best = pl, best_us = us;
+    }
+    return best;
+  }
+  const int64_t tail = tiles % slots;
   if (tail == 0) return best;
   double best_us = estimated_us(best, mode);
   for (int splits = 2; splits <= 64 && splits <= best.Kp / 512 && splits * tail <= 1024; ++splits) {
@@ -267,6 +290,12 @@ double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
   const double per_chunk = small ? (bf16 ? 0.46 : 0.33) : (bf16 ? 0.76 : 0.58);
   const double blocks_per_unit = (double)pl.tiles_m * pl.tiles_n / kPlanComputeUnits;
   const double rounds = std::max(1.0, std::ceil(blocks_per_unit - 1e-9));
+  if (pl.tail_splits > 1) {
+    // slices of the depth (one round by construction): a block's share, then the kernel that adds the slices up
+    // (2.2 us behind the first kernel, and a pass over the partial sums)
+    const double share = (double)fused_chunks_per_slice(K, pl.tail_splits), partial_mb = pl.partial_bytes / 1e6;
+    return 4.4 + (small ? (bf16 ? 0.7 : 0.4) : (bf16 ? 1.1 : 0.8)) + share * per_chunk + 2.2 + 0.35 * partial_mb;
+  }
   const double chunks = (double)(K / 64) + (K % 64 ? 3.0 : 0.0);
   if (rounds == 1.0) {
     const double nearly_full = (!small && bf16 && blocks_per_unit > 0.9) ? 1.2 : 1.0;
@@ -280,42 +309,42 @@ double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
 // by the product estimate (the comparison methods have the 256 x 128 shape only), unless a one-launch shape is
 // allowed (ecgemm_sgemm and what describes it; not for callers that need the packed operands) and estimated to take
 // less than 0.85 of the time: the estimates know nothing of the operands' layouts, which move either by a tenth.
-Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, bool one_launch_allowed) {
-  if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape);
-  const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4);
+Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, OneLaunch one_launch) {
+  if (shape != ECGEMM_SHAPE_AUTO) return plan_with_shape(M, N, K, mode, shape, one_launch);
+  const Plan w4 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_256x128_W4, one_launch);
   if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
-  const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2);
+  const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2, one_launch);
   const Plan split_first = estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
   // (a one-launch block walks the whole depth and an operand is split once per block row or column: beyond these
   // bounds it never wins, and its tile count stays far inside 32 bits)
-  if (!one_launch_allowed || K > 8192 || M > 16384 || N > 16384) return split_first;
-  const Plan tile64 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_64x64_FUSED);
-  const Plan tile32 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_32x32_FUSED);
+  if (one_launch == kOneLaunchNever || K > 8192 || M > 16384 || N > 16384) return split_first;
+  const Plan tile64 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_64x64_FUSED, one_launch);
+  const Plan tile32 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_32x32_FUSED, one_launch);
   // (near a tie the larger tile, which is less at the mercy of the operands' layout)
-  const Plan one_launch = one_launch_us(tile32, K, mode) < 0.95 * one_launch_us(tile64, K, mode) ? tile32 : tile64;
-  return one_launch_us(one_launch, K, mode) < 0.85 * split_first_us(split_first, M, N, K, mode) ? one_launch : split_first;
+  const Plan one = one_launch_us(tile32, K, mode) < 0.95 * one_launch_us(tile64, K, mode) ? tile32 : tile64;
+  return one_launch_us(one, K, mode) < 0.85 * split_first_us(split_first, M, N, K, mode) ? one : split_first;
 }
 
 // A plan is a pure function of its arguments, and loops call the library with the same ones over and over: the last
 // few plans of each thread are kept (ranking up to 128 candidate plans costs a few microseconds, which matters next to
 // a 12 us call; the automatic mode needs two plans per call).
-Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, bool one_launch_allowed) {
+Plan make_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_shape_t shape, OneLaunch one_launch) {
   struct Entry {
     int64_t M = -1, N = -1, K = -1;
     int mode = -1, shape = -1;
-    bool one_launch_allowed = false;
+    int one_launch = -1;
     Plan plan;
   };
   constexpr int kEntries = 4;
   thread_local Entry cache[kEntries];
   thread_local int next = 0;
   for (const Entry& e : cache)
-    if (e.M == M && e.N == N && e.K == K && e.mode == (int)mode && e.shape == (int)shape && e.one_launch_allowed == one_launch_allowed)
+    if (e.M == M && e.N == N && e.K == K && e.mode == (int)mode && e.shape == (int)shape && e.one_launch == (int)one_launch)
       return e.plan;
   Entry& e = cache[next];
   next = (next + 1) % kEntries;
-  e.plan = choose_plan(M, N, K, mode, shape, one_launch_allowed);
-  e.M = M, e.N = N, e.K = K, e.mode = (int)mode, e.shape = (int)shape, e.one_launch_allowed = one_launch_allowed;
+  e.plan = choose_plan(M, N, K, mode, shape, one_launch);
+  e.M = M, e.N = N, e.K = K, e.mode = (int)mode, e.shape = (int)shape, e.one_launch = (int)one_launch;
   return e.plan;
 }
 
@@ -331,13 +360,16 @@ struct AutoPlan {
 };
 AutoPlan make_auto_plan(int64_t M, int64_t N, int64_t K, ecgemm_shape_t shape) {
   AutoPlan ap;
-  ap.fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape, false);
-  ap.bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape, false);
+  ap.fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape, kOneLaunchNever);
+  ap.bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape, kOneLaunchNever);
   ap.exists = ap.fp16.shape && ap.bf16.shape && !ap.fp16.shape->fused && !ap.bf16.shape->fused;
   if (!ap.exists) return ap;
   const size_t blocks_per_row_block = (size_t)(round_up(K, kDepthPad) / 32);
   ap.packed_bytes = std::max(ap.fp16.a_bytes + ap.fp16.b_bytes, ap.bf16.a_bytes + ap.bf16.b_bytes);
   ap.partial_bytes = std::max(ap.fp16.partial_bytes, ap.bf16.partial_bytes);
+  // (a candidate that ecgemm_sgemm would run as one launch runs so here too, with its own partial sums if it slices)
+  ap.partial_bytes = std::max(ap.partial_bytes, std::max(make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, shape, kOneLaunchSliced).partial_bytes,
+                                                         make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, shape, kOneLaunchSliced).partial_bytes));
   const size_t per_block = kStatsPerBlock * sizeof(double);
   ap.stats_a_bytes = align256(per_block * blocks_per_row_block * (size_t)(round_up(M, kRowPad) / 64));
   ap.stats_b_bytes = align256(per_block * blocks_per_row_block * (size_t)(round_up(N, kRowPad) / 64));
@@ -528,7 +560,7 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
   if (pl.tail_splits > 1) {
     const dim3 rgrid((unsigned)pl.tail_tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
     hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, pl.tail_tiles,
-                       pl.full_tiles, pl.tiles_m, pl.tiles_n, group_m, bands, M, N, alpha, beta, C, ldc, gate, gate_value);
+                       pl.full_tiles, pl.tiles_m, pl.tiles_n, group_m, bands, M, N, alpha, beta, C, ldc, gate, gate_value, gate_value);
     ECGEMM_HIP(h, hipGetLastError());
   }
   return ECGEMM_OK;
@@ -537,9 +569,14 @@ ecgemm_status_t launch_product(ecgemm_handle_t h, const Plan& pl, int64_t M, int
 // Steps 1 to 5 in one kernel, on the caller's FP32 operands (small products).
 ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t transA, ecgemm_op_t transB, int64_t M, int64_t N,
                              int64_t K, float alpha, const float* A, int64_t lda, const float* B, int64_t ldb, float beta,
-                             float* C, int64_t ldc, const int* row_log2_scale, const int* col_log2_scale,
+                             float* C, int64_t ldc, const int* row_log2_scale, const int* col_log2_scale, float* partials = nullptr,
                              const int* gate = nullptr, int gate_value = 0, int gate_value_scaled = 0) {
+  if (pl.tail_splits > 1 && partials == nullptr)
+    return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_sgemm: a sliced one-launch plan without room for its partial sums");
   FusedParams fp;
+  fp.k_slices = pl.tail_splits;
+  fp.chunks_per_slice = (int)fused_chunks_per_slice(K, pl.tail_splits);
+  fp.partials = partials;
   fp.gate = gate;  // (with a gate: gate_value runs without the scaling vectors, gate_value_scaled with them)
   fp.gate_value = gate_value;
   fp.gate_value_scaled = gate_value_scaled;
@@ -568,8 +605,14 @@ ecgemm_status_t launch_fused(ecgemm_handle_t h, const Plan& pl, ecgemm_op_t tran
   fp.C = C;
   const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
   void* args[] = {&fp};
-  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused->kernel[layout_a][layout_b]), dim3((unsigned)tiles),
-                                dim3((unsigned)pl.shape->threads), args, 0, h->stream));
+  ECGEMM_HIP(h, hipLaunchKernel(reinterpret_cast<const void*>(pl.shape->fused->kernel[layout_a][layout_b]),
+                                dim3((unsigned)(tiles * pl.tail_splits)), dim3((unsigned)pl.shape->threads), args, 0, h->stream));
+  if (pl.tail_splits > 1) {  // the slices in ascending order, then alpha / beta (tiles in the order of the kernel above)
+    const dim3 rgrid((unsigned)tiles, (unsigned)(pl.shape->bm * pl.shape->bn / 1024));
+    hipLaunchKernelGGL(pl.shape->reduce, rgrid, dim3(256), 0, h->stream, partials, pl.tail_splits, (int)tiles, 0, pl.tiles_m,
+                       pl.tiles_n, 4, 1, M, N, alpha, beta, C, ldc, gate, gate_value, gate_value_scaled);
+    ECGEMM_HIP(h, hipGetLastError());
+  }
   return ECGEMM_OK;
 }
 
@@ -778,7 +821,7 @@ ecgemm_status_t ecgemm_debug_tile_order(ecgemm_handle_t handle, int64_t M, int64
   if (!disagreements) return bad_arg(handle, 8, "ecgemm_debug_tile_order: null output");
   const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, true);  // as ecgemm_plan_info
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, kOneLaunchSliced);  // as ecgemm_plan_info
   if (!pl.shape || pl.shape->fused) return fail(handle, ECGEMM_ERR_UNSUPPORTED, "ecgemm_debug_tile_order: no product kernel of this shape and mode");
   const int group_m = group_m_of(pl, handle ? handle->forced_group_m : 0);
   const int bands = column_bands(pl, group_m, mode, handle ? handle->forced_column_bands : 0);
@@ -814,11 +857,11 @@ ecgemm_status_t ecgemm_workspace_size(ecgemm_handle_t handle, ecgemm_op_t transA
     return ECGEMM_OK;
   }
   const ecgemm_shape_t shape = handle ? handle->shape : ECGEMM_SHAPE_AUTO;
-  const Plan pl = make_plan(M, N, K, mode, shape, true);
+  const Plan pl = make_plan(M, N, K, mode, shape, kOneLaunchSliced);
   if (!pl.shape) return no_plan(handle, pl, "ecgemm_workspace_size");
   *bytes = pl.total_bytes;
   // (ecgemm_product on the same problem never takes a one-launch shape by itself and may need room for partial sums)
-  if (pl.shape->fused && shape == ECGEMM_SHAPE_AUTO) *bytes = std::max(*bytes, make_plan(M, N, K, mode, shape, false).partial_bytes);
+  if (pl.shape->fused && shape == ECGEMM_SHAPE_AUTO) *bytes = std::max(*bytes, make_plan(M, N, K, mode, shape, kOneLaunchNever).partial_bytes);
   return ECGEMM_OK;
 }
 
@@ -831,7 +874,7 @@ ecgemm_status_t ecgemm_plan_info(ecgemm_handle_t handle, int64_t M, int64_t N, i
   if (!info) return bad_arg(handle, 6, "ecgemm_plan_info: null output");
   const ecgemm_status_t st = check_sizes(handle, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, true);
+  const Plan pl = make_plan(M, N, K, mode, handle ? handle->shape : ECGEMM_SHAPE_AUTO, kOneLaunchSliced);
   if (!pl.shape) return no_plan(handle, pl, "ecgemm_plan_info");
   info->shape = (int)(pl.shape - &kShapes[(int)mode][0]) + 1;
   info->tile_m = pl.shape->bm;
@@ -1168,8 +1211,8 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   // Every candidate runs the way ecgemm_sgemm would run it in that mode, so that the result is that call's bit for
   // bit: a small product as one launch on the FP32 operands (the measuring splits above still write their packed
   // parts, which nothing reads then), the others with the product kernels on the packed operands.
-  const Plan one_fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, h->shape, true);
-  const Plan one_bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, h->shape, true);
+  const Plan one_fp16 = make_plan(M, N, K, ECGEMM_MODE_FP16_SPLIT, h->shape, kOneLaunchSliced);
+  const Plan one_bf16 = make_plan(M, N, K, ECGEMM_MODE_BF16_FULL, h->shape, kOneLaunchSliced);
   const bool fp16_one_launch = one_fp16.shape && one_fp16.shape->fused, bf16_one_launch = one_bf16.shape && one_bf16.shape->fused;
   if (!bf16_one_launch) {
     st = launch_split(h, ECGEMM_MODE_BF16_FULL, bf16_a, &bf16_b);
@@ -1179,7 +1222,7 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
   const int log2_out_scale = -(h->log2_scale_a + h->log2_scale_b);
   if (fp16_one_launch) {  // with and without the scaling vectors in one launch, which looks at the choice itself
     st = launch_fused(h, one_fp16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, try_scaled ? scales_a : nullptr,
-                      try_scaled ? scales_b : nullptr, choice, kChoiceFp16, try_scaled ? kChoiceFp16Scaled : kChoiceFp16);
+                      try_scaled ? scales_b : nullptr, partials, choice, kChoiceFp16, try_scaled ? kChoiceFp16Scaled : kChoiceFp16);
     if (st != ECGEMM_OK) return st;
   } else {
     for (int scaled = 0; scaled <= (try_scaled ? 1 : 0); ++scaled) {
@@ -1189,8 +1232,8 @@ ecgemm_status_t sgemm_auto(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t tr
       if (st != ECGEMM_OK) return st;
     }
   }
-  st = bf16_one_launch ? launch_fused(h, one_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, nullptr, nullptr, choice,
-                                      kChoiceBf16, kChoiceBf16)
+  st = bf16_one_launch ? launch_fused(h, one_bf16, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, nullptr, nullptr, partials,
+                                      choice, kChoiceBf16, kChoiceBf16)
                        : launch_product(h, ap.bf16, M, N, alpha, ws, ws + ap.bf16.a_bytes, beta, C, ldc, ECGEMM_MODE_BF16_FULL, partials,
                                         log2_out_scale, nullptr, nullptr, choice, kChoiceBf16);
   if (st != ECGEMM_OK) return st;
@@ -1241,7 +1284,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
   }
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 4);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, h->shape, true);
+  const Plan pl = make_plan(M, N, K, mode, h->shape, kOneLaunchSliced);
   if (!pl.shape) return no_plan(h, pl, "ecgemm_sgemm");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 4, "ecgemm_sgemm: too many tiles");
   SplitJob job_a, job_b;
@@ -1274,7 +1317,7 @@ ecgemm_status_t sgemm_common(ecgemm_handle_t h, ecgemm_op_t transA, ecgemm_op_t 
 
   if (pl.shape->fused) {
     if (timing) ECGEMM_HIP(h, hipEventRecord(tc.split_done, h->stream));  // no split pass: all the time is the product's
-    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, row_log2_scale_a, col_log2_scale_b);
+    st = launch_fused(h, pl, transA, transB, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, row_log2_scale_a, col_log2_scale_b, partials);
   } else {
     st = launch_split(h, mode, job_a, &job_b);
     if (st != ECGEMM_OK) return st;
@@ -1358,7 +1401,7 @@ ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int
   if (!packedB || ((uintptr_t)packedB % 16) != 0) return bad_arg(h, 7, "ecgemm_product: packed operand is null or not 16-byte aligned");
   ecgemm_status_t st = check_sizes(h, M, N, K, mode, 2);
   if (st != ECGEMM_OK) return st;
-  const Plan pl = make_plan(M, N, K, mode, h->shape, false);
+  const Plan pl = make_plan(M, N, K, mode, h->shape, kOneLaunchNever);
   if (!pl.shape || pl.shape->fused)
     return fail(h, ECGEMM_ERR_UNSUPPORTED, "ecgemm_product: the handle's kernel shape does not take packed operands in this mode");
   if (pl.items() + 16 > 0x7fffffffLL) return bad_arg(h, 2, "ecgemm_product: too many tiles");

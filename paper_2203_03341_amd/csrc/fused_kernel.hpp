@@ -57,6 +57,12 @@ struct FusedParams {
   const int* row_log2_scale;  // device, M entries
   const int* col_log2_scale;  // device, N entries
   float* C;
+  // k_slices > 1 (deep products of small matrices, where whole tiles would leave most compute units idle): block b
+  // takes tile b % tiles over chunks_per_slice 64-deep chunks from chunk (b / tiles) chunks_per_slice on and leaves
+  // its sums, before alpha / beta, in partials[b / tiles][b % tiles][n][m] for reduce_tail_kernel, as the product
+  // kernels do for their sliced tiles.  k_slices == 1: every block the whole depth, nothing written but C.
+  int k_slices, chunks_per_slice;
+  float* partials;
   // Automatic mode choice only, else null: the kernel runs without the scaling vectors if *gate == gate_value, with
   // them if *gate == gate_value_scaled, and does nothing otherwise
   const int* gate;
@@ -397,8 +403,18 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  int tile_index = (int)blockIdx.x, slice = 0;
+  if (p.k_slices > 1) {  // the block's slice of the depth is a product of its own from here on
+    const int tiles = p.tiles_m * p.tiles_n;
+    slice = tile_index / tiles, tile_index -= slice * tiles;
+    const int64_t k_begin = (int64_t)slice * p.chunks_per_slice * 64;  // < K: the host makes no empty slices
+    const int64_t k_end = k_begin + (int64_t)p.chunks_per_slice * 64;
+    p.A += LAYOUT_A == kFusedRows ? k_begin * p.lda : k_begin;
+    p.B += LAYOUT_B == kFusedRows ? k_begin * p.ldb : k_begin;
+    p.K = (k_end < p.K ? k_end : p.K) - k_begin;
+  }
   int tile_m, tile_n;
-  tile_coordinates((int)blockIdx.x, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
+  tile_coordinates(tile_index, p.tiles_m, p.tiles_n, 4, 1, tile_m, tile_n);
   const int chunks = (int)((p.K + 63) / 64);  // >= 1
 
   // Every wave of the block passes exactly `chunks` barriers, whichever of the two roles it has: a splitting wave one
@@ -576,6 +592,22 @@ __global__ void __launch_bounds__(fused_threads(TILE), 1) fused_kernel(const Fus
   // ---- epilogue, as in product_kernel: lane l holds row m and columns n_base + 8 (v / 4) + v % 4
   const int64_t m = (int64_t)tile_m * BM + wave_m * 32 + (lane & 31);
   const int64_t n_base = (int64_t)tile_n * BN + wave_n * 32 + 4 * (lane >> 5);
+  if (p.k_slices > 1) {
+    // the slice's sums, scaling undone, before alpha / beta; zero where the tile reaches beyond C
+    float* out = p.partials + ((int64_t)slice * (p.tiles_m * p.tiles_n) + tile_index) * (BM * BN) +
+                 (wave_n * 32 + 4 * (lane >> 5)) * BM + wave_m * 32 + (lane & 31);
+    const int row_exponent = (p.row_log2_scale != nullptr && m < p.M) ? p.row_log2_scale[m] : 0;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int64_t n = n_base + 8 * (v / 4) + (v % 4);
+      const float last_slice = acc_main[v] + acc_corr[v] * corr_scale;
+      float c = (earlier_slices ? sliced[v] + last_slice : last_slice) * p.out_scale;
+      const bool inside = m < p.M && n < p.N;
+      if (p.row_log2_scale != nullptr && inside) c = unscale(c, row_exponent, p.col_log2_scale[n]);
+      store_partial(out + (8 * (v / 4) + (v % 4)) * BM, inside ? c : 0.0f);
+    }
+    return;
+  }
   if (m >= p.M) return;
   const int row_exponent = p.row_log2_scale != nullptr ? p.row_log2_scale[m] : 0;
 #pragma unroll

@@ -67,10 +67,13 @@ ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4, false>(const P
 ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2, false>(const ProductParams);
 ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16W4, true>(const ProductParams);  // for calls with scaling vectors
 ECGEMM_FP16_GROUP template __global__ void product_kernel<Fp16X2, true>(const ProductParams);
-ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<256, 128>(const float*, int, int, int, int, int, int, int, int64_t,
-                                                                       int64_t, float, float, float*, int64_t, const int*, int);
-ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<128, 128>(const float*, int, int, int, int, int, int, int, int64_t,
-                                                                       int64_t, float, float, float*, int64_t, const int*, int);
+#define ECGEMM_REDUCE_KERNEL(BM, BN)                                                                                        \
+  ECGEMM_FP16_GROUP template __global__ void reduce_tail_kernel<BM, BN>(const float*, int, int, int, int, int, int, int, int64_t, \
+                                                                        int64_t, float, float, float*, int64_t, const int*, int, int);
+ECGEMM_REDUCE_KERNEL(256, 128)
+ECGEMM_REDUCE_KERNEL(128, 128)
+ECGEMM_REDUCE_KERNEL(64, 64)  // (the one-launch shapes, when they slice the depth)
+ECGEMM_REDUCE_KERNEL(32, 32)
 ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4, false>(const ProductParams);
 ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16X2, false>(const ProductParams);
 ECGEMM_BF16_GROUP template __global__ void product_kernel<Bf16W4, true>(const ProductParams);

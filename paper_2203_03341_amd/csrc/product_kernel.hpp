@@ -940,9 +940,11 @@ template <int BM, int BN>
 __global__ void __launch_bounds__(256) reduce_tail_kernel(const float* __restrict__ partials, int tail_splits, int tail_tiles,
                                                           int full_tiles, int tiles_m, int tiles_n, int group_m,
                                                           int column_bands, int64_t M, int64_t N, float alpha, float beta, float* __restrict__ C,
-                                                          int64_t ldc, const int* gate, int gate_value) {
+                                                          int64_t ldc, const int* gate, int gate_value, int gate_value_too) {
   static_assert(BM % 4 == 0 && (BM * BN) % 1024 == 0, "tile shape");
-  if (!gate_open(gate, gate_value)) return;
+  // (two values: the one-launch kernel serves the FP16 candidate of the automatic choice with and without scaling
+  // vectors; everyone else passes the same value twice)
+  if (!gate_open(gate, gate_value) && !gate_open(gate, gate_value_too)) return;
   int tile_m, tile_n;
   tile_coordinates(full_tiles + blockIdx.x, tiles_m, tiles_n, group_m, column_bands, tile_m, tile_n);
   const int e = (blockIdx.y * 256 + threadIdx.x) * 4;  // element of the tile, stored [n_local][m_local]

@@ -123,18 +123,27 @@ def test_plan_of_the_baseline_configs():
     p = ec.plan_info(300, 200, 100, ec.MODE_FP16_MARKIDIS)             # comparison methods: one shape
     assert (p["shape"], p["tiles_m"], p["tiles_n"]) == (W4, 2, 2)
     # small products: one launch that splits for itself, 32 x 32 tiles while those leave compute units idle, 64 x 64
-    # after that, nothing in the workspace, never sliced; the split-first shapes again once blocks crowd the units
+    # after that, nothing in the workspace; deep products of few tiles: the same with the depth in slices of at least
+    # 512 (all blocks in one round) and a reduction; the split-first shapes again once blocks crowd the units or the
+    # depth is beyond 8192
     F64, F32 = ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
-        for (M, N, K, shape) in [(1, 1, 1, F32), (256, 256, 256, F32), (512, 512, 512, F32), (300, 200, 77, F32),
-                                 (4096, 128, 128, (F32, F64)), (1024, 1024, 256, F64), (1536, 1536, 1536, X2), (128, 128, 8256, X2),
-                                 (256, 256, 4096, X2)]:
+        for (M, N, K, shape, sliced) in [(1, 1, 1, F32, False), (256, 256, 256, F32, False), (512, 512, 512, F32, False),
+                                         (300, 200, 77, F32, False), (4096, 128, 128, (F32, F64), False), (1024, 1024, 256, F64, False),
+                                         (1536, 1536, 1536, X2, None), (128, 128, 8256, X2, None), (256, 256, 4096, (F32, F64), True),
+                                         (128, 128, 4096, (F32, F64), True), (64, 64, 1023, (F32, F64), False)]:
             p = ec.plan_info(M, N, K, mode)
             assert p["shape"] == shape or (isinstance(shape, tuple) and p["shape"] in shape), (M, N, K, mode, p)
             if p["shape"] in (F64, F32):
                 tile = 64 if p["shape"] == F64 else 32
-                assert (p["tile_m"], p["tile_n"], p["slices"], p["sliced_tiles"], p["workspace_bytes"]) == (tile, tile, 1, 0, 0)
-                assert p["grid"] == p["tiles_m"] * p["tiles_n"] == -(-M // tile) * -(-N // tile) and p["estimated_us"] > 4
+                tiles = -(-M // tile) * -(-N // tile)
+                assert (p["tile_m"], p["tile_n"]) == (tile, tile) and p["tiles_m"] * p["tiles_n"] == tiles and p["estimated_us"] > 4
+                assert (p["slices"] > 1) == sliced and p["grid"] == tiles * p["slices"]
+                if sliced:
+                    assert p["sliced_tiles"] == tiles and p["grid"] <= 256 and K // p["slices"] >= 512
+                    assert p["workspace_bytes"] == p["slices"] * tiles * tile * tile * 4
+                else:
+                    assert (p["sliced_tiles"], p["workspace_bytes"]) == (0, 0)
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
         for (M, N, K) in [(1, 1, 1), (257, 129, 33), (5000, 7000, 900), (20000, 300, 70000)]:
             p = ec.plan_info(M, N, K, mode)
@@ -175,9 +184,19 @@ def test_plans_of_random_problems_are_well_formed():
         assert p["whole_tiles"] + p["sliced_tiles"] == p["tiles_m"] * p["tiles_n"], case
         assert (p["slices"] == 1) == (p["sliced_tiles"] == 0), case
         assert 1 <= p["column_bands"] <= max(1, p["tiles_n"]) and p["group_m"] in (4, 8), case
-        if p["shape"] in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):      # one launch: nothing packed, nothing sliced
-            assert (p["workspace_bytes"], p["slices"]) == (0, 1) and p["tile_m"] == p["tile_n"] == (64 if p["shape"] == 3 else 32), case
+        if p["shape"] in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):      # one launch: nothing packed; every tile sliced or none
+            tile = 64 if p["shape"] == 3 else 32
+            assert p["tile_m"] == p["tile_n"] == tile, case
             assert mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL) and K <= 8192 and p["tiles_m"] * p["tiles_n"] <= 2048, case
+            if p["slices"] == 1:
+                assert p["workspace_bytes"] == 0, case
+            else:
+                tiles = p["tiles_m"] * p["tiles_n"]
+                assert p["sliced_tiles"] == tiles and p["slices"] * tiles <= 256 and K // p["slices"] >= 512, case
+                assert p["workspace_bytes"] == p["slices"] * tiles * tile * tile * 4, case
+                chunks = -(-K // 64)
+                per_slice = -(-(-(-chunks // p["slices"])) // 8) * 8          # equal shares rounded up to whole 512-deep runs
+                assert per_slice * (p["slices"] - 1) < chunks, case            # the last slice is not empty
             continue
         Kp = -(-K // 32) * 32
         parts = {ec.MODE_FP16_SPLIT: 2, ec.MODE_BF16_FULL: 3, ec.MODE_FP16_MARKIDIS: 2, ec.MODE_FP32_MFMA: 2}[mode]

@@ -577,6 +577,40 @@ def test_one_launch_shape_with_leading_dimensions_beyond_32_bit_offsets(mode):
     assert np.array_equal(outs[0].view(np.uint32), outs[1].view(np.uint32))
 
 
+@pytest.mark.parametrize("mode", ["fp16", "bf16"])
+@pytest.mark.parametrize("transA,transB,size", [("N", "N", (128, 128, 4096)), ("T", "N", (300, 200, 5000)), ("N", "T", (33, 700, 3000)),
+                                                 ("T", "T", (64, 64, 4101))])
+def test_one_launch_plans_with_the_depth_in_slices(mode, transA, transB, size):
+    """Deep products of few tiles run as one launch whose blocks take a slice of the depth each, plus the reduction
+    kernel that adds the slices in ascending order.  The result must pass the accuracy rule against the oracle, and
+    with alpha = 1, beta = 0 it must equal, bit for bit, the FP32 sum in the same order of the products of the slices
+    computed one by one (each of them a one-launch call of its own)."""
+    import torch
+    import paper_2203_03341_amd as ec
+    M, N, K = size
+    mode_id = _modes()[mode]
+    p = ec.plan_info(M, N, K, mode_id)
+    assert p["shape"] >= ec.SHAPE_64x64_FUSED and p["slices"] > 1 and p["sliced_tiles"] == p["tiles_m"] * p["tiles_n"]
+    _check(transA, transB, M, N, K, 1.5, 0.5, mode, "urand", seed=51, pad=1)
+    A, B = _inputs(M, N, K, transA, transB, "urand", 52)
+    whole = _gpu_sgemm(transA, transB, M, N, K, 1.0, A, B, 0.0, None, mode)[:M, :N]
+    chunks = -(-K // 64)
+    per_slice = 64 * (-(-(-(-chunks // p["slices"])) // 8) * 8)      # equal shares of 64-deep chunks, rounded up to whole runs of 512
+    opA, opB = gemm.logical(transA, A, M, K), gemm.logical(transB, B, K, N)
+    total = None
+    for k0 in range(0, K, per_slice):
+        k1 = min(K, k0 + per_slice)
+        a = np.asfortranarray(opA[:, k0:k1])                          # (these calls see both operands untransposed; the values and
+        b = np.asfortranarray(opB[k0:k1, :])                          # their order along the depth are what the slice of the big call sees)
+        # (a slice of 1024 or more is itself cut at multiples of 512 by its own call, across blocks; inside the big
+        # call's block the same runs of 512 are added in registers, in the same order)
+        assert ec.plan_info(M, N, k1 - k0, mode_id)["shape"] >= ec.SHAPE_64x64_FUSED
+        part = _gpu_sgemm("N", "N", M, N, k1 - k0, 1.0, a, b, 0.0, None, mode)[:M, :N]
+        total = part if total is None else (total + part).astype(np.float32)
+    assert k1 == K and -(-K // per_slice) == p["slices"]
+    assert np.array_equal(whole.view(np.uint32), total.view(np.uint32))
+
+
 def test_one_launch_shapes_equal_the_split_first_shape_on_random_small_problems():
     """Random sizes up to 300 x 300 x 512 (one slice of depth in every shape), both transposes, padded leading
     dimensions of every alignment, alpha and beta, magnitudes over 16 binades, now and then a value beyond the FP16

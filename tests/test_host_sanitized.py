@@ -79,8 +79,10 @@ int main(void) {
     CHECK(info.slices >= 1 && info.slices <= 64 && (int64_t)info.slices * info.sliced_tiles <= 1024);
     CHECK(info.grid > 0 && info.column_bands >= 1 && info.column_bands <= 8 && info.estimated_us > 0.0);
     CHECK(ecgemm_workspace_size(NULL, ECGEMM_OP_T, ECGEMM_OP_N, M, N, K, (ecgemm_mode_t)mode, &bytes) == ECGEMM_OK);
-    if (info.shape >= 3) { /* one launch: nothing in the workspace, one block per tile, small products only */
-      CHECK(info.workspace_bytes == 0 && info.slices == 1 && info.grid == (int64_t)info.tiles_m * info.tiles_n && mode <= 1);
+    if (info.shape >= 3) { /* one launch: one block per tile and slice of the depth, only partial sums in the workspace, small products only */
+      CHECK(info.grid == (int64_t)info.tiles_m * info.tiles_n * info.slices && mode <= 1);
+      CHECK(info.workspace_bytes == (info.slices > 1 ? (size_t)info.slices * info.sliced_tiles * info.tile_m * info.tile_n * 4 : 0));
+      CHECK(info.slices == 1 || (info.grid <= 256 && K / info.slices >= 512 && info.sliced_tiles == info.tiles_m * info.tiles_n));
       CHECK(info.tile_m == (info.shape == 3 ? 64 : 32) && K <= 8192 && info.grid <= 4096);
     } else {
       CHECK(info.grid % 8 == 0 && bytes == info.workspace_bytes);
