@@ -77,6 +77,10 @@ WORKLOADS = {
     "x_oneblock_tn_fp16": (64, 64, 4096, "T", "N", "fp16", 1.0, 0.0, "urand", None),
     "x_oneblock_nt_fp16": (64, 64, 4096, "N", "T", "fp16", 1.0, 0.0, "urand", None),
     "x_oneblock_nn_bf16": (64, 64, 4096, "N", "N", "bf16", 1.0, 0.0, "urand", None),
+    # deep products of few tiles: one launch with the depth in slices plus the reduction
+    "x_deep_128x4096_fp16": (128, 128, 4096, "N", "N", "fp16", 1.0, 0.0, "urand", None),
+    "x_deep_128x4096_bf16": (128, 128, 4096, "N", "N", "bf16", 1.0, 0.0, "urand", None),
+    "x_deep_512x2048_fp16": (512, 512, 2048, "N", "N", "fp16", 1.0, 0.0, "urand", None),
     # not baseline configs either: the method with the leading product accumulated outside the matrix unit, as the
     # paper's listing does against round-toward-zero, next to the default (inside) at the same size
     "x_8192_fp16_urand": (8192, 8192, 8192, "N", "N", "fp16", 1.0, 0.0, "urand", 256),

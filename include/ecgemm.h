@@ -101,7 +101,8 @@ ecgemm_status_t ecgemm_set_stream(ecgemm_handle_t handle, void *hip_stream);
 
 /* Bytes of device workspace ecgemm_sgemm needs for this problem: the split operands in matrix-unit fragment order,
  * zero-padded to whole tiles, plus at most 128 MiB of partial sums for output tiles that are cut into slices along K.
- * (Small products run as one launch that needs neither; the size returned for them is what ecgemm_product needs.)
+ * (Small products run as one launch that needs no packed operands, and partial sums only where deep products of few
+ * tiles are cut into slices along K; the size returned for them is the larger of that and what ecgemm_product needs.)
  * The plan behind it is made for the 256 compute units of the MI355X, so the size depends on the problem, the mode and
  * the kernel shape only; `handle` supplies the shape forced with ecgemm_set_shape (ecgemm_debug.h) and may be NULL
  * (automatic choice).  transA and transB are checked and otherwise do not matter: the split pass absorbs the
@@ -313,8 +314,8 @@ ecgemm_status_t ecgemm_split(ecgemm_handle_t handle, ecgemm_op_t op, int64_t row
  * For op(B) that means: ecgemm_split(op = T if B is stored K x N (transB == N), op = N if stored N x K).  packedA,
  * packedB: device, read only.  C, ldc, alpha, beta as in ecgemm_sgemm.  Uses the workspace only for the partial sums
  * of tiles sliced along K.  The result is bitwise what ecgemm_sgemm returns for the same operands and kernel shape
- * (with the automatic shape, ecgemm_sgemm may run a small product as one launch, which never slices along K, where
- * this function slices: then the two agree to FP32 rounding).
+ * (with the automatic shape, ecgemm_sgemm may run a small product as one launch, which slices along K differently
+ * from this function or not at all: then the two agree to FP32 rounding).
  */
 ecgemm_status_t ecgemm_product(ecgemm_handle_t handle, int64_t M, int64_t N, int64_t K, float alpha,
                                const void *packedA, const void *packedB, float beta, float *C, int64_t ldc,

@@ -54,11 +54,13 @@ extern "C" {
  *   128x128_X2     block tile 128 x 128, 4 waves of 64 x 64, two blocks per compute unit (the two modes of the method);
  *   64x64_FUSED    the paper's own arrangement (last paragraph of section "Incorporating our method into CUTLASS"):
  *                  one kernel reads the FP32 operands, splits them in registers and multiplies; no split pass, no
- *                  packed operands or partial sums in the workspace, one launch (the two modes of the method;
- *                  ecgemm_sgemm, ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64: eight waves
- *                  that fetch and split, four that multiply 32 x 32 each, the whole depth per block; every block
- *                  splits the rows of A and columns of B that it uses again, so this is for small products, where
- *                  launches and latencies decide the time.
+ *                  packed operands in the workspace, one launch (the two modes of the method; ecgemm_sgemm,
+ *                  ecgemm_sgemm_scaled and ecgemm_sgemm_noalloc only).  Block tile 64 x 64: eight waves that fetch
+ *                  and split, four that multiply 32 x 32 each; every block splits the rows of A and columns of B that
+ *                  it uses again, so this is for small products, where launches and latencies decide the time.  A
+ *                  block takes the whole depth, unless the tiles are so few that slices of it (at least 512 deep, a
+ *                  block each, all blocks in one round of the compute units) are estimated to be faster: then every
+ *                  tile is cut, the blocks leave partial sums in the workspace and a second launch adds them up.
  *   32x32_FUSED    the same with block tile 32 x 32: eight waves fetch and split, one multiplies.  Four times the
  *                  blocks with half the split work each: for products so small that 64 x 64 tiles leave most
  *                  compute units idle.

@@ -1,7 +1,8 @@
 // The paper's own arrangement of the method for one block (section "Incorporating our method into CUTLASS", last
 // paragraph): the block reads FP32 tiles of A and B, forms the low-precision parts in registers (Eqs. corr-1-1024 ..
 // corr-4-1024, or the three BF16 terms) and multiplies them right away; no split pass over the operands, no packed
-// copies in HBM, no partial sums: one launch.  Every block that touches a tile of A splits it again (N / 64 times per
+// copies in HBM: one launch (two where a deep product of few tiles is cut into slices of the depth, a block each,
+// whose partial sums reduce_tail_kernel adds up).  Every block that touches a tile of A splits it again (N / 64 times per
 // element), so this pays where launches and latencies, not arithmetic, decide the time: small products.
 //
 // One block: TILE x TILE of C over the whole depth of the product, TILE = 64 or 32, made by eight waves that fetch and
