@@ -274,7 +274,8 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 // Both are fits to timings of back-to-back calls on one MI355X (squares from 64 to 1536 and a dozen other small
 // shapes, both modes).
 //   split first: the product estimate above, the launches (5.6 us), and the split pass, which costs about 1 us per MB
-//   of FP32 operands (1.4 us with three BF16 parts to write) until it is hidden behind the product's launch (8.5 us).
+//   of FP32 operands (1.4 us with three BF16 parts to write) up to 8.5 us, and 0.45 (0.55) us per MB beyond: operands
+//   much larger than the product (deep products of small matrices) are a pass at the memory's pace.
 //   one launch: 4.4 us, then the blocks in rounds of one per compute unit (a block's 9 or 12 waves leave no registers
 //   for a second one beside it).  A round is what a block needs per 64-deep chunk (0.33 / 0.58 us for 32 / 64 tiles in
 //   FP16 mode, 0.46 / 0.76 in BF16 mode; a fifth more for 64 x 64 BF16 blocks once nearly every unit has one) plus
@@ -283,7 +284,10 @@ Plan plan_with_shape(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm
 //   chunks' worth).
 double split_first_us(const Plan& pl, int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode) {
   const double operand_mb = 4.0 * ((double)M + (double)N) * (double)K / 1e6;
-  return estimated_us(pl, mode) + 5.6 + std::min(8.5, (mode == ECGEMM_MODE_BF16_FULL ? 1.4 : 1.0) * operand_mb);
+  // (beyond 8.5 us the pass runs at the memory's pace: 8 or 10 bytes moved per element)
+  const bool bf16 = mode == ECGEMM_MODE_BF16_FULL;
+  const double small_pass = (bf16 ? 1.4 : 1.0) * operand_mb;
+  return estimated_us(pl, mode) + 5.6 + (small_pass <= 8.5 ? small_pass : 8.5 + (bf16 ? 0.55 : 0.45) * (operand_mb - 8.5 / (bf16 ? 1.4 : 1.0)));
 }
 double one_launch_us(const Plan& pl, int64_t K, ecgemm_mode_t mode) {
   const bool bf16 = mode == ECGEMM_MODE_BF16_FULL, small = pl.shape->bm == 32;
@@ -315,12 +319,13 @@ Plan choose_plan(int64_t M, int64_t N, int64_t K, ecgemm_mode_t mode, ecgemm_sha
   if (mode != ECGEMM_MODE_FP16_SPLIT && mode != ECGEMM_MODE_BF16_FULL) return w4;
   const Plan x2 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_128x128_X2, one_launch);
   const Plan split_first = estimated_us(x2, mode) < estimated_us(w4, mode) ? x2 : w4;
-  // (a one-launch block walks the whole depth and an operand is split once per block row or column: beyond these
-  // bounds it never wins, and its tile count stays far inside 32 bits)
-  if (one_launch == kOneLaunchNever || K > 8192 || M > 16384 || N > 16384) return split_first;
+  // (a one-launch block walks the whole depth, or its slice of it, and an operand is split once per block row or
+  // column: beyond these bounds it never wins, and its tile count stays far inside 32 bits)
+  if (one_launch == kOneLaunchNever || M > 16384 || N > 16384 || (K > 8192 && one_launch != kOneLaunchSliced)) return split_first;
   const Plan tile64 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_64x64_FUSED, one_launch);
   const Plan tile32 = plan_with_shape(M, N, K, mode, ECGEMM_SHAPE_32x32_FUSED, one_launch);
   // (near a tie the larger tile, which is less at the mercy of the operands' layout)
+  if (K > 8192 && tile64.tail_splits == 1 && tile32.tail_splits == 1) return split_first;  // too many tiles for slices
   const Plan one = one_launch_us(tile32, K, mode) < 0.95 * one_launch_us(tile64, K, mode) ? tile32 : tile64;
   return one_launch_us(one, K, mode) < 0.85 * split_first_us(split_first, M, N, K, mode) ? one : split_first;
 }

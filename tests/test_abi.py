@@ -110,8 +110,10 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (ec.SHAPE_64x64_FUSED, 0, 1, 256)
     p = ec.plan_info(1280, 1280, 1280, ec.MODE_BF16_FULL)              # 25 tiles x 2 slices would leave CUs idle: smaller tiles
     assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (X2, 100, 2, 200)
-    p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # 2 W4 tiles could not fill the chip: smaller tiles,
-    assert (p["shape"], p["sliced_tiles"]) == (X2, 16) and 16 <= p["slices"] <= 32   # one or two slices per compute unit
+    p = ec.plan_info(640, 640, 16384, ec.MODE_BF16_FULL)               # 6 W4 tiles could not fill the chip: smaller tiles,
+    assert (p["shape"], p["sliced_tiles"]) == (X2, 25) and 10 <= p["slices"] <= 21   # one or two slices per compute unit
+    p = ec.plan_info(512, 512, 16384, ec.MODE_BF16_FULL)               # few enough tiles for one launch: 64 of 64 x 64 in 4 slices
+    assert (p["shape"], p["sliced_tiles"], p["slices"], p["grid"]) == (ec.SHAPE_64x64_FUSED, 64, 4, 256)
     p = ec.plan_info(1792, 1792, 1792, ec.MODE_FP16_SPLIT)             # 196 tiles of 128 x 128, one per CU: slices would only add traffic
     assert (p["shape"], p["whole_tiles"], p["slices"]) == (X2, 196, 1)
     p = ec.plan_info(2048, 2048, 2048, ec.MODE_FP16_SPLIT)             # 256 tiles of 128 x 128 beat 128 of 256 x 128 in 2 slices
@@ -124,13 +126,13 @@ def test_plan_of_the_baseline_configs():
     assert (p["shape"], p["tiles_m"], p["tiles_n"]) == (W4, 2, 2)
     # small products: one launch that splits for itself, 32 x 32 tiles while those leave compute units idle, 64 x 64
     # after that, nothing in the workspace; deep products of few tiles: the same with the depth in slices of at least
-    # 512 (all blocks in one round) and a reduction; the split-first shapes again once blocks crowd the units or the
-    # depth is beyond 8192
+    # 512 (all blocks in one round) and a reduction; the split-first shapes again once blocks crowd the units, or the
+    # depth is beyond 8192 and the tiles are too many for slices
     F64, F32 = ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED
     for mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL):
         for (M, N, K, shape, sliced) in [(1, 1, 1, F32, False), (256, 256, 256, F32, False), (512, 512, 512, F32, False),
                                          (300, 200, 77, F32, False), (4096, 128, 128, (F32, F64), False), (1024, 1024, 256, F64, False),
-                                         (1536, 1536, 1536, X2, None), (128, 128, 8256, X2, None), (256, 256, 4096, (F32, F64), True),
+                                         (1536, 1536, 1536, X2, None), (128, 128, 8256, (F32, F64), True), (1024, 1024, 8256, (W4, X2), None), (256, 256, 4096, (F32, F64), True),
                                          (128, 128, 4096, (F32, F64), True), (64, 64, 1023, (F32, F64), False)]:
             p = ec.plan_info(M, N, K, mode)
             assert p["shape"] == shape or (isinstance(shape, tuple) and p["shape"] in shape), (M, N, K, mode, p)
@@ -187,7 +189,7 @@ def test_plans_of_random_problems_are_well_formed():
         if p["shape"] in (ec.SHAPE_64x64_FUSED, ec.SHAPE_32x32_FUSED):      # one launch: nothing packed; every tile sliced or none
             tile = 64 if p["shape"] == 3 else 32
             assert p["tile_m"] == p["tile_n"] == tile, case
-            assert mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL) and K <= 8192 and p["tiles_m"] * p["tiles_n"] <= 2048, case
+            assert mode in (ec.MODE_FP16_SPLIT, ec.MODE_BF16_FULL) and (K <= 8192 or p["slices"] > 1) and p["tiles_m"] * p["tiles_n"] <= 2048, case
             if p["slices"] == 1:
                 assert p["workspace_bytes"] == 0, case
             else:

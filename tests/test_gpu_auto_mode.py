@@ -114,13 +114,13 @@ def test_choice_and_result_for_the_papers_input_types(transA, transB, pad):
 
 def test_each_candidate_runs_as_its_fixed_mode_would():
     """Sizes that a fixed mode runs as one launch on the FP32 operands (256^3), with the split-first kernels (1536^3),
-    and 1024 x 1024 x 2304, where the FP16 mode takes one launch and the BF16 mode splits first: whichever candidate
+    and 768 x 1280 x 3584, where the FP16 mode takes one launch and the BF16 mode splits first: whichever candidate
     wins runs that way, so that the bits are the fixed mode's.  (The checks are those of every other case here: the
     oracle's choice, bit equality with the direct call, the accuracy bar.)"""
     import paper_2203_03341_amd as ec
     h = ec.Handle()
     one_launch = lambda size, mode: h.plan_info(*size, mode)["shape"] >= ec.SHAPE_64x64_FUSED
-    small, mixed, large = (256, 256, 256), (1024, 1024, 2304), (1536, 1536, 1536)
+    small, mixed, large = (256, 256, 256), (768, 1280, 3584), (1536, 1536, 1536)
     assert one_launch(small, ec.MODE_FP16_SPLIT) and one_launch(small, ec.MODE_BF16_FULL)
     assert one_launch(mixed, ec.MODE_FP16_SPLIT) and not one_launch(mixed, ec.MODE_BF16_FULL)
     assert not one_launch(large, ec.MODE_FP16_SPLIT) and not one_launch(large, ec.MODE_BF16_FULL)

@@ -299,7 +299,7 @@ def test_bitwise_reproducible_and_stream(mode):
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("size", [(1024, 768, 3072), (300, 200, 260)])
+@pytest.mark.parametrize("size", [(1280, 1024, 3072), (300, 200, 260)])
 def test_a_call_can_be_captured_in_a_graph_and_replayed(mode, size):
     """With a caller workspace the call only launches kernels (no allocation, no memset, no wait), so it can be recorded
     into a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager bits.

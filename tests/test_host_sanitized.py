@@ -83,7 +83,7 @@ int main(void) {
       CHECK(info.grid == (int64_t)info.tiles_m * info.tiles_n * info.slices && mode <= 1);
       CHECK(info.workspace_bytes == (info.slices > 1 ? (size_t)info.slices * info.sliced_tiles * info.tile_m * info.tile_n * 4 : 0));
       CHECK(info.slices == 1 || (info.grid <= 256 && K / info.slices >= 512 && info.sliced_tiles == info.tiles_m * info.tiles_n));
-      CHECK(info.tile_m == (info.shape == 3 ? 64 : 32) && K <= 8192 && info.grid <= 4096);
+      CHECK(info.tile_m == (info.shape == 3 ? 64 : 32) && (K <= 8192 || info.slices > 1) && info.grid <= 4096);
     } else {
       CHECK(info.grid % 8 == 0 && bytes == info.workspace_bytes);
     }
