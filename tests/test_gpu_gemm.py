@@ -299,12 +299,13 @@ def test_bitwise_reproducible_and_stream(mode):
 
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
-@pytest.mark.parametrize("size", [(1280, 1024, 3072), (300, 200, 260)])
+@pytest.mark.parametrize("size", [(1280, 1024, 3072), (300, 200, 260), (128, 128, 4096)])
 def test_a_call_can_be_captured_in_a_graph_and_replayed(mode, size):
     """With a caller workspace the call only launches kernels (no allocation, no memset, no wait), so it can be recorded
     into a HIP graph.  Every replay, with eager work and synchronisations in between, must give the eager bits.
     The first size runs as split pair + product with every tile sliced along K + reduction, three kernels; the second
-    as one launch that needs no workspace."""
+    as one launch that needs no workspace; the third as one launch with the depth in slices + reduction, whose partial
+    sums are all the workspace holds."""
     import torch
     import paper_2203_03341_amd as ec
     M, N, K = size
@@ -315,7 +316,8 @@ def test_a_call_can_be_captured_in_a_graph_and_replayed(mode, size):
     stream = torch.cuda.Stream()
     h.set_stream(stream.cuda_stream)
     nbytes = h.workspace_size(ec.OP_N, ec.OP_N, M, N, K, mode_id)
-    assert (nbytes == 0) == (h.plan_info(M, N, K, mode_id)["shape"] >= ec.SHAPE_64x64_FUSED) == (M == 300)
+    plan = h.plan_info(M, N, K, mode_id)
+    assert (plan["shape"] >= ec.SHAPE_64x64_FUSED) == (M <= 300) and (nbytes == 0) == (M == 300) and (plan["slices"] > 1) == (M != 300)
     workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
     h.set_workspace(workspace, max(nbytes, 256))
     dA, dB, dC_in = to_device(A), to_device(B), to_device(C)
