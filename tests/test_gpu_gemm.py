@@ -416,6 +416,29 @@ def test_random_shapes_transposes_and_scalars(seed):
                ratio_rule=K >= 64)
 
 
+@pytest.mark.parametrize("seed", [0, 1])
+def test_random_deep_products_of_few_tiles(seed):
+    # few tiles and a deep k: the planner cuts the depth into slices over the blocks of one launch (or of the
+    # split-first shapes beyond 8192); depths on both sides of every boundary it has, ragged last slices included
+    import paper_2203_03341_amd as ec
+    rng = np.random.default_rng(2000 + seed)
+    h = ec.Handle()
+    for case in range(6):
+        M, N = int(rng.integers(1, 260)), int(rng.integers(1, 260))
+        K = int(rng.choice([rng.integers(2600, 8192), rng.integers(8193, 24000), rng.choice([4096, 8191, 8192, 8193, 16385])]))
+        transA, transB = str(rng.choice(["N", "T"])), str(rng.choice(["N", "T"]))
+        alpha = float(rng.choice([1.0, -0.5, 1.5]))
+        beta = float(rng.choice([0.0, 1.0, -0.5]))
+        mode = str(rng.choice(["fp16", "bf16"]))
+        pad = int(rng.integers(0, 4))
+        p = h.plan_info(M, N, K, _modes()[mode])
+        print(f"case {seed}.{case}: {transA}{transB} {M}x{N}x{K} alpha {alpha} beta {beta} {mode} pad {pad}: shape {p['shape']}, "
+              f"{p['slices']} slices", flush=True)
+        assert p["slices"] > 1
+        _check(transA, transB, M, N, K, alpha, beta, mode, "urand", seed=seed * 100 + case, pad=pad)
+    h.destroy()
+
+
 # ----- every kernel shape on its own (the automatic choice exercises only one per size)
 
 @pytest.mark.parametrize("mode", ["fp16", "bf16"])
